@@ -1,0 +1,158 @@
+"""The local-update step, written out step by step (CPU oracle; test infrastructure only).
+
+One synchronous step on a minibatch (paper section 3; cost accounting of appendix A.2 counts one
+forward per layer per step for every variant, which fixes the synchronous reading):
+
+  1. h_0 = x;  h_l = f_l(h_{l-1}; theta_l) for l = 1..L  (one forward pass, weights theta_t).
+  2. For each auxiliary head j attached after layer e_j with window w_j: s_j = max(e_j - w_j, 0);
+     loss_j = CE(head_j(f_{e_j} o ... o f_{s_j+1}(const(h_{s_j}))), y), where const() blocks the
+     gradient ("each block ... receives the activations output by the previous block as input").
+  3. grad(head_j params) = d loss_j / d(head params); grad(theta_l) = combine over the heads whose
+     window covers l of d loss_j / d theta_l  (greedy / overlapping / chunked / backprop differ
+     only in the list of (e_j, w_j)); combine is a sum, or a mean ("averaging updates").
+  4. Every covered parameter tensor takes one optimizer update; layers covered by no window and
+     their state are left untouched (the "last K layers" baseline).
+  5. Return loss_j evaluated at theta_t for every head.
+
+Each loss_j is differentiated separately, exactly as defined; no fusion of overlapping windows.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import layers as L
+
+
+def _cast(P, dtype):
+    return {k: np.asarray(v, dtype=dtype) for k, v in P.items()}
+
+
+def _windows(cfg):
+    return [(max(h.after_layer - h.window, 0), h.after_layer) for h in cfg.heads]
+
+
+def forward_all(cfg, P, x):
+    """Step 1.  Returns activations hs[0..L] (hs[0] = x) and per-layer caches[1..L]."""
+    hs = [x]
+    caches = [None]
+    for li in range(1, cfg.n_layers + 1):
+        out, c = L.layer_fwd(cfg, P, li, hs[-1])
+        hs.append(out)
+        caches.append(c)
+    return hs, caches
+
+
+def eval_loss(cfg, params, x, y, dtype=np.float64):
+    """Steps 1-2, values only: the loss of every head at the current weights."""
+    P = _cast(params, dtype)
+    xx = x if np.issubdtype(np.asarray(x).dtype, np.integer) else np.asarray(x, dtype=dtype)
+    hs, _ = forward_all(cfg, P, xx)
+    return np.array([L.head_loss(cfg, P, hi, hs[h.after_layer], y)[0]
+                     for hi, h in enumerate(cfg.heads, start=1)], dtype=np.float64)
+
+
+def head_gradients(cfg, P, hi, hs, caches, y):
+    """Steps 2-3 for one head: loss_j and the gradient of loss_j w.r.t. everything in its window.
+
+    hs[s_j] is treated as data: the backward pass stops there (need_dx False at layer s_j + 1).
+    """
+    s, e = _windows(cfg)[hi - 1]
+    loss, hc = L.head_loss(cfg, P, hi, hs[e], y)
+    dh, grads = L.head_bwd(cfg, P, hi, hc)
+    for li in range(e, s, -1):
+        dh, g = L.layer_bwd(cfg, P, li, caches[li], dh, need_dx=(li > s + 1))
+        grads.update(g)
+    return loss, grads
+
+
+def local_gradients(cfg, params, x, y, dtype=np.float64, per_head=False):
+    """Steps 1-3.  Returns (losses[n_heads], grads by parameter name, coverage count by name).
+
+    Parameters covered by no window are absent from ``grads``.
+    """
+    P = _cast(params, dtype)
+    xx = x if np.issubdtype(np.asarray(x).dtype, np.integer) else np.asarray(x, dtype=dtype)
+    hs, caches = forward_all(cfg, P, xx)
+    losses = []
+    total, count, each = {}, {}, []
+    for hi in range(1, len(cfg.heads) + 1):
+        loss, g = head_gradients(cfg, P, hi, hs, caches, y)
+        losses.append(loss)
+        each.append(g)
+        for k, v in g.items():
+            if k in total:
+                total[k] = total[k] + v
+                count[k] += 1
+            else:
+                total[k] = v.copy()
+                count[k] = 1
+    if cfg.combine == "mean":
+        total = {k: v / count[k] for k, v in total.items()}
+    elif cfg.combine != "sum":
+        raise ValueError(cfg.combine)
+    if per_head:
+        return np.array(losses), total, count, each
+    return np.array(losses), total, count
+
+
+def block_gradients(cfg, params, hi, h_s, y, dtype=np.float64):
+    """Head hi alone, fed its window input h_s as data (that input is detached by definition, so
+    the block's loss and gradients depend on the rest of the network only through h_s)."""
+    P = _cast(params, dtype)
+    s, e = _windows(cfg)[hi - 1]
+    x = h_s if np.issubdtype(np.asarray(h_s).dtype, np.integer) else np.asarray(h_s, dtype=dtype)
+    hs = {s: x}
+    caches = {}
+    for li in range(s + 1, e + 1):
+        hs[li], caches[li] = L.layer_fwd(cfg, P, li, hs[li - 1])
+    loss, hc = L.head_loss(cfg, P, hi, hs[e], y)
+    dh, grads = L.head_bwd(cfg, P, hi, hc)
+    for li in range(e, s, -1):
+        dh, g = L.layer_bwd(cfg, P, li, caches[li], dh, need_dx=(li > s + 1))
+        grads.update(g)
+    return loss, grads, hs[e]
+
+
+# ----------------------------------------------------------------------------- optimizers
+def new_state(cfg, params, dtype=np.float64):
+    st = {"t": 0}
+    if cfg.opt.kind in ("sgdm", "adam"):
+        st["m"] = {k: np.zeros(v.shape, dtype) for k, v in params.items()}
+    if cfg.opt.kind == "adam":
+        st["v"] = {k: np.zeros(v.shape, dtype) for k, v in params.items()}
+    return st
+
+
+def optimizer_update(opt, p, g, state, name, t):
+    """One update of one tensor.  SGD: p -= lr g.  SGD-momentum: v = mu v + g; p -= lr v.
+    Adam: m = b1 m + (1-b1) g; v = b2 v + (1-b2) g^2; p -= lr (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps).
+    Optional L2 weight decay adds wd*p to g first."""
+    if opt.weight_decay:
+        g = g + opt.weight_decay * p
+    if opt.kind == "sgd":
+        return p - opt.lr * g
+    if opt.kind == "sgdm":
+        m = opt.momentum * state["m"][name] + g
+        state["m"][name] = m
+        return p - opt.lr * m
+    if opt.kind == "adam":
+        m = opt.beta1 * state["m"][name] + (1.0 - opt.beta1) * g
+        v = opt.beta2 * state["v"][name] + (1.0 - opt.beta2) * g * g
+        state["m"][name] = m
+        state["v"][name] = v
+        mhat = m / (1.0 - opt.beta1 ** t)
+        vhat = v / (1.0 - opt.beta2 ** t)
+        return p - opt.lr * mhat / (np.sqrt(vhat) + opt.eps)
+    raise ValueError(opt.kind)
+
+
+def local_step(cfg, params, state, x, y, dtype=np.float64):
+    """Steps 1-5.  Returns (losses, new params, grads).  ``state`` is updated in place."""
+    losses, grads, _ = local_gradients(cfg, params, x, y, dtype)
+    state["t"] += 1
+    t = state["t"]
+    new = {}
+    for k, p in params.items():
+        p = np.asarray(p, dtype=dtype)
+        new[k] = optimizer_update(cfg.opt, p, grads[k], state, k, t) if k in grads else p
+    return losses, new, grads
