@@ -1,0 +1,157 @@
+/*
+ * lp.h -- C ABI of the local-parallelism training step for AMD MI355X (gfx950).
+ *
+ * The library trains a deep network by *local updates* (paper section 3): the network is an
+ * ordered list of atomic layers; a local-training scheme is a list of auxiliary heads, head j
+ * attached after layer e_j, whose loss is backpropagated through the last w_j layers ending at
+ * e_j and no further (the activation entering layer e_j - w_j + 1 is treated as data).  Greedy
+ * local parallelism is one head per layer with w = 1; overlapping is w = 2; chunked is one head
+ * every K layers with w = K; ordinary backpropagation is a single head with w = L; the
+ * "last K layers" baseline is a single head with w = K.  Every parameter covered by at least one
+ * window takes one optimizer update per step, as soon as its gradient is final; nothing waits for
+ * a global backward pass.
+ *
+ * All pointers named *_dev are DEVICE pointers, all others are HOST pointers.  The caller owns
+ * every device buffer and the HIP stream; the library owns only host metadata.  No entry point
+ * throws or aborts: each returns an lp_status, and lp_last_error() gives the text.  Argument
+ * errors are found on the host before anything is launched and leave the context unchanged.
+ * One context may be used by one host thread at a time.
+ */
+#ifndef LP_H_
+#define LP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lp_ctx lp_ctx; /* opaque */
+
+typedef enum {
+  LP_OK = 0,
+  LP_EINVAL = 1,       /* null pointer, bad enum, window < 1, heads not ordered by layer, ...     */
+  LP_ESHAPE = 2,       /* batch > max_batch, width not divisible by heads, unsupported size      */
+  LP_EALIGN = 3,       /* a device buffer is not 256-byte aligned                                 */
+  LP_ENOMEM = 4,       /* a device buffer is smaller than lp_query_sizes() asked for              */
+  LP_EDEVICE = 5,      /* a HIP call failed (text in lp_last_error)                               */
+  LP_ESTATE = 6,       /* context unusable (failed init, destroyed)                               */
+  LP_EUNSUPPORTED = 7, /* valid request that this build does not implement                        */
+  LP_ENOTFOUND = 8     /* unknown tensor name                                                     */
+} lp_status;
+
+typedef enum { LP_F32 = 0, LP_BF16 = 1 } lp_dtype; /* compute dtype; master weights, gradients and
+                                                      optimizer state are always fp32 */
+typedef enum { LP_I32 = 2 } lp_dtype_extra;        /* reported by lp_tensor_info for index data */
+
+/* Atomic layer forms (appendix A "MLP", appendix B.2 "Transformers", appendix B.3 "ResNets"). */
+typedef enum {
+  LP_LAYER_RESMLP = 0,       /* p = x (or x Win^T + bin if in_dim != width);
+                                out = p + W2 relu(W1 p + b1) + b2                                   */
+  LP_LAYER_DECODER = 1,      /* pre-LN causal decoder layer: u = h + Wo attn(LN1 h); out = u + FFN(LN2 u) */
+  LP_LAYER_RESNET_STAGE = 2  /* optional stem conv3x3+BN+ReLU, then n BasicBlocks (conv-BN-ReLU-conv-BN,
+                                add shortcut, ReLU); first block strided with a 1x1 conv+BN shortcut */
+} lp_layer_kind;
+
+/* Auxiliary heads: same form as the global objective (section 3). */
+typedef enum {
+  LP_HEAD_LINEAR_CE = 0,      /* Linear(in_dim -> n_classes) + softmax cross-entropy              */
+  LP_HEAD_POOL_LINEAR_CE = 1, /* mean over H x W, then Linear + CE                                 */
+  LP_HEAD_LN_LINEAR_CE = 2    /* LayerNorm, Linear to the vocabulary (no bias), next-token CE      */
+} lp_head_kind;
+
+typedef enum { LP_OPT_SGD = 0, LP_OPT_SGDM = 1, LP_OPT_ADAM = 2 } lp_opt_kind;
+typedef enum { LP_COMBINE_SUM = 0, LP_COMBINE_MEAN = 1 } lp_combine;
+typedef enum { LP_ACT_GELU = 0, LP_ACT_RELU = 1 } lp_act;
+
+typedef struct {
+  int kind;                 /* lp_layer_kind */
+  int in_dim, width, hidden;                 /* resmlp: in, width, hidden.  decoder: width d, hidden F */
+  int n_heads, seq_len, causal, act;         /* decoder */
+  int in_ch, out_ch, stride, n_basic_blocks, has_stem, in_hw; /* resnet stage (square NHWC input) */
+} lp_layer_spec;
+
+typedef struct {
+  int kind;                 /* lp_head_kind */
+  int after_layer;          /* e_j, 1-based; heads must be listed with non-decreasing e_j          */
+  int window;               /* w_j >= 1; clamped to e_j                                            */
+  int in_dim, n_classes, bias;
+} lp_head_spec;
+
+typedef struct {
+  int kind;                 /* lp_opt_kind */
+  float lr, momentum, beta1, beta2, eps, weight_decay;
+} lp_opt_spec;
+
+typedef struct {
+  int n_layers;
+  const lp_layer_spec* layers;
+  int n_heads;
+  const lp_head_spec* heads;
+  lp_opt_spec opt;
+  int combine;              /* lp_combine: how the contributions of several heads to one layer merge
+                               (the paper averages duplicated layers; a config may ask for the sum)  */
+  int dtype;                /* lp_dtype */
+  int max_batch;
+  int vocab;                /* > 0: layer 1 owns a token embedding [vocab, width] + fixed sinusoidal
+                               positions, and x is int32 token ids                                  */
+  uint64_t seed;            /* seed of the built-in weight initialiser                              */
+} lp_model_spec;
+
+typedef struct { size_t param_bytes, state_bytes, work_bytes; } lp_sizes;
+typedef struct { void* params_dev; void* state_dev; void* work_dev; } lp_buffers;
+
+/* Sizes of the three caller-allocated device buffers for this model (host only, no HIP call).
+ * params: fp32 master weights (+ a bf16 working copy when dtype is bf16); state: optimizer
+ * moments; work: gradients, activations and scratch. */
+int lp_query_sizes(const lp_model_spec* spec, lp_sizes* out);
+
+/* Build a context over caller-allocated buffers (each 256-byte aligned and at least as large as
+ * lp_query_sizes says), zero the optimizer state, and initialise the weights from spec->seed
+ * (Kaiming-normal for MLP / conv / small heads, N(0, 0.02) for decoder layers and vocabulary
+ * heads, gains 1, biases 0).  `hip_stream` is a hipStream_t (NULL = default stream); all later
+ * work of this context is enqueued on it.  The spec is copied; the buffers are borrowed until
+ * lp_destroy.  On failure *out is NULL. */
+int lp_init_blocks(const lp_model_spec* spec, const lp_buffers* buffers, void* hip_stream, lp_ctx** out);
+
+/* One local-update step on one minibatch (section 3): forward through all layers with the
+ * current weights; for every head, its loss, the gradient inside its window only, and the
+ * optimizer update of every covered parameter.  x_dev: fp32 [batch, in_dim] (resmlp), fp32 or bf16
+ * NHWC [batch, H, W, C] in the compute dtype (resnet), int32 [batch, seq_len] token ids (decoder
+ * with vocab).  y_dev: int32 [batch] class labels, or int32 [batch, seq_len] next-token targets.
+ * losses_dev: fp32 [n_heads], head j's mean loss at the PRE-update weights.  Asynchronous: results
+ * are valid once the context's stream has been synchronised. */
+int lp_local_step(lp_ctx* ctx, const void* x_dev, const int32_t* y_dev, int batch, float* losses_dev);
+
+/* Forward pass and head losses only; no state changes.  (BatchNorm uses the statistics of the
+ * batch given, so this equals the losses a step on the same batch would report.) */
+int lp_eval_loss(lp_ctx* ctx, const void* x_dev, const int32_t* y_dev, int batch, float* losses_dev);
+
+/* Named tensors.  Parameters "L3.wqkv", "H2.w" (fp32 master; setting one also refreshes the bf16
+ * working copy); their gradients of the last step "L3.wqkv.grad" and optimizer moments ".m", ".v"
+ * (fp32); layer outputs of the last forward "L3.out" and the embedded input "L0.out" (compute
+ * dtype, shaped for the batch of that call).  lp_tensor_info reports shape, lp_dtype and bytes.
+ * get/set copy synchronously between host memory and the device after draining the stream;
+ * `bytes` must equal the tensor's size. */
+int lp_tensor_info(lp_ctx* ctx, const char* name, int64_t shape[4], int* ndim, int* dtype, size_t* bytes);
+int lp_get_tensor(lp_ctx* ctx, const char* name, void* dst_host, size_t bytes);
+int lp_set_tensor(lp_ctx* ctx, const char* name, const void* src_host, size_t bytes);
+/* Number of parameter tensors, and the i-th name (storage order: layers, then heads). */
+int lp_num_params(lp_ctx* ctx);
+const char* lp_param_name(lp_ctx* ctx, int i);
+/* Optimizer step counter t (Adam bias correction uses t counted from 1). */
+int lp_get_step(lp_ctx* ctx);
+int lp_set_step(lp_ctx* ctx, int t);
+
+/* Text of the last error on this context (or of the last failed init when ctx is NULL); valid
+ * until the next call. */
+const char* lp_last_error(const lp_ctx* ctx);
+
+/* Free host metadata.  Never frees caller memory. */
+void lp_destroy(lp_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LP_H_ */

@@ -1,0 +1,9 @@
+"""Local-parallelism training step for AMD MI355X: HIP kernels behind a C ABI (liblp.so) and a thin
+ctypes binding with the same entry-point names."""
+from .binding import (LpError, LocalTrainer, lib, make_spec, lp_query_sizes, lp_init_blocks, lp_local_step,
+                      lp_eval_loss, lp_tensor_info, lp_get_tensor, lp_set_tensor, lp_param_names, lp_get_step,
+                      lp_set_step, lp_destroy, LIB_PATH)
+
+__all__ = ["LpError", "LocalTrainer", "lib", "make_spec", "lp_query_sizes", "lp_init_blocks", "lp_local_step",
+           "lp_eval_loss", "lp_tensor_info", "lp_get_tensor", "lp_set_tensor", "lp_param_names", "lp_get_step",
+           "lp_set_step", "lp_destroy", "LIB_PATH"]

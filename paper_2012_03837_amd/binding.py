@@ -1,0 +1,256 @@
+"""ctypes binding of liblp.so: argument marshalling only.
+
+Every function mirrors an entry point of include/lp.h under the same name.  PyTorch supplies
+device memory and the HIP stream; nothing is computed here.  There is no CPU fallback: if the
+library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblp.so")
+
+LP_OK, LP_EINVAL, LP_ESHAPE, LP_EALIGN, LP_ENOMEM, LP_EDEVICE, LP_ESTATE, LP_EUNSUPPORTED, LP_ENOTFOUND = range(9)
+LP_F32, LP_BF16, LP_I32 = 0, 1, 2
+LAYER_KINDS = {"resmlp": 0, "decoder": 1, "resnet_stage": 2}
+HEAD_KINDS = {"linear_ce": 0, "pool_linear_ce": 1, "ln_linear_ce": 2}
+OPT_KINDS = {"sgd": 0, "sgdm": 1, "adam": 2}
+COMBINE = {"sum": 0, "mean": 1}
+ACTS = {"gelu": 0, "relu": 1}
+DTYPES = {"f32": LP_F32, "bf16": LP_BF16}
+
+
+class LpError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"lp status {status}: {msg}")
+        self.status = status
+
+
+class lp_layer_spec(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("kind", "in_dim", "width", "hidden", "n_heads", "seq_len", "causal", "act",
+                                        "in_ch", "out_ch", "stride", "n_basic_blocks", "has_stem", "in_hw")]
+
+
+class lp_head_spec(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("kind", "after_layer", "window", "in_dim", "n_classes", "bias")]
+
+
+class lp_opt_spec(C.Structure):
+    _fields_ = [("kind", C.c_int)] + [(n, C.c_float) for n in ("lr", "momentum", "beta1", "beta2", "eps",
+                                                                "weight_decay")]
+
+
+class lp_model_spec(C.Structure):
+    _fields_ = [("n_layers", C.c_int), ("layers", C.POINTER(lp_layer_spec)), ("n_heads", C.c_int),
+                ("heads", C.POINTER(lp_head_spec)), ("opt", lp_opt_spec), ("combine", C.c_int), ("dtype", C.c_int),
+                ("max_batch", C.c_int), ("vocab", C.c_int), ("seed", C.c_uint64)]
+
+
+class lp_sizes(C.Structure):
+    _fields_ = [("param_bytes", C.c_size_t), ("state_bytes", C.c_size_t), ("work_bytes", C.c_size_t)]
+
+
+class lp_buffers(C.Structure):
+    _fields_ = [("params_dev", C.c_void_p), ("state_dev", C.c_void_p), ("work_dev", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads liblp.so (built by `python -m paper_2012_03837_amd.build`); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2012_03837_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, ip, sz = C.c_void_p, C.c_int, C.c_size_t
+        L.lp_query_sizes.argtypes = [C.POINTER(lp_model_spec), C.POINTER(lp_sizes)]
+        L.lp_init_blocks.argtypes = [C.POINTER(lp_model_spec), C.POINTER(lp_buffers), vp, C.POINTER(vp)]
+        L.lp_local_step.argtypes = [vp, vp, vp, ip, vp]
+        L.lp_eval_loss.argtypes = [vp, vp, vp, ip, vp]
+        L.lp_tensor_info.argtypes = [vp, C.c_char_p, C.POINTER(C.c_int64), C.POINTER(ip), C.POINTER(ip), C.POINTER(sz)]
+        L.lp_get_tensor.argtypes = [vp, C.c_char_p, vp, sz]
+        L.lp_set_tensor.argtypes = [vp, C.c_char_p, vp, sz]
+        L.lp_num_params.argtypes = [vp]
+        L.lp_param_name.argtypes = [vp, ip]
+        L.lp_param_name.restype = C.c_char_p
+        L.lp_get_step.argtypes = [vp]
+        L.lp_set_step.argtypes = [vp, ip]
+        L.lp_last_error.argtypes = [vp]
+        L.lp_last_error.restype = C.c_char_p
+        L.lp_destroy.argtypes = [vp]
+        L.lp_destroy.restype = None
+        _lib = L
+    return _lib
+
+
+def make_spec(cfg, max_batch: int | None = None):
+    """lp_model_spec from a plain-data model description (fields as in lp_inputs.ModelCfg).
+    Returns (spec, keepalive): the arrays the spec points into must outlive its use."""
+    layers = (lp_layer_spec * len(cfg.layers))()
+    for i, l in enumerate(cfg.layers):
+        layers[i] = lp_layer_spec(LAYER_KINDS[l.kind], l.in_dim, l.width, l.hidden, l.n_heads, l.seq_len, l.causal,
+                                  ACTS[l.act], l.in_ch, l.out_ch, l.stride, l.n_basic_blocks, l.has_stem, l.in_hw)
+    heads = (lp_head_spec * len(cfg.heads))()
+    for i, h in enumerate(cfg.heads):
+        heads[i] = lp_head_spec(HEAD_KINDS[h.kind], h.after_layer, h.window, h.in_dim, h.n_classes, h.bias)
+    o = cfg.opt
+    opt = lp_opt_spec(OPT_KINDS[o.kind], o.lr, o.momentum, o.beta1, o.beta2, o.eps, o.weight_decay)
+    spec = lp_model_spec(len(cfg.layers), layers, len(cfg.heads), heads, opt, COMBINE[cfg.combine],
+                         DTYPES[cfg.dtype], cfg.batch if max_batch is None else max_batch, cfg.vocab, cfg.seed)
+    return spec, (layers, heads)
+
+
+def _check(status: int, ctx=None):
+    if status != LP_OK:
+        msg = lib().lp_last_error(ctx)
+        raise LpError(status, msg.decode() if msg else "")
+
+
+def lp_query_sizes(spec: lp_model_spec) -> lp_sizes:
+    out = lp_sizes()
+    _check(lib().lp_query_sizes(C.byref(spec), C.byref(out)))
+    return out
+
+
+def lp_init_blocks(spec: lp_model_spec, params_ptr: int, state_ptr: int, work_ptr: int, stream: int = 0) -> int:
+    bufs = lp_buffers(params_ptr, state_ptr, work_ptr)
+    ctx = C.c_void_p()
+    _check(lib().lp_init_blocks(C.byref(spec), C.byref(bufs), C.c_void_p(stream), C.byref(ctx)))
+    return ctx.value
+
+
+def lp_local_step(ctx: int, x_ptr: int, y_ptr: int, batch: int, losses_ptr: int) -> None:
+    _check(lib().lp_local_step(ctx, x_ptr, y_ptr, batch, losses_ptr), ctx)
+
+
+def lp_eval_loss(ctx: int, x_ptr: int, y_ptr: int, batch: int, losses_ptr: int) -> None:
+    _check(lib().lp_eval_loss(ctx, x_ptr, y_ptr, batch, losses_ptr), ctx)
+
+
+def lp_tensor_info(ctx: int, name: str):
+    shape = (C.c_int64 * 4)()
+    ndim, dtype, nbytes = C.c_int(), C.c_int(), C.c_size_t()
+    _check(lib().lp_tensor_info(ctx, name.encode(), shape, C.byref(ndim), C.byref(dtype), C.byref(nbytes)), ctx)
+    return tuple(shape[i] for i in range(ndim.value)), dtype.value, nbytes.value
+
+
+def _bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def lp_get_tensor(ctx: int, name: str) -> np.ndarray:
+    """Copies a named tensor to the host; bf16 tensors are widened to float32 (exactly)."""
+    shape, dtype, nbytes = lp_tensor_info(ctx, name)
+    raw = np.empty(nbytes, dtype=np.uint8)
+    _check(lib().lp_get_tensor(ctx, name.encode(), raw.ctypes.data, nbytes), ctx)
+    if dtype == LP_BF16:
+        return _bf16_bits_to_f32(raw.view(np.uint16)).reshape(shape)
+    return raw.view(np.float32 if dtype == LP_F32 else np.int32).reshape(shape)
+
+
+def lp_set_tensor(ctx: int, name: str, value: np.ndarray) -> None:
+    shape, dtype, nbytes = lp_tensor_info(ctx, name)
+    if dtype != LP_F32:
+        raise LpError(LP_EUNSUPPORTED, "only fp32 tensors can be set")
+    v = np.ascontiguousarray(value, dtype=np.float32)
+    if tuple(v.shape) != tuple(shape):
+        raise LpError(LP_ESHAPE, f"{name}: shape {v.shape} != {shape}")
+    _check(lib().lp_set_tensor(ctx, name.encode(), v.ctypes.data, nbytes), ctx)
+
+
+def lp_param_names(ctx: int):
+    L = lib()
+    return [L.lp_param_name(ctx, i).decode() for i in range(L.lp_num_params(ctx))]
+
+
+def lp_get_step(ctx: int) -> int:
+    return lib().lp_get_step(ctx)
+
+
+def lp_set_step(ctx: int, t: int) -> None:
+    _check(lib().lp_set_step(ctx, t), ctx)
+
+
+def lp_destroy(ctx: int) -> None:
+    lib().lp_destroy(ctx)
+
+
+class LocalTrainer:
+    """Owns the three device buffers (torch tensors) and a context over them."""
+
+    def __init__(self, cfg, device="cuda:0", max_batch: int | None = None, stream=None):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the local-update step runs only on the HIP device")
+        self.torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.spec, self._keep = make_spec(cfg, max_batch)
+        sz = lp_query_sizes(self.spec)
+        self.sizes = sz
+        with torch.cuda.device(self.device):
+            self.params = torch.empty(sz.param_bytes, dtype=torch.uint8, device=self.device)
+            self.state = torch.empty(sz.state_bytes, dtype=torch.uint8, device=self.device)
+            self.work = torch.empty(sz.work_bytes, dtype=torch.uint8, device=self.device)
+            self.losses = torch.zeros(len(cfg.heads), dtype=torch.float32, device=self.device)
+            self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+            torch.cuda.synchronize(self.device)
+            self.ctx = lp_init_blocks(self.spec, self.params.data_ptr(), self.state.data_ptr(), self.work.data_ptr(),
+                                      self.stream.cuda_stream)
+
+    # ---- data staging (host numpy -> device tensors in the layout lp.h asks for)
+    def stage(self, x: np.ndarray, y: np.ndarray):
+        torch = self.torch
+        if np.issubdtype(x.dtype, np.integer):
+            xd = torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(self.device)
+        else:
+            xd = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(self.device)
+            if self.cfg.dtype == "bf16":
+                xd = xd.to(torch.bfloat16)
+        yd = torch.from_numpy(np.ascontiguousarray(y, dtype=np.int32)).to(self.device)
+        return xd.contiguous(), yd.contiguous()
+
+    def step(self, xd, yd, batch: int | None = None):
+        b = xd.shape[0] if batch is None else batch
+        lp_local_step(self.ctx, xd.data_ptr(), yd.data_ptr(), b, self.losses.data_ptr())
+        return self.losses
+
+    def eval(self, xd, yd, batch: int | None = None):
+        b = xd.shape[0] if batch is None else batch
+        lp_eval_loss(self.ctx, xd.data_ptr(), yd.data_ptr(), b, self.losses.data_ptr())
+        return self.losses
+
+    def get(self, name: str) -> np.ndarray:
+        return lp_get_tensor(self.ctx, name)
+
+    def set(self, name: str, value: np.ndarray) -> None:
+        lp_set_tensor(self.ctx, name, value)
+
+    def names(self):
+        return lp_param_names(self.ctx)
+
+    def set_params(self, params: Dict[str, np.ndarray]) -> None:
+        for k, v in params.items():
+            self.set(k, v)
+
+    def get_params(self) -> Dict[str, np.ndarray]:
+        return {k: self.get(k) for k in self.names()}
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            self.torch.cuda.synchronize(self.device)
+            lp_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

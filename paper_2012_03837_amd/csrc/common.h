@@ -1,0 +1,129 @@
+// Shared declarations of the HIP library: element types, error plumbing, and the internal
+// kernel-launch API ("ops") that the layer drivers call.  gfx950 only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace lp {
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+enum DType { F32 = 0, BF16 = 1, I32 = 2 };
+static inline size_t dtype_size(int dt) { return dt == BF16 ? 2 : 4; }
+
+__device__ __forceinline__ float to_f(float v) { return v; }
+__device__ __forceinline__ float to_f(bf16_t v) { return static_cast<float>(v); }
+template <typename T> __device__ __forceinline__ T from_f(float f);
+template <> __device__ __forceinline__ float from_f<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float f) { return static_cast<bf16_t>(f); }
+
+enum Act { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
+
+__device__ __forceinline__ float gelu_f(float x) {
+  const float c = 0.7978845608028654f, a = 0.044715f;
+  float t = tanhf(c * (x + a * x * x * x));
+  return 0.5f * x * (1.0f + t);
+}
+__device__ __forceinline__ float dgelu_f(float x) {
+  const float c = 0.7978845608028654f, a = 0.044715f;
+  float t = tanhf(c * (x + a * x * x * x));
+  float dt = (1.0f - t * t) * c * (1.0f + 3.0f * a * x * x);
+  return 0.5f * (1.0f + t) + 0.5f * x * dt;
+}
+
+// C[M,N] (+)= alpha * sum_k A(m,k) B(n,k), then the epilogue:
+//   v = acc (+ bias[n]); if (pre) pre[m,n] = v; v = act(v); if (dact) v *= act'(dact_src[m,n]);
+//   if (res) v += res[m,n]; C[m,n] = (accumulate ? C[m,n] : 0) + v.
+// A(m,k) = a_kc ? A[m*lda + k] : A[k*lda + m];  B(n,k) = b_kc ? B[n*ldb + k] : B[k*ldb + n].
+// Operands, pre, dact_src and res are in the compute dtype; C is compute dtype unless c_f32.
+struct GemmArgs {
+  const void* A = nullptr; int64_t lda = 0; int a_kc = 1;
+  const void* B = nullptr; int64_t ldb = 0; int b_kc = 1;
+  void* C = nullptr; int64_t ldc = 0; int c_f32 = 0;
+  int M = 0, N = 0, K = 0;
+  const float* bias = nullptr;
+  int act = ACT_NONE;
+  void* pre = nullptr;
+  const void* dact_src = nullptr; int dact = ACT_NONE; int64_t ldd = 0;
+  const void* res = nullptr; int64_t ldr = 0;
+  int accumulate = 0;
+};
+
+// Convolution as an implicit GEMM over NHWC activations and [O,R,S,C] filters.
+struct ConvArgs {
+  int N, H, W, C;      // input
+  int O, R, S;         // filters
+  int stride, pad;
+  int P, Q;            // output spatial
+};
+
+struct OpCtx {
+  hipStream_t stream;
+  int dt;              // compute dtype
+  float* partial;      // fp32 scratch for two-stage reductions
+  size_t partial_elems;
+};
+
+// ---- ops (each enqueues on ctx.stream and returns a hipError_t) -------------------------------
+hipError_t op_gemm(const OpCtx& c, const GemmArgs& g);
+hipError_t op_fill_f32(const OpCtx& c, float* p, size_t n, float v);
+hipError_t op_cast_to_compute(const OpCtx& c, const float* src, void* dst, size_t n);
+
+hipError_t op_embed_fwd(const OpCtx& c, const int32_t* ids, const float* emb, const float* pe, void* out,
+                        int T, int S, int d, int V);
+hipError_t op_embed_bwd(const OpCtx& c, const int32_t* ids, const void* dh, float* demb, int T, int V, int d,
+                        int accumulate);
+hipError_t op_posenc_init(const OpCtx& c, float* pe, int S, int d);
+
+hipError_t op_layernorm_fwd(const OpCtx& c, const void* x, const float* g, const float* b, void* y,
+                            float* mean, float* rstd, int rows, int d);
+// dx = (add ? add : 0) + LN-backward(dy); dg/db accumulate if `accumulate`.  dx may be null.
+hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const float* mean, const float* rstd,
+                            const float* g, const void* add, void* dx, float* dg, float* db, int rows, int d,
+                            int accumulate);
+hipError_t op_colsum(const OpCtx& c, const void* dy, int64_t ld, float* out, int rows, int n, int accumulate);
+
+hipError_t op_attn_fwd(const OpCtx& c, const void* qkv, void* o, float* lse, int B, int S, int H, int dh,
+                       int causal);
+hipError_t op_attn_bwd(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout,
+                       void* dqkv, float* delta, int B, int S, int H, int dh, int causal);
+
+// Row-wise softmax cross-entropy over logits z [rows, n] (compute dtype, leading dim ld).
+// loss_rows[r] = logsumexp(z_r) - z[r, y_r].  If write_grad: z is overwritten by
+// (softmax(z_r) - onehot(y_r)) * inv_rows.
+hipError_t op_softmax_ce(const OpCtx& c, void* z, int64_t ld, const int32_t* y, float* loss_rows, int rows,
+                         int n, int write_grad, float inv_rows);
+hipError_t op_mean(const OpCtx& c, const float* v, int n, float* out);
+
+struct OptArgs {
+  int kind; float lr, momentum, beta1, beta2, eps, weight_decay; int t; float grad_scale;
+};
+hipError_t op_optimizer(const OpCtx& c, const OptArgs& o, float* p, const float* g, float* m, float* v,
+                        void* p_lowp, size_t n);
+
+hipError_t op_init_normal(const OpCtx& c, float* p, size_t n, float std, uint64_t seed, uint64_t stream_id);
+
+// conv / batchnorm / pooling
+hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out);
+hipError_t op_conv_bwd_data(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx);
+hipError_t op_conv_bwd_weight(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
+                              int accumulate);
+// y = [relu]( bn(z) (+ res) ), batch statistics over rows = N*H*W; saves mean, rstd.
+hipError_t op_batchnorm_fwd(const OpCtx& c, const void* z, const float* g, const float* b, const void* res,
+                            void* y, float* mean, float* rstd, int rows, int C, int relu);
+// dy_eff = relu ? dy * (y > 0) : dy;  dz = bn-backward(dy_eff); dg, db; if dres: dres = dy_eff.
+hipError_t op_batchnorm_bwd(const OpCtx& c, const void* dy, const void* y, const void* z, const float* mean,
+                            const float* rstd, const float* g, void* dz, void* dres, float* dg, float* db,
+                            int rows, int C, int relu, int accumulate);
+hipError_t op_avgpool_fwd(const OpCtx& c, const void* x, void* out, int N, int HW, int C);
+hipError_t op_avgpool_bwd(const OpCtx& c, const void* dfeat, void* dx, int N, int HW, int C);
+hipError_t op_add(const OpCtx& c, const void* a, const void* b, void* out, size_t n);
+
+}  // namespace lp

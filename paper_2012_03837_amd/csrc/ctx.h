@@ -1,0 +1,125 @@
+// Host-side context of the library: copied spec, parameter table, buffer layout, per-layer
+// activation slots.  Nothing here is visible through the C ABI.
+#pragma once
+
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/lp.h"
+#include "common.h"
+
+namespace lp {
+
+struct Tensor {
+  std::string name;
+  int ndim = 0;
+  int64_t shape[4] = {0, 0, 0, 0};
+  size_t numel = 0;
+  size_t off = 0;        // element offset in the flat parameter space (multiple of 64)
+  int owner = 0;         // layer index 1..L, or L + head index (1-based)
+  int init = 0;          // 0: normal(std), 1: ones, 2: zeros
+  float std = 0.f;
+};
+
+// One convolution + BatchNorm unit of a ResNet stage.
+struct ConvUnit {
+  ConvArgs a;
+  int w = -1, g = -1, b = -1;   // tensor indices: filter, BN gain, BN shift
+  void* z = nullptr;            // conv output
+  void* y = nullptr;            // BN (+res) (+ReLU) output
+  float* mean = nullptr;
+  float* rstd = nullptr;
+  int relu = 0;
+};
+struct BasicBlock { ConvUnit c1, c2, proj; bool has_proj = false; };
+
+struct LayerState {
+  lp_layer_spec s;
+  size_t p_begin = 0, p_end = 0;     // flat parameter range [begin, end)
+  int coverage = 0;                  // number of heads whose window covers this layer
+  int seen = 0;                      // contributions received so far in the current step
+  void* out = nullptr;               // layer output (compute dtype)
+  size_t out_elems_per_sample = 0;
+  // tensor indices (−1 if absent)
+  std::map<std::string, int> t;
+  // residual MLP
+  void *mlp_p = nullptr, *mlp_r = nullptr;
+  // decoder
+  void *a = nullptr, *qkv = nullptr, *o = nullptr, *u = nullptr, *c = nullptr, *fpre = nullptr, *f = nullptr;
+  float *mean1 = nullptr, *rstd1 = nullptr, *mean2 = nullptr, *rstd2 = nullptr, *lse = nullptr;
+  // resnet stage
+  bool has_stem = false;
+  ConvUnit stem;
+  std::vector<BasicBlock> blocks;
+};
+
+struct HeadState {
+  lp_head_spec s;
+  size_t p_begin = 0, p_end = 0;
+  int s_lo = 0, e = 0;               // window (s_lo, e]
+  std::map<std::string, int> t;
+};
+
+struct Arena {
+  char* base = nullptr;
+  size_t used = 0;
+  void* take(size_t bytes) {
+    size_t o = (used + 255) & ~(size_t)255;
+    used = o + bytes;
+    return base ? base + o : nullptr;
+  }
+};
+
+}  // namespace lp
+
+struct lp_ctx {
+  lp_model_spec spec;
+  std::vector<lp_layer_spec> layer_specs;
+  std::vector<lp_head_spec> head_specs;
+  std::vector<lp::Tensor> tensors;
+  std::map<std::string, int> index;
+  std::vector<lp::LayerState> layers;   // [0] unused; 1..L
+  std::vector<lp::HeadState> heads;     // 0-based
+  size_t P = 0;                         // flat parameter elements
+  int dt = 0;
+  hipStream_t stream = nullptr;
+  // device memory (borrowed)
+  float* master = nullptr; void* lowp = nullptr;
+  float* mom = nullptr; float* var = nullptr;
+  float* grads = nullptr;
+  float* partial = nullptr; size_t partial_elems = 0;
+  float* loss_rows = nullptr;
+  float* pe = nullptr;
+  void* h0 = nullptr;                    // embedded input of layer 1
+  const void* x_in = nullptr;            // input of the current call
+  // backward scratch
+  void *dA = nullptr, *dB = nullptr, *dF = nullptr, *dc = nullptr, *du = nullptr, *dO = nullptr, *dqkv = nullptr,
+       *da = nullptr;
+  float* delta = nullptr;
+  void *sG = nullptr, *sZ = nullptr, *sR = nullptr, *sD1 = nullptr, *sD2 = nullptr;  // resnet
+  // head scratch
+  void *feat = nullptr, *logits = nullptr, *dfeat = nullptr;
+  float *hmean = nullptr, *hrstd = nullptr;
+  int step_t = 0;
+  int last_batch = 0;
+  bool ok = false;
+  std::string err;
+
+  lp::OpCtx op() const {
+    lp::OpCtx c; c.stream = stream; c.dt = dt; c.partial = partial; c.partial_elems = partial_elems; return c;
+  }
+  float* P32(int ti) const { return master + tensors[ti].off; }
+  float* G32(int ti) const { return grads + tensors[ti].off; }
+  // matrix weights in the compute dtype (bf16 working copy, or the fp32 master itself)
+  const void* W(int ti) const {
+    return dt == lp::BF16 ? (const void*)((const lp::bf16_t*)lowp + tensors[ti].off) : (const void*)(master + tensors[ti].off);
+  }
+};
+
+namespace lp {
+int drv_forward(lp_ctx* c, int li, int batch, const int32_t* ids_or_null);
+int drv_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int accumulate);
+int drv_head(lp_ctx* c, int hi, int batch, const int32_t* y, float* loss_out, bool backward, void* dh);
+size_t layer_out_elems(const lp_layer_spec& s, int batch);
+}

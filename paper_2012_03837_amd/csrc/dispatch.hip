@@ -1,0 +1,33 @@
+// Choice of kernel per op and compute dtype: MFMA kernels for bf16 where they apply, plain kernels
+// for fp32 and for shapes the MFMA kernels do not take.
+#include "common.h"
+
+namespace lp {
+
+hipError_t attn_fwd_plain(const OpCtx& c, const void* qkv, void* o, float* lse, int B, int S, int H, int dh, int causal);
+hipError_t attn_bwd_plain(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout,
+                          void* dqkv, float* delta, int B, int S, int H, int dh, int causal);
+hipError_t conv_fwd_plain(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out);
+hipError_t conv_bwd_data_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx);
+hipError_t conv_bwd_weight_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
+                                 int accumulate);
+
+hipError_t op_attn_fwd(const OpCtx& c, const void* qkv, void* o, float* lse, int B, int S, int H, int dh, int causal) {
+  return attn_fwd_plain(c, qkv, o, lse, B, S, H, dh, causal);
+}
+hipError_t op_attn_bwd(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout, void* dqkv,
+                       float* delta, int B, int S, int H, int dh, int causal) {
+  return attn_bwd_plain(c, qkv, o, lse, dout, dqkv, delta, B, S, H, dh, causal);
+}
+hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {
+  return conv_fwd_plain(c, a, x, w, out);
+}
+hipError_t op_conv_bwd_data(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx) {
+  return conv_bwd_data_plain(c, a, dout, w, dx);
+}
+hipError_t op_conv_bwd_weight(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
+                              int accumulate) {
+  return conv_bwd_weight_plain(c, a, dout, x, dw, accumulate);
+}
+
+}  // namespace lp

@@ -1,0 +1,313 @@
+// Layer and head drivers: the sequence of kernel launches for the forward pass of one atomic layer,
+// its backward pass inside a truncation window, and an auxiliary head's loss and gradient.
+#include "ctx.h"
+
+namespace lp {
+
+#define DO(expr)                                                                           \
+  do {                                                                                     \
+    hipError_t e_ = (expr);                                                                \
+    if (e_ != hipSuccess) {                                                                \
+      c->err = std::string(#expr) + ": " + hipGetErrorString(e_);                          \
+      return LP_EDEVICE;                                                                   \
+    }                                                                                      \
+  } while (0)
+
+static inline char* bptr(void* p, size_t elems, int dt) { return (char*)p + elems * dtype_size(dt); }
+
+size_t layer_out_elems(const lp_layer_spec& s, int batch) {
+  switch (s.kind) {
+    case LP_LAYER_RESMLP: return (size_t)batch * s.width;
+    case LP_LAYER_DECODER: return (size_t)batch * s.seq_len * s.width;
+    case LP_LAYER_RESNET_STAGE: { int hw = s.in_hw / s.stride; return (size_t)batch * hw * hw * s.out_ch; }
+  }
+  return 0;
+}
+
+static const void* layer_input(lp_ctx* c, int li) {
+  if (li == 1) return (c->spec.vocab > 0 && c->layers[1].s.kind == LP_LAYER_DECODER) ? c->h0 : c->x_in;
+  return c->layers[li - 1].out;
+}
+
+// y = x W^T + b with optional activation / saved pre-activation / residual
+static GemmArgs lin_fwd(const lp_ctx* c, const void* x, int rows, int ti_w, int ti_b, void* y) {
+  const Tensor& w = c->tensors[ti_w];
+  GemmArgs g;
+  g.A = x; g.lda = w.shape[1]; g.a_kc = 1;
+  g.B = c->W(ti_w); g.ldb = w.shape[1]; g.b_kc = 1;
+  g.C = y; g.ldc = w.shape[0];
+  g.M = rows; g.N = (int)w.shape[0]; g.K = (int)w.shape[1];
+  g.bias = ti_b >= 0 ? c->P32(ti_b) : nullptr;
+  return g;
+}
+// dx = dy W  (W is [out, in]: reduction over `out`, which is W's slow index)
+static GemmArgs lin_dgrad(const lp_ctx* c, const void* dy, int rows, int ti_w, void* dx) {
+  const Tensor& w = c->tensors[ti_w];
+  GemmArgs g;
+  g.A = dy; g.lda = w.shape[0]; g.a_kc = 1;
+  g.B = c->W(ti_w); g.ldb = w.shape[1]; g.b_kc = 0;
+  g.C = dx; g.ldc = w.shape[1];
+  g.M = rows; g.N = (int)w.shape[1]; g.K = (int)w.shape[0];
+  return g;
+}
+// dW[out, in] (+)= dy^T x   (reduction over rows: the slow index of both operands), fp32 output
+static GemmArgs lin_wgrad(const lp_ctx* c, const void* dy, const void* x, int rows, int ti_w, int accumulate) {
+  const Tensor& w = c->tensors[ti_w];
+  GemmArgs g;
+  g.A = dy; g.lda = w.shape[0]; g.a_kc = 0;
+  g.B = x; g.ldb = w.shape[1]; g.b_kc = 0;
+  g.C = c->G32(ti_w); g.ldc = w.shape[1]; g.c_f32 = 1;
+  g.M = (int)w.shape[0]; g.N = (int)w.shape[1]; g.K = rows;
+  g.accumulate = accumulate;
+  return g;
+}
+
+// ===================================================================================== residual MLP
+static int mlp_forward(lp_ctx* c, int li, int batch) {
+  LayerState& L = c->layers[li];
+  OpCtx o = c->op();
+  const void* x = layer_input(c, li);
+  const void* p = x;
+  if (L.t.count("win")) {
+    GemmArgs g = lin_fwd(c, x, batch, L.t["win"], L.t["bin"], L.mlp_p);
+    DO(op_gemm(o, g));
+    p = L.mlp_p;
+  }
+  GemmArgs g1 = lin_fwd(c, p, batch, L.t["w1"], L.t["b1"], L.mlp_r);
+  g1.act = ACT_RELU;
+  DO(op_gemm(o, g1));
+  GemmArgs g2 = lin_fwd(c, L.mlp_r, batch, L.t["w2"], L.t["b2"], L.out);
+  g2.res = p; g2.ldr = L.s.width;
+  DO(op_gemm(o, g2));
+  return LP_OK;
+}
+
+static int mlp_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int acc) {
+  LayerState& L = c->layers[li];
+  OpCtx o = c->op();
+  const void* x = layer_input(c, li);
+  bool proj = L.t.count("win") > 0;
+  const void* p = proj ? L.mlp_p : x;
+  int width = L.s.width, hidden = L.s.hidden;
+  DO(op_colsum(o, dout, width, c->G32(L.t["b2"]), batch, width, acc));
+  DO(op_gemm(o, lin_wgrad(c, dout, L.mlp_r, batch, L.t["w2"], acc)));
+  // da = (dout W2) * relu'(r)
+  GemmArgs gd = lin_dgrad(c, dout, batch, L.t["w2"], c->dF);
+  gd.dact = ACT_RELU; gd.dact_src = L.mlp_r; gd.ldd = hidden;
+  DO(op_gemm(o, gd));
+  DO(op_colsum(o, c->dF, hidden, c->G32(L.t["b1"]), batch, hidden, acc));
+  DO(op_gemm(o, lin_wgrad(c, c->dF, p, batch, L.t["w1"], acc)));
+  if (!proj && !need_dx) return LP_OK;
+  // dp = da W1 + dout
+  void* dp = proj ? c->dc : dx;
+  GemmArgs g1 = lin_dgrad(c, c->dF, batch, L.t["w1"], dp);
+  g1.res = dout; g1.ldr = width;
+  DO(op_gemm(o, g1));
+  if (proj) {
+    DO(op_colsum(o, dp, width, c->G32(L.t["bin"]), batch, width, acc));
+    DO(op_gemm(o, lin_wgrad(c, dp, x, batch, L.t["win"], acc)));
+    if (need_dx) DO(op_gemm(o, lin_dgrad(c, dp, batch, L.t["win"], dx)));
+  }
+  return LP_OK;
+}
+
+// ===================================================================================== decoder layer
+static int dec_forward(lp_ctx* c, int li, int batch, const int32_t* ids) {
+  LayerState& L = c->layers[li];
+  OpCtx o = c->op();
+  int S = L.s.seq_len, d = L.s.width, H = L.s.n_heads, T = batch * S;
+  if (li == 1 && c->spec.vocab > 0)
+    DO(op_embed_fwd(o, ids, c->P32(L.t["emb"]), c->pe, c->h0, T, S, d, c->spec.vocab));
+  const void* x = layer_input(c, li);
+  DO(op_layernorm_fwd(o, x, c->P32(L.t["ln1.g"]), c->P32(L.t["ln1.b"]), L.a, L.mean1, L.rstd1, T, d));
+  DO(op_gemm(o, lin_fwd(c, L.a, T, L.t["wqkv"], L.t["bqkv"], L.qkv)));
+  DO(op_attn_fwd(o, L.qkv, L.o, L.lse, batch, S, H, d / H, L.s.causal));
+  GemmArgs go = lin_fwd(c, L.o, T, L.t["wo"], L.t["bo"], L.u);
+  go.res = x; go.ldr = d;
+  DO(op_gemm(o, go));
+  DO(op_layernorm_fwd(o, L.u, c->P32(L.t["ln2.g"]), c->P32(L.t["ln2.b"]), L.c, L.mean2, L.rstd2, T, d));
+  GemmArgs g1 = lin_fwd(c, L.c, T, L.t["w1"], L.t["b1"], L.f);
+  g1.act = L.s.act == LP_ACT_RELU ? ACT_RELU : ACT_GELU;
+  g1.pre = L.fpre;
+  DO(op_gemm(o, g1));
+  GemmArgs g2 = lin_fwd(c, L.f, T, L.t["w2"], L.t["b2"], L.out);
+  g2.res = L.u; g2.ldr = d;
+  DO(op_gemm(o, g2));
+  return LP_OK;
+}
+
+static int dec_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int acc,
+                        const int32_t* ids) {
+  LayerState& L = c->layers[li];
+  OpCtx o = c->op();
+  int S = L.s.seq_len, d = L.s.width, H = L.s.n_heads, F = L.s.hidden, T = batch * S;
+  const void* x = layer_input(c, li);
+  bool has_emb = (li == 1 && c->spec.vocab > 0);
+  // FFN
+  DO(op_colsum(o, dout, d, c->G32(L.t["b2"]), T, d, acc));
+  DO(op_gemm(o, lin_wgrad(c, dout, L.f, T, L.t["w2"], acc)));
+  GemmArgs gd = lin_dgrad(c, dout, T, L.t["w2"], c->dF);
+  gd.dact = L.s.act == LP_ACT_RELU ? ACT_RELU : ACT_GELU; gd.dact_src = L.fpre; gd.ldd = F;
+  DO(op_gemm(o, gd));
+  DO(op_colsum(o, c->dF, F, c->G32(L.t["b1"]), T, F, acc));
+  DO(op_gemm(o, lin_wgrad(c, c->dF, L.c, T, L.t["w1"], acc)));
+  DO(op_gemm(o, lin_dgrad(c, c->dF, T, L.t["w1"], c->dc)));
+  // du = dout + LN2-backward(dc)
+  DO(op_layernorm_bwd(o, c->dc, L.u, L.mean2, L.rstd2, c->P32(L.t["ln2.g"]), dout, c->du, c->G32(L.t["ln2.g"]),
+                      c->G32(L.t["ln2.b"]), T, d, acc));
+  // attention block
+  DO(op_colsum(o, c->du, d, c->G32(L.t["bo"]), T, d, acc));
+  DO(op_gemm(o, lin_wgrad(c, c->du, L.o, T, L.t["wo"], acc)));
+  DO(op_gemm(o, lin_dgrad(c, c->du, T, L.t["wo"], c->dO)));
+  DO(op_attn_bwd(o, L.qkv, L.o, L.lse, c->dO, c->dqkv, c->delta, batch, S, H, d / H, L.s.causal));
+  DO(op_colsum(o, c->dqkv, 3 * d, c->G32(L.t["bqkv"]), T, 3 * d, acc));
+  DO(op_gemm(o, lin_wgrad(c, c->dqkv, L.a, T, L.t["wqkv"], acc)));
+  DO(op_gemm(o, lin_dgrad(c, c->dqkv, T, L.t["wqkv"], c->da)));
+  // dh = du + LN1-backward(da); the input gradient itself is only needed inside a window or for the embedding
+  bool want_dx = need_dx || has_emb;
+  void* dh = want_dx ? (has_emb ? c->da : dx) : nullptr;   // LN backward may write over its own dy rows
+  DO(op_layernorm_bwd(o, c->da, x, L.mean1, L.rstd1, c->P32(L.t["ln1.g"]), c->du, dh, c->G32(L.t["ln1.g"]),
+                      c->G32(L.t["ln1.b"]), T, d, acc));
+  if (has_emb) DO(op_embed_bwd(o, ids, dh, c->G32(L.t["emb"]), T, c->spec.vocab, d, acc));
+  return LP_OK;
+}
+
+// ===================================================================================== ResNet stage
+static int unit_forward(lp_ctx* c, ConvUnit& u, const void* x, const void* res) {
+  OpCtx o = c->op();
+  DO(op_conv_fwd(o, u.a, x, c->W(u.w), u.z));
+  int rows = u.a.N * u.a.P * u.a.Q;
+  DO(op_batchnorm_fwd(o, u.z, c->P32(u.g), c->P32(u.b), res, u.y, u.mean, u.rstd, rows, u.a.O, u.relu));
+  return LP_OK;
+}
+// dy -> (dz in sZ) -> dw, and dx if asked.  dres (if non-null) receives the ReLU-masked dy.
+static int unit_backward(lp_ctx* c, ConvUnit& u, const void* x, const void* dy, void* dres, void* dx, int acc) {
+  OpCtx o = c->op();
+  int rows = u.a.N * u.a.P * u.a.Q;
+  DO(op_batchnorm_bwd(o, dy, u.y, u.z, u.mean, u.rstd, c->P32(u.g), c->sZ, dres, c->G32(u.g), c->G32(u.b), rows,
+                      u.a.O, u.relu, acc));
+  DO(op_conv_bwd_weight(o, u.a, c->sZ, x, c->G32(u.w), acc));
+  if (dx) DO(op_conv_bwd_data(o, u.a, c->sZ, c->W(u.w), dx));
+  return LP_OK;
+}
+static void set_batch(ConvUnit& u, int batch) { u.a.N = batch; }
+
+static int res_forward(lp_ctx* c, int li, int batch) {
+  LayerState& L = c->layers[li];
+  const void* h = layer_input(c, li);
+  int st;
+  if (L.has_stem) {
+    set_batch(L.stem, batch);
+    if ((st = unit_forward(c, L.stem, h, nullptr)) != LP_OK) return st;
+    h = L.stem.y;
+  }
+  for (auto& b : L.blocks) {
+    set_batch(b.c1, batch); set_batch(b.c2, batch); set_batch(b.proj, batch);
+    if ((st = unit_forward(c, b.c1, h, nullptr)) != LP_OK) return st;
+    const void* sc = h;
+    if (b.has_proj) {
+      if ((st = unit_forward(c, b.proj, h, nullptr)) != LP_OK) return st;
+      sc = b.proj.y;
+    }
+    if ((st = unit_forward(c, b.c2, b.c1.y, sc)) != LP_OK) return st;
+    h = b.c2.y;
+  }
+  return LP_OK;
+}
+
+static int res_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int acc) {
+  LayerState& L = c->layers[li];
+  OpCtx o = c->op();
+  const void* g = dout;
+  int st;
+  for (int bi = (int)L.blocks.size() - 1; bi >= 0; --bi) {
+    BasicBlock& b = L.blocks[bi];
+    const void* bin = bi > 0 ? L.blocks[bi - 1].c2.y : (L.has_stem ? L.stem.y : layer_input(c, li));
+    bool first_op = (bi == 0 && !L.has_stem);
+    bool want_dx = need_dx || !first_op;
+    // c2: dz2 -> dw2, dt (into sD1); masked upstream gradient ds -> sR
+    if ((st = unit_backward(c, b.c2, b.c1.y, g, c->sR, c->sD1, acc)) != LP_OK) return st;
+    // c1
+    if ((st = unit_backward(c, b.c1, bin, c->sD1, nullptr, want_dx ? c->sD1 : nullptr, acc)) != LP_OK) return st;
+    size_t n_in = (size_t)b.c1.a.N * b.c1.a.H * b.c1.a.W * b.c1.a.C;
+    void* dst = (first_op && need_dx) ? dx : c->sG;
+    if (b.has_proj) {
+      if ((st = unit_backward(c, b.proj, bin, c->sR, nullptr, want_dx ? c->sD2 : nullptr, acc)) != LP_OK) return st;
+      if (want_dx) DO(op_add(o, c->sD1, c->sD2, dst, n_in));
+    } else {
+      if (want_dx) DO(op_add(o, c->sD1, c->sR, dst, n_in));
+    }
+    g = dst;
+  }
+  if (L.has_stem) {
+    if ((st = unit_backward(c, L.stem, layer_input(c, li), g, nullptr, need_dx ? dx : nullptr, acc)) != LP_OK)
+      return st;
+  }
+  return LP_OK;
+}
+
+// ===================================================================================== dispatch
+int drv_forward(lp_ctx* c, int li, int batch, const int32_t* ids) {
+  switch (c->layers[li].s.kind) {
+    case LP_LAYER_RESMLP: return mlp_forward(c, li, batch);
+    case LP_LAYER_DECODER: return dec_forward(c, li, batch, ids);
+    case LP_LAYER_RESNET_STAGE: return res_forward(c, li, batch);
+  }
+  return LP_EINVAL;
+}
+int drv_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int accumulate) {
+  switch (c->layers[li].s.kind) {
+    case LP_LAYER_RESMLP: return mlp_backward(c, li, batch, dout, dx, need_dx, accumulate);
+    case LP_LAYER_DECODER: return dec_backward(c, li, batch, dout, dx, need_dx, accumulate, (const int32_t*)c->x_in);
+    case LP_LAYER_RESNET_STAGE: return res_backward(c, li, batch, dout, dx, need_dx, accumulate);
+  }
+  return LP_EINVAL;
+}
+
+// ===================================================================================== heads
+// Loss of head hi on the output of layer e; if `backward`, also the head's parameter gradients and
+// d loss / d h_e into dh.
+int drv_head(lp_ctx* c, int hi, int batch, const int32_t* y, float* loss_out, bool backward, void* dh) {
+  HeadState& Hd = c->heads[hi];
+  LayerState& L = c->layers[Hd.e];
+  OpCtx o = c->op();
+  const void* h = L.out;
+  int rows, in_dim = Hd.s.in_dim, ncls = Hd.s.n_classes;
+  const void* feat = h;
+  int hw = 0;
+  if (Hd.s.kind == LP_HEAD_POOL_LINEAR_CE) {
+    int side = L.s.in_hw / L.s.stride;
+    hw = side * side;
+    rows = batch;
+    DO(op_avgpool_fwd(o, h, c->feat, batch, hw, in_dim));
+    feat = c->feat;
+  } else if (Hd.s.kind == LP_HEAD_LN_LINEAR_CE) {
+    rows = batch * L.s.seq_len;
+    DO(op_layernorm_fwd(o, h, c->P32(Hd.t["ln.g"]), c->P32(Hd.t["ln.b"]), c->feat, c->hmean, c->hrstd, rows, in_dim));
+    feat = c->feat;
+  } else {
+    rows = batch;
+  }
+  int tb = Hd.t.count("b") ? Hd.t["b"] : -1;
+  DO(op_gemm(o, lin_fwd(c, feat, rows, Hd.t["w"], tb, c->logits)));
+  DO(op_softmax_ce(o, c->logits, ncls, y, c->loss_rows, rows, ncls, backward ? 1 : 0, 1.0f / (float)rows));
+  DO(op_mean(o, c->loss_rows, rows, loss_out));
+  if (!backward) return LP_OK;
+  // logits now hold dZ
+  if (tb >= 0) DO(op_colsum(o, c->logits, ncls, c->G32(tb), rows, ncls, 0));
+  DO(op_gemm(o, lin_wgrad(c, c->logits, feat, rows, Hd.t["w"], 0)));
+  if (Hd.s.kind == LP_HEAD_LINEAR_CE) {
+    DO(op_gemm(o, lin_dgrad(c, c->logits, rows, Hd.t["w"], dh)));
+  } else {
+    DO(op_gemm(o, lin_dgrad(c, c->logits, rows, Hd.t["w"], c->dfeat)));
+    if (Hd.s.kind == LP_HEAD_POOL_LINEAR_CE) {
+      DO(op_avgpool_bwd(o, c->dfeat, dh, batch, hw, in_dim));
+    } else {
+      DO(op_layernorm_bwd(o, c->dfeat, h, c->hmean, c->hrstd, c->P32(Hd.t["ln.g"]), nullptr, dh,
+                          c->G32(Hd.t["ln.g"]), c->G32(Hd.t["ln.b"]), rows, in_dim, 0));
+    }
+  }
+  return LP_OK;
+}
+
+}  // namespace lp

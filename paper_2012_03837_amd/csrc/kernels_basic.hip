@@ -1,0 +1,429 @@
+// Memory-bound kernels: fills and casts, embedding, LayerNorm, column sums, softmax cross-entropy,
+// the fused optimizer update, and the weight initialiser.  64-wide wavefront reductions; every
+// reduction has a fixed order, so repeated runs are bit-identical.
+#include "common.h"
+
+namespace lp {
+
+#define LP_LAUNCH_CHECK() hipGetLastError()
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// Sum over a block of 256 threads (4 waves); result valid in every thread.  `sh` holds >= 4 floats.
+__device__ __forceinline__ float block_sum_256(float v, float* sh) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return sh[0] + sh[1] + sh[2] + sh[3];
+}
+__device__ __forceinline__ float block_max_256(float v, float* sh) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+}
+
+// ------------------------------------------------------------------------------------ fill / cast
+__global__ void k_fill_f32(float* p, size_t n, float v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t st = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += st) p[i] = v;
+}
+hipError_t op_fill_f32(const OpCtx& c, float* p, size_t n, float v) {
+  if (n == 0) return hipSuccess;
+  int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+  k_fill_f32<<<blocks, 256, 0, c.stream>>>(p, n, v);
+  return LP_LAUNCH_CHECK();
+}
+
+template <typename T>
+__global__ void k_cast(const float* src, T* dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t st = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += st) dst[i] = from_f<T>(src[i]);
+}
+hipError_t op_cast_to_compute(const OpCtx& c, const float* src, void* dst, size_t n) {
+  if (n == 0) return hipSuccess;
+  int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+  if (c.dt == BF16) k_cast<bf16_t><<<blocks, 256, 0, c.stream>>>(src, (bf16_t*)dst, n);
+  else k_cast<float><<<blocks, 256, 0, c.stream>>>(src, (float*)dst, n);
+  return LP_LAUNCH_CHECK();
+}
+
+template <typename T>
+__global__ void k_add(const T* a, const T* b, T* out, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t st = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += st) out[i] = from_f<T>(to_f(a[i]) + to_f(b[i]));
+}
+hipError_t op_add(const OpCtx& c, const void* a, const void* b, void* out, size_t n) {
+  if (n == 0) return hipSuccess;
+  int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+  if (c.dt == BF16) k_add<bf16_t><<<blocks, 256, 0, c.stream>>>((const bf16_t*)a, (const bf16_t*)b, (bf16_t*)out, n);
+  else k_add<float><<<blocks, 256, 0, c.stream>>>((const float*)a, (const float*)b, (float*)out, n);
+  return LP_LAUNCH_CHECK();
+}
+
+// ------------------------------------------------------------------------------------ embedding
+// Fixed sinusoidal positions, evaluated once in double precision at init:
+// pe[s, 2i] = sin(s / 10000^(2i/d)), pe[s, 2i+1] = cos(same angle).
+__global__ void k_posenc(float* pe, int S, int d) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= S * d) return;
+  int s = i / d, j = i % d;
+  double ang = (double)s / pow(10000.0, (double)(j / 2 * 2) / (double)d);
+  pe[i] = (float)((j & 1) ? cos(ang) : sin(ang));
+}
+hipError_t op_posenc_init(const OpCtx& c, float* pe, int S, int d) {
+  int n = S * d;
+  k_posenc<<<(n + 255) / 256, 256, 0, c.stream>>>(pe, S, d);
+  return LP_LAUNCH_CHECK();
+}
+
+template <typename T>
+__global__ void k_embed_fwd(const int32_t* ids, const float* emb, const float* pe, T* out, int T_, int S, int d,
+                            int V) {
+  int t = blockIdx.x;
+  int id = ids[t];
+  id = id < 0 ? 0 : (id >= V ? V - 1 : id);   // out-of-range ids are clamped, never read out of bounds
+  int s = t % S;
+  const float* e = emb + (size_t)id * d;
+  const float* p = pe + (size_t)s * d;
+  T* o = out + (size_t)t * d;
+  for (int j = threadIdx.x; j < d; j += blockDim.x) o[j] = from_f<T>(e[j] + p[j]);
+}
+hipError_t op_embed_fwd(const OpCtx& c, const int32_t* ids, const float* emb, const float* pe, void* out,
+                        int T_, int S, int d, int V) {
+  if (T_ == 0) return hipSuccess;
+  if (c.dt == BF16) k_embed_fwd<bf16_t><<<T_, 128, 0, c.stream>>>(ids, emb, pe, (bf16_t*)out, T_, S, d, V);
+  else k_embed_fwd<float><<<T_, 128, 0, c.stream>>>(ids, emb, pe, (float*)out, T_, S, d, V);
+  return LP_LAUNCH_CHECK();
+}
+
+// Gradient of the embedding table: row v = sum over the positions t with ids[t] == v of dh[t, :],
+// taken in increasing t (fixed order: no atomics).  One block per (row, 256-column slab): the block
+// scans all ids, compacts the matching positions in order, then sums those rows.
+template <typename T>
+__global__ void k_embed_bwd(const int32_t* ids, const T* dh, float* demb, int T_, int d, int accumulate) {
+  __shared__ int pos[256];
+  __shared__ int wcount[4];
+  int v = blockIdx.x;
+  int col = blockIdx.y * 256 + threadIdx.x;
+  float acc = 0.f;
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int base = 0; base < T_; base += 256) {
+    int t = base + threadIdx.x;
+    bool hit = (t < T_) && (ids[t] == v);
+    unsigned long long mask = __ballot(hit);
+    if (lane == 0) wcount[w] = __popcll(mask);
+    __syncthreads();
+    int off = 0;
+    for (int i = 0; i < w; ++i) off += wcount[i];
+    int total = wcount[0] + wcount[1] + wcount[2] + wcount[3];
+    if (hit) pos[off + __popcll(mask & ((1ull << lane) - 1ull))] = t;
+    __syncthreads();
+    if (col < d)
+      for (int i = 0; i < total; ++i) acc += to_f(dh[(size_t)pos[i] * d + col]);
+    __syncthreads();
+  }
+  if (col < d) {
+    size_t o = (size_t)v * d + col;
+    demb[o] = accumulate ? demb[o] + acc : acc;
+  }
+}
+hipError_t op_embed_bwd(const OpCtx& c, const int32_t* ids, const void* dh, float* demb, int T_, int V, int d,
+                        int accumulate) {
+  dim3 grid(V, (d + 255) / 256);
+  if (c.dt == BF16) k_embed_bwd<bf16_t><<<grid, 256, 0, c.stream>>>(ids, (const bf16_t*)dh, demb, T_, d, accumulate);
+  else k_embed_bwd<float><<<grid, 256, 0, c.stream>>>(ids, (const float*)dh, demb, T_, d, accumulate);
+  return LP_LAUNCH_CHECK();
+}
+
+// ------------------------------------------------------------------------------------ LayerNorm
+// One wavefront per row; biased variance, eps 1e-5; statistics in fp32.
+constexpr float kLnEps = 1e-5f;
+
+template <typename T>
+__global__ void k_ln_fwd(const T* x, const float* g, const float* b, T* y, float* mean, float* rstd, int rows,
+                         int d) {
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const T* xr = x + (size_t)row * d;
+  float s = 0.f;
+  for (int j = lane; j < d; j += 64) s += to_f(xr[j]);
+  float mu = wave_sum(s) / (float)d;
+  float q = 0.f;
+  for (int j = lane; j < d; j += 64) { float t = to_f(xr[j]) - mu; q += t * t; }
+  float rs = rsqrtf(wave_sum(q) / (float)d + kLnEps);
+  T* yr = y + (size_t)row * d;
+  for (int j = lane; j < d; j += 64) yr[j] = from_f<T>((to_f(xr[j]) - mu) * rs * g[j] + b[j]);
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+}
+hipError_t op_layernorm_fwd(const OpCtx& c, const void* x, const float* g, const float* b, void* y, float* mean,
+                            float* rstd, int rows, int d) {
+  if (rows == 0) return hipSuccess;
+  int blocks = (rows + 3) / 4;
+  if (c.dt == BF16) k_ln_fwd<bf16_t><<<blocks, 256, 0, c.stream>>>((const bf16_t*)x, g, b, (bf16_t*)y, mean, rstd, rows, d);
+  else k_ln_fwd<float><<<blocks, 256, 0, c.stream>>>((const float*)x, g, b, (float*)y, mean, rstd, rows, d);
+  return LP_LAUNCH_CHECK();
+}
+
+// Backward.  Per row: dxhat = dy*g; dx = (dxhat - mean(dxhat) - xhat*mean(dxhat*xhat)) * rstd (+ add).
+// Parameter gradients: each block owns a contiguous slab of rows and writes its partial sums of
+// dy*xhat and dy to partial[block, 0..d) and partial[nblk + block, 0..d); a second kernel adds the
+// partials in block order.
+constexpr int kLnBwdRowsPerBlock = 32;
+template <typename T>
+__global__ void k_ln_bwd(const T* dy, const T* x, const float* mean, const float* rstd, const float* g,
+                         const T* add, T* dx, float* partial, int rows, int d) {
+  extern __shared__ float sh[];   // [4 waves][2][d]
+  int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float* pg = sh + (size_t)(w * 2) * d;
+  float* pb = pg + d;
+  for (int j = lane; j < d; j += 64) { pg[j] = 0.f; pb[j] = 0.f; }
+  int row0 = blockIdx.x * kLnBwdRowsPerBlock;
+  for (int r = w; r < kLnBwdRowsPerBlock; r += 4) {
+    int row = row0 + r;
+    if (row >= rows) break;
+    const T* xr = x + (size_t)row * d;
+    const T* dr = dy + (size_t)row * d;
+    float mu = mean[row], rs = rstd[row];
+    float s1 = 0.f, s2 = 0.f;
+    for (int j = lane; j < d; j += 64) {
+      float xh = (to_f(xr[j]) - mu) * rs;
+      float dyv = to_f(dr[j]);
+      float dxh = dyv * g[j];
+      s1 += dxh;
+      s2 += dxh * xh;
+      pg[j] += dyv * xh;
+      pb[j] += dyv;
+    }
+    s1 = wave_sum(s1) / (float)d;
+    s2 = wave_sum(s2) / (float)d;
+    if (dx) {
+      T* ox = dx + (size_t)row * d;
+      const T* ar = add ? add + (size_t)row * d : nullptr;
+      for (int j = lane; j < d; j += 64) {
+        float xh = (to_f(xr[j]) - mu) * rs;
+        float v = (to_f(dr[j]) * g[j] - s1 - xh * s2) * rs;
+        if (ar) v += to_f(ar[j]);
+        ox[j] = from_f<T>(v);
+      }
+    }
+  }
+  __syncthreads();
+  int nblk = gridDim.x;
+  for (int j = threadIdx.x; j < d; j += blockDim.x) {
+    float a = 0.f, bsum = 0.f;
+    for (int ww = 0; ww < 4; ++ww) { a += sh[(size_t)(ww * 2) * d + j]; bsum += sh[(size_t)(ww * 2 + 1) * d + j]; }
+    partial[(size_t)blockIdx.x * d + j] = a;
+    partial[(size_t)(nblk + blockIdx.x) * d + j] = bsum;
+  }
+}
+// out[j] (+)= sum_b partial[b, j], in block order.
+__global__ void k_reduce_partials(const float* partial, int nblk, int n, float* out, int accumulate) {
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  float a = 0.f;
+  for (int b = 0; b < nblk; ++b) a += partial[(size_t)b * n + j];
+  out[j] = accumulate ? out[j] + a : a;
+}
+hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const float* mean, const float* rstd,
+                            const float* g, const void* add, void* dx, float* dg, float* db, int rows, int d,
+                            int accumulate) {
+  if (rows == 0) return hipSuccess;
+  int nblk = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
+  if ((size_t)nblk * d * 2 > c.partial_elems) return hipErrorInvalidValue;
+  size_t shm = (size_t)8 * d * sizeof(float);
+  if (c.dt == BF16)
+    k_ln_bwd<bf16_t><<<nblk, 256, shm, c.stream>>>((const bf16_t*)dy, (const bf16_t*)x, mean, rstd, g,
+                                                   (const bf16_t*)add, (bf16_t*)dx, c.partial, rows, d);
+  else
+    k_ln_bwd<float><<<nblk, 256, shm, c.stream>>>((const float*)dy, (const float*)x, mean, rstd, g,
+                                                  (const float*)add, (float*)dx, c.partial, rows, d);
+  hipError_t e = LP_LAUNCH_CHECK();
+  if (e != hipSuccess) return e;
+  k_reduce_partials<<<(d + 255) / 256, 256, 0, c.stream>>>(c.partial, nblk, d, dg, accumulate);
+  k_reduce_partials<<<(d + 255) / 256, 256, 0, c.stream>>>(c.partial + (size_t)nblk * d, nblk, d, db, accumulate);
+  return LP_LAUNCH_CHECK();
+}
+
+// ------------------------------------------------------------------------------------ column sums
+// out[j] (+)= sum_r dy[r, j]  (bias gradients).  Block = 64 columns x 4 row-lanes over a slab of rows.
+constexpr int kColsumRows = 128;
+template <typename T>
+__global__ void k_colsum_partial(const T* dy, int64_t ld, float* partial, int rows, int n) {
+  __shared__ float sh[4][64];
+  int col = blockIdx.x * 64 + (threadIdx.x & 63);
+  int w = threadIdx.x >> 6;
+  int r0 = blockIdx.y * kColsumRows;
+  int r1 = r0 + kColsumRows < rows ? r0 + kColsumRows : rows;
+  float a = 0.f;
+  if (col < n)
+    for (int r = r0 + w; r < r1; r += 4) a += to_f(dy[(size_t)r * ld + col]);
+  sh[w][threadIdx.x & 63] = a;
+  __syncthreads();
+  if (w == 0 && col < n)
+    partial[(size_t)blockIdx.y * n + col] = sh[0][threadIdx.x] + sh[1][threadIdx.x] + sh[2][threadIdx.x] + sh[3][threadIdx.x];
+}
+hipError_t op_colsum(const OpCtx& c, const void* dy, int64_t ld, float* out, int rows, int n, int accumulate) {
+  if (n == 0) return hipSuccess;
+  int nslab = (rows + kColsumRows - 1) / kColsumRows;
+  if (nslab < 1) nslab = 1;
+  if ((size_t)nslab * n > c.partial_elems) return hipErrorInvalidValue;
+  dim3 grid((n + 63) / 64, nslab);
+  if (c.dt == BF16) k_colsum_partial<bf16_t><<<grid, 256, 0, c.stream>>>((const bf16_t*)dy, ld, c.partial, rows, n);
+  else k_colsum_partial<float><<<grid, 256, 0, c.stream>>>((const float*)dy, ld, c.partial, rows, n);
+  k_reduce_partials<<<(n + 255) / 256, 256, 0, c.stream>>>(c.partial, nslab, n, out, accumulate);
+  return LP_LAUNCH_CHECK();
+}
+
+// ------------------------------------------------------------------------------------ softmax CE
+// One block of 256 threads per row.  Pass 1: running max and sum of exp (online).  Pass 2 (if
+// write_grad): z <- (exp(z - lse) - [j == y]) * inv_rows.
+template <typename T>
+__global__ void k_softmax_ce(T* z, int64_t ld, const int32_t* y, float* loss_rows, int n, int write_grad,
+                             float inv_rows) {
+  __shared__ float sh[4];
+  int row = blockIdx.x;
+  T* zr = z + (size_t)row * ld;
+  float m = -INFINITY, s = 0.f;
+  for (int j = threadIdx.x; j < n; j += 256) {
+    float v = to_f(zr[j]);
+    if (v > m) { s = s * __expf(m - v) + 1.f; m = v; }
+    else s += __expf(v - m);
+  }
+  float gm = block_max_256(m, sh);
+  float contrib = (m == -INFINITY) ? 0.f : s * __expf(m - gm);
+  float gs = block_sum_256(contrib, sh);
+  float lse = gm + __logf(gs);
+  int yy = y[row];
+  bool y_ok = yy >= 0 && yy < n;               // a label outside [0, n) contributes lse and no one-hot term
+  if (threadIdx.x == 0) loss_rows[row] = lse - (y_ok ? to_f(zr[yy]) : 0.f);
+  if (write_grad) {
+    __syncthreads();
+    for (int j = threadIdx.x; j < n; j += 256) {
+      float p = __expf(to_f(zr[j]) - lse);
+      if (j == yy) p -= 1.f;
+      zr[j] = from_f<T>(p * inv_rows);
+    }
+  }
+}
+hipError_t op_softmax_ce(const OpCtx& c, void* z, int64_t ld, const int32_t* y, float* loss_rows, int rows, int n,
+                         int write_grad, float inv_rows) {
+  if (rows == 0) return hipSuccess;
+  if (c.dt == BF16) k_softmax_ce<bf16_t><<<rows, 256, 0, c.stream>>>((bf16_t*)z, ld, y, loss_rows, n, write_grad, inv_rows);
+  else k_softmax_ce<float><<<rows, 256, 0, c.stream>>>((float*)z, ld, y, loss_rows, n, write_grad, inv_rows);
+  return LP_LAUNCH_CHECK();
+}
+
+// out[0] = mean(v[0..n)) with a fixed summation tree (one block).
+__global__ void k_mean(const float* v, int n, float* out) {
+  __shared__ float sh[4];
+  float a = 0.f;
+  for (int i = threadIdx.x; i < n; i += 256) a += v[i];
+  float s = block_sum_256(a, sh);
+  if (threadIdx.x == 0) out[0] = s / (float)n;
+}
+hipError_t op_mean(const OpCtx& c, const float* v, int n, float* out) {
+  k_mean<<<1, 256, 0, c.stream>>>(v, n, out);
+  return LP_LAUNCH_CHECK();
+}
+
+// ------------------------------------------------------------------------------------ optimizer
+// One fused pass over a flat parameter range: reads p, g (and m, v), writes p (and m, v) and the
+// low-precision working copy.  SGD: p -= lr g.  SGD-momentum: m = mu m + g; p -= lr m.
+// Adam: m = b1 m + (1-b1) g; v = b2 v + (1-b2) g^2; p -= lr (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps).
+template <int KIND, bool LOWP>
+__global__ void k_optimizer(float* __restrict__ p, const float* __restrict__ g, float* __restrict__ m,
+                            float* __restrict__ v, bf16_t* __restrict__ pl, size_t n4, size_t n, float lr,
+                            float mu, float b1, float b2, float eps, float wd, float c1, float c2, float gs) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t st = (size_t)gridDim.x * blockDim.x;
+  for (; i < n4; i += st) {
+    float4 pp = reinterpret_cast<const float4*>(p)[i];
+    float4 gg = reinterpret_cast<const float4*>(g)[i];
+    float pv[4] = {pp.x, pp.y, pp.z, pp.w};
+    float gv[4] = {gg.x * gs, gg.y * gs, gg.z * gs, gg.w * gs};
+    float mv[4], vv[4];
+    if (KIND >= 1) { float4 t = reinterpret_cast<const float4*>(m)[i]; mv[0] = t.x; mv[1] = t.y; mv[2] = t.z; mv[3] = t.w; }
+    if (KIND == 2) { float4 t = reinterpret_cast<const float4*>(v)[i]; vv[0] = t.x; vv[1] = t.y; vv[2] = t.z; vv[3] = t.w; }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      float gk = gv[k] + wd * pv[k];
+      if (KIND == 0) pv[k] -= lr * gk;
+      else if (KIND == 1) { mv[k] = mu * mv[k] + gk; pv[k] -= lr * mv[k]; }
+      else {
+        mv[k] = b1 * mv[k] + (1.f - b1) * gk;
+        vv[k] = b2 * vv[k] + (1.f - b2) * gk * gk;
+        pv[k] -= lr * (mv[k] * c1) / (sqrtf(vv[k] * c2) + eps);
+      }
+    }
+    reinterpret_cast<float4*>(p)[i] = make_float4(pv[0], pv[1], pv[2], pv[3]);
+    if (KIND >= 1) reinterpret_cast<float4*>(m)[i] = make_float4(mv[0], mv[1], mv[2], mv[3]);
+    if (KIND == 2) reinterpret_cast<float4*>(v)[i] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+    if (LOWP) {
+      bf16x4 o = {static_cast<bf16_t>(pv[0]), static_cast<bf16_t>(pv[1]), static_cast<bf16_t>(pv[2]), static_cast<bf16_t>(pv[3])};
+      reinterpret_cast<bf16x4*>(pl)[i] = o;
+    }
+  }
+}
+hipError_t op_optimizer(const OpCtx& c, const OptArgs& o, float* p, const float* g, float* m, float* v,
+                        void* p_lowp, size_t n) {
+  if (n == 0) return hipSuccess;
+  if (n % 4) return hipErrorInvalidValue;   // ranges are padded to 64 elements by the layout
+  size_t n4 = n / 4;
+  size_t want = (n4 + 255) / 256;
+  int blocks = (int)(want < 256 * 16 ? want : 256 * 16);
+  float c1 = 1.f, c2 = 1.f;
+  if (o.kind == 2) {
+    c1 = (float)(1.0 / (1.0 - pow((double)o.beta1, (double)o.t)));
+    c2 = (float)(1.0 / (1.0 - pow((double)o.beta2, (double)o.t)));
+  }
+  bf16_t* pl = (bf16_t*)p_lowp;
+#define LP_OPT(K, L) k_optimizer<K, L><<<blocks, 256, 0, c.stream>>>(p, g, m, v, pl, n4, n, o.lr, o.momentum, o.beta1, o.beta2, o.eps, o.weight_decay, c1, c2, o.grad_scale)
+  if (o.kind == 0) { if (pl) LP_OPT(0, true); else LP_OPT(0, false); }
+  else if (o.kind == 1) { if (pl) LP_OPT(1, true); else LP_OPT(1, false); }
+  else { if (pl) LP_OPT(2, true); else LP_OPT(2, false); }
+#undef LP_OPT
+  return LP_LAUNCH_CHECK();
+}
+
+// ------------------------------------------------------------------------------------ init
+// Counter-based normal generator: two 64-bit mixes of (seed, stream, index) -> Box-Muller.
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+__global__ void k_init_normal(float* p, size_t n, float std, uint64_t seed, uint64_t sid) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t st = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += st) {
+    uint64_t a = mix64(mix64(seed ^ (sid * 0xD1342543DE82EF95ull)) + 2 * i);
+    uint64_t b = mix64(a + 1);
+    float u1 = ((float)(a >> 40) + 1.0f) * (1.0f / 16777217.0f);
+    float u2 = (float)(b >> 40) * (1.0f / 16777216.0f);
+    p[i] = std * sqrtf(-2.0f * logf(u1)) * cosf(6.283185307179586f * u2);
+  }
+}
+hipError_t op_init_normal(const OpCtx& c, float* p, size_t n, float std, uint64_t seed, uint64_t sid) {
+  if (n == 0) return hipSuccess;
+  int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+  k_init_normal<<<blocks, 256, 0, c.stream>>>(p, n, std, seed, sid);
+  return LP_LAUNCH_CHECK();
+}
+
+}  // namespace lp

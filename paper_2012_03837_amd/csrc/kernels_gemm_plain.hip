@@ -1,0 +1,152 @@
+// Plain tiled FMA GEMM with fp32 accumulation, generic over operand accessors.  It serves the fp32
+// compute path (the latency-bound residual-MLP configuration) and any shape or layout the MFMA
+// kernels do not take.  Convolutions run through it as implicit GEMMs over NHWC gathers.
+#include "common.h"
+#include "gemm_common.h"
+
+namespace lp {
+
+template <typename T>
+struct PlainOperand {          // logical (i, k) -> p[i*ld + k] if kc else p[k*ld + i]
+  const T* p; int64_t ld; int kc;
+  __device__ __forceinline__ float operator()(int i, int k) const {
+    return to_f(kc ? p[(size_t)i * ld + k] : p[(size_t)k * ld + i]);
+  }
+};
+
+// Convolution gathers (NHWC activations, [O,R,S,C] filters).
+template <typename T>
+struct ConvInputPatch {        // (m=(n,p,q), k=(r,s,c)) -> x[n, p*stride+r-pad, q*stride+s-pad, c] or 0
+  const T* x; ConvArgs a;
+  __device__ __forceinline__ float operator()(int m, int k) const {
+    int q = m % a.Q, t = m / a.Q, p = t % a.P, n = t / a.P;
+    int c = k % a.C, u = k / a.C, s = u % a.S, r = u / a.S;
+    int h = p * a.stride + r - a.pad, w = q * a.stride + s - a.pad;
+    if (h < 0 || h >= a.H || w < 0 || w >= a.W) return 0.f;
+    return to_f(x[(((size_t)n * a.H + h) * a.W + w) * a.C + c]);
+  }
+};
+template <typename T>
+struct ConvOutputGather {      // (m=(n,h,w), k=(r,s,o)) -> dout[n, (h+pad-r)/stride, (w+pad-s)/stride, o] if integral
+  const T* d; ConvArgs a;
+  __device__ __forceinline__ float operator()(int m, int k) const {
+    int w = m % a.W, t = m / a.W, h = t % a.H, n = t / a.H;
+    int o = k % a.O, u = k / a.O, s = u % a.S, r = u / a.S;
+    int hp = h + a.pad - r, wq = w + a.pad - s;
+    if (hp < 0 || wq < 0 || hp % a.stride || wq % a.stride) return 0.f;
+    int p = hp / a.stride, q = wq / a.stride;
+    if (p >= a.P || q >= a.Q) return 0.f;
+    return to_f(d[(((size_t)n * a.P + p) * a.Q + q) * a.O + o]);
+  }
+};
+template <typename T>
+struct ConvFilterT {           // (c, k=(r,s,o)) -> w[o, r, s, c]
+  const T* w; ConvArgs a;
+  __device__ __forceinline__ float operator()(int c, int k) const {
+    int o = k % a.O, u = k / a.O;   // u = r*S + s
+    return to_f(w[((size_t)o * a.R * a.S + u) * a.C + c]);
+  }
+};
+template <typename T>
+struct ConvPatchByCol {        // (j=(r,s,c), k=m) -> input patch element: same gather with arguments swapped
+  ConvInputPatch<T> g;
+  __device__ __forceinline__ float operator()(int j, int m) const { return g(m, j); }
+};
+
+constexpr int PBM = 64, PBN = 64, PBK = 16;
+
+template <typename T, typename OA, typename OB>
+__global__ void __launch_bounds__(256) k_gemm_plain(OA A, OB B, Epilogue e, int M, int N, int K) {
+  __shared__ float As[PBK][PBM + 1];
+  __shared__ float Bs[PBK][PBN + 1];
+  int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+  int m0 = blockIdx.y * PBM, n0 = blockIdx.x * PBN;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += PBK) {
+    for (int i = threadIdx.x; i < PBM * PBK; i += 256) {
+      int kk = i % PBK, mm = i / PBK;
+      int m = m0 + mm, k = k0 + kk;
+      As[kk][mm] = (m < M && k < K) ? A(m, k) : 0.f;
+      int n = n0 + mm;
+      Bs[kk][mm] = (n < N && k < K) ? B(n, k) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < PBK; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      if (m < M && n < N) epilogue_store<T>(e, m, n, acc[i][j]);
+    }
+}
+
+template <typename T, typename OA, typename OB>
+static hipError_t launch_plain(hipStream_t s, OA A, OB B, const Epilogue& e, int M, int N, int K) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  dim3 grid((N + PBN - 1) / PBN, (M + PBM - 1) / PBM);
+  k_gemm_plain<T, OA, OB><<<grid, 256, 0, s>>>(A, B, e, M, N, K);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t gemm_plain_t(const OpCtx& c, const GemmArgs& g) {
+  PlainOperand<T> A{(const T*)g.A, g.lda, g.a_kc}, B{(const T*)g.B, g.ldb, g.b_kc};
+  return launch_plain<T>(c.stream, A, B, make_epilogue(g), g.M, g.N, g.K);
+}
+hipError_t gemm_plain(const OpCtx& c, const GemmArgs& g) {
+  return c.dt == BF16 ? gemm_plain_t<bf16_t>(c, g) : gemm_plain_t<float>(c, g);
+}
+
+static Epilogue plain_out(void* C, int64_t ldc, int c_f32, int accumulate) {
+  GemmArgs g; g.C = C; g.ldc = ldc; g.c_f32 = c_f32; g.accumulate = accumulate;
+  return make_epilogue(g);
+}
+
+template <typename T>
+static hipError_t conv_fwd_t(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {
+  int M = a.N * a.P * a.Q, K = a.R * a.S * a.C;
+  ConvInputPatch<T> A{(const T*)x, a};
+  PlainOperand<T> B{(const T*)w, K, 1};
+  return launch_plain<T>(c.stream, A, B, plain_out(out, a.O, 0, 0), M, a.O, K);
+}
+template <typename T>
+static hipError_t conv_bwd_data_t(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx) {
+  int M = a.N * a.H * a.W, K = a.R * a.S * a.O;
+  ConvOutputGather<T> A{(const T*)dout, a};
+  ConvFilterT<T> B{(const T*)w, a};
+  return launch_plain<T>(c.stream, A, B, plain_out(dx, a.C, 0, 0), M, a.C, K);
+}
+template <typename T>
+static hipError_t conv_bwd_weight_t(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
+                                    int accumulate) {
+  int Mrows = a.N * a.P * a.Q, J = a.R * a.S * a.C;
+  PlainOperand<T> A{(const T*)dout, a.O, 0};            // (o, m) -> dout[m*O + o]
+  ConvPatchByCol<T> B{ConvInputPatch<T>{(const T*)x, a}};
+  return launch_plain<T>(c.stream, A, B, plain_out(dw, J, 1, accumulate), a.O, J, Mrows);
+}
+
+hipError_t conv_fwd_plain(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {
+  return c.dt == BF16 ? conv_fwd_t<bf16_t>(c, a, x, w, out) : conv_fwd_t<float>(c, a, x, w, out);
+}
+hipError_t conv_bwd_data_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx) {
+  return c.dt == BF16 ? conv_bwd_data_t<bf16_t>(c, a, dout, w, dx) : conv_bwd_data_t<float>(c, a, dout, w, dx);
+}
+hipError_t conv_bwd_weight_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
+                                 int accumulate) {
+  return c.dt == BF16 ? conv_bwd_weight_t<bf16_t>(c, a, dout, x, dw, accumulate)
+                      : conv_bwd_weight_t<float>(c, a, dout, x, dw, accumulate);
+}
+
+}  // namespace lp

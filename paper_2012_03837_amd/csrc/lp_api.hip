@@ -1,0 +1,546 @@
+// C ABI of the library: spec validation, buffer layout, context life cycle, the local-update step
+// (paper section 3) and named-tensor access.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "ctx.h"
+
+using namespace lp;
+
+static thread_local std::string g_init_err;
+
+static int fail(lp_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg; else g_init_err = msg;
+  return code;
+}
+
+// ------------------------------------------------------------------------------------- validation
+static int validate(const lp_model_spec* sp, std::string& err) {
+  if (!sp) { err = "spec is null"; return LP_EINVAL; }
+  if (sp->n_layers < 1 || !sp->layers) { err = "need at least one layer"; return LP_EINVAL; }
+  if (sp->n_heads < 1 || !sp->heads) { err = "need at least one head"; return LP_EINVAL; }
+  if (sp->dtype != LP_F32 && sp->dtype != LP_BF16) { err = "bad dtype"; return LP_EINVAL; }
+  if (sp->combine != LP_COMBINE_SUM && sp->combine != LP_COMBINE_MEAN) { err = "bad combine"; return LP_EINVAL; }
+  if (sp->opt.kind < LP_OPT_SGD || sp->opt.kind > LP_OPT_ADAM) { err = "bad optimizer kind"; return LP_EINVAL; }
+  if (sp->max_batch < 1) { err = "max_batch must be >= 1"; return LP_ESHAPE; }
+  if (sp->vocab < 0) { err = "vocab must be >= 0"; return LP_EINVAL; }
+  int kind0 = sp->layers[0].kind;
+  int64_t prev_out = -1;
+  for (int i = 0; i < sp->n_layers; ++i) {
+    const lp_layer_spec& l = sp->layers[i];
+    char where[32]; snprintf(where, sizeof where, "layer %d: ", i + 1);
+    if (l.kind != kind0) { err = std::string(where) + "all layers must be of one kind"; return LP_EUNSUPPORTED; }
+    if (l.kind == LP_LAYER_RESMLP) {
+      if (l.in_dim < 1 || l.width < 1 || l.hidden < 1) { err = std::string(where) + "dims must be >= 1"; return LP_ESHAPE; }
+      if (prev_out >= 0 && l.in_dim != prev_out) { err = std::string(where) + "in_dim != previous width"; return LP_ESHAPE; }
+      prev_out = l.width;
+    } else if (l.kind == LP_LAYER_DECODER) {
+      if (l.width < 1 || l.hidden < 1 || l.n_heads < 1 || l.seq_len < 1) { err = std::string(where) + "dims must be >= 1"; return LP_ESHAPE; }
+      if (l.width % l.n_heads) { err = std::string(where) + "width not divisible by n_heads"; return LP_ESHAPE; }
+      int dh = l.width / l.n_heads;
+      if (dh != 4 && dh != 8 && dh != 16 && dh != 32 && dh != 64) { err = std::string(where) + "head size must be 4, 8, 16, 32 or 64"; return LP_ESHAPE; }
+      if (l.act != LP_ACT_GELU && l.act != LP_ACT_RELU) { err = std::string(where) + "bad activation"; return LP_EINVAL; }
+      if (prev_out >= 0 && l.width != prev_out) { err = std::string(where) + "width changes between layers"; return LP_ESHAPE; }
+      if (i > 0 && l.seq_len != sp->layers[0].seq_len) { err = std::string(where) + "seq_len changes between layers"; return LP_ESHAPE; }
+      if (sp->vocab == 0) { err = "decoder layers need vocab > 0 (token input)"; return LP_EUNSUPPORTED; }
+      prev_out = l.width;
+    } else if (l.kind == LP_LAYER_RESNET_STAGE) {
+      if (l.in_ch < 1 || l.out_ch < 1 || l.in_hw < 1 || l.n_basic_blocks < 1) { err = std::string(where) + "dims must be >= 1"; return LP_ESHAPE; }
+      if (l.stride != 1 && l.stride != 2) { err = std::string(where) + "stride must be 1 or 2"; return LP_ESHAPE; }
+      if (l.in_hw % l.stride) { err = std::string(where) + "in_hw not divisible by stride"; return LP_ESHAPE; }
+      if (l.has_stem && l.stride != 1) { err = std::string(where) + "a stem stage has stride 1"; return LP_ESHAPE; }
+      if (prev_out >= 0 && l.in_ch != prev_out) { err = std::string(where) + "in_ch != previous out_ch"; return LP_ESHAPE; }
+      if (i > 0 && l.in_hw != sp->layers[i - 1].in_hw / sp->layers[i - 1].stride) { err = std::string(where) + "in_hw does not match previous stage"; return LP_ESHAPE; }
+      prev_out = l.out_ch;
+    } else {
+      err = std::string(where) + "bad layer kind"; return LP_EINVAL;
+    }
+  }
+  if (kind0 != LP_LAYER_DECODER && sp->vocab > 0) { err = "vocab > 0 needs decoder layers"; return LP_EUNSUPPORTED; }
+  int prev_e = 0;
+  for (int j = 0; j < sp->n_heads; ++j) {
+    const lp_head_spec& h = sp->heads[j];
+    char where[32]; snprintf(where, sizeof where, "head %d: ", j + 1);
+    if (h.after_layer < 1 || h.after_layer > sp->n_layers) { err = std::string(where) + "after_layer out of range"; return LP_EINVAL; }
+    if (h.after_layer < prev_e) { err = std::string(where) + "heads must be ordered by after_layer"; return LP_EINVAL; }
+    prev_e = h.after_layer;
+    if (h.window < 1) { err = std::string(where) + "window must be >= 1"; return LP_EINVAL; }
+    if (h.n_classes < 2) { err = std::string(where) + "n_classes must be >= 2"; return LP_ESHAPE; }
+    const lp_layer_spec& l = sp->layers[h.after_layer - 1];
+    int want_kind = kind0 == LP_LAYER_RESMLP ? LP_HEAD_LINEAR_CE : kind0 == LP_LAYER_DECODER ? LP_HEAD_LN_LINEAR_CE : LP_HEAD_POOL_LINEAR_CE;
+    if (h.kind != want_kind) { err = std::string(where) + "head kind does not fit the layer kind"; return LP_EUNSUPPORTED; }
+    int feat = kind0 == LP_LAYER_RESNET_STAGE ? l.out_ch : l.width;
+    if (h.in_dim != feat) { err = std::string(where) + "in_dim != layer output width"; return LP_ESHAPE; }
+    if (kind0 == LP_LAYER_DECODER && h.n_classes != sp->vocab) { err = std::string(where) + "n_classes != vocab"; return LP_ESHAPE; }
+    if (kind0 == LP_LAYER_DECODER && h.bias) { err = std::string(where) + "vocabulary heads have no bias"; return LP_EUNSUPPORTED; }
+  }
+  return LP_OK;
+}
+
+// ------------------------------------------------------------------------------------- layout
+static int add_tensor(lp_ctx* c, const std::string& name, std::initializer_list<int64_t> shape, int owner, int init,
+                      float std) {
+  Tensor t;
+  t.name = name; t.ndim = (int)shape.size(); t.numel = 1;
+  int i = 0;
+  for (int64_t s : shape) { t.shape[i++] = s; t.numel *= (size_t)s; }
+  t.off = c->P; t.owner = owner; t.init = init; t.std = std;
+  c->P += (t.numel + 63) & ~(size_t)63;
+  c->index[name] = (int)c->tensors.size();
+  c->tensors.push_back(t);
+  return (int)c->tensors.size() - 1;
+}
+
+static void build_params(lp_ctx* c) {
+  const lp_model_spec& sp = c->spec;
+  int L = sp.n_layers;
+  c->layers.assign(L + 1, LayerState());
+  for (int li = 1; li <= L; ++li) {
+    LayerState& S = c->layers[li];
+    S.s = c->layer_specs[li - 1];
+    const lp_layer_spec& l = S.s;
+    S.p_begin = c->P;
+    std::string p = "L" + std::to_string(li) + ".";
+    auto kaiming = [](int64_t fan_in) { return (float)sqrt(2.0 / (double)fan_in); };
+    auto W = [&](const char* n, std::initializer_list<int64_t> sh, float std) { S.t[n] = add_tensor(c, p + n, sh, li, 0, std); };
+    auto Z = [&](const char* n, int64_t k) { S.t[n] = add_tensor(c, p + n, {k}, li, 2, 0.f); };
+    auto O = [&](const char* n, int64_t k) { S.t[n] = add_tensor(c, p + n, {k}, li, 1, 0.f); };
+    if (l.kind == LP_LAYER_RESMLP) {
+      if (l.in_dim != l.width) { W("win", {l.width, l.in_dim}, kaiming(l.in_dim)); Z("bin", l.width); }
+      W("w1", {l.hidden, l.width}, kaiming(l.width)); Z("b1", l.hidden);
+      W("w2", {l.width, l.hidden}, kaiming(l.hidden)); Z("b2", l.width);
+    } else if (l.kind == LP_LAYER_DECODER) {
+      int64_t d = l.width, F = l.hidden;
+      if (li == 1 && sp.vocab > 0) W("emb", {sp.vocab, d}, 0.02f);
+      O("ln1.g", d); Z("ln1.b", d);
+      W("wqkv", {3 * d, d}, 0.02f); Z("bqkv", 3 * d);
+      W("wo", {d, d}, 0.02f); Z("bo", d);
+      O("ln2.g", d); Z("ln2.b", d);
+      W("w1", {F, d}, 0.02f); Z("b1", F);
+      W("w2", {d, F}, 0.02f); Z("b2", d);
+    } else {
+      int64_t co = l.out_ch;
+      if (l.has_stem) { W("stem.w", {co, 3, 3, l.in_ch}, kaiming(9 * l.in_ch)); O("stem.bn.g", co); Z("stem.bn.b", co); }
+      for (int b = 0; b < l.n_basic_blocks; ++b) {
+        std::string q = "b" + std::to_string(b + 1) + ".";
+        int64_t cin = (l.has_stem || b > 0) ? co : l.in_ch;
+        W((q + "conv1.w").c_str(), {co, 3, 3, cin}, kaiming(9 * cin)); O((q + "bn1.g").c_str(), co); Z((q + "bn1.b").c_str(), co);
+        W((q + "conv2.w").c_str(), {co, 3, 3, co}, kaiming(9 * co)); O((q + "bn2.g").c_str(), co); Z((q + "bn2.b").c_str(), co);
+        if (b == 0 && !l.has_stem && (l.stride != 1 || cin != co)) {
+          W((q + "proj.w").c_str(), {co, 1, 1, cin}, kaiming(cin)); O((q + "proj.bn.g").c_str(), co); Z((q + "proj.bn.b").c_str(), co);
+        }
+      }
+    }
+    S.p_end = c->P;
+  }
+  c->heads.assign(sp.n_heads, HeadState());
+  for (int hi = 0; hi < sp.n_heads; ++hi) {
+    HeadState& Hd = c->heads[hi];
+    Hd.s = c->head_specs[hi];
+    Hd.e = Hd.s.after_layer;
+    Hd.s_lo = Hd.e - Hd.s.window < 0 ? 0 : Hd.e - Hd.s.window;
+    Hd.p_begin = c->P;
+    std::string p = "H" + std::to_string(hi + 1) + ".";
+    int owner = L + hi + 1;
+    bool vocab_head = Hd.s.kind == LP_HEAD_LN_LINEAR_CE;
+    if (vocab_head) {
+      Hd.t["ln.g"] = add_tensor(c, p + "ln.g", {Hd.s.in_dim}, owner, 1, 0.f);
+      Hd.t["ln.b"] = add_tensor(c, p + "ln.b", {Hd.s.in_dim}, owner, 2, 0.f);
+    }
+    float std = vocab_head ? 0.02f : (float)sqrt(2.0 / (double)Hd.s.in_dim);
+    Hd.t["w"] = add_tensor(c, p + "w", {Hd.s.n_classes, Hd.s.in_dim}, owner, 0, std);
+    if (Hd.s.bias) Hd.t["b"] = add_tensor(c, p + "b", {Hd.s.n_classes}, owner, 2, 0.f);
+    Hd.p_end = c->P;
+    for (int li = Hd.s_lo + 1; li <= Hd.e; ++li) c->layers[li].coverage++;
+  }
+}
+
+static ConvUnit make_unit(lp_ctx* c, const std::string& wname, const std::string& bnpre, int N, int H, int C, int O,
+                          int R, int stride, int pad, int relu) {
+  ConvUnit u;
+  u.a.N = N; u.a.H = H; u.a.W = H; u.a.C = C; u.a.O = O; u.a.R = R; u.a.S = R; u.a.stride = stride; u.a.pad = pad;
+  u.a.P = (H + 2 * pad - R) / stride + 1; u.a.Q = u.a.P;
+  u.w = c->index[wname]; u.g = c->index[bnpre + "g"]; u.b = c->index[bnpre + "b"];
+  u.relu = relu;
+  return u;
+}
+
+// Assigns every work / params / state region.  With null bases it only measures.
+static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
+  const lp_model_spec& sp = c->spec;
+  int dt = c->dt, B = sp.max_batch, L = sp.n_layers;
+  size_t es = dtype_size(dt);
+  Arena pa, sa, wa;
+  if (buf) { pa.base = (char*)buf->params_dev; sa.base = (char*)buf->state_dev; wa.base = (char*)buf->work_dev; }
+  c->master = (float*)pa.take(c->P * 4);
+  c->lowp = dt == BF16 ? pa.take(c->P * 2) : nullptr;
+  c->mom = sp.opt.kind >= LP_OPT_SGDM ? (float*)sa.take(c->P * 4) : nullptr;
+  c->var = sp.opt.kind == LP_OPT_ADAM ? (float*)sa.take(c->P * 4) : nullptr;
+  if (sa.used == 0) sa.take(256);
+  c->grads = (float*)wa.take(c->P * 4);
+
+  size_t partial = 4096, max_rows = (size_t)B, max_act = 0, max_head_logits = 0, max_feat = 0;
+  int kind0 = sp.layers[0].kind;
+  for (int li = 1; li <= L; ++li) {
+    LayerState& S = c->layers[li];
+    const lp_layer_spec& l = S.s;
+    if (l.kind != LP_LAYER_RESNET_STAGE) S.out = wa.take(layer_out_elems(l, B) * es);
+    if (l.kind == LP_LAYER_RESMLP) {
+      S.mlp_p = l.in_dim != l.width ? wa.take((size_t)B * l.width * es) : nullptr;
+      S.mlp_r = wa.take((size_t)B * l.hidden * es);
+      size_t w = l.hidden > l.width ? l.hidden : l.width;
+      if (w < (size_t)l.in_dim) w = l.in_dim;
+      if ((size_t)B * w > max_act) max_act = (size_t)B * w;
+      size_t pr = (size_t)((B + 127) / 128) * w;
+      if (pr > partial) partial = pr;
+    } else if (l.kind == LP_LAYER_DECODER) {
+      size_t T = (size_t)B * l.seq_len, d = l.width, F = l.hidden;
+      S.a = wa.take(T * d * es); S.qkv = wa.take(T * 3 * d * es); S.o = wa.take(T * d * es);
+      S.u = wa.take(T * d * es); S.c = wa.take(T * d * es);
+      S.fpre = wa.take(T * F * es); S.f = wa.take(T * F * es);
+      S.mean1 = (float*)wa.take(T * 4); S.rstd1 = (float*)wa.take(T * 4);
+      S.mean2 = (float*)wa.take(T * 4); S.rstd2 = (float*)wa.take(T * 4);
+      S.lse = (float*)wa.take(T * l.n_heads * 4);
+      if (T > max_rows) max_rows = T;
+      size_t widest = F > 3 * d ? F : 3 * d;
+      size_t pr = ((T + 31) / 32) * d * 2;
+      size_t pc = ((T + 127) / 128) * (widest > (size_t)sp.vocab ? widest : (size_t)sp.vocab);
+      if (pr > partial) partial = pr;
+      if (pc > partial) partial = pc;
+    } else {
+      int hw_in = l.in_hw, hw_out = l.in_hw / l.stride;
+      std::string p = "L" + std::to_string(li) + ".";
+      auto alloc_unit = [&](ConvUnit& u) {
+        size_t n = (size_t)B * u.a.P * u.a.Q * u.a.O;
+        u.z = wa.take(n * es); u.y = wa.take(n * es);
+        u.mean = (float*)wa.take((size_t)u.a.O * 4); u.rstd = (float*)wa.take((size_t)u.a.O * 4);
+        size_t nin = (size_t)B * u.a.H * u.a.W * u.a.C;
+        if (n > max_act) max_act = n;
+        if (nin > max_act) max_act = nin;
+        size_t rows = (size_t)B * u.a.P * u.a.Q;
+        size_t pr = (2 * ((rows + 255) / 256) + 2) * u.a.O;
+        if (pr > partial) partial = pr;
+      };
+      S.has_stem = l.has_stem != 0;
+      S.blocks.clear();
+      if (S.has_stem) {
+        S.stem = make_unit(c, p + "stem.w", p + "stem.bn.", B, hw_in, l.in_ch, l.out_ch, 3, 1, 1, 1);
+        alloc_unit(S.stem);
+      }
+      for (int b = 0; b < l.n_basic_blocks; ++b) {
+        std::string q = p + "b" + std::to_string(b + 1) + ".";
+        bool first = (b == 0 && !S.has_stem);
+        int cin = first ? l.in_ch : l.out_ch;
+        int stride = first ? l.stride : 1;
+        int hin = first ? hw_in : hw_out;
+        BasicBlock bb;
+        bb.c1 = make_unit(c, q + "conv1.w", q + "bn1.", B, hin, cin, l.out_ch, 3, stride, 1, 1);
+        bb.c2 = make_unit(c, q + "conv2.w", q + "bn2.", B, hw_out, l.out_ch, l.out_ch, 3, 1, 1, 1);
+        bb.has_proj = c->index.count(q + "proj.w") > 0;
+        if (bb.has_proj) bb.proj = make_unit(c, q + "proj.w", q + "proj.bn.", B, hin, cin, l.out_ch, 1, stride, 0, 0);
+        alloc_unit(bb.c1); alloc_unit(bb.c2);
+        if (bb.has_proj) alloc_unit(bb.proj);
+        S.blocks.push_back(bb);
+      }
+      // the stage output is the last block's y; keep `out` as an alias instead of a copy
+      S.out = S.blocks.back().c2.y;
+    }
+  }
+  for (auto& Hd : c->heads) {
+    const lp_layer_spec& l = c->layers[Hd.e].s;
+    size_t rows = kind0 == LP_LAYER_DECODER ? (size_t)B * l.seq_len : (size_t)B;
+    if (rows * Hd.s.n_classes > max_head_logits) max_head_logits = rows * Hd.s.n_classes;
+    if (rows * Hd.s.in_dim > max_feat) max_feat = rows * Hd.s.in_dim;
+    if (rows > max_rows) max_rows = rows;
+    size_t pc = ((rows + 127) / 128) * (size_t)(Hd.s.n_classes > Hd.s.in_dim ? Hd.s.n_classes : Hd.s.in_dim);
+    if (pc > partial) partial = pc;
+  }
+  c->partial_elems = partial;
+  c->partial = (float*)wa.take(partial * 4);
+  c->loss_rows = (float*)wa.take(max_rows * 4);
+  c->feat = wa.take(max_feat * es);
+  c->dfeat = wa.take(max_feat * es);
+  c->logits = wa.take(max_head_logits * es);
+  c->hmean = (float*)wa.take(max_rows * 4);
+  c->hrstd = (float*)wa.take(max_rows * 4);
+  if (kind0 == LP_LAYER_DECODER) {
+    const lp_layer_spec& l = sp.layers[0];
+    size_t T = (size_t)B * l.seq_len, d = l.width, F = l.hidden;
+    c->pe = (float*)wa.take((size_t)l.seq_len * d * 4);
+    c->h0 = wa.take(T * d * es);
+    c->dA = wa.take(T * d * es); c->dB = wa.take(T * d * es);
+    c->dF = wa.take(T * F * es); c->dc = wa.take(T * d * es); c->du = wa.take(T * d * es);
+    c->dO = wa.take(T * d * es); c->dqkv = wa.take(T * 3 * d * es); c->da = wa.take(T * d * es);
+    c->delta = (float*)wa.take(T * l.n_heads * 4);
+  } else if (kind0 == LP_LAYER_RESMLP) {
+    c->dA = wa.take(max_act * es); c->dB = wa.take(max_act * es);
+    c->dF = wa.take(max_act * es); c->dc = wa.take(max_act * es);
+  } else {
+    c->dA = wa.take(max_act * es); c->dB = wa.take(max_act * es);
+    c->sG = wa.take(max_act * es); c->sZ = wa.take(max_act * es); c->sR = wa.take(max_act * es);
+    c->sD1 = wa.take(max_act * es); c->sD2 = wa.take(max_act * es);
+  }
+  if (sizes) {
+    sizes->param_bytes = (pa.used + 255) & ~(size_t)255;
+    sizes->state_bytes = (sa.used + 255) & ~(size_t)255;
+    sizes->work_bytes = (wa.used + 255) & ~(size_t)255;
+  }
+}
+
+static lp_ctx* make_host_ctx(const lp_model_spec* sp) {
+  lp_ctx* c = new lp_ctx();
+  c->spec = *sp;
+  c->layer_specs.assign(sp->layers, sp->layers + sp->n_layers);
+  c->head_specs.assign(sp->heads, sp->heads + sp->n_heads);
+  c->spec.layers = c->layer_specs.data();
+  c->spec.heads = c->head_specs.data();
+  c->dt = sp->dtype;
+  build_params(c);
+  return c;
+}
+
+extern "C" int lp_query_sizes(const lp_model_spec* spec, lp_sizes* out) {
+  std::string err;
+  int st = validate(spec, err);
+  if (st != LP_OK) return fail(nullptr, st, err);
+  if (!out) return fail(nullptr, LP_EINVAL, "out is null");
+  lp_ctx* c = make_host_ctx(spec);
+  plan(c, nullptr, out);
+  delete c;
+  return LP_OK;
+}
+
+#define CK(expr)                                                                                 \
+  do {                                                                                           \
+    hipError_t e_ = (expr);                                                                      \
+    if (e_ != hipSuccess) return fail(c, LP_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+static int refresh_lowp(lp_ctx* c, size_t off, size_t n) {
+  if (c->dt != BF16) return LP_OK;
+  CK(op_cast_to_compute(c->op(), c->master + off, (bf16_t*)c->lowp + off, n));
+  return LP_OK;
+}
+
+extern "C" int lp_init_blocks(const lp_model_spec* spec, const lp_buffers* buffers, void* hip_stream, lp_ctx** out) {
+  if (out) *out = nullptr;
+  std::string err;
+  int st = validate(spec, err);
+  if (st != LP_OK) return fail(nullptr, st, err);
+  if (!out) return fail(nullptr, LP_EINVAL, "out is null");
+  if (!buffers || !buffers->params_dev || !buffers->state_dev || !buffers->work_dev)
+    return fail(nullptr, LP_EINVAL, "buffers (params, state, work) must be non-null");
+  if (((uintptr_t)buffers->params_dev | (uintptr_t)buffers->state_dev | (uintptr_t)buffers->work_dev) & 255)
+    return fail(nullptr, LP_EALIGN, "device buffers must be 256-byte aligned");
+  lp_ctx* c = make_host_ctx(spec);
+  c->stream = (hipStream_t)hip_stream;
+  lp_sizes sz;
+  plan(c, buffers, &sz);
+  auto bail = [&](int code) { g_init_err = c->err; delete c; return code; };
+  // the caller vouches for the sizes; probe that the last byte of each buffer is device memory
+  {
+    struct { const void* p; size_t n; const char* what; } bufs[3] = {
+        {buffers->params_dev, sz.param_bytes, "params"}, {buffers->state_dev, sz.state_bytes, "state"},
+        {buffers->work_dev, sz.work_bytes, "work"}};
+    for (auto& b : bufs) {
+      void* base = nullptr; size_t len = 0;
+      hipError_t e = hipMemGetAddressRange((hipDeviceptr_t*)&base, &len, (hipDeviceptr_t)b.p);
+      if (e != hipSuccess) { c->err = std::string(b.what) + " buffer is not device memory: " + hipGetErrorString(e); (void)hipGetLastError(); return bail(LP_EDEVICE); }
+      size_t avail = len - ((const char*)b.p - (const char*)base);
+      if (avail < b.n) { c->err = std::string(b.what) + " buffer too small: have " + std::to_string(avail) + " bytes, need " + std::to_string(b.n); return bail(LP_ENOMEM); }
+    }
+  }
+  OpCtx o = c->op();
+  hipError_t e;
+#define CKI(expr) do { e = (expr); if (e != hipSuccess) { c->err = std::string(#expr) + ": " + hipGetErrorString(e); return bail(LP_EDEVICE); } } while (0)
+  CKI(op_fill_f32(o, c->master, c->P, 0.f));
+  if (c->mom) CKI(op_fill_f32(o, c->mom, c->P, 0.f));
+  if (c->var) CKI(op_fill_f32(o, c->var, c->P, 0.f));
+  CKI(op_fill_f32(o, c->grads, c->P, 0.f));
+  for (size_t i = 0; i < c->tensors.size(); ++i) {
+    const Tensor& t = c->tensors[i];
+    if (t.init == 0) CKI(op_init_normal(o, c->master + t.off, t.numel, t.std, spec->seed, (uint64_t)i));
+    else if (t.init == 1) CKI(op_fill_f32(o, c->master + t.off, t.numel, 1.f));
+  }
+  if (c->dt == BF16) CKI(op_cast_to_compute(o, c->master, c->lowp, c->P));
+  if (c->pe) CKI(op_posenc_init(o, c->pe, spec->layers[0].seq_len, spec->layers[0].width));
+  CKI(hipStreamSynchronize(c->stream));
+#undef CKI
+  c->ok = true;
+  *out = c;
+  return LP_OK;
+}
+
+extern "C" void lp_destroy(lp_ctx* c) { delete c; }
+
+extern "C" const char* lp_last_error(const lp_ctx* c) { return c ? c->err.c_str() : g_init_err.c_str(); }
+
+// ------------------------------------------------------------------------------------- step / eval
+static int check_call(lp_ctx* c, const void* x, const int32_t* y, int batch, float* losses) {
+  if (!c) return LP_EINVAL;
+  if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
+  if (!x || !y || !losses) return fail(c, LP_EINVAL, "x_dev, y_dev and losses_dev must be non-null");
+  if (batch < 0 || batch > c->spec.max_batch)
+    return fail(c, LP_ESHAPE, "batch " + std::to_string(batch) + " outside [0, max_batch=" + std::to_string(c->spec.max_batch) + "]");
+  return LP_OK;
+}
+
+static int optimizer_range(lp_ctx* c, size_t b, size_t e, float grad_scale) {
+  OptArgs a;
+  const lp_opt_spec& s = c->spec.opt;
+  a.kind = s.kind; a.lr = s.lr; a.momentum = s.momentum; a.beta1 = s.beta1; a.beta2 = s.beta2; a.eps = s.eps;
+  a.weight_decay = s.weight_decay; a.t = c->step_t; a.grad_scale = grad_scale;
+  CK(op_optimizer(c->op(), a, c->master + b, c->grads + b, c->mom ? c->mom + b : nullptr,
+                  c->var ? c->var + b : nullptr, c->lowp ? (void*)((bf16_t*)c->lowp + b) : nullptr, e - b));
+  return LP_OK;
+}
+
+static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* losses, bool train) {
+  int st = check_call(c, x, y, batch, losses);
+  if (st != LP_OK) return st;
+  int L = c->spec.n_layers, J = c->spec.n_heads;
+  if (batch == 0) {
+    CK(op_fill_f32(c->op(), losses, (size_t)J, 0.f));
+    return LP_OK;
+  }
+  c->x_in = x;
+  c->last_batch = batch;
+  if (train) {
+    c->step_t += 1;
+    for (int li = 1; li <= L; ++li) c->layers[li].seen = 0;
+  }
+  const int32_t* ids = c->spec.vocab > 0 ? (const int32_t*)x : nullptr;
+  int hj = 0;
+  for (int li = 1; li <= L; ++li) {
+    if ((st = drv_forward(c, li, batch, ids)) != LP_OK) return st;
+    // every head attached after this layer runs as soon as the activation exists
+    for (; hj < J && c->heads[hj].e == li; ++hj) {
+      HeadState& Hd = c->heads[hj];
+      if ((st = drv_head(c, hj, batch, y, losses + hj, train, c->dA)) != LP_OK) return st;
+      if (!train) continue;
+      void* dcur = c->dA; void* dnext = c->dB;
+      for (int lj = Hd.e; lj > Hd.s_lo; --lj) {
+        LayerState& S = c->layers[lj];
+        bool need_dx = lj > Hd.s_lo + 1;          // the window input is data: no gradient leaves the window
+        if ((st = drv_backward(c, lj, batch, dcur, dnext, need_dx, S.seen > 0 ? 1 : 0)) != LP_OK) return st;
+        S.seen += 1;
+        void* t = dcur; dcur = dnext; dnext = t;
+      }
+      if ((st = optimizer_range(c, Hd.p_begin, Hd.p_end, 1.f)) != LP_OK) return st;
+      // a layer is updated as soon as the last head covering it has contributed
+      for (int lj = Hd.e; lj > Hd.s_lo; --lj) {
+        LayerState& S = c->layers[lj];
+        if (S.seen == S.coverage) {
+          float gs = c->spec.combine == LP_COMBINE_MEAN ? 1.f / (float)S.coverage : 1.f;
+          if ((st = optimizer_range(c, S.p_begin, S.p_end, gs)) != LP_OK) return st;
+        }
+      }
+    }
+  }
+  return LP_OK;
+}
+
+extern "C" int lp_local_step(lp_ctx* c, const void* x, const int32_t* y, int batch, float* losses) {
+  return run(c, x, y, batch, losses, true);
+}
+extern "C" int lp_eval_loss(lp_ctx* c, const void* x, const int32_t* y, int batch, float* losses) {
+  return run(c, x, y, batch, losses, false);
+}
+
+// ------------------------------------------------------------------------------------- tensors
+struct Resolved { void* ptr; int dtype; int ndim; int64_t shape[4]; size_t bytes; bool is_param; size_t off; size_t numel; };
+
+static int resolve(lp_ctx* c, const char* name, Resolved* r) {
+  if (!c) return LP_EINVAL;
+  if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
+  if (!name) return fail(c, LP_EINVAL, "name is null");
+  std::string n(name);
+  memset(r, 0, sizeof *r);
+  auto suffix = [&](const char* s) { size_t k = strlen(s); return n.size() > k && n.compare(n.size() - k, k, s) == 0; };
+  if (suffix(".out") && n[0] == 'L') {
+    int li = atoi(n.c_str() + 1);
+    if (li < 0 || li > c->spec.n_layers || n != "L" + std::to_string(li) + ".out") return fail(c, LP_ENOTFOUND, "no tensor " + n);
+    int B = c->last_batch;
+    if (li == 0) {
+      if (!c->h0) return fail(c, LP_ENOTFOUND, "L0.out exists only for models with an embedding");
+      const lp_layer_spec& l = c->layers[1].s;
+      r->ptr = c->h0; r->ndim = 2; r->shape[0] = (int64_t)B * l.seq_len; r->shape[1] = l.width;
+    } else {
+      const lp_layer_spec& l = c->layers[li].s;
+      r->ptr = c->layers[li].out;
+      if (l.kind == LP_LAYER_RESMLP) { r->ndim = 2; r->shape[0] = B; r->shape[1] = l.width; }
+      else if (l.kind == LP_LAYER_DECODER) { r->ndim = 2; r->shape[0] = (int64_t)B * l.seq_len; r->shape[1] = l.width; }
+      else { int hw = l.in_hw / l.stride; r->ndim = 4; r->shape[0] = B; r->shape[1] = hw; r->shape[2] = hw; r->shape[3] = l.out_ch; }
+    }
+    r->dtype = c->dt;
+    r->numel = 1;
+    for (int i = 0; i < r->ndim; ++i) r->numel *= (size_t)r->shape[i];
+    r->bytes = r->numel * dtype_size(c->dt);
+    return LP_OK;
+  }
+  float* base = c->master;
+  std::string pn = n;
+  bool is_param = true;
+  if (suffix(".grad")) { base = c->grads; pn = n.substr(0, n.size() - 5); is_param = false; }
+  else if (suffix(".m") && c->index.count(n.substr(0, n.size() - 2))) { base = c->mom; pn = n.substr(0, n.size() - 2); is_param = false; }
+  else if (suffix(".v") && c->index.count(n.substr(0, n.size() - 2))) { base = c->var; pn = n.substr(0, n.size() - 2); is_param = false; }
+  auto it = c->index.find(pn);
+  if (it == c->index.end()) return fail(c, LP_ENOTFOUND, "no tensor " + n);
+  if (!base) return fail(c, LP_ENOTFOUND, "this optimizer keeps no " + n);
+  const Tensor& t = c->tensors[it->second];
+  r->ptr = base + t.off; r->dtype = F32; r->ndim = t.ndim;
+  for (int i = 0; i < 4; ++i) r->shape[i] = t.shape[i];
+  r->numel = t.numel; r->bytes = t.numel * 4; r->is_param = is_param; r->off = t.off;
+  return LP_OK;
+}
+
+extern "C" int lp_tensor_info(lp_ctx* c, const char* name, int64_t shape[4], int* ndim, int* dtype, size_t* bytes) {
+  Resolved r;
+  int st = resolve(c, name, &r);
+  if (st != LP_OK) return st;
+  if (shape) for (int i = 0; i < 4; ++i) shape[i] = r.shape[i];
+  if (ndim) *ndim = r.ndim;
+  if (dtype) *dtype = r.dtype;
+  if (bytes) *bytes = r.bytes;
+  return LP_OK;
+}
+
+extern "C" int lp_get_tensor(lp_ctx* c, const char* name, void* dst, size_t bytes) {
+  Resolved r;
+  int st = resolve(c, name, &r);
+  if (st != LP_OK) return st;
+  if (!dst) return fail(c, LP_EINVAL, "dst_host is null");
+  if (bytes != r.bytes) return fail(c, LP_ESHAPE, std::string(name) + ": have " + std::to_string(r.bytes) + " bytes, caller gave " + std::to_string(bytes));
+  CK(hipStreamSynchronize(c->stream));
+  if (bytes) CK(hipMemcpy(dst, r.ptr, bytes, hipMemcpyDeviceToHost));
+  return LP_OK;
+}
+
+extern "C" int lp_set_tensor(lp_ctx* c, const char* name, const void* src, size_t bytes) {
+  Resolved r;
+  int st = resolve(c, name, &r);
+  if (st != LP_OK) return st;
+  if (!src) return fail(c, LP_EINVAL, "src_host is null");
+  if (bytes != r.bytes) return fail(c, LP_ESHAPE, std::string(name) + ": have " + std::to_string(r.bytes) + " bytes, caller gave " + std::to_string(bytes));
+  CK(hipStreamSynchronize(c->stream));
+  if (bytes) CK(hipMemcpy(r.ptr, src, bytes, hipMemcpyHostToDevice));
+  if (r.is_param) {
+    if ((st = refresh_lowp(c, r.off, r.numel)) != LP_OK) return st;
+    CK(hipStreamSynchronize(c->stream));
+  }
+  return LP_OK;
+}
+
+extern "C" int lp_num_params(lp_ctx* c) { return c ? (int)c->tensors.size() : 0; }
+extern "C" const char* lp_param_name(lp_ctx* c, int i) {
+  if (!c || i < 0 || i >= (int)c->tensors.size()) return nullptr;
+  return c->tensors[i].name.c_str();
+}
+extern "C" int lp_get_step(lp_ctx* c) { return c ? c->step_t : -1; }
+extern "C" int lp_set_step(lp_ctx* c, int t) {
+  if (!c) return LP_EINVAL;
+  if (t < 0) return fail(c, LP_EINVAL, "step must be >= 0");
+  c->step_t = t;
+  return LP_OK;
+}

@@ -1,0 +1,127 @@
+"""GPU parity: lp_local_step / lp_eval_loss through the C ABI against the CPU oracle, element by
+element (per-tensor relative L2 error) on scaled-down forms of the five configurations: sizes the
+oracle finishes in seconds, ragged with respect to every kernel tile."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import lp_inputs as LI
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lpmod():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2012_03837_amd as lp
+    return lp
+
+
+from gpu_util import compare_step, data_for, generic_params, relerr, tol_for  # noqa: E402
+
+
+SMALL = ["cfg1_small", "cfg2_small", "cfg3_small", "cfg4_small", "cfg5_small"]
+
+
+@pytest.mark.parametrize("name", SMALL)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_local_step_matches_oracle(lpmod, name, dtype):
+    cfg = dataclasses.replace(LI.make_config(name), dtype=dtype)
+    print(f"[case] {name} {dtype}", flush=True)
+    tr = lpmod.LocalTrainer(cfg)
+    x, y = data_for(cfg)
+    worst = compare_step(tr, cfg, generic_params(cfg), x, y, n_steps=1, label=f"{name}/{dtype}")
+    print("worst rel err", worst, flush=True)
+    tr.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1_small", "cfg3_small", "cfg2_small"])
+def test_three_steps_fp32(lpmod, name):
+    """Optimizer state carried across steps (Adam bias correction with t > 1, momentum)."""
+    cfg = dataclasses.replace(LI.make_config(name), dtype="f32")
+    tr = lpmod.LocalTrainer(cfg)
+    x, y = data_for(cfg)
+    compare_step(tr, cfg, generic_params(cfg), x, y, n_steps=3, label=name)
+    tr.close()
+
+
+@pytest.mark.parametrize("scheme,combine", [("backprop", "sum"), ("last2", "sum"), ("overlap", "mean"),
+                                            ("deep_supervision", "sum")])
+def test_schemes_fp32(lpmod, scheme, combine):
+    """Backprop as one block, the last-K baseline (earlier layers untouched, bit for bit), averaged
+    overlapping windows, and full windows from every head."""
+    cfg = LI.make_config("cfg3_small", scheme=scheme, combine=combine, n_layers=4, dtype="f32")
+    tr = lpmod.LocalTrainer(cfg)
+    x, y = data_for(cfg)
+    compare_step(tr, cfg, generic_params(cfg), x, y, label=f"{scheme}/{combine}")
+    tr.close()
+
+
+def test_cfg1_full_size_fp32(lpmod):
+    """The full residual-MLP configuration (the oracle finishes it in well under a second)."""
+    cfg = LI.make_config("cfg1")
+    tr = lpmod.LocalTrainer(cfg)
+    x, y = data_for(cfg)
+    compare_step(tr, cfg, LI.init_params(cfg), x, y, label="cfg1")
+    tr.close()
+
+
+def test_smaller_batch_and_empty_batch(lpmod):
+    cfg = dataclasses.replace(LI.make_config("cfg3_small"), dtype="f32")
+    tr = lpmod.LocalTrainer(cfg)                     # max_batch 3
+    x, y = data_for(cfg, batch=2)
+    compare_step(tr, cfg, generic_params(cfg), x, y, label="batch2")
+    before = tr.get_params()
+    t0 = lpmod.lp_get_step(tr.ctx)
+    xd, yd = tr.stage(x, y)
+    lpmod.lp_local_step(tr.ctx, xd.data_ptr(), yd.data_ptr(), 0, tr.losses.data_ptr())
+    assert lpmod.lp_get_step(tr.ctx) == t0
+    assert not np.any(tr.losses.cpu().numpy())
+    after = tr.get_params()
+    for k in before:
+        np.testing.assert_array_equal(before[k], after[k])
+    with pytest.raises(lpmod.LpError) as e:
+        lpmod.lp_local_step(tr.ctx, xd.data_ptr(), yd.data_ptr(), 4, tr.losses.data_ptr())
+    assert e.value.status == 2
+    with pytest.raises(lpmod.LpError) as e:
+        lpmod.lp_local_step(tr.ctx, 0, yd.data_ptr(), 2, tr.losses.data_ptr())
+    assert e.value.status == 1
+    with pytest.raises(lpmod.LpError) as e:
+        tr.get("L9.nope")
+    assert e.value.status == 8
+    tr.close()
+
+
+def test_builtin_init_statistics(lpmod):
+    cfg = LI.make_config("cfg3_small")
+    tr = lpmod.LocalTrainer(cfg)
+    w = tr.get("L2.w1")
+    assert abs(w.std() - 0.02) < 0.002 and abs(w.mean()) < 0.002
+    assert np.all(tr.get("L1.ln1.g") == 1) and not np.any(tr.get("L1.b1"))
+    tr.close()
+    cfg = LI.make_config("cfg1")
+    tr = lpmod.LocalTrainer(cfg)
+    w = tr.get("L2.w1")
+    assert abs(w.std() - np.sqrt(2 / 256)) < 0.01
+    w2 = tr.get("L3.w1")
+    assert abs(np.corrcoef(w.ravel(), w2.ravel())[0, 1]) < 0.02
+    tr.close()
+
+
+def test_repeatable_bitwise(lpmod):
+    """Fixed reduction orders: two runs from the same state give identical bits."""
+    cfg = LI.make_config("cfg4_small")
+    x, y = data_for(cfg)
+    outs = []
+    for _ in range(2):
+        tr = lpmod.LocalTrainer(cfg)
+        tr.set_params(generic_params(cfg))
+        xd, yd = tr.stage(x, y)
+        l = tr.step(xd, yd).cpu().numpy().copy()
+        outs.append((l, tr.get("L1.emb"), tr.get("L2.wqkv"), tr.get("H3.w")))
+        tr.close()
+    for a, b in zip(*outs):
+        np.testing.assert_array_equal(a, b)
