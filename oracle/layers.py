@@ -15,15 +15,15 @@ from . import ops
 
 
 # ============================================================================= residual MLP
-def resmlp_fwd(P, pre, l, x):
+def resmlp_fwd(P, pre, l, x, q=ops.identity):
     cache = {"x": x}
     if l.in_dim != l.width:
-        p = ops.linear_fwd(x, P[pre + "win"], P[pre + "bin"])
+        p = q(ops.linear_fwd(x, P[pre + "win"], P[pre + "bin"]))
     else:
         p = x
     a = ops.linear_fwd(p, P[pre + "w1"], P[pre + "b1"])
-    r = ops.relu_fwd(a)
-    out = p + ops.linear_fwd(r, P[pre + "w2"], P[pre + "b2"])
+    r = q(ops.relu_fwd(a))
+    out = q(p + ops.linear_fwd(r, P[pre + "w2"], P[pre + "b2"]))
     cache.update(p=p, a=a, r=r)
     return out, cache
 
@@ -31,7 +31,7 @@ def resmlp_fwd(P, pre, l, x):
 def resmlp_bwd(P, pre, l, cache, dout, need_dx=True):
     g = {}
     dr, g[pre + "w2"], g[pre + "b2"] = ops.linear_bwd(cache["r"], P[pre + "w2"], dout)
-    da = ops.relu_bwd(cache["a"], dr)
+    da = ops.relu_bwd(cache["r"], dr)          # r > 0 exactly where a > 0
     dp, g[pre + "w1"], g[pre + "b1"] = ops.linear_bwd(cache["p"], P[pre + "w1"], da)
     dp = dp + dout
     if l.in_dim != l.width:
@@ -52,7 +52,7 @@ def _merge_heads(t):
     return t.transpose(0, 2, 1, 3).reshape(B * S, H * dh)
 
 
-def decoder_fwd(P, pre, l, x, first, vocab):
+def decoder_fwd(P, pre, l, x, first, vocab, q=ops.identity):
     """x: token ids [B, S] if this is layer 1 of a model with an embedding, else h [B*S, d]."""
     S, d, H = l.seq_len, l.width, l.n_heads
     cache = {}
@@ -61,24 +61,27 @@ def decoder_fwd(P, pre, l, x, first, vocab):
         B = ids.shape[0]
         emb = P[pre + "emb"]
         pe = ops.sinusoid_positions(S, d, emb.dtype)
-        h = ops.embed_fwd(ids, emb, pe).reshape(B * S, d)
+        h = q(ops.embed_fwd(ids, emb, pe).reshape(B * S, d))
         cache["ids"] = ids
     else:
         h = x
         B = h.shape[0] // S
     a, c_ln1 = ops.layernorm_fwd(h, P[pre + "ln1.g"], P[pre + "ln1.b"])
-    qkv = ops.linear_fwd(a, P[pre + "wqkv"], P[pre + "bqkv"])
-    q = _split_heads(qkv[:, :d], B, S, H)
+    a = q(a)
+    qkv = q(ops.linear_fwd(a, P[pre + "wqkv"], P[pre + "bqkv"]))
+    qh = _split_heads(qkv[:, :d], B, S, H)
     k = _split_heads(qkv[:, d:2 * d], B, S, H)
     v = _split_heads(qkv[:, 2 * d:], B, S, H)
-    o4, p = ops.attention_fwd(q, k, v, causal=bool(l.causal))
-    o = _merge_heads(o4)
-    u = h + ops.linear_fwd(o, P[pre + "wo"], P[pre + "bo"])
+    o4, p = ops.attention_fwd(qh, k, v, causal=bool(l.causal))
+    o = q(_merge_heads(o4))
+    u = q(h + ops.linear_fwd(o, P[pre + "wo"], P[pre + "bo"]))
     c, c_ln2 = ops.layernorm_fwd(u, P[pre + "ln2.g"], P[pre + "ln2.b"])
-    f_pre = ops.linear_fwd(c, P[pre + "w1"], P[pre + "b1"])
-    f = ops.gelu_fwd(f_pre) if l.act == "gelu" else ops.relu_fwd(f_pre)
-    out = u + ops.linear_fwd(f, P[pre + "w2"], P[pre + "b2"])
-    cache.update(B=B, a=a, c_ln1=c_ln1, q=q, k=k, v=v, p=p, o=o, c=c, c_ln2=c_ln2, f_pre=f_pre, f=f)
+    c = q(c)
+    f_exact = ops.linear_fwd(c, P[pre + "w1"], P[pre + "b1"])
+    f = q(ops.gelu_fwd(f_exact) if l.act == "gelu" else ops.relu_fwd(f_exact))
+    f_pre = q(f_exact)
+    out = q(u + ops.linear_fwd(f, P[pre + "w2"], P[pre + "b2"]))
+    cache.update(B=B, a=a, c_ln1=c_ln1, q=qh, k=k, v=v, p=p, o=o, c=c, c_ln2=c_ln2, f_pre=f_pre, f=f)
     return out, cache
 
 
@@ -105,38 +108,40 @@ def decoder_bwd(P, pre, l, cache, dout, need_dx, first, vocab):
 
 
 # ============================================================================= ResNet stage
-def _conv_bn(P, wname, bnpre, x, stride, pad, relu):
-    z = ops.conv2d_fwd(x, P[wname], stride, pad)
+def _conv_bn(P, wname, bnpre, x, stride, pad, relu, res=None, q=ops.identity):
+    """out = [relu]( BN(conv(x)) [+ res] ); the conv output and the result are stored activations."""
+    z = q(ops.conv2d_fwd(x, P[wname], stride, pad))
     y, bn = ops.batchnorm_fwd(z, P[bnpre + "g"], P[bnpre + "b"])
-    out = ops.relu_fwd(y) if relu else y
-    return out, {"x": x, "bn": bn, "y": y, "stride": stride, "pad": pad, "relu": relu}
+    if res is not None:
+        y = y + res
+    out = q(ops.relu_fwd(y) if relu else y)
+    return out, {"x": x, "bn": bn, "out": out, "stride": stride, "pad": pad, "relu": relu}
 
 
 def _conv_bn_bwd(P, wname, bnpre, c, dout, g, need_dx=True):
-    dy = ops.relu_bwd(c["y"], dout) if c["relu"] else dout
+    """Returns (dx, dy) where dy is dout masked by the unit's ReLU (= gradient of the residual input)."""
+    dy = ops.relu_bwd(c["out"], dout) if c["relu"] else dout     # out > 0 exactly where the pre-ReLU value is
     dz, g[bnpre + "g"], g[bnpre + "b"] = ops.batchnorm_bwd(c["bn"], P[bnpre + "g"], dy)
     dx, g[wname] = ops.conv2d_bwd(c["x"], P[wname], c["stride"], c["pad"], dz, need_dx)
-    return dx
+    return dx, dy
 
 
-def resnet_stage_fwd(P, pre, l, x):
+def resnet_stage_fwd(P, pre, l, x, q=ops.identity):
     """stem (optional) then n BasicBlocks: relu(bn2(conv2(relu(bn1(conv1 x)))) + shortcut(x))."""
     cache = {"blocks": []}
     h = x
     if l.has_stem:
-        h, cache["stem"] = _conv_bn(P, pre + "stem.w", pre + "stem.bn.", h, 1, 1, True)
+        h, cache["stem"] = _conv_bn(P, pre + "stem.w", pre + "stem.bn.", h, 1, 1, True, q=q)
     for b in range(l.n_basic_blocks):
-        q = pre + f"b{b + 1}."
+        n = pre + f"b{b + 1}."
         stride = l.stride if (b == 0 and not l.has_stem) else 1
         bc = {"in": h}
-        t, bc["c1"] = _conv_bn(P, q + "conv1.w", q + "bn1.", h, stride, 1, True)
-        t, bc["c2"] = _conv_bn(P, q + "conv2.w", q + "bn2.", t, 1, 1, False)
-        if (q + "proj.w") in P:
-            sc, bc["proj"] = _conv_bn(P, q + "proj.w", q + "proj.bn.", h, stride, 0, False)
+        t, bc["c1"] = _conv_bn(P, n + "conv1.w", n + "bn1.", h, stride, 1, True, q=q)
+        if (n + "proj.w") in P:
+            sc, bc["proj"] = _conv_bn(P, n + "proj.w", n + "proj.bn.", h, stride, 0, False, q=q)
         else:
             sc = h
-        bc["sum"] = t + sc
-        h = ops.relu_fwd(bc["sum"])
+        h, bc["c2"] = _conv_bn(P, n + "conv2.w", n + "bn2.", t, 1, 1, True, res=sc, q=q)
         cache["blocks"].append(bc)
     return h, cache
 
@@ -148,30 +153,29 @@ def resnet_stage_bwd(P, pre, l, cache, dout, need_dx=True):
         q = pre + f"b{b + 1}."
         bc = cache["blocks"][b]
         first_op = (b == 0 and not l.has_stem)
-        ds = ops.relu_bwd(bc["sum"], dh)
-        dt = _conv_bn_bwd(P, q + "conv2.w", q + "bn2.", bc["c2"], ds, g)
+        dt, ds = _conv_bn_bwd(P, q + "conv2.w", q + "bn2.", bc["c2"], dh, g)
         want_dx = need_dx or not first_op
-        dx_main = _conv_bn_bwd(P, q + "conv1.w", q + "bn1.", bc["c1"], dt, g, want_dx)
+        dx_main, _ = _conv_bn_bwd(P, q + "conv1.w", q + "bn1.", bc["c1"], dt, g, want_dx)
         if "proj" in bc:
-            dx_sc = _conv_bn_bwd(P, q + "proj.w", q + "proj.bn.", bc["proj"], ds, g, want_dx)
+            dx_sc, _ = _conv_bn_bwd(P, q + "proj.w", q + "proj.bn.", bc["proj"], ds, g, want_dx)
         else:
             dx_sc = ds
         dh = (dx_main + dx_sc) if want_dx else None
     if l.has_stem:
-        dh = _conv_bn_bwd(P, pre + "stem.w", pre + "stem.bn.", cache["stem"], dh, g, need_dx)
+        dh, _ = _conv_bn_bwd(P, pre + "stem.w", pre + "stem.bn.", cache["stem"], dh, g, need_dx)
     return (dh if need_dx else None), g
 
 
 # ============================================================================= dispatch
-def layer_fwd(cfg, P, li, x):
+def layer_fwd(cfg, P, li, x, q=ops.identity):
     l = cfg.layers[li - 1]
     pre = f"L{li}."
     if l.kind == "resmlp":
-        return resmlp_fwd(P, pre, l, x)
+        return resmlp_fwd(P, pre, l, x, q)
     if l.kind == "decoder":
-        return decoder_fwd(P, pre, l, x, li == 1, cfg.vocab)
+        return decoder_fwd(P, pre, l, x, li == 1, cfg.vocab, q)
     if l.kind == "resnet_stage":
-        return resnet_stage_fwd(P, pre, l, x)
+        return resnet_stage_fwd(P, pre, l, x, q)
     raise ValueError(l.kind)
 
 
@@ -188,21 +192,22 @@ def layer_bwd(cfg, P, li, cache, dout, need_dx):
 
 
 # ============================================================================= heads
-def head_loss(cfg, P, hi, h, y):
+def head_loss(cfg, P, hi, h, y, q=ops.identity):
     """Auxiliary objective of head hi on activation h with labels y.  Returns (loss, cache)."""
     hd = cfg.heads[hi - 1]
     pre = f"H{hi}."
     cache = {}
     if hd.kind == "pool_linear_ce":
-        feat = h.mean(axis=(1, 2))
+        feat = q(h.mean(axis=(1, 2)))
         cache["hw_shape"] = h.shape
     elif hd.kind == "ln_linear_ce":
         feat, cache["ln"] = ops.layernorm_fwd(h, P[pre + "ln.g"], P[pre + "ln.b"])
+        feat = q(feat)
     elif hd.kind == "linear_ce":
         feat = h
     else:
         raise ValueError(hd.kind)
-    z = ops.linear_fwd(feat, P[pre + "w"], P[pre + "b"] if hd.bias else None)
+    z = q(ops.linear_fwd(feat, P[pre + "w"], P[pre + "b"] if hd.bias else None))
     yy = y.reshape(-1)
     loss, p = ops.softmax_ce_fwd(z, yy)
     cache.update(feat=feat, p=p, y=yy)

@@ -21,43 +21,57 @@ from __future__ import annotations
 import numpy as np
 
 from . import layers as L
+from . import ops
 
 
-def _cast(P, dtype):
-    return {k: np.asarray(v, dtype=dtype) for k, v in P.items()}
+def _policy(stored):
+    """Storage precision of forward activations and matrix weight operands: None = exact (float64),
+    "bf16" = rounded to bfloat16 wherever a "bf16 compute" configuration keeps them in memory."""
+    if stored is None:
+        return ops.identity
+    if stored == "bf16":
+        return ops.bf16_round
+    raise ValueError(stored)
+
+
+def _cast(P, dtype, q=ops.identity):
+    """Weights as the forward/backward passes see them: vectors exact, matrices in storage precision."""
+    return {k: (q(np.asarray(v, dtype=dtype)) if np.ndim(v) >= 2 else np.asarray(v, dtype=dtype))
+            for k, v in P.items()}
 
 
 def _windows(cfg):
     return [(max(h.after_layer - h.window, 0), h.after_layer) for h in cfg.heads]
 
 
-def forward_all(cfg, P, x):
+def forward_all(cfg, P, x, q=ops.identity):
     """Step 1.  Returns activations hs[0..L] (hs[0] = x) and per-layer caches[1..L]."""
     hs = [x]
     caches = [None]
     for li in range(1, cfg.n_layers + 1):
-        out, c = L.layer_fwd(cfg, P, li, hs[-1])
+        out, c = L.layer_fwd(cfg, P, li, hs[-1], q)
         hs.append(out)
         caches.append(c)
     return hs, caches
 
 
-def eval_loss(cfg, params, x, y, dtype=np.float64):
+def eval_loss(cfg, params, x, y, dtype=np.float64, stored=None):
     """Steps 1-2, values only: the loss of every head at the current weights."""
-    P = _cast(params, dtype)
+    q = _policy(stored)
+    P = _cast(params, dtype, q)
     xx = x if np.issubdtype(np.asarray(x).dtype, np.integer) else np.asarray(x, dtype=dtype)
-    hs, _ = forward_all(cfg, P, xx)
-    return np.array([L.head_loss(cfg, P, hi, hs[h.after_layer], y)[0]
+    hs, _ = forward_all(cfg, P, xx, q)
+    return np.array([L.head_loss(cfg, P, hi, hs[h.after_layer], y, q)[0]
                      for hi, h in enumerate(cfg.heads, start=1)], dtype=np.float64)
 
 
-def head_gradients(cfg, P, hi, hs, caches, y):
+def head_gradients(cfg, P, hi, hs, caches, y, q=ops.identity):
     """Steps 2-3 for one head: loss_j and the gradient of loss_j w.r.t. everything in its window.
 
     hs[s_j] is treated as data: the backward pass stops there (need_dx False at layer s_j + 1).
     """
     s, e = _windows(cfg)[hi - 1]
-    loss, hc = L.head_loss(cfg, P, hi, hs[e], y)
+    loss, hc = L.head_loss(cfg, P, hi, hs[e], y, q)
     dh, grads = L.head_bwd(cfg, P, hi, hc)
     for li in range(e, s, -1):
         dh, g = L.layer_bwd(cfg, P, li, caches[li], dh, need_dx=(li > s + 1))
@@ -65,18 +79,19 @@ def head_gradients(cfg, P, hi, hs, caches, y):
     return loss, grads
 
 
-def local_gradients(cfg, params, x, y, dtype=np.float64, per_head=False):
+def local_gradients(cfg, params, x, y, dtype=np.float64, per_head=False, stored=None):
     """Steps 1-3.  Returns (losses[n_heads], grads by parameter name, coverage count by name).
 
     Parameters covered by no window are absent from ``grads``.
     """
-    P = _cast(params, dtype)
+    q = _policy(stored)
+    P = _cast(params, dtype, q)
     xx = x if np.issubdtype(np.asarray(x).dtype, np.integer) else np.asarray(x, dtype=dtype)
-    hs, caches = forward_all(cfg, P, xx)
+    hs, caches = forward_all(cfg, P, xx, q)
     losses = []
     total, count, each = {}, {}, []
     for hi in range(1, len(cfg.heads) + 1):
-        loss, g = head_gradients(cfg, P, hi, hs, caches, y)
+        loss, g = head_gradients(cfg, P, hi, hs, caches, y, q)
         losses.append(loss)
         each.append(g)
         for k, v in g.items():
@@ -95,17 +110,18 @@ def local_gradients(cfg, params, x, y, dtype=np.float64, per_head=False):
     return np.array(losses), total, count
 
 
-def block_gradients(cfg, params, hi, h_s, y, dtype=np.float64):
+def block_gradients(cfg, params, hi, h_s, y, dtype=np.float64, stored=None):
     """Head hi alone, fed its window input h_s as data (that input is detached by definition, so
     the block's loss and gradients depend on the rest of the network only through h_s)."""
-    P = _cast(params, dtype)
+    q = _policy(stored)
+    P = _cast(params, dtype, q)
     s, e = _windows(cfg)[hi - 1]
     x = h_s if np.issubdtype(np.asarray(h_s).dtype, np.integer) else np.asarray(h_s, dtype=dtype)
     hs = {s: x}
     caches = {}
     for li in range(s + 1, e + 1):
-        hs[li], caches[li] = L.layer_fwd(cfg, P, li, hs[li - 1])
-    loss, hc = L.head_loss(cfg, P, hi, hs[e], y)
+        hs[li], caches[li] = L.layer_fwd(cfg, P, li, hs[li - 1], q)
+    loss, hc = L.head_loss(cfg, P, hi, hs[e], y, q)
     dh, grads = L.head_bwd(cfg, P, hi, hc)
     for li in range(e, s, -1):
         dh, g = L.layer_bwd(cfg, P, li, caches[li], dh, need_dx=(li > s + 1))
@@ -146,9 +162,10 @@ def optimizer_update(opt, p, g, state, name, t):
     raise ValueError(opt.kind)
 
 
-def local_step(cfg, params, state, x, y, dtype=np.float64):
-    """Steps 1-5.  Returns (losses, new params, grads).  ``state`` is updated in place."""
-    losses, grads, _ = local_gradients(cfg, params, x, y, dtype)
+def local_step(cfg, params, state, x, y, dtype=np.float64, stored=None):
+    """Steps 1-5.  Returns (losses, new params, grads).  ``state`` is updated in place.  The update
+    always acts on the exact (master) weights, whatever the storage precision of the passes."""
+    losses, grads, _ = local_gradients(cfg, params, x, y, dtype, stored=stored)
     state["t"] += 1
     t = state["t"]
     new = {}

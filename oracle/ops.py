@@ -18,6 +18,25 @@ LN_EPS = 1e-5
 BN_EPS = 1e-5
 
 
+# ----------------------------------------------------------------------------- storage precision
+def bf16_round(x):
+    """Round to the nearest bfloat16 (ties to even) and return in the input's float type.
+
+    Used only in the "stored-activation precision" mode of the oracle: a configuration that says
+    "bf16 compute" stores every forward activation and every matrix weight operand as bf16, and the
+    ReLU on/off decisions are then taken on those stored values.  Arithmetic stays in float64."""
+    a = np.asarray(x, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    out = r.astype(np.uint32).view(np.float32)
+    out = np.where(np.isfinite(a), out, a)
+    return out.astype(np.asarray(x).dtype if np.asarray(x).dtype.kind == "f" else np.float64)
+
+
+def identity(x):
+    return x
+
+
 # ----------------------------------------------------------------------------- linear
 def linear_fwd(x, w, b=None):
     """y[n, o] = sum_i x[n, i] w[o, i] (+ b[o]);  w is [out, in]."""

@@ -300,3 +300,26 @@ def test_resnet_stage_vs_torch_autograd():
     for k in P:
         tg = tP[k].grad
         close(grads[k], tg.permute(0, 2, 3, 1) if tg.ndim == 4 else tg, 1e-10)
+
+
+def test_bf16_round_vs_library():
+    """The oracle's own round-to-nearest-even bf16 rounding equals the library conversion, bit for bit."""
+    x = np.concatenate([RNG.standard_normal(5000) * 10.0 ** RNG.integers(-6, 6, 5000),
+                        np.array([0.0, -0.0, 1.0, 1.00390625, 1.001953125, 1.005859375, 3.3895314e38])])
+    got = ops.bf16_round(x)
+    ref = torch.tensor(x, dtype=torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert got.dtype == np.float64
+    np.testing.assert_array_equal(got, ref)
+
+
+def test_stored_precision_mode_keeps_structure():
+    """With bf16 storage the oracle still obeys the window rule and stays close to the exact one."""
+    import oracle
+    cfg = LI.make_config("cfg2_small")
+    P = LI.init_params(cfg)
+    x, y = LI.make_batch(cfg)
+    l0, g0, _ = oracle.local_gradients(cfg, P, x, y)
+    l1, g1, _ = oracle.local_gradients(cfg, P, x, y, stored="bf16")
+    assert set(g0) == set(g1)
+    assert np.abs(l0 - l1).max() < 2e-2
+    assert np.abs(l0 - l1).max() > 0
