@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the local-update step on one MI355X.
+
+A step is one lp_local_step over one synthetic minibatch: forward through every layer, every
+auxiliary head's loss and in-window backward pass, and every optimizer update.  Inputs are
+pre-staged in HBM; the timed region holds only the K step calls between two device
+synchronisations.  One JSON line goes to stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3       # MI355X fp32 vector
+PEAK_HBM_GBS = 8000.0
+
+
+def gemm_flops_per_step(cfg):
+    """Algorithmic FLOPs of the dense contractions of one step (2*M*N*K each): forward once per
+    layer; per head, its own forward + dgrad + wgrad and dgrad + wgrad of every layer in its window
+    (appendix A.2 accounting: one forward per layer, one backward per (head, layer-in-window))."""
+    import lp_inputs as LI
+    B = cfg.batch
+    kind = cfg.layers[0].kind
+
+    def layer_fwd(l):
+        if kind == "decoder":
+            T = B * l.seq_len
+            return 2.0 * T * l.width * (3 * l.width + l.width + 2 * l.hidden)
+        if kind == "resmlp":
+            f = 2.0 * B * l.width * l.hidden * 2
+            if l.in_dim != l.width:
+                f += 2.0 * B * l.in_dim * l.width
+            return f
+        # resnet stage
+        f = 0.0
+        hw_out = l.in_hw // l.stride
+        if l.has_stem:
+            f += 2.0 * B * l.in_hw * l.in_hw * l.out_ch * 9 * l.in_ch
+        for b in range(l.n_basic_blocks):
+            first = (b == 0 and not l.has_stem)
+            cin = l.in_ch if first else l.out_ch
+            f += 2.0 * B * hw_out * hw_out * l.out_ch * 9 * cin
+            f += 2.0 * B * hw_out * hw_out * l.out_ch * 9 * l.out_ch
+            if first and (l.stride != 1 or cin != l.out_ch):
+                f += 2.0 * B * hw_out * hw_out * l.out_ch * cin
+        return f
+
+    def head_fwd(h):
+        l = cfg.layers[h.after_layer - 1]
+        rows = B * l.seq_len if kind == "decoder" else B
+        return 2.0 * rows * h.in_dim * h.n_classes
+
+    total = sum(layer_fwd(l) for l in cfg.layers)
+    for h, (s, e) in zip(cfg.heads, LI.head_windows(cfg)):
+        total += 3.0 * head_fwd(h)
+        for li in range(s + 1, e + 1):
+            total += 2.0 * layer_fwd(cfg.layers[li - 1])
+    return total
+
+
+def attention_flops_per_step(cfg):
+    """Causal attention: forward 2*B*H*S^2*dh (two matmuls, half masked), backward twice that."""
+    import lp_inputs as LI
+    if cfg.layers[0].kind != "decoder":
+        return 0.0, 0.0
+    B = cfg.batch
+    fwd = 0.0
+    bwd = 0.0
+    per = [2.0 * B * l.n_heads * l.seq_len ** 2 * (l.width // l.n_heads) for l in cfg.layers]
+    fwd = sum(per)
+    for (s, e) in LI.head_windows(cfg):
+        for li in range(s + 1, e + 1):
+            bwd += 2.0 * per[li - 1]
+    return fwd, bwd
+
+
+def optimizer_bytes_per_step(cfg):
+    """Adam 30 B/param (read p, g, m, v; write p, m, v in fp32 + the bf16 copy), SGD-momentum 22,
+    SGD 12 (+2 with a bf16 copy); only parameters covered by a window are updated."""
+    import numpy as np
+    import lp_inputs as LI
+    per = {"sgd": 12, "sgdm": 20, "adam": 28}[cfg.opt.kind] + (2 if cfg.dtype == "bf16" else 0)
+    covered = set()
+    for (s, e) in LI.head_windows(cfg):
+        covered |= set(range(s + 1, e + 1))
+    n = 0
+    for name, shape in LI.param_shapes(cfg).items():
+        if name.startswith("H") or int(name.split(".")[0][1:]) in covered:
+            n += int(np.prod(shape))
+    return n * per, n
+
+
+def cpu_baseline(cfg, budget_s=30.0):
+    """The CPU oracle (float32 mode, numpy/BLAS on the host cores) timed on a bounded sample of the
+    same workload and scaled to whole-step samples/s."""
+    import numpy as np
+    import lp_inputs as LI
+    import oracle
+    from oracle import local as OL
+    cores = os.cpu_count() or 1
+    try:
+        import threadpoolctl
+        info = threadpoolctl.threadpool_info()
+        threads = max([i.get("num_threads", 1) for i in info] or [1])
+    except Exception:
+        threads = cores
+    P = LI.init_params(cfg)
+    x, y = LI.make_batch(cfg, 0)
+    kind = cfg.layers[0].kind
+    if kind == "decoder":
+        # one block: head 1 with its window, input = the token ids (window starts at layer 0)
+        hi = 1
+        s, e = LI.head_windows(cfg)[0]
+        names = [k for k in P if k.startswith("H1.") or (k[0] == "L" and s < int(k.split(".")[0][1:]) <= e)]
+        st = oracle.new_state(cfg, {k: P[k] for k in names}, np.float32)
+        t0 = time.perf_counter()
+        loss, grads, _ = oracle.block_gradients(cfg, P, hi, x, y, dtype=np.float32)
+        for k in grads:
+            OL.optimizer_update(cfg.opt, P[k], grads[k].astype(np.float32), st, k, 1)
+        dt = time.perf_counter() - t0
+        total_flops = gemm_flops_per_step(cfg) + sum(attention_flops_per_step(cfg))
+        import dataclasses
+        sub = dataclasses.replace(cfg, layers=cfg.layers[:e], heads=cfg.heads[:1])
+        sample_flops = gemm_flops_per_step(sub) + sum(attention_flops_per_step(sub))
+        scale = total_flops / sample_flops
+        step_s = dt * scale
+        sample = (f"block 1 of {len(cfg.heads)} (layers {s + 1}..{e} + aux head + optimizer), float32, "
+                  f"{dt:.1f} s, scaled by the step's FLOP ratio x{scale:.2f}")
+    else:
+        st = oracle.new_state(cfg, P, np.float32)
+        oracle.local_step(cfg, P, st, x, y, dtype=np.float32)     # warm-up
+        reps = 0
+        t0 = time.perf_counter()
+        while True:
+            oracle.local_step(cfg, P, st, x, y, dtype=np.float32)
+            reps += 1
+            if time.perf_counter() - t0 > min(budget_s, 10.0) or reps >= 3:
+                break
+        step_s = (time.perf_counter() - t0) / reps
+        sample = f"{reps} whole step(s), float32"
+    return {"value": cfg.batch / step_s, "unit": "samples/s", "cores": threads, "kind": "oracle",
+            "sample": sample, "host_cpus": cores}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg3", help="cfg1..cfg5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="skip the HIP-event pass (used under rocprofv3)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (local parallelism is measured on a single MI355X); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import lp_inputs as LI
+    import paper_2012_03837_amd as lp
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    cfg = LI.make_config(args.config)
+    tr = lp.LocalTrainer(cfg)
+    K, W = args.steps, args.warmup
+    n_stage = min(K + W, 8)
+    staged = [tr.stage(*LI.make_batch(cfg, i)) for i in range(n_stage)]
+    torch.cuda.synchronize()
+
+    def run(n, first):
+        for i in range(n):
+            xd, yd = staged[(first + i) % n_stage]
+            tr.step(xd, yd)
+
+    run(W, 0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(K, W)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec = t1 - t0
+    ms_per_step = sec / K * 1e3
+    value = cfg.batch * K / sec
+    losses = tr.losses.cpu().numpy().tolist()
+
+    # second pass over the same K steps with HIP events around every op, for the per-kernel figures
+    phases = {}
+    roofline = None
+    if not args.no_profile:
+        lp.lp_profile_enable(tr.ctx, True)
+        for i in range(K):
+            xd, yd = staged[(W + i) % n_stage]
+            tr.step(xd, yd)
+            lp.lp_profile_read(tr.ctx, 0)
+        for kc, name in enumerate(lp.KERNEL_CLASSES):
+            ms, n, fl = lp.lp_profile_read(tr.ctx, kc)
+            if n:
+                phases[name] = {"ms_per_step": ms / K, "ops_per_step": n / K, "flops_launched_per_step": fl / K}
+        lp.lp_profile_enable(tr.ctx, False)
+        gf = gemm_flops_per_step(cfg)
+        af, ab = attention_flops_per_step(cfg)
+        ob, npar = optimizer_bytes_per_step(cfg)
+        key = "gemm" if "gemm" in phases and cfg.layers[0].kind != "resnet_stage" else "conv"
+        if key in phases:
+            p = phases[key]
+            peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+            algo = gf if key == "gemm" else gf
+            ach = algo / (p["ms_per_step"] * 1e-3) / 1e12
+            roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": "k_gemm_mfma" if cfg.dtype == "bf16" else "k_gemm_plain",
+                        "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                        "algorithmic_flops_per_step": algo, "launches_per_step": p["ops_per_step"],
+                        "avg_launch_ms": p["ms_per_step"] / p["ops_per_step"]}
+        if "gemm" in phases:
+            phases["gemm"]["algorithmic_tflops"] = gf / 1e12
+        if "attn_fwd" in phases:
+            phases["attn_fwd"]["achieved_tflops"] = af / (phases["attn_fwd"]["ms_per_step"] * 1e-3) / 1e12
+        if "attn_bwd" in phases:
+            phases["attn_bwd"]["achieved_tflops"] = ab / (phases["attn_bwd"]["ms_per_step"] * 1e-3) / 1e12
+        if "optimizer" in phases:
+            phases["optimizer"]["achieved_GBs"] = ob / (phases["optimizer"]["ms_per_step"] * 1e-3) / 1e9
+            phases["optimizer"]["frac_of_hbm_peak"] = phases["optimizer"]["achieved_GBs"] / PEAK_HBM_GBS
+            phases["optimizer"]["bytes_per_step"] = ob
+
+    out = {
+        "metric": "samples/sec per local-update step", "value": value, "unit": "samples/s", "n_gpus": 1,
+        "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": cfg.batch, "n_layers": cfg.n_layers, "n_heads_aux": len(cfg.heads),
+                   "windows": LI.head_windows(cfg)[:3] + (["..."] if len(cfg.heads) > 3 else []),
+                   "optimizer": cfg.opt.kind, "combine": cfg.combine},
+        "roofline": roofline,
+        "phases": phases,
+        "final_losses": losses[:4],
+    }
+    if cfg.layers[0].kind == "decoder":
+        out["tokens_per_s"] = value * cfg.layers[0].seq_len
+        out["config"].update(seq_len=cfg.layers[0].seq_len, d_model=cfg.layers[0].width, vocab=cfg.vocab)
+    tr.close()
+    del tr
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -144,6 +144,18 @@ const char* lp_param_name(lp_ctx* ctx, int i);
 int lp_get_step(lp_ctx* ctx);
 int lp_set_step(lp_ctx* ctx, int t);
 
+/* Per-kernel-class timing.  While enabled, every op brackets its launches with a pair of HIP events
+ * on the context's stream.  lp_profile_read drains the stream and returns, for one class, the summed
+ * event time in ms, the number of ops launched and (for GEMM / convolution classes) the FLOPs
+ * launched, all since profiling was last enabled.  Read after every step: the event pool holds 8192
+ * pairs.  Enabling resets the totals. */
+typedef enum {
+  LP_KC_GEMM = 0, LP_KC_ATTN_FWD, LP_KC_ATTN_BWD, LP_KC_LAYERNORM, LP_KC_SOFTMAX_CE, LP_KC_OPTIMIZER, LP_KC_EMBED,
+  LP_KC_COLSUM, LP_KC_CONV, LP_KC_BATCHNORM, LP_KC_OTHER, LP_KC_COUNT
+} lp_kernel_class;
+int lp_profile_enable(lp_ctx* ctx, int on);
+int lp_profile_read(lp_ctx* ctx, int kernel_class, double* total_ms, long long* launches, double* flops);
+
 /* Text of the last error on this context (or of the last failed init when ctx is NULL); valid
  * until the next call. */
 const char* lp_last_error(const lp_ctx* ctx);

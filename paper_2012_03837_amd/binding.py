@@ -84,6 +84,8 @@ def lib() -> C.CDLL:
         L.lp_set_step.argtypes = [vp, ip]
         L.lp_last_error.argtypes = [vp]
         L.lp_last_error.restype = C.c_char_p
+        L.lp_profile_enable.argtypes = [vp, ip]
+        L.lp_profile_read.argtypes = [vp, ip, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]
         L.lp_destroy.argtypes = [vp]
         L.lp_destroy.restype = None
         _lib = L
@@ -176,6 +178,21 @@ def lp_get_step(ctx: int) -> int:
 
 def lp_set_step(ctx: int, t: int) -> None:
     _check(lib().lp_set_step(ctx, t), ctx)
+
+
+KERNEL_CLASSES = ("gemm", "attn_fwd", "attn_bwd", "layernorm", "softmax_ce", "optimizer", "embed", "colsum", "conv",
+                  "batchnorm", "other")
+
+
+def lp_profile_enable(ctx: int, on: bool) -> None:
+    _check(lib().lp_profile_enable(ctx, int(on)), ctx)
+
+
+def lp_profile_read(ctx: int, kernel_class: int):
+    """(total event ms, ops launched, FLOPs launched) of one kernel class since profiling was enabled."""
+    ms, n, fl = C.c_double(), C.c_longlong(), C.c_double()
+    _check(lib().lp_profile_read(ctx, kernel_class, C.byref(ms), C.byref(n), C.byref(fl)), ctx)
+    return ms.value, n.value, fl.value
 
 
 def lp_destroy(ctx: int) -> None:

@@ -64,11 +64,36 @@ struct ConvArgs {
   int P, Q;            // output spatial
 };
 
+// Optional per-kernel-class timing with HIP events recorded on the launch stream.
+enum KernelClass { KC_GEMM = 0, KC_ATTN_FWD, KC_ATTN_BWD, KC_LAYERNORM, KC_SOFTMAX_CE, KC_OPTIMIZER, KC_EMBED,
+                   KC_COLSUM, KC_CONV, KC_BATCHNORM, KC_OTHER, KC_COUNT };
+struct Profiler {
+  bool on = false;
+  struct Pair { hipEvent_t a, b; int kc; };
+  Pair* pairs = nullptr; int cap = 0; int used = 0; int dropped = 0;
+  double total_ms[KC_COUNT] = {}; long long launches[KC_COUNT] = {}; double flops[KC_COUNT] = {};
+};
+
 struct OpCtx {
   hipStream_t stream;
   int dt;              // compute dtype
   float* partial;      // fp32 scratch for two-stage reductions
   size_t partial_elems;
+  Profiler* prof = nullptr;
+};
+
+// RAII bracket: records an event pair around the launches of one op when profiling is on.
+struct ProfScope {
+  Profiler* p; hipStream_t s; int idx = -1;
+  ProfScope(const OpCtx& c, int kc, double flops = 0.0) : p(c.prof), s(c.stream) {
+    if (!p || !p->on) { p = nullptr; return; }
+    p->launches[kc] += 1; p->flops[kc] += flops;
+    if (p->used >= p->cap) { p->dropped += 1; p = nullptr; return; }
+    idx = p->used++;
+    p->pairs[idx].kc = kc;
+    (void)hipEventRecord(p->pairs[idx].a, s);
+  }
+  ~ProfScope() { if (p) (void)hipEventRecord(p->pairs[idx].b, s); }
 };
 
 // ---- ops (each enqueues on ctx.stream and returns a hipError_t) -------------------------------

@@ -106,8 +106,10 @@ struct lp_ctx {
   bool ok = false;
   std::string err;
 
+  mutable lp::Profiler prof;
   lp::OpCtx op() const {
-    lp::OpCtx c; c.stream = stream; c.dt = dt; c.partial = partial; c.partial_elems = partial_elems; return c;
+    lp::OpCtx c; c.stream = stream; c.dt = dt; c.partial = partial; c.partial_elems = partial_elems;
+    c.prof = &prof; return c;
   }
   float* P32(int ti) const { return master + tensors[ti].off; }
   float* G32(int ti) const { return grads + tensors[ti].off; }

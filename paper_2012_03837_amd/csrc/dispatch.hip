@@ -13,20 +13,25 @@ hipError_t conv_bwd_weight_plain(const OpCtx& c, const ConvArgs& a, const void* 
                                  int accumulate);
 
 hipError_t op_attn_fwd(const OpCtx& c, const void* qkv, void* o, float* lse, int B, int S, int H, int dh, int causal) {
+  ProfScope prof_(c, KC_ATTN_FWD);
   return attn_fwd_plain(c, qkv, o, lse, B, S, H, dh, causal);
 }
 hipError_t op_attn_bwd(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout, void* dqkv,
                        float* delta, int B, int S, int H, int dh, int causal) {
+  ProfScope prof_(c, KC_ATTN_BWD);
   return attn_bwd_plain(c, qkv, o, lse, dout, dqkv, delta, B, S, H, dh, causal);
 }
 hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {
+  ProfScope prof_(c, KC_CONV, 2.0 * a.N * a.P * a.Q * a.O * a.R * a.S * a.C);
   return conv_fwd_plain(c, a, x, w, out);
 }
 hipError_t op_conv_bwd_data(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx) {
+  ProfScope prof_(c, KC_CONV, 2.0 * a.N * a.P * a.Q * a.O * a.R * a.S * a.C);
   return conv_bwd_data_plain(c, a, dout, w, dx);
 }
 hipError_t op_conv_bwd_weight(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                               int accumulate) {
+  ProfScope prof_(c, KC_CONV, 2.0 * a.N * a.P * a.Q * a.O * a.R * a.S * a.C);
   return conv_bwd_weight_plain(c, a, dout, x, dw, accumulate);
 }
 

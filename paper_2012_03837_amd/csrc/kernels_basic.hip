@@ -67,6 +67,7 @@ __global__ void k_add(const T* a, const T* b, T* out, size_t n) {
   for (; i < n; i += st) out[i] = from_f<T>(to_f(a[i]) + to_f(b[i]));
 }
 hipError_t op_add(const OpCtx& c, const void* a, const void* b, void* out, size_t n) {
+  ProfScope prof_(c, KC_OTHER);
   if (n == 0) return hipSuccess;
   int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
   if (c.dt == BF16) k_add<bf16_t><<<blocks, 256, 0, c.stream>>>((const bf16_t*)a, (const bf16_t*)b, (bf16_t*)out, n);
@@ -104,6 +105,7 @@ __global__ void k_embed_fwd(const int32_t* ids, const float* emb, const float* p
 }
 hipError_t op_embed_fwd(const OpCtx& c, const int32_t* ids, const float* emb, const float* pe, void* out,
                         int T_, int S, int d, int V) {
+  ProfScope prof_(c, KC_EMBED);
   if (T_ == 0) return hipSuccess;
   if (c.dt == BF16) k_embed_fwd<bf16_t><<<T_, 128, 0, c.stream>>>(ids, emb, pe, (bf16_t*)out, T_, S, d, V);
   else k_embed_fwd<float><<<T_, 128, 0, c.stream>>>(ids, emb, pe, (float*)out, T_, S, d, V);
@@ -143,6 +145,7 @@ __global__ void k_embed_bwd(const int32_t* ids, const T* dh, float* demb, int T_
 }
 hipError_t op_embed_bwd(const OpCtx& c, const int32_t* ids, const void* dh, float* demb, int T_, int V, int d,
                         int accumulate) {
+  ProfScope prof_(c, KC_EMBED);
   dim3 grid(V, (d + 255) / 256);
   if (c.dt == BF16) k_embed_bwd<bf16_t><<<grid, 256, 0, c.stream>>>(ids, (const bf16_t*)dh, demb, T_, d, accumulate);
   else k_embed_bwd<float><<<grid, 256, 0, c.stream>>>(ids, (const float*)dh, demb, T_, d, accumulate);
@@ -172,6 +175,7 @@ __global__ void k_ln_fwd(const T* x, const float* g, const float* b, T* y, float
 }
 hipError_t op_layernorm_fwd(const OpCtx& c, const void* x, const float* g, const float* b, void* y, float* mean,
                             float* rstd, int rows, int d) {
+  ProfScope prof_(c, KC_LAYERNORM);
   if (rows == 0) return hipSuccess;
   int blocks = (rows + 3) / 4;
   if (c.dt == BF16) k_ln_fwd<bf16_t><<<blocks, 256, 0, c.stream>>>((const bf16_t*)x, g, b, (bf16_t*)y, mean, rstd, rows, d);
@@ -242,6 +246,7 @@ __global__ void k_reduce_partials(const float* partial, int nblk, int n, float* 
 hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const float* mean, const float* rstd,
                             const float* g, const void* add, void* dx, float* dg, float* db, int rows, int d,
                             int accumulate) {
+  ProfScope prof_(c, KC_LAYERNORM);
   if (rows == 0) return hipSuccess;
   int nblk = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
   if ((size_t)nblk * d * 2 > c.partial_elems) return hipErrorInvalidValue;
@@ -278,6 +283,7 @@ __global__ void k_colsum_partial(const T* dy, int64_t ld, float* partial, int ro
     partial[(size_t)blockIdx.y * n + col] = sh[0][threadIdx.x] + sh[1][threadIdx.x] + sh[2][threadIdx.x] + sh[3][threadIdx.x];
 }
 hipError_t op_colsum(const OpCtx& c, const void* dy, int64_t ld, float* out, int rows, int n, int accumulate) {
+  ProfScope prof_(c, KC_COLSUM);
   if (n == 0) return hipSuccess;
   int nslab = (rows + kColsumRows - 1) / kColsumRows;
   if (nslab < 1) nslab = 1;
@@ -322,6 +328,7 @@ __global__ void k_softmax_ce(T* z, int64_t ld, const int32_t* y, float* loss_row
 }
 hipError_t op_softmax_ce(const OpCtx& c, void* z, int64_t ld, const int32_t* y, float* loss_rows, int rows, int n,
                          int write_grad, float inv_rows) {
+  ProfScope prof_(c, KC_SOFTMAX_CE);
   if (rows == 0) return hipSuccess;
   if (c.dt == BF16) k_softmax_ce<bf16_t><<<rows, 256, 0, c.stream>>>((bf16_t*)z, ld, y, loss_rows, n, write_grad, inv_rows);
   else k_softmax_ce<float><<<rows, 256, 0, c.stream>>>((float*)z, ld, y, loss_rows, n, write_grad, inv_rows);
@@ -337,6 +344,7 @@ __global__ void k_mean(const float* v, int n, float* out) {
   if (threadIdx.x == 0) out[0] = s / (float)n;
 }
 hipError_t op_mean(const OpCtx& c, const float* v, int n, float* out) {
+  ProfScope prof_(c, KC_OTHER);
   k_mean<<<1, 256, 0, c.stream>>>(v, n, out);
   return LP_LAUNCH_CHECK();
 }
@@ -381,6 +389,7 @@ __global__ void k_optimizer(float* __restrict__ p, const float* __restrict__ g, 
 }
 hipError_t op_optimizer(const OpCtx& c, const OptArgs& o, float* p, const float* g, float* m, float* v,
                         void* p_lowp, size_t n) {
+  ProfScope prof_(c, KC_OPTIMIZER);
   if (n == 0) return hipSuccess;
   if (n % 4) return hipErrorInvalidValue;   // ranges are padded to 64 elements by the layout
   size_t n4 = n / 4;

@@ -133,6 +133,7 @@ static int use_plain() {
 }
 
 hipError_t op_gemm(const OpCtx& c, const GemmArgs& g) {
+  ProfScope prof_(c, KC_GEMM, 2.0 * g.M * g.N * g.K);
   if (c.dt == BF16 && !use_plain()) return gemm_mfma(c, g);
   return gemm_plain(c, g);
 }

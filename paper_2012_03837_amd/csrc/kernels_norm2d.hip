@@ -105,6 +105,7 @@ static hipError_t bn_fwd_t(const OpCtx& c, const void* z, const float* g, const 
 }
 hipError_t op_batchnorm_fwd(const OpCtx& c, const void* z, const float* g, const float* b, const void* res, void* y,
                             float* mean, float* rstd, int rows, int C, int relu) {
+  ProfScope prof_(c, KC_BATCHNORM);
   if (rows == 0) return hipSuccess;
   return c.dt == BF16 ? bn_fwd_t<bf16_t>(c, z, g, b, res, y, mean, rstd, rows, C, relu)
                       : bn_fwd_t<float>(c, z, g, b, res, y, mean, rstd, rows, C, relu);
@@ -131,6 +132,7 @@ static hipError_t bn_bwd_t(const OpCtx& c, const void* dy, const void* y, const 
 hipError_t op_batchnorm_bwd(const OpCtx& c, const void* dy, const void* y, const void* z, const float* mean,
                             const float* rstd, const float* g, void* dz, void* dres, float* dg, float* db, int rows,
                             int C, int relu, int accumulate) {
+  ProfScope prof_(c, KC_BATCHNORM);
   if (rows == 0) return hipSuccess;
   return c.dt == BF16 ? bn_bwd_t<bf16_t>(c, dy, y, z, mean, rstd, g, dz, dres, dg, db, rows, C, relu, accumulate)
                       : bn_bwd_t<float>(c, dy, y, z, mean, rstd, g, dz, dres, dg, db, rows, C, relu, accumulate);
@@ -158,12 +160,14 @@ __global__ void k_avgpool_bwd(const T* dfeat, T* dx, size_t n, int HW, int C) {
   }
 }
 hipError_t op_avgpool_fwd(const OpCtx& c, const void* x, void* out, int N, int HW, int C) {
+  ProfScope prof_(c, KC_OTHER);
   if (N == 0) return hipSuccess;
   if (c.dt == BF16) k_avgpool_fwd<bf16_t><<<N, 256, 0, c.stream>>>((const bf16_t*)x, (bf16_t*)out, HW, C);
   else k_avgpool_fwd<float><<<N, 256, 0, c.stream>>>((const float*)x, (float*)out, HW, C);
   return hipGetLastError();
 }
 hipError_t op_avgpool_bwd(const OpCtx& c, const void* dfeat, void* dx, int N, int HW, int C) {
+  ProfScope prof_(c, KC_OTHER);
   size_t n = (size_t)N * HW * C;
   if (n == 0) return hipSuccess;
   if (c.dt == BF16) k_avgpool_bwd<bf16_t><<<ew_blocks(n), 256, 0, c.stream>>>((const bf16_t*)dfeat, (bf16_t*)dx, n, HW, C);

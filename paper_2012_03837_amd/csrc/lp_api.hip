@@ -372,7 +372,63 @@ extern "C" int lp_init_blocks(const lp_model_spec* spec, const lp_buffers* buffe
   return LP_OK;
 }
 
-extern "C" void lp_destroy(lp_ctx* c) { delete c; }
+static void prof_free(lp_ctx* c) {
+  for (int i = 0; i < c->prof.cap; ++i) { (void)hipEventDestroy(c->prof.pairs[i].a); (void)hipEventDestroy(c->prof.pairs[i].b); }
+  delete[] c->prof.pairs;
+  c->prof.pairs = nullptr; c->prof.cap = 0; c->prof.used = 0;
+}
+// Folds finished event pairs into the per-class totals.
+static int prof_collect(lp_ctx* c) {
+  if (c->prof.used == 0) return LP_OK;
+  CK(hipStreamSynchronize(c->stream));
+  for (int i = 0; i < c->prof.used; ++i) {
+    float ms = 0.f;
+    CK(hipEventElapsedTime(&ms, c->prof.pairs[i].a, c->prof.pairs[i].b));
+    c->prof.total_ms[c->prof.pairs[i].kc] += ms;
+  }
+  c->prof.used = 0;
+  return LP_OK;
+}
+
+extern "C" int lp_profile_enable(lp_ctx* c, int on) {
+  if (!c) return LP_EINVAL;
+  if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
+  if (on && !c->prof.pairs) {
+    const int cap = 8192;
+    c->prof.pairs = new Profiler::Pair[cap];
+    for (int i = 0; i < cap; ++i) {
+      CK(hipEventCreate(&c->prof.pairs[i].a));
+      CK(hipEventCreate(&c->prof.pairs[i].b));
+      c->prof.cap = i + 1;
+    }
+  }
+  if (on) {
+    int st = prof_collect(c);
+    if (st != LP_OK) return st;
+    for (int k = 0; k < KC_COUNT; ++k) { c->prof.total_ms[k] = 0; c->prof.launches[k] = 0; c->prof.flops[k] = 0; }
+    c->prof.dropped = 0;
+  }
+  c->prof.on = on != 0;
+  return LP_OK;
+}
+
+extern "C" int lp_profile_read(lp_ctx* c, int kernel_class, double* total_ms, long long* launches, double* flops) {
+  if (!c) return LP_EINVAL;
+  if (kernel_class < 0 || kernel_class >= KC_COUNT) return fail(c, LP_EINVAL, "bad kernel class");
+  int st = prof_collect(c);
+  if (st != LP_OK) return st;
+  if (c->prof.dropped) return fail(c, LP_ESTATE, "event pool overflowed: read the profile after every step");
+  if (total_ms) *total_ms = c->prof.total_ms[kernel_class];
+  if (launches) *launches = c->prof.launches[kernel_class];
+  if (flops) *flops = c->prof.flops[kernel_class];
+  return LP_OK;
+}
+
+extern "C" void lp_destroy(lp_ctx* c) {
+  if (!c) return;
+  prof_free(c);
+  delete c;
+}
 
 extern "C" const char* lp_last_error(const lp_ctx* c) { return c ? c->err.c_str() : g_init_err.c_str(); }
 
