@@ -1,0 +1,79 @@
+/*
+ * lp_kernels.h -- kernel-level C ABI: the individual HIP ops the local-update step is made of,
+ * callable on caller-owned DEVICE buffers.  Used by the per-kernel parity tests and by the bench's
+ * per-kernel roofline measurements.  Every call enqueues on `stream` (a hipStream_t, NULL = default)
+ * and returns 0 or a nonzero hipError_t code; nothing is allocated.  `dtype` is the compute dtype
+ * (0 = fp32, 1 = bf16) of activations and matrix operands; gradients of parameters, statistics and
+ * optimizer state are fp32.  `scratch_dev` is fp32 workspace for two-stage reductions
+ * (scratch_elems floats; a call that needs more fails with hipErrorInvalidValue).
+ */
+#ifndef LP_KERNELS_H_
+#define LP_KERNELS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[M,N] (+)= sum_k A(m,k) B(n,k) followed by the fused epilogue
+ *   v (+= bias[n]); pre[m,n] = v; v = act(v); v *= act'(dact_src[m,n]); v += res[m,n].
+ * A(m,k) = a_kc ? A[m*lda+k] : A[k*lda+m]; B(n,k) = b_kc ? B[n*ldb+k] : B[k*ldb+n]  (the forward, dgrad
+ * and wgrad forms of a linear layer: paper appendix A, "MLP").  act / dact: 0 none, 1 ReLU, 2 GELU(tanh).
+ * plain != 0 forces the FMA kernel instead of the MFMA kernel. */
+int lpk_gemm(int dtype, const void* A, int64_t lda, int a_kc, const void* B, int64_t ldb, int b_kc, void* C,
+             int64_t ldc, int c_f32, int M, int N, int K, const float* bias, int act, void* pre,
+             const void* dact_src, int dact, int64_t ldd, const void* res, int64_t ldr, int accumulate, int plain,
+             void* stream);
+
+/* Causal (or full) multi-head attention of a decoder layer (appendix B.2).  qkv [B*S, 3*H*dh]
+ * (q | k | v), o [B*S, H*dh], lse [B,H,S] = log-sum-exp of the scaled scores, delta [B,H,S] scratch. */
+int lpk_attention_fwd(int dtype, const void* qkv, void* o, float* lse, int B, int S, int H, int dh, int causal,
+                      int plain, void* stream);
+int lpk_attention_bwd(int dtype, const void* qkv, const void* o, const float* lse, const void* dout, void* dqkv,
+                      float* delta, int B, int S, int H, int dh, int causal, int plain, void* stream);
+
+/* LayerNorm over the last dimension (eps 1e-5, biased variance); backward adds `add` to dx if given. */
+int lpk_layernorm_fwd(int dtype, const void* x, const float* g, const float* b, void* y, float* mean, float* rstd,
+                      int rows, int d, void* stream);
+int lpk_layernorm_bwd(int dtype, const void* dy, const void* x, const float* mean, const float* rstd,
+                      const float* g, const void* add, void* dx, float* dg, float* db, int rows, int d,
+                      int accumulate, float* scratch_dev, size_t scratch_elems, void* stream);
+
+/* Row-wise softmax cross-entropy (the auxiliary objective, section 3): loss_rows[r] = lse(z_r) - z[r,y_r];
+ * with write_grad, z is overwritten by (softmax(z_r) - onehot(y_r)) * inv_rows. */
+int lpk_softmax_ce(int dtype, void* z, int64_t ld, const int32_t* y, float* loss_rows, int rows, int n,
+                   int write_grad, float inv_rows, void* stream);
+
+/* Fused optimizer update over a flat range (kind 0 SGD, 1 SGD-momentum, 2 Adam; appendix B lists the
+ * optimizers); n must be a multiple of 4; p_bf16 (may be NULL) receives the bf16 working copy. */
+int lpk_optimizer(int kind, float lr, float momentum, float beta1, float beta2, float eps, float weight_decay,
+                  int t, float grad_scale, float* p, const float* g, float* m, float* v, void* p_bf16, size_t n,
+                  void* stream);
+
+/* Embedding-table gradient: demb[v,:] (+)= sum of dh[t,:] over positions with ids[t] == v, in order of t. */
+int lpk_embed_bwd(int dtype, const int32_t* ids, const void* dh, float* demb, int T, int V, int d, int accumulate,
+                  void* stream);
+
+/* NHWC convolution with [O,R,S,C] filters as implicit GEMM (appendix B.3), forward / data gradient /
+ * filter gradient (fp32). */
+int lpk_conv_fwd(int dtype, const void* x, const void* w, void* out, int N, int H, int W, int C, int O, int R,
+                 int stride, int pad, void* stream);
+int lpk_conv_bwd_data(int dtype, const void* dout, const void* w, void* dx, int N, int H, int W, int C, int O, int R,
+                      int stride, int pad, void* stream);
+int lpk_conv_bwd_weight(int dtype, const void* dout, const void* x, float* dw, int N, int H, int W, int C, int O,
+                        int R, int stride, int pad, int accumulate, void* stream);
+
+/* BatchNorm with batch statistics over rows = N*H*W, fused residual add and ReLU. */
+int lpk_batchnorm_fwd(int dtype, const void* z, const float* g, const float* b, const void* res, void* y,
+                      float* mean, float* rstd, int rows, int C, int relu, float* scratch_dev, size_t scratch_elems,
+                      void* stream);
+int lpk_batchnorm_bwd(int dtype, const void* dy, const void* y, const void* z, const float* mean, const float* rstd,
+                      const float* g, void* dz, void* dres, float* dg, float* db, int rows, int C, int relu,
+                      int accumulate, float* scratch_dev, size_t scratch_elems, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LP_KERNELS_H_ */

@@ -1,5 +1,6 @@
 // Choice of kernel per op and compute dtype: MFMA kernels for bf16 where they apply, plain kernels
 // for fp32 and for shapes the MFMA kernels do not take.
+#include <stdlib.h>
 #include "common.h"
 
 namespace lp {
@@ -12,13 +13,25 @@ hipError_t conv_bwd_data_plain(const OpCtx& c, const ConvArgs& a, const void* do
 hipError_t conv_bwd_weight_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                                  int accumulate);
 
+hipError_t attn_fwd_mfma(const OpCtx& c, const void* qkv, void* o, float* lse, int B, int S, int H, int causal);
+hipError_t attn_bwd_mfma(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout,
+                         void* dqkv, float* delta, int B, int S, int H, int causal);
+
+static bool use_mfma_attn(const OpCtx& c, int dh) {
+  static int plain = -1;
+  if (plain < 0) { const char* s = getenv("LP_PLAIN_ATTN"); plain = (s && s[0] == '1') ? 1 : 0; }
+  return c.dt == BF16 && dh == 64 && !plain;
+}
+
 hipError_t op_attn_fwd(const OpCtx& c, const void* qkv, void* o, float* lse, int B, int S, int H, int dh, int causal) {
   ProfScope prof_(c, KC_ATTN_FWD);
+  if (use_mfma_attn(c, dh)) return attn_fwd_mfma(c, qkv, o, lse, B, S, H, causal);
   return attn_fwd_plain(c, qkv, o, lse, B, S, H, dh, causal);
 }
 hipError_t op_attn_bwd(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout, void* dqkv,
                        float* delta, int B, int S, int H, int dh, int causal) {
   ProfScope prof_(c, KC_ATTN_BWD);
+  if (use_mfma_attn(c, dh)) return attn_bwd_mfma(c, qkv, o, lse, dout, dqkv, delta, B, S, H, causal);
   return attn_bwd_plain(c, qkv, o, lse, dout, dqkv, delta, B, S, H, dh, causal);
 }
 hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {

@@ -1,0 +1,102 @@
+// Kernel-level C ABI (include/lp_kernels.h): thin wrappers that build an OpCtx and call one op.
+#include "../../include/lp_kernels.h"
+#include "common.h"
+
+namespace lp {
+hipError_t gemm_plain(const OpCtx& c, const GemmArgs& g);
+hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g);
+hipError_t attn_fwd_plain(const OpCtx& c, const void* qkv, void* o, float* lse, int B, int S, int H, int dh, int causal);
+hipError_t attn_bwd_plain(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout,
+                          void* dqkv, float* delta, int B, int S, int H, int dh, int causal);
+hipError_t conv_fwd_plain(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out);
+hipError_t conv_bwd_data_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx);
+hipError_t conv_bwd_weight_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
+                                 int accumulate);
+}
+using namespace lp;
+
+static OpCtx mk(int dtype, void* stream, float* scratch = nullptr, size_t n = 0) {
+  OpCtx c; c.stream = (hipStream_t)stream; c.dt = dtype; c.partial = scratch; c.partial_elems = n; c.prof = nullptr;
+  return c;
+}
+static ConvArgs mkconv(int N, int H, int W, int C, int O, int R, int stride, int pad) {
+  ConvArgs a; a.N = N; a.H = H; a.W = W; a.C = C; a.O = O; a.R = R; a.S = R; a.stride = stride; a.pad = pad;
+  a.P = (H + 2 * pad - R) / stride + 1; a.Q = (W + 2 * pad - R) / stride + 1;
+  return a;
+}
+
+extern "C" int lpk_gemm(int dtype, const void* A, int64_t lda, int a_kc, const void* B, int64_t ldb, int b_kc, void* C,
+                        int64_t ldc, int c_f32, int M, int N, int K, const float* bias, int act, void* pre,
+                        const void* dact_src, int dact, int64_t ldd, const void* res, int64_t ldr, int accumulate,
+                        int plain, void* stream) {
+  GemmArgs g;
+  g.A = A; g.lda = lda; g.a_kc = a_kc; g.B = B; g.ldb = ldb; g.b_kc = b_kc; g.C = C; g.ldc = ldc; g.c_f32 = c_f32;
+  g.M = M; g.N = N; g.K = K; g.bias = bias; g.act = act; g.pre = pre; g.dact_src = dact_src; g.dact = dact; g.ldd = ldd;
+  g.res = res; g.ldr = ldr; g.accumulate = accumulate;
+  OpCtx c = mk(dtype, stream);
+  if (plain || dtype != BF16) return (int)gemm_plain(c, g);
+  return (int)op_gemm(c, g);
+}
+extern "C" int lpk_attention_fwd(int dtype, const void* qkv, void* o, float* lse, int B, int S, int H, int dh,
+                                 int causal, int plain, void* stream) {
+  OpCtx c = mk(dtype, stream);
+  if (plain) return (int)attn_fwd_plain(c, qkv, o, lse, B, S, H, dh, causal);
+  return (int)op_attn_fwd(c, qkv, o, lse, B, S, H, dh, causal);
+}
+extern "C" int lpk_attention_bwd(int dtype, const void* qkv, const void* o, const float* lse, const void* dout,
+                                 void* dqkv, float* delta, int B, int S, int H, int dh, int causal, int plain,
+                                 void* stream) {
+  OpCtx c = mk(dtype, stream);
+  if (plain) return (int)attn_bwd_plain(c, qkv, o, lse, dout, dqkv, delta, B, S, H, dh, causal);
+  return (int)op_attn_bwd(c, qkv, o, lse, dout, dqkv, delta, B, S, H, dh, causal);
+}
+extern "C" int lpk_layernorm_fwd(int dtype, const void* x, const float* g, const float* b, void* y, float* mean,
+                                 float* rstd, int rows, int d, void* stream) {
+  return (int)op_layernorm_fwd(mk(dtype, stream), x, g, b, y, mean, rstd, rows, d);
+}
+extern "C" int lpk_layernorm_bwd(int dtype, const void* dy, const void* x, const float* mean, const float* rstd,
+                                 const float* g, const void* add, void* dx, float* dg, float* db, int rows, int d,
+                                 int accumulate, float* scratch, size_t scratch_elems, void* stream) {
+  return (int)op_layernorm_bwd(mk(dtype, stream, scratch, scratch_elems), dy, x, mean, rstd, g, add, dx, dg, db, rows,
+                               d, accumulate);
+}
+extern "C" int lpk_softmax_ce(int dtype, void* z, int64_t ld, const int32_t* y, float* loss_rows, int rows, int n,
+                              int write_grad, float inv_rows, void* stream) {
+  return (int)op_softmax_ce(mk(dtype, stream), z, ld, y, loss_rows, rows, n, write_grad, inv_rows);
+}
+extern "C" int lpk_optimizer(int kind, float lr, float momentum, float beta1, float beta2, float eps,
+                             float weight_decay, int t, float grad_scale, float* p, const float* g, float* m, float* v,
+                             void* p_bf16, size_t n, void* stream) {
+  OptArgs o; o.kind = kind; o.lr = lr; o.momentum = momentum; o.beta1 = beta1; o.beta2 = beta2; o.eps = eps;
+  o.weight_decay = weight_decay; o.t = t; o.grad_scale = grad_scale;
+  if (kind < 0 || kind > 2) return (int)hipErrorInvalidValue;
+  return (int)op_optimizer(mk(F32, stream), o, p, g, m, v, p_bf16, n);
+}
+extern "C" int lpk_embed_bwd(int dtype, const int32_t* ids, const void* dh, float* demb, int T, int V, int d,
+                             int accumulate, void* stream) {
+  return (int)op_embed_bwd(mk(dtype, stream), ids, dh, demb, T, V, d, accumulate);
+}
+extern "C" int lpk_conv_fwd(int dtype, const void* x, const void* w, void* out, int N, int H, int W, int C, int O,
+                            int R, int stride, int pad, void* stream) {
+  return (int)op_conv_fwd(mk(dtype, stream), mkconv(N, H, W, C, O, R, stride, pad), x, w, out);
+}
+extern "C" int lpk_conv_bwd_data(int dtype, const void* dout, const void* w, void* dx, int N, int H, int W, int C,
+                                 int O, int R, int stride, int pad, void* stream) {
+  return (int)op_conv_bwd_data(mk(dtype, stream), mkconv(N, H, W, C, O, R, stride, pad), dout, w, dx);
+}
+extern "C" int lpk_conv_bwd_weight(int dtype, const void* dout, const void* x, float* dw, int N, int H, int W, int C,
+                                   int O, int R, int stride, int pad, int accumulate, void* stream) {
+  return (int)op_conv_bwd_weight(mk(dtype, stream), mkconv(N, H, W, C, O, R, stride, pad), dout, x, dw, accumulate);
+}
+extern "C" int lpk_batchnorm_fwd(int dtype, const void* z, const float* g, const float* b, const void* res, void* y,
+                                 float* mean, float* rstd, int rows, int C, int relu, float* scratch,
+                                 size_t scratch_elems, void* stream) {
+  return (int)op_batchnorm_fwd(mk(dtype, stream, scratch, scratch_elems), z, g, b, res, y, mean, rstd, rows, C, relu);
+}
+extern "C" int lpk_batchnorm_bwd(int dtype, const void* dy, const void* y, const void* z, const float* mean,
+                                 const float* rstd, const float* g, void* dz, void* dres, float* dg, float* db,
+                                 int rows, int C, int relu, int accumulate, float* scratch, size_t scratch_elems,
+                                 void* stream) {
+  return (int)op_batchnorm_bwd(mk(dtype, stream, scratch, scratch_elems), dy, y, z, mean, rstd, g, dz, dres, dg, db,
+                               rows, C, relu, accumulate);
+}

@@ -1,0 +1,267 @@
+"""Per-kernel GPU parity through the kernel-level C ABI, against the CPU oracle's primitives in
+float64 on the same (bf16-representable) inputs.  Shapes span several tiles plus ragged tails."""
+import numpy as np
+import pytest
+
+from oracle import ops
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def K():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2012_03837_amd import kernels
+    return kernels
+
+
+def zeros(*shape, dtype=None):
+    import torch
+    return torch.zeros(*shape, device="cuda", dtype=dtype or torch.float32)
+
+
+def ones(*shape):
+    import torch
+    return torch.ones(*shape, device="cuda", dtype=torch.float32)
+
+
+def dev(a, dtype):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.to(torch.bfloat16) if dtype == 1 and t.is_floating_point() else t
+
+
+def host(t):
+    import torch
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def rnd(rng, shape, dtype, scale=1.0):
+    """Random values that are exactly representable in the compute dtype."""
+    a = (rng.standard_normal(shape) * scale).astype(np.float32)
+    return ops.bf16_round(a).astype(np.float32) if dtype == 1 else a
+
+
+def relerr(a, ref):
+    return float(np.linalg.norm(np.asarray(a, np.float64).ravel() - np.asarray(ref, np.float64).ravel())
+                 / max(np.linalg.norm(np.asarray(ref, np.float64).ravel()), 1e-30))
+
+
+GEMM_SHAPES = [(200, 136, 72), (128, 128, 32), (1, 8, 8), (333, 257, 40), (64, 1000, 128), (600, 128, 600)]
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("a_kc,b_kc", [(1, 1), (1, 0), (0, 0), (0, 1)])
+def test_gemm_layouts_and_epilogues(K, dtype, a_kc, b_kc):
+    import torch
+    rng = np.random.default_rng(5)
+    for (M, N, Kd) in GEMM_SHAPES:
+        A = rnd(rng, (M, Kd), dtype)
+        B = rnd(rng, (N, Kd), dtype)
+        bias = rng.standard_normal(N).astype(np.float32)
+        res = rnd(rng, (M, N), dtype)
+        dsrc = rnd(rng, (M, N), dtype)
+        Am = A if a_kc else np.ascontiguousarray(A.T)
+        Bm = B if b_kc else np.ascontiguousarray(B.T)
+        dA, dB = dev(Am, dtype), dev(Bm, dtype)
+        ref0 = A.astype(np.float64) @ B.astype(np.float64).T
+        tol_lo = 4e-3 if dtype == 1 else 2e-6
+        # (1) plain product into fp32, with accumulate
+        C0 = rng.standard_normal((M, N)).astype(np.float32)
+        dC = dev(C0, 0)
+        K.lpk_gemm(dtype, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, dC, N, 1, M, N, Kd, accumulate=1)
+        assert relerr(host(dC), ref0 + C0) <= 2e-6, (M, N, Kd, "acc")
+        # (2) bias + GELU with saved pre-activation + residual, compute-dtype output
+        out = torch.zeros(M, N, device="cuda", dtype=torch.bfloat16 if dtype else torch.float32)
+        pre = torch.zeros_like(out)
+        K.lpk_gemm(dtype, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out, N, 0, M, N, Kd, bias=dev(bias, 0), act=2,
+                   pre=pre, res=dev(res, dtype), ldr=N)
+        v = ref0 + bias
+        assert relerr(host(pre), v) <= tol_lo
+        assert relerr(host(out), ops.gelu_fwd(v) + res) <= tol_lo, (M, N, Kd, "gelu")
+        # (3) backward-activation epilogues
+        for dact, fn in ((1, lambda s, g: g * (s > 0)), (2, ops.gelu_bwd)):
+            K.lpk_gemm(dtype, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out, N, 0, M, N, Kd, dact_src=dev(dsrc, dtype),
+                       dact=dact, ldd=N)
+            assert relerr(host(out), fn(dsrc.astype(np.float64), ref0)) <= tol_lo, (M, N, Kd, "dact", dact)
+        # (4) the MFMA and plain kernels agree on bf16
+        if dtype == 1:
+            o2 = torch.zeros(M, N, device="cuda", dtype=torch.float32)
+            K.lpk_gemm(dtype, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, o2, N, 1, M, N, Kd, plain=1)
+            assert relerr(host(o2), ref0) <= 2e-6
+
+
+@pytest.mark.parametrize("causal", [1, 0])
+@pytest.mark.parametrize("S", [64, 200, 256, 333])
+def test_attention_mfma_vs_oracle(K, S, causal):
+    import torch
+    rng = np.random.default_rng(S)
+    B, H, dh = 2, 3, 64
+    d = H * dh
+    qkv = rnd(rng, (B * S, 3 * d), 1, scale=1.5)          # sharp softmax: scores of order a few units
+    dout = rnd(rng, (B * S, d), 1)
+    dq = dev(qkv, 1)
+    o = torch.zeros(B * S, d, device="cuda", dtype=torch.bfloat16)
+    lse = torch.zeros(B, H, S, device="cuda", dtype=torch.float32)
+    K.lpk_attention_fwd(1, dq, o, lse, B, S, H, dh, causal)
+
+    def split(t):
+        return t.reshape(B, S, H, dh).transpose(0, 2, 1, 3)
+    q64 = qkv.astype(np.float64)
+    q, k, v = split(q64[:, :d]), split(q64[:, d:2 * d]), split(q64[:, 2 * d:])
+    ro, p = ops.attention_fwd(q, k, v, causal=bool(causal))
+    ro2 = ro.transpose(0, 2, 1, 3).reshape(B * S, d)
+    assert relerr(host(o), ro2) <= 6e-3
+    s = (q @ np.swapaxes(k, -1, -2)) / 8.0
+    if causal:
+        s = np.where(np.tril(np.ones((S, S), bool)), s, -np.inf)
+    ref_lse = np.log(np.exp(s - s.max(-1, keepdims=True)).sum(-1)) + s.max(-1)
+    assert np.abs(host(lse) - ref_lse).max() <= 2e-3
+    # backward, fed the kernel's own o and lse
+    dqkv = torch.zeros(B * S, 3 * d, device="cuda", dtype=torch.bfloat16)
+    delta = torch.zeros(B, H, S, device="cuda", dtype=torch.float32)
+    K.lpk_attention_bwd(1, dq, o, lse, dev(dout, 1), dqkv, delta, B, S, H, dh, causal)
+    rdq, rdk, rdv = ops.attention_bwd(q, k, v, p, split(dout.astype(np.float64)))
+    merge = lambda t: t.transpose(0, 2, 1, 3).reshape(B * S, d)
+    g = host(dqkv)
+    assert relerr(g[:, :d], merge(rdq)) <= 1.5e-2
+    assert relerr(g[:, d:2 * d], merge(rdk)) <= 1.5e-2
+    assert relerr(g[:, 2 * d:], merge(rdv)) <= 1.5e-2
+    # plain kernel on the same inputs
+    o2 = torch.zeros_like(o); lse2 = torch.zeros_like(lse); dqkv2 = torch.zeros_like(dqkv)
+    K.lpk_attention_fwd(1, dq, o2, lse2, B, S, H, dh, causal, plain=1)
+    K.lpk_attention_bwd(1, dq, o2, lse2, dev(dout, 1), dqkv2, delta, B, S, H, dh, causal, plain=1)
+    assert relerr(host(o2), ro2) <= 6e-3
+    assert relerr(host(dqkv2)[:, :d], merge(rdq)) <= 1.5e-2
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("rows,d", [(37, 128), (600, 768), (5, 40), (130, 1024)])
+def test_layernorm(K, dtype, rows, d):
+    import torch
+    rng = np.random.default_rng(rows)
+    x = rnd(rng, (rows, d), dtype, 2.0) + (1.0 if dtype == 0 else 0.0)
+    x = ops.bf16_round(x).astype(np.float32) if dtype else x
+    g = rng.standard_normal(d).astype(np.float32)
+    b = rng.standard_normal(d).astype(np.float32)
+    dy = rnd(rng, (rows, d), dtype)
+    add = rnd(rng, (rows, d), dtype)
+    tdt = torch.bfloat16 if dtype else torch.float32
+    y = torch.zeros(rows, d, device="cuda", dtype=tdt)
+    mean = zeros(rows); rstd = zeros(rows)
+    K.lpk_layernorm_fwd(dtype, dev(x, dtype), dev(g, 0), dev(b, 0), y, mean, rstd, rows, d)
+    ry, cache = ops.layernorm_fwd(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64))
+    tol = 4e-3 if dtype else 2e-6
+    assert relerr(host(y), ry) <= tol
+    assert relerr(host(mean), x.astype(np.float64).mean(-1)) <= 1e-5
+    dx = torch.zeros(rows, d, device="cuda", dtype=tdt)
+    dg = ones(d); db = ones(d)
+    scratch = zeros(2 * ((rows + 31) // 32) * d + 16)
+    K.lpk_layernorm_bwd(dtype, dev(dy, dtype), dev(x, dtype), mean, rstd, dev(g, 0), dev(add, dtype), dx, dg, db, rows, d,
+                        1, scratch)
+    rdx, rdg, rdb = ops.layernorm_bwd(cache, g.astype(np.float64), dy.astype(np.float64))
+    assert relerr(host(dx), rdx + add) <= tol
+    assert relerr(host(dg), rdg + 1) <= 1e-5 and relerr(host(db), rdb + 1) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("rows,n", [(50, 10), (19, 1000), (7, 32000)])
+def test_softmax_ce(K, dtype, rows, n):
+    import torch
+    rng = np.random.default_rng(n)
+    z = rnd(rng, (rows, n), dtype, 3.0)
+    y = rng.integers(0, n, rows).astype(np.int32)
+    dz = dev(z, dtype)
+    loss = zeros(rows)
+    K.lpk_softmax_ce(dtype, dz, n, dev(y, 0), loss, rows, n, 1, 1.0 / rows)
+    z64 = z.astype(np.float64)
+    ref_loss, p = ops.softmax_ce_fwd(z64, y)
+    rows_ref = np.log(np.exp(z64 - z64.max(-1, keepdims=True)).sum(-1)) + z64.max(-1) - z64[np.arange(rows), y]
+    assert np.abs(host(loss) - rows_ref).max() <= 2e-5 * max(1, np.abs(rows_ref).max())
+    assert relerr(host(dz), ops.softmax_ce_bwd(p, y)) <= (4e-3 if dtype else 2e-5)
+
+
+@pytest.mark.parametrize("kind", [0, 1, 2])
+def test_optimizer_kernel(K, kind):
+    """Identical fp32 inputs, non-zero moments, t > 1."""
+    import torch
+    import lp_inputs as LI
+    from oracle import local as OL
+    rng = np.random.default_rng(kind)
+    n = 4 * 1237
+    p, g = rng.standard_normal(n).astype(np.float32), rng.standard_normal(n).astype(np.float32)
+    m = (0.1 * rng.standard_normal(n)).astype(np.float32)
+    v = (0.01 * rng.random(n)).astype(np.float32)
+    dp, dg, dm, dv = dev(p, 0), dev(g, 0), dev(m, 0), dev(v, 0)
+    low = torch.zeros(n, device="cuda", dtype=torch.bfloat16)
+    K.lpk_optimizer(kind, 1e-2, 0.9, 0.9, 0.999, 1e-8, 0.0, 7, 0.5, dp, dg, dm, dv, low, n)
+    opt = LI.OptCfg(("sgd", "sgdm", "adam")[kind], lr=1e-2)
+    st = {"m": {"p": m.astype(np.float64)}, "v": {"p": v.astype(np.float64)}}
+    ref = OL.optimizer_update(opt, p.astype(np.float64), 0.5 * g.astype(np.float64), st, "p", 7)
+    assert relerr(host(dp), ref) <= 1e-6
+    assert np.abs(host(dp) - ref).max() <= 1e-6
+    if kind >= 1:
+        assert relerr(host(dm), st["m"]["p"]) <= 1e-6
+    if kind == 2:
+        assert relerr(host(dv), st["v"]["p"]) <= 1e-6
+    np.testing.assert_array_equal(host(low), ops.bf16_round(host(dp).astype(np.float32)))
+
+
+def test_embed_bwd_repeated_tokens(K):
+    import torch
+    rng = np.random.default_rng(0)
+    T, V, d = 700, 50, 136
+    ids = rng.integers(0, V, T).astype(np.int32)
+    ids[:300] = 3
+    dh = rnd(rng, (T, d), 1)
+    demb = ones(V, d)
+    K.lpk_embed_bwd(1, dev(ids, 0), dev(dh, 1), demb, T, V, d, 1)
+    ref = ops.embed_bwd(ids, V, dh.astype(np.float64)) + 1
+    assert relerr(host(demb), ref) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("N,H,C,O,R,stride,pad", [(3, 9, 5, 7, 3, 1, 1), (2, 8, 16, 24, 3, 2, 1), (2, 8, 16, 8, 1, 2, 0),
+                                                  (4, 12, 3, 64, 3, 1, 1)])
+def test_conv_and_batchnorm(K, dtype, N, H, C, O, R, stride, pad):
+    import torch
+    rng = np.random.default_rng(H)
+    x = rnd(rng, (N, H, H, C), dtype)
+    w = rnd(rng, (O, R, R, C), dtype, 0.3)
+    P = (H + 2 * pad - R) // stride + 1
+    tdt = torch.bfloat16 if dtype else torch.float32
+    out = torch.zeros(N, P, P, O, device="cuda", dtype=tdt)
+    K.lpk_conv_fwd(dtype, dev(x, dtype), dev(w, dtype), out, N, H, H, C, O, R, stride, pad)
+    ref = ops.conv2d_fwd(x.astype(np.float64), w.astype(np.float64), stride, pad)
+    tol = 4e-3 if dtype else 2e-6
+    assert relerr(host(out), ref) <= tol
+    dout = rnd(rng, (N, P, P, O), dtype)
+    dx = torch.zeros(N, H, H, C, device="cuda", dtype=tdt)
+    dw = zeros(O, R, R, C)
+    K.lpk_conv_bwd_data(dtype, dev(dout, dtype), dev(w, dtype), dx, N, H, H, C, O, R, stride, pad)
+    K.lpk_conv_bwd_weight(dtype, dev(dout, dtype), dev(x, dtype), dw, N, H, H, C, O, R, stride, pad)
+    rdx, rdw = ops.conv2d_bwd(x.astype(np.float64), w.astype(np.float64), stride, pad, dout.astype(np.float64))
+    assert relerr(host(dx), rdx) <= tol
+    assert relerr(host(dw), rdw) <= 2e-6
+    # batchnorm + residual + relu on the conv output
+    rows = N * P * P
+    z = host(out).astype(np.float32)
+    g = rng.standard_normal(O).astype(np.float32); b = rng.standard_normal(O).astype(np.float32)
+    res = rnd(rng, (N, P, P, O), dtype)
+    y = torch.zeros_like(out); mean = zeros(O); rstd = zeros(O)
+    scratch = zeros((2 * ((rows + 255) // 256) + 2) * O + 64)
+    K.lpk_batchnorm_fwd(dtype, out, dev(g, 0), dev(b, 0), dev(res, dtype), y, mean, rstd, rows, O, 1, scratch)
+    ry, cache = ops.batchnorm_fwd(z.astype(np.float64), g.astype(np.float64), b.astype(np.float64))
+    ry = np.maximum(ry + res, 0)
+    assert relerr(host(y), ry) <= tol
+    dy = rnd(rng, (N, P, P, O), dtype)
+    dz = torch.zeros_like(out); dres = torch.zeros_like(out)
+    dg = zeros(O); db = zeros(O)
+    K.lpk_batchnorm_bwd(dtype, dev(dy, dtype), y, out, mean, rstd, dev(g, 0), dz, dres, dg, db, rows, O, 1, 0, scratch)
+    dy_eff = dy.astype(np.float64) * (host(y) > 0)
+    rdz, rdg, rdb = ops.batchnorm_bwd(cache, g.astype(np.float64), dy_eff)
+    assert relerr(host(dz), rdz) <= (6e-3 if dtype else 2e-5)
+    assert relerr(host(dres), dy_eff) <= 1e-7
+    assert relerr(host(dg), rdg) <= 2e-5 and relerr(host(db), rdb) <= 2e-5

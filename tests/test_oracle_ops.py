@@ -10,12 +10,11 @@ from oracle import ops
 from oracle import local as OLoc
 import lp_inputs as LI
 
-torch.set_default_dtype(torch.float64)
 RNG = np.random.default_rng(11)
 
 
 def T(a, grad=False):
-    t = torch.tensor(np.asarray(a, dtype=np.float64))
+    t = torch.tensor(np.asarray(a, dtype=np.float64), dtype=torch.float64)
     t.requires_grad_(grad)
     return t
 
