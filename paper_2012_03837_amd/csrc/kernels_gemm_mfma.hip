@@ -1,8 +1,17 @@
-// bf16 GEMM on the CDNA4 matrix cores: v_mfma_f32_32x32x16_bf16, fp32 accumulation, operands staged
-// through LDS with the reduction index contiguous.  Block tile 128x128x32, four 64-wide wavefronts
-// in a 2x2 arrangement, each owning a 64x64 sub-tile (2x2 MFMA tiles).  Either operand may be stored
-// with the reduction index as its slow dimension (dgrad / wgrad forms); such tiles are transposed on
-// their way into LDS.
+// bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
+//
+// Block tile 256(m) x 128(n) x 32(k), 256 threads = four 64-wide wavefronts in a 2x2 arrangement, each
+// owning 128 x 64 (4 x 2 MFMA tiles, 128 accumulator registers), two blocks per CU.  Operand tiles go
+// global -> registers -> LDS (double buffered, one barrier per k-tile).  An operand stored with the
+// reduction index contiguous ("kc": forward activations and [out,in] weights) sits in LDS as
+// [row][k] and is read with 16-byte ds_read; one stored with the reduction index as the slow
+// dimension (dgrad weights, both wgrad operands) sits as [k][row], exactly as in memory, and is read
+// with the gfx950 transposing LDS read (ds_read_b64_tr_b16), so nothing is ever transposed by the
+// vector ALU.  The MFMA takes the n-side fragment as its first operand, which leaves each lane with
+// runs of 8 consecutive n for one m: the fused epilogue (bias, activation, saved pre-activation,
+// activation derivative, residual, accumulate) reads and writes 16 bytes per lane.
+// Blocks are renumbered so that each XCD (blocks are dealt round-robin to the 8 XCDs) walks a
+// compact group of tiles and re-uses its own L2.
 #include <stdlib.h>
 #include "common.h"
 #include "gemm_common.h"
@@ -11,118 +20,275 @@ namespace lp {
 
 hipError_t gemm_plain(const OpCtx& c, const GemmArgs& g);
 
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int LDK = BK + 8;   // padded LDS row (elements); 80 bytes keeps 16-byte alignment
+namespace {
 
-struct TileSrc { const bf16_t* p; int64_t ld; int kc; int rows; int vec; };
+constexpr int BM = 256, BN = 128, BK = 32;
+constexpr int KC_LD = BK + 8;        // [row][k] tiles: 80-byte rows
+constexpr int TA_LD = BM + 16;       // [k][row] tiles: padded rows
+constexpr int TB_LD = BN + 16;
+constexpr int A_ELEMS = BM * KC_LD > BK * TA_LD ? BM * KC_LD : BK * TA_LD;
+constexpr int B_ELEMS = BN * KC_LD > BK * TB_LD ? BN * KC_LD : BK * TB_LD;
 
-// Fetch the two 8-element chunks this thread stages for one operand tile.
-// kc:  tile is [128 rows][32 k]; chunk c -> row c/4, k-chunk c%4 (8 consecutive k).
-// !kc: tile is [32 k][128 rows] in memory; chunk c -> k c/16, row-chunk c%16 (8 consecutive rows).
-__device__ __forceinline__ void fetch_chunks(const TileSrc& s, int r0, int k0, int K, bf16x8 v[2]) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    int c = threadIdx.x + 256 * i;
-    bf16x8 val;
-    if (s.kc) {
-      int row = r0 + c / 4, k = k0 + (c % 4) * 8;
-      if (s.vec && row < s.rows && k + 8 <= K) {
-        val = *reinterpret_cast<const bf16x8*>(s.p + (size_t)row * s.ld + k);
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          val[j] = (row < s.rows && k + j < K) ? s.p[(size_t)row * s.ld + k + j] : (bf16_t)0.f;
-      }
-    } else {
-      int k = k0 + c / 16, row = r0 + (c % 16) * 8;
-      if (s.vec && k < K && row + 8 <= s.rows) {
-        val = *reinterpret_cast<const bf16x8*>(s.p + (size_t)k * s.ld + row);
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          val[j] = (k < K && row + j < s.rows) ? s.p[(size_t)k * s.ld + row + j] : (bf16_t)0.f;
-      }
-    }
-    v[i] = val;
-  }
-}
-__device__ __forceinline__ void stage_chunks(int kc, bf16_t (*sm)[LDK], const bf16x8 v[2]) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    int c = threadIdx.x + 256 * i;
-    if (kc) {
-      *reinterpret_cast<bf16x8*>(&sm[c / 4][(c % 4) * 8]) = v[i];
-    } else {
-      int k = c / 16, row = (c % 16) * 8;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) sm[row + j][k] = v[i][j];
-    }
-  }
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+struct Operand { const bf16_t* p; int64_t ld; int rows; };
+
+// MFMA row i of the n-side fragment holds tile column 16*(g/2) + 8*h + 4*(g%2) + j, i = 8g + 4h + j, so
+// that accumulator values 0..7 / 8..15 of lane-half h are columns 8h..8h+7 / 16+8h..16+8h+7.
+__device__ __forceinline__ int nmap(int i) {
+  int g = i >> 3, h = (i >> 2) & 1, j = i & 3;
+  return 16 * (g >> 1) + 8 * h + 4 * (g & 1) + j;
 }
 
-__global__ void __launch_bounds__(256) k_gemm_mfma(TileSrc A, TileSrc B, Epilogue e, int M, int N, int K) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[BM][LDK];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[BN][LDK];
+// ---- global -> registers ------------------------------------------------------------------------
+// kc tile [ROWS][32]: ROWS*4 chunks of 8 k; thread takes chunks tid + 256*i.
+template <int ROWS>
+__device__ __forceinline__ void fetch_kc(const Operand& o, int r0, int k0, int K, bf16x8* v) {
+#pragma unroll
+  for (int i = 0; i < ROWS / 64; ++i) {
+    int c = threadIdx.x + 256 * i;
+    int row = r0 + (c >> 2), k = k0 + (c & 3) * 8;
+    row = row < o.rows ? row : o.rows - 1;
+    bf16x8 t = *reinterpret_cast<const bf16x8*>(o.p + (size_t)row * o.ld + (k < K ? k : 0));
+    if (k >= K) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t[e] = (bf16_t)0.f;
+    }
+    v[i] = t;
+  }
+}
+// transposed tile, memory [32 k][ROWS]: 32*ROWS/8 chunks of 8 rows; thread takes chunks tid + 256*i.
+template <int ROWS>
+__device__ __forceinline__ void fetch_t(const Operand& o, int r0, int k0, int K, bf16x8* v) {
+  constexpr int CPR = ROWS / 8;   // chunks per k-row
+#pragma unroll
+  for (int i = 0; i < ROWS / 64; ++i) {
+    int c = threadIdx.x + 256 * i;
+    int k = k0 + c / CPR, row = r0 + (c % CPR) * 8;
+    row = row + 8 <= o.rows ? row : o.rows - 8;
+    bf16x8 t = *reinterpret_cast<const bf16x8*>(o.p + (size_t)(k < K ? k : 0) * o.ld + row);
+    if (k >= K) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t[e] = (bf16_t)0.f;
+    }
+    v[i] = t;
+  }
+}
+// ---- registers -> LDS ---------------------------------------------------------------------------
+template <int ROWS>
+__device__ __forceinline__ void stage_kc(bf16_t* sm, const bf16x8* v) {
+#pragma unroll
+  for (int i = 0; i < ROWS / 64; ++i) {
+    int c = threadIdx.x + 256 * i;
+    *reinterpret_cast<bf16x8*>(sm + (c >> 2) * KC_LD + (c & 3) * 8) = v[i];
+  }
+}
+template <int ROWS, int LD>
+__device__ __forceinline__ void stage_t(bf16_t* sm, const bf16x8* v) {
+  constexpr int CPR = ROWS / 8;
+#pragma unroll
+  for (int i = 0; i < ROWS / 64; ++i) {
+    int c = threadIdx.x + 256 * i;
+    *reinterpret_cast<bf16x8*>(sm + (c / CPR) * LD + (c % CPR) * 8) = v[i];
+  }
+}
+// ---- LDS -> MFMA fragments ----------------------------------------------------------------------
+// kc: lane reads 8 consecutive k of its row.
+__device__ __forceinline__ bf16x8 frag_kc(const bf16_t* sm, int row, int ks, int lane) {
+  return *reinterpret_cast<const bf16x8*>(sm + row * KC_LD + ks + 8 * (lane >> 5));
+}
+// transposed: two ds_read_b64_tr_b16.  In a 16-lane group, lane s supplies the address of 4 consecutive
+// rows at k = kbase + s/4, row chunk s%4; lane j = 4c + e receives rows chunk c element e for k = kbase..+3.
+// `rowbase` is the tile row of chunk (lane%4) for this lane's 16-lane group.
+template <int LD>
+__device__ __forceinline__ bf16x8 frag_t(const bf16_t* sm, int rowbase, int ks, int lane) {
+  int kb = ks + 8 * (lane >> 5) + ((lane & 15) >> 2);
+  const bf16_t* p = sm + kb * LD + rowbase;
+  bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p));
+  bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 4 * LD));
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { r[e] = lo[e]; r[4 + e] = hi[e]; }
+  return r;
+}
+
+template <bool A_KC, bool B_KC>
+__global__ void __launch_bounds__(256, 2) k_gemm_mfma(Operand A, Operand B, Epilogue e, int M, int N, int K,
+                                                      int tiles_m, int tiles_n) {
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][A_ELEMS];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][B_ELEMS];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  f32x16 acc[2][2];
+  // XCD-aware renumbering, then column-major groups of 8 tile rows
+  int pid = blockIdx.x;
+  {
+    const int nb = tiles_m * tiles_n, per = nb / 8;
+    if (pid < per * 8) pid = (pid & 7) * per + (pid >> 3);
+    const int GROUP = 8;
+    int width = GROUP * tiles_n, gid = pid / width;
+    int first = gid * GROUP, gs = tiles_m - first < GROUP ? tiles_m - first : GROUP;
+    int tm = first + (pid % width) % gs, tn = (pid % width) / gs;
+    pid = tm * tiles_n + tn;
+  }
+  const int m0 = (pid / tiles_n) * BM, n0 = (pid % tiles_n) * BN;
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 64;
+
+  f32x16 acc[2][4];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  bf16x8 ra[2], rb[2];
-  fetch_chunks(A, m0, 0, K, ra);
-  fetch_chunks(B, n0, 0, K, rb);
-  const int lr = lane & 31, lk = (lane >> 5) * 8;
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    stage_chunks(A.kc, As, ra);
-    stage_chunks(B.kc, Bs, rb);
-    __syncthreads();
-    if (k0 + BK < K) {
-      fetch_chunks(A, m0, k0 + BK, K, ra);
-      fetch_chunks(B, n0, k0 + BK, K, rb);
-    }
+  bf16x8 ra[BM / 64], rb[BN / 64];
+  auto fetch = [&](int k0) {
+    if (A_KC) fetch_kc<BM>(A, m0, k0, K, ra); else fetch_t<BM>(A, m0, k0, K, ra);
+    if (B_KC) fetch_kc<BN>(B, n0, k0, K, rb); else fetch_t<BN>(B, n0, k0, K, rb);
+  };
+  auto stage = [&](int buf) {
+    if (A_KC) stage_kc<BM>(As[buf], ra); else stage_t<BM, TA_LD>(As[buf], ra);
+    if (B_KC) stage_kc<BN>(Bs[buf], rb); else stage_t<BN, TB_LD>(Bs[buf], rb);
+  };
+  // fragment addressing that does not depend on k
+  const int li = lane & 31;
+  const int n_row = nmap(li);                                // kc: tile column read by this lane
+  const int c4 = lane & 3, half16 = (lane >> 4) & 1;         // transposed: chunk and 16-row half of the group
+  // n-side chunk c of half16: MFMA rows 16*half16 + 4c .. +3  ->  columns nmap(16*half16 + 4c) .. +3
+  const int n_rowbase_t = nmap(16 * half16 + 4 * c4);
+  const int m_rowbase_t = 16 * half16 + 4 * c4;
+
+  const int nt = (K + BK - 1) / BK;
+  fetch(0);
+  stage(0);
+  __syncthreads();
+  if (nt > 1) fetch(BK);
+  for (int t = 0; t < nt; ++t) {
+    const int cur = t & 1;
+    if (t + 1 < nt) stage(cur ^ 1);
+    if (t + 2 < nt) fetch((t + 2) * BK);
+    const bf16_t* as = As[cur];
+    const bf16_t* bs = Bs[cur];
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
-      bf16x8 fa[2], fb[2];
+      bf16x8 fn[2], fm[4];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        fa[i] = *reinterpret_cast<const bf16x8*>(&As[wm + i * 32 + lr][ks + lk]);
-        fb[i] = *reinterpret_cast<const bf16x8*>(&Bs[wn + i * 32 + lr][ks + lk]);
-      }
+      for (int i = 0; i < 2; ++i)
+        fn[i] = B_KC ? frag_kc(bs, wn + 32 * i + n_row, ks, lane) : frag_t<TB_LD>(bs, wn + 32 * i + n_rowbase_t, ks, lane);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        fm[j] = A_KC ? frag_kc(as, wm + 32 * j + li, ks, lane) : frag_t<TA_LD>(as, wm + 32 * j + m_rowbase_t, ks, lane);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
     }
     __syncthreads();
   }
-  // accumulator layout of the 32x32 MFMA: value v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32
+
+  // epilogue: lane = row m, accumulator values 8q..8q+7 = columns 16q + 8*(lane/32) .. +7
+  const int hf = lane >> 5;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int j = 0; j < 4; ++j) {
+    const int m = m0 + wm + 32 * j + li;
+    if (m >= M) continue;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        int m = m0 + wm + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-        int n = n0 + wn + j * 32 + lr;
-        if (m < M && n < N) epilogue_store<bf16_t>(e, m, n, acc[i][j][v]);
+      for (int q = 0; q < 2; ++q) {
+        const int n = n0 + wn + 32 * i + 16 * q + 8 * hf;
+        if (n >= N) continue;
+        float v[8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) v[x] = acc[i][j][8 * q + x];
+        if (e.bias) {
+          f32x4 b0 = *reinterpret_cast<const f32x4*>(e.bias + n), b1 = *reinterpret_cast<const f32x4*>(e.bias + n + 4);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) { v[x] += b0[x]; v[4 + x] += b1[x]; }
+        }
+        if (e.pre) {
+          bf16x8 w;
+#pragma unroll
+          for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
+          *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16_t*>(e.pre) + (size_t)m * e.ldc + n) = w;
+        }
+        if (e.act == ACT_RELU) {
+#pragma unroll
+          for (int x = 0; x < 8; ++x) v[x] = fmaxf(v[x], 0.f);
+        } else if (e.act == ACT_GELU) {
+#pragma unroll
+          for (int x = 0; x < 8; ++x) v[x] = gelu_f(v[x]);
+        }
+        if (e.dact != ACT_NONE) {
+          bf16x8 s = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(e.dact_src) + (size_t)m * e.ldd + n);
+          if (e.dact == ACT_RELU) {
+#pragma unroll
+            for (int x = 0; x < 8; ++x) v[x] = (float)s[x] > 0.f ? v[x] : 0.f;
+          } else {
+#pragma unroll
+            for (int x = 0; x < 8; ++x) v[x] *= dgelu_f((float)s[x]);
+          }
+        }
+        if (e.res) {
+          bf16x8 r = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(e.res) + (size_t)m * e.ldr + n);
+#pragma unroll
+          for (int x = 0; x < 8; ++x) v[x] += (float)r[x];
+        }
+        if (e.c_f32) {
+          float* cp = reinterpret_cast<float*>(e.C) + (size_t)m * e.ldc + n;
+          if (e.accumulate) {
+            f32x4 c0 = *reinterpret_cast<const f32x4*>(cp), c1 = *reinterpret_cast<const f32x4*>(cp + 4);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) { v[x] += c0[x]; v[4 + x] += c1[x]; }
+          }
+          f32x4 o0 = {v[0], v[1], v[2], v[3]}, o1 = {v[4], v[5], v[6], v[7]};
+          *reinterpret_cast<f32x4*>(cp) = o0;
+          *reinterpret_cast<f32x4*>(cp + 4) = o1;
+        } else {
+          bf16_t* cp = reinterpret_cast<bf16_t*>(e.C) + (size_t)m * e.ldc + n;
+          if (e.accumulate) {
+            bf16x8 c0 = *reinterpret_cast<const bf16x8*>(cp);
+#pragma unroll
+            for (int x = 0; x < 8; ++x) v[x] += (float)c0[x];
+          }
+          bf16x8 w;
+#pragma unroll
+          for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
+          *reinterpret_cast<bf16x8*>(cp) = w;
+        }
       }
+  }
 }
 
-static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+// Shapes the MFMA kernel takes: every vector access must be 16-byte aligned and never straddle an edge.
+bool fast_ok(const GemmArgs& g) {
+  if (g.M < 1 || g.N < 8 || g.K < 1) return false;
+  if (g.N % 8 || g.K % 8 || g.lda % 8 || g.ldb % 8 || g.ldc % 8) return false;
+  if (!g.a_kc && (g.M % 8 || g.M < 8)) return false;
+  if (!aligned16(g.A) || !aligned16(g.B) || !aligned16(g.C)) return false;
+  if (g.bias && !aligned16(g.bias)) return false;
+  if (g.pre && !aligned16(g.pre)) return false;
+  if (g.dact_src && (!aligned16(g.dact_src) || g.ldd % 8)) return false;
+  if (g.res && (!aligned16(g.res) || g.ldr % 8)) return false;
+  return true;
+}
+
+}  // namespace
 
 hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
-  TileSrc A{(const bf16_t*)g.A, g.lda, g.a_kc, g.M, (aligned16(g.A) && g.lda % 8 == 0) ? 1 : 0};
-  TileSrc B{(const bf16_t*)g.B, g.ldb, g.b_kc, g.N, (aligned16(g.B) && g.ldb % 8 == 0) ? 1 : 0};
-  dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM);
-  k_gemm_mfma<<<grid, 256, 0, c.stream>>>(A, B, make_epilogue(g), g.M, g.N, g.K);
+  Operand A{(const bf16_t*)g.A, g.lda, g.M}, B{(const bf16_t*)g.B, g.ldb, g.N};
+  int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
+  dim3 grid(tm * tn);
+  Epilogue e = make_epilogue(g);
+#define LP_GEMM(AK, BK_) k_gemm_mfma<AK, BK_><<<grid, 256, 0, c.stream>>>(A, B, e, g.M, g.N, g.K, tm, tn)
+  if (g.a_kc && g.b_kc) LP_GEMM(true, true);
+  else if (g.a_kc && !g.b_kc) LP_GEMM(true, false);
+  else if (!g.a_kc && g.b_kc) LP_GEMM(false, true);
+  else LP_GEMM(false, false);
+#undef LP_GEMM
   return hipGetLastError();
 }
 
@@ -134,7 +300,7 @@ static int use_plain() {
 
 hipError_t op_gemm(const OpCtx& c, const GemmArgs& g) {
   ProfScope prof_(c, KC_GEMM, 2.0 * g.M * g.N * g.K);
-  if (c.dt == BF16 && !use_plain()) return gemm_mfma(c, g);
+  if (c.dt == BF16 && !use_plain() && fast_ok(g)) return gemm_mfma(c, g);
   return gemm_plain(c, g);
 }
 
