@@ -80,6 +80,8 @@ struct OpCtx {
   float* partial;      // fp32 scratch for two-stage reductions
   size_t partial_elems;
   Profiler* prof = nullptr;
+  float* splitk_ws = nullptr;   // fp32 workspace for split-K partial sums (may be null: no split-K)
+  size_t splitk_elems = 0;
 };
 
 // RAII bracket: records an event pair around the launches of one op when profiling is on.

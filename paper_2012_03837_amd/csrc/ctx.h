@@ -89,6 +89,7 @@ struct lp_ctx {
   float* mom = nullptr; float* var = nullptr;
   float* grads = nullptr;
   float* partial = nullptr; size_t partial_elems = 0;
+  float* splitk_ws = nullptr; size_t splitk_elems = 0;
   float* loss_rows = nullptr;
   float* pe = nullptr;
   void* h0 = nullptr;                    // embedded input of layer 1
@@ -109,7 +110,7 @@ struct lp_ctx {
   mutable lp::Profiler prof;
   lp::OpCtx op() const {
     lp::OpCtx c; c.stream = stream; c.dt = dt; c.partial = partial; c.partial_elems = partial_elems;
-    c.prof = &prof; return c;
+    c.prof = &prof; c.splitk_ws = splitk_ws; c.splitk_elems = splitk_elems; return c;
   }
   float* P32(int ti) const { return master + tensors[ti].off; }
   float* G32(int ti) const { return grads + tensors[ti].off; }

@@ -5,6 +5,15 @@
 
 namespace lp {
 
+bool ln_fast_ok(const OpCtx& c, const void* a, const void* b, const void* cc, const void* dd, int d);
+hipError_t ln_fwd_fast(const OpCtx& c, const void* x, const float* g, const float* b, void* y, float* mean, float* rstd,
+                       int rows, int d);
+hipError_t ln_bwd_fast(const OpCtx& c, const void* dy, const void* x, const float* mean, const float* rstd,
+                       const float* g, const void* add, void* dx, int rows, int d, int* nblk_out);
+bool ce_fast_ok(const OpCtx& c, const void* z, int64_t ld, int n);
+hipError_t ce_fast(const OpCtx& c, void* z, int64_t ld, const int32_t* y, float* loss_rows, int rows, int n,
+                   int write_grad, float inv_rows);
+
 #define LP_LAUNCH_CHECK() hipGetLastError()
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -177,6 +186,7 @@ hipError_t op_layernorm_fwd(const OpCtx& c, const void* x, const float* g, const
                             float* rstd, int rows, int d) {
   ProfScope prof_(c, KC_LAYERNORM);
   if (rows == 0) return hipSuccess;
+  if (ln_fast_ok(c, x, y, nullptr, nullptr, d)) return ln_fwd_fast(c, x, g, b, y, mean, rstd, rows, d);
   int blocks = (rows + 3) / 4;
   if (c.dt == BF16) k_ln_fwd<bf16_t><<<blocks, 256, 0, c.stream>>>((const bf16_t*)x, g, b, (bf16_t*)y, mean, rstd, rows, d);
   else k_ln_fwd<float><<<blocks, 256, 0, c.stream>>>((const float*)x, g, b, (float*)y, mean, rstd, rows, d);
@@ -235,19 +245,35 @@ __global__ void k_ln_bwd(const T* dy, const T* x, const float* mean, const float
     partial[(size_t)(nblk + blockIdx.x) * d + j] = bsum;
   }
 }
-// out[j] (+)= sum_b partial[b, j], in block order.
+// out[j] (+)= sum_b partial[b, j].  Block = 64 columns x 4 row groups; group q adds rows q, q+4, ... in
+// order and the four group sums are then added in order (a fixed tree).
 __global__ void k_reduce_partials(const float* partial, int nblk, int n, float* out, int accumulate) {
-  int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= n) return;
+  __shared__ float sh[4][64];
+  int lc = threadIdx.x & 63, q = threadIdx.x >> 6;
+  int j = blockIdx.x * 64 + lc;
   float a = 0.f;
-  for (int b = 0; b < nblk; ++b) a += partial[(size_t)b * n + j];
-  out[j] = accumulate ? out[j] + a : a;
+  if (j < n)
+    for (int b = q; b < nblk; b += 4) a += partial[(size_t)b * n + j];
+  sh[q][lc] = a;
+  __syncthreads();
+  if (q == 0 && j < n) {
+    float t = sh[0][lc] + sh[1][lc] + sh[2][lc] + sh[3][lc];
+    out[j] = accumulate ? out[j] + t : t;
+  }
 }
 hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const float* mean, const float* rstd,
                             const float* g, const void* add, void* dx, float* dg, float* db, int rows, int d,
                             int accumulate) {
   ProfScope prof_(c, KC_LAYERNORM);
   if (rows == 0) return hipSuccess;
+  if (ln_fast_ok(c, dy, x, add, dx, d)) {
+    int nb = 0;
+    hipError_t e = ln_bwd_fast(c, dy, x, mean, rstd, g, add, dx, rows, d, &nb);
+    if (e != hipSuccess) return e;
+    k_reduce_partials<<<(d + 63) / 64, 256, 0, c.stream>>>(c.partial, nb, d, dg, accumulate);
+    k_reduce_partials<<<(d + 63) / 64, 256, 0, c.stream>>>(c.partial + (size_t)nb * d, nb, d, db, accumulate);
+    return LP_LAUNCH_CHECK();
+  }
   int nblk = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
   if ((size_t)nblk * d * 2 > c.partial_elems) return hipErrorInvalidValue;
   size_t shm = (size_t)8 * d * sizeof(float);
@@ -259,8 +285,8 @@ hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const
                                                   (const float*)add, (float*)dx, c.partial, rows, d);
   hipError_t e = LP_LAUNCH_CHECK();
   if (e != hipSuccess) return e;
-  k_reduce_partials<<<(d + 255) / 256, 256, 0, c.stream>>>(c.partial, nblk, d, dg, accumulate);
-  k_reduce_partials<<<(d + 255) / 256, 256, 0, c.stream>>>(c.partial + (size_t)nblk * d, nblk, d, db, accumulate);
+  k_reduce_partials<<<(d + 63) / 64, 256, 0, c.stream>>>(c.partial, nblk, d, dg, accumulate);
+  k_reduce_partials<<<(d + 63) / 64, 256, 0, c.stream>>>(c.partial + (size_t)nblk * d, nblk, d, db, accumulate);
   return LP_LAUNCH_CHECK();
 }
 
@@ -291,7 +317,7 @@ hipError_t op_colsum(const OpCtx& c, const void* dy, int64_t ld, float* out, int
   dim3 grid((n + 63) / 64, nslab);
   if (c.dt == BF16) k_colsum_partial<bf16_t><<<grid, 256, 0, c.stream>>>((const bf16_t*)dy, ld, c.partial, rows, n);
   else k_colsum_partial<float><<<grid, 256, 0, c.stream>>>((const float*)dy, ld, c.partial, rows, n);
-  k_reduce_partials<<<(n + 255) / 256, 256, 0, c.stream>>>(c.partial, nslab, n, out, accumulate);
+  k_reduce_partials<<<(n + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, n, out, accumulate);
   return LP_LAUNCH_CHECK();
 }
 
@@ -330,6 +356,7 @@ hipError_t op_softmax_ce(const OpCtx& c, void* z, int64_t ld, const int32_t* y, 
                          int write_grad, float inv_rows) {
   ProfScope prof_(c, KC_SOFTMAX_CE);
   if (rows == 0) return hipSuccess;
+  if (ce_fast_ok(c, z, ld, n)) return ce_fast(c, z, ld, y, loss_rows, rows, n, write_grad, inv_rows);
   if (c.dt == BF16) k_softmax_ce<bf16_t><<<rows, 256, 0, c.stream>>>((bf16_t*)z, ld, y, loss_rows, n, write_grad, inv_rows);
   else k_softmax_ce<float><<<rows, 256, 0, c.stream>>>((float*)z, ld, y, loss_rows, n, write_grad, inv_rows);
   return LP_LAUNCH_CHECK();

@@ -22,11 +22,9 @@ hipError_t gemm_plain(const OpCtx& c, const GemmArgs& g);
 
 namespace {
 
-constexpr int BM = 256, BN = 128, BK = 32;
+constexpr int BN = 128, BK = 32;
 constexpr int KC_LD = BK + 8;        // [row][k] tiles: 80-byte rows
-constexpr int TA_LD = BM + 16;       // [k][row] tiles: padded rows
-constexpr int TB_LD = BN + 16;
-constexpr int A_ELEMS = BM * KC_LD > BK * TA_LD ? BM * KC_LD : BK * TA_LD;
+constexpr int TB_LD = BN + 16;       // [k][row] tiles: padded rows
 constexpr int B_ELEMS = BN * KC_LD > BK * TB_LD ? BN * KC_LD : BK * TB_LD;
 
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
@@ -112,14 +110,77 @@ __device__ __forceinline__ bf16x8 frag_t(const bf16_t* sm, int rowbase, int ks, 
   return r;
 }
 
-template <bool A_KC, bool B_KC>
+// Fused epilogue on 8 consecutive columns n..n+7 of row m.
+__device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float* v) {
+  if (e.bias) {
+    f32x4 b0 = *reinterpret_cast<const f32x4*>(e.bias + n), b1 = *reinterpret_cast<const f32x4*>(e.bias + n + 4);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) { v[x] += b0[x]; v[4 + x] += b1[x]; }
+  }
+  if (e.pre) {
+    bf16x8 w;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
+    *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16_t*>(e.pre) + (size_t)m * e.ldc + n) = w;
+  }
+  if (e.act == ACT_RELU) {
+#pragma unroll
+    for (int x = 0; x < 8; ++x) v[x] = fmaxf(v[x], 0.f);
+  } else if (e.act == ACT_GELU) {
+#pragma unroll
+    for (int x = 0; x < 8; ++x) v[x] = gelu_f(v[x]);
+  }
+  if (e.dact != ACT_NONE) {
+    bf16x8 s = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(e.dact_src) + (size_t)m * e.ldd + n);
+    if (e.dact == ACT_RELU) {
+#pragma unroll
+      for (int x = 0; x < 8; ++x) v[x] = (float)s[x] > 0.f ? v[x] : 0.f;
+    } else {
+#pragma unroll
+      for (int x = 0; x < 8; ++x) v[x] *= dgelu_f((float)s[x]);
+    }
+  }
+  if (e.res) {
+    bf16x8 r = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(e.res) + (size_t)m * e.ldr + n);
+#pragma unroll
+    for (int x = 0; x < 8; ++x) v[x] += (float)r[x];
+  }
+  if (e.c_f32) {
+    float* cp = reinterpret_cast<float*>(e.C) + (size_t)m * e.ldc + n;
+    if (e.accumulate) {
+      f32x4 c0 = *reinterpret_cast<const f32x4*>(cp), c1 = *reinterpret_cast<const f32x4*>(cp + 4);
+#pragma unroll
+      for (int x = 0; x < 4; ++x) { v[x] += c0[x]; v[4 + x] += c1[x]; }
+    }
+    f32x4 o0 = {v[0], v[1], v[2], v[3]}, o1 = {v[4], v[5], v[6], v[7]};
+    *reinterpret_cast<f32x4*>(cp) = o0;
+    *reinterpret_cast<f32x4*>(cp + 4) = o1;
+  } else {
+    bf16_t* cp = reinterpret_cast<bf16_t*>(e.C) + (size_t)m * e.ldc + n;
+    if (e.accumulate) {
+      bf16x8 c0 = *reinterpret_cast<const bf16x8*>(cp);
+#pragma unroll
+      for (int x = 0; x < 8; ++x) v[x] += (float)c0[x];
+    }
+    bf16x8 w;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
+    *reinterpret_cast<bf16x8*>(cp) = w;
+  }
+}
+
+template <bool A_KC, bool B_KC, int BM>
 __global__ void __launch_bounds__(256, 2) k_gemm_mfma(Operand A, Operand B, Epilogue e, int M, int N, int K,
-                                                      int tiles_m, int tiles_n) {
+                                                      int tiles_m, int tiles_n, int splits, float* ws) {
+  constexpr int TM = BM / 64;          // 32-row MFMA tiles per wave along m
+  constexpr int TA_LD = BM + 16;
+  constexpr int A_ELEMS = BM * KC_LD > BK * TA_LD ? BM * KC_LD : BK * TA_LD;
   __shared__ __attribute__((aligned(16))) bf16_t As[2][A_ELEMS];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[2][B_ELEMS];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // XCD-aware renumbering, then column-major groups of 8 tile rows
-  int pid = blockIdx.x;
+  const int split = blockIdx.x % splits;
+  int pid = blockIdx.x / splits;
   {
     const int nb = tiles_m * tiles_n, per = nb / 8;
     if (pid < per * 8) pid = (pid & 7) * per + (pid >> 3);
@@ -130,13 +191,13 @@ __global__ void __launch_bounds__(256, 2) k_gemm_mfma(Operand A, Operand B, Epil
     pid = tm * tiles_n + tn;
   }
   const int m0 = (pid / tiles_n) * BM, n0 = (pid % tiles_n) * BN;
-  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 64;
+  const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * 64;
 
-  f32x16 acc[2][4];
+  f32x16 acc[2][TM];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < TM; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
@@ -157,30 +218,35 @@ __global__ void __launch_bounds__(256, 2) k_gemm_mfma(Operand A, Operand B, Epil
   const int n_rowbase_t = nmap(16 * half16 + 4 * c4);
   const int m_rowbase_t = 16 * half16 + 4 * c4;
 
-  const int nt = (K + BK - 1) / BK;
-  fetch(0);
-  stage(0);
+  const int nt_all = (K + BK - 1) / BK, per = (nt_all + splits - 1) / splits;
+  const int t_first = split * per;
+  const int nt = nt_all - t_first < per ? (nt_all - t_first > 0 ? nt_all - t_first : 0) : per;
+  const int kbase = t_first * BK;
+  if (nt > 0) {
+    fetch(kbase);
+    stage(0);
+  }
   __syncthreads();
-  if (nt > 1) fetch(BK);
+  if (nt > 1) fetch(kbase + BK);
   for (int t = 0; t < nt; ++t) {
     const int cur = t & 1;
     if (t + 1 < nt) stage(cur ^ 1);
-    if (t + 2 < nt) fetch((t + 2) * BK);
+    if (t + 2 < nt) fetch(kbase + (t + 2) * BK);
     const bf16_t* as = As[cur];
     const bf16_t* bs = Bs[cur];
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
-      bf16x8 fn[2], fm[4];
+      bf16x8 fn[2], fm[TM];
 #pragma unroll
       for (int i = 0; i < 2; ++i)
         fn[i] = B_KC ? frag_kc(bs, wn + 32 * i + n_row, ks, lane) : frag_t<TB_LD>(bs, wn + 32 * i + n_rowbase_t, ks, lane);
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < TM; ++j)
         fm[j] = A_KC ? frag_kc(as, wm + 32 * j + li, ks, lane) : frag_t<TA_LD>(as, wm + 32 * j + m_rowbase_t, ks, lane);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TM; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
     }
     __syncthreads();
@@ -189,7 +255,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_mfma(Operand A, Operand B, Epil
   // epilogue: lane = row m, accumulator values 8q..8q+7 = columns 16q + 8*(lane/32) .. +7
   const int hf = lane >> 5;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < TM; ++j) {
     const int m = m0 + wm + 32 * j + li;
     if (m >= M) continue;
 #pragma unroll
@@ -201,63 +267,32 @@ __global__ void __launch_bounds__(256, 2) k_gemm_mfma(Operand A, Operand B, Epil
         float v[8];
 #pragma unroll
         for (int x = 0; x < 8; ++x) v[x] = acc[i][j][8 * q + x];
-        if (e.bias) {
-          f32x4 b0 = *reinterpret_cast<const f32x4*>(e.bias + n), b1 = *reinterpret_cast<const f32x4*>(e.bias + n + 4);
-#pragma unroll
-          for (int x = 0; x < 4; ++x) { v[x] += b0[x]; v[4 + x] += b1[x]; }
-        }
-        if (e.pre) {
-          bf16x8 w;
-#pragma unroll
-          for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
-          *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16_t*>(e.pre) + (size_t)m * e.ldc + n) = w;
-        }
-        if (e.act == ACT_RELU) {
-#pragma unroll
-          for (int x = 0; x < 8; ++x) v[x] = fmaxf(v[x], 0.f);
-        } else if (e.act == ACT_GELU) {
-#pragma unroll
-          for (int x = 0; x < 8; ++x) v[x] = gelu_f(v[x]);
-        }
-        if (e.dact != ACT_NONE) {
-          bf16x8 s = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(e.dact_src) + (size_t)m * e.ldd + n);
-          if (e.dact == ACT_RELU) {
-#pragma unroll
-            for (int x = 0; x < 8; ++x) v[x] = (float)s[x] > 0.f ? v[x] : 0.f;
-          } else {
-#pragma unroll
-            for (int x = 0; x < 8; ++x) v[x] *= dgelu_f((float)s[x]);
-          }
-        }
-        if (e.res) {
-          bf16x8 r = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(e.res) + (size_t)m * e.ldr + n);
-#pragma unroll
-          for (int x = 0; x < 8; ++x) v[x] += (float)r[x];
-        }
-        if (e.c_f32) {
-          float* cp = reinterpret_cast<float*>(e.C) + (size_t)m * e.ldc + n;
-          if (e.accumulate) {
-            f32x4 c0 = *reinterpret_cast<const f32x4*>(cp), c1 = *reinterpret_cast<const f32x4*>(cp + 4);
-#pragma unroll
-            for (int x = 0; x < 4; ++x) { v[x] += c0[x]; v[4 + x] += c1[x]; }
-          }
+        if (splits > 1) {     // raw partial sums; the reduction kernel applies the epilogue
+          float* wp = ws + ((size_t)split * M + m) * N + n;
           f32x4 o0 = {v[0], v[1], v[2], v[3]}, o1 = {v[4], v[5], v[6], v[7]};
-          *reinterpret_cast<f32x4*>(cp) = o0;
-          *reinterpret_cast<f32x4*>(cp + 4) = o1;
+          *reinterpret_cast<f32x4*>(wp) = o0;
+          *reinterpret_cast<f32x4*>(wp + 4) = o1;
         } else {
-          bf16_t* cp = reinterpret_cast<bf16_t*>(e.C) + (size_t)m * e.ldc + n;
-          if (e.accumulate) {
-            bf16x8 c0 = *reinterpret_cast<const bf16x8*>(cp);
-#pragma unroll
-            for (int x = 0; x < 8; ++x) v[x] += (float)c0[x];
-          }
-          bf16x8 w;
-#pragma unroll
-          for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
-          *reinterpret_cast<bf16x8*>(cp) = w;
+          epilogue8(e, m, n, v);
         }
       }
   }
+}
+
+// Sums split-K partials in split order and applies the epilogue; one thread per 8 columns.
+__global__ void k_splitk_reduce(const float* __restrict__ ws, Epilogue e, int M, int N, int splits) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int n8 = N >> 3;
+  if (idx >= (size_t)M * n8) return;
+  int m = (int)(idx / n8), n = (int)(idx % n8) * 8;
+  float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < splits; ++s) {
+    const float* p = ws + ((size_t)s * M + m) * N + n;
+    f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) { v[x] += a[x]; v[4 + x] += b[x]; }
+  }
+  epilogue8(e, m, n, v);
 }
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
@@ -277,18 +312,42 @@ bool fast_ok(const GemmArgs& g) {
 
 }  // namespace
 
+// Tile and split choice.  Big tiles when they fill the chip; otherwise 128-row tiles, and for long
+// reductions over few tiles (weight gradients over all tokens, the head's input gradient over the
+// vocabulary) split-K with fp32 partials summed in split order by a second kernel.
 hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   Operand A{(const bf16_t*)g.A, g.lda, g.M}, B{(const bf16_t*)g.B, g.ldb, g.N};
-  int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
-  dim3 grid(tm * tn);
   Epilogue e = make_epilogue(g);
-#define LP_GEMM(AK, BK_) k_gemm_mfma<AK, BK_><<<grid, 256, 0, c.stream>>>(A, B, e, g.M, g.N, g.K, tm, tn)
-  if (g.a_kc && g.b_kc) LP_GEMM(true, true);
-  else if (g.a_kc && !g.b_kc) LP_GEMM(true, false);
-  else if (!g.a_kc && g.b_kc) LP_GEMM(false, true);
-  else LP_GEMM(false, false);
+  const int tn = (g.N + BN - 1) / BN;
+  const int tiles256 = ((g.M + 255) / 256) * tn;
+  int bm = 256, splits = 1;
+  if (tiles256 < 400) {
+    bm = 128;
+    const int tiles128 = ((g.M + 127) / 128) * tn;
+    if (tiles128 < 400 && g.K >= 2048 && c.splitk_ws) {
+      splits = (512 + tiles128 - 1) / tiles128;
+      if (splits > 8) splits = 8;
+      if (splits > g.K / 512) splits = g.K / 512;
+      while (splits > 1 && (size_t)splits * g.M * g.N > c.splitk_elems) --splits;
+      if (splits < 1) splits = 1;
+    }
+  }
+  const int tm = (g.M + bm - 1) / bm;
+  dim3 grid(tm * tn * splits);
+#define LP_GEMM(AK, BK_, BM_) \
+  k_gemm_mfma<AK, BK_, BM_><<<grid, 256, 0, c.stream>>>(A, B, e, g.M, g.N, g.K, tm, tn, splits, c.splitk_ws)
+#define LP_GEMM_BM(AK, BK_) do { if (bm == 256) LP_GEMM(AK, BK_, 256); else LP_GEMM(AK, BK_, 128); } while (0)
+  if (g.a_kc && g.b_kc) LP_GEMM_BM(true, true);
+  else if (g.a_kc && !g.b_kc) LP_GEMM_BM(true, false);
+  else if (!g.a_kc && g.b_kc) LP_GEMM_BM(false, true);
+  else LP_GEMM_BM(false, false);
+#undef LP_GEMM_BM
 #undef LP_GEMM
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess || splits == 1) return err;
+  size_t work = (size_t)g.M * (g.N / 8);
+  k_splitk_reduce<<<(unsigned)((work + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, splits);
   return hipGetLastError();
 }
 

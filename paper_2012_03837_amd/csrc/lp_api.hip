@@ -258,6 +258,10 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
   }
   c->partial_elems = partial;
   c->partial = (float*)wa.take(partial * 4);
+  if (dt == BF16) {   // split-K partial sums: at most 8 splits of fewer than 400 tiles of 128 x 128
+    c->splitk_elems = (size_t)8 * 400 * 128 * 128;
+    c->splitk_ws = (float*)wa.take(c->splitk_elems * 4);
+  }
   c->loss_rows = (float*)wa.take(max_rows * 4);
   c->feat = wa.take(max_feat * es);
   c->dfeat = wa.take(max_feat * es);

@@ -49,7 +49,8 @@ def relerr(a, ref):
                  / max(np.linalg.norm(np.asarray(ref, np.float64).ravel()), 1e-30))
 
 
-GEMM_SHAPES = [(200, 136, 72), (128, 128, 32), (1, 8, 8), (333, 257, 40), (64, 1000, 128), (600, 128, 600)]
+GEMM_SHAPES = [(200, 136, 72), (128, 128, 32), (1, 8, 8), (333, 257, 40), (64, 1000, 128), (600, 128, 600),
+               (264, 136, 4104), (520, 264, 2048)]
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
@@ -86,7 +87,14 @@ def test_gemm_layouts_and_epilogues(K, dtype, a_kc, b_kc):
             K.lpk_gemm(dtype, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out, N, 0, M, N, Kd, dact_src=dev(dsrc, dtype),
                        dact=dact, ldd=N)
             assert relerr(host(out), fn(dsrc.astype(np.float64), ref0)) <= tol_lo, (M, N, Kd, "dact", dact)
-        # (4) the MFMA and plain kernels agree on bf16
+        # (4) split-K with ordered partial sums (long reductions over few tiles)
+        if dtype == 1:
+            ws = zeros(8 * M * N)
+            o3 = zeros(M, N)
+            K.lpk_gemm(dtype, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, o3, N, 1, M, N, Kd, bias=dev(bias, 0),
+                       splitk_ws=ws)
+            assert relerr(host(o3), ref0 + bias) <= 2e-6, (M, N, Kd, "splitk")
+        # (5) the MFMA and plain kernels agree on bf16
         if dtype == 1:
             o2 = torch.zeros(M, N, device="cuda", dtype=torch.float32)
             K.lpk_gemm(dtype, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, o2, N, 1, M, N, Kd, plain=1)
