@@ -47,12 +47,7 @@ __device__ __forceinline__ void fetch_kc(const Operand& o, int r0, int k0, int K
     int c = threadIdx.x + 256 * i;
     int row = r0 + (c >> 2), k = k0 + (c & 3) * 8;
     row = row < o.rows ? row : o.rows - 1;
-    bf16x8 t = *reinterpret_cast<const bf16x8*>(o.p + (size_t)row * o.ld + (k < K ? k : 0));
-    if (k >= K) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) t[e] = (bf16_t)0.f;
-    }
-    v[i] = t;
+    v[i] = *reinterpret_cast<const bf16x8*>(o.p + (size_t)row * o.ld + (k < K ? k : 0));
   }
 }
 // transposed tile, memory [32 k][ROWS]: 32*ROWS/8 chunks of 8 rows; thread takes chunks tid + 256*i.
@@ -64,30 +59,34 @@ __device__ __forceinline__ void fetch_t(const Operand& o, int r0, int k0, int K,
     int c = threadIdx.x + 256 * i;
     int k = k0 + c / CPR, row = r0 + (c % CPR) * 8;
     row = row + 8 <= o.rows ? row : o.rows - 8;
-    bf16x8 t = *reinterpret_cast<const bf16x8*>(o.p + (size_t)(k < K ? k : 0) * o.ld + row);
-    if (k >= K) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) t[e] = (bf16_t)0.f;
-    }
-    v[i] = t;
+    v[i] = *reinterpret_cast<const bf16x8*>(o.p + (size_t)(k < K ? k : 0) * o.ld + row);
   }
 }
 // ---- registers -> LDS ---------------------------------------------------------------------------
+// Chunks whose k lies beyond K (only in the last k-tile) are zeroed here, at the point where the loaded
+// registers are first needed, so that the loads themselves stay in flight across the MFMA phase.
+__device__ __forceinline__ bf16x8 zero_if(bf16x8 t, bool z) {
+  if (z) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) t[e] = (bf16_t)0.f;
+  }
+  return t;
+}
 template <int ROWS>
-__device__ __forceinline__ void stage_kc(bf16_t* sm, const bf16x8* v) {
+__device__ __forceinline__ void stage_kc(bf16_t* sm, const bf16x8* v, int k0, int K) {
 #pragma unroll
   for (int i = 0; i < ROWS / 64; ++i) {
     int c = threadIdx.x + 256 * i;
-    *reinterpret_cast<bf16x8*>(sm + (c >> 2) * KC_LD + (c & 3) * 8) = v[i];
+    *reinterpret_cast<bf16x8*>(sm + (c >> 2) * KC_LD + (c & 3) * 8) = zero_if(v[i], k0 + (c & 3) * 8 >= K);
   }
 }
 template <int ROWS, int LD>
-__device__ __forceinline__ void stage_t(bf16_t* sm, const bf16x8* v) {
+__device__ __forceinline__ void stage_t(bf16_t* sm, const bf16x8* v, int k0, int K) {
   constexpr int CPR = ROWS / 8;
 #pragma unroll
   for (int i = 0; i < ROWS / 64; ++i) {
     int c = threadIdx.x + 256 * i;
-    *reinterpret_cast<bf16x8*>(sm + (c / CPR) * LD + (c % CPR) * 8) = v[i];
+    *reinterpret_cast<bf16x8*>(sm + (c / CPR) * LD + (c % CPR) * 8) = zero_if(v[i], k0 + c / CPR >= K);
   }
 }
 // ---- LDS -> MFMA fragments ----------------------------------------------------------------------
@@ -206,9 +205,10 @@ __global__ void __launch_bounds__(256, 2) k_gemm_mfma(Operand A, Operand B, Epil
     if (A_KC) fetch_kc<BM>(A, m0, k0, K, ra); else fetch_t<BM>(A, m0, k0, K, ra);
     if (B_KC) fetch_kc<BN>(B, n0, k0, K, rb); else fetch_t<BN>(B, n0, k0, K, rb);
   };
-  auto stage = [&](int buf) {
-    if (A_KC) stage_kc<BM>(As[buf], ra); else stage_t<BM, TA_LD>(As[buf], ra);
-    if (B_KC) stage_kc<BN>(Bs[buf], rb); else stage_t<BN, TB_LD>(Bs[buf], rb);
+  auto stage = [&](int buf, int k0) {
+    if (k0 + BK <= K) k0 = -BK;      // no chunk of this tile can reach K: the masks fold away
+    if (A_KC) stage_kc<BM>(As[buf], ra, k0, K); else stage_t<BM, TA_LD>(As[buf], ra, k0, K);
+    if (B_KC) stage_kc<BN>(Bs[buf], rb, k0, K); else stage_t<BN, TB_LD>(Bs[buf], rb, k0, K);
   };
   // fragment addressing that does not depend on k
   const int li = lane & 31;
@@ -224,13 +224,13 @@ __global__ void __launch_bounds__(256, 2) k_gemm_mfma(Operand A, Operand B, Epil
   const int kbase = t_first * BK;
   if (nt > 0) {
     fetch(kbase);
-    stage(0);
+    stage(0, kbase);
   }
   __syncthreads();
   if (nt > 1) fetch(kbase + BK);
   for (int t = 0; t < nt; ++t) {
     const int cur = t & 1;
-    if (t + 1 < nt) stage(cur ^ 1);
+    if (t + 1 < nt) stage(cur ^ 1, kbase + (t + 1) * BK);
     if (t + 2 < nt) fetch(kbase + (t + 2) * BK);
     const bf16_t* as = As[cur];
     const bf16_t* bs = Bs[cur];
