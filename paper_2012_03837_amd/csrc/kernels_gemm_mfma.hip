@@ -19,6 +19,8 @@
 namespace lp {
 
 hipError_t gemm_plain(const OpCtx& c, const GemmArgs& g);
+bool gemm_dma_ok(const GemmArgs& g);
+hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, int nwn, int splits);
 
 namespace {
 
@@ -315,36 +317,73 @@ bool fast_ok(const GemmArgs& g) {
 // Tile and split choice.  Big tiles when they fill the chip; otherwise 128-row tiles, and for long
 // reductions over few tiles (weight gradients over all tokens, the head's input gradient over the
 // vocabulary) split-K with fp32 partials summed in split order by a second kernel.
+static int kernel_choice() {   // LP_GEMM_KERNEL = auto | v2 | dma4 | dma2 (for measurements)
+  static int v = -1;
+  if (v < 0) {
+    const char* s = getenv("LP_GEMM_KERNEL");
+    v = !s ? 0 : (s[0] == 'v' ? 1 : (s[0] == 'd' && s[3] == '4' ? 2 : (s[0] == 'd' && s[3] == '2' ? 3 : 0)));
+  }
+  return v;
+}
+
+// Kernel variants and a small cost model to choose among them.  A variant is a tile shape with a
+// number of resident blocks per CU and a measured sustained rate for a full CU; the estimate is
+// rounds x (tile time + fixed fill/drain time) plus the traffic of split-K partial sums.
+struct Variant { int kind; int bm, bn; int per_cu; double flops_per_cycle_cu; double fixed_cycles; };
+static const Variant kVariants[] = {
+    {2, 256, 256, 1, 1700.0, 9000.0},   // direct-to-LDS, 8 waves, 4 stages
+    {3, 256, 128, 2, 1500.0, 7000.0},   // direct-to-LDS, 4 waves, 3 stages
+    {1, 256, 128, 2, 1300.0, 6000.0},   // register-staged, big tile
+    {0, 128, 128, 2, 1000.0, 5000.0},   // register-staged, small tile
+};
+
 hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
-  Operand A{(const bf16_t*)g.A, g.lda, g.M}, B{(const bf16_t*)g.B, g.ldb, g.N};
-  Epilogue e = make_epilogue(g);
-  const int tn = (g.N + BN - 1) / BN;
-  const int tiles256 = ((g.M + 255) / 256) * tn;
-  int bm = 256, splits = 1;
-  if (tiles256 < 400) {
-    bm = 128;
-    const int tiles128 = ((g.M + 127) / 128) * tn;
-    if (tiles128 < 400 && g.K >= 2048 && c.splitk_ws) {
-      splits = (512 + tiles128 - 1) / tiles128;
-      if (splits > 8) splits = 8;
-      if (splits > g.K / 512) splits = g.K / 512;
-      while (splits > 1 && (size_t)splits * g.M * g.N > c.splitk_elems) --splits;
-      if (splits < 1) splits = 1;
+  const int choice = kernel_choice();
+  const bool dma_ok = gemm_dma_ok(g);
+  const double flops = 2.0 * g.M * g.N * g.K;
+  double best = 1e300;
+  int best_v = 3, best_s = 1;
+  for (int vi = 0; vi < 4; ++vi) {
+    const Variant& v = kVariants[vi];
+    if ((v.kind >= 2) && !dma_ok) continue;
+    if (choice == 1 && v.kind >= 2) continue;
+    if (choice == 2 && v.kind != 2) continue;
+    if (choice == 3 && v.kind != 3) continue;
+    const long tiles = (long)((g.M + v.bm - 1) / v.bm) * ((g.N + v.bn - 1) / v.bn);
+    const long slots = 256L * v.per_cu;
+    for (int sp = 1; sp <= 8; ++sp) {
+      if (sp > 1 && (!c.splitk_ws || g.K / sp < 512 || (size_t)sp * g.M * g.N > c.splitk_elems)) break;
+      const long blocks = tiles * sp;
+      const long rounds = (blocks + slots - 1) / slots;
+      const double tile_cycles = 2.0 * v.bm * v.bn * ((double)g.K / sp) / (v.flops_per_cycle_cu / v.per_cu);
+      double cycles = rounds * (tile_cycles + v.fixed_cycles);
+      if (sp > 1) cycles += 2.0 * sp * (double)g.M * g.N * 4.0 / (5.0e12 / 2.4e9) + 12000.0;
+      if (cycles < best) { best = cycles; best_v = vi; best_s = sp; }
     }
   }
-  const int tm = (g.M + bm - 1) / bm;
-  dim3 grid(tm * tn * splits);
+  (void)flops;
+  const Variant& v = kVariants[best_v];
+  const int splits = best_s;
+  Epilogue e = make_epilogue(g);
+  hipError_t err;
+  if (v.kind >= 2) {
+    err = gemm_dma(c, g, v.kind == 2 ? 4 : 2, splits);
+  } else {
+    Operand A{(const bf16_t*)g.A, g.lda, g.M}, B{(const bf16_t*)g.B, g.ldb, g.N};
+    const int bm = v.bm, tn = (g.N + BN - 1) / BN, tm = (g.M + bm - 1) / bm;
+    dim3 grid(tm * tn * splits);
 #define LP_GEMM(AK, BK_, BM_) \
   k_gemm_mfma<AK, BK_, BM_><<<grid, 256, 0, c.stream>>>(A, B, e, g.M, g.N, g.K, tm, tn, splits, c.splitk_ws)
 #define LP_GEMM_BM(AK, BK_) do { if (bm == 256) LP_GEMM(AK, BK_, 256); else LP_GEMM(AK, BK_, 128); } while (0)
-  if (g.a_kc && g.b_kc) LP_GEMM_BM(true, true);
-  else if (g.a_kc && !g.b_kc) LP_GEMM_BM(true, false);
-  else if (!g.a_kc && g.b_kc) LP_GEMM_BM(false, true);
-  else LP_GEMM_BM(false, false);
+    if (g.a_kc && g.b_kc) LP_GEMM_BM(true, true);
+    else if (g.a_kc && !g.b_kc) LP_GEMM_BM(true, false);
+    else if (!g.a_kc && g.b_kc) LP_GEMM_BM(false, true);
+    else LP_GEMM_BM(false, false);
 #undef LP_GEMM_BM
 #undef LP_GEMM
-  hipError_t err = hipGetLastError();
+    err = hipGetLastError();
+  }
   if (err != hipSuccess || splits == 1) return err;
   size_t work = (size_t)g.M * (g.N / 8);
   k_splitk_reduce<<<(unsigned)((work + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, splits);
