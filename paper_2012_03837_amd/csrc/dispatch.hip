@@ -17,6 +17,17 @@ hipError_t attn_fwd_mfma(const OpCtx& c, const void* qkv, void* o, float* lse, i
 hipError_t attn_bwd_mfma(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout,
                          void* dqkv, float* delta, int B, int S, int H, int causal);
 
+bool conv_mfma_ok(const OpCtx& c, const ConvArgs& a, const void* p0, const void* p1, const void* p2);
+hipError_t conv_fwd_mfma(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out);
+hipError_t conv_bwd_data_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx);
+hipError_t conv_bwd_weight_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
+                                int accumulate);
+static bool plain_conv() {
+  static int v = -1;
+  if (v < 0) { const char* s = getenv("LP_PLAIN_CONV"); v = (s && s[0] == '1') ? 1 : 0; }
+  return v != 0;
+}
+
 static bool use_mfma_attn(const OpCtx& c, int dh) {
   static int plain = -1;
   if (plain < 0) { const char* s = getenv("LP_PLAIN_ATTN"); plain = (s && s[0] == '1') ? 1 : 0; }
@@ -36,15 +47,18 @@ hipError_t op_attn_bwd(const OpCtx& c, const void* qkv, const void* o, const flo
 }
 hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {
   ProfScope prof_(c, KC_CONV, 2.0 * a.N * a.P * a.Q * a.O * a.R * a.S * a.C);
+  if (!plain_conv() && conv_mfma_ok(c, a, x, w, out)) return conv_fwd_mfma(c, a, x, w, out);
   return conv_fwd_plain(c, a, x, w, out);
 }
 hipError_t op_conv_bwd_data(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx) {
   ProfScope prof_(c, KC_CONV, 2.0 * a.N * a.P * a.Q * a.O * a.R * a.S * a.C);
+  if (!plain_conv() && conv_mfma_ok(c, a, dout, w, dx)) return conv_bwd_data_mfma(c, a, dout, w, dx);
   return conv_bwd_data_plain(c, a, dout, w, dx);
 }
 hipError_t op_conv_bwd_weight(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                               int accumulate) {
   ProfScope prof_(c, KC_CONV, 2.0 * a.N * a.P * a.Q * a.O * a.R * a.S * a.C);
+  if (!plain_conv() && conv_mfma_ok(c, a, dout, x, dw)) return conv_bwd_weight_mfma(c, a, dout, x, dw, accumulate);
   return conv_bwd_weight_plain(c, a, dout, x, dw, accumulate);
 }
 

@@ -1,0 +1,216 @@
+// 3x3 / 1x1 convolutions over NHWC bf16 activations as implicit GEMMs on the matrix cores.  No im2col
+// buffer exists: the operand loaders of the MFMA tile kernel gather pixels directly (16 bytes = 8
+// consecutive channels per lane) and report zero padding / stride holes as invalid chunks, which the
+// LDS staging step zero-fills.
+//   forward : out[(n,p,q), o]  = sum_{(r,s,c)} x[n, p*st+r-pad, q*st+s-pad, c] * w[o, r, s, c]
+//   dgrad   : dx[(n,h,w), c]   = sum_{(r,s,o)} dout[n, (h+pad-r)/st, (w+pad-s)/st, o] * w[o, r, s, c]
+//   wgrad   : dw[o, (r,s,c)]   = sum_{(n,p,q)} dout[(n,p,q), o] * x[n, p*st+r-pad, q*st+s-pad, c]   (fp32, split-K)
+// Needs C % 8 == 0 and O % 8 == 0; the 3-channel stem convolution stays on the plain kernel.
+#include "common.h"
+#include "gemm_common.h"
+#include "mfma_tile.h"
+
+namespace lp {
+
+namespace {
+
+using namespace mfma;
+
+// forward A operand: rows (n,p,q), k = (r,s,c), reduction index contiguous.
+struct ConvFwdA {
+  static constexpr bool KC = true;
+  const bf16_t* x; ConvArgs a; int M;
+  int h0[4], w0[4], nb[4];
+  template <int ROWS> __device__ __forceinline__ void init(int r0) {
+#pragma unroll
+    for (int i = 0; i < ROWS / 64; ++i) {
+      int row = r0 + (threadIdx.x >> 2) + 64 * i;
+      if (row < M) {
+        int q = row % a.Q, t = row / a.Q, p = t % a.P, n = t / a.P;
+        h0[i] = p * a.stride - a.pad; w0[i] = q * a.stride - a.pad; nb[i] = n * a.H * a.W;
+      } else {
+        h0[i] = -(1 << 20); w0[i] = 0; nb[i] = 0;
+      }
+    }
+  }
+  template <int ROWS> __device__ __forceinline__ unsigned fetch(int, int k0, int K, bf16x8* v) const {
+    int kk = k0 + (threadIdx.x & 3) * 8;
+    bool kok = kk < K;
+    int rs = kok ? kk / a.C : 0, c = kok ? kk - rs * a.C : 0;
+    int r = rs / a.S, s = rs - r * a.S;
+    unsigned inv = 0;
+#pragma unroll
+    for (int i = 0; i < ROWS / 64; ++i) {
+      int h = h0[i] + r, w = w0[i] + s;
+      bool ok = kok && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
+      size_t off = ok ? ((size_t)(nb[i] + h * a.W + w) * a.C + c) : 0;
+      v[i] = *reinterpret_cast<const bf16x8*>(x + off);
+      inv |= (ok ? 0u : 1u) << i;
+    }
+    return inv;
+  }
+};
+
+// dgrad A operand: rows (n,h,w) of the input, k = (r,s,o), gathered from dout.
+struct ConvBwdA {
+  static constexpr bool KC = true;
+  const bf16_t* d; ConvArgs a; int M;
+  int hp0[4], wp0[4], nb[4];
+  template <int ROWS> __device__ __forceinline__ void init(int r0) {
+#pragma unroll
+    for (int i = 0; i < ROWS / 64; ++i) {
+      int row = r0 + (threadIdx.x >> 2) + 64 * i;
+      if (row < M) {
+        int w = row % a.W, t = row / a.W, h = t % a.H, n = t / a.H;
+        hp0[i] = h + a.pad; wp0[i] = w + a.pad; nb[i] = n * a.P * a.Q;
+      } else {
+        hp0[i] = -(1 << 20); wp0[i] = 0; nb[i] = 0;
+      }
+    }
+  }
+  template <int ROWS> __device__ __forceinline__ unsigned fetch(int, int k0, int K, bf16x8* v) const {
+    int kk = k0 + (threadIdx.x & 3) * 8;
+    bool kok = kk < K;
+    int rs = kok ? kk / a.O : 0, o = kok ? kk - rs * a.O : 0;
+    int r = rs / a.S, s = rs - r * a.S;
+    unsigned inv = 0;
+#pragma unroll
+    for (int i = 0; i < ROWS / 64; ++i) {
+      int hp = hp0[i] - r, wq = wp0[i] - s;
+      bool ok = kok && hp >= 0 && wq >= 0;
+      int p = 0, q = 0;
+      if (ok) {
+        p = hp / a.stride; q = wq / a.stride;
+        ok = (p * a.stride == hp) && (q * a.stride == wq) && p < a.P && q < a.Q;
+      }
+      size_t off = ok ? ((size_t)(nb[i] + p * a.Q + q) * a.O + o) : 0;
+      v[i] = *reinterpret_cast<const bf16x8*>(d + off);
+      inv |= (ok ? 0u : 1u) << i;
+    }
+    return inv;
+  }
+};
+
+// dgrad B operand: rows = input channel c (contiguous in memory), k = (r,s,o): w[o, r, s, c].
+struct ConvFilterT {
+  static constexpr bool KC = false;
+  const bf16_t* w; ConvArgs a;
+  template <int ROWS> __device__ __forceinline__ void init(int) {}
+  template <int ROWS> __device__ __forceinline__ unsigned fetch(int r0, int k0, int K, bf16x8* v) const {
+    constexpr int CPR = ROWS / 8;
+    int row = r0 + (threadIdx.x % CPR) * 8;
+    row = row + 8 <= a.C ? row : a.C - 8;
+#pragma unroll
+    for (int i = 0; i < ROWS / 64; ++i) {
+      int k = k0 + threadIdx.x / CPR + (256 / CPR) * i;
+      k = k < K ? k : 0;
+      int rs = k / a.O, o = k - rs * a.O;
+      v[i] = *reinterpret_cast<const bf16x8*>(w + ((size_t)o * a.R * a.S + rs) * a.C + row);
+    }
+    return 0u;
+  }
+};
+
+// wgrad B operand: rows j = (r,s,c) (c contiguous), k = output pixel (n,p,q): gathered input patches.
+struct ConvPatchT {
+  static constexpr bool KC = false;
+  const bf16_t* x; ConvArgs a; int J;
+  int r, s, c0; bool jok;
+  template <int ROWS> __device__ __forceinline__ void init(int r0) {
+    constexpr int CPR = ROWS / 8;
+    int j = r0 + (threadIdx.x % CPR) * 8;
+    jok = j < J;
+    int rs = jok ? j / a.C : 0;
+    c0 = jok ? j - rs * a.C : 0;
+    r = rs / a.S; s = rs - r * a.S;
+  }
+  template <int ROWS> __device__ __forceinline__ unsigned fetch(int, int k0, int K, bf16x8* v) const {
+    constexpr int CPR = ROWS / 8;
+    unsigned inv = 0;
+#pragma unroll
+    for (int i = 0; i < ROWS / 64; ++i) {
+      int k = k0 + threadIdx.x / CPR + (256 / CPR) * i;
+      bool ok = jok && k < K;
+      size_t off = 0;
+      if (ok) {
+        int q = k % a.Q, t = k / a.Q, p = t % a.P, n = t / a.P;
+        int h = p * a.stride + r - a.pad, w = q * a.stride + s - a.pad;
+        ok = (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
+        if (ok) off = ((size_t)(n * a.H + h) * a.W + w) * a.C + c0;
+      }
+      v[i] = *reinterpret_cast<const bf16x8*>(x + off);
+      inv |= (ok ? 0u : 1u) << i;
+    }
+    return inv;
+  }
+};
+
+__global__ void k_conv_splitk_reduce(const float* __restrict__ ws, float* __restrict__ out, int M, int N, int splits,
+                                     int accumulate) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t total = (size_t)M * N;
+  if (idx >= total) return;
+  float a = 0.f;
+  for (int s = 0; s < splits; ++s) a += ws[(size_t)s * total + idx];
+  out[idx] = accumulate ? out[idx] + a : a;
+}
+
+Epilogue plain_epilogue(void* C, int64_t ldc, int c_f32, int accumulate) {
+  GemmArgs g; g.C = C; g.ldc = ldc; g.c_f32 = c_f32; g.accumulate = accumulate;
+  return make_epilogue(g);
+}
+
+template <class LA, class LB>
+hipError_t launch(const OpCtx& c, LA A, LB B, const Epilogue& e, int M, int N, int K, int splits) {
+  const int tn = (N + BN - 1) / BN;
+  const bool big = ((M + 255) / 256) * tn * splits >= 400;
+  const int bm = big ? 256 : 128;
+  const int tm = (M + bm - 1) / bm;
+  dim3 grid(tm * tn * splits);
+  if (big) k_mfma_tiles<LA, LB, 256><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
+  else k_mfma_tiles<LA, LB, 128><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
+  return hipGetLastError();
+}
+
+bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+
+bool conv_mfma_ok(const OpCtx& c, const ConvArgs& a, const void* p0, const void* p1, const void* p2) {
+  return c.dt == BF16 && a.C % 8 == 0 && a.O % 8 == 0 && a.C >= 8 && a.O >= 8 && al16(p0) && al16(p1) && al16(p2);
+}
+
+hipError_t conv_fwd_mfma(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {
+  const int M = a.N * a.P * a.Q, K = a.R * a.S * a.C;
+  ConvFwdA A{(const bf16_t*)x, a, M};
+  PlainLoader<true> B{Operand{(const bf16_t*)w, K, a.O}};
+  return launch(c, A, B, plain_epilogue(out, a.O, 0, 0), M, a.O, K, 1);
+}
+hipError_t conv_bwd_data_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx) {
+  const int M = a.N * a.H * a.W, K = a.R * a.S * a.O;
+  ConvBwdA A{(const bf16_t*)dout, a, M};
+  ConvFilterT B{(const bf16_t*)w, a};
+  return launch(c, A, B, plain_epilogue(dx, a.C, 0, 0), M, a.C, K, 1);
+}
+hipError_t conv_bwd_weight_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
+                                int accumulate) {
+  const int Mrows = a.N * a.P * a.Q, J = a.R * a.S * a.C;
+  PlainLoader<false> A{Operand{(const bf16_t*)dout, a.O, a.O}};
+  ConvPatchT B{(const bf16_t*)x, a, J};
+  const int tiles = ((a.O + 127) / 128) * ((J + BN - 1) / BN);
+  int splits = 1;
+  if (c.splitk_ws) {
+    splits = (512 + tiles - 1) / tiles;
+    if (splits > 64) splits = 64;
+    if (splits > Mrows / 512) splits = Mrows / 512;
+    while (splits > 1 && (size_t)splits * a.O * J > c.splitk_elems) --splits;
+    if (splits < 1) splits = 1;
+  }
+  hipError_t e = launch(c, A, B, plain_epilogue(dw, J, 1, accumulate), a.O, J, Mrows, splits);
+  if (e != hipSuccess || splits == 1) return e;
+  size_t total = (size_t)a.O * J;
+  k_conv_splitk_reduce<<<(unsigned)((total + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, dw, a.O, J, splits, accumulate);
+  return hipGetLastError();
+}
+
+}  // namespace lp

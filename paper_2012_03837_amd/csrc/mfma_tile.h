@@ -1,0 +1,286 @@
+// Shared pieces of the register-staged MFMA tile kernel: LDS staging, fragment reads (straight and
+// transposing), the fused epilogue, and the kernel template itself, generic over operand loaders.
+// A loader turns (tile row, k) into 16-byte global loads; the plain loaders read dense matrices, the
+// convolution loaders gather NHWC pixels (implicit GEMM) and report zero padding as invalid chunks.
+#pragma once
+#include "common.h"
+#include "gemm_common.h"
+
+namespace lp {
+namespace mfma {
+
+constexpr int BN = 128, BK = 32;
+constexpr int KC_LD = BK + 8;        // [row][k] tiles: 80-byte rows
+constexpr int TB_LD = BN + 16;       // [k][row] tiles: padded rows
+constexpr int B_ELEMS = BN * KC_LD > BK * TB_LD ? BN * KC_LD : BK * TB_LD;
+
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+struct Operand { const bf16_t* p; int64_t ld; int rows; };
+
+// MFMA row i of the n-side fragment holds tile column 16*(g/2) + 8*h + 4*(g%2) + j, i = 8g + 4h + j, so
+// that accumulator values 0..7 / 8..15 of lane-half h are columns 8h..8h+7 / 16+8h..16+8h+7.
+__device__ __forceinline__ int nmap(int i) {
+  int g = i >> 3, h = (i >> 2) & 1, j = i & 3;
+  return 16 * (g >> 1) + 8 * h + 4 * (g & 1) + j;
+}
+
+// ---- registers -> LDS ---------------------------------------------------------------------------
+// Chunks whose k lies beyond K (only in the last k-tile) are zeroed here, at the point where the loaded
+// registers are first needed, so that the loads themselves stay in flight across the MFMA phase.
+__device__ __forceinline__ bf16x8 zero_if(bf16x8 t, bool z) {
+  if (z) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) t[e] = (bf16_t)0.f;
+  }
+  return t;
+}
+template <int ROWS>
+__device__ __forceinline__ void stage_kc(bf16_t* sm, const bf16x8* v, int k0, int K, unsigned invalid) {
+#pragma unroll
+  for (int i = 0; i < ROWS / 64; ++i) {
+    int c = threadIdx.x + 256 * i;
+    *reinterpret_cast<bf16x8*>(sm + (c >> 2) * KC_LD + (c & 3) * 8) =
+        zero_if(v[i], k0 + (c & 3) * 8 >= K || ((invalid >> i) & 1u));
+  }
+}
+template <int ROWS, int LD>
+__device__ __forceinline__ void stage_t(bf16_t* sm, const bf16x8* v, int k0, int K, unsigned invalid) {
+  constexpr int CPR = ROWS / 8;
+#pragma unroll
+  for (int i = 0; i < ROWS / 64; ++i) {
+    int c = threadIdx.x + 256 * i;
+    *reinterpret_cast<bf16x8*>(sm + (c / CPR) * LD + (c % CPR) * 8) =
+        zero_if(v[i], k0 + c / CPR >= K || ((invalid >> i) & 1u));
+  }
+}
+// ---- LDS -> MFMA fragments ----------------------------------------------------------------------
+// kc: lane reads 8 consecutive k of its row.
+__device__ __forceinline__ bf16x8 frag_kc(const bf16_t* sm, int row, int ks, int lane) {
+  return *reinterpret_cast<const bf16x8*>(sm + row * KC_LD + ks + 8 * (lane >> 5));
+}
+// transposed: two ds_read_b64_tr_b16.  In a 16-lane group, lane s supplies the address of 4 consecutive
+// rows at k = kbase + s/4, row chunk s%4; lane j = 4c + e receives rows chunk c element e for k = kbase..+3.
+// `rowbase` is the tile row of chunk (lane%4) for this lane's 16-lane group.
+template <int LD>
+__device__ __forceinline__ bf16x8 frag_t(const bf16_t* sm, int rowbase, int ks, int lane) {
+  int kb = ks + 8 * (lane >> 5) + ((lane & 15) >> 2);
+  const bf16_t* p = sm + kb * LD + rowbase;
+  bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p));
+  bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 4 * LD));
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { r[e] = lo[e]; r[4 + e] = hi[e]; }
+  return r;
+}
+
+// Fused epilogue on 8 consecutive columns n..n+7 of row m.
+__device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float* v) {
+  if (e.bias) {
+    f32x4 b0 = *reinterpret_cast<const f32x4*>(e.bias + n), b1 = *reinterpret_cast<const f32x4*>(e.bias + n + 4);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) { v[x] += b0[x]; v[4 + x] += b1[x]; }
+  }
+  if (e.pre) {
+    bf16x8 w;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
+    *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16_t*>(e.pre) + (size_t)m * e.ldc + n) = w;
+  }
+  if (e.act == ACT_RELU) {
+#pragma unroll
+    for (int x = 0; x < 8; ++x) v[x] = fmaxf(v[x], 0.f);
+  } else if (e.act == ACT_GELU) {
+#pragma unroll
+    for (int x = 0; x < 8; ++x) v[x] = gelu_f(v[x]);
+  }
+  if (e.dact != ACT_NONE) {
+    bf16x8 s = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(e.dact_src) + (size_t)m * e.ldd + n);
+    if (e.dact == ACT_RELU) {
+#pragma unroll
+      for (int x = 0; x < 8; ++x) v[x] = (float)s[x] > 0.f ? v[x] : 0.f;
+    } else {
+#pragma unroll
+      for (int x = 0; x < 8; ++x) v[x] *= dgelu_f((float)s[x]);
+    }
+  }
+  if (e.res) {
+    bf16x8 r = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(e.res) + (size_t)m * e.ldr + n);
+#pragma unroll
+    for (int x = 0; x < 8; ++x) v[x] += (float)r[x];
+  }
+  if (e.c_f32) {
+    float* cp = reinterpret_cast<float*>(e.C) + (size_t)m * e.ldc + n;
+    if (e.accumulate) {
+      f32x4 c0 = *reinterpret_cast<const f32x4*>(cp), c1 = *reinterpret_cast<const f32x4*>(cp + 4);
+#pragma unroll
+      for (int x = 0; x < 4; ++x) { v[x] += c0[x]; v[4 + x] += c1[x]; }
+    }
+    f32x4 o0 = {v[0], v[1], v[2], v[3]}, o1 = {v[4], v[5], v[6], v[7]};
+    *reinterpret_cast<f32x4*>(cp) = o0;
+    *reinterpret_cast<f32x4*>(cp + 4) = o1;
+  } else {
+    bf16_t* cp = reinterpret_cast<bf16_t*>(e.C) + (size_t)m * e.ldc + n;
+    if (e.accumulate) {
+      bf16x8 c0 = *reinterpret_cast<const bf16x8*>(cp);
+#pragma unroll
+      for (int x = 0; x < 8; ++x) v[x] += (float)c0[x];
+    }
+    bf16x8 w;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
+    *reinterpret_cast<bf16x8*>(cp) = w;
+  }
+}
+
+
+// ---- dense-matrix loaders ------------------------------------------------------------------------
+// kc tile [ROWS][32]: ROWS*4 chunks of 8 k; thread takes chunks tid + 256*i.
+// transposed tile, memory [32 k][ROWS]: 32*ROWS/8 chunks of 8 rows; thread takes chunks tid + 256*i.
+template <bool KC_>
+struct PlainLoader {
+  static constexpr bool KC = KC_;
+  Operand o;
+  template <int ROWS> __device__ __forceinline__ void init(int) {}
+  template <int ROWS>
+  __device__ __forceinline__ unsigned fetch(int r0, int k0, int K, bf16x8* v) const {
+    if (KC) {
+#pragma unroll
+      for (int i = 0; i < ROWS / 64; ++i) {
+        int c = threadIdx.x + 256 * i;
+        int row = r0 + (c >> 2), k = k0 + (c & 3) * 8;
+        row = row < o.rows ? row : o.rows - 1;
+        v[i] = *reinterpret_cast<const bf16x8*>(o.p + (size_t)row * o.ld + (k < K ? k : 0));
+      }
+    } else {
+      constexpr int CPR = ROWS / 8;   // chunks per k-row
+#pragma unroll
+      for (int i = 0; i < ROWS / 64; ++i) {
+        int c = threadIdx.x + 256 * i;
+        int k = k0 + c / CPR, row = r0 + (c % CPR) * 8;
+        row = row + 8 <= o.rows ? row : o.rows - 8;
+        v[i] = *reinterpret_cast<const bf16x8*>(o.p + (size_t)(k < K ? k : 0) * o.ld + row);
+      }
+    }
+    return 0u;
+  }
+};
+
+template <class LA, class LB, int BM>
+__global__ void __launch_bounds__(256, 2) k_mfma_tiles(LA A, LB B, Epilogue e, int M, int N, int K, int tiles_m,
+                                                       int tiles_n, int splits, float* ws) {
+  constexpr bool A_KC = LA::KC, B_KC = LB::KC;
+  constexpr int TM = BM / 64;          // 32-row MFMA tiles per wave along m
+  constexpr int TA_LD = BM + 16;
+  constexpr int A_ELEMS = BM * KC_LD > BK * TA_LD ? BM * KC_LD : BK * TA_LD;
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][A_ELEMS];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][B_ELEMS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // XCD-aware renumbering, then column-major groups of 8 tile rows
+  const int split = blockIdx.x % splits;
+  int pid = blockIdx.x / splits;
+  {
+    const int nb = tiles_m * tiles_n, per = nb / 8;
+    if (pid < per * 8) pid = (pid & 7) * per + (pid >> 3);
+    const int GROUP = 8;
+    int width = GROUP * tiles_n, gid = pid / width;
+    int first = gid * GROUP, gs = tiles_m - first < GROUP ? tiles_m - first : GROUP;
+    int tm = first + (pid % width) % gs, tn = (pid % width) / gs;
+    pid = tm * tiles_n + tn;
+  }
+  const int m0 = (pid / tiles_n) * BM, n0 = (pid % tiles_n) * BN;
+  const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * 64;
+
+  f32x16 acc[2][TM];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  bf16x8 ra[BM / 64], rb[BN / 64];
+  unsigned inva = 0, invb = 0;       // chunks the loader declared invalid (implicit zero padding)
+  A.template init<BM>(m0);
+  B.template init<BN>(n0);
+  auto fetch = [&](int k0) {
+    inva = A.template fetch<BM>(m0, k0, K, ra);
+    invb = B.template fetch<BN>(n0, k0, K, rb);
+  };
+  auto stage = [&](int buf, int k0) {
+    if (k0 + BK <= K) k0 = -BK;      // no chunk of this tile can reach K: the masks fold away
+    if (A_KC) stage_kc<BM>(As[buf], ra, k0, K, inva); else stage_t<BM, TA_LD>(As[buf], ra, k0, K, inva);
+    if (B_KC) stage_kc<BN>(Bs[buf], rb, k0, K, invb); else stage_t<BN, TB_LD>(Bs[buf], rb, k0, K, invb);
+  };
+  // fragment addressing that does not depend on k
+  const int li = lane & 31;
+  const int n_row = nmap(li);                                // kc: tile column read by this lane
+  const int c4 = lane & 3, half16 = (lane >> 4) & 1;         // transposed: chunk and 16-row half of the group
+  // n-side chunk c of half16: MFMA rows 16*half16 + 4c .. +3  ->  columns nmap(16*half16 + 4c) .. +3
+  const int n_rowbase_t = nmap(16 * half16 + 4 * c4);
+  const int m_rowbase_t = 16 * half16 + 4 * c4;
+
+  const int nt_all = (K + BK - 1) / BK, per = (nt_all + splits - 1) / splits;
+  const int t_first = split * per;
+  const int nt = nt_all - t_first < per ? (nt_all - t_first > 0 ? nt_all - t_first : 0) : per;
+  const int kbase = t_first * BK;
+  if (nt > 0) {
+    fetch(kbase);
+    stage(0, kbase);
+  }
+  __syncthreads();
+  if (nt > 1) fetch(kbase + BK);
+  for (int t = 0; t < nt; ++t) {
+    const int cur = t & 1;
+    if (t + 1 < nt) stage(cur ^ 1, kbase + (t + 1) * BK);
+    if (t + 2 < nt) fetch(kbase + (t + 2) * BK);
+    const bf16_t* as = As[cur];
+    const bf16_t* bs = Bs[cur];
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += 16) {
+      bf16x8 fn[2], fm[TM];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        fn[i] = B_KC ? frag_kc(bs, wn + 32 * i + n_row, ks, lane) : frag_t<TB_LD>(bs, wn + 32 * i + n_rowbase_t, ks, lane);
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+        fm[j] = A_KC ? frag_kc(as, wm + 32 * j + li, ks, lane) : frag_t<TA_LD>(as, wm + 32 * j + m_rowbase_t, ks, lane);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // epilogue: lane = row m, accumulator values 8q..8q+7 = columns 16q + 8*(lane/32) .. +7
+  const int hf = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    const int m = m0 + wm + 32 * j + li;
+    if (m >= M) continue;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int n = n0 + wn + 32 * i + 16 * q + 8 * hf;
+        if (n >= N) continue;
+        float v[8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) v[x] = acc[i][j][8 * q + x];
+        if (splits > 1) {     // raw partial sums; the reduction kernel applies the epilogue
+          float* wp = ws + ((size_t)split * M + m) * N + n;
+          f32x4 o0 = {v[0], v[1], v[2], v[3]}, o1 = {v[4], v[5], v[6], v[7]};
+          *reinterpret_cast<f32x4*>(wp) = o0;
+          *reinterpret_cast<f32x4*>(wp + 4) = o1;
+        } else {
+          epilogue8(e, m, n, v);
+        }
+      }
+  }
+}
+
+
+}  // namespace mfma
+}  // namespace lp

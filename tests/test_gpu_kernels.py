@@ -232,7 +232,8 @@ def test_embed_bwd_repeated_tokens(K):
 
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("N,H,C,O,R,stride,pad", [(3, 9, 5, 7, 3, 1, 1), (2, 8, 16, 24, 3, 2, 1), (2, 8, 16, 8, 1, 2, 0),
-                                                  (4, 12, 3, 64, 3, 1, 1)])
+                                                  (4, 12, 3, 64, 3, 1, 1), (5, 14, 64, 136, 3, 1, 1),
+                                                  (3, 16, 72, 128, 3, 2, 1), (6, 10, 128, 64, 1, 2, 0)])
 def test_conv_and_batchnorm(K, dtype, N, H, C, O, R, stride, pad):
     import torch
     rng = np.random.default_rng(H)
