@@ -264,3 +264,207 @@ hipError_t ce_fast(const OpCtx& c, void* z, int64_t ld, const int32_t* y, float*
 }
 
 }  // namespace lp
+
+// ===================================================================================================
+// BatchNorm over [rows, C] bf16 with C % 8 == 0: 16 bytes (8 channels) per lane.
+//   statistics : one pass; per-channel sums of (x - p) and (x - p)^2 with the pivot p = the channel's
+//                value in row 0 (a sample of the distribution, so the shifted variance formula
+//                S2/n - (S1/n)^2 does not cancel), per-slab partials, ordered reduction
+//   apply      : y = [relu]((z - mean) * rstd * g + b (+ res))
+//   backward   : per-slab partial sums of dy_eff and dy_eff * xhat, then
+//                dz = g * rstd * (dy_eff - mean(dy_eff) - xhat * mean(dy_eff * xhat)), dres = dy_eff
+// Block = (C/8) channel chunks x (256 / (C/8)) row lanes; C <= 2048.
+namespace lp {
+namespace {
+
+constexpr float kBnEpsV = 1e-5f;
+
+// MODE 0: s0 = sum (z - p), s1 = sum (z - p)^2.   MODE 1: s0 = sum dy_eff, s1 = sum dy_eff * xhat.
+template <int MODE>
+__global__ void __launch_bounds__(256) k_bn_partial_v(const bf16_t* __restrict__ a, const bf16_t* __restrict__ yrelu,
+                                                      const bf16_t* __restrict__ z, const float* __restrict__ mean,
+                                                      const float* __restrict__ rstd, float* __restrict__ partial,
+                                                      int rows, int C, int slab, int relu) {
+  extern __shared__ float sh[];        // [2][RL][C]
+  const int cpr = C >> 3, RL = 256 / cpr;
+  const int cc = threadIdx.x % cpr, rl = threadIdx.x / cpr;
+  const int r0 = blockIdx.x * slab;
+  const int r1 = r0 + slab < rows ? r0 + slab : rows;
+  float s0[8], s1[8], p[8], q[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { s0[e] = 0.f; s1[e] = 0.f; }
+  if (rl < RL) {
+    if (MODE == 0) load8(z + 8 * cc, p);                      // pivot: row 0
+    else { loadf8(mean + 8 * cc, p); loadf8(rstd + 8 * cc, q); }
+    for (int r = r0 + rl; r < r1; r += RL) {
+      const size_t off = (size_t)r * C + 8 * cc;
+      float v[8];
+      load8(a + off, v);
+      if (MODE == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { float t = v[e] - p[e]; s0[e] += t; s1[e] += t * t; }
+      } else {
+        float zz[8];
+        load8(z + off, zz);
+        if (relu) {
+          float yy[8];
+          load8(yrelu + off, yy);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = yy[e] > 0.f ? v[e] : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { s0[e] += v[e]; s1[e] += v[e] * (zz[e] - p[e]) * q[e]; }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sh[(size_t)rl * C + 8 * cc + e] = s0[e];
+      sh[(size_t)(RL + rl) * C + 8 * cc + e] = s1[e];
+    }
+  }
+  __syncthreads();
+  const int nslab = gridDim.x;
+  for (int j = threadIdx.x; j < C; j += 256) {
+    float t0 = 0.f, t1 = 0.f;
+    for (int r = 0; r < RL; ++r) { t0 += sh[(size_t)r * C + j]; t1 += sh[(size_t)(RL + r) * C + j]; }
+    partial[(size_t)blockIdx.x * C + j] = t0;
+    partial[(size_t)(nslab + blockIdx.x) * C + j] = t1;
+  }
+}
+// Adds the slab partials in order (64 channels x 4 slab groups per block) and finishes.
+// mode 0: forward statistics (needs the pivots from row 0 of z); mode 1: plain sums into sums[0..C), sums[C..2C).
+__global__ void k_bn_finish_v(const float* __restrict__ partial, int nslab, int C, int rows, const bf16_t* __restrict__ z,
+                              float* __restrict__ out0, float* __restrict__ out1, int mode) {
+  __shared__ float sh[2][4][64];
+  const int lc = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lc;
+  float a = 0.f, b = 0.f;
+  if (j < C)
+    for (int s = q; s < nslab; s += 4) { a += partial[(size_t)s * C + j]; b += partial[(size_t)(nslab + s) * C + j]; }
+  sh[0][q][lc] = a; sh[1][q][lc] = b;
+  __syncthreads();
+  if (q != 0 || j >= C) return;
+  a = sh[0][0][lc] + sh[0][1][lc] + sh[0][2][lc] + sh[0][3][lc];
+  b = sh[1][0][lc] + sh[1][1][lc] + sh[1][2][lc] + sh[1][3][lc];
+  if (mode == 0) {
+    const float inv = 1.f / (float)rows, m1 = a * inv;
+    float var = b * inv - m1 * m1;
+    var = var > 0.f ? var : 0.f;
+    out0[j] = (float)z[j] + m1;
+    out1[j] = rsqrtf(var + kBnEpsV);
+  } else {
+    out0[j] = a; out1[j] = b;
+  }
+}
+__global__ void __launch_bounds__(256) k_bn_apply_v(const bf16_t* __restrict__ z, const float* __restrict__ g,
+                                                    const float* __restrict__ b, const bf16_t* __restrict__ res,
+                                                    bf16_t* __restrict__ y, const float* __restrict__ mean,
+                                                    const float* __restrict__ rstd, size_t nchunks, int C, int relu) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, st = (size_t)gridDim.x * 256;
+  for (; i < nchunks; i += st) {
+    const int c = (int)((i * 8) % C);
+    float v[8], gg[8], bb[8], mu[8], rs[8];
+    load8(z + i * 8, v); loadf8(g + c, gg); loadf8(b + c, bb); loadf8(mean + c, mu); loadf8(rstd + c, rs);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (v[e] - mu[e]) * rs[e] * gg[e] + bb[e];
+    if (res) {
+      float r[8];
+      load8(res + i * 8, r);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += r[e];
+    }
+    if (relu) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+    }
+    store8(y + i * 8, v);
+  }
+}
+__global__ void __launch_bounds__(256) k_bn_bwd_apply_v(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ yrelu,
+                                                        const bf16_t* __restrict__ z, const float* __restrict__ mean,
+                                                        const float* __restrict__ rstd, const float* __restrict__ g,
+                                                        const float* __restrict__ sums, bf16_t* __restrict__ dz,
+                                                        bf16_t* __restrict__ dres, size_t nchunks, int C, int rows,
+                                                        int relu) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, st = (size_t)gridDim.x * 256;
+  const float inv = 1.f / (float)rows;
+  for (; i < nchunks; i += st) {
+    const int c = (int)((i * 8) % C);
+    float d[8], zz[8], mu[8], rs[8], gg[8], s0[8], s1[8], o[8];
+    load8(dy + i * 8, d); load8(z + i * 8, zz);
+    loadf8(mean + c, mu); loadf8(rstd + c, rs); loadf8(g + c, gg); loadf8(sums + c, s0); loadf8(sums + C + c, s1);
+    if (relu) {
+      float yy[8];
+      load8(yrelu + i * 8, yy);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d[e] = yy[e] > 0.f ? d[e] : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float xh = (zz[e] - mu[e]) * rs[e];
+      o[e] = gg[e] * rs[e] * (d[e] - s0[e] * inv - xh * s1[e] * inv);
+    }
+    store8(dz + i * 8, o);
+    if (dres) store8(dres + i * 8, d);
+  }
+}
+__global__ void k_accum2(const float* src, float* dst0, float* dst1, int C, int accumulate) {
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= C) return;
+  dst0[j] = accumulate ? dst0[j] + src[j] : src[j];
+  dst1[j] = accumulate ? dst1[j] + src[C + j] : src[C + j];
+}
+
+int bn_slab(int rows, int C) {
+  int RL = 256 / (C / 8);
+  int slab = (rows + 1023) / 1024;         // aim at about a thousand blocks
+  int min_slab = RL * 8;
+  if (slab < min_slab) slab = min_slab;
+  return slab;
+}
+int blocks_for(size_t n) { size_t b = (n + 255) / 256; return (int)(b < 16384 ? b : 16384); }
+
+}  // namespace
+
+bool bn_fast_ok(const OpCtx& c, int rows, int C, const void* a, const void* b, const void* cc, const void* d) {
+  if (c.dt != BF16 || C % 8 || C < 8 || C > 2048 || (256 % (C / 8)) || rows < 1) return false;
+  return al16(a) && al16(b) && (!cc || al16(cc)) && (!d || al16(d));
+}
+size_t bn_fast_scratch(int rows, int C) {
+  int slab = bn_slab(rows, C);
+  size_t nslab = (rows + slab - 1) / slab;
+  return (2 * nslab + 2) * (size_t)C;
+}
+hipError_t bn_fwd_fast(const OpCtx& c, const void* z, const float* g, const float* b, const void* res, void* y,
+                       float* mean, float* rstd, int rows, int C, int relu) {
+  const int slab = bn_slab(rows, C), nslab = (rows + slab - 1) / slab;
+  if ((size_t)2 * nslab * C > c.partial_elems) return hipErrorInvalidValue;
+  const int RL = 256 / (C / 8);
+  const size_t shm = (size_t)2 * RL * C * sizeof(float);
+  k_bn_partial_v<0><<<nslab, 256, shm, c.stream>>>((const bf16_t*)z, nullptr, (const bf16_t*)z, nullptr, nullptr,
+                                                   c.partial, rows, C, slab, 0);
+  k_bn_finish_v<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, C, rows, (const bf16_t*)z, mean, rstd, 0);
+  const size_t nch = (size_t)rows * C / 8;
+  k_bn_apply_v<<<blocks_for(nch), 256, 0, c.stream>>>((const bf16_t*)z, g, b, (const bf16_t*)res, (bf16_t*)y, mean, rstd,
+                                                     nch, C, relu);
+  return hipGetLastError();
+}
+hipError_t bn_bwd_fast(const OpCtx& c, const void* dy, const void* y, const void* z, const float* mean,
+                       const float* rstd, const float* g, void* dz, void* dres, float* dg, float* db, int rows, int C,
+                       int relu, int accumulate) {
+  const int slab = bn_slab(rows, C), nslab = (rows + slab - 1) / slab;
+  if ((size_t)(2 * nslab + 2) * C > c.partial_elems) return hipErrorInvalidValue;
+  float* sums = c.partial + (size_t)2 * nslab * C;
+  const int RL = 256 / (C / 8);
+  const size_t shm = (size_t)2 * RL * C * sizeof(float);
+  k_bn_partial_v<1><<<nslab, 256, shm, c.stream>>>((const bf16_t*)dy, (const bf16_t*)y, (const bf16_t*)z, mean, rstd,
+                                                   c.partial, rows, C, slab, relu);
+  k_bn_finish_v<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, C, rows, nullptr, sums, sums + C, 1);
+  const size_t nch = (size_t)rows * C / 8;
+  k_bn_bwd_apply_v<<<blocks_for(nch), 256, 0, c.stream>>>((const bf16_t*)dy, (const bf16_t*)y, (const bf16_t*)z, mean,
+                                                         rstd, g, sums, (bf16_t*)dz, (bf16_t*)dres, nch, C, rows, relu);
+  k_accum2<<<(C + 255) / 256, 256, 0, c.stream>>>(sums, db, dg, C, accumulate);
+  return hipGetLastError();
+}
+
+}  // namespace lp

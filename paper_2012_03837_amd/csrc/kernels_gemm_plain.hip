@@ -55,14 +55,22 @@ struct ConvPatchByCol {        // (j=(r,s,c), k=m) -> input patch element: same 
 
 constexpr int PBM = 64, PBN = 64, PBK = 16;
 
+// gridDim.z > 1: split-K.  Block z reduces k in [z*kper, (z+1)*kper) and writes its raw fp32 tile to
+// ws[z][M][N]; k_plain_splitk_reduce then adds the slices in order.
 template <typename T, typename OA, typename OB>
-__global__ void __launch_bounds__(256) k_gemm_plain(OA A, OB B, Epilogue e, int M, int N, int K) {
+__global__ void __launch_bounds__(256) k_gemm_plain(OA A, OB B, Epilogue e, int M, int N, int K, int kper = 0,
+                                                    float* ws = nullptr) {
   __shared__ float As[PBK][PBM + 1];
   __shared__ float Bs[PBK][PBN + 1];
   int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
   int m0 = blockIdx.y * PBM, n0 = blockIdx.x * PBN;
   float acc[4][4] = {};
-  for (int k0 = 0; k0 < K; k0 += PBK) {
+  int kbeg = 0;
+  if (ws) {
+    kbeg = blockIdx.z * kper;
+    K = kbeg + kper < K ? kbeg + kper : K;
+  }
+  for (int k0 = kbeg; k0 < K; k0 += PBK) {
     for (int i = threadIdx.x; i < PBM * PBK; i += 256) {
       int kk = i % PBK, mm = i / PBK;
       int m = m0 + mm, k = k0 + kk;
@@ -88,8 +96,18 @@ __global__ void __launch_bounds__(256) k_gemm_plain(OA A, OB B, Epilogue e, int 
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
-      if (m < M && n < N) epilogue_store<T>(e, m, n, acc[i][j]);
+      if (m < M && n < N) {
+        if (ws) ws[((size_t)blockIdx.z * M + m) * N + n] = acc[i][j];
+        else epilogue_store<T>(e, m, n, acc[i][j]);
+      }
     }
+}
+__global__ void k_plain_splitk_reduce(const float* ws, float* out, size_t total, int splits, int accumulate) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  float a = 0.f;
+  for (int s = 0; s < splits; ++s) a += ws[(size_t)s * total + idx];
+  out[idx] = accumulate ? out[idx] + a : a;
 }
 
 template <typename T, typename OA, typename OB>
@@ -134,7 +152,20 @@ static hipError_t conv_bwd_weight_t(const OpCtx& c, const ConvArgs& a, const voi
   int Mrows = a.N * a.P * a.Q, J = a.R * a.S * a.C;
   PlainOperand<T> A{(const T*)dout, a.O, 0};            // (o, m) -> dout[m*O + o]
   ConvPatchByCol<T> B{ConvInputPatch<T>{(const T*)x, a}};
-  return launch_plain<T>(c.stream, A, B, plain_out(dw, J, 1, accumulate), a.O, J, Mrows);
+  // few output tiles and a very long reduction (the stem: 64 x 27 outputs over 262144 pixels): split-K
+  int tiles = ((J + PBN - 1) / PBN) * ((a.O + PBM - 1) / PBM);
+  int splits = tiles >= 256 ? 1 : 512 / tiles;
+  if (splits > Mrows / 256) splits = Mrows / 256;
+  while (splits > 1 && (size_t)splits * a.O * J > c.splitk_elems) --splits;
+  if (!c.splitk_ws || splits < 2) return launch_plain<T>(c.stream, A, B, plain_out(dw, J, 1, accumulate), a.O, J, Mrows);
+  int kper = ((Mrows + splits - 1) / splits + PBK - 1) / PBK * PBK;
+  splits = (Mrows + kper - 1) / kper;
+  dim3 grid((J + PBN - 1) / PBN, (a.O + PBM - 1) / PBM, splits);
+  k_gemm_plain<T, PlainOperand<T>, ConvPatchByCol<T>><<<grid, 256, 0, c.stream>>>(A, B, plain_out(dw, J, 1, 0), a.O, J,
+                                                                                 Mrows, kper, c.splitk_ws);
+  size_t total = (size_t)a.O * J;
+  k_plain_splitk_reduce<<<(unsigned)((total + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, dw, total, splits, accumulate);
+  return hipGetLastError();
 }
 
 hipError_t conv_fwd_plain(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {

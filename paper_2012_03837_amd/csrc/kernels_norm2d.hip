@@ -5,8 +5,15 @@
 
 namespace lp {
 
+bool bn_fast_ok(const OpCtx& c, int rows, int C, const void* a, const void* b, const void* cc, const void* d);
+hipError_t bn_fwd_fast(const OpCtx& c, const void* z, const float* g, const float* b, const void* res, void* y,
+                       float* mean, float* rstd, int rows, int C, int relu);
+hipError_t bn_bwd_fast(const OpCtx& c, const void* dy, const void* y, const void* z, const float* mean,
+                       const float* rstd, const float* g, void* dz, void* dres, float* dg, float* db, int rows, int C,
+                       int relu, int accumulate);
+
 constexpr float kBnEps = 1e-5f;
-constexpr int kSlabRows = 256;
+constexpr int kSlabRows = 1024;
 
 // MODE 0: sum x.  MODE 1: sum (x - mu)^2.  MODE 2: two sums for backward: dy_eff and dy_eff * xhat.
 template <typename T, int MODE>
@@ -43,11 +50,19 @@ __global__ void k_bn_partial(const T* a, const T* yrelu, const T* z, const float
   }
 }
 // mode 0: out = sum/rows.  mode 1: out = rsqrt(sum/rows + eps).  mode 2: out = sum.
+// Block = 64 channels x 4 slab groups; group q adds slabs q, q+4, ... in order, then the four group sums
+// are added in order (a fixed tree).
 __global__ void k_bn_finalize(const float* partial, int nslab, int C, int rows, float* out, int mode) {
-  int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= C) return;
+  __shared__ float sh[4][64];
+  int lc = threadIdx.x & 63, q = threadIdx.x >> 6;
+  int j = blockIdx.x * 64 + lc;
   float a = 0.f;
-  for (int b = 0; b < nslab; ++b) a += partial[(size_t)b * C + j];
+  if (j < C)
+    for (int b = q; b < nslab; b += 4) a += partial[(size_t)b * C + j];
+  sh[q][lc] = a;
+  __syncthreads();
+  if (q != 0 || j >= C) return;
+  a = sh[0][lc] + sh[1][lc] + sh[2][lc] + sh[3][lc];
   if (mode == 0) out[j] = a / (float)rows;
   else if (mode == 1) out[j] = rsqrtf(a / (float)rows + kBnEps);
   else out[j] = a;
@@ -96,9 +111,9 @@ static hipError_t bn_fwd_t(const OpCtx& c, const void* z, const float* g, const 
   if ((size_t)nslab * C > c.partial_elems) return hipErrorInvalidValue;
   dim3 grid((C + 63) / 64, nslab);
   k_bn_partial<T, 0><<<grid, 256, 0, c.stream>>>((const T*)z, nullptr, nullptr, nullptr, nullptr, c.partial, rows, C, 0);
-  k_bn_finalize<<<(C + 255) / 256, 256, 0, c.stream>>>(c.partial, nslab, C, rows, mean, 0);
+  k_bn_finalize<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, C, rows, mean, 0);
   k_bn_partial<T, 1><<<grid, 256, 0, c.stream>>>((const T*)z, nullptr, nullptr, mean, nullptr, c.partial, rows, C, 0);
-  k_bn_finalize<<<(C + 255) / 256, 256, 0, c.stream>>>(c.partial, nslab, C, rows, rstd, 1);
+  k_bn_finalize<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, C, rows, rstd, 1);
   size_t n = (size_t)rows * C;
   k_bn_apply<T><<<ew_blocks(n), 256, 0, c.stream>>>((const T*)z, g, b, (const T*)res, (T*)y, mean, rstd, n, C, relu);
   return hipGetLastError();
@@ -107,6 +122,7 @@ hipError_t op_batchnorm_fwd(const OpCtx& c, const void* z, const float* g, const
                             float* mean, float* rstd, int rows, int C, int relu) {
   ProfScope prof_(c, KC_BATCHNORM);
   if (rows == 0) return hipSuccess;
+  if (bn_fast_ok(c, rows, C, z, y, res, nullptr)) return bn_fwd_fast(c, z, g, b, res, y, mean, rstd, rows, C, relu);
   return c.dt == BF16 ? bn_fwd_t<bf16_t>(c, z, g, b, res, y, mean, rstd, rows, C, relu)
                       : bn_fwd_t<float>(c, z, g, b, res, y, mean, rstd, rows, C, relu);
 }
@@ -120,8 +136,8 @@ static hipError_t bn_bwd_t(const OpCtx& c, const void* dy, const void* y, const 
   float* sums = c.partial + (size_t)2 * nslab * C;   // [0..C) = sum dy, [C..2C) = sum dy*xhat
   dim3 grid((C + 63) / 64, nslab);
   k_bn_partial<T, 2><<<grid, 256, 0, c.stream>>>((const T*)dy, (const T*)y, (const T*)z, mean, rstd, c.partial, rows, C, relu);
-  k_bn_finalize<<<(C + 255) / 256, 256, 0, c.stream>>>(c.partial, nslab, C, rows, sums, 2);
-  k_bn_finalize<<<(C + 255) / 256, 256, 0, c.stream>>>(c.partial + (size_t)nslab * C, nslab, C, rows, sums + C, 2);
+  k_bn_finalize<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, C, rows, sums, 2);
+  k_bn_finalize<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial + (size_t)nslab * C, nslab, C, rows, sums + C, 2);
   size_t n = (size_t)rows * C;
   k_bn_bwd_apply<T><<<ew_blocks(n), 256, 0, c.stream>>>((const T*)dy, (const T*)y, (const T*)z, mean, rstd, g, sums,
                                                        (T*)dz, (T*)dres, n, C, rows, relu);
@@ -134,6 +150,8 @@ hipError_t op_batchnorm_bwd(const OpCtx& c, const void* dy, const void* y, const
                             int C, int relu, int accumulate) {
   ProfScope prof_(c, KC_BATCHNORM);
   if (rows == 0) return hipSuccess;
+  if (bn_fast_ok(c, rows, C, dy, y, z, dz) && (!dres || ((uintptr_t)dres & 15) == 0))
+    return bn_bwd_fast(c, dy, y, z, mean, rstd, g, dz, dres, dg, db, rows, C, relu, accumulate);
   return c.dt == BF16 ? bn_bwd_t<bf16_t>(c, dy, y, z, mean, rstd, g, dz, dres, dg, db, rows, C, relu, accumulate)
                       : bn_bwd_t<float>(c, dy, y, z, mean, rstd, g, dz, dres, dg, db, rows, C, relu, accumulate);
 }

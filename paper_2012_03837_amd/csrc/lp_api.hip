@@ -219,7 +219,7 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
         if (n > max_act) max_act = n;
         if (nin > max_act) max_act = nin;
         size_t rows = (size_t)B * u.a.P * u.a.Q;
-        size_t pr = (2 * ((rows + 255) / 256) + 2) * u.a.O;
+        size_t pr = (size_t)(2 * 1024 + 2) * u.a.O;   // up to 1024 row slabs, two sums each, plus the totals
         if (pr > partial) partial = pr;
       };
       S.has_stem = l.has_stem != 0;
@@ -258,8 +258,8 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
   }
   c->partial_elems = partial;
   c->partial = (float*)wa.take(partial * 4);
-  if (dt == BF16) {   // split-K partial sums: at most 8 splits of fewer than 400 tiles of 128 x 128
-    c->splitk_elems = (size_t)8 * 400 * 128 * 128;
+  if (dt == BF16 || kind0 == LP_LAYER_RESNET_STAGE) {   // split-K partial sums
+    c->splitk_elems = dt == BF16 ? (size_t)8 * 400 * 128 * 128 : (size_t)1 << 22;
     c->splitk_ws = (float*)wa.take(c->splitk_elems * 4);
   }
   c->loss_rows = (float*)wa.take(max_rows * 4);
