@@ -156,6 +156,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg3", help="cfg1..cfg5")
+    ap.add_argument("--streams", type=int, default=2, help="side streams for the heads' chains (0 = one stream)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the HIP-event pass (used under rocprofv3)")
     args = ap.parse_args()
@@ -173,7 +174,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     cfg = LI.make_config(args.config)
-    tr = lp.LocalTrainer(cfg)
+    tr = lp.LocalTrainer(cfg, n_streams=args.streams)
     K, W = args.steps, args.warmup
     n_stage = min(K + W, 8)
     staged = [tr.stage(*LI.make_batch(cfg, i)) for i in range(n_stage)]
@@ -239,7 +240,7 @@ def main():
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "batch": cfg.batch, "n_layers": cfg.n_layers, "n_heads_aux": len(cfg.heads),
                    "windows": LI.head_windows(cfg)[:3] + (["..."] if len(cfg.heads) > 3 else []),
-                   "optimizer": cfg.opt.kind, "combine": cfg.combine},
+                   "optimizer": cfg.opt.kind, "combine": cfg.combine, "side_streams": args.streams},
         "roofline": roofline,
         "phases": phases,
         "final_losses": losses[:4],

@@ -97,6 +97,12 @@ typedef struct {
   int vocab;                /* > 0: layer 1 owns a token embedding [vocab, width] + fixed sinusoidal
                                positions, and x is int32 token ids                                  */
   uint64_t seed;            /* seed of the built-in weight initialiser                              */
+  int n_streams;            /* 0: everything on the caller's stream.  n > 0: each head's loss, in-window
+                               backward pass and updates run on one of n side streams (the library creates
+                               them, default priority) as soon as the head's activation exists, while the
+                               forward pass continues on the caller's stream; all of them are joined back
+                               into the caller's stream before lp_local_step returns.  Results do not depend
+                               on n (every per-parameter accumulation keeps its order).  At most 8.        */
 } lp_model_spec;
 
 typedef struct { size_t param_bytes, state_bytes, work_bytes; } lp_sizes;

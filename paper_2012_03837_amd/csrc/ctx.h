@@ -73,7 +73,24 @@ struct Arena {
 
 }  // namespace lp
 
-struct lp_ctx {
+// Scratch that one chain of work (a head's loss, its in-window backward pass and the updates) needs:
+// one set for the caller's stream and one per side stream.
+struct lp_scratch {
+  hipStream_t cur_stream = nullptr;
+  float* partial = nullptr; size_t partial_elems = 0;
+  float* splitk_ws = nullptr; size_t splitk_elems = 0;
+  float* loss_rows = nullptr;
+  // backward scratch
+  void *dA = nullptr, *dB = nullptr, *dF = nullptr, *dc = nullptr, *du = nullptr, *dO = nullptr, *dqkv = nullptr,
+       *da = nullptr;
+  float* delta = nullptr;
+  void *sG = nullptr, *sZ = nullptr, *sR = nullptr, *sD1 = nullptr, *sD2 = nullptr;  // resnet
+  // head scratch
+  void *feat = nullptr, *logits = nullptr, *dfeat = nullptr;
+  float *hmean = nullptr, *hrstd = nullptr;
+};
+
+struct lp_ctx : lp_scratch {
   lp_model_spec spec;
   std::vector<lp_layer_spec> layer_specs;
   std::vector<lp_head_spec> head_specs;
@@ -88,20 +105,14 @@ struct lp_ctx {
   float* master = nullptr; void* lowp = nullptr;
   float* mom = nullptr; float* var = nullptr;
   float* grads = nullptr;
-  float* partial = nullptr; size_t partial_elems = 0;
-  float* splitk_ws = nullptr; size_t splitk_elems = 0;
-  float* loss_rows = nullptr;
   float* pe = nullptr;
   void* h0 = nullptr;                    // embedded input of layer 1
   const void* x_in = nullptr;            // input of the current call
-  // backward scratch
-  void *dA = nullptr, *dB = nullptr, *dF = nullptr, *dc = nullptr, *du = nullptr, *dO = nullptr, *dqkv = nullptr,
-       *da = nullptr;
-  float* delta = nullptr;
-  void *sG = nullptr, *sZ = nullptr, *sR = nullptr, *sD1 = nullptr, *sD2 = nullptr;  // resnet
-  // head scratch
-  void *feat = nullptr, *logits = nullptr, *dfeat = nullptr;
-  float *hmean = nullptr, *hrstd = nullptr;
+  // scratch sets: [0] belongs to the caller's stream, [1..n_side] to the side streams
+  std::vector<lp_scratch> sets;
+  int n_side = 0;
+  std::vector<hipEvent_t> ev_fwd, ev_contrib, ev_chain;
+  void use(int i) { static_cast<lp_scratch&>(*this) = sets[i]; }
   int step_t = 0;
   int last_batch = 0;
   bool ok = false;
@@ -109,7 +120,7 @@ struct lp_ctx {
 
   mutable lp::Profiler prof;
   lp::OpCtx op() const {
-    lp::OpCtx c; c.stream = stream; c.dt = dt; c.partial = partial; c.partial_elems = partial_elems;
+    lp::OpCtx c; c.stream = cur_stream; c.dt = dt; c.partial = partial; c.partial_elems = partial_elems;
     c.prof = &prof; c.splitk_ws = splitk_ws; c.splitk_elems = splitk_elems; return c;
   }
   float* P32(int ti) const { return master + tensors[ti].off; }

@@ -25,6 +25,7 @@ static int validate(const lp_model_spec* sp, std::string& err) {
   if (sp->opt.kind < LP_OPT_SGD || sp->opt.kind > LP_OPT_ADAM) { err = "bad optimizer kind"; return LP_EINVAL; }
   if (sp->max_batch < 1) { err = "max_batch must be >= 1"; return LP_ESHAPE; }
   if (sp->vocab < 0) { err = "vocab must be >= 0"; return LP_EINVAL; }
+  if (sp->n_streams < 0 || sp->n_streams > 8) { err = "n_streams must be in [0, 8]"; return LP_EINVAL; }
   int kind0 = sp->layers[0].kind;
   int64_t prev_out = -1;
   for (int i = 0; i < sp->n_layers; ++i) {
@@ -256,35 +257,44 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
     size_t pc = ((rows + 127) / 128) * (size_t)(Hd.s.n_classes > Hd.s.in_dim ? Hd.s.n_classes : Hd.s.in_dim);
     if (pc > partial) partial = pc;
   }
-  c->partial_elems = partial;
-  c->partial = (float*)wa.take(partial * 4);
-  if (dt == BF16 || kind0 == LP_LAYER_RESNET_STAGE) {   // split-K partial sums
-    c->splitk_elems = dt == BF16 ? (size_t)8 * 400 * 128 * 128 : (size_t)1 << 22;
-    c->splitk_ws = (float*)wa.take(c->splitk_elems * 4);
-  }
-  c->loss_rows = (float*)wa.take(max_rows * 4);
-  c->feat = wa.take(max_feat * es);
-  c->dfeat = wa.take(max_feat * es);
-  c->logits = wa.take(max_head_logits * es);
-  c->hmean = (float*)wa.take(max_rows * 4);
-  c->hrstd = (float*)wa.take(max_rows * 4);
   if (kind0 == LP_LAYER_DECODER) {
     const lp_layer_spec& l = sp.layers[0];
-    size_t T = (size_t)B * l.seq_len, d = l.width, F = l.hidden;
-    c->pe = (float*)wa.take((size_t)l.seq_len * d * 4);
-    c->h0 = wa.take(T * d * es);
-    c->dA = wa.take(T * d * es); c->dB = wa.take(T * d * es);
-    c->dF = wa.take(T * F * es); c->dc = wa.take(T * d * es); c->du = wa.take(T * d * es);
-    c->dO = wa.take(T * d * es); c->dqkv = wa.take(T * 3 * d * es); c->da = wa.take(T * d * es);
-    c->delta = (float*)wa.take(T * l.n_heads * 4);
-  } else if (kind0 == LP_LAYER_RESMLP) {
-    c->dA = wa.take(max_act * es); c->dB = wa.take(max_act * es);
-    c->dF = wa.take(max_act * es); c->dc = wa.take(max_act * es);
-  } else {
-    c->dA = wa.take(max_act * es); c->dB = wa.take(max_act * es);
-    c->sG = wa.take(max_act * es); c->sZ = wa.take(max_act * es); c->sR = wa.take(max_act * es);
-    c->sD1 = wa.take(max_act * es); c->sD2 = wa.take(max_act * es);
+    c->pe = (float*)wa.take((size_t)l.seq_len * l.width * 4);
+    c->h0 = wa.take((size_t)B * l.seq_len * l.width * es);
   }
+  // one scratch set for the caller's stream and one per side stream
+  c->n_side = sp.n_streams;
+  c->sets.assign(1 + c->n_side, lp_scratch());
+  for (auto& S : c->sets) {
+    S.partial_elems = partial;
+    S.partial = (float*)wa.take(partial * 4);
+    if (dt == BF16 || kind0 == LP_LAYER_RESNET_STAGE) {   // split-K partial sums
+      S.splitk_elems = dt == BF16 ? (size_t)8 * 400 * 128 * 128 : (size_t)1 << 22;
+      S.splitk_ws = (float*)wa.take(S.splitk_elems * 4);
+    }
+    S.loss_rows = (float*)wa.take(max_rows * 4);
+    S.feat = wa.take(max_feat * es);
+    S.dfeat = wa.take(max_feat * es);
+    S.logits = wa.take(max_head_logits * es);
+    S.hmean = (float*)wa.take(max_rows * 4);
+    S.hrstd = (float*)wa.take(max_rows * 4);
+    if (kind0 == LP_LAYER_DECODER) {
+      const lp_layer_spec& l = sp.layers[0];
+      size_t T = (size_t)B * l.seq_len, d = l.width, F = l.hidden;
+      S.dA = wa.take(T * d * es); S.dB = wa.take(T * d * es);
+      S.dF = wa.take(T * F * es); S.dc = wa.take(T * d * es); S.du = wa.take(T * d * es);
+      S.dO = wa.take(T * d * es); S.dqkv = wa.take(T * 3 * d * es); S.da = wa.take(T * d * es);
+      S.delta = (float*)wa.take(T * l.n_heads * 4);
+    } else if (kind0 == LP_LAYER_RESMLP) {
+      S.dA = wa.take(max_act * es); S.dB = wa.take(max_act * es);
+      S.dF = wa.take(max_act * es); S.dc = wa.take(max_act * es);
+    } else {
+      S.dA = wa.take(max_act * es); S.dB = wa.take(max_act * es);
+      S.sG = wa.take(max_act * es); S.sZ = wa.take(max_act * es); S.sR = wa.take(max_act * es);
+      S.sD1 = wa.take(max_act * es); S.sD2 = wa.take(max_act * es);
+    }
+  }
+  c->use(0);
   if (sizes) {
     sizes->param_bytes = (pa.used + 255) & ~(size_t)255;
     sizes->state_bytes = (sa.used + 255) & ~(size_t)255;
@@ -355,6 +365,22 @@ extern "C" int lp_init_blocks(const lp_model_spec* spec, const lp_buffers* buffe
       if (avail < b.n) { c->err = std::string(b.what) + " buffer too small: have " + std::to_string(avail) + " bytes, need " + std::to_string(b.n); return bail(LP_ENOMEM); }
     }
   }
+  // streams and events
+  c->sets[0].cur_stream = c->stream;
+  {
+    hipError_t es_ = hipSuccess;
+    for (int i = 1; i <= c->n_side && es_ == hipSuccess; ++i)
+      es_ = hipStreamCreateWithFlags(&c->sets[i].cur_stream, hipStreamNonBlocking);
+    int L = spec->n_layers, J = spec->n_heads;
+    c->ev_fwd.assign(L + 1, nullptr); c->ev_contrib.assign(L + 1, nullptr); c->ev_chain.assign(J, nullptr);
+    if (c->n_side > 0) {
+      for (auto* v : {&c->ev_fwd, &c->ev_contrib, &c->ev_chain})
+        for (auto& ev : *v)
+          if (es_ == hipSuccess) es_ = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+    }
+    if (es_ != hipSuccess) { c->err = std::string("stream/event creation: ") + hipGetErrorString(es_); return bail(LP_EDEVICE); }
+  }
+  c->use(0);
   OpCtx o = c->op();
   hipError_t e;
 #define CKI(expr) do { e = (expr); if (e != hipSuccess) { c->err = std::string(#expr) + ": " + hipGetErrorString(e); return bail(LP_EDEVICE); } } while (0)
@@ -430,6 +456,11 @@ extern "C" int lp_profile_read(lp_ctx* c, int kernel_class, double* total_ms, lo
 
 extern "C" void lp_destroy(lp_ctx* c) {
   if (!c) return;
+  for (size_t i = 1; i < c->sets.size(); ++i)
+    if (c->sets[i].cur_stream) { (void)hipStreamSynchronize(c->sets[i].cur_stream); (void)hipStreamDestroy(c->sets[i].cur_stream); }
+  for (auto* v : {&c->ev_fwd, &c->ev_contrib, &c->ev_chain})
+    for (auto ev : *v)
+      if (ev) (void)hipEventDestroy(ev);
   prof_free(c);
   delete c;
 }
@@ -471,20 +502,30 @@ static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* los
     for (int li = 1; li <= L; ++li) c->layers[li].seen = 0;
   }
   const int32_t* ids = c->spec.vocab > 0 ? (const int32_t*)x : nullptr;
-  int hj = 0;
+  const bool side = train && c->n_side > 0;
+  int hj = 0, chain = 0;
+  c->use(0);
   for (int li = 1; li <= L; ++li) {
+    c->use(0);
     if ((st = drv_forward(c, li, batch, ids)) != LP_OK) return st;
+    if (side && hj < J && c->heads[hj].e == li) CK(hipEventRecord(c->ev_fwd[li], c->stream));
     // every head attached after this layer runs as soon as the activation exists
     for (; hj < J && c->heads[hj].e == li; ++hj) {
       HeadState& Hd = c->heads[hj];
+      const int set = side ? 1 + (chain++ % c->n_side) : 0;
+      c->use(set);
+      if (set) CK(hipStreamWaitEvent(c->cur_stream, c->ev_fwd[li], 0));
       if ((st = drv_head(c, hj, batch, y, losses + hj, train, c->dA)) != LP_OK) return st;
       if (!train) continue;
       void* dcur = c->dA; void* dnext = c->dB;
       for (int lj = Hd.e; lj > Hd.s_lo; --lj) {
         LayerState& S = c->layers[lj];
         bool need_dx = lj > Hd.s_lo + 1;          // the window input is data: no gradient leaves the window
+        // contributions of several heads to one layer keep their order: wait for the previous one
+        if (set && S.seen > 0) CK(hipStreamWaitEvent(c->cur_stream, c->ev_contrib[lj], 0));
         if ((st = drv_backward(c, lj, batch, dcur, dnext, need_dx, S.seen > 0 ? 1 : 0)) != LP_OK) return st;
         S.seen += 1;
+        if (set && S.seen < S.coverage) CK(hipEventRecord(c->ev_contrib[lj], c->cur_stream));
         void* t = dcur; dcur = dnext; dnext = t;
       }
       if ((st = optimizer_range(c, Hd.p_begin, Hd.p_end, 1.f)) != LP_OK) return st;
@@ -496,8 +537,12 @@ static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* los
           if ((st = optimizer_range(c, S.p_begin, S.p_end, gs)) != LP_OK) return st;
         }
       }
+      if (set) CK(hipEventRecord(c->ev_chain[hj], c->cur_stream));
     }
   }
+  c->use(0);
+  if (side)
+    for (int j = 0; j < J; ++j) CK(hipStreamWaitEvent(c->stream, c->ev_chain[j], 0));
   return LP_OK;
 }
 

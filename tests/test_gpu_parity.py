@@ -128,3 +128,31 @@ def test_repeatable_bitwise(lpmod):
         tr.close()
     for a, b in zip(*outs):
         np.testing.assert_array_equal(a, b)
+
+
+@pytest.mark.parametrize("name", ["cfg1_small", "cfg2_small", "cfg4_small", "cfg5_small"])
+def test_side_streams_bit_identical(lpmod, name):
+    """Heads' chains on side streams (forward continues on the caller's stream) give the same bits as
+    everything on one stream, over three steps; and parity with the oracle holds."""
+    cfg = LI.make_config(name)
+    outs = []
+    for ns in (0, 3):
+        tr = lpmod.LocalTrainer(cfg, n_streams=ns)
+        tr.set_params(generic_params(cfg))
+        ls = []
+        for step in range(3):
+            xd, yd = tr.stage(*data_for(cfg, step))
+            ls.append(tr.step(xd, yd).cpu().numpy().copy())
+        P = tr.get_params()
+        G = {k: tr.get(k + ".grad") for k in P}
+        outs.append((ls, P, G))
+        tr.close()
+    for a, b in zip(outs[0][0], outs[1][0]):
+        np.testing.assert_array_equal(a, b)
+    for k in outs[0][1]:
+        np.testing.assert_array_equal(outs[0][1][k], outs[1][1][k])
+        np.testing.assert_array_equal(outs[0][2][k], outs[1][2][k])
+    tr = lpmod.LocalTrainer(cfg, n_streams=2)
+    x, y = data_for(cfg)
+    compare_step(tr, cfg, generic_params(cfg), x, y, n_steps=1, label=name + "/streams", stored=stored_for(cfg))
+    tr.close()
