@@ -214,12 +214,16 @@ def main():
         af, ab = attention_flops_per_step(cfg)
         ob, npar = optimizer_bytes_per_step(cfg)
         key = "gemm" if "gemm" in phases and cfg.layers[0].kind != "resnet_stage" else "conv"
+        # the class's ops: GEMMs run k_gemm_dma / k_mfma_tiles (+ k_splitk_reduce), convolutions the
+        # same tile kernel through gather loaders; the fp32 path runs k_gemm_plain
+        kernel_names = {"gemm": "k_gemm_dma+k_mfma_tiles+k_splitk_reduce" if cfg.dtype == "bf16" else "k_gemm_plain",
+                        "conv": "k_mfma_tiles<Conv*>+k_gemm_plain(stem)+k_splitk_reduce"}
         if key in phases:
             p = phases[key]
             peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
             algo = gf if key == "gemm" else gf
             ach = algo / (p["ms_per_step"] * 1e-3) / 1e12
-            roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": "k_gemm_mfma" if cfg.dtype == "bf16" else "k_gemm_plain",
+            roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": kernel_names[key],
                         "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                         "algorithmic_flops_per_step": algo, "launches_per_step": p["ops_per_step"],
                         "avg_launch_ms": p["ms_per_step"] / p["ops_per_step"]}

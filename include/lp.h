@@ -151,7 +151,8 @@ int lp_get_step(lp_ctx* ctx);
 int lp_set_step(lp_ctx* ctx, int t);
 
 /* Per-kernel-class timing.  While enabled, every op brackets its launches with a pair of HIP events
- * on the context's stream.  lp_profile_read drains the stream and returns, for one class, the summed
+ * on the context's stream, and the side streams are not used (each duration is then the op's own, not
+ * shared with a concurrent chain; results are bit-identical either way).  lp_profile_read drains the stream and returns, for one class, the summed
  * event time in ms, the number of ops launched and (for GEMM / convolution classes) the FLOPs
  * launched, all since profiling was last enabled.  Read after every step: the event pool holds 8192
  * pairs.  Enabling resets the totals. */

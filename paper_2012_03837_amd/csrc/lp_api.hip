@@ -502,7 +502,8 @@ static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* los
     for (int li = 1; li <= L; ++li) c->layers[li].seen = 0;
   }
   const int32_t* ids = c->spec.vocab > 0 ? (const int32_t*)x : nullptr;
-  const bool side = train && c->n_side > 0;
+  // with per-op timing on, everything runs on the caller's stream so that each duration is the op's own
+  const bool side = train && c->n_side > 0 && !c->prof.on;
   int hj = 0, chain = 0;
   c->use(0);
   for (int li = 1; li <= L; ++li) {
