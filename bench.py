@@ -21,6 +21,15 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3       # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0
 
+# Traffic beyond L2 of the timed kernel class, bytes per launch: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# (two separate runs of this file), scaled by the same counters' readings for the plain copy kernel
+# (--copy-calibration).  Counters cannot be read from inside this process, so the figures measured for the
+# committed kernels are recorded here; the summary with the commands is profiles/cfg3_gemm_hbm_traffic_pmc.md.
+MEASURED_TRAFFIC = {
+    "cfg3": {"bytes_per_launch": 4.77e8, "read_bytes_per_step": 66.4e9, "written_bytes_per_step": 19.4e9,
+             "algorithmic_bytes_per_step": 31.1e9},
+}
+
 
 def gemm_flops_per_step(cfg):
     """Algorithmic FLOPs of the dense contractions of one step (2*M*N*K each): forward once per
@@ -159,6 +168,9 @@ def main():
     ap.add_argument("--streams", type=int, default=2, help="side streams for the heads' chains (0 = one stream)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the HIP-event pass (used under rocprofv3)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run the plain copy kernel (5 x 1 GiB): the known traffic that scales rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (local parallelism is measured on a single MI355X); "
@@ -173,6 +185,17 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
+    if args.copy_calibration:
+        from paper_2012_03837_amd import kernels as LK
+        n = 1 << 30
+        src = torch.full((n,), 7, device="cuda", dtype=torch.uint8)
+        dst = torch.zeros_like(src)
+        for _ in range(5):
+            LK.lpk_copy(src, dst, n)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"kernel": "k_copy16", "launches": 5, "bytes_read_per_launch": n,
+                                               "bytes_written_per_launch": n}}))
+        return
     cfg = LI.make_config(args.config)
     tr = lp.LocalTrainer(cfg, n_streams=args.streams)
     K, W = args.steps, args.warmup
@@ -224,7 +247,9 @@ def main():
             algo = gf if key == "gemm" else gf
             ach = algo / (p["ms_per_step"] * 1e-3) / 1e12
             roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": kernel_names[key],
-                        "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                        "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+                        "traffic": MEASURED_TRAFFIC.get(cfg.name, {}).get("bytes_per_launch"),
+                        "traffic_detail": MEASURED_TRAFFIC.get(cfg.name),
                         "algorithmic_flops_per_step": algo, "launches_per_step": p["ops_per_step"],
                         "avg_launch_ms": p["ms_per_step"] / p["ops_per_step"]}
         if "gemm" in phases:

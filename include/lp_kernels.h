@@ -54,6 +54,11 @@ int lpk_optimizer(int kind, float lr, float momentum, float beta1, float beta2, 
                   int t, float grad_scale, float* p, const float* g, float* m, float* v, void* p_bf16, size_t n,
                   void* stream);
 
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned), one
+ * 16-byte load and store per lane.  Not part of the method: it is the kernel of known traffic against
+ * which the HBM counters (FETCH_SIZE, WRITE_SIZE) are scaled when a kernel's traffic is measured. */
+int lpk_copy(const void* src_dev, void* dst_dev, size_t bytes, void* stream);
+
 /* Embedding-table gradient: demb[v,:] (+)= sum of dh[t,:] over positions with ids[t] == v, in order of t. */
 int lpk_embed_bwd(int dtype, const int32_t* ids, const void* dh, float* demb, int T, int V, int d, int accumulate,
                   void* stream);

@@ -101,6 +101,7 @@ struct ProfScope {
 // ---- ops (each enqueues on ctx.stream and returns a hipError_t) -------------------------------
 hipError_t op_gemm(const OpCtx& c, const GemmArgs& g);
 hipError_t op_fill_f32(const OpCtx& c, float* p, size_t n, float v);
+hipError_t op_copy(const OpCtx& c, const void* src, void* dst, size_t bytes);   // bytes % 16 == 0
 hipError_t op_cast_to_compute(const OpCtx& c, const float* src, void* dst, size_t n);
 
 hipError_t op_embed_fwd(const OpCtx& c, const int32_t* ids, const float* emb, const float* pe, void* out,

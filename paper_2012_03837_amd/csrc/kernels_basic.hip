@@ -55,6 +55,21 @@ hipError_t op_fill_f32(const OpCtx& c, float* p, size_t n, float v) {
   return LP_LAUNCH_CHECK();
 }
 
+// Plain device copy, 16 bytes per lane: the known-size kernel against which hardware traffic counters
+// are scaled.
+__global__ void k_copy16(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t st = (size_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += st) dst[i] = src[i];
+}
+hipError_t op_copy(const OpCtx& c, const void* src, void* dst, size_t bytes) {
+  if (bytes == 0) return hipSuccess;
+  size_t n16 = bytes / 16;
+  int blocks = (int)((n16 + 255) / 256 < 16384 ? (n16 + 255) / 256 : 16384);
+  k_copy16<<<blocks, 256, 0, c.stream>>>((const uint4*)src, (uint4*)dst, n16);
+  return LP_LAUNCH_CHECK();
+}
+
 template <typename T>
 __global__ void k_cast(const float* src, T* dst, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -73,6 +73,10 @@ extern "C" int lpk_optimizer(int kind, float lr, float momentum, float beta1, fl
   if (kind < 0 || kind > 2) return (int)hipErrorInvalidValue;
   return (int)op_optimizer(mk(F32, stream), o, p, g, m, v, p_bf16, n);
 }
+extern "C" int lpk_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (bytes % 16 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return (int)hipErrorInvalidValue;
+  return (int)op_copy(mk(0, stream), src, dst, bytes);
+}
 extern "C" int lpk_embed_bwd(int dtype, const int32_t* ids, const void* dh, float* demb, int T, int V, int d,
                              int accumulate, void* stream) {
   return (int)op_embed_bwd(mk(dtype, stream), ids, dh, demb, T, V, d, accumulate);

@@ -68,6 +68,10 @@ def lpk_optimizer(kind, lr, momentum, beta1, beta2, eps, weight_decay, t, grad_s
         "lpk_optimizer")
 
 
+def lpk_copy(src, dst, nbytes):
+    _ck(lib().lpk_copy(_p(src), _p(dst), _sz(nbytes), _stream()), "lpk_copy")
+
+
 def lpk_embed_bwd(dtype, ids, dh, demb, T, V, d, accumulate=0):
     _ck(lib().lpk_embed_bwd(_i(dtype), _p(ids), _p(dh), _p(demb), _i(T), _i(V), _i(d), _i(accumulate), _stream()),
         "lpk_embed_bwd")

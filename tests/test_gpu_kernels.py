@@ -230,6 +230,16 @@ def test_embed_bwd_repeated_tokens(K):
     assert relerr(host(demb), ref) <= 1e-5
 
 
+def test_copy_bit_exact(K):
+    import torch
+    src = torch.randint(-2**31, 2**31 - 1, (1 << 20) + 12, device="cuda", dtype=torch.int32)
+    dst = torch.zeros_like(src)
+    K.lpk_copy(src, dst, src.numel() * 4)
+    assert torch.equal(src, dst)
+    with pytest.raises(RuntimeError):
+        K.lpk_copy(src, dst, 24)          # not a multiple of 16
+
+
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("N,H,C,O,R,stride,pad", [(3, 9, 5, 7, 3, 1, 1), (2, 8, 16, 24, 3, 2, 1), (2, 8, 16, 8, 1, 2, 0),
                                                   (4, 12, 3, 64, 3, 1, 1), (5, 14, 64, 136, 3, 1, 1),
