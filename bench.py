@@ -232,6 +232,7 @@ def main():
             ms, n, fl = lp.lp_profile_read(tr.ctx, kc)
             if n:
                 phases[name] = {"ms_per_step": ms / K, "ops_per_step": n / K, "flops_launched_per_step": fl / K}
+        shapes = lp.lp_profile_gemm_shapes(tr.ctx)
         lp.lp_profile_enable(tr.ctx, False)
         gf = gemm_flops_per_step(cfg)
         af, ab = attention_flops_per_step(cfg)
@@ -254,6 +255,11 @@ def main():
                         "avg_launch_ms": p["ms_per_step"] / p["ops_per_step"]}
         if "gemm" in phases:
             phases["gemm"]["algorithmic_tflops"] = gf / 1e12
+            phases["gemm"]["by_shape"] = [
+                {"M": r["M"], "N": r["N"], "K": r["K"], "layout": f"{r['a_kc']}{r['b_kc']}", "per_step": r["count"] / K,
+                 "avg_us": r["ms"] / r["count"] * 1e3,
+                 "tflops": 2.0 * r["M"] * r["N"] * r["K"] * r["count"] / (r["ms"] * 1e-3) / 1e12}
+                for r in sorted(shapes, key=lambda r: -r["ms"])[:16]]
         if "attn_fwd" in phases:
             phases["attn_fwd"]["achieved_tflops"] = af / (phases["attn_fwd"]["ms_per_step"] * 1e-3) / 1e12
         if "attn_bwd" in phases:

@@ -161,6 +161,10 @@ typedef enum {
   LP_KC_COLSUM, LP_KC_CONV, LP_KC_BATCHNORM, LP_KC_OTHER, LP_KC_COUNT
 } lp_kernel_class;
 int lp_profile_enable(lp_ctx* ctx, int on);
+/* GEMM ops by shape since profiling was enabled, as text into the host buffer `out` of `cap` bytes, one
+ * line per shape: "M N K a_kc b_kc c_f32 count total_ms" (operand layouts as in lpk_gemm).  LP_ESHAPE if
+ * the buffer is too small. */
+int lp_profile_gemm_shapes(lp_ctx* ctx, char* out, size_t cap);
 int lp_profile_read(lp_ctx* ctx, int kernel_class, double* total_ms, long long* launches, double* flops);
 
 /* Text of the last error on this context (or of the last failed init when ctx is NULL); valid

@@ -21,12 +21,15 @@ extern "C" {
  *   v (+= bias[n]); pre[m,n] = v; v = act(v); v *= act'(dact_src[m,n]); v += res[m,n].
  * A(m,k) = a_kc ? A[m*lda+k] : A[k*lda+m]; B(n,k) = b_kc ? B[n*ldb+k] : B[k*ldb+n]  (the forward, dgrad
  * and wgrad forms of a linear layer: paper appendix A, "MLP").  act / dact: 0 none, 1 ReLU, 2 GELU(tanh).
- * plain != 0 forces the FMA kernel instead of the MFMA kernel.  splitk_ws_dev (may be NULL) is fp32
- * workspace of splitk_ws_elems floats: with it, long reductions over few output tiles are split along k
- * and the partial sums added in a fixed order (at most 8 * M * N floats are used). */
+ * variant: 0 lets the library choose the kernel; 1 forces the FMA kernel; for bf16, 2 forces the
+ * register-staged MFMA kernel, 3 / 4 the direct-to-LDS kernel with 256 x 128 tiles and the last partial wave
+ * of tiles computed whole / cut along k, 5 / 6 the same with 256 x 256 tiles (an error if the shape does
+ * not qualify: K % 32 != 0, or no workspace for a cut).  splitk_ws_dev (may be NULL) is fp32 workspace of
+ * splitk_ws_elems floats: with it, reductions over few output tiles are split along k and the partial sums
+ * added in a fixed order (at most max(8 * M * N, 2^25) floats are used). */
 int lpk_gemm(int dtype, const void* A, int64_t lda, int a_kc, const void* B, int64_t ldb, int b_kc, void* C,
              int64_t ldc, int c_f32, int M, int N, int K, const float* bias, int act, void* pre,
-             const void* dact_src, int dact, int64_t ldd, const void* res, int64_t ldr, int accumulate, int plain,
+             const void* dact_src, int dact, int64_t ldd, const void* res, int64_t ldr, int accumulate, int variant,
              float* splitk_ws_dev, size_t splitk_ws_elems, void* stream);
 
 /* Causal (or full) multi-head attention of a decoder layer (appendix B.2).  qkv [B*S, 3*H*dh]

@@ -86,6 +86,7 @@ def lib() -> C.CDLL:
         L.lp_last_error.restype = C.c_char_p
         L.lp_profile_enable.argtypes = [vp, ip]
         L.lp_profile_read.argtypes = [vp, ip, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]
+        L.lp_profile_gemm_shapes.argtypes = [vp, C.c_char_p, sz]
         L.lp_destroy.argtypes = [vp]
         L.lp_destroy.restype = None
         _lib = L
@@ -194,6 +195,18 @@ def lp_profile_read(ctx: int, kernel_class: int):
     ms, n, fl = C.c_double(), C.c_longlong(), C.c_double()
     _check(lib().lp_profile_read(ctx, kernel_class, C.byref(ms), C.byref(n), C.byref(fl)), ctx)
     return ms.value, n.value, fl.value
+
+
+def lp_profile_gemm_shapes(ctx: int):
+    """GEMM ops by shape since profiling was enabled: dicts with M, N, K, a_kc, b_kc, c_f32, count, ms."""
+    buf = C.create_string_buffer(1 << 16)
+    _check(lib().lp_profile_gemm_shapes(ctx, buf, len(buf)), ctx)
+    rows = []
+    for line in buf.value.decode().splitlines():
+        M, N, K, a, b, f, n, ms = line.split()
+        rows.append({"M": int(M), "N": int(N), "K": int(K), "a_kc": int(a), "b_kc": int(b), "c_f32": int(f),
+                     "count": int(n), "ms": float(ms)})
+    return rows
 
 
 def lp_destroy(ctx: int) -> None:

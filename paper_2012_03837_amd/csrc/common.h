@@ -1,6 +1,7 @@
 // Shared declarations of the HIP library: element types, error plumbing, and the internal
 // kernel-launch API ("ops") that the layer drivers call.  gfx950 only.
 #pragma once
+#include <map>
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -69,9 +70,12 @@ enum KernelClass { KC_GEMM = 0, KC_ATTN_FWD, KC_ATTN_BWD, KC_LAYERNORM, KC_SOFTM
                    KC_COLSUM, KC_CONV, KC_BATCHNORM, KC_OTHER, KC_COUNT };
 struct Profiler {
   bool on = false;
-  struct Pair { hipEvent_t a, b; int kc; };
+  struct Pair { hipEvent_t a, b; int kc; uint64_t tag; };
   Pair* pairs = nullptr; int cap = 0; int used = 0; int dropped = 0;
   double total_ms[KC_COUNT] = {}; long long launches[KC_COUNT] = {}; double flops[KC_COUNT] = {};
+  // GEMM ops by shape: tag = M | N << 20 | K << 40 | a_kc << 60 | b_kc << 61 | c_f32 << 62
+  struct ShapeTotal { double ms = 0; long long n = 0; };
+  std::map<uint64_t, ShapeTotal> by_shape;
 };
 
 struct OpCtx {
@@ -80,6 +84,7 @@ struct OpCtx {
   float* partial;      // fp32 scratch for two-stage reductions
   size_t partial_elems;
   Profiler* prof = nullptr;
+  int gemm_variant = 0;         // 0: chosen by the cost model; otherwise a forced GEMM kernel (see lpk_gemm)
   float* splitk_ws = nullptr;   // fp32 workspace for split-K partial sums (may be null: no split-K)
   size_t splitk_elems = 0;
 };
@@ -87,12 +92,12 @@ struct OpCtx {
 // RAII bracket: records an event pair around the launches of one op when profiling is on.
 struct ProfScope {
   Profiler* p; hipStream_t s; int idx = -1;
-  ProfScope(const OpCtx& c, int kc, double flops = 0.0) : p(c.prof), s(c.stream) {
+  ProfScope(const OpCtx& c, int kc, double flops = 0.0, uint64_t tag = 0) : p(c.prof), s(c.stream) {
     if (!p || !p->on) { p = nullptr; return; }
     p->launches[kc] += 1; p->flops[kc] += flops;
     if (p->used >= p->cap) { p->dropped += 1; p = nullptr; return; }
     idx = p->used++;
-    p->pairs[idx].kc = kc;
+    p->pairs[idx].kc = kc; p->pairs[idx].tag = tag;
     (void)hipEventRecord(p->pairs[idx].a, s);
   }
   ~ProfScope() { if (p) (void)hipEventRecord(p->pairs[idx].b, s); }

@@ -12,6 +12,9 @@
 //   kc tile   [row][4 chunks of 8 k]   : chunk c of row r sits in slot c ^ ((r>>2)&3)
 //   k-major   [k][32.. chunks of 8 rows]: chunk j of k-row k sits in slot j ^ ((k&3)<<2)   (read with
 //                                         ds_read_b64_tr_b16, as in the register-staged kernel)
+// The grid is persistent (one block per resident slot): a block computes several whole tiles, starting the
+// next tile's loads before it writes the finished one, and the last partial wave of tiles is cut along k
+// so that every CU gets the same number of k-steps (see SkPlan).
 // One barrier per k-tile: wait until this thread's loads of tile t have landed (s_waitcnt vmcnt leaves
 // the younger tiles in flight), barrier, issue the loads of tile t+NSTAGE-1 into the stage that was read
 // during tile t-1, then 16 MFMAs per wave on tile t.  Requires K % 32 == 0 (no zero fill on this path).
@@ -154,53 +157,67 @@ __device__ __forceinline__ bf16x8 frag_t(const char* sm, int rowbase, int k) {
   return r;
 }
 
+// Work distribution of one launch.  The grid is persistent: G blocks, as many as are resident at once.
+//  - Tiles [0, full*G) are computed whole, `full` per block ("waves").  Block b sits on XCD b % 8 (the
+//    dispatcher deals blocks round-robin), so XCD x is given the contiguous tile range
+//    [x*full*G/8, (x+1)*full*G/8) and walks it G/8 tiles at a time: concurrent blocks of an XCD share
+//    operand rows/columns in its L2, and so do successive waves.
+//  - The remaining tail_tiles (< G unless upb == kt) are cut along k: the tail is tail_tiles*kt k-steps
+//    in tile-major order, block v takes k-steps [v*upb, (v+1)*upb).  A block's piece of a tile that is
+//    not the whole tile is written as raw fp32 partial sums to a slab of the workspace (slab 2v when the
+//    piece starts inside the tile, 2v+1 when it starts at the tile's first k-step), and k_sk_fixup adds
+//    the slabs of each tile in block order and applies the epilogue.  upb == kt degenerates to one whole
+//    tile per block and no partial sums.  No block ever waits for another.
+struct SkPlan {
+  int tiles_m, tiles_n, kt;
+  int full, tail_tiles, upb, G;
+};
+
+__device__ __forceinline__ void tile_coords(int q, int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int GROUP = 8;   // column-major groups of 8 tile rows
+  int width = GROUP * tiles_n, gid = q / width;
+  int first = gid * GROUP, gs = tiles_m - first < GROUP ? tiles_m - first : GROUP;
+  tm = first + (q % width) % gs;
+  tn = (q % width) / gs;
+}
+
+// Epilogue of one wave's 128 x 64 sub-tile: lane (li, hf) holds, for row m = ..+li of m-tile j, the
+// columns 32*i + 16*q + 8*hf .. +7 of n-tile i in acc[i][j][8q .. 8q+7].
+__device__ __forceinline__ void store_subtile(const Epilogue& e, const f32x16 (&acc)[2][4], int m_base, int n_base,
+                                              int li, int hf, int M, int N) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int m = m_base + 32 * j + li;
+    if (m >= M) continue;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int n = n_base + 32 * i + 16 * q + 8 * hf;
+        if (n >= N) continue;
+        float v[8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) v[x] = acc[i][j][8 * q + x];
+        epilogue8(e, m, n, v);
+      }
+  }
+}
+
+// Partial-sum slab of one block tile, in accumulator order: 16 bytes per lane, 1 KB per wave store.
+__device__ __forceinline__ size_t slab_index(int wave, int ij, int c, int lane) {
+  return ((((size_t)wave * 8 + ij) * 4 + c) * 64 + lane) * 4;
+}
+
 template <bool A_KC, bool B_KC, int NWN, int NSTAGE>
 __global__ void __launch_bounds__(128 * NWN, NWN == 4 ? 1 : 2)
-k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, int K, int tiles_m, int tiles_n, int splits, float* ws) {
+k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) {
   constexpr int BN = 64 * NWN, NWAVES = 2 * NWN;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int AI = (A_BYTES / 1024) / NWAVES, BI = (B_BYTES / 1024) / NWAVES, LPT = AI + BI;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int split = blockIdx.x % splits;
-  int pid = blockIdx.x / splits;
-  {
-    const int nb = tiles_m * tiles_n, per = nb / 8;
-    if (pid < per * 8) pid = (pid & 7) * per + (pid >> 3);
-    const int GROUP = 8;
-    int width = GROUP * tiles_n, gid = pid / width;
-    int first = gid * GROUP, gs = tiles_m - first < GROUP ? tiles_m - first : GROUP;
-    int tm = first + (pid % width) % gs, tn = (pid % width) / gs;
-    pid = tm * tiles_n + tn;
-  }
-  const int m0 = (pid / tiles_n) * BM, n0 = (pid % tiles_n) * BN;
   const int wm = (wave / NWN) * 128, wn = (wave % NWN) * 64;
-
-  const int nt_all = K / BK, per_split = (nt_all + splits - 1) / splits;
-  const int t_first = split * per_split;
-  const int nt = nt_all - t_first < per_split ? (nt_all - t_first > 0 ? nt_all - t_first : 0) : per_split;
-
-  DmaPlan<A_KC, BM, AI> pa;
-  DmaPlan<B_KC, BN, BI> pb;
-  pa.init(A, m0, wave, lane, t_first * BK);
-  pb.init(B, n0, wave, lane, t_first * BK);
-
-  f32x16 acc[2][4];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-#pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s)
-    if (s < nt) {
-      pa.issue(smem + s * STAGE_BYTES, s);
-      pb.issue(smem + s * STAGE_BYTES + A_BYTES, s);
-    }
-
   const int li = lane & 31, hf = lane >> 5;
   const int n_row = nmap(li);
   const int c4 = lane & 3, half16 = (lane >> 4) & 1;
@@ -208,72 +225,159 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, int K, int tiles_m, i
   const int m_rowbase_t = 16 * half16 + 4 * c4;
   const int kq = (lane & 15) >> 2;
 
-  // Fragments of one 16-wide k-step: 2 on the n side, 4 on the m side.
-  auto read_frags = [&](const char* as, const char* bs, int ks, bf16x8* fn, bf16x8* fm) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-      fn[i] = B_KC ? frag_kc(bs, wn + 32 * i + n_row, 2 * ks + hf)
-                   : frag_t<BN>(bs, wn + 32 * i + n_rowbase_t, 16 * ks + 8 * hf + kq);
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      fm[j] = A_KC ? frag_kc(as, wm + 32 * j + li, 2 * ks + hf)
-                   : frag_t<BM>(as, wm + 32 * j + m_rowbase_t, 16 * ks + 8 * hf + kq);
+  // this block's work: `full` whole tiles, then k-steps [u, ue) of the tail
+  const int Gx = p.G >> 3, xcd = blockIdx.x & 7, slot_in_xcd = blockIdx.x >> 3;
+  const int v = xcd * Gx + slot_in_xcd;
+  const long tail_steps = (long)p.tail_tiles * p.kt;
+  long u = (long)v * p.upb, ue = u + p.upb;
+  if (ue > tail_steps) ue = tail_steps;
+  int w = 0;
+  int q = 0, ks = 0, ke = 0;          // current item: tile q, k-steps [ks, ke)
+  auto next_item = [&]() -> bool {
+    if (w < p.full) { q = (xcd * p.full + w) * Gx + slot_in_xcd; ks = 0; ke = p.kt; ++w; return true; }
+    if (u < ue) {
+      const int tr = (int)(u / p.kt);
+      ks = (int)(u - (long)tr * p.kt);
+      const long len = (p.kt - ks) < (ue - u) ? (p.kt - ks) : (ue - u);
+      ke = ks + (int)len;
+      q = p.full * p.G + tr;
+      u += len;
+      return true;
+    }
+    return false;
   };
-  auto mma = [&](const bf16x8* fn, const bf16x8* fm) {
+
+  DmaPlan<A_KC, BM, AI> pa;
+  DmaPlan<B_KC, BN, BI> pb;
+  int m0 = 0, n0 = 0, nt = 0;
+  auto start_item = [&]() {          // addresses of the item's operands and the first NSTAGE-1 k-tiles' loads
+    int tm, tn;
+    tile_coords(q, p.tiles_m, p.tiles_n, tm, tn);
+    m0 = tm * BM; n0 = tn * BN; nt = ke - ks;
+    pa.init(A, m0, wave, lane, ks * BK);
+    pb.init(B, n0, wave, lane, ks * BK);
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s)
+      if (s < nt) {
+        pa.issue(smem + s * STAGE_BYTES, s);
+        pb.issue(smem + s * STAGE_BYTES + A_BYTES, s);
+      }
+  };
+
+  bool have = next_item();
+  if (have) start_item();
+  while (have) {
+    f32x16 acc[2][4];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
-  };
+#pragma unroll
+        for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.f;
 
-  for (int t = 0; t < nt; ++t) {
-    // loads of tile t are the oldest outstanding; the younger tiles (at most NSTAGE-2) stay in flight
-    if (t + NSTAGE - 2 < nt) wait_loads_and_barrier<(NSTAGE - 2) * LPT>();
-    else if (NSTAGE > 3 && t + NSTAGE - 3 < nt) wait_loads_and_barrier<(NSTAGE > 3 ? NSTAGE - 3 : 0) * LPT>();
-    else wait_loads_and_barrier<0>();
-    if (t + NSTAGE - 1 < nt) {
-      char* dst = smem + ((t + NSTAGE - 1) % NSTAGE) * STAGE_BYTES;
-      pa.issue(dst, t + NSTAGE - 1);
-      pb.issue(dst + A_BYTES, t + NSTAGE - 1);
-    }
-    const char* as = smem + (t % NSTAGE) * STAGE_BYTES;
-    const char* bs = as + A_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 fn[2], fm[4];
-      read_frags(as, bs, ks, fn, fm);
-      mma(fn, fm);
-    }
-  }
-
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int m = m0 + wm + 32 * j + li;
-    if (m >= M) continue;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const int n = n0 + wn + 32 * i + 16 * q + 8 * hf;
-        if (n >= N) continue;
-        float v[8];
-#pragma unroll
-        for (int x = 0; x < 8; ++x) v[x] = acc[i][j][8 * q + x];
-        if (splits > 1) {
-          float* wp = ws + ((size_t)split * M + m) * N + n;
-          f32x4 o0 = {v[0], v[1], v[2], v[3]}, o1 = {v[4], v[5], v[6], v[7]};
-          *reinterpret_cast<f32x4*>(wp) = o0;
-          *reinterpret_cast<f32x4*>(wp + 4) = o1;
-        } else {
-          epilogue8(e, m, n, v);
-        }
+    for (int t = 0; t < nt; ++t) {
+      // The loads of k-tile t are this thread's oldest outstanding loads; the younger k-tiles (at most
+      // NSTAGE-2) stay in flight.  The first k-tile of an item waits for everything: behind the loads
+      // issued by start_item sit the previous item's epilogue stores.
+      if (t == 0) wait_loads_and_barrier<0>();
+      else if (t + NSTAGE - 2 < nt) wait_loads_and_barrier<(NSTAGE - 2) * LPT>();
+      else if (NSTAGE > 3 && t + NSTAGE - 3 < nt) wait_loads_and_barrier<(NSTAGE > 3 ? NSTAGE - 3 : 0) * LPT>();
+      else wait_loads_and_barrier<0>();
+      if (t + NSTAGE - 1 < nt) {
+        char* dst = smem + ((t + NSTAGE - 1) % NSTAGE) * STAGE_BYTES;
+        pa.issue(dst, t + NSTAGE - 1);
+        pb.issue(dst + A_BYTES, t + NSTAGE - 1);
       }
+      const char* as = smem + (t % NSTAGE) * STAGE_BYTES;
+      const char* bs = as + A_BYTES;
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        bf16x8 fn[2], fm[4];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          fn[i] = B_KC ? frag_kc(bs, wn + 32 * i + n_row, 2 * kk + hf)
+                       : frag_t<BN>(bs, wn + 32 * i + n_rowbase_t, 16 * kk + 8 * hf + kq);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          fm[j] = A_KC ? frag_kc(as, wm + 32 * j + li, 2 * kk + hf)
+                       : frag_t<BM>(as, wm + 32 * j + m_rowbase_t, 16 * kk + 8 * hf + kq);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
+      }
+    }
+
+    // this item's output coordinates, before the next item replaces them
+    const int cm = m0 + wm, cn = n0 + wn;
+    const bool whole = ks == 0 && ke == p.kt;
+    const int slab = 2 * v + (ks == 0 ? 1 : 0);
+    have = next_item();
+    // every wave is done reading the LDS stages: the next item's first loads may overwrite them, and
+    // they fly while this item's results are written
+    asm volatile("s_barrier" ::: "memory");
+    if (have) start_item();
+    if (whole) {
+      store_subtile(e, acc, cm, cn, li, hf, M, N);
+    } else {
+      float* sp = ws + (size_t)slab * (BM * BN);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            f32x4 o = {acc[i][j][4 * c], acc[i][j][4 * c + 1], acc[i][j][4 * c + 2], acc[i][j][4 * c + 3]};
+            *reinterpret_cast<f32x4*>(sp + slab_index(wave, i * 4 + j, c, lane)) = o;
+          }
+    }
   }
 }
 
+// Adds the partial-sum slabs of every tail tile that was cut, in block order, and applies the epilogue.
+// One thread per run of 8 columns (the unit of the fused epilogue), with the main kernel's
+// lane-to-element mapping: thread (wave, ij, q, lane) owns acc[i][j][8q .. 8q+7] of that lane.
+template <int NWN>
+__global__ void __launch_bounds__(256) k_sk_fixup(const float* __restrict__ ws, Epilogue e, int M, int N, SkPlan p) {
+  constexpr int BN = 64 * NWN, NWAVES = 2 * NWN, BLOCKS_PER_TILE = NWAVES * 16 * 64 / 256;
+  const int tr = blockIdx.x / BLOCKS_PER_TILE;
+  const int unit = (blockIdx.x % BLOCKS_PER_TILE) * 4 + (threadIdx.x >> 6);      // (wave, ij, q)
+  const int lane = threadIdx.x & 63;
+  const int wave = unit >> 4, ij = (unit >> 1) & 7, q = unit & 1;
+  const long u0 = (long)tr * p.kt, u1 = u0 + p.kt;
+  const int v_lo = (int)(u0 / p.upb), v_hi = (int)((u1 - 1) / p.upb);
+  if (v_lo == v_hi) return;            // computed whole by one block
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int v = v_lo; v <= v_hi; ++v) {
+    const int slab = 2 * v + ((long)v * p.upb <= u0 ? 1 : 0);
+    const float* sp = ws + (size_t)slab * (BM * BN);
+    f32x4 a = *reinterpret_cast<const f32x4*>(sp + slab_index(wave, ij, 2 * q, lane));
+    f32x4 b = *reinterpret_cast<const f32x4*>(sp + slab_index(wave, ij, 2 * q + 1, lane));
+#pragma unroll
+    for (int x = 0; x < 4; ++x) { acc[x] += a[x]; acc[4 + x] += b[x]; }
+  }
+  int tm, tn;
+  tile_coords(p.full * p.G + tr, p.tiles_m, p.tiles_n, tm, tn);
+  const int i = ij >> 2, j = ij & 3, li = lane & 31, hf = lane >> 5;
+  const int m = tm * BM + (wave / NWN) * 128 + 32 * j + li;
+  const int n = tn * BN + (wave % NWN) * 64 + 32 * i + 16 * q + 8 * hf;
+  if (m < M && n < N) epilogue8(e, m, n, acc);
+}
+
+int device_cus() {
+  static int n = 0;
+  if (!n) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 8)
+      v = 256;
+    n = v;
+  }
+  return n;
+}
+
 template <bool A_KC, bool B_KC, int NWN, int NSTAGE>
-hipError_t launch(const OpCtx& c, const GemmArgs& g, int splits) {
+hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool partials) {
   constexpr int BN = 64 * NWN;
   constexpr int smem = NSTAGE * (BM + BN) * BK * 2;
   static bool configured = false;
@@ -284,9 +388,11 @@ hipError_t launch(const OpCtx& c, const GemmArgs& g, int splits) {
     configured = true;
   }
   Operand A{(const bf16_t*)g.A, g.lda, g.M}, B{(const bf16_t*)g.B, g.ldb, g.N};
-  int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
-  kern<<<dim3(tm * tn * splits), 128 * NWN, smem, c.stream>>>(A, B, make_epilogue(g), g.M, g.N, g.K, tm, tn, splits,
-                                                             c.splitk_ws);
+  Epilogue e = make_epilogue(g);
+  kern<<<dim3(p.G), 128 * NWN, smem, c.stream>>>(A, B, e, g.M, g.N, p, c.splitk_ws);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess || !partials) return err;
+  k_sk_fixup<NWN><<<dim3(p.tail_tiles * (2 * NWN * 16 * 64 / 256)), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, p);
   return hipGetLastError();
 }
 
@@ -296,9 +402,59 @@ hipError_t launch(const OpCtx& c, const GemmArgs& g, int splits) {
 // 8-row chunk column set (rows >= 8, rows % 8 == 0 is already required by the caller's checks).
 bool gemm_dma_ok(const GemmArgs& g) { return g.K % 32 == 0 && g.K >= 32 && g.M >= 8 && g.N >= 8; }
 
-// nwn = 4: 256 x 256 tiles; nwn = 2: 256 x 128 tiles.
-hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, int nwn, int splits) {
-#define LP_DMA(AK, BK_) (nwn == 4 ? launch<AK, BK_, 4, 4>(c, g, splits) : launch<AK, BK_, 2, 3>(c, g, splits))
+// Distribution of an M x N x K problem over the persistent grid of the variant with 64*nwn-column tiles.
+// cut_tail: cut the last, partial wave of tiles along k (needs workspace); otherwise one tile per block.
+// Returns false if the workspace cannot hold the partial sums.  *partial_bytes = bytes of partial sums
+// written (and read again), *steps = k-steps on the longest block.
+bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int nwn, bool cut_tail, DmaGemmPlan* out) {
+  const int bn = 64 * nwn, per_cu = nwn == 4 ? 1 : 2;
+  SkPlan p;
+  p.G = (device_cus() * per_cu) & ~7;
+  p.tiles_m = (g.M + BM - 1) / BM;
+  p.tiles_n = (g.N + bn - 1) / bn;
+  p.kt = g.K / BK;
+  const long T = (long)p.tiles_m * p.tiles_n;
+  p.full = (int)(T / p.G);
+  p.tail_tiles = (int)(T - (long)p.full * p.G);
+  p.upb = p.kt;
+  long partial_slabs = 0;
+  if (cut_tail && p.tail_tiles > 0) {
+    const long U = (long)p.tail_tiles * p.kt;
+    long upb = (U + p.G - 1) / p.G;
+    const long min_len = 4, max_cut = 16;                 // shortest piece; most pieces per tile
+    if (upb < min_len) upb = min_len;
+    if (upb * max_cut < p.kt) upb = (p.kt + max_cut - 1) / max_cut;
+    if (upb > p.kt) upb = p.kt;
+    p.upb = (int)upb;
+    if (p.upb < p.kt) {
+      // count the pieces that are not whole tiles
+      const long blocks = (U + upb - 1) / upb;
+      for (long v = 0; v < blocks; ++v) {
+        long u = v * upb, ue = u + upb < U ? u + upb : U;
+        while (u < ue) {
+          long tr = u / p.kt, ks = u - tr * p.kt, len = (p.kt - ks) < (ue - u) ? (p.kt - ks) : (ue - u);
+          if (!(ks == 0 && len == p.kt)) ++partial_slabs;
+          u += len;
+        }
+      }
+      if (!c.splitk_ws || (size_t)2 * p.G * BM * bn > c.splitk_elems) return false;
+    }
+  }
+  out->nwn = nwn;
+  out->full = p.full; out->tail_tiles = p.tail_tiles; out->upb = p.upb; out->G = p.G; out->kt = p.kt;
+  out->tiles_m = p.tiles_m; out->tiles_n = p.tiles_n;
+  out->partial_bytes = (double)partial_slabs * BM * bn * 4.0;
+  out->steps = (long)p.full * p.kt + (p.tail_tiles > 0 ? p.upb : 0);
+  out->items = p.full + (p.tail_tiles > 0 ? (p.upb < p.kt ? 2 : 1) : 0);
+  return true;
+}
+
+hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d) {
+  SkPlan p;
+  p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.kt = d.kt; p.full = d.full; p.tail_tiles = d.tail_tiles;
+  p.upb = d.upb; p.G = d.G;
+  const bool partials = d.partial_bytes > 0;
+#define LP_DMA(AK, BK_) (d.nwn == 4 ? launch<AK, BK_, 4, 4>(c, g, p, partials) : launch<AK, BK_, 2, 3>(c, g, p, partials))
   if (g.a_kc && g.b_kc) return LP_DMA(true, true);
   if (g.a_kc && !g.b_kc) return LP_DMA(true, false);
   if (!g.a_kc && g.b_kc) return LP_DMA(false, true);

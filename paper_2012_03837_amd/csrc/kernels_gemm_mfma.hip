@@ -21,7 +21,8 @@ namespace lp {
 
 hipError_t gemm_plain(const OpCtx& c, const GemmArgs& g);
 bool gemm_dma_ok(const GemmArgs& g);
-hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, int nwn, int splits);
+bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int nwn, bool cut_tail, DmaGemmPlan* out);
+hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d);
 
 namespace {
 
@@ -60,77 +61,97 @@ bool fast_ok(const GemmArgs& g) {
 
 }  // namespace
 
-// Tile and split choice.  Big tiles when they fill the chip; otherwise 128-row tiles, and for long
-// reductions over few tiles (weight gradients over all tokens, the head's input gradient over the
-// vocabulary) split-K with fp32 partials summed in split order by a second kernel.
-static int kernel_choice() {   // LP_GEMM_KERNEL = auto | v2 | dma4 | dma2 (for measurements)
+// Forced kernel family: 0 none; 2 register-staged; 3 / 4 direct-to-LDS 256 x 128 with the tail whole / cut
+// along k; 5 / 6 the same for 256 x 256; 7 / 8 256 x 128 / 256 x 256 with either tail.
+// LP_GEMM_KERNEL = v2 | dma2 | dma4 (| dma2w, dma2c, dma4w, dma4c) sets 2 / 7 / 8 (3, 4, 5, 6) for a whole
+// process (for measurements); a shape the forced kernel does not take falls back to the register-staged one.
+static int env_choice() {
   static int v = -1;
   if (v < 0) {
     const char* s = getenv("LP_GEMM_KERNEL");
-    v = !s ? 0 : (s[0] == 'v' ? 1 : (s[0] == 'd' && s[3] == '4' ? 2 : (s[0] == 'd' && s[3] == '2' ? 3 : 0)));
+    v = !s ? 0 : (s[0] == 'v' ? 2 : (s[0] == 'd' && s[3] == '2' ? 7 : (s[0] == 'd' && s[3] == '4' ? 8 : 0)));
+    if (v >= 7 && s[4] == 'w') v = v == 7 ? 3 : 5;        // dma2w / dma4w: tail computed whole
+    else if (v >= 7 && s[4] == 'c') v = v == 7 ? 4 : 6;   // dma2c / dma4c: tail cut along k
   }
   return v;
 }
 
-// Kernel variants and a small cost model to choose among them.  A variant is a tile shape with a
-// number of resident blocks per CU and a measured sustained rate for a full CU; the estimate is
-// rounds x (tile time + fixed fill/drain time) plus the traffic of split-K partial sums.
-struct Variant { int kind; int bm, bn; int per_cu; double flops_per_cycle_cu; double fixed_cycles; };
-static const Variant kVariants[] = {
-    {2, 256, 256, 1, 1700.0, 9000.0},   // direct-to-LDS, 8 waves, 4 stages
-    {3, 256, 128, 2, 1500.0, 7000.0},   // direct-to-LDS, 4 waves, 3 stages
-    {1, 256, 128, 2, 1300.0, 6000.0},   // register-staged, big tile
-    {0, 128, 128, 2, 1000.0, 5000.0},   // register-staged, small tile
+// A small cost model picks the kernel.  Each variant has a measured cost per 32-deep k-step of one block
+// and a fixed cost per tile (pipeline fill, epilogue); split-K and the k-cut tail add the traffic of
+// their fp32 partial sums and a second launch.
+static const double kPartialBytesPerCycle = 4.0e12 / 2.4e9;   // partial sums: written, then read once more
+static const double kSecondLaunchCycles = 12000.0;
+struct TileVariant { int bm; int per_cu; double step_cycles; double fixed_cycles; };
+static const TileVariant kRegStaged[2] = {
+    {128, 2, 2097.0, 5000.0},     // 128 x 128, two blocks per CU share the CU: cycles per step per block
+    {256, 2, 3226.0, 6000.0},     // 256 x 128
 };
+static double dma_bias() {   // LP_GEMM_DMA_BIAS scales the direct-to-LDS kernel's estimated cost (for measurements)
+  static double v = -1.0;
+  if (v < 0) { const char* s = getenv("LP_GEMM_DMA_BIAS"); v = s ? atof(s) : 1.0; if (!(v > 0)) v = 1.0; }
+  return v;
+}
+static const double kDmaStep[2] = {2796.0, 2467.0};      // 256 x 128 (two per CU), 256 x 256
+static const double kDmaFixed[2] = {7000.0, 9000.0};
 
 hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
-  const int choice = kernel_choice();
-  const bool dma_ok = gemm_dma_ok(g);
-  const double flops = 2.0 * g.M * g.N * g.K;
+  const int choice = c.gemm_variant ? c.gemm_variant : env_choice();
   double best = 1e300;
-  int best_v = 3, best_s = 1;
-  for (int vi = 0; vi < 4; ++vi) {
-    const Variant& v = kVariants[vi];
-    if ((v.kind >= 2) && !dma_ok) continue;
-    if (choice == 1 && v.kind >= 2) continue;
-    if (choice == 2 && v.kind != 2) continue;
-    if (choice == 3 && v.kind != 3) continue;
-    const long tiles = (long)((g.M + v.bm - 1) / v.bm) * ((g.N + v.bn - 1) / v.bn);
-    const long slots = 256L * v.per_cu;
-    for (int sp = 1; sp <= 8; ++sp) {
-      if (sp > 1 && (!c.splitk_ws || g.K / sp < 512 || (size_t)sp * g.M * g.N > c.splitk_elems)) break;
-      const long blocks = tiles * sp;
-      const long rounds = (blocks + slots - 1) / slots;
-      const double tile_cycles = 2.0 * v.bm * v.bn * ((double)g.K / sp) / (v.flops_per_cycle_cu / v.per_cu);
-      double cycles = rounds * (tile_cycles + v.fixed_cycles);
-      if (sp > 1) cycles += 2.0 * sp * (double)g.M * g.N * 4.0 / (5.0e12 / 2.4e9) + 12000.0;
-      if (cycles < best) { best = cycles; best_v = vi; best_s = sp; }
+  // direct-to-LDS persistent kernel: two tile widths, tail whole or cut along k
+  DmaGemmPlan best_dma;
+  bool use_dma = false;
+  if (gemm_dma_ok(g) && choice != 2) {
+    for (int wi = 0; wi < 2; ++wi) {
+      if (((choice == 3 || choice == 4 || choice == 7) && wi == 1) || ((choice == 5 || choice == 6 || choice == 8) && wi == 0))
+        continue;
+      for (int cut = 0; cut < 2; ++cut) {
+        if (((choice == 3 || choice == 5) && cut) || ((choice == 4 || choice == 6) && !cut)) continue;
+        DmaGemmPlan d;
+        if (!gemm_dma_plan(c, g, wi ? 4 : 2, cut != 0, &d)) continue;
+        if (cut && d.partial_bytes == 0 && choice < 3) continue;         // same as the uncut plan
+        double cycles = d.steps * kDmaStep[wi] + d.items * kDmaFixed[wi];
+        if (d.partial_bytes > 0) cycles += 2.0 * d.partial_bytes / kPartialBytesPerCycle + kSecondLaunchCycles;
+        cycles *= dma_bias();
+        if (cycles < best) { best = cycles; best_dma = d; use_dma = true; }
+      }
     }
   }
-  (void)flops;
-  const Variant& v = kVariants[best_v];
+  // register-staged kernel: any aligned shape, uniform split-K
+  int best_v = 0, best_s = 1;
+  if (c.gemm_variant > 2 && !use_dma) return hipErrorInvalidValue;   // the forced kernel does not take this shape
+  if (choice <= 2 || !use_dma) {
+    for (int vi = 0; vi < 2; ++vi) {
+      const TileVariant& v = kRegStaged[vi];
+      const long tiles = (long)((g.M + v.bm - 1) / v.bm) * ((g.N + BN - 1) / BN);
+      const long slots = 256L * v.per_cu;
+      for (int sp = 1; sp <= 8; ++sp) {
+        if (sp > 1 && (!c.splitk_ws || g.K / sp < 512 || (size_t)sp * g.M * g.N > c.splitk_elems)) break;
+        const long rounds = (tiles * sp + slots - 1) / slots;
+        double cycles = rounds * (((double)g.K / sp / BK) * v.step_cycles + v.fixed_cycles);
+        if (sp > 1) cycles += 2.0 * sp * (double)g.M * g.N * 4.0 / kPartialBytesPerCycle + kSecondLaunchCycles;
+        if (cycles < best) { best = cycles; best_v = vi; best_s = sp; use_dma = false; }
+      }
+    }
+  }
+  if (use_dma) return gemm_dma(c, g, best_dma);
+
   const int splits = best_s;
   Epilogue e = make_epilogue(g);
-  hipError_t err;
-  if (v.kind >= 2) {
-    err = gemm_dma(c, g, v.kind == 2 ? 4 : 2, splits);
-  } else {
-    Operand A{(const bf16_t*)g.A, g.lda, g.M}, B{(const bf16_t*)g.B, g.ldb, g.N};
-    const int bm = v.bm, tn = (g.N + BN - 1) / BN, tm = (g.M + bm - 1) / bm;
-    dim3 grid(tm * tn * splits);
+  Operand A{(const bf16_t*)g.A, g.lda, g.M}, B{(const bf16_t*)g.B, g.ldb, g.N};
+  const int bm = kRegStaged[best_v].bm, tn = (g.N + BN - 1) / BN, tm = (g.M + bm - 1) / bm;
+  dim3 grid(tm * tn * splits);
 #define LP_GEMM(AK, BK_, BM_)                                                                             \
   k_mfma_tiles<PlainLoader<AK>, PlainLoader<BK_>, BM_><<<grid, 256, 0, c.stream>>>(                       \
       PlainLoader<AK>{A}, PlainLoader<BK_>{B}, e, g.M, g.N, g.K, tm, tn, splits, c.splitk_ws)
 #define LP_GEMM_BM(AK, BK_) do { if (bm == 256) LP_GEMM(AK, BK_, 256); else LP_GEMM(AK, BK_, 128); } while (0)
-    if (g.a_kc && g.b_kc) LP_GEMM_BM(true, true);
-    else if (g.a_kc && !g.b_kc) LP_GEMM_BM(true, false);
-    else if (!g.a_kc && g.b_kc) LP_GEMM_BM(false, true);
-    else LP_GEMM_BM(false, false);
+  if (g.a_kc && g.b_kc) LP_GEMM_BM(true, true);
+  else if (g.a_kc && !g.b_kc) LP_GEMM_BM(true, false);
+  else if (!g.a_kc && g.b_kc) LP_GEMM_BM(false, true);
+  else LP_GEMM_BM(false, false);
 #undef LP_GEMM_BM
 #undef LP_GEMM
-    err = hipGetLastError();
-  }
+  hipError_t err = hipGetLastError();
   if (err != hipSuccess || splits == 1) return err;
   size_t work = (size_t)g.M * (g.N / 8);
   k_splitk_reduce<<<(unsigned)((work + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, splits);
@@ -144,7 +165,10 @@ static int use_plain() {
 }
 
 hipError_t op_gemm(const OpCtx& c, const GemmArgs& g) {
-  ProfScope prof_(c, KC_GEMM, 2.0 * g.M * g.N * g.K);
+  const uint64_t tag = (uint64_t)(g.M & 0xfffff) | (uint64_t)(g.N & 0xfffff) << 20 | (uint64_t)(g.K & 0xfffff) << 40 |
+                       (uint64_t)(g.a_kc != 0) << 60 | (uint64_t)(g.b_kc != 0) << 61 | (uint64_t)(g.c_f32 != 0) << 62;
+  ProfScope prof_(c, KC_GEMM, 2.0 * g.M * g.N * g.K, tag);
+  if (c.gemm_variant >= 2 && !(c.dt == BF16 && fast_ok(g))) return hipErrorInvalidValue;
   if (c.dt == BF16 && !use_plain() && fast_ok(g)) return gemm_mfma(c, g);
   return gemm_plain(c, g);
 }

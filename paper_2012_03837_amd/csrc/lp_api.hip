@@ -415,6 +415,7 @@ static int prof_collect(lp_ctx* c) {
     float ms = 0.f;
     CK(hipEventElapsedTime(&ms, c->prof.pairs[i].a, c->prof.pairs[i].b));
     c->prof.total_ms[c->prof.pairs[i].kc] += ms;
+    if (c->prof.pairs[i].tag) { auto& t = c->prof.by_shape[c->prof.pairs[i].tag]; t.ms += ms; t.n += 1; }
   }
   c->prof.used = 0;
   return LP_OK;
@@ -437,6 +438,7 @@ extern "C" int lp_profile_enable(lp_ctx* c, int on) {
     if (st != LP_OK) return st;
     for (int k = 0; k < KC_COUNT; ++k) { c->prof.total_ms[k] = 0; c->prof.launches[k] = 0; c->prof.flops[k] = 0; }
     c->prof.dropped = 0;
+    c->prof.by_shape.clear();
   }
   c->prof.on = on != 0;
   return LP_OK;
@@ -451,6 +453,24 @@ extern "C" int lp_profile_read(lp_ctx* c, int kernel_class, double* total_ms, lo
   if (total_ms) *total_ms = c->prof.total_ms[kernel_class];
   if (launches) *launches = c->prof.launches[kernel_class];
   if (flops) *flops = c->prof.flops[kernel_class];
+  return LP_OK;
+}
+
+extern "C" int lp_profile_gemm_shapes(lp_ctx* c, char* out, size_t cap) {
+  if (!c) return LP_EINVAL;
+  if (!out || cap == 0) return fail(c, LP_EINVAL, "out is null or empty");
+  int st = prof_collect(c);
+  if (st != LP_OK) return st;
+  std::string text;
+  for (const auto& kv : c->prof.by_shape) {
+    const uint64_t t = kv.first;
+    char line[160];
+    snprintf(line, sizeof line, "%d %d %d %d %d %d %lld %.6f\n", (int)(t & 0xfffff), (int)(t >> 20 & 0xfffff),
+             (int)(t >> 40 & 0xfffff), (int)(t >> 60 & 1), (int)(t >> 61 & 1), (int)(t >> 62 & 1), kv.second.n, kv.second.ms);
+    text += line;
+  }
+  if (text.size() + 1 > cap) return fail(c, LP_ESHAPE, "buffer too small for the shape table");
+  memcpy(out, text.c_str(), text.size() + 1);
   return LP_OK;
 }
 

@@ -28,14 +28,16 @@ static ConvArgs mkconv(int N, int H, int W, int C, int O, int R, int stride, int
 extern "C" int lpk_gemm(int dtype, const void* A, int64_t lda, int a_kc, const void* B, int64_t ldb, int b_kc, void* C,
                         int64_t ldc, int c_f32, int M, int N, int K, const float* bias, int act, void* pre,
                         const void* dact_src, int dact, int64_t ldd, const void* res, int64_t ldr, int accumulate,
-                        int plain, float* splitk_ws, size_t splitk_ws_elems, void* stream) {
+                        int variant, float* splitk_ws, size_t splitk_ws_elems, void* stream) {
+  if (variant < 0 || variant > 6) return (int)hipErrorInvalidValue;
   GemmArgs g;
   g.A = A; g.lda = lda; g.a_kc = a_kc; g.B = B; g.ldb = ldb; g.b_kc = b_kc; g.C = C; g.ldc = ldc; g.c_f32 = c_f32;
   g.M = M; g.N = N; g.K = K; g.bias = bias; g.act = act; g.pre = pre; g.dact_src = dact_src; g.dact = dact; g.ldd = ldd;
   g.res = res; g.ldr = ldr; g.accumulate = accumulate;
   OpCtx c = mk(dtype, stream);
   c.splitk_ws = splitk_ws; c.splitk_elems = splitk_ws_elems;
-  if (plain || dtype != BF16) return (int)gemm_plain(c, g);
+  if (variant == 1 || dtype != BF16) return (int)gemm_plain(c, g);
+  c.gemm_variant = variant;
   return (int)op_gemm(c, g);
 }
 extern "C" int lpk_attention_fwd(int dtype, const void* qkv, void* o, float* lse, int B, int S, int H, int dh,

@@ -29,10 +29,11 @@ _i, _i64, _f, _sz = C.c_int, C.c_int64, C.c_float, C.c_size_t
 
 
 def lpk_gemm(dtype, A, lda, a_kc, B, ldb, b_kc, Cout, ldc, c_f32, M, N, K, bias=None, act=0, pre=None, dact_src=None,
-             dact=0, ldd=0, res=None, ldr=0, accumulate=0, plain=0, splitk_ws=None):
+             dact=0, ldd=0, res=None, ldr=0, accumulate=0, plain=0, splitk_ws=None, variant=None):
+    variant = (1 if plain else 0) if variant is None else variant
     _ck(lib().lpk_gemm(_i(dtype), _p(A), _i64(lda), _i(a_kc), _p(B), _i64(ldb), _i(b_kc), _p(Cout), _i64(ldc),
                        _i(c_f32), _i(M), _i(N), _i(K), _p(bias), _i(act), _p(pre), _p(dact_src), _i(dact), _i64(ldd),
-                       _p(res), _i64(ldr), _i(accumulate), _i(plain), _p(splitk_ws),
+                       _p(res), _i64(ldr), _i(accumulate), _i(variant), _p(splitk_ws),
                        _sz(0 if splitk_ws is None else splitk_ws.numel()), _stream()), "lpk_gemm")
 
 

@@ -230,9 +230,55 @@ def test_embed_bwd_repeated_tokens(K):
     assert relerr(host(demb), ref) <= 1e-5
 
 
+# Shapes for the persistent direct-to-LDS GEMM: fewer tiles than blocks, exactly one wave of tiles,
+# whole waves plus a tail, ragged edges in m and n, reductions shorter than the LDS ring.
+DMA_SHAPES = [(520, 264, 4096), (4096, 4096, 64), (4104, 4360, 96), (8192, 776, 768), (2056, 8200, 32),
+              (6000, 12000, 160), (264, 136, 16384)]
+
+
+@pytest.mark.parametrize("variant", [3, 4, 5, 6])
+@pytest.mark.parametrize("a_kc,b_kc", [(1, 1), (1, 0), (0, 0), (0, 1)])
+def test_gemm_persistent_variants(K, variant, a_kc, b_kc):
+    import torch
+    rng = np.random.default_rng(11)
+    ws = zeros(1 << 25)
+    for (M, N, Kd) in DMA_SHAPES:
+        A = rnd(rng, (M, Kd), 1, 0.5)
+        B = rnd(rng, (N, Kd), 1, 0.5)
+        Am = A if a_kc else np.ascontiguousarray(A.T)
+        Bm = B if b_kc else np.ascontiguousarray(B.T)
+        dA, dB = dev(Am, 1), dev(Bm, 1)
+        ref = torch.from_numpy(A).cuda().double() @ torch.from_numpy(B).cuda().double().T   # library matmul in fp64
+        out = torch.full((M, N), 7.0, device="cuda", dtype=torch.float32)
+        K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out, N, 1, M, N, Kd, variant=variant, splitk_ws=ws)
+        err = float((out.double() - ref).norm() / ref.norm())
+        assert err <= 2e-6, (M, N, Kd, variant, err)
+        # bias + residual epilogue into bf16, applied once even where a tile is summed from pieces
+        bias = rng.standard_normal(N).astype(np.float32)
+        res = rnd(rng, (M, N), 1)
+        outb = torch.zeros(M, N, device="cuda", dtype=torch.bfloat16)
+        K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, outb, N, 0, M, N, Kd, bias=dev(bias, 0),
+                   res=dev(res, 1), ldr=N, variant=variant, splitk_ws=ws)
+        refb = ref + torch.from_numpy(bias).cuda().double() + torch.from_numpy(res).cuda().double()
+        errb = float((outb.double() - refb).norm() / refb.norm())
+        assert errb <= 4e-3, (M, N, Kd, variant, errb)
+        # repeatable bit for bit
+        out2 = torch.zeros_like(out)
+        K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out2, N, 1, M, N, Kd, variant=variant, splitk_ws=ws)
+        assert torch.equal(out, out2)
+
+
+def test_gemm_forced_variant_rejects_unsupported_shape(K):
+    import torch
+    A = torch.zeros(64, 40, device="cuda", dtype=torch.bfloat16)
+    out = torch.zeros(64, 64, device="cuda", dtype=torch.float32)
+    with pytest.raises(RuntimeError):
+        K.lpk_gemm(1, A, 40, 1, A, 40, 1, out, 64, 1, 64, 64, 40, variant=5)      # K % 32 != 0
+
+
 def test_copy_bit_exact(K):
     import torch
-    src = torch.randint(-2**31, 2**31 - 1, (1 << 20) + 12, device="cuda", dtype=torch.int32)
+    src = torch.randint(-2**31, 2**31 - 1, ((1 << 20) + 12,), device="cuda", dtype=torch.int32)
     dst = torch.zeros_like(src)
     K.lpk_copy(src, dst, src.numel() * 4)
     assert torch.equal(src, dst)
