@@ -165,7 +165,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg3", help="cfg1..cfg5")
-    ap.add_argument("--streams", type=int, default=2, help="side streams for the heads' chains (0 = one stream)")
+    ap.add_argument("--streams", type=int, default=3, help="side streams for the heads' chains (0 = one stream)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the HIP-event pass (used under rocprofv3)")
     ap.add_argument("--copy-calibration", action="store_true",

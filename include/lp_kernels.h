@@ -23,8 +23,9 @@ extern "C" {
  * and wgrad forms of a linear layer: paper appendix A, "MLP").  act / dact: 0 none, 1 ReLU, 2 GELU(tanh).
  * variant: 0 lets the library choose the kernel; 1 forces the FMA kernel; for bf16, 2 forces the
  * register-staged MFMA kernel, 3 / 4 the direct-to-LDS kernel with 256 x 128 tiles and the last partial wave
- * of tiles computed whole / cut along k, 5 / 6 the same with 256 x 256 tiles (an error if the shape does
- * not qualify: K % 32 != 0, or no workspace for a cut).  splitk_ws_dev (may be NULL) is fp32 workspace of
+ * of tiles computed whole / cut along k, 5 / 6 the same with 256 x 256 tiles and 8 wavefronts, 7 / 8 with
+ * 256 x 256 tiles and 4 wavefronts (an error if the shape does not qualify: K % 32 != 0, or no workspace
+ * for a cut).  splitk_ws_dev (may be NULL) is fp32 workspace of
  * splitk_ws_elems floats: with it, reductions over few output tiles are split along k and the partial sums
  * added in a fixed order (at most max(8 * M * N, 2^25) floats are used). */
 int lpk_gemm(int dtype, const void* A, int64_t lda, int a_kc, const void* B, int64_t ldb, int b_kc, void* C,

@@ -48,7 +48,7 @@ __device__ __forceinline__ void epilogue_store(const Epilogue& e, int m, int n, 
 // Host-side description of how the direct-to-LDS GEMM spreads one problem over its persistent grid
 // (filled by gemm_dma_plan, priced by the variant choice, consumed by gemm_dma).
 struct DmaGemmPlan {
-  int nwn = 4;                       // tile columns / 64
+  int kind = 1;                      // 0: 256 x 128 tiles; 1: 256 x 256, 8 waves; 2: 256 x 256, 4 waves
   int tiles_m = 0, tiles_n = 0, kt = 0;
   int full = 0, tail_tiles = 0, upb = 0, G = 0;
   double partial_bytes = 0;          // fp32 partial sums written (and read again by the fix-up kernel)

@@ -2,9 +2,12 @@
 // direct-to-LDS load (global_load_lds_dwordx4: no registers, no VALU), through a ring of NSTAGE LDS
 // stages, so several k-tiles of HBM / L2 latency are in flight behind the MFMA phase.
 //
-// Block tile 256(m) x BN(n) x 32(k), BN = 64*NWN; 2*NWN wavefronts, each owning 128 x 64 (4 x 2 tiles of
-// v_mfma_f32_32x32x16_bf16).  BN = 256: 512 threads, 4 stages (128 KB LDS), one block per CU.
-// BN = 128: 256 threads, 3 stages (72 KB), two blocks per CU.
+// Block tile 256(m) x BN(n) x 32(k); 2 x WNW wavefronts, each owning 128 x 32*TN (4 x TN tiles of
+// v_mfma_f32_32x32x16_bf16).  Three shapes:
+//   256 x 256, 8 waves of 128 x 64  (WNW 4, TN 2): 4 stages (128 KB LDS), one block per CU, 2 waves per SIMD
+//   256 x 256, 4 waves of 128 x 128 (WNW 2, TN 4): 4 stages, one block per CU, 1 wave per SIMD with all 512
+//                registers; a third less LDS read traffic per flop (8 fragment reads per 16 MFMAs)
+//   256 x 128, 4 waves of 128 x 64  (WNW 2, TN 2): 3 stages (72 KB), two blocks per CU.
 //
 // A direct-to-LDS load writes lane l's 16 bytes at (wave-uniform base) + 16*l, so a wave fills 1 KB of
 // contiguous LDS; tiles are therefore unpadded and bank conflicts are avoided by an XOR swizzle that the
@@ -18,6 +21,7 @@
 // One barrier per k-tile: wait until this thread's loads of tile t have landed (s_waitcnt vmcnt leaves
 // the younger tiles in flight), barrier, issue the loads of tile t+NSTAGE-1 into the stage that was read
 // during tile t-1, then 16 MFMAs per wave on tile t.  Requires K % 32 == 0 (no zero fill on this path).
+#include <type_traits>
 #include "common.h"
 #include "gemm_common.h"
 
@@ -183,14 +187,15 @@ __device__ __forceinline__ void tile_coords(int q, int tiles_m, int tiles_n, int
 
 // Epilogue of one wave's 128 x 64 sub-tile: lane (li, hf) holds, for row m = ..+li of m-tile j, the
 // columns 32*i + 16*q + 8*hf .. +7 of n-tile i in acc[i][j][8q .. 8q+7].
-__device__ __forceinline__ void store_subtile(const Epilogue& e, const f32x16 (&acc)[2][4], int m_base, int n_base,
+template <int TN>
+__device__ __forceinline__ void store_subtile(const Epilogue& e, const f32x16 (&acc)[TN][4], int m_base, int n_base,
                                               int li, int hf, int M, int N) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int m = m_base + 32 * j + li;
     if (m >= M) continue;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TN; ++i)
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
         const int n = n_base + 32 * i + 16 * q + 8 * hf;
@@ -204,20 +209,38 @@ __device__ __forceinline__ void store_subtile(const Epilogue& e, const f32x16 (&
 }
 
 // Partial-sum slab of one block tile, in accumulator order: 16 bytes per lane, 1 KB per wave store.
+template <int TN>
 __device__ __forceinline__ size_t slab_index(int wave, int ij, int c, int lane) {
-  return ((((size_t)wave * 8 + ij) * 4 + c) * 64 + lane) * 4;
+  return ((((size_t)wave * (4 * TN) + ij) * 4 + c) * 64 + lane) * 4;
 }
 
-template <bool A_KC, bool B_KC, int NWN, int NSTAGE>
-__global__ void __launch_bounds__(128 * NWN, NWN == 4 ? 1 : 2)
+// Scheduling hint for one k-substep: 16 MFMAs, with the NDS LDS reads of the next substep spread over the
+// first 12 of them (the last reads then have four MFMAs' time to land before they are waited for) and
+// NVM direct-to-LDS loads spread over all of them.  A wave issues in order: a burst of loads that fills
+// the memory pipeline's queue would hold back the MFMAs behind it.
+template <int NDS, int NVM>
+__device__ __forceinline__ void interleave_hint() {
+#pragma unroll
+  for (int g = 0; g < 16; ++g) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // one MFMA
+    const int n = g < 12 ? (NDS * (g + 1)) / 12 - (NDS * g) / 12 : 0;           // then this many LDS reads
+    if (n == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    else if (n == 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    const int m = (NVM * (g + 1)) / 16 - (NVM * g) / 16;                        // and this many global loads
+    if (m == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+  }
+}
+
+template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE>
+__global__ void __launch_bounds__(128 * WNW, (WNW * TN == 4) ? 2 : (WNW == 4 ? 2 : 1))
 k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) {
-  constexpr int BN = 64 * NWN, NWAVES = 2 * NWN;
+  constexpr int BN = 32 * TN * WNW, NWAVES = 2 * WNW;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int AI = (A_BYTES / 1024) / NWAVES, BI = (B_BYTES / 1024) / NWAVES, LPT = AI + BI;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = (wave / NWN) * 128, wn = (wave % NWN) * 64;
+  const int wm = (wave / WNW) * 128, wn = (wave % WNW) * (32 * TN);
   const int li = lane & 31, hf = lane >> 5;
   const int n_row = nmap(li);
   const int c4 = lane & 3, half16 = (lane >> 4) & 1;
@@ -267,46 +290,125 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
   bool have = next_item();
   if (have) start_item();
   while (have) {
-    f32x16 acc[2][4];
+    f32x16 acc[TN][4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TN; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.f;
 
-    for (int t = 0; t < nt; ++t) {
-      // The loads of k-tile t are this thread's oldest outstanding loads; the younger k-tiles (at most
-      // NSTAGE-2) stay in flight.  The first k-tile of an item waits for everything: behind the loads
-      // issued by start_item sit the previous item's epilogue stores.
-      if (t == 0) wait_loads_and_barrier<0>();
-      else if (t + NSTAGE - 2 < nt) wait_loads_and_barrier<(NSTAGE - 2) * LPT>();
-      else if (NSTAGE > 3 && t + NSTAGE - 3 < nt) wait_loads_and_barrier<(NSTAGE > 3 ? NSTAGE - 3 : 0) * LPT>();
-      else wait_loads_and_barrier<0>();
-      if (t + NSTAGE - 1 < nt) {
-        char* dst = smem + ((t + NSTAGE - 1) % NSTAGE) * STAGE_BYTES;
-        pa.issue(dst, t + NSTAGE - 1);
-        pb.issue(dst + A_BYTES, t + NSTAGE - 1);
-      }
-      const char* as = smem + (t % NSTAGE) * STAGE_BYTES;
-      const char* bs = as + A_BYTES;
+    if constexpr (TN == 4) {
+      // One wave per SIMD: nothing else hides a fragment read's latency, so the reads are software
+      // pipelined by hand.  Each 16-deep k-substep's 16 MFMAs run while the next substep's fragments are
+      // read into a second register set; the reads of the next k-tile's first substep need that tile in
+      // LDS, so the wait + barrier sits in the middle of a k-tile, between its two substeps.
+      auto read = [&](const char* as, const char* bs, int kk, bf16x8* fn, bf16x8* fm) {
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        bf16x8 fn[2], fm[4];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TN; ++i)
           fn[i] = B_KC ? frag_kc(bs, wn + 32 * i + n_row, 2 * kk + hf)
                        : frag_t<BN>(bs, wn + 32 * i + n_rowbase_t, 16 * kk + 8 * hf + kq);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
           fm[j] = A_KC ? frag_kc(as, wm + 32 * j + li, 2 * kk + hf)
                        : frag_t<BM>(as, wm + 32 * j + m_rowbase_t, 16 * kk + 8 * hf + kq);
+      };
+      auto mma = [&](const bf16x8* fn, const bf16x8* fm) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TN; ++i)
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
+      };
+      constexpr int NDS = (A_KC ? 4 : 8) + (B_KC ? TN : 2 * TN);   // LDS read instructions per substep
+      bf16x8 fn0[TN], fm0[4], fn1[TN], fm1[4];
+      wait_loads_and_barrier<0>();
+      if (NSTAGE - 1 < nt) {
+        pa.issue(smem + (NSTAGE - 1) * STAGE_BYTES, NSTAGE - 1);
+        pb.issue(smem + (NSTAGE - 1) * STAGE_BYTES + A_BYTES, NSTAGE - 1);
       }
+      read(smem, smem + A_BYTES, 0, fn0, fm0);
+      // Every k-tile but the last.  STEADY (k-tiles 1 .. nt-NSTAGE): the loads of k-tile t+NSTAGE-1 are issued
+      // unconditionally, so that the second substep is one basic block in which the scheduler can spread them
+      // between the MFMAs; the few k-tiles before and after take the branching form.
+      auto step = [&](int t, auto steady) {
+        constexpr bool STEADY = decltype(steady)::value;
+        const char* as = smem + (t % NSTAGE) * STAGE_BYTES;
+        read(as, as + A_BYTES, 1, fn1, fm1);
+        mma(fn0, fm0);
+        interleave_hint<NDS, 0>();
+        __builtin_amdgcn_sched_barrier(0);
+        // k-tile t+1 must have landed; the loads of k-tiles t+2 .. t+NSTAGE-2 stay in flight
+        if (STEADY) wait_loads_and_barrier<(NSTAGE - 3) * LPT>();
+        else if (NSTAGE > 4 && t + 3 < nt) wait_loads_and_barrier<(NSTAGE > 4 ? 2 : 0) * LPT>();
+        else if (t + 2 < nt) wait_loads_and_barrier<LPT>();
+        else wait_loads_and_barrier<0>();
+        char* dst = smem + ((t + NSTAGE - 1) % NSTAGE) * STAGE_BYTES;   // the stage read in k-tile t-1
+        const char* an = smem + ((t + 1) % NSTAGE) * STAGE_BYTES;
+        if (STEADY) {
+          pa.issue(dst, t + NSTAGE - 1);
+          pb.issue(dst + A_BYTES, t + NSTAGE - 1);
+          read(an, an + A_BYTES, 0, fn0, fm0);
+          mma(fn1, fm1);
+          interleave_hint<NDS, LPT>();
+        } else {
+          if (t >= 1 && t + NSTAGE - 1 < nt) {
+            pa.issue(dst, t + NSTAGE - 1);
+            pb.issue(dst + A_BYTES, t + NSTAGE - 1);
+          }
+          read(an, an + A_BYTES, 0, fn0, fm0);
+          mma(fn1, fm1);
+          interleave_hint<NDS, 0>();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      int t = 0;
+      if (nt > 1) step(t++, std::false_type{});
+      for (; t + NSTAGE <= nt; ++t) step(t, std::true_type{});
+      for (; t + 1 < nt; ++t) step(t, std::false_type{});
+      {
+        const char* as = smem + ((nt - 1) % NSTAGE) * STAGE_BYTES;
+        read(as, as + A_BYTES, 1, fn1, fm1);
+        mma(fn0, fm0);
+        interleave_hint<NDS, 0>();
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fn1, fm1);
+      }
+    } else {
+      for (int t = 0; t < nt; ++t) {
+        // The loads of k-tile t are this thread's oldest outstanding loads; the younger k-tiles (at most
+        // NSTAGE-2) stay in flight.  The first k-tile of an item waits for everything: behind the loads
+        // issued by start_item sit the previous item's epilogue stores.
+        if (t == 0) wait_loads_and_barrier<0>();
+        else if (t + NSTAGE - 2 < nt) wait_loads_and_barrier<(NSTAGE - 2) * LPT>();
+        else if (NSTAGE > 3 && t + NSTAGE - 3 < nt) wait_loads_and_barrier<(NSTAGE > 3 ? NSTAGE - 3 : 0) * LPT>();
+        else wait_loads_and_barrier<0>();
+        if (t + NSTAGE - 1 < nt) {
+          char* dst = smem + ((t + NSTAGE - 1) % NSTAGE) * STAGE_BYTES;
+          pa.issue(dst, t + NSTAGE - 1);
+          pb.issue(dst + A_BYTES, t + NSTAGE - 1);
+        }
+        const char* as = smem + (t % NSTAGE) * STAGE_BYTES;
+        const char* bs = as + A_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+          bf16x8 fn[TN], fm[4];
+#pragma unroll
+          for (int i = 0; i < TN; ++i)
+            fn[i] = B_KC ? frag_kc(bs, wn + 32 * i + n_row, 2 * kk + hf)
+                         : frag_t<BN>(bs, wn + 32 * i + n_rowbase_t, 16 * kk + 8 * hf + kq);
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            fm[j] = A_KC ? frag_kc(as, wm + 32 * j + li, 2 * kk + hf)
+                         : frag_t<BM>(as, wm + 32 * j + m_rowbase_t, 16 * kk + 8 * hf + kq);
+#pragma unroll
+          for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
+        }
+      }
+
     }
 
     // this item's output coordinates, before the next item replaces them
@@ -319,17 +421,17 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
     asm volatile("s_barrier" ::: "memory");
     if (have) start_item();
     if (whole) {
-      store_subtile(e, acc, cm, cn, li, hf, M, N);
+      store_subtile<TN>(e, acc, cm, cn, li, hf, M, N);
     } else {
       float* sp = ws + (size_t)slab * (BM * BN);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             f32x4 o = {acc[i][j][4 * c], acc[i][j][4 * c + 1], acc[i][j][4 * c + 2], acc[i][j][4 * c + 3]};
-            *reinterpret_cast<f32x4*>(sp + slab_index(wave, i * 4 + j, c, lane)) = o;
+            *reinterpret_cast<f32x4*>(sp + slab_index<TN>(wave, i * 4 + j, c, lane)) = o;
           }
     }
   }
@@ -338,13 +440,13 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
 // Adds the partial-sum slabs of every tail tile that was cut, in block order, and applies the epilogue.
 // One thread per run of 8 columns (the unit of the fused epilogue), with the main kernel's
 // lane-to-element mapping: thread (wave, ij, q, lane) owns acc[i][j][8q .. 8q+7] of that lane.
-template <int NWN>
+template <int WNW, int TN>
 __global__ void __launch_bounds__(256) k_sk_fixup(const float* __restrict__ ws, Epilogue e, int M, int N, SkPlan p) {
-  constexpr int BN = 64 * NWN, NWAVES = 2 * NWN, BLOCKS_PER_TILE = NWAVES * 16 * 64 / 256;
+  constexpr int BN = 32 * TN * WNW, NWAVES = 2 * WNW, UNITS_PER_WAVE = 8 * TN, BLOCKS_PER_TILE = NWAVES * UNITS_PER_WAVE / 4;
   const int tr = blockIdx.x / BLOCKS_PER_TILE;
   const int unit = (blockIdx.x % BLOCKS_PER_TILE) * 4 + (threadIdx.x >> 6);      // (wave, ij, q)
   const int lane = threadIdx.x & 63;
-  const int wave = unit >> 4, ij = (unit >> 1) & 7, q = unit & 1;
+  const int wave = unit / UNITS_PER_WAVE, ij = (unit % UNITS_PER_WAVE) >> 1, q = unit & 1;
   const long u0 = (long)tr * p.kt, u1 = u0 + p.kt;
   const int v_lo = (int)(u0 / p.upb), v_hi = (int)((u1 - 1) / p.upb);
   if (v_lo == v_hi) return;            // computed whole by one block
@@ -352,16 +454,16 @@ __global__ void __launch_bounds__(256) k_sk_fixup(const float* __restrict__ ws, 
   for (int v = v_lo; v <= v_hi; ++v) {
     const int slab = 2 * v + ((long)v * p.upb <= u0 ? 1 : 0);
     const float* sp = ws + (size_t)slab * (BM * BN);
-    f32x4 a = *reinterpret_cast<const f32x4*>(sp + slab_index(wave, ij, 2 * q, lane));
-    f32x4 b = *reinterpret_cast<const f32x4*>(sp + slab_index(wave, ij, 2 * q + 1, lane));
+    f32x4 a = *reinterpret_cast<const f32x4*>(sp + slab_index<TN>(wave, ij, 2 * q, lane));
+    f32x4 b = *reinterpret_cast<const f32x4*>(sp + slab_index<TN>(wave, ij, 2 * q + 1, lane));
 #pragma unroll
     for (int x = 0; x < 4; ++x) { acc[x] += a[x]; acc[4 + x] += b[x]; }
   }
   int tm, tn;
   tile_coords(p.full * p.G + tr, p.tiles_m, p.tiles_n, tm, tn);
   const int i = ij >> 2, j = ij & 3, li = lane & 31, hf = lane >> 5;
-  const int m = tm * BM + (wave / NWN) * 128 + 32 * j + li;
-  const int n = tn * BN + (wave % NWN) * 64 + 32 * i + 16 * q + 8 * hf;
+  const int m = tm * BM + (wave / WNW) * 128 + 32 * j + li;
+  const int n = tn * BN + (wave % WNW) * (32 * TN) + 32 * i + 16 * q + 8 * hf;
   if (m < M && n < N) epilogue8(e, m, n, acc);
 }
 
@@ -376,12 +478,12 @@ int device_cus() {
   return n;
 }
 
-template <bool A_KC, bool B_KC, int NWN, int NSTAGE>
+template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE>
 hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool partials) {
-  constexpr int BN = 64 * NWN;
+  constexpr int BN = 32 * TN * WNW;
   constexpr int smem = NSTAGE * (BM + BN) * BK * 2;
   static bool configured = false;
-  auto kern = k_gemm_dma<A_KC, B_KC, NWN, NSTAGE>;
+  auto kern = k_gemm_dma<A_KC, B_KC, WNW, TN, NSTAGE>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
@@ -389,10 +491,10 @@ hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool parti
   }
   Operand A{(const bf16_t*)g.A, g.lda, g.M}, B{(const bf16_t*)g.B, g.ldb, g.N};
   Epilogue e = make_epilogue(g);
-  kern<<<dim3(p.G), 128 * NWN, smem, c.stream>>>(A, B, e, g.M, g.N, p, c.splitk_ws);
+  kern<<<dim3(p.G), 128 * WNW, smem, c.stream>>>(A, B, e, g.M, g.N, p, c.splitk_ws);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || !partials) return err;
-  k_sk_fixup<NWN><<<dim3(p.tail_tiles * (2 * NWN * 16 * 64 / 256)), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, p);
+  k_sk_fixup<WNW, TN><<<dim3(p.tail_tiles * (2 * WNW * 8 * TN / 4)), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, p);
   return hipGetLastError();
 }
 
@@ -402,12 +504,13 @@ hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool parti
 // 8-row chunk column set (rows >= 8, rows % 8 == 0 is already required by the caller's checks).
 bool gemm_dma_ok(const GemmArgs& g) { return g.K % 32 == 0 && g.K >= 32 && g.M >= 8 && g.N >= 8; }
 
-// Distribution of an M x N x K problem over the persistent grid of the variant with 64*nwn-column tiles.
+// Distribution of an M x N x K problem over the persistent grid of one tile shape
+// (kind 0: 256 x 128, two blocks per CU; 1: 256 x 256 with 8 waves; 2: 256 x 256 with 4 waves).
 // cut_tail: cut the last, partial wave of tiles along k (needs workspace); otherwise one tile per block.
 // Returns false if the workspace cannot hold the partial sums.  *partial_bytes = bytes of partial sums
 // written (and read again), *steps = k-steps on the longest block.
-bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int nwn, bool cut_tail, DmaGemmPlan* out) {
-  const int bn = 64 * nwn, per_cu = nwn == 4 ? 1 : 2;
+bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int kind, bool cut_tail, DmaGemmPlan* out) {
+  const int bn = kind == 0 ? 128 : 256, per_cu = kind == 0 ? 2 : 1;
   SkPlan p;
   p.G = (device_cus() * per_cu) & ~7;
   p.tiles_m = (g.M + BM - 1) / BM;
@@ -440,7 +543,7 @@ bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int nwn, bool cut_tail, Dm
       if (!c.splitk_ws || (size_t)2 * p.G * BM * bn > c.splitk_elems) return false;
     }
   }
-  out->nwn = nwn;
+  out->kind = kind;
   out->full = p.full; out->tail_tiles = p.tail_tiles; out->upb = p.upb; out->G = p.G; out->kt = p.kt;
   out->tiles_m = p.tiles_m; out->tiles_n = p.tiles_n;
   out->partial_bytes = (double)partial_slabs * BM * bn * 4.0;
@@ -454,7 +557,10 @@ hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d) {
   p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.kt = d.kt; p.full = d.full; p.tail_tiles = d.tail_tiles;
   p.upb = d.upb; p.G = d.G;
   const bool partials = d.partial_bytes > 0;
-#define LP_DMA(AK, BK_) (d.nwn == 4 ? launch<AK, BK_, 4, 4>(c, g, p, partials) : launch<AK, BK_, 2, 3>(c, g, p, partials))
+#define LP_DMA(AK, BK_)                                                    \
+  (d.kind == 1 ? launch<AK, BK_, 4, 2, 4>(c, g, p, partials)               \
+               : d.kind == 2 ? launch<AK, BK_, 2, 4, 5>(c, g, p, partials) \
+                             : launch<AK, BK_, 2, 2, 3>(c, g, p, partials))
   if (g.a_kc && g.b_kc) return LP_DMA(true, true);
   if (g.a_kc && !g.b_kc) return LP_DMA(true, false);
   if (!g.a_kc && g.b_kc) return LP_DMA(false, true);

@@ -21,7 +21,7 @@ namespace lp {
 
 hipError_t gemm_plain(const OpCtx& c, const GemmArgs& g);
 bool gemm_dma_ok(const GemmArgs& g);
-bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int nwn, bool cut_tail, DmaGemmPlan* out);
+bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int kind, bool cut_tail, DmaGemmPlan* out);
 hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d);
 
 namespace {
@@ -61,17 +61,21 @@ bool fast_ok(const GemmArgs& g) {
 
 }  // namespace
 
-// Forced kernel family: 0 none; 2 register-staged; 3 / 4 direct-to-LDS 256 x 128 with the tail whole / cut
-// along k; 5 / 6 the same for 256 x 256; 7 / 8 256 x 128 / 256 x 256 with either tail.
-// LP_GEMM_KERNEL = v2 | dma2 | dma4 (| dma2w, dma2c, dma4w, dma4c) sets 2 / 7 / 8 (3, 4, 5, 6) for a whole
-// process (for measurements); a shape the forced kernel does not take falls back to the register-staged one.
+// Forced kernel: 0 none; 2 register-staged; 3 + 2*kind + cut for the direct-to-LDS kernel of tile shape
+// `kind` (0: 256 x 128; 1: 256 x 256 with 8 waves; 2: 256 x 256 with 4 waves) with the tail whole (cut 0)
+// or cut along k (cut 1); 13 + 2*kind for that shape with either tail.
+// LP_GEMM_KERNEL = v2 | dma2 | dma4 | dmaw, optionally followed by w or c (dma4c, ...), forces one for a
+// whole process (for measurements); a shape the forced kernel does not take falls back to the others.
 static int env_choice() {
   static int v = -1;
   if (v < 0) {
     const char* s = getenv("LP_GEMM_KERNEL");
-    v = !s ? 0 : (s[0] == 'v' ? 2 : (s[0] == 'd' && s[3] == '2' ? 7 : (s[0] == 'd' && s[3] == '4' ? 8 : 0)));
-    if (v >= 7 && s[4] == 'w') v = v == 7 ? 3 : 5;        // dma2w / dma4w: tail computed whole
-    else if (v >= 7 && s[4] == 'c') v = v == 7 ? 4 : 6;   // dma2c / dma4c: tail cut along k
+    v = 0;
+    if (s && s[0] == 'v') v = 2;
+    else if (s && s[0] == 'd' && s[1] == 'm' && s[2] == 'a') {
+      const int kind = s[3] == '2' ? 0 : (s[3] == '4' ? 1 : (s[3] == 'w' ? 2 : -1));
+      if (kind >= 0) v = s[4] == 'w' ? 3 + 2 * kind : (s[4] == 'c' ? 4 + 2 * kind : 13 + 2 * kind);
+    }
   }
   return v;
 }
@@ -91,8 +95,8 @@ static double dma_bias() {   // LP_GEMM_DMA_BIAS scales the direct-to-LDS kernel
   if (v < 0) { const char* s = getenv("LP_GEMM_DMA_BIAS"); v = s ? atof(s) : 1.0; if (!(v > 0)) v = 1.0; }
   return v;
 }
-static const double kDmaStep[2] = {2796.0, 2467.0};      // 256 x 128 (two per CU), 256 x 256
-static const double kDmaFixed[2] = {7000.0, 9000.0};
+static const double kDmaStep[3] = {2796.0, 2467.0, 2467.0};      // 256 x 128 (two per CU), 256 x 256
+static const double kDmaFixed[3] = {7000.0, 9000.0, 9000.0};
 
 hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
@@ -101,16 +105,18 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   // direct-to-LDS persistent kernel: two tile widths, tail whole or cut along k
   DmaGemmPlan best_dma;
   bool use_dma = false;
+  int force_kind = -1, force_cut = -1;
+  if (choice >= 13) force_kind = (choice - 13) / 2;
+  else if (choice >= 3) { force_kind = (choice - 3) / 2; force_cut = (choice - 3) % 2; }
   if (gemm_dma_ok(g) && choice != 2) {
-    for (int wi = 0; wi < 2; ++wi) {
-      if (((choice == 3 || choice == 4 || choice == 7) && wi == 1) || ((choice == 5 || choice == 6 || choice == 8) && wi == 0))
-        continue;
+    for (int kind = 0; kind < 3; ++kind) {
+      if (force_kind >= 0 ? kind != force_kind : kind == 2) continue;   // the 4-wave 256 x 256 shape only when asked for
       for (int cut = 0; cut < 2; ++cut) {
-        if (((choice == 3 || choice == 5) && cut) || ((choice == 4 || choice == 6) && !cut)) continue;
+        if (force_cut >= 0 && cut != force_cut) continue;
         DmaGemmPlan d;
-        if (!gemm_dma_plan(c, g, wi ? 4 : 2, cut != 0, &d)) continue;
-        if (cut && d.partial_bytes == 0 && choice < 3) continue;         // same as the uncut plan
-        double cycles = d.steps * kDmaStep[wi] + d.items * kDmaFixed[wi];
+        if (!gemm_dma_plan(c, g, kind, cut != 0, &d)) continue;
+        if (cut && d.partial_bytes == 0 && force_cut < 0) continue;      // same as the uncut plan
+        double cycles = d.steps * kDmaStep[kind] + d.items * kDmaFixed[kind];
         if (d.partial_bytes > 0) cycles += 2.0 * d.partial_bytes / kPartialBytesPerCycle + kSecondLaunchCycles;
         cycles *= dma_bias();
         if (cycles < best) { best = cycles; best_dma = d; use_dma = true; }

@@ -236,7 +236,7 @@ DMA_SHAPES = [(520, 264, 4096), (4096, 4096, 64), (4104, 4360, 96), (8192, 776, 
               (6000, 12000, 160), (264, 136, 16384)]
 
 
-@pytest.mark.parametrize("variant", [3, 4, 5, 6])
+@pytest.mark.parametrize("variant", [3, 4, 5, 6, 7, 8])
 @pytest.mark.parametrize("a_kc,b_kc", [(1, 1), (1, 0), (0, 0), (0, 1)])
 def test_gemm_persistent_variants(K, variant, a_kc, b_kc):
     import torch
