@@ -214,24 +214,26 @@ __device__ __forceinline__ size_t slab_index(int wave, int ij, int c, int lane) 
   return ((((size_t)wave * (4 * TN) + ij) * 4 + c) * 64 + lane) * 4;
 }
 
-// Scheduling hint for one k-substep: 16 MFMAs, with the NDS LDS reads of the next substep spread over the
-// first 12 of them (the last reads then have four MFMAs' time to land before they are waited for) and
+// Scheduling hint for one k-substep: NMF MFMAs, with the NDS LDS reads of the next substep spread over the
+// first three quarters of them (the last reads then have time to land before they are waited for) and
 // NVM direct-to-LDS loads spread over all of them.  A wave issues in order: a burst of loads that fills
 // the memory pipeline's queue would hold back the MFMAs behind it.
-template <int NDS, int NVM>
+template <int NMF, int NDS, int NVM>
 __device__ __forceinline__ void interleave_hint() {
+  constexpr int RD = NMF * 3 / 4;      // MFMAs over which the LDS reads are spread
 #pragma unroll
-  for (int g = 0; g < 16; ++g) {
+  for (int g = 0; g < NMF; ++g) {
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // one MFMA
-    const int n = g < 12 ? (NDS * (g + 1)) / 12 - (NDS * g) / 12 : 0;           // then this many LDS reads
+    const int n = g < RD ? (NDS * (g + 1)) / RD - (NDS * g) / RD : 0;           // then this many LDS reads
     if (n == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     else if (n == 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-    const int m = (NVM * (g + 1)) / 16 - (NVM * g) / 16;                        // and this many global loads
+    else if (n == 3) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+    const int m = (NVM * (g + 1)) / NMF - (NVM * g) / NMF;                      // and this many global loads
     if (m == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
   }
 }
 
-template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE>
+template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE, bool PIPE>
 __global__ void __launch_bounds__(128 * WNW, (WNW * TN == 4) ? 2 : (WNW == 4 ? 2 : 1))
 k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) {
   constexpr int BN = 32 * TN * WNW, NWAVES = 2 * WNW;
@@ -298,7 +300,7 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
 #pragma unroll
         for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.f;
 
-    if constexpr (TN == 4) {
+    if constexpr (PIPE) {
       // One wave per SIMD: nothing else hides a fragment read's latency, so the reads are software
       // pipelined by hand.  Each 16-deep k-substep's 16 MFMAs run while the next substep's fragments are
       // read into a second register set; the reads of the next k-tile's first substep need that tile in
@@ -336,7 +338,7 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
         const char* as = smem + (t % NSTAGE) * STAGE_BYTES;
         read(as, as + A_BYTES, 1, fn1, fm1);
         mma(fn0, fm0);
-        interleave_hint<NDS, 0>();
+        interleave_hint<4 * TN, NDS, 0>();
         __builtin_amdgcn_sched_barrier(0);
         // k-tile t+1 must have landed; the loads of k-tiles t+2 .. t+NSTAGE-2 stay in flight
         if (STEADY) wait_loads_and_barrier<(NSTAGE - 3) * LPT>();
@@ -350,7 +352,7 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
           pb.issue(dst + A_BYTES, t + NSTAGE - 1);
           read(an, an + A_BYTES, 0, fn0, fm0);
           mma(fn1, fm1);
-          interleave_hint<NDS, LPT>();
+          interleave_hint<4 * TN, NDS, LPT>();
         } else {
           if (t >= 1 && t + NSTAGE - 1 < nt) {
             pa.issue(dst, t + NSTAGE - 1);
@@ -358,7 +360,7 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
           }
           read(an, an + A_BYTES, 0, fn0, fm0);
           mma(fn1, fm1);
-          interleave_hint<NDS, 0>();
+          interleave_hint<4 * TN, NDS, 0>();
         }
         __builtin_amdgcn_sched_barrier(0);
       };
@@ -370,7 +372,7 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
         const char* as = smem + ((nt - 1) % NSTAGE) * STAGE_BYTES;
         read(as, as + A_BYTES, 1, fn1, fm1);
         mma(fn0, fm0);
-        interleave_hint<NDS, 0>();
+        interleave_hint<4 * TN, NDS, 0>();
         __builtin_amdgcn_sched_barrier(0);
         mma(fn1, fm1);
       }
@@ -478,12 +480,12 @@ int device_cus() {
   return n;
 }
 
-template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE>
+template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE, bool PIPE>
 hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool partials) {
   constexpr int BN = 32 * TN * WNW;
   constexpr int smem = NSTAGE * (BM + BN) * BK * 2;
   static bool configured = false;
-  auto kern = k_gemm_dma<A_KC, B_KC, WNW, TN, NSTAGE>;
+  auto kern = k_gemm_dma<A_KC, B_KC, WNW, TN, NSTAGE, PIPE>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
@@ -558,9 +560,9 @@ hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d) {
   p.upb = d.upb; p.G = d.G;
   const bool partials = d.partial_bytes > 0;
 #define LP_DMA(AK, BK_)                                                    \
-  (d.kind == 1 ? launch<AK, BK_, 4, 2, 4>(c, g, p, partials)               \
-               : d.kind == 2 ? launch<AK, BK_, 2, 4, 5>(c, g, p, partials) \
-                             : launch<AK, BK_, 2, 2, 3>(c, g, p, partials))
+  (d.kind == 1 ? launch<AK, BK_, 4, 2, 4, true>(c, g, p, partials)                \
+   : d.kind == 2 ? launch<AK, BK_, 2, 4, 5, true>(c, g, p, partials)              \
+                 : launch<AK, BK_, 2, 2, 3, false>(c, g, p, partials))
   if (g.a_kc && g.b_kc) return LP_DMA(true, true);
   if (g.a_kc && !g.b_kc) return LP_DMA(true, false);
   if (!g.a_kc && g.b_kc) return LP_DMA(false, true);

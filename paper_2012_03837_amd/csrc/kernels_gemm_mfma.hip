@@ -12,6 +12,7 @@
 // activation derivative, residual, accumulate) reads and writes 16 bytes per lane.
 // Blocks are renumbered so that each XCD (blocks are dealt round-robin to the 8 XCDs) walks a
 // compact group of tiles and re-uses its own L2.
+#include <stdio.h>
 #include <stdlib.h>
 #include "common.h"
 #include "gemm_common.h"
@@ -95,7 +96,7 @@ static double dma_bias() {   // LP_GEMM_DMA_BIAS scales the direct-to-LDS kernel
   if (v < 0) { const char* s = getenv("LP_GEMM_DMA_BIAS"); v = s ? atof(s) : 1.0; if (!(v > 0)) v = 1.0; }
   return v;
 }
-static const double kDmaStep[3] = {2796.0, 2467.0, 2467.0};      // 256 x 128 (two per CU), 256 x 256
+static const double kDmaStep[3] = {2796.0, 2300.0, 2300.0};      // 256 x 128 (two per CU), 256 x 256
 static const double kDmaFixed[3] = {7000.0, 9000.0, 9000.0};
 
 hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
