@@ -63,9 +63,12 @@ int lpk_optimizer(int kind, float lr, float momentum, float beta1, float beta2, 
  * which the HBM counters (FETCH_SIZE, WRITE_SIZE) are scaled when a kernel's traffic is measured. */
 int lpk_copy(const void* src_dev, void* dst_dev, size_t bytes, void* stream);
 
-/* Embedding-table gradient: demb[v,:] (+)= sum of dh[t,:] over positions with ids[t] == v, in order of t. */
+/* Embedding-table gradient: demb[v,:] (+)= sum of dh[t,:] over positions with ids[t] == v, in order of t
+ * (ids outside [0, V) count as the nearest valid id, as in the forward lookup).  scratch_dev (may be NULL)
+ * is device scratch of scratch_elems 4-byte words; with at least V words the kernel first counts every
+ * id's positions there and skips the rows that do not occur. */
 int lpk_embed_bwd(int dtype, const int32_t* ids, const void* dh, float* demb, int T, int V, int d, int accumulate,
-                  void* stream);
+                  float* scratch_dev, size_t scratch_elems, void* stream);
 
 /* NHWC convolution with [O,R,S,C] filters as implicit GEMM (appendix B.3), forward / data gradient /
  * filter gradient (fp32). */

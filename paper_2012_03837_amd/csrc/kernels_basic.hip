@@ -137,42 +137,69 @@ hipError_t op_embed_fwd(const OpCtx& c, const int32_t* ids, const float* emb, co
 }
 
 // Gradient of the embedding table: row v = sum over the positions t with ids[t] == v of dh[t, :],
-// taken in increasing t (fixed order: no atomics).  One block per (row, 256-column slab): the block
-// scans all ids, compacts the matching positions in order, then sums those rows.
+// taken in increasing t (fixed order; the only atomics are integer counts, which are exact).  A first
+// kernel counts the positions of every id (ids outside [0, V) are clamped as in the forward pass); then
+// one block per (row, 256-column slab): a row that does not occur is zero-filled at once (most of a
+// Zipf vocabulary), otherwise the block scans all ids, compacts the matching positions in order and
+// sums those rows.
+__device__ __forceinline__ int clamp_id(int id, int V) { return id < 0 ? 0 : (id >= V ? V - 1 : id); }
+
+__global__ void k_id_count(const int32_t* __restrict__ ids, int* __restrict__ counts, int T_, int V) {
+  int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < T_) atomicAdd(&counts[clamp_id(ids[t], V)], 1);
+}
+
 template <typename T>
-__global__ void k_embed_bwd(const int32_t* ids, const T* dh, float* demb, int T_, int d, int accumulate) {
+__global__ void k_embed_bwd(const int32_t* ids, const int* __restrict__ counts, const T* dh, float* demb, int T_,
+                            int V, int d, int accumulate) {
   __shared__ int pos[256];
   __shared__ int wcount[4];
   int v = blockIdx.x;
   int col = blockIdx.y * 256 + threadIdx.x;
   float acc = 0.f;
-  int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  for (int base = 0; base < T_; base += 256) {
-    int t = base + threadIdx.x;
-    bool hit = (t < T_) && (ids[t] == v);
-    unsigned long long mask = __ballot(hit);
-    if (lane == 0) wcount[w] = __popcll(mask);
-    __syncthreads();
-    int off = 0;
-    for (int i = 0; i < w; ++i) off += wcount[i];
-    int total = wcount[0] + wcount[1] + wcount[2] + wcount[3];
-    if (hit) pos[off + __popcll(mask & ((1ull << lane) - 1ull))] = t;
-    __syncthreads();
-    if (col < d)
-      for (int i = 0; i < total; ++i) acc += to_f(dh[(size_t)pos[i] * d + col]);
-    __syncthreads();
+  const int n_hits = counts ? counts[v] : -1;        // block-uniform
+  if (n_hits != 0) {
+    int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int found = 0;
+    for (int base = 0; base < T_ && (n_hits < 0 || found < n_hits); base += 256) {
+      int t = base + threadIdx.x;
+      bool hit = (t < T_) && (clamp_id(ids[t], V) == v);
+      unsigned long long mask = __ballot(hit);
+      if (lane == 0) wcount[w] = __popcll(mask);
+      __syncthreads();
+      int off = 0;
+      for (int i = 0; i < w; ++i) off += wcount[i];
+      int total = wcount[0] + wcount[1] + wcount[2] + wcount[3];
+      if (hit) pos[off + __popcll(mask & ((1ull << lane) - 1ull))] = t;
+      __syncthreads();
+      if (col < d)
+        for (int i = 0; i < total; ++i) acc += to_f(dh[(size_t)pos[i] * d + col]);
+      found += total;
+      __syncthreads();
+    }
   }
   if (col < d) {
     size_t o = (size_t)v * d + col;
-    demb[o] = accumulate ? demb[o] + acc : acc;
+    if (n_hits != 0 || !accumulate) demb[o] = accumulate ? demb[o] + acc : acc;
   }
 }
 hipError_t op_embed_bwd(const OpCtx& c, const int32_t* ids, const void* dh, float* demb, int T_, int V, int d,
                         int accumulate) {
   ProfScope prof_(c, KC_EMBED);
+  if (V <= 0 || d <= 0) return hipSuccess;
+  // per-id counts in the reduction scratch (integers; 0.0f is the zero word)
+  int* counts = nullptr;
+  if (c.partial && (size_t)V <= c.partial_elems && T_ > 0) {
+    counts = reinterpret_cast<int*>(c.partial);
+    hipError_t e = op_fill_f32(c, c.partial, (size_t)V, 0.f);
+    if (e != hipSuccess) return e;
+    k_id_count<<<(T_ + 255) / 256, 256, 0, c.stream>>>(ids, counts, T_, V);
+  }
   dim3 grid(V, (d + 255) / 256);
-  if (c.dt == BF16) k_embed_bwd<bf16_t><<<grid, 256, 0, c.stream>>>(ids, (const bf16_t*)dh, demb, T_, d, accumulate);
-  else k_embed_bwd<float><<<grid, 256, 0, c.stream>>>(ids, (const float*)dh, demb, T_, d, accumulate);
+  if (c.dt == BF16)
+    k_embed_bwd<bf16_t><<<grid, 256, 0, c.stream>>>(ids, counts, (const bf16_t*)dh, demb, T_, V, d, accumulate);
+  else
+    k_embed_bwd<float><<<grid, 256, 0, c.stream>>>(ids, counts, (const float*)dh, demb, T_, V, d, accumulate);
   return LP_LAUNCH_CHECK();
 }
 
@@ -260,19 +287,34 @@ __global__ void k_ln_bwd(const T* dy, const T* x, const float* mean, const float
     partial[(size_t)(nblk + blockIdx.x) * d + j] = bsum;
   }
 }
-// out[j] (+)= sum_b partial[b, j].  Block = 64 columns x 4 row groups; group q adds rows q, q+4, ... in
-// order and the four group sums are then added in order (a fixed tree).
-__global__ void k_reduce_partials(const float* partial, int nblk, int n, float* out, int accumulate) {
-  __shared__ float sh[4][64];
+// out[j] (+)= sum_b partial[b, j].  Block = 64 columns x 16 row groups; group q adds rows q, q+16, ... in
+// order (four independent loads in flight at a time) and the sixteen group sums are then added in order:
+// a fixed tree, so the result does not depend on the launch.
+constexpr int kReduceGroups = 16;
+__global__ void __launch_bounds__(64 * kReduceGroups)
+k_reduce_partials(const float* __restrict__ partial, int nblk, int n, float* out, int accumulate,
+                  float* out_y1 = nullptr) {
+  // blockIdx.y == 1: a second table of partials stored right behind the first, summed into out_y1
+  if (blockIdx.y == 1) { partial += (size_t)nblk * n; out = out_y1; }
+  __shared__ float sh[kReduceGroups][64];
   int lc = threadIdx.x & 63, q = threadIdx.x >> 6;
   int j = blockIdx.x * 64 + lc;
   float a = 0.f;
-  if (j < n)
-    for (int b = q; b < nblk; b += 4) a += partial[(size_t)b * n + j];
+  if (j < n) {
+    int b = q;
+    for (; b + 3 * kReduceGroups < nblk; b += 4 * kReduceGroups) {
+      float v0 = partial[(size_t)b * n + j], v1 = partial[(size_t)(b + kReduceGroups) * n + j];
+      float v2 = partial[(size_t)(b + 2 * kReduceGroups) * n + j], v3 = partial[(size_t)(b + 3 * kReduceGroups) * n + j];
+      a += v0; a += v1; a += v2; a += v3;
+    }
+    for (; b < nblk; b += kReduceGroups) a += partial[(size_t)b * n + j];
+  }
   sh[q][lc] = a;
   __syncthreads();
   if (q == 0 && j < n) {
-    float t = sh[0][lc] + sh[1][lc] + sh[2][lc] + sh[3][lc];
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < kReduceGroups; ++g) t += sh[g][lc];
     out[j] = accumulate ? out[j] + t : t;
   }
 }
@@ -285,8 +327,7 @@ hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const
     int nb = 0;
     hipError_t e = ln_bwd_fast(c, dy, x, mean, rstd, g, add, dx, rows, d, &nb);
     if (e != hipSuccess) return e;
-    k_reduce_partials<<<(d + 63) / 64, 256, 0, c.stream>>>(c.partial, nb, d, dg, accumulate);
-    k_reduce_partials<<<(d + 63) / 64, 256, 0, c.stream>>>(c.partial + (size_t)nb * d, nb, d, db, accumulate);
+    k_reduce_partials<<<dim3((d + 63) / 64, 2), 64 * kReduceGroups, 0, c.stream>>>(c.partial, nb, d, dg, accumulate, db);
     return LP_LAUNCH_CHECK();
   }
   int nblk = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
@@ -300,8 +341,7 @@ hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const
                                                   (const float*)add, (float*)dx, c.partial, rows, d);
   hipError_t e = LP_LAUNCH_CHECK();
   if (e != hipSuccess) return e;
-  k_reduce_partials<<<(d + 63) / 64, 256, 0, c.stream>>>(c.partial, nblk, d, dg, accumulate);
-  k_reduce_partials<<<(d + 63) / 64, 256, 0, c.stream>>>(c.partial + (size_t)nblk * d, nblk, d, db, accumulate);
+  k_reduce_partials<<<dim3((d + 63) / 64, 2), 64 * kReduceGroups, 0, c.stream>>>(c.partial, nblk, d, dg, accumulate, db);
   return LP_LAUNCH_CHECK();
 }
 
@@ -323,16 +363,50 @@ __global__ void k_colsum_partial(const T* dy, int64_t ld, float* partial, int ro
   if (w == 0 && col < n)
     partial[(size_t)blockIdx.y * n + col] = sh[0][threadIdx.x] + sh[1][threadIdx.x] + sh[2][threadIdx.x] + sh[3][threadIdx.x];
 }
+// bf16, 16-byte loads: block = 16 column chunks of 8 (128 columns) x 16 row lanes over a slab of kColsumRows
+// rows; row lane w adds rows w, w+16, ... in order, the 16 lane sums are then added in order.
+__global__ void __launch_bounds__(256)
+k_colsum_partial_v(const bf16_t* __restrict__ dy, int64_t ld, float* __restrict__ partial, int rows, int n) {
+  __shared__ float sh[16][128];
+  const int ch = threadIdx.x & 15, w = threadIdx.x >> 4;
+  const int col = blockIdx.x * 128 + ch * 8;
+  const int r0 = blockIdx.y * kColsumRows;
+  const int r1 = r0 + kColsumRows < rows ? r0 + kColsumRows : rows;
+  float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (col < n)
+    for (int r = r0 + w; r < r1; r += 16) {
+      bf16x8 v = *reinterpret_cast<const bf16x8*>(dy + (size_t)r * ld + col);
+#pragma unroll
+      for (int x = 0; x < 8; ++x) a[x] += (float)v[x];
+    }
+#pragma unroll
+  for (int x = 0; x < 8; ++x) sh[w][ch * 8 + x] = a[x];
+  __syncthreads();
+  if (threadIdx.x < 128) {
+    const int cc = blockIdx.x * 128 + threadIdx.x;
+    if (cc < n) {
+      float t = 0.f;
+#pragma unroll
+      for (int g = 0; g < 16; ++g) t += sh[g][threadIdx.x];
+      partial[(size_t)blockIdx.y * n + cc] = t;
+    }
+  }
+}
 hipError_t op_colsum(const OpCtx& c, const void* dy, int64_t ld, float* out, int rows, int n, int accumulate) {
   ProfScope prof_(c, KC_COLSUM);
   if (n == 0) return hipSuccess;
   int nslab = (rows + kColsumRows - 1) / kColsumRows;
   if (nslab < 1) nslab = 1;
   if ((size_t)nslab * n > c.partial_elems) return hipErrorInvalidValue;
+  if (c.dt == BF16 && n % 8 == 0 && ld % 8 == 0 && ((uintptr_t)dy & 15) == 0) {
+    k_colsum_partial_v<<<dim3((n + 127) / 128, nslab), 256, 0, c.stream>>>((const bf16_t*)dy, ld, c.partial, rows, n);
+    k_reduce_partials<<<(n + 63) / 64, 64 * kReduceGroups, 0, c.stream>>>(c.partial, nslab, n, out, accumulate);
+    return LP_LAUNCH_CHECK();
+  }
   dim3 grid((n + 63) / 64, nslab);
   if (c.dt == BF16) k_colsum_partial<bf16_t><<<grid, 256, 0, c.stream>>>((const bf16_t*)dy, ld, c.partial, rows, n);
   else k_colsum_partial<float><<<grid, 256, 0, c.stream>>>((const float*)dy, ld, c.partial, rows, n);
-  k_reduce_partials<<<(n + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, n, out, accumulate);
+  k_reduce_partials<<<(n + 63) / 64, 64 * kReduceGroups, 0, c.stream>>>(c.partial, nslab, n, out, accumulate);
   return LP_LAUNCH_CHECK();
 }
 

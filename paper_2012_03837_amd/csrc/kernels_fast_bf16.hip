@@ -331,21 +331,32 @@ __global__ void __launch_bounds__(256) k_bn_partial_v(const bf16_t* __restrict__
     partial[(size_t)(nslab + blockIdx.x) * C + j] = t1;
   }
 }
-// Adds the slab partials in order (64 channels x 4 slab groups per block) and finishes.
+// Adds the slab partials in order (64 channels x 16 slab groups per block: group q adds slabs q, q+16, ...
+// with two independent pairs of loads in flight, then the group sums are added in order) and finishes.
 // mode 0: forward statistics (needs the pivots from row 0 of z); mode 1: plain sums into sums[0..C), sums[C..2C).
-__global__ void k_bn_finish_v(const float* __restrict__ partial, int nslab, int C, int rows, const bf16_t* __restrict__ z,
-                              float* __restrict__ out0, float* __restrict__ out1, int mode) {
-  __shared__ float sh[2][4][64];
+constexpr int kBnFinishGroups = 16;
+__global__ void __launch_bounds__(64 * kBnFinishGroups)
+k_bn_finish_v(const float* __restrict__ partial, int nslab, int C, int rows, const bf16_t* __restrict__ z,
+              float* __restrict__ out0, float* __restrict__ out1, int mode) {
+  __shared__ float sh[2][kBnFinishGroups][64];
   const int lc = threadIdx.x & 63, q = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + lc;
   float a = 0.f, b = 0.f;
-  if (j < C)
-    for (int s = q; s < nslab; s += 4) { a += partial[(size_t)s * C + j]; b += partial[(size_t)(nslab + s) * C + j]; }
+  if (j < C) {
+    int s = q;
+    for (; s + kBnFinishGroups < nslab; s += 2 * kBnFinishGroups) {
+      const float a0 = partial[(size_t)s * C + j], b0 = partial[(size_t)(nslab + s) * C + j];
+      const float a1 = partial[(size_t)(s + kBnFinishGroups) * C + j], b1 = partial[(size_t)(nslab + s + kBnFinishGroups) * C + j];
+      a += a0; a += a1; b += b0; b += b1;
+    }
+    for (; s < nslab; s += kBnFinishGroups) { a += partial[(size_t)s * C + j]; b += partial[(size_t)(nslab + s) * C + j]; }
+  }
   sh[0][q][lc] = a; sh[1][q][lc] = b;
   __syncthreads();
   if (q != 0 || j >= C) return;
-  a = sh[0][0][lc] + sh[0][1][lc] + sh[0][2][lc] + sh[0][3][lc];
-  b = sh[1][0][lc] + sh[1][1][lc] + sh[1][2][lc] + sh[1][3][lc];
+  a = 0.f; b = 0.f;
+#pragma unroll
+  for (int g = 0; g < kBnFinishGroups; ++g) { a += sh[0][g][lc]; b += sh[1][g][lc]; }
   if (mode == 0) {
     const float inv = 1.f / (float)rows, m1 = a * inv;
     float var = b * inv - m1 * m1;
@@ -443,7 +454,7 @@ hipError_t bn_fwd_fast(const OpCtx& c, const void* z, const float* g, const floa
   const size_t shm = (size_t)2 * RL * C * sizeof(float);
   k_bn_partial_v<0><<<nslab, 256, shm, c.stream>>>((const bf16_t*)z, nullptr, (const bf16_t*)z, nullptr, nullptr,
                                                    c.partial, rows, C, slab, 0);
-  k_bn_finish_v<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, C, rows, (const bf16_t*)z, mean, rstd, 0);
+  k_bn_finish_v<<<(C + 63) / 64, 64 * kBnFinishGroups, 0, c.stream>>>(c.partial, nslab, C, rows, (const bf16_t*)z, mean, rstd, 0);
   const size_t nch = (size_t)rows * C / 8;
   k_bn_apply_v<<<blocks_for(nch), 256, 0, c.stream>>>((const bf16_t*)z, g, b, (const bf16_t*)res, (bf16_t*)y, mean, rstd,
                                                      nch, C, relu);
@@ -459,7 +470,7 @@ hipError_t bn_bwd_fast(const OpCtx& c, const void* dy, const void* y, const void
   const size_t shm = (size_t)2 * RL * C * sizeof(float);
   k_bn_partial_v<1><<<nslab, 256, shm, c.stream>>>((const bf16_t*)dy, (const bf16_t*)y, (const bf16_t*)z, mean, rstd,
                                                    c.partial, rows, C, slab, relu);
-  k_bn_finish_v<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, C, rows, nullptr, sums, sums + C, 1);
+  k_bn_finish_v<<<(C + 63) / 64, 64 * kBnFinishGroups, 0, c.stream>>>(c.partial, nslab, C, rows, nullptr, sums, sums + C, 1);
   const size_t nch = (size_t)rows * C / 8;
   k_bn_bwd_apply_v<<<blocks_for(nch), 256, 0, c.stream>>>((const bf16_t*)dy, (const bf16_t*)y, (const bf16_t*)z, mean,
                                                          rstd, g, sums, (bf16_t*)dz, (bf16_t*)dres, nch, C, rows, relu);

@@ -80,8 +80,8 @@ extern "C" int lpk_copy(const void* src, void* dst, size_t bytes, void* stream) 
   return (int)op_copy(mk(0, stream), src, dst, bytes);
 }
 extern "C" int lpk_embed_bwd(int dtype, const int32_t* ids, const void* dh, float* demb, int T, int V, int d,
-                             int accumulate, void* stream) {
-  return (int)op_embed_bwd(mk(dtype, stream), ids, dh, demb, T, V, d, accumulate);
+                             int accumulate, float* scratch, size_t scratch_elems, void* stream) {
+  return (int)op_embed_bwd(mk(dtype, stream, scratch, scratch_elems), ids, dh, demb, T, V, d, accumulate);
 }
 extern "C" int lpk_conv_fwd(int dtype, const void* x, const void* w, void* out, int N, int H, int W, int C, int O,
                             int R, int stride, int pad, void* stream) {

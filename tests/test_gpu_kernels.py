@@ -217,17 +217,22 @@ def test_optimizer_kernel(K, kind):
     np.testing.assert_array_equal(host(low), ops.bf16_round(host(dp).astype(np.float32)))
 
 
-def test_embed_bwd_repeated_tokens(K):
+@pytest.mark.parametrize("with_counts", [False, True])
+@pytest.mark.parametrize("accumulate", [0, 1])
+def test_embed_bwd_repeated_tokens(K, with_counts, accumulate):
     import torch
     rng = np.random.default_rng(0)
-    T, V, d = 700, 50, 136
-    ids = rng.integers(0, V, T).astype(np.int32)
+    T, V, d = 700, 90, 136
+    ids = rng.integers(0, 50, T).astype(np.int32)         # rows 50..89 never occur
     ids[:300] = 3
+    ids[5], ids[6] = -4, 1000                              # out of range: counted as rows 0 and V-1
     dh = rnd(rng, (T, d), 1)
     demb = ones(V, d)
-    K.lpk_embed_bwd(1, dev(ids, 0), dev(dh, 1), demb, T, V, d, 1)
-    ref = ops.embed_bwd(ids, V, dh.astype(np.float64)) + 1
+    scratch = zeros(4096) if with_counts else None
+    K.lpk_embed_bwd(1, dev(ids, 0), dev(dh, 1), demb, T, V, d, accumulate, scratch=scratch)
+    ref = ops.embed_bwd(np.clip(ids, 0, V - 1), V, dh.astype(np.float64)) + accumulate
     assert relerr(host(demb), ref) <= 1e-5
+    assert np.all(host(demb)[50:89] == accumulate)         # absent rows: exactly zero, or untouched
 
 
 # Shapes for the persistent direct-to-LDS GEMM: fewer tiles than blocks, exactly one wave of tiles,
