@@ -280,6 +280,33 @@ def main():
         "phases": phases,
         "final_losses": losses[:4],
     }
+    # the paper's hardware-independent axes for this configuration (appendix A): total and sequential FLOPs
+    # of one step, from the matmul / convolution / attention FLOPs counted above (backward = 2 x forward)
+    try:
+        import numpy as np
+        sub1 = __import__("dataclasses").replace(cfg, heads=cfg.heads[:0])
+        fwd_total = gemm_flops_per_step(sub1) + attention_flops_per_step(sub1)[0]
+        l0 = cfg.layers[cfg.heads[0].after_layer - 1]
+        rows = cfg.batch * (l0.seq_len if l0.kind == "decoder" else 1)
+        aux = 2.0 * rows * cfg.heads[0].in_dim * cfg.heads[0].n_classes / cfg.batch
+        npar = float(sum(int(np.prod(sh)) for sh in LI.param_shapes(cfg).values()))
+        wins = LI.head_windows(cfg)
+        widths = {e - s_ for (s_, e) in wins}
+        if len(wins) == 1:
+            method, Kc = "backprop", 1
+        elif len(wins) == cfg.n_layers and widths == {1}:
+            method, Kc = "greedy", 1
+        elif len(wins) == cfg.n_layers:
+            method, Kc = "overlap", 1
+        else:
+            method, Kc = "chunk", len(wins)
+        cpe, cost, tm, par = lp.lp_cost_model(fwd_total / cfg.batch / cfg.n_layers, aux, 2.0, cfg.n_layers, npar, method,
+                                             1.0, float(cfg.batch), Kc)
+        out["cost_model"] = {"method": method, "chunks": Kc, "forward_flops_per_layer_per_example": fwd_total / cfg.batch / cfg.n_layers,
+                             "aux_flops_per_example": aux, "backward_multiplier": 2.0, "parameters": npar,
+                             "total_flops_per_step": cost, "sequential_flops_per_step": tm, "parallelism": par}
+    except Exception as ex:      # the cost model is an annotation; it never fails the benchmark
+        out["cost_model"] = {"error": str(ex)}
     if cfg.layers[0].kind == "decoder":
         out["tokens_per_s"] = value * cfg.layers[0].seq_len
         out["config"].update(seq_len=cfg.layers[0].seq_len, d_model=cfg.layers[0].width, vocab=cfg.vocab)

@@ -174,6 +174,34 @@ const char* lp_last_error(const lp_ctx* ctx);
 /* Free host metadata.  Never frees caller memory. */
 void lp_destroy(lp_ctx* ctx);
 
+/* ---- FLOP cost model (appendix A, "Calculation of Total FLOPs and Sequential FLOPs") ----------------
+ * Host arithmetic only; no device is touched.  A model is four numbers: average forward FLOPs per layer per
+ * example, auxiliary-loss FLOPs per example, the backward multiplier, and its parameter count (the optimizer
+ * costs 10 FLOPs per parameter per step; overlapping adds 2 per parameter for averaging duplicated layers).
+ *   cost_per_example: backprop (1+bm)(L f + a); greedy (1+bm) L (f + a);
+ *                     overlapping L (f + a) + (L-1) bm (2 f + a) + bm (f + a);
+ *                     K chunks (1+bm)(L f + K a); last K layers (L f + a) + bm (K f + a)
+ *   cost = cost_per_example * steps * batch + steps * per-step optimizer cost
+ *   time = cost / (batch * parallelism), parallelism = 1, L, L, K, (L + K bm) / (K (1 + bm)) respectively.
+ * (The chunk and last-K lines are printed damaged in the paper; these forms reduce to greedy at K = L and to
+ * backprop at K = 1 resp. K = L, as the prose requires.)  K is ignored by the first three methods. */
+typedef enum { LP_METHOD_BACKPROP = 0, LP_METHOD_GREEDY = 1, LP_METHOD_OVERLAP = 2, LP_METHOD_CHUNK = 3,
+               LP_METHOD_LAST_K = 4 } lp_method;
+typedef struct {
+  double forward_cost;         /* average forward FLOPs per layer per example */
+  double aux_cost;             /* FLOPs of one auxiliary loss per example */
+  double backward_multiplier;
+  double parameters;
+  int layers;
+} lp_cost_inputs;
+typedef struct { double cost_per_example, cost, time, parallelism; } lp_cost;
+/* LP_EINVAL on a null pointer, an unknown method, layers < 1, K outside [1, layers] for the chunk / last-K
+ * methods, or non-positive steps / batch_size. */
+int lp_cost_model(const lp_cost_inputs* in, int method, int K, double steps, double batch_size, lp_cost* out);
+/* The MLP's constants (appendix A, "MLP"): layer = (2 I N - I) + N + 2 N with I = input_size for the first
+ * layer and N after it, averaged over `layers`; auxiliary classifier = (2 N 10 - N) + 10 + 5*10. */
+int lp_mlp_flops(int input_size, int hidden, int layers, double* forward_cost, double* aux_cost);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,6 +59,16 @@ class lp_buffers(C.Structure):
     _fields_ = [("params_dev", C.c_void_p), ("state_dev", C.c_void_p), ("work_dev", C.c_void_p)]
 
 
+class lp_cost_inputs(C.Structure):
+    _fields_ = [("forward_cost", C.c_double), ("aux_cost", C.c_double), ("backward_multiplier", C.c_double),
+                ("parameters", C.c_double), ("layers", C.c_int)]
+
+
+class lp_cost(C.Structure):
+    _fields_ = [("cost_per_example", C.c_double), ("cost", C.c_double), ("time", C.c_double),
+                ("parallelism", C.c_double)]
+
+
 _lib = None
 
 
@@ -87,6 +97,8 @@ def lib() -> C.CDLL:
         L.lp_profile_enable.argtypes = [vp, ip]
         L.lp_profile_read.argtypes = [vp, ip, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]
         L.lp_profile_gemm_shapes.argtypes = [vp, C.c_char_p, sz]
+        L.lp_cost_model.argtypes = [C.POINTER(lp_cost_inputs), ip, ip, C.c_double, C.c_double, C.POINTER(lp_cost)]
+        L.lp_mlp_flops.argtypes = [ip, ip, ip, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.lp_destroy.argtypes = [vp]
         L.lp_destroy.restype = None
         _lib = L
@@ -207,6 +219,28 @@ def lp_profile_gemm_shapes(ctx: int):
         rows.append({"M": int(M), "N": int(N), "K": int(K), "a_kc": int(a), "b_kc": int(b), "c_f32": int(f),
                      "count": int(n), "ms": float(ms)})
     return rows
+
+
+METHODS = {"backprop": 0, "greedy": 1, "overlap": 2, "chunk": 3, "last_k": 4}
+
+
+def lp_cost_model(forward_cost, aux_cost, backward_multiplier, layers, parameters, method, steps, batch_size, K=1):
+    """(cost_per_example, cost, time, parallelism) of the appendix-A cost model; method is a METHODS key."""
+    inp = lp_cost_inputs(float(forward_cost), float(aux_cost), float(backward_multiplier), float(parameters), int(layers))
+    out = lp_cost()
+    rc = lib().lp_cost_model(C.byref(inp), METHODS[method] if isinstance(method, str) else int(method), int(K),
+                             float(steps), float(batch_size), C.byref(out))
+    if rc != 0:
+        raise LpError(rc, "lp_cost_model: invalid argument")
+    return out.cost_per_example, out.cost, out.time, out.parallelism
+
+
+def lp_mlp_flops(input_size, hidden, layers):
+    f, a = C.c_double(), C.c_double()
+    rc = lib().lp_mlp_flops(int(input_size), int(hidden), int(layers), C.byref(f), C.byref(a))
+    if rc != 0:
+        raise LpError(rc, "lp_mlp_flops: invalid argument")
+    return f.value, a.value
 
 
 def lp_destroy(ctx: int) -> None:
