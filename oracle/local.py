@@ -173,3 +173,26 @@ def local_step(cfg, params, state, x, y, dtype=np.float64, stored=None):
         p = np.asarray(p, dtype=dtype)
         new[k] = optimizer_update(cfg.opt, p, grads[k], state, k, t) if k in grads else p
     return losses, new, grads
+
+
+def layer_gradient_cosines(cfg, grads_a, grads_b):
+    """Section 5, "Gradient Angles" (Fig. 6a): for every layer l, the cosine of the angle between two
+    gradients of all of layer l's parameters taken as one vector,
+        cos_l = <a_l, b_l> / (|a_l| |b_l|),
+    here between the gradients two schemes (e.g. greedy local updates and backprop) leave for the same
+    parameters and minibatch.  A layer for which either gradient is absent or zero gets 0."""
+    out = np.zeros(cfg.n_layers)
+    for l in range(1, cfg.n_layers + 1):
+        names = sorted(k for k in set(grads_a) | set(grads_b) if k.startswith(f"L{l}."))
+        dot = na = nb = 0.0
+        for k in names:
+            a = np.asarray(grads_a.get(k, 0.0), dtype=np.float64)
+            b = np.asarray(grads_b.get(k, 0.0), dtype=np.float64)
+            if k in grads_a:
+                na += float(np.sum(a * a))
+            if k in grads_b:
+                nb += float(np.sum(b * b))
+            if k in grads_a and k in grads_b:
+                dot += float(np.sum(a * b))
+        out[l - 1] = dot / np.sqrt(na * nb) if na > 0.0 and nb > 0.0 else 0.0
+    return out

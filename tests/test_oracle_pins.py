@@ -159,6 +159,53 @@ def test_p5_last_block_matches_backprop(kind):
     assert np.linalg.norm(gg[k_mid] - gb[k_mid]) > 1e-3 * np.linalg.norm(gb[k_mid])
 
 
+def backprop_params(g_cfg, P):
+    """The backprop scheme's parameters: the same layers, and the greedy scheme's last head as its only head."""
+    Pb = {k: v for k, v in P.items() if not k.startswith("H")}
+    nh = len(g_cfg.heads)
+    for k, v in P.items():
+        if k.startswith(f"H{nh}."):
+            Pb["H1." + k.split(".", 1)[1]] = v
+    return Pb
+
+
+@pytest.mark.parametrize("kind", ["mlp", "dec", "res"])
+def test_p11_gradient_cosines(kind):
+    """Section 5, "Gradient Angles": cosine per layer between greedy local and backprop gradients.  The last
+    layer's is exactly 1 (its local gradient is backprop's); the definition is checked on vectors with a known
+    angle, and for invariance under positive rescaling of either side."""
+    g_cfg = tiny(kind, scheme="greedy")
+    b_cfg = tiny(kind, scheme="backprop")
+    P, x, y = setup(g_cfg)
+    _, gg, _ = oracle.local_gradients(g_cfg, P, x, y)
+    _, gb, _ = oracle.local_gradients(b_cfg, backprop_params(g_cfg, P), x, y)
+    cos = oracle.layer_gradient_cosines(g_cfg, gg, gb)
+    L = g_cfg.n_layers
+    assert cos.shape == (L,)
+    assert abs(cos[L - 1] - 1.0) <= 1e-12
+    assert np.all(np.abs(cos) <= 1.0 + 1e-12)
+    assert abs(cos[0]) < 1.0 - 1e-6                      # an early layer is not parallel to backprop's gradient
+    # brute force for layer 1: one concatenated vector per side
+    a = np.concatenate([gg[k].ravel() for k in sorted(gg) if k.startswith("L1.")])
+    b = np.concatenate([gb[k].ravel() for k in sorted(gb) if k.startswith("L1.")])
+    assert cos[0] == pytest.approx(float(a @ b) / float(np.sqrt((a @ a) * (b @ b))), rel=1e-12)
+    # invariances: rescaling one side, and identical / opposite gradients
+    cos2 = oracle.layer_gradient_cosines(g_cfg, {k: 3.5 * v for k, v in gg.items()}, gb)
+    np.testing.assert_allclose(cos2, cos, rtol=1e-12)
+    np.testing.assert_allclose(oracle.layer_gradient_cosines(g_cfg, gg, gg), 1.0, rtol=1e-12)
+    np.testing.assert_allclose(oracle.layer_gradient_cosines(g_cfg, gg, {k: -v for k, v in gg.items()}), -1.0, rtol=1e-12)
+    # a known angle: 60 degrees between (1, 0) and (1/2, sqrt(3)/2) spread over two tensors of layer 1
+    k1, k2 = sorted(k for k in gg if k.startswith("L1."))[:2]
+    ea = {k1: np.zeros_like(gg[k1]), k2: np.zeros_like(gg[k2])}
+    eb = {k1: np.zeros_like(gg[k1]), k2: np.zeros_like(gg[k2])}
+    ea[k1].flat[0] = 1.0
+    eb[k1].flat[0] = 0.5
+    eb[k2].flat[0] = np.sqrt(3.0) / 2.0
+    assert oracle.layer_gradient_cosines(g_cfg, ea, eb)[0] == pytest.approx(0.5, rel=1e-12)
+    # a layer without a gradient on one side gets 0
+    assert oracle.layer_gradient_cosines(g_cfg, {k: v for k, v in gg.items() if not k.startswith("L1.")}, gb)[0] == 0.0
+
+
 def test_p6_overlap_bookkeeping():
     """Overlapping scheme (appendix A.2): two backward passes for each non-terminal layer, one
     for the terminal layer: 2L-1 (head, layer) pairs; mean = sum / coverage."""
