@@ -150,6 +150,14 @@ const char* lp_param_name(lp_ctx* ctx, int i);
 int lp_get_step(lp_ctx* ctx);
 int lp_set_step(lp_ctx* ctx, int t);
 
+/* Gradient similarity (section 5, "Gradient Angles"; Fig. 6a): out_dev[l-1] (device, n_layers floats) =
+ * cosine of the angle between the gradients that the last lp_local_step of ctx_a and of ctx_b left for
+ * layer l's parameters, all of the layer's tensors taken as one vector; 0 where either gradient is zero
+ * (a layer outside every window).  The contexts must describe the same layers (their heads may differ:
+ * e.g. greedy heads in one, a single head with a full window in the other).  Enqueued on ctx_a's stream
+ * after ctx_b's stream has been drained. */
+int lp_grad_cosine(lp_ctx* ctx_a, lp_ctx* ctx_b, float* out_dev);
+
 /* Per-kernel-class timing.  While enabled, every op brackets its launches with a pair of HIP events
  * on the context's stream, and the side streams are not used (each duration is then the op's own, not
  * shared with a concurrent chain; results are bit-identical either way).  lp_profile_read drains the stream and returns, for one class, the summed

@@ -99,6 +99,7 @@ def lib() -> C.CDLL:
         L.lp_profile_gemm_shapes.argtypes = [vp, C.c_char_p, sz]
         L.lp_cost_model.argtypes = [C.POINTER(lp_cost_inputs), ip, ip, C.c_double, C.c_double, C.POINTER(lp_cost)]
         L.lp_mlp_flops.argtypes = [ip, ip, ip, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.lp_grad_cosine.argtypes = [vp, vp, vp]
         L.lp_destroy.argtypes = [vp]
         L.lp_destroy.restype = None
         _lib = L
@@ -219,6 +220,10 @@ def lp_profile_gemm_shapes(ctx: int):
         rows.append({"M": int(M), "N": int(N), "K": int(K), "a_kc": int(a), "b_kc": int(b), "c_f32": int(f),
                      "count": int(n), "ms": float(ms)})
     return rows
+
+
+def lp_grad_cosine(ctx_a: int, ctx_b: int, out_dev_ptr: int) -> None:
+    _check(lib().lp_grad_cosine(ctx_a, ctx_b, out_dev_ptr), ctx_a)
 
 
 METHODS = {"backprop": 0, "greedy": 1, "overlap": 2, "chunk": 3, "last_k": 4}

@@ -106,6 +106,8 @@ struct ProfScope {
 // ---- ops (each enqueues on ctx.stream and returns a hipError_t) -------------------------------
 hipError_t op_gemm(const OpCtx& c, const GemmArgs& g);
 hipError_t op_fill_f32(const OpCtx& c, float* p, size_t n, float v);
+// out[0] = <a, b> / (|a| |b|) over n floats (0 if either norm is 0); uses 3 * 128 floats of c.partial
+hipError_t op_cosine(const OpCtx& c, const float* a, const float* b, size_t n, float* out);
 hipError_t op_copy(const OpCtx& c, const void* src, void* dst, size_t bytes);   // bytes % 16 == 0
 hipError_t op_cast_to_compute(const OpCtx& c, const float* src, void* dst, size_t n);
 

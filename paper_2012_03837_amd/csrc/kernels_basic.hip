@@ -465,6 +465,37 @@ hipError_t op_mean(const OpCtx& c, const float* v, int n, float* out) {
   return LP_LAUNCH_CHECK();
 }
 
+// ------------------------------------------------------------------------------------ cosine
+// <a, b>, <a, a>, <b, b> of two fp32 ranges: per-block partial sums in a fixed tree, then one block adds
+// the partials in order in double and writes <a, b> / sqrt(<a, a> <b, b>) (0 if either vector is zero).
+constexpr int kCosBlocks = 128;
+__global__ void __launch_bounds__(256) k_dot3_partial(const float* __restrict__ a, const float* __restrict__ b, size_t n,
+                                                      float* __restrict__ partial) {
+  __shared__ float sh[4];
+  float d = 0.f, aa = 0.f, bb = 0.f;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const float x = a[i], y = b[i];
+    d += x * y; aa += x * x; bb += y * y;
+  }
+  d = block_sum_256(d, sh);
+  aa = block_sum_256(aa, sh);
+  bb = block_sum_256(bb, sh);
+  if (threadIdx.x == 0) { partial[3 * blockIdx.x] = d; partial[3 * blockIdx.x + 1] = aa; partial[3 * blockIdx.x + 2] = bb; }
+}
+__global__ void k_cos_finish(const float* __restrict__ partial, int nblk, float* __restrict__ out) {
+  if (threadIdx.x != 0) return;
+  double d = 0.0, aa = 0.0, bb = 0.0;
+  for (int i = 0; i < nblk; ++i) { d += partial[3 * i]; aa += partial[3 * i + 1]; bb += partial[3 * i + 2]; }
+  out[0] = (aa > 0.0 && bb > 0.0) ? (float)(d / sqrt(aa * bb)) : 0.f;
+}
+hipError_t op_cosine(const OpCtx& c, const float* a, const float* b, size_t n, float* out) {
+  ProfScope prof_(c, KC_OTHER);
+  if ((size_t)3 * kCosBlocks > c.partial_elems) return hipErrorInvalidValue;
+  k_dot3_partial<<<kCosBlocks, 256, 0, c.stream>>>(a, b, n, c.partial);
+  k_cos_finish<<<1, 64, 0, c.stream>>>(c.partial, kCosBlocks, out);
+  return LP_LAUNCH_CHECK();
+}
+
 // ------------------------------------------------------------------------------------ optimizer
 // One fused pass over a flat parameter range: reads p, g (and m, v), writes p (and m, v) and the
 // low-precision working copy.  SGD: p -= lr g.  SGD-momentum: m = mu m + g; p -= lr m.

@@ -663,6 +663,25 @@ extern "C" const char* lp_param_name(lp_ctx* c, int i) {
   if (!c || i < 0 || i >= (int)c->tensors.size()) return nullptr;
   return c->tensors[i].name.c_str();
 }
+extern "C" int lp_grad_cosine(lp_ctx* a, lp_ctx* b, float* out_dev) {
+  if (!a || !b) return LP_EINVAL;
+  lp_ctx* c = a;     // errors are recorded on ctx_a
+  if (!a->ok || !b->ok) return fail(a, LP_ESTATE, "context is not usable");
+  if (!out_dev) return fail(a, LP_EINVAL, "out_dev is null");
+  if (a->spec.n_layers != b->spec.n_layers) return fail(a, LP_ESHAPE, "the two contexts have different numbers of layers");
+  for (int li = 1; li <= a->spec.n_layers; ++li)
+    if (a->layers[li].p_end - a->layers[li].p_begin != b->layers[li].p_end - b->layers[li].p_begin)
+      return fail(a, LP_ESHAPE, "layer " + std::to_string(li) + " has different parameters in the two contexts");
+  if (b->stream != a->stream) CK(hipStreamSynchronize(b->stream));     // b's gradients are complete
+  a->use(0);
+  for (int li = 1; li <= a->spec.n_layers; ++li) {
+    const LayerState& A = a->layers[li];
+    const LayerState& B = b->layers[li];
+    CK(op_cosine(a->op(), a->grads + A.p_begin, b->grads + B.p_begin, A.p_end - A.p_begin, out_dev + (li - 1)));
+  }
+  return LP_OK;
+}
+
 extern "C" int lp_get_step(lp_ctx* c) { return c ? c->step_t : -1; }
 extern "C" int lp_set_step(lp_ctx* c, int t) {
   if (!c) return LP_EINVAL;

@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 
 import lp_inputs as LI
+import oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -156,3 +157,39 @@ def test_side_streams_bit_identical(lpmod, name):
     x, y = data_for(cfg)
     compare_step(tr, cfg, generic_params(cfg), x, y, n_steps=1, label=name + "/streams", stored=stored_for(cfg))
     tr.close()
+
+
+@pytest.mark.parametrize("name,dtype,tol", [("cfg3_small", "f32", 1e-4), ("cfg1_small", "f32", 1e-4),
+                                            ("cfg3_small", "bf16", 2e-2)])
+def test_gradient_cosines_local_vs_backprop(lpmod, name, dtype, tol):
+    """Section 5, "Gradient Angles": per-layer cosine between greedy-local and backprop gradients on the same
+    parameters and minibatch, device reductions against the oracle's; the last layer's is 1."""
+    import torch
+    g_cfg = dataclasses.replace(LI.make_config(name, scheme="greedy"), dtype=dtype)
+    b_cfg = dataclasses.replace(LI.make_config(name, scheme="backprop"), dtype=dtype)
+    P = generic_params(g_cfg)
+    nh = len(g_cfg.heads)
+    Pb = {k: v for k, v in P.items() if not k.startswith("H")}
+    Pb.update({"H1." + k.split(".", 1)[1]: v for k, v in P.items() if k.startswith(f"H{nh}.")})
+    x, y = data_for(g_cfg)
+    ta, tb = lpmod.LocalTrainer(g_cfg), lpmod.LocalTrainer(b_cfg)
+    ta.set_params(P)
+    tb.set_params(Pb)
+    xd, yd = ta.stage(x, y)
+    ta.step(xd, yd)
+    tb.step(xd, yd)
+    out = torch.zeros(g_cfg.n_layers, device="cuda", dtype=torch.float32)
+    lpmod.lp_grad_cosine(ta.ctx, tb.ctx, out.data_ptr())
+    got = out.cpu().numpy().astype(np.float64)
+    Pq = {k: np.asarray(v, np.float64) for k, v in P.items()}
+    Pbq = {k: np.asarray(v, np.float64) for k, v in Pb.items()}
+    _, gg, _ = oracle.local_gradients(g_cfg, Pq, x, y)
+    _, gb, _ = oracle.local_gradients(b_cfg, Pbq, x, y)
+    ref = oracle.layer_gradient_cosines(g_cfg, gg, gb)
+    assert np.max(np.abs(got - ref)) <= tol, (got, ref)
+    assert abs(got[-1] - 1.0) <= (1e-5 if dtype == "f32" else 2e-3)
+    # a context against itself: exactly parallel
+    lpmod.lp_grad_cosine(ta.ctx, ta.ctx, out.data_ptr())
+    np.testing.assert_allclose(out.cpu().numpy(), 1.0, atol=1e-6)
+    ta.close()
+    tb.close()
