@@ -13,7 +13,7 @@ primitive and for a whole decoder layer.  The paper prints no numeric example of
 end-to-end values themselves are pinned only through those properties.
 """
 from .local import (eval_loss, local_gradients, local_step, block_gradients, new_state,
-                    forward_all, optimizer_update, layer_gradient_cosines)
+                    forward_all, optimizer_update, layer_gradient_cosines, new_pipeline, pipelined_step)
 
 __all__ = ["eval_loss", "local_gradients", "local_step", "block_gradients", "new_state",
-           "forward_all", "optimizer_update", "layer_gradient_cosines"]
+           "forward_all", "optimizer_update", "layer_gradient_cosines", "new_pipeline", "pipelined_step"]

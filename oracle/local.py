@@ -196,3 +196,44 @@ def layer_gradient_cosines(cfg, grads_a, grads_b):
                 dot += float(np.sum(a * b))
         out[l - 1] = dot / np.sqrt(na * nb) if na > 0.0 and nb > 0.0 else 0.0
     return out
+
+
+# ----------------------------------------------------------------------------- pipelined schedule
+def new_pipeline(cfg):
+    """State of the pipelined schedule: for every block j >= 2 the (activation, labels) pair that block j-1
+    produced in the previous call (None while the pipeline is still filling), and every block's own
+    number of updates."""
+    J = len(cfg.heads)
+    return {"stash": [None] * (J + 2), "updates": [0] * (J + 1)}
+
+
+def pipelined_step(cfg, params, state, pipe, x, y, dtype=np.float64, stored=None):
+    """One call of the pipelined form of local parallelism (section 6: the pipeline runs in steady state
+    after a ramp-up, updates applied asynchronously; section 3: activations and labels move forward one
+    stage per iteration, so every stage has the input and target it needs for local learning).
+
+    The heads' windows must tile the layers (block j = layers e_{j-1}+1 .. e_j).  In call t block 1 takes the
+    call's minibatch (x, y); block j >= 2 takes the activation block j-1 produced in call t-1 (with the
+    weights block j-1 had then) together with the labels that travelled with it, i.e. minibatch t-j+1.
+    Every block runs forward, its head's loss, the backward pass inside the block and its own update; a
+    block whose input has not arrived yet (t < j) does nothing and reports loss 0.  The optimizer's step
+    count of a block is the number of updates that block has taken.
+    Returns (losses, new params); ``state`` and ``pipe`` are updated in place."""
+    wins = _windows(cfg)
+    assert wins[0][0] == 0 and all(wins[j][0] == wins[j - 1][1] for j in range(1, len(wins))), "windows must tile"
+    J = len(cfg.heads)
+    losses = np.zeros(J)
+    new = {k: np.asarray(v, dtype=dtype) for k, v in params.items()}
+    nxt = [None] * (J + 2)
+    for j in range(1, J + 1):
+        inp = (x, y) if j == 1 else pipe["stash"][j]
+        if inp is None:
+            continue
+        loss, grads, out = block_gradients(cfg, params, j, inp[0], inp[1], dtype, stored)
+        losses[j - 1] = loss
+        pipe["updates"][j] += 1
+        for k, g in grads.items():
+            new[k] = optimizer_update(cfg.opt, np.asarray(params[k], dtype=dtype), g, state, k, pipe["updates"][j])
+        nxt[j + 1] = (out, inp[1])
+    pipe["stash"] = nxt
+    return losses, new

@@ -206,6 +206,61 @@ def test_p11_gradient_cosines(kind):
     assert oracle.layer_gradient_cosines(g_cfg, {k: v for k, v in gg.items() if not k.startswith("L1.")}, gb)[0] == 0.0
 
 
+@pytest.mark.parametrize("kind", ["mlp", "dec", "res"])
+def test_p12_pipelined_schedule(kind):
+    """Pipelined form (section 6; section 3, labels travel with the activations).  (a) one block: identical to
+    the synchronous step; (b) frozen weights (lr 0): head j in call t reports exactly the synchronous loss of
+    minibatch t-j+1, and 0 while the pipeline fills; (c) with updates on, block 2's input in call t is block 1's
+    output of call t-1 under the weights block 1 had then (a delay line written out by hand), and a block
+    that has not started keeps its weights bit for bit."""
+    # (a)
+    b_cfg = tiny(kind, scheme="backprop")
+    P, x, y = setup(b_cfg)
+    st_a, st_b = oracle.new_state(b_cfg, P), oracle.new_state(b_cfg, P)
+    pipe = oracle.new_pipeline(b_cfg)
+    la, Pa, _ = oracle.local_step(b_cfg, P, st_a, x, y)
+    lb, Pb = oracle.pipelined_step(b_cfg, P, st_b, pipe, x, y)
+    np.testing.assert_array_equal(la, lb)
+    for k in Pa:
+        np.testing.assert_array_equal(Pa[k], Pb[k])
+    # (b)
+    g_cfg = tiny(kind, scheme="greedy")
+    frozen = dataclasses.replace(g_cfg, opt=dataclasses.replace(g_cfg.opt, kind="sgd", lr=0.0))
+    P, _, _ = setup(frozen)
+    J = len(frozen.heads)
+    batches = [LI.make_batch(frozen, i) for i in range(J + 2)]
+    sync = [oracle.eval_loss(frozen, P, bx, by) for bx, by in batches]
+    st, pipe, cur = oracle.new_state(frozen, P), oracle.new_pipeline(frozen), P
+    for t, (bx, by) in enumerate(batches, start=1):
+        losses, cur = oracle.pipelined_step(frozen, cur, st, pipe, bx, by)
+        for j in range(1, J + 1):
+            want = sync[t - j][j - 1] if t - j >= 0 else 0.0
+            assert losses[j - 1] == pytest.approx(want, rel=1e-13, abs=0.0), (t, j)
+    # (c)
+    P, _, _ = setup(g_cfg)
+    st, pipe = oracle.new_state(g_cfg, P), oracle.new_pipeline(g_cfg)
+    (x1, y1), (x2, y2) = LI.make_batch(g_cfg, 0), LI.make_batch(g_cfg, 1)
+    l1, P1 = oracle.pipelined_step(g_cfg, P, st, pipe, x1, y1)
+    assert np.all(l1[1:] == 0.0)
+    for k in P:
+        if not (k.startswith("L1.") or k.startswith("H1.")):
+            np.testing.assert_array_equal(P1[k], np.asarray(P[k], np.float64))     # blocks 2.. have not started
+    l2, P2 = oracle.pipelined_step(g_cfg, P1, st, pipe, x2, y2)
+    # by hand: block 1's output on minibatch 1 under the ORIGINAL weights feeds block 2 now, with labels y1
+    _, _, a1 = oracle.block_gradients(g_cfg, P, 1, x1, y1)
+    loss2, grads2, _ = oracle.block_gradients(g_cfg, P1, 2, a1, y1)
+    assert l2[1] == pytest.approx(loss2, rel=1e-14)
+    st_hand = oracle.new_state(g_cfg, P)
+    for k, g in grads2.items():
+        np.testing.assert_allclose(P2[k], oracle.optimizer_update(g_cfg.opt, np.asarray(P1[k], np.float64), g, st_hand, k, 1),
+                                   rtol=1e-14, atol=0)
+    # ... and not the output under the updated weights (the input really is one call stale)
+    _, _, a1_new = oracle.block_gradients(g_cfg, P1, 1, x1, y1)
+    assert np.linalg.norm(a1_new - a1) > 1e-9 * np.linalg.norm(a1)
+    # block 1 meanwhile works on minibatch 2
+    assert l2[0] == pytest.approx(oracle.block_gradients(g_cfg, P1, 1, x2, y2)[0], rel=1e-14)
+
+
 def test_p6_overlap_bookkeeping():
     """Overlapping scheme (appendix A.2): two backward passes for each non-terminal layer, one
     for the terminal layer: 2L-1 (head, layer) pairs; mean = sum / coverage."""
