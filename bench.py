@@ -166,6 +166,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg3", help="cfg1..cfg5")
     ap.add_argument("--streams", type=int, default=3, help="side streams for the heads' chains (0 = one stream)")
+    ap.add_argument("--schedule", default="sync", choices=["sync", "pipelined"],
+                    help="sync: every block works on the call's minibatch (the headline metric); pipelined: block j "
+                         "works on block j-1's output of the previous call (steady state after warm-up)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the HIP-event pass (used under rocprofv3)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -197,7 +200,7 @@ def main():
                                                "bytes_written_per_launch": n}}))
         return
     cfg = LI.make_config(args.config)
-    tr = lp.LocalTrainer(cfg, n_streams=args.streams)
+    tr = lp.LocalTrainer(cfg, n_streams=args.streams, schedule=args.schedule)
     K, W = args.steps, args.warmup
     n_stage = min(K + W, 8)
     staged = [tr.stage(*LI.make_batch(cfg, i)) for i in range(n_stage)]
@@ -275,7 +278,8 @@ def main():
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "batch": cfg.batch, "n_layers": cfg.n_layers, "n_heads_aux": len(cfg.heads),
                    "windows": LI.head_windows(cfg)[:3] + (["..."] if len(cfg.heads) > 3 else []),
-                   "optimizer": cfg.opt.kind, "combine": cfg.combine, "side_streams": args.streams},
+                   "optimizer": cfg.opt.kind, "combine": cfg.combine, "side_streams": args.streams,
+                   "schedule": args.schedule},
         "roofline": roofline,
         "phases": phases,
         "final_losses": losses[:4],

@@ -64,6 +64,11 @@ typedef enum {
 typedef enum { LP_OPT_SGD = 0, LP_OPT_SGDM = 1, LP_OPT_ADAM = 2 } lp_opt_kind;
 typedef enum { LP_COMBINE_SUM = 0, LP_COMBINE_MEAN = 1 } lp_combine;
 typedef enum { LP_ACT_GELU = 0, LP_ACT_RELU = 1 } lp_act;
+/* LP_SCHED_SYNC: every block works on the call's minibatch (one forward pass with the current weights).
+ * LP_SCHED_PIPELINED: the steady-state pipeline of section 6 / section 3: block 1 works on the call's
+ * minibatch, block j >= 2 on the activation that block j-1 produced in the previous call, with the labels
+ * that travelled with it; blocks are then independent within a call.  Needs windows that tile the layers. */
+typedef enum { LP_SCHED_SYNC = 0, LP_SCHED_PIPELINED = 1 } lp_schedule;
 
 typedef struct {
   int kind;                 /* lp_layer_kind */
@@ -103,6 +108,7 @@ typedef struct {
                                forward pass continues on the caller's stream; all of them are joined back
                                into the caller's stream before lp_local_step returns.  Results do not depend
                                on n (every per-parameter accumulation keeps its order).  At most 8.        */
+  int schedule;             /* lp_schedule: how lp_local_step feeds the blocks (see there)                 */
 } lp_model_spec;
 
 typedef struct { size_t param_bytes, state_bytes, work_bytes; } lp_sizes;
@@ -127,7 +133,13 @@ int lp_init_blocks(const lp_model_spec* spec, const lp_buffers* buffers, void* h
  * NHWC [batch, H, W, C] in the compute dtype (resnet), int32 [batch, seq_len] token ids (decoder
  * with vocab).  y_dev: int32 [batch] class labels, or int32 [batch, seq_len] next-token targets.
  * losses_dev: fp32 [n_heads], head j's mean loss at the PRE-update weights.  Asynchronous: results
- * are valid once the context's stream has been synchronised. */
+ * are valid once the context's stream has been synchronised.
+ * With schedule LP_SCHED_PIPELINED, call t gives block 1 the minibatch (x, y) and block j >= 2 the output
+ * of block j-1 from call t-1 (computed with the weights block j-1 had then) and minibatch t-j+1's labels;
+ * each block runs forward, loss, in-block backward and its update (its optimizer step count is its own
+ * number of updates).  A block whose input has not arrived yet (t < j) does nothing and reports loss 0.
+ * x_dev and y_dev are copied where a later call needs them and may be reused after the call.  A call with
+ * batch 0 does not advance the pipeline.  lp_eval_loss is the same in both schedules. */
 int lp_local_step(lp_ctx* ctx, const void* x_dev, const int32_t* y_dev, int batch, float* losses_dev);
 
 /* Forward pass and head losses only; no state changes.  (BatchNorm uses the statistics of the

@@ -48,7 +48,8 @@ class lp_opt_spec(C.Structure):
 class lp_model_spec(C.Structure):
     _fields_ = [("n_layers", C.c_int), ("layers", C.POINTER(lp_layer_spec)), ("n_heads", C.c_int),
                 ("heads", C.POINTER(lp_head_spec)), ("opt", lp_opt_spec), ("combine", C.c_int), ("dtype", C.c_int),
-                ("max_batch", C.c_int), ("vocab", C.c_int), ("seed", C.c_uint64), ("n_streams", C.c_int)]
+                ("max_batch", C.c_int), ("vocab", C.c_int), ("seed", C.c_uint64), ("n_streams", C.c_int),
+                ("schedule", C.c_int)]
 
 
 class lp_sizes(C.Structure):
@@ -106,7 +107,10 @@ def lib() -> C.CDLL:
     return _lib
 
 
-def make_spec(cfg, max_batch: int | None = None, n_streams: int = 0):
+SCHEDULES = {"sync": 0, "pipelined": 1}
+
+
+def make_spec(cfg, max_batch: int | None = None, n_streams: int = 0, schedule: str = "sync"):
     """lp_model_spec from a plain-data model description (fields as in lp_inputs.ModelCfg).
     Returns (spec, keepalive): the arrays the spec points into must outlive its use."""
     layers = (lp_layer_spec * len(cfg.layers))()
@@ -120,7 +124,7 @@ def make_spec(cfg, max_batch: int | None = None, n_streams: int = 0):
     opt = lp_opt_spec(OPT_KINDS[o.kind], o.lr, o.momentum, o.beta1, o.beta2, o.eps, o.weight_decay)
     spec = lp_model_spec(len(cfg.layers), layers, len(cfg.heads), heads, opt, COMBINE[cfg.combine],
                          DTYPES[cfg.dtype], cfg.batch if max_batch is None else max_batch, cfg.vocab, cfg.seed,
-                         n_streams)
+                         n_streams, SCHEDULES[schedule])
     return spec, (layers, heads)
 
 
@@ -255,14 +259,15 @@ def lp_destroy(ctx: int) -> None:
 class LocalTrainer:
     """Owns the three device buffers (torch tensors) and a context over them."""
 
-    def __init__(self, cfg, device="cuda:0", max_batch: int | None = None, stream=None, n_streams: int = 0):
+    def __init__(self, cfg, device="cuda:0", max_batch: int | None = None, stream=None, n_streams: int = 0,
+                 schedule: str = "sync"):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the local-update step runs only on the HIP device")
         self.torch = torch
         self.cfg = cfg
         self.device = torch.device(device)
-        self.spec, self._keep = make_spec(cfg, max_batch, n_streams)
+        self.spec, self._keep = make_spec(cfg, max_batch, n_streams, schedule)
         sz = lp_query_sizes(self.spec)
         self.sizes = sz
         with torch.cuda.device(self.device):

@@ -40,6 +40,7 @@ struct LayerState {
   int coverage = 0;                  // number of heads whose window covers this layer
   int seen = 0;                      // contributions received so far in the current step
   void* out = nullptr;               // layer output (compute dtype)
+  const void* in_override = nullptr; // pipelined schedule: this layer reads its input here (a block's first layer)
   size_t out_elems_per_sample = 0;
   // tensor indices (−1 if absent)
   std::map<std::string, int> t;
@@ -112,6 +113,13 @@ struct lp_ctx : lp_scratch {
   std::vector<lp_scratch> sets;
   int n_side = 0;
   std::vector<hipEvent_t> ev_fwd, ev_contrib, ev_chain;
+  // pipelined schedule (1-based by block = head): the input of block j >= 2, the labels each block uses,
+  // the batch size of each block's current input and of its last run, and each block's update count
+  std::vector<void*> stash_act;
+  std::vector<int32_t*> ybuf;
+  std::vector<int> in_batch, ran_batch, blk_updates;
+  size_t label_elems_per_sample = 1;
+  hipEvent_t ev_pipe = nullptr;
   void use(int i) { static_cast<lp_scratch&>(*this) = sets[i]; }
   int step_t = 0;
   int last_batch = 0;

@@ -25,6 +25,7 @@ size_t layer_out_elems(const lp_layer_spec& s, int batch) {
 }
 
 static const void* layer_input(lp_ctx* c, int li) {
+  if (c->layers[li].in_override) return c->layers[li].in_override;
   if (li == 1) return (c->spec.vocab > 0 && c->layers[1].s.kind == LP_LAYER_DECODER) ? c->h0 : c->x_in;
   return c->layers[li - 1].out;
 }

@@ -76,6 +76,16 @@ static int validate(const lp_model_spec* sp, std::string& err) {
     if (kind0 == LP_LAYER_DECODER && h.n_classes != sp->vocab) { err = std::string(where) + "n_classes != vocab"; return LP_ESHAPE; }
     if (kind0 == LP_LAYER_DECODER && h.bias) { err = std::string(where) + "vocabulary heads have no bias"; return LP_EUNSUPPORTED; }
   }
+  if (sp->schedule != LP_SCHED_SYNC && sp->schedule != LP_SCHED_PIPELINED) { err = "bad schedule"; return LP_EINVAL; }
+  if (sp->schedule == LP_SCHED_PIPELINED) {     // blocks must tile the layers: window j starts where window j-1 ends
+    int end = 0;
+    for (int j = 0; j < sp->n_heads; ++j) {
+      const lp_head_spec& h = sp->heads[j];
+      int w = h.window < h.after_layer ? h.window : h.after_layer;
+      if (h.after_layer - w != end) { err = "the pipelined schedule needs windows that tile the layers"; return LP_EUNSUPPORTED; }
+      end = h.after_layer;
+    }
+  }
   return LP_OK;
 }
 
@@ -262,6 +272,17 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
     c->pe = (float*)wa.take((size_t)l.seq_len * l.width * 4);
     c->h0 = wa.take((size_t)B * l.seq_len * l.width * es);
   }
+  if (sp.schedule == LP_SCHED_PIPELINED) {
+    const int J = sp.n_heads;
+    c->label_elems_per_sample = kind0 == LP_LAYER_DECODER ? (size_t)sp.layers[0].seq_len : 1;
+    c->stash_act.assign(J + 1, nullptr);
+    c->ybuf.assign(J + 1, nullptr);
+    for (int j = 1; j <= J; ++j) {
+      if (j >= 2) c->stash_act[j] = wa.take(layer_out_elems(c->layers[c->heads[j - 2].e].s, B) * es);
+      c->ybuf[j] = (int32_t*)wa.take((size_t)B * c->label_elems_per_sample * 4);
+    }
+    c->in_batch.assign(J + 1, 0); c->ran_batch.assign(J + 1, 0); c->blk_updates.assign(J + 1, 0);
+  }
   // one scratch set for the caller's stream and one per side stream
   c->n_side = sp.n_streams;
   c->sets.assign(1 + c->n_side, lp_scratch());
@@ -377,6 +398,7 @@ extern "C" int lp_init_blocks(const lp_model_spec* spec, const lp_buffers* buffe
       for (auto* v : {&c->ev_fwd, &c->ev_contrib, &c->ev_chain})
         for (auto& ev : *v)
           if (es_ == hipSuccess) es_ = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+      if (es_ == hipSuccess) es_ = hipEventCreateWithFlags(&c->ev_pipe, hipEventDisableTiming);
     }
     if (es_ != hipSuccess) { c->err = std::string("stream/event creation: ") + hipGetErrorString(es_); return bail(LP_EDEVICE); }
   }
@@ -481,6 +503,7 @@ extern "C" void lp_destroy(lp_ctx* c) {
   for (auto* v : {&c->ev_fwd, &c->ev_contrib, &c->ev_chain})
     for (auto ev : *v)
       if (ev) (void)hipEventDestroy(ev);
+  if (c->ev_pipe) (void)hipEventDestroy(c->ev_pipe);
   prof_free(c);
   delete c;
 }
@@ -497,13 +520,71 @@ static int check_call(lp_ctx* c, const void* x, const int32_t* y, int batch, flo
   return LP_OK;
 }
 
-static int optimizer_range(lp_ctx* c, size_t b, size_t e, float grad_scale) {
+static int optimizer_range(lp_ctx* c, size_t b, size_t e, float grad_scale, int t = -1) {
   OptArgs a;
   const lp_opt_spec& s = c->spec.opt;
   a.kind = s.kind; a.lr = s.lr; a.momentum = s.momentum; a.beta1 = s.beta1; a.beta2 = s.beta2; a.eps = s.eps;
-  a.weight_decay = s.weight_decay; a.t = c->step_t; a.grad_scale = grad_scale;
+  a.weight_decay = s.weight_decay; a.t = t >= 0 ? t : c->step_t; a.grad_scale = grad_scale;
   CK(op_optimizer(c->op(), a, c->master + b, c->grads + b, c->mom ? c->mom + b : nullptr,
                   c->var ? c->var + b : nullptr, c->lowp ? (void*)((bf16_t*)c->lowp + b) : nullptr, e - b));
+  return LP_OK;
+}
+
+// One call of the pipelined schedule: first the hand-over on the caller's stream (every block's output of
+// the previous call and the labels that go with it move one block forward; the call's labels are kept for
+// the following calls), then every block that has an input runs as an independent chain.
+static int run_pipelined(lp_ctx* c, const void* x, const int32_t* y, int batch, float* losses) {
+  const int J = c->spec.n_heads;
+  const size_t es = dtype_size(c->dt), ly = c->label_elems_per_sample * 4;
+  c->use(0);
+  CK(op_fill_f32(c->op(), losses, (size_t)J, 0.f));
+  c->x_in = x;
+  c->last_batch = batch;
+  c->step_t += 1;
+  for (int j = J; j >= 2; --j) {
+    const int nb = c->ran_batch[j - 1];            // what block j-1 produced in the previous call
+    c->in_batch[j] = nb;
+    if (nb == 0) continue;
+    const LayerState& src = c->layers[c->heads[j - 2].e];
+    CK(hipMemcpyAsync(c->stash_act[j], src.out, layer_out_elems(src.s, nb) * es, hipMemcpyDeviceToDevice, c->stream));
+    CK(hipMemcpyAsync(c->ybuf[j], c->ybuf[j - 1], (size_t)nb * ly, hipMemcpyDeviceToDevice, c->stream));
+  }
+  c->in_batch[1] = batch;
+  CK(hipMemcpyAsync(c->ybuf[1], y, (size_t)batch * ly, hipMemcpyDeviceToDevice, c->stream));
+  const bool side = c->n_side > 0 && !c->prof.on;
+  if (side) CK(hipEventRecord(c->ev_pipe, c->stream));
+  const int32_t* ids = c->spec.vocab > 0 ? (const int32_t*)x : nullptr;
+  for (int li = 1; li <= c->spec.n_layers; ++li) { c->layers[li].seen = 0; c->layers[li].in_override = nullptr; }
+  int chain = 0, st;
+  for (int j = 1; j <= J; ++j) {
+    const int nb = c->in_batch[j];
+    c->ran_batch[j] = nb;
+    if (nb == 0) continue;
+    HeadState& Hd = c->heads[j - 1];
+    const int set = side ? 1 + (chain++ % c->n_side) : 0;
+    c->use(set);
+    if (set) CK(hipStreamWaitEvent(c->cur_stream, c->ev_pipe, 0));
+    if (j >= 2) c->layers[Hd.s_lo + 1].in_override = c->stash_act[j];
+    for (int li = Hd.s_lo + 1; li <= Hd.e; ++li)
+      if ((st = drv_forward(c, li, nb, ids)) != LP_OK) return st;
+    if ((st = drv_head(c, j - 1, nb, c->ybuf[j], losses + (j - 1), true, c->dA)) != LP_OK) return st;
+    void* dcur = c->dA; void* dnext = c->dB;
+    for (int lj = Hd.e; lj > Hd.s_lo; --lj) {
+      if ((st = drv_backward(c, lj, nb, dcur, dnext, lj > Hd.s_lo + 1, 0)) != LP_OK) return st;
+      c->layers[lj].seen = 1;
+      void* t = dcur; dcur = dnext; dnext = t;
+    }
+    const int t_blk = ++c->blk_updates[j];          // the block's own number of updates
+    if ((st = optimizer_range(c, Hd.p_begin, Hd.p_end, 1.f, t_blk)) != LP_OK) return st;
+    for (int lj = Hd.e; lj > Hd.s_lo; --lj)
+      if ((st = optimizer_range(c, c->layers[lj].p_begin, c->layers[lj].p_end, 1.f, t_blk)) != LP_OK) return st;
+    if (set) CK(hipEventRecord(c->ev_chain[j - 1], c->cur_stream));
+    else if (side) CK(hipEventRecord(c->ev_chain[j - 1], c->stream));
+  }
+  c->use(0);
+  if (side)
+    for (int j = 1; j <= J; ++j)
+      if (c->ran_batch[j] > 0) CK(hipStreamWaitEvent(c->stream, c->ev_chain[j - 1], 0));
   return LP_OK;
 }
 
@@ -511,6 +592,8 @@ static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* los
   int st = check_call(c, x, y, batch, losses);
   if (st != LP_OK) return st;
   int L = c->spec.n_layers, J = c->spec.n_heads;
+  if (train && batch > 0 && c->spec.schedule == LP_SCHED_PIPELINED) return run_pipelined(c, x, y, batch, losses);
+  for (int li = 1; li <= L; ++li) c->layers[li].in_override = nullptr;
   if (batch == 0) {
     CK(op_fill_f32(c->op(), losses, (size_t)J, 0.f));
     return LP_OK;

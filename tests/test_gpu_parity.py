@@ -193,3 +193,46 @@ def test_gradient_cosines_local_vs_backprop(lpmod, name, dtype, tol):
     np.testing.assert_allclose(out.cpu().numpy(), 1.0, atol=1e-6)
     ta.close()
     tb.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1_small", "cfg3_small", "cfg2_small", "cfg5_small"])
+def test_pipelined_schedule_matches_oracle(lpmod, name):
+    """The pipelined schedule (section 6; labels travel with the activations, section 3) over J + 2 calls with a
+    different minibatch each: losses (exactly 0 while a block waits for its first input), every block's
+    parameters and optimizer moments after the last call, against the oracle's delay line; and the same
+    bits with the blocks spread over side streams."""
+    cfg = dataclasses.replace(LI.make_config(name), dtype="f32")
+    J = len(cfg.heads)
+    P0 = generic_params(cfg)
+    finals = []
+    for ns in (0, 2):
+        tr = lpmod.LocalTrainer(cfg, schedule="pipelined", n_streams=ns)
+        tr.set_params(P0)
+        P = {k: v.astype(np.float64) for k, v in P0.items()}
+        st, pipe = oracle.new_state(cfg, P), oracle.new_pipeline(cfg)
+        for t in range(1, J + 3):
+            x, y = data_for(cfg, t)
+            xd, yd = tr.stage(x, y)
+            got = tr.step(xd, yd).cpu().numpy().copy()
+            ref, P = oracle.pipelined_step(cfg, P, st, pipe, x, y)
+            for j in range(J):
+                if t < j + 1:
+                    assert got[j] == 0.0 and ref[j] == 0.0, (t, j)
+                else:
+                    assert abs(got[j] - ref[j]) <= 1e-4 * abs(ref[j]), (name, t, j, got[j], ref[j])
+        got_params = tr.get_params()
+        for k in P0:
+            assert relerr(got_params[k], P[k]) <= 2e-4, (name, k, relerr(got_params[k], P[k]))
+            for sname in ("m", "v"):
+                if sname in st:
+                    assert relerr(tr.get(k + "." + sname), st[sname][k]) <= 4e-4, (name, sname, k)
+        finals.append(got_params)
+        tr.close()
+    for k in P0:
+        np.testing.assert_array_equal(finals[0][k], finals[1][k])
+
+
+def test_pipelined_schedule_needs_tiling_windows(lpmod):
+    cfg = dataclasses.replace(LI.make_config("cfg4_small"), dtype="f32")      # overlapping windows
+    with pytest.raises(lpmod.LpError):
+        lpmod.LocalTrainer(cfg, schedule="pipelined")
