@@ -10,7 +10,8 @@
 // The accumulator layout of v_mfma_f32_32x32x16_bf16 (value v of lane l: row 8*(v/4) + 4*(l/32) + v%4,
 // column l%32) is exactly the B-operand layout of the next MFMA over the row index, so P and dS
 // never pass through LDS.  Operands whose reduction index is the slow one in memory (V for the
-// forward, K for dQ, Q and dO for dK/dV) are transposed on their way into LDS.
+// forward, K for dQ, Q and dO for dK/dV) sit in LDS as in memory and are read with the transposing LDS
+// read (ds_read_b64_tr_b16).  The next tile's global loads are issued before the current tile's MFMAs.
 // Layout: qkv [B*S, 3*H*64] (q | k | v, head h at columns h*64..), o [B*S, H*64], lse [B, H, S].
 #include "common.h"
 
@@ -39,42 +40,50 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int kk) {
   for (int e = 0; e < 8; ++e) r[e] = (bf16_t)a[8 * kk + e];
   return r;
 }
-// A-operand fragment from a transposed LDS tile t[row][col]: the 8 reduction indices of lane half hf
-// in k-step kk of 32-wide block i are col0 + {4hf..4hf+3} and col0 + 8 + {4hf..4hf+3}, col0 = 32i + 16kk.
-__device__ __forceinline__ bf16x8 frag_t(const bf16_t (*t)[ALD], int row, int col0, int hf) {
-  bf16x4 lo = *reinterpret_cast<const bf16x4*>(&t[row][col0 + 4 * hf]);
-  bf16x4 hi = *reinterpret_cast<const bf16x4*>(&t[row][col0 + 8 + 4 * hf]);
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+// A-operand fragment over a reduction index that is the ROW index of a straight LDS tile s[row][col] (a
+// key or query index), for output rows that are its columns c0 .. c0+31 (head-size index): lane (n, hf)
+// gets s[r0 + {4hf..4hf+3}][c0 + n] and s[r0 + 8 + {4hf..4hf+3}][c0 + n], the order in which the previous
+// MFMA's accumulator holds P / dS.  Done with the transposing LDS read (ds_read_b64_tr_b16): within a
+// 16-lane group, lane 4r+c supplies the 8-byte chunk s[row + r][4c..4c+3] and lane 4c+e receives element e
+// of the four chunks r = 0..3, so nothing is ever stored transposed.
+__device__ __forceinline__ bf16x8 frag_tr(const bf16_t (*s)[ALD], int r0, int c0, int lane) {
+  const int g = lane >> 4, l16 = lane & 15, hf = g >> 1;
+  const bf16_t* p = &s[r0 + 4 * hf + (l16 >> 2)][c0 + 16 * (g & 1) + 4 * (l16 & 3)];
+  bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p));
+  bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 8 * ALD));
   bf16x8 r;
 #pragma unroll
   for (int e = 0; e < 4; ++e) { r[e] = lo[e]; r[4 + e] = hi[e]; }
   return r;
 }
-// Stage a [64 rows][64 cols] bf16 tile (rows r0.., row stride ld, valid rows < nrows) into LDS, straight
-// and/or transposed.  256 threads, 16 elements each.
-__device__ __forceinline__ void stage_tile(const bf16_t* src, size_t ld, int r0, int nrows, bf16_t (*straight)[ALD],
-                                           bf16_t (*transposed)[ALD]) {
-  int r = threadIdx.x >> 2, ch = (threadIdx.x & 3) * 16;
-  bf16x8 v0 = zero8(), v1 = zero8();
+// A [64 rows][64 cols] bf16 tile (rows r0.., row stride ld, rows >= nrows read as zero) on its way into
+// LDS: 256 threads, 16 elements each, held in registers between the global load and the LDS store so that
+// the next tile's loads fly while the current tile is computed.
+struct TileRegs { bf16x8 v0, v1; };
+__device__ __forceinline__ TileRegs load_tile(const bf16_t* src, size_t ld, int r0, int nrows) {
+  const int r = threadIdx.x >> 2, ch = (threadIdx.x & 3) * 16;
+  TileRegs t;
+  t.v0 = zero8(); t.v1 = zero8();
   if (r0 + r < nrows) {
     const bf16_t* p = src + (size_t)(r0 + r) * ld + ch;
-    v0 = *reinterpret_cast<const bf16x8*>(p);
-    v1 = *reinterpret_cast<const bf16x8*>(p + 8);
+    t.v0 = *reinterpret_cast<const bf16x8*>(p);
+    t.v1 = *reinterpret_cast<const bf16x8*>(p + 8);
   }
-  if (straight) {
-    *reinterpret_cast<bf16x8*>(&straight[r][ch]) = v0;
-    *reinterpret_cast<bf16x8*>(&straight[r][ch + 8]) = v1;
-  }
-  if (transposed) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { transposed[ch + j][r] = v0[j]; transposed[ch + 8 + j][r] = v1[j]; }
-  }
+  return t;
+}
+__device__ __forceinline__ void store_tile(const TileRegs& t, bf16_t (*dst)[ALD]) {
+  const int r = threadIdx.x >> 2, ch = (threadIdx.x & 3) * 16;
+  *reinterpret_cast<bf16x8*>(&dst[r][ch]) = t.v0;
+  *reinterpret_cast<bf16x8*>(&dst[r][ch + 8]) = t.v1;
 }
 
 // ================================================================================= forward
 __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
                                                        float* __restrict__ lse, int S, int H, int causal) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[64][ALD];
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[64][ALD];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[64][ALD];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, hf = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z, d = H * 64;
   const size_t ld = (size_t)3 * d;
@@ -91,12 +100,17 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict_
   int q_hi = blockIdx.x * 128 + 127;
   if (q_hi > S - 1) q_hi = S - 1;
   const int n_tiles = causal ? q_hi / 64 + 1 : (S + 63) / 64;
+  TileRegs kr = load_tile(base + d + h * 64, ld, 0, S), vr = load_tile(base + 2 * d + h * 64, ld, 0, S);
   for (int jt = 0; jt < n_tiles; ++jt) {
     const int k0 = jt * 64;
     __syncthreads();
-    stage_tile(base + d + h * 64, ld, k0, S, Ks, nullptr);
-    stage_tile(base + 2 * d + h * 64, ld, k0, S, nullptr, Vt);
+    store_tile(kr, Ks);
+    store_tile(vr, Vs);
     __syncthreads();
+    if (jt + 1 < n_tiles) {      // the next key tile's loads fly during this tile's MFMAs
+      kr = load_tile(base + d + h * 64, ld, k0 + 64, S);
+      vr = load_tile(base + 2 * d + h * 64, ld, k0 + 64, S);
+    }
     const bool active = q0 < S && (!causal || k0 <= q0 + 31);
     if (!active) continue;
     f32x16 st[2];
@@ -145,7 +159,7 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict_
       for (int kk = 0; kk < 2; ++kk) {
         bf16x8 pf = pack8(st[i], kk);
 #pragma unroll
-        for (int dh = 0; dh < 2; ++dh) oacc[dh] = MFMA32(frag_t(Vt, 32 * dh + n, 32 * i + 16 * kk, hf), pf, oacc[dh]);
+        for (int dh = 0; dh < 2; ++dh) oacc[dh] = MFMA32(frag_tr(Vs, 32 * i + 16 * kk, 32 * dh, lane), pf, oacc[dh]);
       }
   }
   float lt = l + __shfl_xor(l, 32, 64);
@@ -172,7 +186,6 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq_mfma(const bf16_t* __restri
                                                           float* __restrict__ delta, int S, int H, int causal) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[64][ALD];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[64][ALD];
-  __shared__ __attribute__((aligned(16))) bf16_t Kt[64][ALD];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, hf = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z, d = H * 64;
   const size_t ld = (size_t)3 * d;
@@ -205,12 +218,17 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq_mfma(const bf16_t* __restri
   int q_hi = blockIdx.x * 128 + 127;
   if (q_hi > S - 1) q_hi = S - 1;
   const int n_tiles = causal ? q_hi / 64 + 1 : (S + 63) / 64;
+  TileRegs kr = load_tile(base + d + h * 64, ld, 0, S), vr = load_tile(base + 2 * d + h * 64, ld, 0, S);
   for (int jt = 0; jt < n_tiles; ++jt) {
     const int k0 = jt * 64;
     __syncthreads();
-    stage_tile(base + d + h * 64, ld, k0, S, Ks, Kt);
-    stage_tile(base + 2 * d + h * 64, ld, k0, S, Vs, nullptr);
+    store_tile(kr, Ks);
+    store_tile(vr, Vs);
     __syncthreads();
+    if (jt + 1 < n_tiles) {
+      kr = load_tile(base + d + h * 64, ld, k0 + 64, S);
+      vr = load_tile(base + 2 * d + h * 64, ld, k0 + 64, S);
+    }
     const bool active = q0 < S && (!causal || k0 <= q0 + 31);
     if (!active) continue;
     f32x16 st[2], dp[2];
@@ -240,7 +258,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq_mfma(const bf16_t* __restri
       for (int kk = 0; kk < 2; ++kk) {
         bf16x8 dsf = pack8(st[i], kk);
 #pragma unroll
-        for (int dh = 0; dh < 2; ++dh) dqa[dh] = MFMA32(frag_t(Kt, 32 * dh + n, 32 * i + 16 * kk, hf), dsf, dqa[dh]);
+        for (int dh = 0; dh < 2; ++dh) dqa[dh] = MFMA32(frag_tr(Ks, 32 * i + 16 * kk, 32 * dh, lane), dsf, dqa[dh]);
       }
   }
   if (qi < S) {
@@ -265,8 +283,6 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dkv_mfma(const bf16_t* __restr
                                                            bf16_t* __restrict__ dqkv, int S, int H, int causal) {
   __shared__ __attribute__((aligned(16))) bf16_t Qs[64][ALD];
   __shared__ __attribute__((aligned(16))) bf16_t dOs[64][ALD];
-  __shared__ __attribute__((aligned(16))) bf16_t Qt[64][ALD];
-  __shared__ __attribute__((aligned(16))) bf16_t dOt[64][ALD];
   __shared__ __attribute__((aligned(16))) float lse2s[64];
   __shared__ __attribute__((aligned(16))) float deltas[64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, hf = lane >> 5;
@@ -291,11 +307,16 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dkv_mfma(const bf16_t* __restr
   const float scale = 0.125f, c = 0.125f * kLog2e;
   const int t_begin = causal ? (blockIdx.x * 128) / 64 : 0;
   const int t_end = (S + 63) / 64;
+  TileRegs qr = load_tile(base + h * 64, ld, t_begin * 64, S), dor = load_tile(dob + h * 64, (size_t)d, t_begin * 64, S);
   for (int it = t_begin; it < t_end; ++it) {
     const int q0 = it * 64;
     __syncthreads();
-    stage_tile(base + h * 64, ld, q0, S, Qs, Qt);
-    stage_tile(dob + h * 64, (size_t)d, q0, S, dOs, dOt);
+    store_tile(qr, Qs);
+    store_tile(dor, dOs);
+    if (it + 1 < t_end) {
+      qr = load_tile(base + h * 64, ld, q0 + 64, S);
+      dor = load_tile(dob + h * 64, (size_t)d, q0 + 64, S);
+    }
     if (threadIdx.x < 64) {
       int q = q0 + threadIdx.x;
       size_t si = ((size_t)b * H + h) * S + q;
@@ -336,8 +357,8 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dkv_mfma(const bf16_t* __restr
         bf16x8 pf = pack8(s, kk), dsf = pack8(dp, kk);
 #pragma unroll
         for (int dh = 0; dh < 2; ++dh) {
-          dva[dh] = MFMA32(frag_t(dOt, 32 * dh + n, 32 * i + 16 * kk, hf), pf, dva[dh]);
-          dka[dh] = MFMA32(frag_t(Qt, 32 * dh + n, 32 * i + 16 * kk, hf), dsf, dka[dh]);
+          dva[dh] = MFMA32(frag_tr(dOs, 32 * i + 16 * kk, 32 * dh, lane), pf, dva[dh]);
+          dka[dh] = MFMA32(frag_tr(Qs, 32 * i + 16 * kk, 32 * dh, lane), dsf, dka[dh]);
         }
       }
     }
