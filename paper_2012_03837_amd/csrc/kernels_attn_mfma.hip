@@ -143,7 +143,7 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict_
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        float p = exp2f(st[i][v] - mref);
+        float p = __builtin_amdgcn_exp2f(st[i][v] - mref);
         st[i][v] = p;
         rs += p;
       }
@@ -249,7 +249,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq_mfma(const bf16_t* __restri
       for (int v = 0; v < 16; ++v) {
         int kj = k0 + 32 * i + 8 * (v / 4) + 4 * hf + (v % 4);
         bool masked = kj >= S || qi >= S || (causal && kj > qi);
-        float p = exp2f(st[i][v] * c - lse2);
+        float p = __builtin_amdgcn_exp2f(st[i][v] * c - lse2);
         st[i][v] = masked ? 0.f : p * (dp[i][v] - D) * scale;
       }
 #pragma unroll
@@ -276,7 +276,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq_mfma(const bf16_t* __restri
 }
 
 // ================================================================================= backward: dK, dV
-__global__ void __launch_bounds__(256) k_attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv,
+__global__ void __launch_bounds__(256, 2) k_attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv,
                                                            const float* __restrict__ lse,
                                                            const float* __restrict__ delta,
                                                            const bf16_t* __restrict__ dout,
@@ -346,7 +346,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dkv_mfma(const bf16_t* __restr
           int v = 4 * g + j;
           int qrow = q0 + 32 * i + 8 * g + 4 * hf + j;
           bool masked = qrow >= S || kj >= S || (causal && kj > qrow);
-          float p = exp2f(s[v] * c - l4[j]);
+          float p = __builtin_amdgcn_exp2f(s[v] * c - l4[j]);
           p = masked ? 0.f : p;
           s[v] = p;
           dp[v] = p * (dp[v] - d4[j]) * scale;
