@@ -124,16 +124,29 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict_
       }
     }
     float mt = -INFINITY;
+    // only tiles that touch the diagonal or the end of the sequence need the mask (wave-uniform test)
+    const bool need_mask = k0 + 63 >= S || (causal && k0 + 63 > q0);
+    if (need_mask) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        int kj = k0 + 32 * i + 8 * (v / 4) + 4 * hf + (v % 4);
-        float s = st[i][v] * c;
-        if (kj >= S || (causal && kj > qi)) s = -INFINITY;
-        st[i][v] = s;
-        mt = fmaxf(mt, s);
-      }
+        for (int v = 0; v < 16; ++v) {
+          int kj = k0 + 32 * i + 8 * (v / 4) + 4 * hf + (v % 4);
+          float s = st[i][v] * c;
+          if (kj >= S || (causal && kj > qi)) s = -INFINITY;
+          st[i][v] = s;
+          mt = fmaxf(mt, s);
+        }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float s = st[i][v] * c;
+          st[i][v] = s;
+          mt = fmaxf(mt, s);
+        }
+    }
     mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
     float mn = fmaxf(m, mt);
     float mref = mn == -INFINITY ? 0.f : mn;
@@ -243,15 +256,26 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq_mfma(const bf16_t* __restri
         dp[i] = MFMA32(vf, dof[kk], dp[i]);
       }
     }
+    const bool need_mask = k0 + 63 >= S || q0 + 31 >= S || (causal && k0 + 63 > q0);   // wave-uniform
+    if (need_mask) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        int kj = k0 + 32 * i + 8 * (v / 4) + 4 * hf + (v % 4);
-        bool masked = kj >= S || qi >= S || (causal && kj > qi);
-        float p = __builtin_amdgcn_exp2f(st[i][v] * c - lse2);
-        st[i][v] = masked ? 0.f : p * (dp[i][v] - D) * scale;
-      }
+        for (int v = 0; v < 16; ++v) {
+          int kj = k0 + 32 * i + 8 * (v / 4) + 4 * hf + (v % 4);
+          bool masked = kj >= S || qi >= S || (causal && kj > qi);
+          float p = __builtin_amdgcn_exp2f(st[i][v] * c - lse2);
+          st[i][v] = masked ? 0.f : p * (dp[i][v] - D) * scale;
+        }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float p = __builtin_amdgcn_exp2f(st[i][v] * c - lse2);
+          st[i][v] = p * (dp[i][v] - D) * scale;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -326,6 +350,8 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dkv_mfma(const bf16_t* __re
     __syncthreads();
     const bool active = k0w < S && (!causal || q0 + 63 >= k0w);
     if (!active) continue;
+    // the mask matters only where this wave's keys reach the tile's queries or either runs off the end
+    const bool need_mask = q0 + 63 >= S || k0w + 31 >= S || (causal && k0w + 31 > q0);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       f32x16 s, dp;
@@ -344,10 +370,12 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dkv_mfma(const bf16_t* __re
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           int v = 4 * g + j;
-          int qrow = q0 + 32 * i + 8 * g + 4 * hf + j;
-          bool masked = qrow >= S || kj >= S || (causal && kj > qrow);
           float p = __builtin_amdgcn_exp2f(s[v] * c - l4[j]);
-          p = masked ? 0.f : p;
+          if (need_mask) {
+            int qrow = q0 + 32 * i + 8 * g + 4 * hf + j;
+            bool masked = qrow >= S || kj >= S || (causal && kj > qrow);
+            p = masked ? 0.f : p;
+          }
           s[v] = p;
           dp[v] = p * (dp[v] - d4[j]) * scale;
         }
