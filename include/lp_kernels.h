@@ -24,8 +24,10 @@ extern "C" {
  * variant: 0 lets the library choose the kernel; 1 forces the FMA kernel; for bf16, 2 forces the
  * register-staged MFMA kernel, 3 / 4 the direct-to-LDS kernel with 256 x 128 tiles and the last partial wave
  * of tiles computed whole / cut along k, 5 / 6 the same with 256 x 256 tiles and 8 wavefronts, 7 / 8 with
- * 256 x 256 tiles and 4 wavefronts (an error if the shape does not qualify: K % 32 != 0, or no workspace
- * for a cut).  splitk_ws_dev (may be NULL) is fp32 workspace of
+ * 256 x 256 tiles and 4 wavefronts; 9 / 10 / 11 those three tile shapes in panel mode (outputs 2..8 tiles
+ * wide: the tile columns of one tile row walk the same cut of the reduction together, so that the other
+ * operand is fetched once per row); an error if the shape does not qualify (K % 32 != 0, no workspace for
+ * a cut, an output too narrow or too wide or a reduction too short for panel mode).  splitk_ws_dev (may be NULL) is fp32 workspace of
  * splitk_ws_elems floats: with it, reductions over few output tiles are split along k and the partial sums
  * added in a fixed order (at most max(8 * M * N, 2^25) floats are used). */
 int lpk_gemm(int dtype, const void* A, int64_t lda, int a_kc, const void* B, int64_t ldb, int b_kc, void* C,

@@ -51,6 +51,7 @@ struct DmaGemmPlan {
   int kind = 1;                      // 0: 256 x 128 tiles; 1: 256 x 256, 8 waves; 2: 256 x 256, 4 waves
   int tiles_m = 0, tiles_n = 0, kt = 0;
   int full = 0, tail_tiles = 0, upb = 0, G = 0;
+  int sib = 0;                       // panel mode: tile columns that walk one panel's reduction together
   double partial_bytes = 0;          // fp32 partial sums written (and read again by the fix-up kernel)
   long steps = 0;                    // k-steps on the longest block
   int items = 0;                     // tiles or tile pieces on the longest block

@@ -172,9 +172,18 @@ __device__ __forceinline__ bf16x8 frag_t(const char* sm, int rowbase, int k) {
 //    piece starts inside the tile, 2v+1 when it starts at the tile's first k-step), and k_sk_fixup adds
 //    the slabs of each tile in block order and applies the epilogue.  upb == kt degenerates to one whole
 //    tile per block and no partial sums.  No block ever waits for another.
+//  - Panel mode (sib = tiles_n > 1, full = 0; for outputs only a few tiles wide over a long reduction: the
+//    input gradient and the weight gradient of a vocabulary head): the unit of the cut is a panel, the
+//    tiles_n tiles of one tile row.  The reduction of all panels, tiles_m*kt k-steps in panel-major order,
+//    is cut into equal ranges; a range goes to a group of tiles_n neighbouring blocks of one XCD, block s
+//    of the group computing tile column s.  The blocks of a group walk the same k-steps of the same
+//    A rows in lockstep, so the big operand is fetched into that XCD's L2 once instead of tiles_n times.
+//    Slab numbering and the fix-up are as above with v = group*tiles_n + s; tiles are numbered
+//    tile-column-fastest in this mode.
 struct SkPlan {
   int tiles_m, tiles_n, kt;
   int full, tail_tiles, upb, G;
+  int sib;      // 0: ordinary; otherwise tiles_n (panel mode)
 };
 
 __device__ __forceinline__ void tile_coords(int q, int tiles_m, int tiles_n, int& tm, int& tn) {
@@ -183,6 +192,11 @@ __device__ __forceinline__ void tile_coords(int q, int tiles_m, int tiles_n, int
   int first = gid * GROUP, gs = tiles_m - first < GROUP ? tiles_m - first : GROUP;
   tm = first + (q % width) % gs;
   tn = (q % width) / gs;
+}
+
+__device__ __forceinline__ void plan_tile_coords(const SkPlan& p, int q, int& tm, int& tn) {
+  if (p.sib) { tm = q / p.tiles_n; tn = q - tm * p.tiles_n; }
+  else tile_coords(q, p.tiles_m, p.tiles_n, tm, tn);
 }
 
 // Epilogue of one wave's 128 x 64 sub-tile: lane (li, hf) holds, for row m = ..+li of m-tile j, the
@@ -252,20 +266,32 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
 
   // this block's work: `full` whole tiles, then k-steps [u, ue) of the tail
   const int Gx = p.G >> 3, xcd = blockIdx.x & 7, slot_in_xcd = blockIdx.x >> 3;
-  const int v = xcd * Gx + slot_in_xcd;
-  const long tail_steps = (long)p.tail_tiles * p.kt;
-  long u = (long)v * p.upb, ue = u + p.upb;
+  int v = xcd * Gx + slot_in_xcd;     // index of this block's range of the cut reduction (and of its slabs)
+  long tail_steps = (long)p.tail_tiles * p.kt;
+  long u, ue;
+  int sibling = 0;
+  if (p.sib) {                        // panel mode: groups of p.sib neighbouring blocks of this XCD
+    const int per_xcd = Gx / p.sib, grp = slot_in_xcd / p.sib;
+    sibling = slot_in_xcd - grp * p.sib;
+    const int vg = xcd * per_xcd + grp;
+    tail_steps = (long)p.tiles_m * p.kt;
+    u = grp < per_xcd ? (long)vg * p.upb : tail_steps;       // blocks left over in an XCD have no work
+    v = vg * p.sib + sibling;
+  } else {
+    u = (long)v * p.upb;
+  }
+  ue = u + p.upb;
   if (ue > tail_steps) ue = tail_steps;
   int w = 0;
   int q = 0, ks = 0, ke = 0;          // current item: tile q, k-steps [ks, ke)
   auto next_item = [&]() -> bool {
     if (w < p.full) { q = (xcd * p.full + w) * Gx + slot_in_xcd; ks = 0; ke = p.kt; ++w; return true; }
     if (u < ue) {
-      const int tr = (int)(u / p.kt);
+      const int tr = (int)(u / p.kt);                          // tail tile, or panel
       ks = (int)(u - (long)tr * p.kt);
       const long len = (p.kt - ks) < (ue - u) ? (p.kt - ks) : (ue - u);
       ke = ks + (int)len;
-      q = p.full * p.G + tr;
+      q = p.sib ? tr * p.tiles_n + sibling : p.full * p.G + tr;
       u += len;
       return true;
     }
@@ -277,7 +303,7 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
   int m0 = 0, n0 = 0, nt = 0;
   auto start_item = [&]() {          // addresses of the item's operands and the first NSTAGE-1 k-tiles' loads
     int tm, tn;
-    tile_coords(q, p.tiles_m, p.tiles_n, tm, tn);
+    plan_tile_coords(p, q, tm, tn);
     m0 = tm * BM; n0 = tn * BN; nt = ke - ks;
     pa.init(A, m0, wave, lane, ks * BK);
     pb.init(B, n0, wave, lane, ks * BK);
@@ -449,23 +475,26 @@ __global__ void __launch_bounds__(256) k_sk_fixup(const float* __restrict__ ws, 
   const int unit = (blockIdx.x % BLOCKS_PER_TILE) * 4 + (threadIdx.x >> 6);      // (wave, ij, q)
   const int lane = threadIdx.x & 63;
   const int wave = unit / UNITS_PER_WAVE, ij = (unit % UNITS_PER_WAVE) >> 1, q = unit & 1;
-  const long u0 = (long)tr * p.kt, u1 = u0 + p.kt;
+  int tm, tn;
+  plan_tile_coords(p, p.sib ? tr : p.full * p.G + tr, tm, tn);
+  const int i = ij >> 2, j = ij & 3, li = lane & 31, hf = lane >> 5;
+  const int m = tm * BM + (wave / WNW) * 128 + 32 * j + li;
+  const int n = tn * BN + (wave % WNW) * (32 * TN) + 32 * i + 16 * q + 8 * hf;
+  // the ranges that cut this tile's reduction: of tail tile tr, or in panel mode of the panel of tile tr
+  const int cut_unit = p.sib ? tr / p.tiles_n : tr, sibling = p.sib ? tr - cut_unit * p.tiles_n : 0;
+  const long u0 = (long)cut_unit * p.kt, u1 = u0 + p.kt;
   const int v_lo = (int)(u0 / p.upb), v_hi = (int)((u1 - 1) / p.upb);
   if (v_lo == v_hi) return;            // computed whole by one block
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int v = v_lo; v <= v_hi; ++v) {
-    const int slab = 2 * v + ((long)v * p.upb <= u0 ? 1 : 0);
+  for (int vr = v_lo; vr <= v_hi; ++vr) {
+    const int v = p.sib ? vr * p.sib + sibling : vr;
+    const int slab = 2 * v + ((long)vr * p.upb <= u0 ? 1 : 0);
     const float* sp = ws + (size_t)slab * (BM * BN);
     f32x4 a = *reinterpret_cast<const f32x4*>(sp + slab_index<TN>(wave, ij, 2 * q, lane));
     f32x4 b = *reinterpret_cast<const f32x4*>(sp + slab_index<TN>(wave, ij, 2 * q + 1, lane));
 #pragma unroll
     for (int x = 0; x < 4; ++x) { acc[x] += a[x]; acc[4 + x] += b[x]; }
   }
-  int tm, tn;
-  tile_coords(p.full * p.G + tr, p.tiles_m, p.tiles_n, tm, tn);
-  const int i = ij >> 2, j = ij & 3, li = lane & 31, hf = lane >> 5;
-  const int m = tm * BM + (wave / WNW) * 128 + 32 * j + li;
-  const int n = tn * BN + (wave % WNW) * (32 * TN) + 32 * i + 16 * q + 8 * hf;
   if (m < M && n < N) epilogue8(e, m, n, acc);
 }
 
@@ -496,7 +525,7 @@ hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool parti
   kern<<<dim3(p.G), 128 * WNW, smem, c.stream>>>(A, B, e, g.M, g.N, p, c.splitk_ws);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || !partials) return err;
-  k_sk_fixup<WNW, TN><<<dim3(p.tail_tiles * (2 * WNW * 8 * TN / 4)), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, p);
+  k_sk_fixup<WNW, TN><<<dim3((p.sib ? p.tiles_m * p.tiles_n : p.tail_tiles) * (2 * WNW * 8 * TN / 4)), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, p);
   return hipGetLastError();
 }
 
@@ -508,56 +537,75 @@ bool gemm_dma_ok(const GemmArgs& g) { return g.K % 32 == 0 && g.K >= 32 && g.M >
 
 // Distribution of an M x N x K problem over the persistent grid of one tile shape
 // (kind 0: 256 x 128, two blocks per CU; 1: 256 x 256 with 8 waves; 2: 256 x 256 with 4 waves).
-// cut_tail: cut the last, partial wave of tiles along k (needs workspace); otherwise one tile per block.
-// Returns false if the workspace cannot hold the partial sums.  *partial_bytes = bytes of partial sums
-// written (and read again), *steps = k-steps on the longest block.
-bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int kind, bool cut_tail, DmaGemmPlan* out) {
+// mode 0: every tile whole, one per block per wave; 1: the last, partial wave of tiles cut along k;
+// 2: panel mode (see SkPlan).  Modes 1 and 2 need workspace.  Returns false if the mode does not apply.
+bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int kind, int mode, DmaGemmPlan* out) {
   const int bn = kind == 0 ? 128 : 256, per_cu = kind == 0 ? 2 : 1;
   SkPlan p;
   p.G = (device_cus() * per_cu) & ~7;
   p.tiles_m = (g.M + BM - 1) / BM;
   p.tiles_n = (g.N + bn - 1) / bn;
   p.kt = g.K / BK;
+  p.sib = 0;
   const long T = (long)p.tiles_m * p.tiles_n;
-  p.full = (int)(T / p.G);
-  p.tail_tiles = (int)(T - (long)p.full * p.G);
-  p.upb = p.kt;
-  long partial_slabs = 0;
-  if (cut_tail && p.tail_tiles > 0) {
-    const long U = (long)p.tail_tiles * p.kt;
-    long upb = (U + p.G - 1) / p.G;
-    const long min_len = 4, max_cut = 16;                 // shortest piece; most pieces per tile
+  const long min_len = 4, max_cut = 16;                 // shortest piece; most pieces per tile
+  auto clamp_upb = [&](long upb, bool within_tile) {
     if (upb < min_len) upb = min_len;
     if (upb * max_cut < p.kt) upb = (p.kt + max_cut - 1) / max_cut;
-    if (upb > p.kt) upb = p.kt;
-    p.upb = (int)upb;
-    if (p.upb < p.kt) {
-      // count the pieces that are not whole tiles
-      const long blocks = (U + upb - 1) / upb;
-      for (long v = 0; v < blocks; ++v) {
-        long u = v * upb, ue = u + upb < U ? u + upb : U;
-        while (u < ue) {
-          long tr = u / p.kt, ks = u - tr * p.kt, len = (p.kt - ks) < (ue - u) ? (p.kt - ks) : (ue - u);
-          if (!(ks == 0 && len == p.kt)) ++partial_slabs;
-          u += len;
-        }
+    if (within_tile && upb > p.kt) upb = p.kt;
+    return upb;
+  };
+  // number of pieces that are not whole tiles when `units` k-steps (tile-major, kt per tile) are cut every upb
+  auto count_partial = [&](long units, long upb) {
+    long n = 0;
+    for (long u0 = 0; u0 < units; u0 += upb) {
+      long u = u0, ue = u0 + upb < units ? u0 + upb : units;
+      while (u < ue) {
+        long tr = u / p.kt, ks = u - tr * p.kt, len = (p.kt - ks) < (ue - u) ? (p.kt - ks) : (ue - u);
+        if (!(ks == 0 && len == p.kt)) ++n;
+        u += len;
       }
-      if (!c.splitk_ws || (size_t)2 * p.G * BM * bn > c.splitk_elems) return false;
+    }
+    return n;
+  };
+  long partial_slabs = 0;
+  if (mode == 2) {
+    const int Gx = p.G >> 3;
+    if (p.tiles_n < 2 || p.tiles_n > 8 || p.tiles_n > Gx) return false;
+    const long groups = 8L * (Gx / p.tiles_n), units = (long)p.tiles_m * p.kt;
+    const long upb = clamp_upb((units + groups - 1) / groups, false);
+    // ranges longer than a panel (more panels than groups) work but measured slower than cutting the last
+    // wave of tiles; ranges of whole panels would cut nothing
+    if (upb >= p.kt) return false;
+    p.sib = p.tiles_n; p.full = 0; p.tail_tiles = (int)T; p.upb = (int)upb;
+    partial_slabs = count_partial(units, upb) * p.tiles_n;
+    if (!c.splitk_ws || (size_t)2 * p.G * BM * bn > c.splitk_elems) return false;
+  } else {
+    p.full = (int)(T / p.G);
+    p.tail_tiles = (int)(T - (long)p.full * p.G);
+    p.upb = p.kt;
+    if (mode == 1 && p.tail_tiles > 0) {
+      const long U = (long)p.tail_tiles * p.kt;
+      p.upb = (int)clamp_upb((U + p.G - 1) / p.G, true);
+      if (p.upb < p.kt) {
+        partial_slabs = count_partial(U, p.upb);
+        if (!c.splitk_ws || (size_t)2 * p.G * BM * bn > c.splitk_elems) return false;
+      }
     }
   }
   out->kind = kind;
   out->full = p.full; out->tail_tiles = p.tail_tiles; out->upb = p.upb; out->G = p.G; out->kt = p.kt;
-  out->tiles_m = p.tiles_m; out->tiles_n = p.tiles_n;
+  out->tiles_m = p.tiles_m; out->tiles_n = p.tiles_n; out->sib = p.sib;
   out->partial_bytes = (double)partial_slabs * BM * bn * 4.0;
   out->steps = (long)p.full * p.kt + (p.tail_tiles > 0 ? p.upb : 0);
-  out->items = p.full + (p.tail_tiles > 0 ? (p.upb < p.kt ? 2 : 1) : 0);
+  out->items = p.full + (p.tail_tiles > 0 ? (p.sib ? p.upb / p.kt + 2 : (p.upb < p.kt ? 2 : 1)) : 0);
   return true;
 }
 
 hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d) {
   SkPlan p;
   p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.kt = d.kt; p.full = d.full; p.tail_tiles = d.tail_tiles;
-  p.upb = d.upb; p.G = d.G;
+  p.upb = d.upb; p.G = d.G; p.sib = d.sib;
   const bool partials = d.partial_bytes > 0;
 #define LP_DMA(AK, BK_)                                                    \
   (d.kind == 1 ? launch<AK, BK_, 4, 2, 4, true>(c, g, p, partials)                \

@@ -22,7 +22,7 @@ namespace lp {
 
 hipError_t gemm_plain(const OpCtx& c, const GemmArgs& g);
 bool gemm_dma_ok(const GemmArgs& g);
-bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int kind, bool cut_tail, DmaGemmPlan* out);
+bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int kind, int mode, DmaGemmPlan* out);
 hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d);
 
 namespace {
@@ -64,8 +64,8 @@ bool fast_ok(const GemmArgs& g) {
 
 // Forced kernel: 0 none; 2 register-staged; 3 + 2*kind + cut for the direct-to-LDS kernel of tile shape
 // `kind` (0: 256 x 128; 1: 256 x 256 with 8 waves; 2: 256 x 256 with 4 waves) with the tail whole (cut 0)
-// or cut along k (cut 1); 13 + 2*kind for that shape with either tail.
-// LP_GEMM_KERNEL = v2 | dma2 | dma4 | dmaw, optionally followed by w or c (dma4c, ...), forces one for a
+// or cut along k (cut 1); 9 + kind for that shape in panel mode; 13 + 2*kind for that shape with any of them.
+// LP_GEMM_KERNEL = v2 | dma2 | dma4 | dmaw, optionally followed by w, c or p (dma4c, ...), forces one for a
 // whole process (for measurements); a shape the forced kernel does not take falls back to the others.
 static int env_choice() {
   static int v = -1;
@@ -75,7 +75,7 @@ static int env_choice() {
     if (s && s[0] == 'v') v = 2;
     else if (s && s[0] == 'd' && s[1] == 'm' && s[2] == 'a') {
       const int kind = s[3] == '2' ? 0 : (s[3] == '4' ? 1 : (s[3] == 'w' ? 2 : -1));
-      if (kind >= 0) v = s[4] == 'w' ? 3 + 2 * kind : (s[4] == 'c' ? 4 + 2 * kind : 13 + 2 * kind);
+      if (kind >= 0) v = s[4] == 'w' ? 3 + 2 * kind : (s[4] == 'c' ? 4 + 2 * kind : (s[4] == 'p' ? 9 + kind : 13 + 2 * kind));
     }
   }
   return v;
@@ -91,6 +91,16 @@ static const TileVariant kRegStaged[2] = {
     {128, 2, 2097.0, 5000.0},     // 128 x 128, two blocks per CU share the CU: cycles per step per block
     {256, 2, 3226.0, 6000.0},     // 256 x 128
 };
+static bool panel_ok() {     // LP_GEMM_PANEL=0 switches panel mode off (for measurements)
+  static int v = -1;
+  if (v < 0) { const char* s = getenv("LP_GEMM_PANEL"); v = (s && s[0] == '0') ? 0 : 1; }
+  return v != 0;
+}
+static bool trace_on() {     // LP_GEMM_TRACE=1 prints the chosen kernel and plan of every GEMM (for measurements)
+  static int v = -1;
+  if (v < 0) { const char* s = getenv("LP_GEMM_TRACE"); v = (s && s[0] == '1') ? 1 : 0; }
+  return v != 0;
+}
 static double dma_bias() {   // LP_GEMM_DMA_BIAS scales the direct-to-LDS kernel's estimated cost (for measurements)
   static double v = -1.0;
   if (v < 0) { const char* s = getenv("LP_GEMM_DMA_BIAS"); v = s ? atof(s) : 1.0; if (!(v > 0)) v = 1.0; }
@@ -108,17 +118,21 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   bool use_dma = false;
   int force_kind = -1, force_cut = -1;
   if (choice >= 13) force_kind = (choice - 13) / 2;
+  else if (choice >= 9) { force_kind = choice - 9; force_cut = 2; }
   else if (choice >= 3) { force_kind = (choice - 3) / 2; force_cut = (choice - 3) % 2; }
   if (gemm_dma_ok(g) && choice != 2) {
     for (int kind = 0; kind < 3; ++kind) {
       if (force_kind >= 0 ? kind != force_kind : kind == 2) continue;   // the 4-wave 256 x 256 shape only when asked for
-      for (int cut = 0; cut < 2; ++cut) {
-        if (force_cut >= 0 && cut != force_cut) continue;
+      for (int cut = 0; cut < 3; ++cut) {                 // tail whole / cut along k / panel mode
+        if (force_cut >= 0 ? cut != force_cut : (cut >= 2 && !panel_ok())) continue;
         DmaGemmPlan d;
-        if (!gemm_dma_plan(c, g, kind, cut != 0, &d)) continue;
-        if (cut && d.partial_bytes == 0 && force_cut < 0) continue;      // same as the uncut plan
+        if (!gemm_dma_plan(c, g, kind, cut, &d)) continue;
+        if (cut == 1 && d.partial_bytes == 0 && force_cut < 0) continue;      // same as the uncut plan
         double cycles = d.steps * kDmaStep[kind] + d.items * kDmaFixed[kind];
         if (d.partial_bytes > 0) cycles += 2.0 * d.partial_bytes / kPartialBytesPerCycle + kSecondLaunchCycles;
+        // cut along k tile by tile, the tile columns of a row are at different k-steps and each fetches the
+        // row's operand for itself: measured ~8 % slower than panel mode on a vocabulary head's gradients
+        if (cut == 1 && d.partial_bytes > 0 && d.tiles_n >= 2 && d.tiles_n <= 8) cycles *= 1.12;
         cycles *= dma_bias();
         if (cycles < best) { best = cycles; best_dma = d; use_dma = true; }
       }
@@ -141,6 +155,11 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
       }
     }
   }
+  if (trace_on())
+    fprintf(stderr, "lp gemm %d x %d x %d (%d%d): %s kind %d full %d tail %d upb %d/%d sib %d split %d est %.0f cycles\n", g.M, g.N, g.K,
+            g.a_kc, g.b_kc, use_dma ? "direct-to-LDS" : "register-staged", use_dma ? best_dma.kind : best_v,
+            use_dma ? best_dma.full : 0, use_dma ? best_dma.tail_tiles : 0, use_dma ? best_dma.upb : 0,
+            use_dma ? best_dma.kt : 0, use_dma ? best_dma.sib : 0, use_dma ? 1 : best_s, best);
   if (use_dma) return gemm_dma(c, g, best_dma);
 
   const int splits = best_s;

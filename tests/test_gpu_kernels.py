@@ -273,6 +273,42 @@ def test_gemm_persistent_variants(K, variant, a_kc, b_kc):
         assert torch.equal(out, out2)
 
 
+# Outputs a few tiles wide over long reductions (the shapes of a vocabulary head's input and weight
+# gradients), ragged in every dimension: the panel mode of the persistent kernel.
+PANEL_SHAPES = [(8192, 768, 4096), (2056, 520, 2048), (1304, 1000, 6400), (776, 264, 16384)]
+
+
+@pytest.mark.parametrize("variant", [9, 10, 11])
+@pytest.mark.parametrize("a_kc,b_kc", [(1, 0), (0, 0), (1, 1)])
+def test_gemm_panel_mode(K, variant, a_kc, b_kc):
+    import torch
+    rng = np.random.default_rng(13)
+    ws = zeros(1 << 25)
+    for (M, N, Kd) in PANEL_SHAPES:
+        if variant == 9 and N <= 128:
+            continue
+        A = rnd(rng, (M, Kd), 1, 0.5)
+        B = rnd(rng, (N, Kd), 1, 0.5)
+        Am = A if a_kc else np.ascontiguousarray(A.T)
+        Bm = B if b_kc else np.ascontiguousarray(B.T)
+        dA, dB = dev(Am, 1), dev(Bm, 1)
+        ref = torch.from_numpy(A).cuda().double() @ torch.from_numpy(B).cuda().double().T
+        out = torch.full((M, N), 7.0, device="cuda", dtype=torch.float32)
+        K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out, N, 1, M, N, Kd, variant=variant, splitk_ws=ws)
+        err = float((out.double() - ref).norm() / ref.norm())
+        assert err <= 2e-6, (M, N, Kd, variant, err)
+        bias = rng.standard_normal(N).astype(np.float32)
+        outb = torch.zeros(M, N, device="cuda", dtype=torch.bfloat16)
+        K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, outb, N, 0, M, N, Kd, bias=dev(bias, 0), act=1,
+                   variant=variant, splitk_ws=ws)
+        refb = torch.relu(ref + torch.from_numpy(bias).cuda().double())
+        errb = float((outb.double() - refb).norm() / refb.norm())
+        assert errb <= 4e-3, (M, N, Kd, variant, errb)
+        out2 = torch.zeros_like(out)
+        K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out2, N, 1, M, N, Kd, variant=variant, splitk_ws=ws)
+        assert torch.equal(out, out2)
+
+
 def test_gemm_forced_variant_rejects_unsupported_shape(K):
     import torch
     A = torch.zeros(64, 40, device="cuda", dtype=torch.bfloat16)
