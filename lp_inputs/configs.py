@@ -32,7 +32,7 @@ class LayerCfg:
 
 @dataclass(frozen=True)
 class HeadCfg:
-    kind: str                 # "linear_ce" | "pool_linear_ce" | "ln_linear_ce"
+    kind: str                 # "linear_ce" | "pool_linear_ce" | "ln_linear_ce" | "bn_pool_linear_ce"
     after_layer: int          # e_j, 1-based
     window: int               # w_j >= 1 (clamped to e_j)
     in_dim: int
@@ -117,7 +117,7 @@ def decoder_config(name, n_layers, width, n_heads, hidden, seq_len, batch, vocab
 
 def resnet_config(name, channels=(64, 128, 256, 512), in_hw=32, in_ch=3, n_classes=10, batch=256,
                   n_basic_blocks=2, scheme="greedy", chunk=1, opt=None, combine="sum", dtype="bf16",
-                  seed=0) -> ModelCfg:
+                  seed=0, head="pool_linear_ce") -> ModelCfg:
     layers = []
     hw, cin = in_hw, in_ch
     for i, c in enumerate(channels):
@@ -127,7 +127,7 @@ def resnet_config(name, channels=(64, 128, 256, 512), in_hw=32, in_ch=3, n_class
         hw = hw // stride
         cin = c
     layers = tuple(layers)
-    heads = _scheme_heads("pool_linear_ce", len(layers), scheme, lambda e: layers[e - 1].out_ch,
+    heads = _scheme_heads(head, len(layers), scheme, lambda e: layers[e - 1].out_ch,
                           n_classes, 1, chunk)
     return ModelCfg(name, layers, heads, opt or OptCfg("sgdm", lr=0.1, momentum=0.9), combine, dtype,
                     batch, 0, seed)
@@ -251,6 +251,9 @@ def param_shapes(cfg: ModelCfg) -> Dict[str, Tuple[int, ...]]:
         if h.kind == "ln_linear_ce":
             shapes[p + "ln.g"] = (h.in_dim,)
             shapes[p + "ln.b"] = (h.in_dim,)
+        if h.kind == "bn_pool_linear_ce":
+            shapes[p + "bn.g"] = (h.in_dim,)
+            shapes[p + "bn.b"] = (h.in_dim,)
         shapes[p + "w"] = (h.n_classes, h.in_dim)
         if h.bias:
             shapes[p + "b"] = (h.n_classes,)

@@ -200,6 +200,13 @@ def head_loss(cfg, P, hi, h, y, q=ops.identity):
     if hd.kind == "pool_linear_ce":
         feat = q(h.mean(axis=(1, 2)))
         cache["hw_shape"] = h.shape
+    elif hd.kind == "bn_pool_linear_ce":
+        # appendix B.3: batch normalisation, ReLU, mean over the spatial dimensions, then the linear projection
+        a, cache["bn"] = ops.batchnorm_fwd(h, P[pre + "bn.g"], P[pre + "bn.b"])
+        a = q(ops.relu_fwd(a))
+        cache["a"] = a
+        feat = q(a.mean(axis=(1, 2)))
+        cache["hw_shape"] = h.shape
     elif hd.kind == "ln_linear_ce":
         feat, cache["ln"] = ops.layernorm_fwd(h, P[pre + "ln.g"], P[pre + "ln.b"])
         feat = q(feat)
@@ -226,6 +233,11 @@ def head_bwd(cfg, P, hi, cache):
     if hd.kind == "pool_linear_ce":
         N, Hh, Ww, C = cache["hw_shape"]
         dh = np.broadcast_to(dfeat[:, None, None, :] / (Hh * Ww), (N, Hh, Ww, C)).copy()
+    elif hd.kind == "bn_pool_linear_ce":
+        N, Hh, Ww, C = cache["hw_shape"]
+        da = np.broadcast_to(dfeat[:, None, None, :] / (Hh * Ww), (N, Hh, Ww, C))
+        da = ops.relu_bwd(cache["a"], da)            # the stored post-ReLU activation decides
+        dh, g[pre + "bn.g"], g[pre + "bn.b"] = ops.batchnorm_bwd(cache["bn"], P[pre + "bn.g"], da)
     elif hd.kind == "ln_linear_ce":
         dh, g[pre + "ln.g"], g[pre + "ln.b"] = ops.layernorm_bwd(cache["ln"], P[pre + "ln.g"], dfeat)
     else:

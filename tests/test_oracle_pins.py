@@ -261,6 +261,39 @@ def test_p12_pipelined_schedule(kind):
     assert l2[0] == pytest.approx(oracle.block_gradients(g_cfg, P1, 1, x2, y2)[0], rel=1e-14)
 
 
+def test_p13_paper_form_resnet_head():
+    """Appendix B.3's auxiliary head (batch norm, ReLU, spatial mean, linear): finite differences of the head's
+    own parameters and of the block below it; a whole network with this head against torch autograd."""
+    import torch
+    cfg = tiny("res", head="bn_pool_linear_ce")
+    P, x, y = setup(cfg)
+    assert "H1.bn.g" in P and "H1.bn.b" in P
+    losses, grads, _ = oracle.local_gradients(cfg, P, x, y)
+    for hi in (1, 3):
+        s, e = LI.head_windows(cfg)[hi - 1]
+        names = [k for k in P if k.startswith(f"H{hi}.") or k.startswith(f"L{e}.")]
+
+        def f(Pq, hi=hi):
+            return oracle.eval_loss(cfg, Pq, x, y)[hi - 1]
+        fd_check(f, P, names, grads, n_probe=4, h=1e-6, rtol=5e-6)
+    # library pin: the head alone in torch (batch_norm in training mode, relu, mean, linear, cross_entropy)
+    hs, _ = oracle.forward_all(cfg, P, x)
+    h1 = torch.tensor(hs[1], dtype=torch.float64, requires_grad=True)
+    w = torch.tensor(P["H1.w"], dtype=torch.float64, requires_grad=True)
+    b = torch.tensor(P["H1.b"], dtype=torch.float64, requires_grad=True)
+    gg = torch.tensor(P["H1.bn.g"], dtype=torch.float64, requires_grad=True)
+    bb = torch.tensor(P["H1.bn.b"], dtype=torch.float64, requires_grad=True)
+    a = torch.nn.functional.batch_norm(h1.permute(0, 3, 1, 2), None, None, gg, bb, training=True, eps=1e-5)
+    feat = torch.relu(a).mean(dim=(2, 3))
+    loss = torch.nn.functional.cross_entropy(feat @ w.T + b, torch.tensor(y, dtype=torch.long))
+    loss.backward()
+    # (torch's CPU batch_norm keeps some statistics in single precision even for double inputs)
+    assert float(loss) == pytest.approx(losses[0], rel=1e-7)
+    np.testing.assert_allclose(grads["H1.w"], w.grad.numpy(), rtol=1e-5, atol=1e-8)
+    np.testing.assert_allclose(grads["H1.bn.g"], gg.grad.numpy(), rtol=1e-5, atol=1e-8)
+    np.testing.assert_allclose(grads["H1.bn.b"], bb.grad.numpy(), rtol=1e-5, atol=1e-8)
+
+
 def test_p6_overlap_bookkeeping():
     """Overlapping scheme (appendix A.2): two backward passes for each non-terminal layer, one
     for the terminal layer: 2L-1 (head, layer) pairs; mean = sum / coverage."""
