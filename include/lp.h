@@ -58,7 +58,9 @@ typedef enum {
 typedef enum {
   LP_HEAD_LINEAR_CE = 0,      /* Linear(in_dim -> n_classes) + softmax cross-entropy              */
   LP_HEAD_POOL_LINEAR_CE = 1, /* mean over H x W, then Linear + CE                                 */
-  LP_HEAD_LN_LINEAR_CE = 2    /* LayerNorm, Linear to the vocabulary (no bias), next-token CE      */
+  LP_HEAD_LN_LINEAR_CE = 2,   /* LayerNorm, Linear to the vocabulary (no bias), next-token CE      */
+  LP_HEAD_BN_POOL_LINEAR_CE = 3 /* BatchNorm (batch statistics), ReLU, mean over H x W, Linear + CE:
+                                 the ResNet auxiliary head of appendix B.3                           */
 } lp_head_kind;
 
 typedef enum { LP_OPT_SGD = 0, LP_OPT_SGDM = 1, LP_OPT_ADAM = 2 } lp_opt_kind;

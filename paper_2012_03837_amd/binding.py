@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "liblp.so")
 LP_OK, LP_EINVAL, LP_ESHAPE, LP_EALIGN, LP_ENOMEM, LP_EDEVICE, LP_ESTATE, LP_EUNSUPPORTED, LP_ENOTFOUND = range(9)
 LP_F32, LP_BF16, LP_I32 = 0, 1, 2
 LAYER_KINDS = {"resmlp": 0, "decoder": 1, "resnet_stage": 2}
-HEAD_KINDS = {"linear_ce": 0, "pool_linear_ce": 1, "ln_linear_ce": 2}
+HEAD_KINDS = {"linear_ce": 0, "pool_linear_ce": 1, "ln_linear_ce": 2, "bn_pool_linear_ce": 3}
 OPT_KINDS = {"sgd": 0, "sgdm": 1, "adam": 2}
 COMBINE = {"sum": 0, "mean": 1}
 ACTS = {"gelu": 0, "relu": 1}

@@ -282,6 +282,16 @@ int drv_head(lp_ctx* c, int hi, int batch, const int32_t* y, float* loss_out, bo
     rows = batch;
     DO(op_avgpool_fwd(o, h, c->feat, batch, hw, in_dim));
     feat = c->feat;
+  } else if (Hd.s.kind == LP_HEAD_BN_POOL_LINEAR_CE) {
+    // appendix B.3: batch norm, ReLU, spatial mean, linear.  The normalised, rectified activation lives in the
+    // stage-backward scratch, which this chain does not touch before the head's own backward pass is done.
+    int side = L.s.in_hw / L.s.stride;
+    hw = side * side;
+    rows = batch;
+    DO(op_batchnorm_fwd(o, h, c->P32(Hd.t["bn.g"]), c->P32(Hd.t["bn.b"]), nullptr, c->sG, c->hmean, c->hrstd,
+                        batch * hw, in_dim, 1));
+    DO(op_avgpool_fwd(o, c->sG, c->feat, batch, hw, in_dim));
+    feat = c->feat;
   } else if (Hd.s.kind == LP_HEAD_LN_LINEAR_CE) {
     rows = batch * L.s.seq_len;
     DO(op_layernorm_fwd(o, h, c->P32(Hd.t["ln.g"]), c->P32(Hd.t["ln.b"]), c->feat, c->hmean, c->hrstd, rows, in_dim));
@@ -303,6 +313,10 @@ int drv_head(lp_ctx* c, int hi, int batch, const int32_t* y, float* loss_out, bo
     DO(op_gemm(o, lin_dgrad(c, c->logits, rows, Hd.t["w"], c->dfeat)));
     if (Hd.s.kind == LP_HEAD_POOL_LINEAR_CE) {
       DO(op_avgpool_bwd(o, c->dfeat, dh, batch, hw, in_dim));
+    } else if (Hd.s.kind == LP_HEAD_BN_POOL_LINEAR_CE) {
+      DO(op_avgpool_bwd(o, c->dfeat, c->sZ, batch, hw, in_dim));
+      DO(op_batchnorm_bwd(o, c->sZ, c->sG, h, c->hmean, c->hrstd, c->P32(Hd.t["bn.g"]), dh, nullptr,
+                          c->G32(Hd.t["bn.g"]), c->G32(Hd.t["bn.b"]), batch * hw, in_dim, 1, 0));
     } else {
       DO(op_layernorm_bwd(o, c->dfeat, h, c->hmean, c->hrstd, c->P32(Hd.t["ln.g"]), nullptr, dh,
                           c->G32(Hd.t["ln.g"]), c->G32(Hd.t["ln.b"]), rows, in_dim, 0));

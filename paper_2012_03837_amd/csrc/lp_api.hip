@@ -70,7 +70,9 @@ static int validate(const lp_model_spec* sp, std::string& err) {
     if (h.n_classes < 2) { err = std::string(where) + "n_classes must be >= 2"; return LP_ESHAPE; }
     const lp_layer_spec& l = sp->layers[h.after_layer - 1];
     int want_kind = kind0 == LP_LAYER_RESMLP ? LP_HEAD_LINEAR_CE : kind0 == LP_LAYER_DECODER ? LP_HEAD_LN_LINEAR_CE : LP_HEAD_POOL_LINEAR_CE;
-    if (h.kind != want_kind) { err = std::string(where) + "head kind does not fit the layer kind"; return LP_EUNSUPPORTED; }
+    if (h.kind != want_kind && !(kind0 == LP_LAYER_RESNET_STAGE && h.kind == LP_HEAD_BN_POOL_LINEAR_CE)) {
+      err = std::string(where) + "head kind does not fit the layer kind"; return LP_EUNSUPPORTED;
+    }
     int feat = kind0 == LP_LAYER_RESNET_STAGE ? l.out_ch : l.width;
     if (h.in_dim != feat) { err = std::string(where) + "in_dim != layer output width"; return LP_ESHAPE; }
     if (kind0 == LP_LAYER_DECODER && h.n_classes != sp->vocab) { err = std::string(where) + "n_classes != vocab"; return LP_ESHAPE; }
@@ -158,6 +160,10 @@ static void build_params(lp_ctx* c) {
     if (vocab_head) {
       Hd.t["ln.g"] = add_tensor(c, p + "ln.g", {Hd.s.in_dim}, owner, 1, 0.f);
       Hd.t["ln.b"] = add_tensor(c, p + "ln.b", {Hd.s.in_dim}, owner, 2, 0.f);
+    }
+    if (Hd.s.kind == LP_HEAD_BN_POOL_LINEAR_CE) {
+      Hd.t["bn.g"] = add_tensor(c, p + "bn.g", {Hd.s.in_dim}, owner, 1, 0.f);
+      Hd.t["bn.b"] = add_tensor(c, p + "bn.b", {Hd.s.in_dim}, owner, 2, 0.f);
     }
     float std = vocab_head ? 0.02f : (float)sqrt(2.0 / (double)Hd.s.in_dim);
     Hd.t["w"] = add_tensor(c, p + "w", {Hd.s.n_classes, Hd.s.in_dim}, owner, 0, std);
@@ -264,6 +270,7 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
     if (rows * Hd.s.n_classes > max_head_logits) max_head_logits = rows * Hd.s.n_classes;
     if (rows * Hd.s.in_dim > max_feat) max_feat = rows * Hd.s.in_dim;
     if (rows > max_rows) max_rows = rows;
+    if ((size_t)Hd.s.in_dim > max_rows) max_rows = Hd.s.in_dim;      // per-channel statistics of a BatchNorm head
     size_t pc = ((rows + 127) / 128) * (size_t)(Hd.s.n_classes > Hd.s.in_dim ? Hd.s.n_classes : Hd.s.in_dim);
     if (pc > partial) partial = pc;
   }

@@ -236,3 +236,14 @@ def test_pipelined_schedule_needs_tiling_windows(lpmod):
     cfg = dataclasses.replace(LI.make_config("cfg4_small"), dtype="f32")      # overlapping windows
     with pytest.raises(lpmod.LpError):
         lpmod.LocalTrainer(cfg, schedule="pipelined")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_paper_form_resnet_head(lpmod, dtype):
+    """The ResNet auxiliary head of appendix B.3 (batch norm, ReLU, spatial mean, linear) on every stage."""
+    cfg = dataclasses.replace(LI.make_config("cfg2_small", head="bn_pool_linear_ce"), dtype=dtype)
+    assert cfg.heads[0].kind == "bn_pool_linear_ce"
+    tr = lpmod.LocalTrainer(cfg, n_streams=2)
+    x, y = data_for(cfg)
+    compare_step(tr, cfg, generic_params(cfg), x, y, label="bn head " + dtype, stored=stored_for(cfg))
+    tr.close()
