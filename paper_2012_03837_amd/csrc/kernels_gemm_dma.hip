@@ -21,6 +21,7 @@
 // One barrier per k-tile: wait until this thread's loads of tile t have landed (s_waitcnt vmcnt leaves
 // the younger tiles in flight), barrier, issue the loads of tile t+NSTAGE-1 into the stage that was read
 // during tile t-1, then 16 MFMAs per wave on tile t.  Requires K % 32 == 0 (no zero fill on this path).
+#include <stdlib.h>
 #include <type_traits>
 #include "common.h"
 #include "gemm_common.h"

@@ -247,3 +247,30 @@ def test_paper_form_resnet_head(lpmod, dtype):
     x, y = data_for(cfg)
     compare_step(tr, cfg, generic_params(cfg), x, y, label="bn head " + dtype, stored=stored_for(cfg))
     tr.close()
+
+
+def test_pipelined_schedule_with_changing_batch_sizes(lpmod):
+    """Minibatches of different sizes travel down the pipeline with their own labels; a call with batch 0
+    does not advance it."""
+    cfg = dataclasses.replace(LI.make_config("cfg3_small"), dtype="f32")
+    J = len(cfg.heads)
+    tr = lpmod.LocalTrainer(cfg, schedule="pipelined", n_streams=2)
+    P0 = generic_params(cfg)
+    tr.set_params(P0)
+    P = {k: v.astype(np.float64) for k, v in P0.items()}
+    st, pipe = oracle.new_state(cfg, P), oracle.new_pipeline(cfg)
+    sizes = [cfg.batch, 1, cfg.batch - 1, 0, cfg.batch, 2, 1][: J + 4]
+    for t, b in enumerate(sizes, start=1):
+        x, y = data_for(cfg, t, batch=max(b, 1))
+        xd, yd = tr.stage(x, y)
+        got = tr.step(xd, yd, batch=b).cpu().numpy().copy()
+        if b == 0:
+            assert not np.any(got)
+            continue
+        ref, P = oracle.pipelined_step(cfg, P, st, pipe, x, y)
+        for j in range(J):
+            assert abs(got[j] - ref[j]) <= 1e-4 * max(abs(ref[j]), 1e-30), (t, j, got[j], ref[j])
+    got_params = tr.get_params()
+    for k in P0:
+        assert relerr(got_params[k], P[k]) <= 2e-4, k
+    tr.close()
