@@ -91,20 +91,10 @@ static const TileVariant kRegStaged[2] = {
     {128, 2, 2097.0, 5000.0},     // 128 x 128, two blocks per CU share the CU: cycles per step per block
     {256, 2, 3226.0, 6000.0},     // 256 x 128
 };
-static bool panel_ok() {     // LP_GEMM_PANEL=0 switches panel mode off (for measurements)
-  static int v = -1;
-  if (v < 0) { const char* s = getenv("LP_GEMM_PANEL"); v = (s && s[0] == '0') ? 0 : 1; }
-  return v != 0;
-}
 static bool trace_on() {     // LP_GEMM_TRACE=1 prints the chosen kernel and plan of every GEMM (for measurements)
   static int v = -1;
   if (v < 0) { const char* s = getenv("LP_GEMM_TRACE"); v = (s && s[0] == '1') ? 1 : 0; }
   return v != 0;
-}
-static double dma_bias() {   // LP_GEMM_DMA_BIAS scales the direct-to-LDS kernel's estimated cost (for measurements)
-  static double v = -1.0;
-  if (v < 0) { const char* s = getenv("LP_GEMM_DMA_BIAS"); v = s ? atof(s) : 1.0; if (!(v > 0)) v = 1.0; }
-  return v;
 }
 static const double kDmaStep[3] = {2796.0, 2300.0, 2300.0};      // 256 x 128 (two per CU), 256 x 256
 static const double kDmaFixed[3] = {7000.0, 9000.0, 9000.0};
@@ -124,7 +114,7 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
     for (int kind = 0; kind < 3; ++kind) {
       if (force_kind >= 0 ? kind != force_kind : kind == 2) continue;   // the 4-wave 256 x 256 shape only when asked for
       for (int cut = 0; cut < 3; ++cut) {                 // tail whole / cut along k / panel mode
-        if (force_cut >= 0 ? cut != force_cut : (cut >= 2 && !panel_ok())) continue;
+        if (force_cut >= 0 && cut != force_cut) continue;
         DmaGemmPlan d;
         if (!gemm_dma_plan(c, g, kind, cut, &d)) continue;
         if (cut == 1 && d.partial_bytes == 0 && force_cut < 0) continue;      // same as the uncut plan
@@ -133,7 +123,6 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
         // cut along k tile by tile, the tile columns of a row are at different k-steps and each fetches the
         // row's operand for itself: measured ~8 % slower than panel mode on a vocabulary head's gradients
         if (cut == 1 && d.partial_bytes > 0 && d.tiles_n >= 2 && d.tiles_n <= 8) cycles *= 1.12;
-        cycles *= dma_bias();
         if (cycles < best) { best = cycles; best_dma = d; use_dma = true; }
       }
     }
