@@ -110,7 +110,11 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   if (choice >= 13) force_kind = (choice - 13) / 2;
   else if (choice >= 9) { force_kind = choice - 9; force_cut = 2; }
   else if (choice >= 3) { force_kind = (choice - 3) / 2; force_cut = (choice - 3) % 2; }
-  if (gemm_dma_ok(g) && choice != 2) {
+  // Short reductions over at most two waves of tiles (a layer's K = 768 products): a block that owns its CU
+  // has nothing to overlap its fused epilogue with and its pipeline never reaches steady state; the
+  // register-staged kernel with two blocks per CU measured 10-30 % faster there, so it takes them.
+  const bool short_and_few = g.K <= 1024 && (long)((g.M + 255) / 256) * ((g.N + 255) / 256) <= 512;
+  if (gemm_dma_ok(g) && choice != 2 && !(choice == 0 && short_and_few)) {
     for (int kind = 0; kind < 3; ++kind) {
       if (force_kind >= 0 ? kind != force_kind : kind == 2) continue;   // the 4-wave 256 x 256 shape only when asked for
       for (int cut = 0; cut < 3; ++cut) {                 // tail whole / cut along k / panel mode
