@@ -4,10 +4,12 @@
 //
 // Block tile 256(m) x BN(n) x 32(k); 2 x WNW wavefronts, each owning 128 x 32*TN (4 x TN tiles of
 // v_mfma_f32_32x32x16_bf16).  Three shapes:
-//   256 x 256, 8 waves of 128 x 64  (WNW 4, TN 2): 4 stages (128 KB LDS), one block per CU, 2 waves per SIMD
-//   256 x 256, 4 waves of 128 x 128 (WNW 2, TN 4): 4 stages, one block per CU, 1 wave per SIMD with all 512
-//                registers; a third less LDS read traffic per flop (8 fragment reads per 16 MFMAs)
-//   256 x 128, 4 waves of 128 x 64  (WNW 2, TN 2): 3 stages (72 KB), two blocks per CU.
+//   256 x 256, 8 waves of 128 x 64  (WNW 4, TN 2): 4 stages (128 KB LDS), one block per CU, 2 waves per SIMD,
+//                hand-pipelined main loop (PIPE)
+//   256 x 256, 4 waves of 128 x 128 (WNW 2, TN 4): 5 stages (all 160 KB), one block per CU, 1 wave per SIMD
+//                with all 512 registers, hand-pipelined; a third less LDS read traffic per flop (8 fragment
+//                reads per 16 MFMAs); fastest on resident operands, slower on cold ones: taken only when forced
+//   256 x 128, 4 waves of 128 x 64  (WNW 2, TN 2): 3 stages (72 KB), two blocks per CU, plain main loop.
 //
 // A direct-to-LDS load writes lane l's 16 bytes at (wave-uniform base) + 16*l, so a wave fills 1 KB of
 // contiguous LDS; tiles are therefore unpadded and bank conflicts are avoided by an XOR swizzle that the
@@ -18,10 +20,10 @@
 // The grid is persistent (one block per resident slot): a block computes several whole tiles, starting the
 // next tile's loads before it writes the finished one, and the last partial wave of tiles is cut along k
 // so that every CU gets the same number of k-steps (see SkPlan).
-// One barrier per k-tile: wait until this thread's loads of tile t have landed (s_waitcnt vmcnt leaves
-// the younger tiles in flight), barrier, issue the loads of tile t+NSTAGE-1 into the stage that was read
-// during tile t-1, then 16 MFMAs per wave on tile t.  Requires K % 32 == 0 (no zero fill on this path).
-#include <stdlib.h>
+// Plain main loop, one barrier per k-tile: wait until this thread's loads of tile t have landed (s_waitcnt
+// vmcnt leaves the younger tiles in flight), barrier, issue the loads of tile t+NSTAGE-1 into the stage that
+// was read during tile t-1, then the MFMAs of tile t.  Hand-pipelined main loop (PIPE): see the comment in
+// the kernel.  Requires K % 32 == 0 (no zero fill on this path).
 #include <type_traits>
 #include "common.h"
 #include "gemm_common.h"
