@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(256) k_ln_fwd_v(const bf16_t* __restrict__ x, 
   if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
 }
 
-constexpr int kRowsPerBlock = 32;
+constexpr int kRowsPerBlock = 8;
 // Backward; block partials of dg and db go to partial[blk][d] and partial[nblk + blk][d].
 template <int NCH>
 __global__ void __launch_bounds__(256) k_ln_bwd_v(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,

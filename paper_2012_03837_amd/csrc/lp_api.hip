@@ -221,7 +221,7 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
       S.lse = (float*)wa.take(T * l.n_heads * 4);
       if (T > max_rows) max_rows = T;
       size_t widest = F > 3 * d ? F : 3 * d;
-      size_t pr = ((T + 31) / 32) * d * 2;
+      size_t pr = ((T + 7) / 8) * d * 2;      // LayerNorm backward: dg and db partials of every 8-row block
       size_t pc = ((T + 127) / 128) * (widest > (size_t)sp.vocab ? widest : (size_t)sp.vocab);
       if (pr > partial) partial = pr;
       if (pc > partial) partial = pc;

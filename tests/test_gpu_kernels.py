@@ -166,7 +166,7 @@ def test_layernorm(K, dtype, rows, d):
     assert relerr(host(mean), x.astype(np.float64).mean(-1)) <= 1e-5
     dx = torch.zeros(rows, d, device="cuda", dtype=tdt)
     dg = ones(d); db = ones(d)
-    scratch = zeros(2 * ((rows + 31) // 32) * d + 16)
+    scratch = zeros(2 * ((rows + 7) // 8) * d + 16)
     K.lpk_layernorm_bwd(dtype, dev(dy, dtype), dev(x, dtype), mean, rstd, dev(g, 0), dev(add, dtype), dx, dg, db, rows, d,
                         1, scratch)
     rdx, rdg, rdb = ops.layernorm_bwd(cache, g.astype(np.float64), dy.astype(np.float64))
