@@ -238,7 +238,7 @@ def test_embed_bwd_repeated_tokens(K, with_counts, accumulate):
 # Shapes for the persistent direct-to-LDS GEMM: fewer tiles than blocks, exactly one wave of tiles,
 # whole waves plus a tail, ragged edges in m and n, reductions shorter than the LDS ring.
 DMA_SHAPES = [(520, 264, 4096), (4096, 4096, 64), (4104, 4360, 96), (8192, 776, 768), (2056, 8200, 32),
-              (6000, 12000, 160), (264, 136, 16384)]
+              (6000, 12000, 160), (264, 136, 16384), (4104, 8200, 256), (8192, 8192, 768)]
 
 
 @pytest.mark.parametrize("variant", [3, 4, 5, 6, 7, 8])
