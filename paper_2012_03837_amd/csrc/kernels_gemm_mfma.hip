@@ -1,17 +1,18 @@
-// bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
+// bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation): the choice between the
+// two MFMA kernels and the launch of the register-staged one.
 //
-// Block tile 256(m) x 128(n) x 32(k), 256 threads = four 64-wide wavefronts in a 2x2 arrangement, each
-// owning 128 x 64 (4 x 2 MFMA tiles, 128 accumulator registers), two blocks per CU.  Operand tiles go
-// global -> registers -> LDS (double buffered, one barrier per k-tile).  An operand stored with the
-// reduction index contiguous ("kc": forward activations and [out,in] weights) sits in LDS as
-// [row][k] and is read with 16-byte ds_read; one stored with the reduction index as the slow
-// dimension (dgrad weights, both wgrad operands) sits as [k][row], exactly as in memory, and is read
-// with the gfx950 transposing LDS read (ds_read_b64_tr_b16), so nothing is ever transposed by the
-// vector ALU.  The MFMA takes the n-side fragment as its first operand, which leaves each lane with
-// runs of 8 consecutive n for one m: the fused epilogue (bias, activation, saved pre-activation,
-// activation derivative, residual, accumulate) reads and writes 16 bytes per lane.
-// Blocks are renumbered so that each XCD (blocks are dealt round-robin to the 8 XCDs) walks a
-// compact group of tiles and re-uses its own L2.
+// Register-staged kernel (mfma_tile.h): block tile 256 or 128 (m) x 128 (n) x 32 (k), four wavefronts, two
+// blocks per CU; operand tiles go global -> registers -> LDS (double buffered, one barrier per k-tile).  It
+// takes every 8-aligned shape (K tails are zero-filled while staging) and splits long reductions over few
+// tiles uniformly along k (fp32 partial sums, added in split order by k_splitk_reduce).
+// Direct-to-LDS kernel (kernels_gemm_dma.hip): persistent, for K % 32 == 0; see there.
+// In both, an operand stored with the reduction index contiguous ("kc": forward activations and [out,in]
+// weights) sits in LDS as [row][k] and is read with 16-byte ds_read; one stored with the reduction index as the
+// slow dimension (dgrad weights, both wgrad operands) sits as [k][row], exactly as in memory, and is read with
+// the gfx950 transposing LDS read (ds_read_b64_tr_b16), so nothing is ever transposed by the vector ALU.  The
+// MFMA takes the n-side fragment as its first operand, which leaves each lane with runs of 8 consecutive n for
+// one m: the fused epilogue (bias, activation, saved pre-activation, activation derivative, residual,
+// accumulate) reads and writes 16 bytes per lane.
 #include <stdio.h>
 #include <stdlib.h>
 #include "common.h"
@@ -103,7 +104,7 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   const int choice = c.gemm_variant ? c.gemm_variant : env_choice();
   double best = 1e300;
-  // direct-to-LDS persistent kernel: two tile widths, tail whole or cut along k
+  // direct-to-LDS persistent kernel: tile shape x (tail whole, cut along k, panel mode)
   DmaGemmPlan best_dma;
   bool use_dma = false;
   int force_kind = -1, force_cut = -1;
