@@ -160,7 +160,8 @@ int lp_set_tensor(lp_ctx* ctx, const char* name, const void* src_host, size_t by
 /* Number of parameter tensors, and the i-th name (storage order: layers, then heads). */
 int lp_num_params(lp_ctx* ctx);
 const char* lp_param_name(lp_ctx* ctx, int i);
-/* Optimizer step counter t (Adam bias correction uses t counted from 1). */
+/* Optimizer step counter t = number of lp_local_step calls so far (Adam bias correction uses t counted from 1;
+ * with the pipelined schedule block j's own count is max(0, t - j + 1), which lp_set_step restores). */
 int lp_get_step(lp_ctx* ctx);
 int lp_set_step(lp_ctx* ctx, int t);
 

@@ -777,5 +777,7 @@ extern "C" int lp_set_step(lp_ctx* c, int t) {
   if (!c) return LP_EINVAL;
   if (t < 0) return fail(c, LP_EINVAL, "step must be >= 0");
   c->step_t = t;
+  // pipelined schedule: block j has taken part in every call from the j-th on
+  for (size_t j = 1; j < c->blk_updates.size(); ++j) c->blk_updates[j] = t - (int)(j - 1) > 0 ? t - (int)(j - 1) : 0;
   return LP_OK;
 }
