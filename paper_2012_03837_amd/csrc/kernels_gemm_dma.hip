@@ -17,13 +17,15 @@
 //   kc tile   [row][4 chunks of 8 k]   : chunk c of row r sits in slot c ^ ((r>>2)&3)
 //   k-major   [k][32.. chunks of 8 rows]: chunk j of k-row k sits in slot j ^ ((k&3)<<2)   (read with
 //                                         ds_read_b64_tr_b16, as in the register-staged kernel)
-// The grid is persistent (one block per resident slot): a block computes several whole tiles, starting the
-// next tile's loads before it writes the finished one, and the last partial wave of tiles is cut along k
-// so that every CU gets the same number of k-steps (see SkPlan).
+// The grid is persistent (one block per resident slot): a block computes several whole tiles, and the last
+// partial wave of tiles is cut along k so that every CU gets the same number of k-steps (see SkPlan).
 // Plain main loop, one barrier per k-tile: wait until this thread's loads of tile t have landed (s_waitcnt
 // vmcnt leaves the younger tiles in flight), barrier, issue the loads of tile t+NSTAGE-1 into the stage that
-// was read during tile t-1, then the MFMAs of tile t.  Hand-pipelined main loop (PIPE): see the comment in
-// the kernel.  Requires K % 32 == 0 (no zero fill on this path).
+// was read during tile t-1, then the MFMAs of tile t; the next item's first loads are issued before the
+// finished item is written.  Hand-pipelined main loop (PIPE): the k-tiles of all of a block's items form
+// one stream through the ring of stages, so the loader stays NSTAGE-1 k-tiles ahead across item boundaries
+// and a finished item's stores drain behind the next item's first k-steps; see the comment in the kernel.
+// Requires K % 32 == 0 (no zero fill on this path).
 #include <type_traits>
 #include "common.h"
 #include "gemm_common.h"
@@ -207,6 +209,44 @@ __device__ __forceinline__ void plan_tile_coords(const SkPlan& p, int q, int& tm
 template <int TN>
 __device__ __forceinline__ void store_subtile(const Epilogue& e, const f32x16 (&acc)[TN][4], int m_base, int n_base,
                                               int li, int hf, int M, int N) {
+  // Nothing fused and the sub-tile inside the matrix (both wave-uniform): four row pointers, then
+  // convert-and-store with immediate offsets.  The general path below costs several microseconds of
+  // branches and address arithmetic per tile, during which the block's MFMA pipes idle.
+  const bool plain = !e.bias && !e.pre && e.act == ACT_NONE && e.dact == ACT_NONE && !e.res && !e.accumulate;
+  if (plain && m_base + 128 <= M && n_base + 32 * TN <= N) {
+    if (e.c_f32) {
+      float* base = reinterpret_cast<float*>(e.C) + (size_t)(m_base + li) * e.ldc + n_base + 8 * hf;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float* row = base + (size_t)(32 * j) * e.ldc;
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            f32x4 o0 = {acc[i][j][8 * q], acc[i][j][8 * q + 1], acc[i][j][8 * q + 2], acc[i][j][8 * q + 3]};
+            f32x4 o1 = {acc[i][j][8 * q + 4], acc[i][j][8 * q + 5], acc[i][j][8 * q + 6], acc[i][j][8 * q + 7]};
+            *reinterpret_cast<f32x4*>(row + 32 * i + 16 * q) = o0;
+            *reinterpret_cast<f32x4*>(row + 32 * i + 16 * q + 4) = o1;
+          }
+      }
+    } else {
+      bf16_t* base = reinterpret_cast<bf16_t*>(e.C) + (size_t)(m_base + li) * e.ldc + n_base + 8 * hf;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        bf16_t* row = base + (size_t)(32 * j) * e.ldc;
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            bf16x8 w;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) w[x] = (bf16_t)acc[i][j][8 * q + x];
+            *reinterpret_cast<bf16x8*>(row + 32 * i + 16 * q) = w;
+          }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int m = m_base + 32 * j + li;
@@ -285,17 +325,28 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
   }
   ue = u + p.upb;
   if (ue > tail_steps) ue = tail_steps;
-  int w = 0;
-  int q = 0, ks = 0, ke = 0;          // current item: tile q, k-steps [ks, ke)
-  auto next_item = [&]() -> bool {
-    if (w < p.full) { q = (xcd * p.full + w) * Gx + slot_in_xcd; ks = 0; ke = p.kt; ++w; return true; }
-    if (u < ue) {
-      const int tr = (int)(u / p.kt);                          // tail tile, or panel
-      ks = (int)(u - (long)tr * p.kt);
-      const long len = (p.kt - ks) < (ue - u) ? (p.kt - ks) : (ue - u);
-      ke = ks + (int)len;
-      q = p.sib ? tr * p.tiles_n + sibling : p.full * p.G + tr;
-      u += len;
+  // The block's items in order: `full` whole tiles, then the pieces of its range of the cut reduction.
+  // The sequence depends only on the block and the plan, so the loader and the MFMA side of the pipelined
+  // kernel each walk it with an iterator of their own.
+  struct ItemIter { int w, tr, k0, left; int q, ks, ke; };     // item: tile q, k-steps [ks, ke)
+  auto first_item = [&]() -> ItemIter {     // before the block's first item
+    ItemIter it;
+    it.w = 0;
+    it.tr = (int)(u / p.kt);                // tail tile (or panel) and k-step at which the block's range starts
+    it.k0 = (int)(u - (long)it.tr * p.kt);
+    it.left = ue > u ? (int)(ue - u) : 0;
+    it.q = it.ks = it.ke = 0;
+    return it;
+  };
+  auto advance = [&](ItemIter& it) -> bool {
+    if (it.w < p.full) { it.q = (xcd * p.full + it.w) * Gx + slot_in_xcd; it.ks = 0; it.ke = p.kt; ++it.w; return true; }
+    if (it.left > 0) {
+      const int len = (p.kt - it.k0) < it.left ? (p.kt - it.k0) : it.left;
+      it.ks = it.k0;
+      it.ke = it.k0 + len;
+      it.q = p.sib ? it.tr * p.tiles_n + sibling : p.full * p.G + it.tr;
+      it.left -= len;
+      if (it.ke == p.kt) { ++it.tr; it.k0 = 0; } else it.k0 = it.ke;
       return true;
     }
     return false;
@@ -303,47 +354,117 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
 
   DmaPlan<A_KC, BM, AI> pa;
   DmaPlan<B_KC, BN, BI> pb;
-  int m0 = 0, n0 = 0, nt = 0;
-  auto start_item = [&]() {          // addresses of the item's operands and the first NSTAGE-1 k-tiles' loads
-    int tm, tn;
-    plan_tile_coords(p, q, tm, tn);
-    m0 = tm * BM; n0 = tn * BN; nt = ke - ks;
-    pa.init(A, m0, wave, lane, ks * BK);
-    pb.init(B, n0, wave, lane, ks * BK);
-#pragma unroll
-    for (int s = 0; s < NSTAGE - 1; ++s)
-      if (s < nt) {
-        pa.issue(smem + s * STAGE_BYTES, s);
-        pb.issue(smem + s * STAGE_BYTES + A_BYTES, s);
-      }
-  };
 
-  bool have = next_item();
-  if (have) start_item();
-  while (have) {
-    f32x16 acc[TN][4];
+  // Writes one finished item: a whole tile through the fused epilogue, a piece of a cut tile as raw partial
+  // sums.  Returns the number of vector stores every lane of this wave is certain to have issued.
+  auto write_item = [&](const f32x16 (&acc)[TN][4], const ItemIter& it) -> int {
+    int tm, tn;
+    plan_tile_coords(p, it.q, tm, tn);
+    const int cm = tm * BM + wm, cn = tn * BN + wn;
+    if (it.ks == 0 && it.ke == p.kt) {
+      store_subtile<TN>(e, acc, cm, cn, li, hf, M, N);
+      const bool interior = cm + 128 <= M && cn + 32 * TN <= N;
+      return interior ? 8 * TN * ((e.pre ? 1 : 0) + (e.c_f32 ? 2 : 1)) : 0;
+    }
+    float* sp = ws + (size_t)(2 * v + (it.ks == 0 ? 1 : 0)) * (BM * BN);
 #pragma unroll
     for (int i = 0; i < TN; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.f;
+        for (int c = 0; c < 4; ++c) {
+          f32x4 o = {acc[i][j][4 * c], acc[i][j][4 * c + 1], acc[i][j][4 * c + 2], acc[i][j][4 * c + 3]};
+          *reinterpret_cast<f32x4*>(sp + slab_index<TN>(wave, i * 4 + j, c, lane)) = o;
+        }
+    return 16 * TN;
+  };
 
-    if constexpr (PIPE) {
-      // One wave per SIMD: nothing else hides a fragment read's latency, so the reads are software
-      // pipelined by hand.  Each 16-deep k-substep's 16 MFMAs run while the next substep's fragments are
-      // read into a second register set; the reads of the next k-tile's first substep need that tile in
-      // LDS, so the wait + barrier sits in the middle of a k-tile, between its two substeps.
-      auto read = [&](const char* as, const char* bs, int kk, bf16x8* fn, bf16x8* fm) {
+  if constexpr (PIPE) {
+    // The block's k-tiles, item after item, are one stream through the ring of LDS stages: the loader runs
+    // NSTAGE-1 k-tiles ahead of the MFMAs *across item boundaries*, so the first k-tiles of the next item are
+    // already in flight while the current item finishes, and a finished item's output stores drain behind
+    // the next item's first k-steps instead of in front of them.
+    //
+    // One wave per SIMD (or two): nothing else hides a fragment read's latency, so the reads are software
+    // pipelined by hand.  Each 16-deep k-substep's MFMAs run while the next substep's fragments are read
+    // into a second register set; the reads of the next k-tile's first substep need that tile in LDS, so
+    // the wait + barrier sits in the middle of a k-tile, between its two substeps.
+    //
+    // vmcnt counts loads and stores together, in issue order.  A mid-step wait for k-tile X allows the
+    // younger k-tiles' loads to stay outstanding and, while X is older than the last item's stores, those
+    // stores too (`relax_left` waits; afterwards the stores are necessarily complete).
+    auto read = [&](const char* as, const char* bs, int kk, bf16x8* fn, bf16x8* fm) {
 #pragma unroll
-        for (int i = 0; i < TN; ++i)
-          fn[i] = B_KC ? frag_kc(bs, wn + 32 * i + n_row, 2 * kk + hf)
-                       : frag_t<BN>(bs, wn + 32 * i + n_rowbase_t, 16 * kk + 8 * hf + kq);
+      for (int i = 0; i < TN; ++i)
+        fn[i] = B_KC ? frag_kc(bs, wn + 32 * i + n_row, 2 * kk + hf)
+                     : frag_t<BN>(bs, wn + 32 * i + n_rowbase_t, 16 * kk + 8 * hf + kq);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        fm[j] = A_KC ? frag_kc(as, wm + 32 * j + li, 2 * kk + hf)
+                     : frag_t<BM>(as, wm + 32 * j + m_rowbase_t, 16 * kk + 8 * hf + kq);
+    };
+    constexpr int NDS = (A_KC ? 4 : 8) + (B_KC ? TN : 2 * TN);   // LDS read instructions per substep
+    ItemIter L = first_item(), C = L;
+    int lt = 0, l_left = 0;          // loader: next k-tile of its item, k-tiles of that item not yet issued
+    int lstage = 0, cstage = 0;      // stage the next issued k-tile goes to; stage of the k-tile being multiplied
+    int inflight = 0;                // k-tiles issued and not yet waited for
+    int ns = 0, relax_left = 0;      // stores of the last written item; waits whose k-tile was issued before them
+    // Makes sure the loader has a k-tile to issue, opening the next item if its current one is used up.
+    // The address arithmetic of an item belongs here, outside the MFMA phases.
+    auto loader_ready = [&]() -> bool {
+      if (l_left > 0) return true;
+      if (!advance(L)) return false;
+      int tm, tn;
+      plan_tile_coords(p, L.q, tm, tn);
+      pa.init(A, tm * BM, wave, lane, L.ks * BK);
+      pb.init(B, tn * BN, wave, lane, L.ks * BK);
+      lt = 0; l_left = L.ke - L.ks;
+      return true;
+    };
+    auto issue_tile = [&]() {        // the stream's next k-tile, into the stage after the last one issued
+      char* dst = smem + lstage * STAGE_BYTES;
+      pa.issue(dst, lt);
+      pb.issue(dst + A_BYTES, lt);
+      ++lt; --l_left; ++inflight;
+      lstage = lstage + 1 == NSTAGE ? 0 : lstage + 1;
+    };
+    // Wait until the oldest k-tile in flight has landed, then the barrier.  code = 3*y + x: y k-tiles issued
+    // after it (capped at 2) and 16*x stores (x capped at 2) may stay outstanding.  Allowing fewer than are
+    // really outstanding only waits longer.
+    auto wait_code = [&](int younger, int extra) -> int {
+      const int x = extra >= 32 ? 2 : (extra >= 16 ? 1 : 0);
+      const int y = (NSTAGE >= 5 && younger >= 2) ? 2 : (younger >= 1 ? 1 : 0);
+      return 3 * y + x;
+    };
+    auto wait_oldest = [&](int code) {
+      switch (code) {
+        case 0: wait_loads_and_barrier<0>(); break;
+        case 1: wait_loads_and_barrier<16>(); break;
+        case 2: wait_loads_and_barrier<32>(); break;
+        case 3: wait_loads_and_barrier<LPT>(); break;
+        case 4: wait_loads_and_barrier<LPT + 16>(); break;
+        case 5: wait_loads_and_barrier<LPT + 32>(); break;
+        case 6: wait_loads_and_barrier<2 * LPT>(); break;
+        case 7: wait_loads_and_barrier<2 * LPT + 16>(); break;
+        default: wait_loads_and_barrier<2 * LPT + 32>(); break;
+      }
+    };
+#pragma unroll 1
+    for (int s = 0; s < NSTAGE - 1; ++s)
+      if (loader_ready()) issue_tile();
+    if (!advance(C)) return;         // this block has no work (and the loader issued nothing)
+    bf16x8 fn0[TN], fm0[4], fn1[TN], fm1[4];
+    wait_oldest(wait_code(inflight - 1, 0));
+    --inflight;
+    read(smem, smem + A_BYTES, 0, fn0, fm0);
+    for (;;) {
+      f32x16 acc[TN][4];
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          fm[j] = A_KC ? frag_kc(as, wm + 32 * j + li, 2 * kk + hf)
-                       : frag_t<BM>(as, wm + 32 * j + m_rowbase_t, 16 * kk + 8 * hf + kq);
-      };
+#pragma unroll
+          for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.f;
       auto mma = [&](const bf16x8* fn, const bf16x8* fm) {
 #pragma unroll
         for (int i = 0; i < TN; ++i)
@@ -351,65 +472,94 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
           for (int j = 0; j < 4; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
       };
-      constexpr int NDS = (A_KC ? 4 : 8) + (B_KC ? TN : 2 * TN);   // LDS read instructions per substep
-      bf16x8 fn0[TN], fm0[4], fn1[TN], fm1[4];
-      wait_loads_and_barrier<0>();
-      if (NSTAGE - 1 < nt) {
-        pa.issue(smem + (NSTAGE - 1) * STAGE_BYTES, NSTAGE - 1);
-        pb.issue(smem + (NSTAGE - 1) * STAGE_BYTES + A_BYTES, NSTAGE - 1);
-      }
-      read(smem, smem + A_BYTES, 0, fn0, fm0);
-      // Every k-tile but the last.  STEADY (k-tiles 1 .. nt-NSTAGE): the loads of k-tile t+NSTAGE-1 are issued
-      // unconditionally, so that the second substep is one basic block in which the scheduler can spread them
-      // between the MFMAs; the few k-tiles before and after take the branching form.
-      auto step = [&](int t, auto steady) {
+      // One k-tile.  STEADY: the pipeline is full, the loader is inside this item and no stores are pending,
+      // so the wait is a constant and the loads are issued unconditionally: the second substep is then one
+      // basic block in which the scheduler can spread them between the MFMAs.  Otherwise everything that
+      // needs arithmetic is decided before the first MFMA.  `last`: the item's last k-tile; the next item's
+      // first fragments are read after this item is written, so that they are not live across the epilogue.
+      auto step = [&](auto steady, bool last) {
         constexpr bool STEADY = decltype(steady)::value;
-        const char* as = smem + (t % NSTAGE) * STAGE_BYTES;
+        bool more = false, load = false;
+        int code = 0;
+        if (!STEADY) {
+          more = inflight > 0;                          // the stream has a k-tile after this one
+          code = wait_code(inflight - 1, relax_left > 0 ? ns : 0);
+          load = more && loader_ready();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        const char* as = smem + cstage * STAGE_BYTES;
         read(as, as + A_BYTES, 1, fn1, fm1);
         mma(fn0, fm0);
         interleave_hint<4 * TN, NDS, 0>();
         __builtin_amdgcn_sched_barrier(0);
-        // k-tile t+1 must have landed; the loads of k-tiles t+2 .. t+NSTAGE-2 stay in flight
-        if (STEADY) wait_loads_and_barrier<(NSTAGE - 3) * LPT>();
-        else if (NSTAGE > 4 && t + 3 < nt) wait_loads_and_barrier<(NSTAGE > 4 ? 2 : 0) * LPT>();
-        else if (t + 2 < nt) wait_loads_and_barrier<LPT>();
-        else wait_loads_and_barrier<0>();
-        char* dst = smem + ((t + NSTAGE - 1) % NSTAGE) * STAGE_BYTES;   // the stage read in k-tile t-1
-        const char* an = smem + ((t + 1) % NSTAGE) * STAGE_BYTES;
+        cstage = cstage + 1 == NSTAGE ? 0 : cstage + 1;
+        const char* an = smem + cstage * STAGE_BYTES;
         if (STEADY) {
-          pa.issue(dst, t + NSTAGE - 1);
-          pb.issue(dst + A_BYTES, t + NSTAGE - 1);
+          wait_loads_and_barrier<(NSTAGE - 3) * LPT>();
+          char* dst = smem + lstage * STAGE_BYTES;      // the stage that was read one k-tile ago
+          pa.issue(dst, lt);
+          pb.issue(dst + A_BYTES, lt);
+          ++lt; --l_left;
+          lstage = lstage + 1 == NSTAGE ? 0 : lstage + 1;
           read(an, an + A_BYTES, 0, fn0, fm0);
           mma(fn1, fm1);
           interleave_hint<4 * TN, NDS, LPT>();
         } else {
-          if (t >= 1 && t + NSTAGE - 1 < nt) {
-            pa.issue(dst, t + NSTAGE - 1);
-            pb.issue(dst + A_BYTES, t + NSTAGE - 1);
+          if (more) {
+            wait_oldest(code);
+            --inflight;
+            if (relax_left > 0) --relax_left;
+            if (load) issue_tile();
+            if (!last) read(an, an + A_BYTES, 0, fn0, fm0);
           }
-          read(an, an + A_BYTES, 0, fn0, fm0);
           mma(fn1, fm1);
           interleave_hint<4 * TN, NDS, 0>();
         }
         __builtin_amdgcn_sched_barrier(0);
       };
+      const int nt = C.ke - C.ks;
       int t = 0;
-      if (nt > 1) step(t++, std::false_type{});
-      for (; t + NSTAGE <= nt; ++t) step(t, std::true_type{});
-      for (; t + 1 < nt; ++t) step(t, std::false_type{});
-      {
-        const char* as = smem + ((nt - 1) % NSTAGE) * STAGE_BYTES;
-        read(as, as + A_BYTES, 1, fn1, fm1);
-        mma(fn0, fm0);
-        interleave_hint<4 * TN, NDS, 0>();
-        __builtin_amdgcn_sched_barrier(0);
-        mma(fn1, fm1);
-      }
-    } else {
+      for (; t < nt && relax_left > 0; ++t) step(std::false_type{}, t + 1 == nt);   // behind the last item's stores
+      for (; t + NSTAGE <= nt; ++t) step(std::true_type{}, false);
+      for (; t < nt; ++t) step(std::false_type{}, t + 1 == nt);                     // the loader is in the next item
+      const ItemIter done = C;
+      const bool have = advance(C);
+      ns = write_item(acc, done);
+      relax_left = inflight;
+      if (!have) break;
+      read(smem + cstage * STAGE_BYTES, smem + cstage * STAGE_BYTES + A_BYTES, 0, fn0, fm0);
+    }
+  } else {
+    // Plain main loop, one item after the other.
+    ItemIter I = first_item();
+    int nt = 0;
+    auto start_item = [&]() {          // addresses of the item's operands and the first NSTAGE-1 k-tiles' loads
+      int tm, tn;
+      plan_tile_coords(p, I.q, tm, tn);
+      nt = I.ke - I.ks;
+      pa.init(A, tm * BM, wave, lane, I.ks * BK);
+      pb.init(B, tn * BN, wave, lane, I.ks * BK);
+#pragma unroll
+      for (int s = 0; s < NSTAGE - 1; ++s)
+        if (s < nt) {
+          pa.issue(smem + s * STAGE_BYTES, s);
+          pb.issue(smem + s * STAGE_BYTES + A_BYTES, s);
+        }
+    };
+    bool have = advance(I);
+    if (have) start_item();
+    while (have) {
+      f32x16 acc[TN][4];
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.f;
       for (int t = 0; t < nt; ++t) {
         // The loads of k-tile t are this thread's oldest outstanding loads; the younger k-tiles (at most
         // NSTAGE-2) stay in flight.  The first k-tile of an item waits for everything: behind the loads
-        // issued by start_item sit the previous item's epilogue stores.
+        // issued by start_item sit the previous item's output stores.
         if (t == 0) wait_loads_and_barrier<0>();
         else if (t + NSTAGE - 2 < nt) wait_loads_and_barrier<(NSTAGE - 2) * LPT>();
         else if (NSTAGE > 3 && t + NSTAGE - 3 < nt) wait_loads_and_barrier<(NSTAGE > 3 ? NSTAGE - 3 : 0) * LPT>();
@@ -439,31 +589,13 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
         }
       }
-
-    }
-
-    // this item's output coordinates, before the next item replaces them
-    const int cm = m0 + wm, cn = n0 + wn;
-    const bool whole = ks == 0 && ke == p.kt;
-    const int slab = 2 * v + (ks == 0 ? 1 : 0);
-    have = next_item();
-    // every wave is done reading the LDS stages: the next item's first loads may overwrite them, and
-    // they fly while this item's results are written
-    asm volatile("s_barrier" ::: "memory");
-    if (have) start_item();
-    if (whole) {
-      store_subtile<TN>(e, acc, cm, cn, li, hf, M, N);
-    } else {
-      float* sp = ws + (size_t)slab * (BM * BN);
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            f32x4 o = {acc[i][j][4 * c], acc[i][j][4 * c + 1], acc[i][j][4 * c + 2], acc[i][j][4 * c + 3]};
-            *reinterpret_cast<f32x4*>(sp + slab_index<TN>(wave, i * 4 + j, c, lane)) = o;
-          }
+      const ItemIter done = I;
+      have = advance(I);
+      // every wave is done reading the LDS stages: the next item's first loads may overwrite them, and
+      // they fly while this item's results are written
+      asm volatile("s_barrier" ::: "memory");
+      if (have) start_item();
+      write_item(acc, done);
     }
   }
 }
