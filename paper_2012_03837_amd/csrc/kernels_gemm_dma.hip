@@ -290,6 +290,28 @@ __device__ __forceinline__ void interleave_hint() {
   }
 }
 
+// The same for a substep that also issues direct-to-LDS loads.  Those write LDS and the fragment reads
+// read it, so the scheduler keeps the two kinds in program order (reads first): the reads are spread over
+// the first half of the MFMAs and the loads over the second half.  Asking for an order that contradicts
+// the dependencies makes the scheduler drop the whole hint and emit both as one burst behind the first
+// MFMA, which stalls the MFMA pipe of both waves of a SIMD at once.
+template <int NMF, int NDS, int NVM>
+__device__ __forceinline__ void interleave_hint_loads() {
+  constexpr int RD = NMF / 2;
+#pragma unroll
+  for (int g = 0; g < NMF; ++g) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // one MFMA
+    const int n = g < RD ? (NDS * (g + 1)) / RD - (NDS * g) / RD : 0;
+    if (n == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    else if (n == 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    else if (n == 3) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+    else if (n == 4) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+    const int m = g >= RD ? (NVM * (g - RD + 1)) / (NMF - RD) - (NVM * (g - RD)) / (NMF - RD) : 0;
+    if (m == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    else if (m == 2) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+  }
+}
+
 template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE, bool PIPE>
 __global__ void __launch_bounds__(128 * WNW, (WNW * TN == 4) ? 2 : (WNW == 4 ? 2 : 1))
 k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) {
@@ -478,7 +500,7 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
       // needs arithmetic is decided before the first MFMA.  `last`: the item's last k-tile; the next item's
       // first fragments are read after this item is written, so that they are not live across the epilogue.
       auto step = [&](auto steady, bool last) {
-        constexpr bool STEADY = decltype(steady)::value;
+        constexpr bool STEADY = decltype(steady)::value != 0;
         bool more = false, load = false;
         int code = 0;
         if (!STEADY) {
@@ -489,21 +511,27 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
         }
         const char* as = smem + cstage * STAGE_BYTES;
         read(as, as + A_BYTES, 1, fn1, fm1);
-        mma(fn0, fm0);
-        interleave_hint<4 * TN, NDS, 0>();
+        if (STEADY && decltype(steady)::value == 2) {   // the B half of the k-tile whose A half went out one substep ago
+          const int ps = lstage == 0 ? NSTAGE - 1 : lstage - 1;
+          pb.issue(smem + ps * STAGE_BYTES + A_BYTES, lt - 1);
+          mma(fn0, fm0);
+          interleave_hint_loads<4 * TN, NDS, BI>();
+        } else {
+          mma(fn0, fm0);
+          interleave_hint<4 * TN, NDS, 0>();
+        }
         __builtin_amdgcn_sched_barrier(0);
         cstage = cstage + 1 == NSTAGE ? 0 : cstage + 1;
         const char* an = smem + cstage * STAGE_BYTES;
         if (STEADY) {
           wait_loads_and_barrier<(NSTAGE - 3) * LPT>();
+          read(an, an + A_BYTES, 0, fn0, fm0);
           char* dst = smem + lstage * STAGE_BYTES;      // the stage that was read one k-tile ago
           pa.issue(dst, lt);
-          pb.issue(dst + A_BYTES, lt);
           ++lt; --l_left;
           lstage = lstage + 1 == NSTAGE ? 0 : lstage + 1;
-          read(an, an + A_BYTES, 0, fn0, fm0);
           mma(fn1, fm1);
-          interleave_hint<4 * TN, NDS, LPT>();
+          interleave_hint_loads<4 * TN, NDS, AI>();
         } else {
           if (more) {
             wait_oldest(code);
@@ -519,9 +547,18 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
       };
       const int nt = C.ke - C.ks;
       int t = 0;
-      for (; t < nt && relax_left > 0; ++t) step(std::false_type{}, t + 1 == nt);   // behind the last item's stores
-      for (; t + NSTAGE <= nt; ++t) step(std::true_type{}, false);
-      for (; t < nt; ++t) step(std::false_type{}, t + 1 == nt);                     // the loader is in the next item
+      typedef std::integral_constant<int, 0> General;
+      for (; t < nt && relax_left > 0; ++t) step(General{}, t + 1 == nt);           // behind the last item's stores
+      // Steady k-tiles issue the A half of a k-tile's loads in their second substep and its B half in the
+      // first substep of the next k-tile, so that the loads of all waves are spread over the whole k-tile
+      // instead of arriving at the memory pipeline in one burst behind the barrier.
+      if (t + NSTAGE <= nt) {
+        step(std::integral_constant<int, 1>{}, false);
+        for (++t; t + NSTAGE <= nt; ++t) step(std::integral_constant<int, 2>{}, false);
+        const int ps = lstage == 0 ? NSTAGE - 1 : lstage - 1;
+        pb.issue(smem + ps * STAGE_BYTES + A_BYTES, lt - 1);
+      }
+      for (; t < nt; ++t) step(General{}, t + 1 == nt);                             // the loader is in the next item
       const ItemIter done = C;
       const bool have = advance(C);
       ns = write_item(acc, done);
