@@ -3,6 +3,7 @@
 // A loader turns (tile row, k) into 16-byte global loads; the plain loaders read dense matrices, the
 // convolution loaders gather NHWC pixels (implicit GEMM) and report zero padding as invalid chunks.
 #pragma once
+#include <type_traits>
 #include "common.h"
 #include "gemm_common.h"
 
@@ -167,7 +168,7 @@ struct PlainLoader {
 };
 
 template <class LA, class LB, int BM>
-__global__ void __launch_bounds__(256, 2) k_mfma_tiles(LA A, LB B, Epilogue e, int M, int N, int K, int tiles_m,
+__global__ void __launch_bounds__(256, BM == 128 ? 3 : 2) k_mfma_tiles(LA A, LB B, Epilogue e, int M, int N, int K, int tiles_m,
                                                        int tiles_n, int splits, float* ws) {
   constexpr bool A_KC = LA::KC, B_KC = LB::KC;
   constexpr int TM = BM / 64;          // 32-row MFMA tiles per wave along m
@@ -199,19 +200,25 @@ __global__ void __launch_bounds__(256, 2) k_mfma_tiles(LA A, LB B, Epilogue e, i
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  bf16x8 ra[BM / 64], rb[BN / 64];
-  unsigned inva = 0, invb = 0;       // chunks the loader declared invalid (implicit zero padding)
+  // Global -> register prefetch NSET k-tiles deep: a k-tile's loads are issued NSET k-tiles before its
+  // registers are written to LDS, so their latency is covered by the MFMAs of those k-tiles (and of the
+  // other block on the CU).  The barrier waits for LDS traffic only: a __syncthreads would also wait for
+  // every outstanding global load and put that latency back on the critical path of each k-tile.
+  constexpr int NSET = 2;
+  bf16x8 ra[NSET][BM / 64], rb[NSET][BN / 64];
+  unsigned inva[NSET], invb[NSET];       // chunks the loader declared invalid (implicit zero padding)
   A.template init<BM>(m0);
   B.template init<BN>(n0);
-  auto fetch = [&](int k0) {
-    inva = A.template fetch<BM>(m0, k0, K, ra);
-    invb = B.template fetch<BN>(n0, k0, K, rb);
+  auto fetch = [&](int s, int k0) {
+    inva[s] = A.template fetch<BM>(m0, k0, K, ra[s]);
+    invb[s] = B.template fetch<BN>(n0, k0, K, rb[s]);
   };
-  auto stage = [&](int buf, int k0) {
+  auto stage = [&](int buf, int s, int k0) {
     if (k0 + BK <= K) k0 = -BK;      // no chunk of this tile can reach K: the masks fold away
-    if (A_KC) stage_kc<BM>(As[buf], ra, k0, K, inva); else stage_t<BM, TA_LD>(As[buf], ra, k0, K, inva);
-    if (B_KC) stage_kc<BN>(Bs[buf], rb, k0, K, invb); else stage_t<BN, TB_LD>(Bs[buf], rb, k0, K, invb);
+    if (A_KC) stage_kc<BM>(As[buf], ra[s], k0, K, inva[s]); else stage_t<BM, TA_LD>(As[buf], ra[s], k0, K, inva[s]);
+    if (B_KC) stage_kc<BN>(Bs[buf], rb[s], k0, K, invb[s]); else stage_t<BN, TB_LD>(Bs[buf], rb[s], k0, K, invb[s]);
   };
+  auto lds_barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
   // fragment addressing that does not depend on k
   const int li = lane & 31;
   const int n_row = nmap(li);                                // kc: tile column read by this lane
@@ -224,16 +231,20 @@ __global__ void __launch_bounds__(256, 2) k_mfma_tiles(LA A, LB B, Epilogue e, i
   const int t_first = split * per;
   const int nt = nt_all - t_first < per ? (nt_all - t_first > 0 ? nt_all - t_first : 0) : per;
   const int kbase = t_first * BK;
-  if (nt > 0) {
-    fetch(kbase);
-    stage(0, kbase);
-  }
-  __syncthreads();
-  if (nt > 1) fetch(kbase + BK);
-  for (int t = 0; t < nt; ++t) {
+#pragma unroll
+  for (int s = 0; s < NSET; ++s)
+    if (s < nt) fetch(s, kbase + s * BK);
+  if (nt > 0) stage(0, 0, kbase);
+  lds_barrier();
+  // k-tile t is in LDS buffer t & 1; register set (t + j) % NSET holds k-tile t + j, j = 1 .. NSET-1, and
+  // set t % NSET is free.  The loop is unrolled by NSET so that the sets are named at compile time.
+  // STEADY: k-tiles t + 1 and t + NSET exist, so nothing in the body is conditional and the compiler counts
+  // the outstanding loads exactly (a conditional fetch makes it wait for all of them at the next stage).
+  auto ktile = [&](int t, auto set, auto steady) {
+    constexpr int U = decltype(set)::value;
+    constexpr bool STEADY = decltype(steady)::value;
     const int cur = t & 1;
-    if (t + 1 < nt) stage(cur ^ 1, kbase + (t + 1) * BK);
-    if (t + 2 < nt) fetch(kbase + (t + 2) * BK);
+    if (STEADY || t + NSET < nt) fetch(U, kbase + (t + NSET) * BK);
     const bf16_t* as = As[cur];
     const bf16_t* bs = Bs[cur];
 #pragma unroll
@@ -251,7 +262,19 @@ __global__ void __launch_bounds__(256, 2) k_mfma_tiles(LA A, LB B, Epilogue e, i
         for (int j = 0; j < TM; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
     }
-    __syncthreads();
+    if (STEADY || t + 1 < nt) stage(cur ^ 1, (U + 1) % NSET, kbase + (t + 1) * BK);
+    lds_barrier();
+  };
+  int t0 = 0;
+  for (; t0 + 2 * NSET <= nt; t0 += NSET) {
+    ktile(t0, std::integral_constant<int, 0>{}, std::true_type{});
+    ktile(t0 + 1, std::integral_constant<int, 1>{}, std::true_type{});
+    if (NSET == 3) ktile(t0 + 2, std::integral_constant<int, NSET == 3 ? 2 : 0>{}, std::true_type{});
+  }
+  for (; t0 < nt; t0 += NSET) {
+    ktile(t0, std::integral_constant<int, 0>{}, std::false_type{});
+    if (t0 + 1 < nt) ktile(t0 + 1, std::integral_constant<int, 1>{}, std::false_type{});
+    if (NSET == 3 && t0 + 2 < nt) ktile(t0 + 2, std::integral_constant<int, NSET == 3 ? 2 : 0>{}, std::false_type{});
   }
 
   // epilogue: lane = row m, accumulator values 8q..8q+7 = columns 16q + 8*(lane/32) .. +7
