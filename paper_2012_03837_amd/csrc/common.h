@@ -27,24 +27,22 @@ template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float f) { return s
 
 enum Act { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
 
-// tanh(u) = 1 - 2 / (1 + e^{2u}) on the hardware exp2 and reciprocal: absolute error of a few 1e-7, exact
-// limits for large |u| (e^{2u} = inf gives 1, 0 gives -1).  The activations below only use 1 + t and
-// 1 - t^2, so the lost relative accuracy of t near 0 does not matter; the library tanhf costs several
-// times as many instructions, and in a fused GEMM epilogue the MFMA pipe idles meanwhile.
-__device__ __forceinline__ float tanh_fast(float u) {
-  const float e = __builtin_amdgcn_exp2f(u * 2.8853900817779268f);     // e^{2u}
-  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
+// GELU in its tanh form, 0.5 x (1 + tanh(u)) with u = c (x + a x^3), written through the identity
+// 0.5 (1 + tanh(u)) = sigmoid(2u) = 1 / (1 + e^{-2u}) on the hardware exp2 and reciprocal: absolute error of
+// a few 1e-7 and exact limits for large |x| (e^{-2u} = inf gives 0, 0 gives 1).  The library tanhf costs
+// several times as many instructions, and in a fused GEMM epilogue the MFMA pipe idles meanwhile.
+__device__ __forceinline__ float gelu_gate(float x) {     // sigmoid(2u)
+  const float k1 = -2.0f * 0.7978845608028654f * 1.4426950408889634f, k3 = k1 * 0.044715f;
+  const float x2 = x * x;
+  const float e = __builtin_amdgcn_exp2f(x * (k1 + k3 * x2));          // e^{-2u}
+  return __builtin_amdgcn_rcpf(1.0f + e);
 }
-__device__ __forceinline__ float gelu_f(float x) {
-  const float c = 0.7978845608028654f, a = 0.044715f;
-  float t = tanh_fast(c * (x + a * x * x * x));
-  return 0.5f * x * (1.0f + t);
-}
+__device__ __forceinline__ float gelu_f(float x) { return x * gelu_gate(x); }
+// d/dx [x s(x)] = s + x s', s' = s (1 - s) 2c (1 + 3 a x^2)
 __device__ __forceinline__ float dgelu_f(float x) {
-  const float c = 0.7978845608028654f, a = 0.044715f;
-  float t = tanh_fast(c * (x + a * x * x * x));
-  float dt = (1.0f - t * t) * c * (1.0f + 3.0f * a * x * x);
-  return 0.5f * (1.0f + t) + 0.5f * x * dt;
+  const float c2 = 2.0f * 0.7978845608028654f, a3 = 3.0f * 0.044715f;
+  const float s = gelu_gate(x);
+  return s * (1.0f + x * (1.0f - s) * (c2 + c2 * a3 * x * x));
 }
 
 // C[M,N] (+)= alpha * sum_k A(m,k) B(n,k), then the epilogue:
