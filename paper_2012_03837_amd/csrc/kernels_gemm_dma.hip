@@ -24,7 +24,7 @@
 // was read during tile t-1, then the MFMAs of tile t; the next item's first loads are issued before the
 // finished item is written.  Hand-pipelined main loop (PIPE): the k-tiles of all of a block's items form
 // one stream through the ring of stages, so the loader stays NSTAGE-1 k-tiles ahead across item boundaries
-// and a finished item's stores drain behind the next item's first k-steps; see the comment in the kernel.
+// and the next item's first k-tiles are in flight while a finished item is written; see the comment in the kernel.
 // Requires K % 32 == 0 (no zero fill on this path).
 #include <type_traits>
 #include "common.h"
@@ -377,16 +377,14 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
   DmaPlan<A_KC, BM, AI> pa;
   DmaPlan<B_KC, BN, BI> pb;
 
-  // Writes one finished item: a whole tile through the fused epilogue, a piece of a cut tile as raw partial
-  // sums.  Returns the number of vector stores every lane of this wave is certain to have issued.
-  auto write_item = [&](const f32x16 (&acc)[TN][4], const ItemIter& it) -> int {
+  // Writes one finished item: a whole tile through the fused epilogue, a piece of a cut tile as raw partial sums.
+  auto write_item = [&](const f32x16 (&acc)[TN][4], const ItemIter& it) {
     int tm, tn;
     plan_tile_coords(p, it.q, tm, tn);
     const int cm = tm * BM + wm, cn = tn * BN + wn;
     if (it.ks == 0 && it.ke == p.kt) {
       store_subtile<TN>(e, acc, cm, cn, li, hf, M, N);
-      const bool interior = cm + 128 <= M && cn + 32 * TN <= N;
-      return interior ? 8 * TN * ((e.pre ? 1 : 0) + (e.c_f32 ? 2 : 1)) : 0;
+      return;
     }
     float* sp = ws + (size_t)(2 * v + (it.ks == 0 ? 1 : 0)) * (BM * BN);
 #pragma unroll
@@ -398,23 +396,22 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
           f32x4 o = {acc[i][j][4 * c], acc[i][j][4 * c + 1], acc[i][j][4 * c + 2], acc[i][j][4 * c + 3]};
           *reinterpret_cast<f32x4*>(sp + slab_index<TN>(wave, i * 4 + j, c, lane)) = o;
         }
-    return 16 * TN;
   };
 
   if constexpr (PIPE) {
     // The block's k-tiles, item after item, are one stream through the ring of LDS stages: the loader runs
     // NSTAGE-1 k-tiles ahead of the MFMAs *across item boundaries*, so the first k-tiles of the next item are
-    // already in flight while the current item finishes, and a finished item's output stores drain behind
-    // the next item's first k-steps instead of in front of them.
+    // already in flight while the current item finishes and is written.
     //
     // One wave per SIMD (or two): nothing else hides a fragment read's latency, so the reads are software
     // pipelined by hand.  Each 16-deep k-substep's MFMAs run while the next substep's fragments are read
     // into a second register set; the reads of the next k-tile's first substep need that tile in LDS, so
     // the wait + barrier sits in the middle of a k-tile, between its two substeps.
     //
-    // vmcnt counts loads and stores together, in issue order.  A mid-step wait for k-tile X allows the
-    // younger k-tiles' loads to stay outstanding and, while X is older than the last item's stores, those
-    // stores too (`relax_left` waits; afterwards the stores are necessarily complete).
+    // A mid-step wait for k-tile X allows as many operations outstanding as the younger k-tiles have loads.
+    // vmcnt also counts the finished item's stores; whatever their completion order relative to the loads,
+    // "at most n outstanding" then still implies that all but the youngest n loads have landed.  (Letting
+    // the stores stay outstanding as well, by exact counting, measured no gain.)
     auto read = [&](const char* as, const char* bs, int kk, bf16x8* fn, bf16x8* fm) {
 #pragma unroll
       for (int i = 0; i < TN; ++i)
@@ -430,7 +427,6 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
     int lt = 0, l_left = 0;          // loader: next k-tile of its item, k-tiles of that item not yet issued
     int lstage = 0, cstage = 0;      // stage the next issued k-tile goes to; stage of the k-tile being multiplied
     int inflight = 0;                // k-tiles issued and not yet waited for
-    int ns = 0, relax_left = 0;      // stores of the last written item; waits whose k-tile was issued before them
     // Makes sure the loader has a k-tile to issue, opening the next item if its current one is used up.
     // The address arithmetic of an item belongs here, outside the MFMA phases.
     auto loader_ready = [&]() -> bool {
@@ -450,33 +446,19 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
       ++lt; --l_left; ++inflight;
       lstage = lstage + 1 == NSTAGE ? 0 : lstage + 1;
     };
-    // Wait until the oldest k-tile in flight has landed, then the barrier.  code = 3*y + x: y k-tiles issued
-    // after it (capped at 2) and 16*x stores (x capped at 2) may stay outstanding.  Allowing fewer than are
-    // really outstanding only waits longer.
-    auto wait_code = [&](int younger, int extra) -> int {
-      const int x = extra >= 32 ? 2 : (extra >= 16 ? 1 : 0);
-      const int y = (NSTAGE >= 5 && younger >= 2) ? 2 : (younger >= 1 ? 1 : 0);
-      return 3 * y + x;
-    };
-    auto wait_oldest = [&](int code) {
-      switch (code) {
-        case 0: wait_loads_and_barrier<0>(); break;
-        case 1: wait_loads_and_barrier<16>(); break;
-        case 2: wait_loads_and_barrier<32>(); break;
-        case 3: wait_loads_and_barrier<LPT>(); break;
-        case 4: wait_loads_and_barrier<LPT + 16>(); break;
-        case 5: wait_loads_and_barrier<LPT + 32>(); break;
-        case 6: wait_loads_and_barrier<2 * LPT>(); break;
-        case 7: wait_loads_and_barrier<2 * LPT + 16>(); break;
-        default: wait_loads_and_barrier<2 * LPT + 32>(); break;
-      }
+    // Wait until the oldest k-tile in flight has landed, then the barrier: `younger` k-tiles were issued
+    // after it (capped at 2; allowing fewer than are really outstanding only waits longer).
+    auto wait_oldest = [&](int younger) {
+      if (NSTAGE >= 5 && younger >= 2) wait_loads_and_barrier<2 * LPT>();
+      else if (younger >= 1) wait_loads_and_barrier<LPT>();
+      else wait_loads_and_barrier<0>();
     };
 #pragma unroll 1
     for (int s = 0; s < NSTAGE - 1; ++s)
       if (loader_ready()) issue_tile();
     if (!advance(C)) return;         // this block has no work (and the loader issued nothing)
     bf16x8 fn0[TN], fm0[4], fn1[TN], fm1[4];
-    wait_oldest(wait_code(inflight - 1, 0));
+    wait_oldest(inflight - 1);
     --inflight;
     read(smem, smem + A_BYTES, 0, fn0, fm0);
     for (;;) {
@@ -494,7 +476,7 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
           for (int j = 0; j < 4; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
       };
-      // One k-tile.  STEADY: the pipeline is full, the loader is inside this item and no stores are pending,
+      // One k-tile.  STEADY: the pipeline is full and the loader is inside this item,
       // so the wait is a constant and the loads are issued unconditionally: the second substep is then one
       // basic block in which the scheduler can spread them between the MFMAs.  Otherwise everything that
       // needs arithmetic is decided before the first MFMA.  `last`: the item's last k-tile; the next item's
@@ -502,10 +484,8 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
       auto step = [&](auto steady, bool last) {
         constexpr bool STEADY = decltype(steady)::value != 0;
         bool more = false, load = false;
-        int code = 0;
         if (!STEADY) {
           more = inflight > 0;                          // the stream has a k-tile after this one
-          code = wait_code(inflight - 1, relax_left > 0 ? ns : 0);
           load = more && loader_ready();
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -534,9 +514,8 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
           interleave_hint_loads<4 * TN, NDS, AI>();
         } else {
           if (more) {
-            wait_oldest(code);
+            wait_oldest(inflight - 1);
             --inflight;
-            if (relax_left > 0) --relax_left;
             if (load) issue_tile();
             if (!last) read(an, an + A_BYTES, 0, fn0, fm0);
           }
@@ -548,7 +527,6 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
       const int nt = C.ke - C.ks;
       int t = 0;
       typedef std::integral_constant<int, 0> General;
-      for (; t < nt && relax_left > 0; ++t) step(General{}, t + 1 == nt);           // behind the last item's stores
       // Steady k-tiles issue the A half of a k-tile's loads in their second substep and its B half in the
       // first substep of the next k-tile, so that the loads of all waves are spread over the whole k-tile
       // instead of arriving at the memory pipeline in one burst behind the barrier.
@@ -561,8 +539,7 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
       for (; t < nt; ++t) step(General{}, t + 1 == nt);                             // the loader is in the next item
       const ItemIter done = C;
       const bool have = advance(C);
-      ns = write_item(acc, done);
-      relax_left = inflight;
+      write_item(acc, done);
       if (!have) break;
       read(smem + cstage * STAGE_BYTES, smem + cstage * STAGE_BYTES + A_BYTES, 0, fn0, fm0);
     }
