@@ -35,6 +35,10 @@ namespace lp {
 namespace {
 
 constexpr int BM = 256, BK = 32;
+// The 8-wave 256 x 256 shape keeps 4 KB of LDS per wave beside its stages to turn a finished plain bf16
+// sub-tile around, so that each store instruction writes whole 128-byte lines (see store_subtile).
+constexpr int XPOSE_BYTES_PER_WAVE = 32 * 128;
+constexpr bool xpose_shape(int WNW, int TN, bool PIPE) { return PIPE && WNW == 4 && TN == 2; }
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void glb_void;
@@ -208,7 +212,7 @@ __device__ __forceinline__ void plan_tile_coords(const SkPlan& p, int q, int& tm
 // columns 32*i + 16*q + 8*hf .. +7 of n-tile i in acc[i][j][8q .. 8q+7].
 template <int TN>
 __device__ __forceinline__ void store_subtile(const Epilogue& e, const f32x16 (&acc)[TN][4], int m_base, int n_base,
-                                              int li, int hf, int M, int N) {
+                                              int li, int hf, int M, int N, char* xs) {
   // Nothing fused and the sub-tile inside the matrix (both wave-uniform): four row pointers, then
   // convert-and-store with immediate offsets.  The general path below costs several microseconds of
   // branches and address arithmetic per tile, during which the block's MFMA pipes idle.
@@ -228,6 +232,34 @@ __device__ __forceinline__ void store_subtile(const Epilogue& e, const f32x16 (&
             *reinterpret_cast<f32x4*>(row + 32 * i + 16 * q) = o0;
             *reinterpret_cast<f32x4*>(row + 32 * i + 16 * q + 4) = o1;
           }
+      }
+    } else if (TN == 2 && xs) {
+      // In the accumulators a row's 128 bytes sit in two lanes (32-byte pieces per store instruction: 32 lines
+      // touched, a quarter of each).  Through the wave's LDS patch, 32 rows x 128 bytes at a time (16-byte
+      // chunk c of row r in slot c ^ ((r >> 1) & 7): conflict-free both ways), lane L then holds chunk L % 8
+      // of row L / 8 (+ 8 per instruction), so an instruction writes 8 whole lines.  The stores are
+      // non-temporal: whole lines need no combining in L2, and the operands are not evicted by the output.
+      const int lane = 32 * hf + li;
+      const int rr = lane >> 3, rc = lane & 7;
+      bf16_t* base = reinterpret_cast<bf16_t*>(e.C) + (size_t)(m_base + rr) * e.ldc + n_base + 8 * rc;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            bf16x8 w;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) w[x] = (bf16_t)acc[i][j][8 * q + x];
+            const int c = 4 * i + 2 * q + hf;
+            *reinterpret_cast<bf16x8*>(xs + li * 128 + ((c ^ ((li >> 1) & 7)) << 4)) = w;
+          }
+#pragma unroll
+        for (int I = 0; I < 4; ++I) {
+          const int r = 8 * I + rr;
+          bf16x8 w = *reinterpret_cast<const bf16x8*>(xs + r * 128 + ((rc ^ ((r >> 1) & 7)) << 4));
+          __builtin_nontemporal_store(w, reinterpret_cast<bf16x8*>(base + (size_t)(32 * j + 8 * I) * e.ldc));
+        }
       }
     } else {
       bf16_t* base = reinterpret_cast<bf16_t*>(e.C) + (size_t)(m_base + li) * e.ldc + n_base + 8 * hf;
@@ -383,7 +415,8 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
     plan_tile_coords(p, it.q, tm, tn);
     const int cm = tm * BM + wm, cn = tn * BN + wn;
     if (it.ks == 0 && it.ke == p.kt) {
-      store_subtile<TN>(e, acc, cm, cn, li, hf, M, N);
+      store_subtile<TN>(e, acc, cm, cn, li, hf, M, N,
+                        xpose_shape(WNW, TN, PIPE) ? smem + NSTAGE * STAGE_BYTES + wave * XPOSE_BYTES_PER_WAVE : nullptr);
       return;
     }
     float* sp = ws + (size_t)(2 * v + (it.ks == 0 ? 1 : 0)) * (BM * BN);
@@ -661,7 +694,7 @@ int device_cus() {
 template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE, bool PIPE>
 hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool partials) {
   constexpr int BN = 32 * TN * WNW;
-  constexpr int smem = NSTAGE * (BM + BN) * BK * 2;
+  constexpr int smem = NSTAGE * (BM + BN) * BK * 2 + (xpose_shape(WNW, TN, PIPE) ? 2 * WNW * XPOSE_BYTES_PER_WAVE : 0);
   static bool configured = false;
   auto kern = k_gemm_dma<A_KC, B_KC, WNW, TN, NSTAGE, PIPE>;
   if (!configured) {
