@@ -75,8 +75,11 @@ __device__ __forceinline__ bf16x8 frag_t(const bf16_t* sm, int rowbase, int ks, 
   return r;
 }
 
-// Fused epilogue on 8 consecutive columns n..n+7 of row m.
-__device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float* v) {
+// Fused epilogue on 8 consecutive columns n..n+7 of row m.  STORE_BF16 = false leaves the final values in v
+// (and the pre-activation, if asked for, in *pre_out) instead of storing a compute-dtype result: for the
+// caller that turns a sub-tile around in LDS so as to store whole lines.
+template <bool STORE_BF16 = true>
+__device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float* v, bf16x8* pre_out = nullptr) {
   if (e.bias) {
     f32x4 b0 = *reinterpret_cast<const f32x4*>(e.bias + n), b1 = *reinterpret_cast<const f32x4*>(e.bias + n + 4);
 #pragma unroll
@@ -86,7 +89,8 @@ __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float
     bf16x8 w;
 #pragma unroll
     for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
-    *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16_t*>(e.pre) + (size_t)m * e.ldc + n) = w;
+    if (STORE_BF16) *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16_t*>(e.pre) + (size_t)m * e.ldc + n) = w;
+    else *pre_out = w;
   }
   if (e.act == ACT_RELU) {
 #pragma unroll
@@ -127,10 +131,12 @@ __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float
 #pragma unroll
       for (int x = 0; x < 8; ++x) v[x] += (float)c0[x];
     }
-    bf16x8 w;
+    if (STORE_BF16) {
+      bf16x8 w;
 #pragma unroll
-    for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
-    *reinterpret_cast<bf16x8*>(cp) = w;
+      for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
+      *reinterpret_cast<bf16x8*>(cp) = w;
+    }
   }
 }
 
@@ -174,8 +180,11 @@ __global__ void __launch_bounds__(256, BM == 128 ? 3 : 2) k_mfma_tiles(LA A, LB 
   constexpr int TM = BM / 64;          // 32-row MFMA tiles per wave along m
   constexpr int TA_LD = BM + 16;
   constexpr int A_ELEMS = BM * KC_LD > BK * TA_LD ? BM * KC_LD : BK * TA_LD;
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][A_ELEMS];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][B_ELEMS];
+  // one block of LDS: operand buffers A0 A1 B0 B1; the epilogue reuses it (>= 32 KB) as its patches
+  __shared__ __attribute__((aligned(16))) bf16_t Sm[2 * A_ELEMS + 2 * B_ELEMS];
+  static_assert((2 * A_ELEMS + 2 * B_ELEMS) * 2 >= 4 * 8192, "epilogue patches do not fit");
+  bf16_t* const As[2] = {Sm, Sm + A_ELEMS};
+  bf16_t* const Bs[2] = {Sm + 2 * A_ELEMS, Sm + 2 * A_ELEMS + B_ELEMS};
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // XCD-aware renumbering, then column-major groups of 8 tile rows
   const int split = blockIdx.x % splits;
@@ -279,6 +288,47 @@ __global__ void __launch_bounds__(256, BM == 128 ? 3 : 2) k_mfma_tiles(LA A, LB 
 
   // epilogue: lane = row m, accumulator values 8q..8q+7 = columns 16q + 8*(lane/32) .. +7
   const int hf = lane >> 5;
+  // A compute-dtype result of a sub-tile inside the matrix leaves through LDS: in the accumulators a row's
+  // 128 bytes sit in two lanes, so a store instruction would touch 32 lines and write a quarter of each.
+  // Each wave turns 32 rows x 128 bytes around in a 4 KB patch of the (now idle) operand buffers (16-byte
+  // chunk c of row r in slot c ^ ((r >> 1) & 7): conflict-free both ways); lane L then holds chunk L % 8 of
+  // row L / 8 (+ 8 per instruction) and an instruction stores 8 whole lines.  The pre-activation, if asked
+  // for, goes the same way through a second patch.
+  if (splits == 1 && !e.c_f32 && m0 + wm + BM / 2 <= M && n0 + wn + 64 <= N) {
+    char* xs = reinterpret_cast<char*>(Sm) + wave * 8192;
+    const int rr = lane >> 3, rc = lane & 7;
+    bf16_t* cbase = reinterpret_cast<bf16_t*>(e.C) + (size_t)(m0 + wm + rr) * e.ldc + n0 + wn + 8 * rc;
+    bf16_t* pbase = reinterpret_cast<bf16_t*>(e.pre) + (size_t)(m0 + wm + rr) * e.ldc + n0 + wn + 8 * rc;
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+      const int m = m0 + wm + 32 * j + li;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int n = n0 + wn + 32 * i + 16 * q + 8 * hf;
+          float v[8];
+#pragma unroll
+          for (int x = 0; x < 8; ++x) v[x] = acc[i][j][8 * q + x];
+          bf16x8 pw;
+          epilogue8<false>(e, m, n, v, &pw);
+          bf16x8 w;
+#pragma unroll
+          for (int x = 0; x < 8; ++x) w[x] = (bf16_t)v[x];
+          const int slot = ((4 * i + 2 * q + hf) ^ ((li >> 1) & 7)) << 4;
+          *reinterpret_cast<bf16x8*>(xs + li * 128 + slot) = w;
+          if (e.pre) *reinterpret_cast<bf16x8*>(xs + 4096 + li * 128 + slot) = pw;
+        }
+#pragma unroll
+      for (int I = 0; I < 4; ++I) {
+        const int r = 8 * I + rr, slot = (rc ^ ((r >> 1) & 7)) << 4;
+        const size_t off = (size_t)(32 * j + 8 * I) * e.ldc;
+        *reinterpret_cast<bf16x8*>(cbase + off) = *reinterpret_cast<const bf16x8*>(xs + r * 128 + slot);
+        if (e.pre) *reinterpret_cast<bf16x8*>(pbase + off) = *reinterpret_cast<const bf16x8*>(xs + 4096 + r * 128 + slot);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
     const int m = m0 + wm + 32 * j + li;
