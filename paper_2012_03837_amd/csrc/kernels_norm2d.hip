@@ -177,9 +177,42 @@ __global__ void k_avgpool_bwd(const T* dfeat, T* dx, size_t n, int HW, int C) {
     dx[i] = from_f<T>(to_f(dfeat[img * C + c]) * inv);
   }
 }
+// One block per image, 16-byte loads: thread (p, cv) sums channel vector cv over pixels p, p + P, ...
+// (P = 256 / channel vectors), then the P partial sums of a channel are added in order of p.
+template <typename T>
+__global__ void __launch_bounds__(256) k_avgpool_fwd_v(const T* __restrict__ x, T* __restrict__ out, int HW, int C) {
+  constexpr int VEC = 16 / (int)sizeof(T);
+  typedef T vec_t __attribute__((ext_vector_type(VEC)));
+  __shared__ float part[256 * VEC];
+  const int CV = C / VEC, P = 256 / CV;
+  const int cv = threadIdx.x % CV, p = threadIdx.x / CV;
+  const T* xi = x + (size_t)blockIdx.x * HW * C + cv * VEC;
+  float a[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) a[e] = 0.f;
+  for (int i = p; i < HW; i += P) {
+    vec_t v = *reinterpret_cast<const vec_t*>(xi + (size_t)i * C);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) a[e] += to_f(v[e]);
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) part[p * C + cv * VEC + e] = a[e];
+  __syncthreads();
+  for (int ch = threadIdx.x; ch < C; ch += 256) {
+    float t = 0.f;
+    for (int q = 0; q < P; ++q) t += part[q * C + ch];
+    out[(size_t)blockIdx.x * C + ch] = from_f<T>(t / (float)HW);
+  }
+}
 hipError_t op_avgpool_fwd(const OpCtx& c, const void* x, void* out, int N, int HW, int C) {
   ProfScope prof_(c, KC_OTHER);
   if (N == 0) return hipSuccess;
+  const int vec = c.dt == BF16 ? 8 : 4;
+  if (C % vec == 0 && C / vec <= 256 && 256 % (C / vec) == 0 && ((uintptr_t)x & 15) == 0) {
+    if (c.dt == BF16) k_avgpool_fwd_v<bf16_t><<<N, 256, 0, c.stream>>>((const bf16_t*)x, (bf16_t*)out, HW, C);
+    else k_avgpool_fwd_v<float><<<N, 256, 0, c.stream>>>((const float*)x, (float*)out, HW, C);
+    return hipGetLastError();
+  }
   if (c.dt == BF16) k_avgpool_fwd<bf16_t><<<N, 256, 0, c.stream>>>((const bf16_t*)x, (bf16_t*)out, HW, C);
   else k_avgpool_fwd<float><<<N, 256, 0, c.stream>>>((const float*)x, (float*)out, HW, C);
   return hipGetLastError();
