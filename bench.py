@@ -169,6 +169,9 @@ def main():
     ap.add_argument("--schedule", default="sync", choices=["sync", "pipelined"],
                     help="sync: every block works on the call's minibatch (the headline metric); pipelined: block j "
                          "works on block j-1's output of the previous call (steady state after warm-up)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step through a HIP graph (lp_step_graph; SGD-type optimizers only): each step "
+                         "copies its batch into one pair of device buffers and launches the captured graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the HIP-event pass (used under rocprofv3)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -206,10 +209,19 @@ def main():
     staged = [tr.stage(*LI.make_batch(cfg, i)) for i in range(n_stage)]
     torch.cuda.synchronize()
 
+    if args.graph:
+        tr.step_graph(True)
+        xb, yb = staged[0][0].clone(), staged[0][1].clone()
+
     def run(n, first):
         for i in range(n):
             xd, yd = staged[(first + i) % n_stage]
-            tr.step(xd, yd)
+            if args.graph:
+                xb.copy_(xd)
+                yb.copy_(yd)
+                tr.step(xb, yb)
+            else:
+                tr.step(xd, yd)
 
     run(W, 0)
     torch.cuda.synchronize()
@@ -279,7 +291,7 @@ def main():
         "config": {"workload": cfg.name, "batch": cfg.batch, "n_layers": cfg.n_layers, "n_heads_aux": len(cfg.heads),
                    "windows": LI.head_windows(cfg)[:3] + (["..."] if len(cfg.heads) > 3 else []),
                    "optimizer": cfg.opt.kind, "combine": cfg.combine, "side_streams": args.streams,
-                   "schedule": args.schedule},
+                   "schedule": args.schedule, "graph": bool(args.graph)},
         "roofline": roofline,
         "phases": phases,
         "final_losses": losses[:4],

@@ -165,6 +165,16 @@ const char* lp_param_name(lp_ctx* ctx, int i);
 int lp_get_step(lp_ctx* ctx);
 int lp_set_step(lp_ctx* ctx, int t);
 
+/* Replay of lp_local_step through a HIP graph, for configurations whose step is bound by kernel launches
+ * rather than by the kernels (small blocks: the residual-MLP setting of section 4 on one GPU).  While on, the
+ * first lp_local_step with given (x_dev, y_dev, batch, losses_dev) runs as usual, the second is captured
+ * (side streams included) and launched as a graph, later ones with the same four arguments replay it; other
+ * arguments start over.  The caller refills the same device buffers between steps.  Results are those of the
+ * ordinary step, bit for bit.  Only for optimizers whose kernels take no per-step scalar (SGD, SGD with
+ * momentum) and the synchronous schedule: LP_EINVAL otherwise.  Steps taken while per-kernel timing is
+ * enabled, and lp_eval_loss, run as usual. */
+int lp_step_graph(lp_ctx* ctx, int on);
+
 /* Gradient similarity (section 5, "Gradient Angles"; Fig. 6a): out_dev[l-1] (device, n_layers floats) =
  * cosine of the angle between the gradients that the last lp_local_step of ctx_a and of ctx_b left for
  * layer l's parameters, all of the layer's tensors taken as one vector; 0 where either gradient is zero

@@ -101,6 +101,7 @@ def lib() -> C.CDLL:
         L.lp_cost_model.argtypes = [C.POINTER(lp_cost_inputs), ip, ip, C.c_double, C.c_double, C.POINTER(lp_cost)]
         L.lp_mlp_flops.argtypes = [ip, ip, ip, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.lp_grad_cosine.argtypes = [vp, vp, vp]
+        L.lp_step_graph.argtypes = [vp, C.c_int]
         L.lp_destroy.argtypes = [vp]
         L.lp_destroy.restype = None
         _lib = L
@@ -226,6 +227,10 @@ def lp_profile_gemm_shapes(ctx: int):
     return rows
 
 
+def lp_step_graph(ctx: int, on: bool) -> None:
+    _check(lib().lp_step_graph(ctx, 1 if on else 0), ctx)
+
+
 def lp_grad_cosine(ctx_a: int, ctx_b: int, out_dev_ptr: int) -> None:
     _check(lib().lp_grad_cosine(ctx_a, ctx_b, out_dev_ptr), ctx_a)
 
@@ -296,6 +301,9 @@ class LocalTrainer:
         b = xd.shape[0] if batch is None else batch
         lp_local_step(self.ctx, xd.data_ptr(), yd.data_ptr(), b, self.losses.data_ptr())
         return self.losses
+
+    def step_graph(self, on: bool = True) -> None:
+        lp_step_graph(self.ctx, on)
 
     def eval(self, xd, yd, batch: int | None = None):
         b = xd.shape[0] if batch is None else batch

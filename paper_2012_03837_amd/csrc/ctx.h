@@ -123,6 +123,13 @@ struct lp_ctx : lp_scratch {
   void use(int i) { static_cast<lp_scratch&>(*this) = sets[i]; }
   int step_t = 0;
   int last_batch = 0;
+  // Replay of a captured synchronous step (lp_step_graph): the graph of the last captured call, the
+  // arguments it was captured with, and how many calls with those arguments have run eagerly so far.
+  bool graph_on = false;
+  hipGraphExec_t gexec = nullptr;
+  hipStream_t gstream = nullptr;          // capture stream (the caller's stream may be the null stream, which cannot capture)
+  const void* g_x = nullptr; const int32_t* g_y = nullptr; float* g_losses = nullptr; int g_batch = -1;
+  int g_eager = 0;
   bool ok = false;
   std::string err;
 

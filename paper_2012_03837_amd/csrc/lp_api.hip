@@ -511,6 +511,8 @@ extern "C" void lp_destroy(lp_ctx* c) {
     for (auto ev : *v)
       if (ev) (void)hipEventDestroy(ev);
   if (c->ev_pipe) (void)hipEventDestroy(c->ev_pipe);
+  if (c->gexec) (void)hipGraphExecDestroy(c->gexec);
+  if (c->gstream) (void)hipStreamDestroy(c->gstream);
   prof_free(c);
   delete c;
 }
@@ -657,7 +659,62 @@ static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* los
   return LP_OK;
 }
 
+static void drop_graph(lp_ctx* c) {
+  if (c->gexec) (void)hipGraphExecDestroy(c->gexec);
+  c->gexec = nullptr; c->g_batch = -1; c->g_eager = 0;
+}
+
+// A training step through a HIP graph.  The first call with a given (x, y, batch, losses) runs eagerly (it
+// also does the one-time kernel attribute set-up), the second is captured from the caller's stream (the
+// side streams join the capture through the events they wait on and are joined back by the final waits)
+// and launched, later ones replay the graph.  What a step leaves on the host is redone by hand on a replay.
+static int run_graph(lp_ctx* c, const void* x, const int32_t* y, int batch, float* losses) {
+  int st = check_call(c, x, y, batch, losses);
+  if (st != LP_OK) return st;
+  if (batch == 0 || c->prof.on) return run(c, x, y, batch, losses, true);
+  if (c->gexec && c->g_x == x && c->g_y == y && c->g_batch == batch && c->g_losses == losses) {
+    for (int li = 1; li <= c->spec.n_layers; ++li) { c->layers[li].in_override = nullptr; c->layers[li].seen = c->layers[li].coverage; }
+    c->x_in = x; c->last_batch = batch; c->step_t += 1;
+    CK(hipGraphLaunch(c->gexec, c->stream));
+    return LP_OK;
+  }
+  if (!(c->g_x == x && c->g_y == y && c->g_batch == batch && c->g_losses == losses)) {
+    drop_graph(c);
+    c->g_x = x; c->g_y = y; c->g_batch = batch; c->g_losses = losses;
+  }
+  if (c->g_eager++ == 0) return run(c, x, y, batch, losses, true);
+  // captured on a stream of the context's own, launched on the caller's
+  if (!c->gstream) CK(hipStreamCreateWithFlags(&c->gstream, hipStreamNonBlocking));
+  hipStream_t user = c->stream;
+  CK(hipStreamBeginCapture(c->gstream, hipStreamCaptureModeThreadLocal));
+  c->stream = c->gstream; c->sets[0].cur_stream = c->gstream;
+  st = run(c, x, y, batch, losses, true);
+  c->stream = user; c->sets[0].cur_stream = user; c->use(0);
+  hipGraph_t graph = nullptr;
+  hipError_t e = hipStreamEndCapture(c->gstream, &graph);
+  if (st != LP_OK) { if (graph) (void)hipGraphDestroy(graph); return st; }
+  if (e != hipSuccess || !graph) return fail(c, LP_EDEVICE, std::string("stream capture failed: ") + hipGetErrorString(e));
+  e = hipGraphInstantiate(&c->gexec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (e != hipSuccess) { c->gexec = nullptr; return fail(c, LP_EDEVICE, std::string("graph instantiation failed: ") + hipGetErrorString(e)); }
+  CK(hipGraphLaunch(c->gexec, c->stream));
+  return LP_OK;
+}
+
+extern "C" int lp_step_graph(lp_ctx* c, int on) {
+  if (!c) return LP_EINVAL;
+  if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
+  if (on && c->spec.opt.kind == LP_OPT_ADAM)
+    return fail(c, LP_EINVAL, "graph replay needs an optimizer without per-step scalars (Adam's bias correction changes every step)");
+  if (on && c->spec.schedule == LP_SCHED_PIPELINED)
+    return fail(c, LP_EINVAL, "graph replay is for the synchronous schedule");
+  if (!on) drop_graph(c);
+  c->graph_on = on != 0;
+  return LP_OK;
+}
+
 extern "C" int lp_local_step(lp_ctx* c, const void* x, const int32_t* y, int batch, float* losses) {
+  if (c && c->ok && c->graph_on) return run_graph(c, x, y, batch, losses);
   return run(c, x, y, batch, losses, true);
 }
 extern "C" int lp_eval_loss(lp_ctx* c, const void* x, const int32_t* y, int batch, float* losses) {

@@ -274,3 +274,40 @@ def test_pipelined_schedule_with_changing_batch_sizes(lpmod):
     for k in P0:
         assert relerr(got_params[k], P[k]) <= 2e-4, k
     tr.close()
+
+
+@pytest.mark.parametrize("name,ns", [("cfg1_small", 0), ("cfg1_small", 2), ("cfg2_small", 3)])
+def test_step_graph_replay_bit_identical(lpmod, name, ns):
+    """A step replayed through a HIP graph (first call eager, second captured, later ones replayed; the same
+    device buffers refilled between steps, an eager evaluation and a host read between replays) leaves the
+    same bits as ordinary steps; a call with other buffers starts over; Adam is refused."""
+    import torch
+    cfg = LI.make_config(name)
+    outs = []
+    for graph in (False, True):
+        tr = lpmod.LocalTrainer(cfg, n_streams=ns)
+        tr.set_params(generic_params(cfg))
+        if graph:
+            tr.step_graph(True)
+        xb, yb = tr.stage(*data_for(cfg, 0))
+        ls, ev = [], []
+        for step in range(6):
+            xd, yd = tr.stage(*data_for(cfg, step))
+            if step == 4:                      # other buffers: eager again, then a new capture
+                xb, yb = xd.clone(), yd.clone()
+            xb.copy_(xd); yb.copy_(yd)
+            ls.append(tr.step(xb, yb).cpu().numpy().copy())
+            ev.append(tr.eval(xd, yd).cpu().numpy().copy())
+            torch.cuda.synchronize()
+        P = tr.get_params()
+        assert lpmod.lp_get_step(tr.ctx) == 6
+        outs.append((ls, ev, P))
+        tr.close()
+    for a, b in zip(outs[0][0] + outs[0][1], outs[1][0] + outs[1][1]):
+        np.testing.assert_array_equal(a, b)
+    for k in outs[0][2]:
+        np.testing.assert_array_equal(outs[0][2][k], outs[1][2][k])
+    tr = lpmod.LocalTrainer(LI.make_config("cfg3_small"))
+    with pytest.raises(lpmod.LpError):
+        tr.step_graph(True)
+    tr.close()
