@@ -507,13 +507,13 @@ __global__ void k_optimizer(float* __restrict__ p, const float* __restrict__ g, 
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   size_t st = (size_t)gridDim.x * blockDim.x;
   for (; i < n4; i += st) {
-    float4 pp = reinterpret_cast<const float4*>(p)[i];
-    float4 gg = reinterpret_cast<const float4*>(g)[i];
+    f32x4 pp = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p) + i);
+    f32x4 gg = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(g) + i);
     float pv[4] = {pp.x, pp.y, pp.z, pp.w};
     float gv[4] = {gg.x * gs, gg.y * gs, gg.z * gs, gg.w * gs};
     float mv[4], vv[4];
-    if (KIND >= 1) { float4 t = reinterpret_cast<const float4*>(m)[i]; mv[0] = t.x; mv[1] = t.y; mv[2] = t.z; mv[3] = t.w; }
-    if (KIND == 2) { float4 t = reinterpret_cast<const float4*>(v)[i]; vv[0] = t.x; vv[1] = t.y; vv[2] = t.z; vv[3] = t.w; }
+    if (KIND >= 1) { f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(m) + i); mv[0] = t.x; mv[1] = t.y; mv[2] = t.z; mv[3] = t.w; }
+    if (KIND == 2) { f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(v) + i); vv[0] = t.x; vv[1] = t.y; vv[2] = t.z; vv[3] = t.w; }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       float gk = gv[k] + wd * pv[k];
@@ -525,9 +525,9 @@ __global__ void k_optimizer(float* __restrict__ p, const float* __restrict__ g, 
         pv[k] -= lr * (mv[k] * c1) / (sqrtf(vv[k] * c2) + eps);
       }
     }
-    reinterpret_cast<float4*>(p)[i] = make_float4(pv[0], pv[1], pv[2], pv[3]);
-    if (KIND >= 1) reinterpret_cast<float4*>(m)[i] = make_float4(mv[0], mv[1], mv[2], mv[3]);
-    if (KIND == 2) reinterpret_cast<float4*>(v)[i] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+    { f32x4 o = {pv[0], pv[1], pv[2], pv[3]}; __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p) + i); }
+    if (KIND >= 1) { f32x4 o = {mv[0], mv[1], mv[2], mv[3]}; __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(m) + i); }
+    if (KIND == 2) { f32x4 o = {vv[0], vv[1], vv[2], vv[3]}; __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(v) + i); }
     if (LOWP) {
       bf16x4 o = {static_cast<bf16_t>(pv[0]), static_cast<bf16_t>(pv[1]), static_cast<bf16_t>(pv[2]), static_cast<bf16_t>(pv[3])};
       reinterpret_cast<bf16x4*>(pl)[i] = o;

@@ -183,7 +183,7 @@ __global__ void __launch_bounds__(256) k_softmax_ce_reg(bf16_t* __restrict__ z, 
   for (int i = 0; i < kCeChunks; ++i) {
     int c = threadIdx.x + 256 * i;
     if (c < nch) {
-      v[i] = *reinterpret_cast<const bf16x8*>(zr + 8 * c);
+      v[i] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(zr + 8 * c));
 #pragma unroll
       for (int e = 0; e < 8; ++e) m = fmaxf(m, (float)v[i][e]);
     }
@@ -220,7 +220,7 @@ __global__ void __launch_bounds__(256) k_softmax_ce_reg(bf16_t* __restrict__ z, 
         if (8 * c + e == yy) p -= 1.f;
         o[e] = (bf16_t)(p * inv_rows);
       }
-      *reinterpret_cast<bf16x8*>(zr + 8 * c) = o;
+      __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(zr + 8 * c));
     }
   }
 }
