@@ -116,6 +116,8 @@ hipError_t op_fill_f32(const OpCtx& c, float* p, size_t n, float v);
 hipError_t op_cosine(const OpCtx& c, const float* a, const float* b, size_t n, float* out);
 hipError_t op_copy(const OpCtx& c, const void* src, void* dst, size_t bytes);   // bytes % 16 == 0
 hipError_t op_cast_to_compute(const OpCtx& c, const float* src, void* dst, size_t n);
+// dst[C][R] = src[R][C]^T, bf16, R and C multiples of 8 and both pointers 16-byte aligned
+hipError_t op_transpose_bf16(const OpCtx& c, const void* src, void* dst, int R, int C);
 
 hipError_t op_embed_fwd(const OpCtx& c, const int32_t* ids, const float* emb, const float* pe, void* out,
                         int T, int S, int d, int V);

@@ -46,7 +46,8 @@ static GemmArgs lin_dgrad(const lp_ctx* c, const void* dy, int rows, int ti_w, v
   const Tensor& w = c->tensors[ti_w];
   GemmArgs g;
   g.A = dy; g.lda = w.shape[0]; g.a_kc = 1;
-  g.B = c->W(ti_w); g.ldb = w.shape[1]; g.b_kc = 0;
+  if (c->wt[ti_w]) { g.B = c->wt[ti_w]; g.ldb = w.shape[0]; g.b_kc = 1; }     // transposed copy [in][out]
+  else { g.B = c->W(ti_w); g.ldb = w.shape[1]; g.b_kc = 0; }
   g.C = dx; g.ldc = w.shape[1];
   g.M = rows; g.N = (int)w.shape[1]; g.K = (int)w.shape[0];
   return g;

@@ -556,6 +556,45 @@ hipError_t op_optimizer(const OpCtx& c, const OptArgs& o, float* p, const float*
   return LP_LAUNCH_CHECK();
 }
 
+// ------------------------------------------------------------------------------------ transpose
+// 64 x 64 tiles through LDS: 16-byte loads of 8 columns, 16-byte stores of 8 rows gathered from a padded tile.
+__global__ void __launch_bounds__(256) k_transpose_bf16(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int R, int C) {
+  __shared__ bf16_t tile[64][64 + 2];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tr = threadIdx.x >> 3, tc = (threadIdx.x & 7) * 8;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = r0 + tr + 32 * i, c = c0 + tc;
+    bf16x8 v;
+    if (r < R && c < C) v = *reinterpret_cast<const bf16x8*>(src + (size_t)r * C + c);
+    else {
+#pragma unroll
+      for (int x = 0; x < 8; ++x) v[x] = (bf16_t)0.f;
+    }
+#pragma unroll
+    for (int x = 0; x < 8; ++x) tile[tr + 32 * i][tc + x] = v[x];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int c = c0 + tr + 32 * i, r = r0 + tc;      // output row c, output columns r .. r+7
+    if (c < C && r < R) {
+      bf16x8 v;
+#pragma unroll
+      for (int x = 0; x < 8; ++x) v[x] = tile[tc + x][tr + 32 * i];
+      *reinterpret_cast<bf16x8*>(dst + (size_t)c * R + r) = v;
+    }
+  }
+}
+hipError_t op_transpose_bf16(const OpCtx& c, const void* src, void* dst, int R, int C) {
+  ProfScope prof_(c, KC_OTHER);
+  if (R <= 0 || C <= 0) return hipSuccess;
+  if (R % 8 || C % 8 || (((uintptr_t)src | (uintptr_t)dst) & 15)) return hipErrorInvalidValue;
+  dim3 grid((C + 63) / 64, (R + 63) / 64);
+  k_transpose_bf16<<<grid, 256, 0, c.stream>>>((const bf16_t*)src, (bf16_t*)dst, R, C);
+  return LP_LAUNCH_CHECK();
+}
+
 // ------------------------------------------------------------------------------------ init
 // Counter-based normal generator: two 64-bit mixes of (seed, stream, index) -> Box-Muller.
 __device__ __forceinline__ uint64_t mix64(uint64_t z) {

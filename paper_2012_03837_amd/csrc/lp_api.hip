@@ -279,6 +279,14 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
     c->pe = (float*)wa.take((size_t)l.seq_len * l.width * 4);
     c->h0 = wa.take((size_t)B * l.seq_len * l.width * es);
   }
+  // transposed bf16 copies of the vocabulary heads' weights (see lp_ctx::wt)
+  c->wt.assign(c->tensors.size(), nullptr);
+  if (dt == BF16)
+    for (auto& Hd : c->heads)
+      if (Hd.s.kind == LP_HEAD_LN_LINEAR_CE && Hd.t.count("w")) {
+        const Tensor& w = c->tensors[Hd.t["w"]];
+        if (w.shape[0] % 8 == 0 && w.shape[1] % 8 == 0) c->wt[Hd.t["w"]] = wa.take(w.numel * 2);
+      }
   if (sp.schedule == LP_SCHED_PIPELINED) {
     const int J = sp.n_heads;
     c->label_elems_per_sample = kind0 == LP_LAYER_DECODER ? (size_t)sp.layers[0].seq_len : 1;
@@ -359,10 +367,20 @@ extern "C" int lp_query_sizes(const lp_model_spec* spec, lp_sizes* out) {
     if (e_ != hipSuccess) return fail(c, LP_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
   } while (0)
 
+// Brings the transposed copies of the weights inside parameter range [off, off + n) up to date with the bf16
+// working copy, on the current stream.
+static int refresh_wt(lp_ctx* c, size_t off, size_t n) {
+  for (size_t ti = 0; ti < c->wt.size(); ++ti) {
+    const Tensor& t = c->tensors[ti];
+    if (!c->wt[ti] || t.off < off || t.off >= off + n) continue;
+    CK(op_transpose_bf16(c->op(), c->W((int)ti), c->wt[ti], (int)t.shape[0], (int)t.shape[1]));
+  }
+  return LP_OK;
+}
 static int refresh_lowp(lp_ctx* c, size_t off, size_t n) {
   if (c->dt != BF16) return LP_OK;
   CK(op_cast_to_compute(c->op(), c->master + off, (bf16_t*)c->lowp + off, n));
-  return LP_OK;
+  return refresh_wt(c, off, n);
 }
 
 extern "C" int lp_init_blocks(const lp_model_spec* spec, const lp_buffers* buffers, void* hip_stream, lp_ctx** out) {
@@ -422,7 +440,11 @@ extern "C" int lp_init_blocks(const lp_model_spec* spec, const lp_buffers* buffe
     if (t.init == 0) CKI(op_init_normal(o, c->master + t.off, t.numel, t.std, spec->seed, (uint64_t)i));
     else if (t.init == 1) CKI(op_fill_f32(o, c->master + t.off, t.numel, 1.f));
   }
-  if (c->dt == BF16) CKI(op_cast_to_compute(o, c->master, c->lowp, c->P));
+  if (c->dt == BF16) {
+    CKI(op_cast_to_compute(o, c->master, c->lowp, c->P));
+    for (size_t ti = 0; ti < c->wt.size(); ++ti)
+      if (c->wt[ti]) CKI(op_transpose_bf16(o, c->W((int)ti), c->wt[ti], (int)c->tensors[ti].shape[0], (int)c->tensors[ti].shape[1]));
+  }
   if (c->pe) CKI(op_posenc_init(o, c->pe, spec->layers[0].seq_len, spec->layers[0].width));
   CKI(hipStreamSynchronize(c->stream));
 #undef CKI
@@ -536,7 +558,7 @@ static int optimizer_range(lp_ctx* c, size_t b, size_t e, float grad_scale, int 
   a.weight_decay = s.weight_decay; a.t = t >= 0 ? t : c->step_t; a.grad_scale = grad_scale;
   CK(op_optimizer(c->op(), a, c->master + b, c->grads + b, c->mom ? c->mom + b : nullptr,
                   c->var ? c->var + b : nullptr, c->lowp ? (void*)((bf16_t*)c->lowp + b) : nullptr, e - b));
-  return LP_OK;
+  return c->lowp ? refresh_wt(c, b, e - b) : LP_OK;      // behind the update, on the same stream
 }
 
 // One call of the pipelined schedule: first the hand-over on the caller's stream (every block's output of
