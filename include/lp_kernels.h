@@ -65,6 +65,11 @@ int lpk_optimizer(int kind, float lr, float momentum, float beta1, float beta2, 
  * which the HBM counters (FETCH_SIZE, WRITE_SIZE) are scaled when a kernel's traffic is measured. */
 int lpk_copy(const void* src_dev, void* dst_dev, size_t bytes, void* stream);
 
+/* dst[C][R] = transpose of src[R][C], bf16 (R and C multiples of 8, both pointers 16-byte aligned).  Keeps the
+ * [in][out] copy of a vocabulary head's weight [out][in] with which the head's input-gradient GEMM
+ * (section 3: the backward pass inside a block) has the reduction index fastest in both operands. */
+int lpk_transpose_bf16(const void* src_dev, void* dst_dev, int R, int C, void* stream);
+
 /* Embedding-table gradient: demb[v,:] (+)= sum of dh[t,:] over positions with ids[t] == v, in order of t
  * (ids outside [0, V) count as the nearest valid id, as in the forward lookup).  scratch_dev (may be NULL)
  * is device scratch of scratch_elems 4-byte words; with at least V words the kernel first counts every

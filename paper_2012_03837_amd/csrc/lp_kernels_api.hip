@@ -79,6 +79,9 @@ extern "C" int lpk_copy(const void* src, void* dst, size_t bytes, void* stream) 
   if (bytes % 16 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return (int)hipErrorInvalidValue;
   return (int)op_copy(mk(0, stream), src, dst, bytes);
 }
+extern "C" int lpk_transpose_bf16(const void* src, void* dst, int R, int C, void* stream) {
+  return (int)op_transpose_bf16(mk(1, stream), src, dst, R, C);
+}
 extern "C" int lpk_embed_bwd(int dtype, const int32_t* ids, const void* dh, float* demb, int T, int V, int d,
                              int accumulate, float* scratch, size_t scratch_elems, void* stream) {
   return (int)op_embed_bwd(mk(dtype, stream, scratch, scratch_elems), ids, dh, demb, T, V, d, accumulate);

@@ -73,6 +73,10 @@ def lpk_copy(src, dst, nbytes):
     _ck(lib().lpk_copy(_p(src), _p(dst), _sz(nbytes), _stream()), "lpk_copy")
 
 
+def lpk_transpose_bf16(src, dst, R, C):
+    _ck(lib().lpk_transpose_bf16(_p(src), _p(dst), _i(R), _i(C), _stream()), "lpk_transpose_bf16")
+
+
 def lpk_embed_bwd(dtype, ids, dh, demb, T, V, d, accumulate=0, scratch=None):
     _ck(lib().lpk_embed_bwd(_i(dtype), _p(ids), _p(dh), _p(demb), _i(T), _i(V), _i(d), _i(accumulate), _p(scratch),
                             _sz(0 if scratch is None else scratch.numel()), _stream()), "lpk_embed_bwd")

@@ -327,6 +327,18 @@ def test_copy_bit_exact(K):
         K.lpk_copy(src, dst, 24)          # not a multiple of 16
 
 
+@pytest.mark.parametrize("R,C", [(64, 64), (8, 8), (200, 72), (1000, 264), (32000, 768), (72, 4104)])
+def test_transpose_bf16_bit_exact(K, R, C):
+    """The transposed weight copy is the transpose, bit for bit, also where 64 x 64 tiles are ragged."""
+    import torch
+    src = torch.randn(R, C, device="cuda").to(torch.bfloat16)
+    dst = torch.zeros(C, R, device="cuda", dtype=torch.bfloat16)
+    K.lpk_transpose_bf16(src, dst, R, C)
+    assert torch.equal(dst, src.t().contiguous())
+    with pytest.raises(RuntimeError):
+        K.lpk_transpose_bf16(src, dst, R - 1, C)      # not a multiple of 8
+
+
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("N,H,C,O,R,stride,pad", [(3, 9, 5, 7, 3, 1, 1), (2, 8, 16, 24, 3, 2, 1), (2, 8, 16, 8, 1, 2, 0),
                                                   (4, 12, 3, 64, 3, 1, 1), (5, 14, 64, 136, 3, 1, 1),
