@@ -10,10 +10,15 @@ the exact-zero gradient across truncation boundaries, the reductions to ordinary
 closed forms (zero head => loss = ln C), brute-force loops for convolution / attention /
 optimizers on tiny shapes, and independent library routines (torch CPU autograd) for each
 primitive and for a whole decoder layer.  The paper prints no numeric example of a step, so the
-end-to-end values themselves are pinned only through those properties.
+end-to-end values themselves are pinned only through those properties.  The running statistics of
+batch normalisation (a convention the paper leaves open) are pinned by torch's BatchNorm2d on CPU, a
+closed form on a repeated batch, and the identity "normalising with the batch's own statistics repeats
+batch mode" on a whole model.
 """
+from .ops import BatchNormRunning
 from .local import (eval_loss, local_gradients, local_step, block_gradients, new_state,
                     forward_all, optimizer_update, layer_gradient_cosines, new_pipeline, pipelined_step)
 
 __all__ = ["eval_loss", "local_gradients", "local_step", "block_gradients", "new_state",
-           "forward_all", "optimizer_update", "layer_gradient_cosines", "new_pipeline", "pipelined_step"]
+           "forward_all", "optimizer_update", "layer_gradient_cosines", "new_pipeline", "pipelined_step",
+           "BatchNormRunning"]

@@ -108,14 +108,14 @@ def decoder_bwd(P, pre, l, cache, dout, need_dx, first, vocab):
 
 
 # ============================================================================= ResNet stage
-def _conv_bn(P, wname, bnpre, x, stride, pad, relu, res=None, q=ops.identity):
+def _conv_bn(P, wname, bnpre, x, stride, pad, relu, res=None, q=ops.identity, bn=None):
     """out = [relu]( BN(conv(x)) [+ res] ); the conv output and the result are stored activations."""
     z = q(ops.conv2d_fwd(x, P[wname], stride, pad))
-    y, bn = ops.batchnorm_fwd(z, P[bnpre + "g"], P[bnpre + "b"])
+    y, bnc = ops.batchnorm(z, P[bnpre + "g"], P[bnpre + "b"], bn, bnpre)
     if res is not None:
         y = y + res
     out = q(ops.relu_fwd(y) if relu else y)
-    return out, {"x": x, "bn": bn, "out": out, "stride": stride, "pad": pad, "relu": relu}
+    return out, {"x": x, "bn": bnc, "out": out, "stride": stride, "pad": pad, "relu": relu}
 
 
 def _conv_bn_bwd(P, wname, bnpre, c, dout, g, need_dx=True):
@@ -126,22 +126,22 @@ def _conv_bn_bwd(P, wname, bnpre, c, dout, g, need_dx=True):
     return dx, dy
 
 
-def resnet_stage_fwd(P, pre, l, x, q=ops.identity):
+def resnet_stage_fwd(P, pre, l, x, q=ops.identity, bn=None):
     """stem (optional) then n BasicBlocks: relu(bn2(conv2(relu(bn1(conv1 x)))) + shortcut(x))."""
     cache = {"blocks": []}
     h = x
     if l.has_stem:
-        h, cache["stem"] = _conv_bn(P, pre + "stem.w", pre + "stem.bn.", h, 1, 1, True, q=q)
+        h, cache["stem"] = _conv_bn(P, pre + "stem.w", pre + "stem.bn.", h, 1, 1, True, q=q, bn=bn)
     for b in range(l.n_basic_blocks):
         n = pre + f"b{b + 1}."
         stride = l.stride if (b == 0 and not l.has_stem) else 1
         bc = {"in": h}
-        t, bc["c1"] = _conv_bn(P, n + "conv1.w", n + "bn1.", h, stride, 1, True, q=q)
+        t, bc["c1"] = _conv_bn(P, n + "conv1.w", n + "bn1.", h, stride, 1, True, q=q, bn=bn)
         if (n + "proj.w") in P:
-            sc, bc["proj"] = _conv_bn(P, n + "proj.w", n + "proj.bn.", h, stride, 0, False, q=q)
+            sc, bc["proj"] = _conv_bn(P, n + "proj.w", n + "proj.bn.", h, stride, 0, False, q=q, bn=bn)
         else:
             sc = h
-        h, bc["c2"] = _conv_bn(P, n + "conv2.w", n + "bn2.", t, 1, 1, True, res=sc, q=q)
+        h, bc["c2"] = _conv_bn(P, n + "conv2.w", n + "bn2.", t, 1, 1, True, res=sc, q=q, bn=bn)
         cache["blocks"].append(bc)
     return h, cache
 
@@ -167,7 +167,7 @@ def resnet_stage_bwd(P, pre, l, cache, dout, need_dx=True):
 
 
 # ============================================================================= dispatch
-def layer_fwd(cfg, P, li, x, q=ops.identity):
+def layer_fwd(cfg, P, li, x, q=ops.identity, bn=None):
     l = cfg.layers[li - 1]
     pre = f"L{li}."
     if l.kind == "resmlp":
@@ -175,7 +175,7 @@ def layer_fwd(cfg, P, li, x, q=ops.identity):
     if l.kind == "decoder":
         return decoder_fwd(P, pre, l, x, li == 1, cfg.vocab, q)
     if l.kind == "resnet_stage":
-        return resnet_stage_fwd(P, pre, l, x, q)
+        return resnet_stage_fwd(P, pre, l, x, q, bn)
     raise ValueError(l.kind)
 
 
@@ -192,7 +192,7 @@ def layer_bwd(cfg, P, li, cache, dout, need_dx):
 
 
 # ============================================================================= heads
-def head_loss(cfg, P, hi, h, y, q=ops.identity):
+def head_loss(cfg, P, hi, h, y, q=ops.identity, bn=None):
     """Auxiliary objective of head hi on activation h with labels y.  Returns (loss, cache)."""
     hd = cfg.heads[hi - 1]
     pre = f"H{hi}."
@@ -202,7 +202,7 @@ def head_loss(cfg, P, hi, h, y, q=ops.identity):
         cache["hw_shape"] = h.shape
     elif hd.kind == "bn_pool_linear_ce":
         # appendix B.3: batch normalisation, ReLU, mean over the spatial dimensions, then the linear projection
-        a, cache["bn"] = ops.batchnorm_fwd(h, P[pre + "bn.g"], P[pre + "bn.b"])
+        a, cache["bn"] = ops.batchnorm(h, P[pre + "bn.g"], P[pre + "bn.b"], bn, pre + "bn.")
         a = q(ops.relu_fwd(a))
         cache["a"] = a
         feat = q(a.mean(axis=(1, 2)))

@@ -18,6 +18,8 @@ Each loss_j is differentiated separately, exactly as defined; no fusion of overl
 """
 from __future__ import annotations
 
+import copy
+
 import numpy as np
 
 from . import layers as L
@@ -40,38 +42,48 @@ def _cast(P, dtype, q=ops.identity):
             for k, v in P.items()}
 
 
+def _as_mode(bn, mode):
+    """The same running statistics (shared dictionaries), seen by a forward pass in the given mode."""
+    v = copy.copy(bn)
+    v.mode = mode
+    return v
+
+
 def _windows(cfg):
     return [(max(h.after_layer - h.window, 0), h.after_layer) for h in cfg.heads]
 
 
-def forward_all(cfg, P, x, q=ops.identity):
+def forward_all(cfg, P, x, q=ops.identity, bn=None):
     """Step 1.  Returns activations hs[0..L] (hs[0] = x) and per-layer caches[1..L]."""
     hs = [x]
     caches = [None]
     for li in range(1, cfg.n_layers + 1):
-        out, c = L.layer_fwd(cfg, P, li, hs[-1], q)
+        out, c = L.layer_fwd(cfg, P, li, hs[-1], q, bn)
         hs.append(out)
         caches.append(c)
     return hs, caches
 
 
-def eval_loss(cfg, params, x, y, dtype=np.float64, stored=None):
-    """Steps 1-2, values only: the loss of every head at the current weights."""
+def eval_loss(cfg, params, x, y, dtype=np.float64, stored=None, bn=None):
+    """Steps 1-2, values only: the loss of every head at the current weights.  With ``bn`` (a
+    BatchNormRunning) every batch normalisation uses the running statistics instead of the batch's."""
+    if bn is not None:
+        bn = _as_mode(bn, "use")
     q = _policy(stored)
     P = _cast(params, dtype, q)
     xx = x if np.issubdtype(np.asarray(x).dtype, np.integer) else np.asarray(x, dtype=dtype)
-    hs, _ = forward_all(cfg, P, xx, q)
-    return np.array([L.head_loss(cfg, P, hi, hs[h.after_layer], y, q)[0]
+    hs, _ = forward_all(cfg, P, xx, q, bn)
+    return np.array([L.head_loss(cfg, P, hi, hs[h.after_layer], y, q, bn)[0]
                      for hi, h in enumerate(cfg.heads, start=1)], dtype=np.float64)
 
 
-def head_gradients(cfg, P, hi, hs, caches, y, q=ops.identity):
+def head_gradients(cfg, P, hi, hs, caches, y, q=ops.identity, bn=None):
     """Steps 2-3 for one head: loss_j and the gradient of loss_j w.r.t. everything in its window.
 
     hs[s_j] is treated as data: the backward pass stops there (need_dx False at layer s_j + 1).
     """
     s, e = _windows(cfg)[hi - 1]
-    loss, hc = L.head_loss(cfg, P, hi, hs[e], y, q)
+    loss, hc = L.head_loss(cfg, P, hi, hs[e], y, q, bn)
     dh, grads = L.head_bwd(cfg, P, hi, hc)
     for li in range(e, s, -1):
         dh, g = L.layer_bwd(cfg, P, li, caches[li], dh, need_dx=(li > s + 1))
@@ -79,19 +91,22 @@ def head_gradients(cfg, P, hi, hs, caches, y, q=ops.identity):
     return loss, grads
 
 
-def local_gradients(cfg, params, x, y, dtype=np.float64, per_head=False, stored=None):
+def local_gradients(cfg, params, x, y, dtype=np.float64, per_head=False, stored=None, bn=None):
     """Steps 1-3.  Returns (losses[n_heads], grads by parameter name, coverage count by name).
 
-    Parameters covered by no window are absent from ``grads``.
+    Parameters covered by no window are absent from ``grads``.  With ``bn`` (a BatchNormRunning) every
+    batch normalisation the step evaluates folds its batch statistics into the running ones, once.
     """
+    if bn is not None:
+        bn = _as_mode(bn, "update")
     q = _policy(stored)
     P = _cast(params, dtype, q)
     xx = x if np.issubdtype(np.asarray(x).dtype, np.integer) else np.asarray(x, dtype=dtype)
-    hs, caches = forward_all(cfg, P, xx, q)
+    hs, caches = forward_all(cfg, P, xx, q, bn)
     losses = []
     total, count, each = {}, {}, []
     for hi in range(1, len(cfg.heads) + 1):
-        loss, g = head_gradients(cfg, P, hi, hs, caches, y, q)
+        loss, g = head_gradients(cfg, P, hi, hs, caches, y, q, bn)
         losses.append(loss)
         each.append(g)
         for k, v in g.items():
@@ -110,9 +125,11 @@ def local_gradients(cfg, params, x, y, dtype=np.float64, per_head=False, stored=
     return np.array(losses), total, count
 
 
-def block_gradients(cfg, params, hi, h_s, y, dtype=np.float64, stored=None):
+def block_gradients(cfg, params, hi, h_s, y, dtype=np.float64, stored=None, bn=None):
     """Head hi alone, fed its window input h_s as data (that input is detached by definition, so
     the block's loss and gradients depend on the rest of the network only through h_s)."""
+    if bn is not None:
+        bn = _as_mode(bn, "update")
     q = _policy(stored)
     P = _cast(params, dtype, q)
     s, e = _windows(cfg)[hi - 1]
@@ -120,8 +137,8 @@ def block_gradients(cfg, params, hi, h_s, y, dtype=np.float64, stored=None):
     hs = {s: x}
     caches = {}
     for li in range(s + 1, e + 1):
-        hs[li], caches[li] = L.layer_fwd(cfg, P, li, hs[li - 1], q)
-    loss, hc = L.head_loss(cfg, P, hi, hs[e], y, q)
+        hs[li], caches[li] = L.layer_fwd(cfg, P, li, hs[li - 1], q, bn)
+    loss, hc = L.head_loss(cfg, P, hi, hs[e], y, q, bn)
     dh, grads = L.head_bwd(cfg, P, hi, hc)
     for li in range(e, s, -1):
         dh, g = L.layer_bwd(cfg, P, li, caches[li], dh, need_dx=(li > s + 1))
@@ -162,10 +179,10 @@ def optimizer_update(opt, p, g, state, name, t):
     raise ValueError(opt.kind)
 
 
-def local_step(cfg, params, state, x, y, dtype=np.float64, stored=None):
+def local_step(cfg, params, state, x, y, dtype=np.float64, stored=None, bn=None):
     """Steps 1-5.  Returns (losses, new params, grads).  ``state`` is updated in place.  The update
     always acts on the exact (master) weights, whatever the storage precision of the passes."""
-    losses, grads, _ = local_gradients(cfg, params, x, y, dtype, stored=stored)
+    losses, grads, _ = local_gradients(cfg, params, x, y, dtype, stored=stored, bn=bn)
     state["t"] += 1
     t = state["t"]
     new = {}
@@ -207,7 +224,7 @@ def new_pipeline(cfg):
     return {"stash": [None] * (J + 2), "updates": [0] * (J + 1)}
 
 
-def pipelined_step(cfg, params, state, pipe, x, y, dtype=np.float64, stored=None):
+def pipelined_step(cfg, params, state, pipe, x, y, dtype=np.float64, stored=None, bn=None):
     """One call of the pipelined form of local parallelism (section 6: the pipeline runs in steady state
     after a ramp-up, updates applied asynchronously; section 3: activations and labels move forward one
     stage per iteration, so every stage has the input and target it needs for local learning).
@@ -229,7 +246,7 @@ def pipelined_step(cfg, params, state, pipe, x, y, dtype=np.float64, stored=None
         inp = (x, y) if j == 1 else pipe["stash"][j]
         if inp is None:
             continue
-        loss, grads, out = block_gradients(cfg, params, j, inp[0], inp[1], dtype, stored)
+        loss, grads, out = block_gradients(cfg, params, j, inp[0], inp[1], dtype, stored, bn)
         losses[j - 1] = loss
         pipe["updates"][j] += 1
         for k, g in grads.items():

@@ -112,6 +112,61 @@ def batchnorm_fwd(x, g, b):
     return (xhat * g + b).reshape(x.shape), (xhat, rstd)
 
 
+def batchnorm_running_fwd(x, g, b, run_mean, run_var):
+    """Normalisation with fixed per-channel statistics (evaluation form of Ioffe & Szegedy's batch
+    normalisation, which appendix B.3 cites): y = (x - run_mean) / sqrt(run_var + eps) * g + b."""
+    return (x - run_mean) / np.sqrt(run_var + BN_EPS) * g + b
+
+
+class BatchNormRunning:
+    """Running per-channel statistics of every batch normalisation, keyed by the parameter prefix.
+
+    The paper does not say how its ResNets normalise at evaluation time; this takes the usual convention
+    of the method it cites: an exponential moving average with weight ``momentum`` on the newest batch,
+        run_mean <- (1 - momentum) run_mean + momentum * mean_B
+        run_var  <- (1 - momentum) run_var  + momentum * var_B * n / (n - 1)    (unbiased batch variance)
+    started from mean 0, variance 1.  ``mode`` selects what a forward pass does with it:
+    "update" normalises with the statistics of the batch and folds them in, "use" normalises with the
+    running ones, "batch" ignores it."""
+
+    def __init__(self, momentum=0.1, mode="update"):
+        self.momentum = float(momentum)
+        self.mode = mode
+        self.mean = {}
+        self.var = {}
+
+    def ensure(self, name, C):
+        if name not in self.mean:
+            self.mean[name] = np.zeros(C)
+            self.var[name] = np.ones(C)
+
+    def observe(self, name, x):
+        C = x.shape[-1]
+        x2 = np.asarray(x, dtype=np.float64).reshape(-1, C)
+        n = x2.shape[0]
+        mu = x2.mean(axis=0)
+        var = ((x2 - mu) ** 2).mean(axis=0)
+        if n > 1:
+            var = var * n / (n - 1)
+        self.ensure(name, C)
+        m = self.momentum
+        self.mean[name] = (1.0 - m) * self.mean[name] + m * mu
+        self.var[name] = (1.0 - m) * self.var[name] + m * var
+
+
+def batchnorm(x, g, b, running=None, name=None):
+    """Batch normalisation as a forward pass sees it: (y, cache for batchnorm_bwd or None)."""
+    if running is None or running.mode == "batch":
+        return batchnorm_fwd(x, g, b)
+    running.ensure(name, x.shape[-1])
+    if running.mode == "use":
+        return batchnorm_running_fwd(x, g, b, running.mean[name], running.var[name]), None
+    if running.mode == "update":
+        running.observe(name, x)
+        return batchnorm_fwd(x, g, b)
+    raise ValueError(running.mode)
+
+
 def batchnorm_bwd(cache, g, dy):
     xhat, rstd = cache
     C = xhat.shape[-1]
