@@ -144,13 +144,27 @@ int lp_init_blocks(const lp_model_spec* spec, const lp_buffers* buffers, void* h
  * batch 0 does not advance the pipeline.  lp_eval_loss is the same in both schedules. */
 int lp_local_step(lp_ctx* ctx, const void* x_dev, const int32_t* y_dev, int batch, float* losses_dev);
 
-/* Forward pass and head losses only; no state changes.  (BatchNorm uses the statistics of the
- * batch given, so this equals the losses a step on the same batch would report.) */
+/* Forward pass and head losses only; no state changes.  (By default BatchNorm uses the statistics of the
+ * batch given, so this equals the losses a step on the same batch would report; see lp_bn_running.) */
 int lp_eval_loss(lp_ctx* ctx, const void* x_dev, const int32_t* y_dev, int batch, float* losses_dev);
+
+/* Running statistics of batch normalisation (appendix B.3 normalises the ResNet blocks and their auxiliary
+ * heads with the method of Ioffe & Szegedy; the paper does not say how it evaluates, so this is that method's
+ * usual evaluation form).  Every lp_local_step folds the statistics of each batch normalisation it evaluates,
+ * once, into that normalisation's running pair (fp32, in the state buffer, started at mean 0, variance 1):
+ *   running_mean <- (1 - momentum) running_mean + momentum * mean_B
+ *   running_var  <- (1 - momentum) running_var  + momentum * var_B * n / (n - 1),   n = batch * H * W.
+ * momentum in [0, 1]; 0 keeps them as they are; the default is 0.1.  With eval_with_running != 0,
+ * lp_eval_loss normalises with the running pair instead of the batch's own statistics (each sample is then
+ * evaluated independently of the rest of its batch); the default is 0.  Steps always normalise with the batch.
+ * The pairs are the named tensors "<prefix>.running_mean" / "<prefix>.running_var" for every gain tensor
+ * "<prefix>.g" of a batch normalisation ("L1.stem.bn", "L2.b1.bn1", "H3.bn", ...).
+ * LP_EINVAL for a momentum outside [0, 1]. */
+int lp_bn_running(lp_ctx* ctx, float momentum, int eval_with_running);
 
 /* Named tensors.  Parameters "L3.wqkv", "H2.w" (fp32 master; setting one also refreshes the bf16
  * working copy); their gradients of the last step "L3.wqkv.grad" and optimizer moments ".m", ".v"
- * (fp32); layer outputs of the last forward "L3.out" and the embedded input "L0.out" (compute
+ * (fp32); batch-normalisation running statistics "L2.b1.bn1.running_mean", ".running_var" (fp32); layer outputs of the last forward "L3.out" and the embedded input "L0.out" (compute
  * dtype, shaped for the batch of that call).  lp_tensor_info reports shape, lp_dtype and bytes.
  * get/set copy synchronously between host memory and the device after draining the stream;
  * `bytes` must equal the tensor's size. */

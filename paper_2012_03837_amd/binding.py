@@ -102,6 +102,7 @@ def lib() -> C.CDLL:
         L.lp_mlp_flops.argtypes = [ip, ip, ip, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.lp_grad_cosine.argtypes = [vp, vp, vp]
         L.lp_step_graph.argtypes = [vp, C.c_int]
+        L.lp_bn_running.argtypes = [vp, C.c_float, C.c_int]
         L.lp_destroy.argtypes = [vp]
         L.lp_destroy.restype = None
         _lib = L
@@ -231,6 +232,10 @@ def lp_step_graph(ctx: int, on: bool) -> None:
     _check(lib().lp_step_graph(ctx, 1 if on else 0), ctx)
 
 
+def lp_bn_running(ctx: int, momentum: float = 0.1, eval_with_running: bool = False) -> None:
+    _check(lib().lp_bn_running(ctx, float(momentum), 1 if eval_with_running else 0), ctx)
+
+
 def lp_grad_cosine(ctx_a: int, ctx_b: int, out_dev_ptr: int) -> None:
     _check(lib().lp_grad_cosine(ctx_a, ctx_b, out_dev_ptr), ctx_a)
 
@@ -304,6 +309,9 @@ class LocalTrainer:
 
     def step_graph(self, on: bool = True) -> None:
         lp_step_graph(self.ctx, on)
+
+    def bn_running(self, momentum: float = 0.1, eval_with_running: bool = False) -> None:
+        lp_bn_running(self.ctx, momentum, eval_with_running)
 
     def eval(self, xd, yd, batch: int | None = None):
         b = xd.shape[0] if batch is None else batch

@@ -158,9 +158,21 @@ hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const v
 hipError_t op_conv_bwd_data(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx);
 hipError_t op_conv_bwd_weight(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                               int accumulate);
-// y = [relu]( bn(z) (+ res) ), batch statistics over rows = N*H*W; saves mean, rstd.
+// Running statistics of one batch normalisation (the evaluation form of the method appendix B.3 cites).
+// use == 0: the forward pass normalises with the batch's statistics and folds them in,
+//   mean <- (1 - momentum) mean + momentum mean_B,  var <- (1 - momentum) var + momentum var_B rows / (rows - 1);
+// use == 1: it normalises with mean / var as they stand and leaves them alone.
+struct BnRunning {
+  float* mean = nullptr;
+  float* var = nullptr;
+  float momentum = 0.f;
+  int use = 0;
+};
+// y = [relu]( bn(z) (+ res) ), batch statistics over rows = N*H*W (or the running ones, see BnRunning);
+// saves the mean and reciprocal standard deviation it normalised with.
 hipError_t op_batchnorm_fwd(const OpCtx& c, const void* z, const float* g, const float* b, const void* res,
-                            void* y, float* mean, float* rstd, int rows, int C, int relu);
+                            void* y, float* mean, float* rstd, int rows, int C, int relu,
+                            const BnRunning* run = nullptr);
 // dy_eff = relu ? dy * (y > 0) : dy;  dz = bn-backward(dy_eff); dg, db; if dres: dres = dy_eff.
 hipError_t op_batchnorm_bwd(const OpCtx& c, const void* dy, const void* y, const void* z, const float* mean,
                             const float* rstd, const float* g, void* dz, void* dres, float* dg, float* db,

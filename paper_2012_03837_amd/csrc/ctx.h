@@ -109,6 +109,24 @@ struct lp_ctx : lp_scratch {
   // direct-to-LDS kernel runs 18 % faster than with a k-major operand (ds_read_b128 instead of two
   // transposing 8-byte reads per fragment).
   std::vector<void*> wt;
+  // running statistics of every batch normalisation: for the gain tensor with index i and C channels,
+  // run_off[i] >= 0 and bn_run + run_off[i] holds the running mean, the next C floats the running variance
+  float* bn_run = nullptr;
+  size_t bn_run_elems = 0;
+  std::vector<long> run_off;
+  float bn_momentum = 0.1f;      // 0: keep no running statistics
+  int bn_eval_running = 0;       // lp_eval_loss normalises with the running statistics
+  int bn_mode = 0;               // what the forward pass in flight does: 0 batch only, 1 batch + fold in, 2 running
+  lp::BnRunning bn_tmp;
+  const lp::BnRunning* bn_for(int gain_tensor, int C) {
+    if (bn_mode == 0 || !bn_run || gain_tensor < 0 || gain_tensor >= (int)run_off.size() || run_off[gain_tensor] < 0)
+      return nullptr;
+    bn_tmp.mean = bn_run + run_off[gain_tensor];
+    bn_tmp.var = bn_tmp.mean + C;
+    bn_tmp.momentum = bn_momentum;
+    bn_tmp.use = bn_mode == 2;
+    return &bn_tmp;
+  }
   float* mom = nullptr; float* var = nullptr;
   float* grads = nullptr;
   float* pe = nullptr;

@@ -179,7 +179,8 @@ static int unit_forward(lp_ctx* c, ConvUnit& u, const void* x, const void* res) 
   OpCtx o = c->op();
   DO(op_conv_fwd(o, u.a, x, c->W(u.w), u.z));
   int rows = u.a.N * u.a.P * u.a.Q;
-  DO(op_batchnorm_fwd(o, u.z, c->P32(u.g), c->P32(u.b), res, u.y, u.mean, u.rstd, rows, u.a.O, u.relu));
+  DO(op_batchnorm_fwd(o, u.z, c->P32(u.g), c->P32(u.b), res, u.y, u.mean, u.rstd, rows, u.a.O, u.relu,
+                      c->bn_for(u.g, u.a.O)));
   return LP_OK;
 }
 // dy -> (dz in sZ) -> dw, and dx if asked.  dres (if non-null) receives the ReLU-masked dy.
@@ -290,7 +291,7 @@ int drv_head(lp_ctx* c, int hi, int batch, const int32_t* y, float* loss_out, bo
     hw = side * side;
     rows = batch;
     DO(op_batchnorm_fwd(o, h, c->P32(Hd.t["bn.g"]), c->P32(Hd.t["bn.b"]), nullptr, c->sG, c->hmean, c->hrstd,
-                        batch * hw, in_dim, 1));
+                        batch * hw, in_dim, 1, c->bn_for(Hd.t["bn.g"], in_dim)));
     DO(op_avgpool_fwd(o, c->sG, c->feat, batch, hw, in_dim));
     feat = c->feat;
   } else if (Hd.s.kind == LP_HEAD_LN_LINEAR_CE) {

@@ -337,7 +337,8 @@ __global__ void __launch_bounds__(256) k_bn_partial_v(const bf16_t* __restrict__
 constexpr int kBnFinishGroups = 16;
 __global__ void __launch_bounds__(64 * kBnFinishGroups)
 k_bn_finish_v(const float* __restrict__ partial, int nslab, int C, int rows, const bf16_t* __restrict__ z,
-              float* __restrict__ out0, float* __restrict__ out1, int mode) {
+              float* __restrict__ out0, float* __restrict__ out1, int mode, float* __restrict__ run_mean = nullptr,
+              float* __restrict__ run_var = nullptr, float momentum = 0.f) {
   __shared__ float sh[2][kBnFinishGroups][64];
   const int lc = threadIdx.x & 63, q = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + lc;
@@ -361,8 +362,14 @@ k_bn_finish_v(const float* __restrict__ partial, int nslab, int C, int rows, con
     const float inv = 1.f / (float)rows, m1 = a * inv;
     float var = b * inv - m1 * m1;
     var = var > 0.f ? var : 0.f;
-    out0[j] = (float)z[j] + m1;
+    const float mu = (float)z[j] + m1;
+    out0[j] = mu;
     out1[j] = rsqrtf(var + kBnEpsV);
+    if (run_mean) {   // running statistics take the unbiased batch variance
+      const float unb = rows > 1 ? var * ((float)rows / (float)(rows - 1)) : var;
+      run_mean[j] = (1.f - momentum) * run_mean[j] + momentum * mu;
+      run_var[j] = (1.f - momentum) * run_var[j] + momentum * unb;
+    }
   } else {
     out0[j] = a; out1[j] = b;
   }
@@ -447,14 +454,19 @@ size_t bn_fast_scratch(int rows, int C) {
   return (2 * nslab + 2) * (size_t)C;
 }
 hipError_t bn_fwd_fast(const OpCtx& c, const void* z, const float* g, const float* b, const void* res, void* y,
-                       float* mean, float* rstd, int rows, int C, int relu) {
-  const int slab = bn_slab(rows, C), nslab = (rows + slab - 1) / slab;
-  if ((size_t)2 * nslab * C > c.partial_elems) return hipErrorInvalidValue;
-  const int RL = 256 / (C / 8);
-  const size_t shm = (size_t)2 * RL * C * sizeof(float);
-  k_bn_partial_v<0><<<nslab, 256, shm, c.stream>>>((const bf16_t*)z, nullptr, (const bf16_t*)z, nullptr, nullptr,
-                                                   c.partial, rows, C, slab, 0);
-  k_bn_finish_v<<<(C + 63) / 64, 64 * kBnFinishGroups, 0, c.stream>>>(c.partial, nslab, C, rows, (const bf16_t*)z, mean, rstd, 0);
+                       float* mean, float* rstd, int rows, int C, int relu, const BnRunning* run) {
+  const bool given = run && run->use;   // mean / rstd already hold the statistics to normalise with
+  if (!given) {
+    const int slab = bn_slab(rows, C), nslab = (rows + slab - 1) / slab;
+    if ((size_t)2 * nslab * C > c.partial_elems) return hipErrorInvalidValue;
+    const int RL = 256 / (C / 8);
+    const size_t shm = (size_t)2 * RL * C * sizeof(float);
+    k_bn_partial_v<0><<<nslab, 256, shm, c.stream>>>((const bf16_t*)z, nullptr, (const bf16_t*)z, nullptr, nullptr,
+                                                     c.partial, rows, C, slab, 0);
+    k_bn_finish_v<<<(C + 63) / 64, 64 * kBnFinishGroups, 0, c.stream>>>(
+        c.partial, nslab, C, rows, (const bf16_t*)z, mean, rstd, 0, run ? run->mean : nullptr,
+        run ? run->var : nullptr, run ? run->momentum : 0.f);
+  }
   const size_t nch = (size_t)rows * C / 8;
   k_bn_apply_v<<<blocks_for(nch), 256, 0, c.stream>>>((const bf16_t*)z, g, b, (const bf16_t*)res, (bf16_t*)y, mean, rstd,
                                                      nch, C, relu);

@@ -7,7 +7,7 @@ namespace lp {
 
 bool bn_fast_ok(const OpCtx& c, int rows, int C, const void* a, const void* b, const void* cc, const void* d);
 hipError_t bn_fwd_fast(const OpCtx& c, const void* z, const float* g, const float* b, const void* res, void* y,
-                       float* mean, float* rstd, int rows, int C, int relu);
+                       float* mean, float* rstd, int rows, int C, int relu, const BnRunning* run);
 hipError_t bn_bwd_fast(const OpCtx& c, const void* dy, const void* y, const void* z, const float* mean,
                        const float* rstd, const float* g, void* dz, void* dres, float* dg, float* db, int rows, int C,
                        int relu, int accumulate);
@@ -52,7 +52,10 @@ __global__ void k_bn_partial(const T* a, const T* yrelu, const T* z, const float
 // mode 0: out = sum/rows.  mode 1: out = rsqrt(sum/rows + eps).  mode 2: out = sum.
 // Block = 64 channels x 4 slab groups; group q adds slabs q, q+4, ... in order, then the four group sums
 // are added in order (a fixed tree).
-__global__ void k_bn_finalize(const float* partial, int nslab, int C, int rows, float* out, int mode) {
+// With ``run`` (modes 0 and 1) the result is also folded into a running statistic: the mean as it is, the
+// variance in its unbiased form.
+__global__ void k_bn_finalize(const float* partial, int nslab, int C, int rows, float* out, int mode,
+                              float* run = nullptr, float momentum = 0.f) {
   __shared__ float sh[4][64];
   int lc = threadIdx.x & 63, q = threadIdx.x >> 6;
   int j = blockIdx.x * 64 + lc;
@@ -63,9 +66,21 @@ __global__ void k_bn_finalize(const float* partial, int nslab, int C, int rows, 
   __syncthreads();
   if (q != 0 || j >= C) return;
   a = sh[0][lc] + sh[1][lc] + sh[2][lc] + sh[3][lc];
-  if (mode == 0) out[j] = a / (float)rows;
-  else if (mode == 1) out[j] = rsqrtf(a / (float)rows + kBnEps);
-  else out[j] = a;
+  if (mode == 0) {
+    const float mu = a / (float)rows;
+    out[j] = mu;
+    if (run) run[j] = (1.f - momentum) * run[j] + momentum * mu;
+  } else if (mode == 1) {
+    out[j] = rsqrtf(a / (float)rows + kBnEps);
+    if (run) run[j] = (1.f - momentum) * run[j] + momentum * (a / (float)(rows > 1 ? rows - 1 : 1));
+  } else {
+    out[j] = a;
+  }
+}
+// The statistics an evaluation pass normalises with: the running mean, and 1 / sqrt(running variance + eps).
+__global__ void k_bn_load_running(const float* run_mean, const float* run_var, float* mean, float* rstd, int C) {
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < C) { mean[j] = run_mean[j]; rstd[j] = rsqrtf(run_var[j] + kBnEps); }
 }
 template <typename T>
 __global__ void k_bn_apply(const T* z, const float* g, const float* b, const T* res, T* y, const float* mean,
@@ -106,25 +121,32 @@ static int ew_blocks(size_t n) { size_t b = (n + 255) / 256; return (int)(b < 81
 
 template <typename T>
 static hipError_t bn_fwd_t(const OpCtx& c, const void* z, const float* g, const float* b, const void* res, void* y,
-                           float* mean, float* rstd, int rows, int C, int relu) {
-  int nslab = (rows + kSlabRows - 1) / kSlabRows;
-  if ((size_t)nslab * C > c.partial_elems) return hipErrorInvalidValue;
-  dim3 grid((C + 63) / 64, nslab);
-  k_bn_partial<T, 0><<<grid, 256, 0, c.stream>>>((const T*)z, nullptr, nullptr, nullptr, nullptr, c.partial, rows, C, 0);
-  k_bn_finalize<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, C, rows, mean, 0);
-  k_bn_partial<T, 1><<<grid, 256, 0, c.stream>>>((const T*)z, nullptr, nullptr, mean, nullptr, c.partial, rows, C, 0);
-  k_bn_finalize<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, C, rows, rstd, 1);
+                           float* mean, float* rstd, int rows, int C, int relu, const BnRunning* run) {
+  if (!(run && run->use)) {
+    int nslab = (rows + kSlabRows - 1) / kSlabRows;
+    if ((size_t)nslab * C > c.partial_elems) return hipErrorInvalidValue;
+    dim3 grid((C + 63) / 64, nslab);
+    float* rm = run ? run->mean : nullptr;
+    float* rv = run ? run->var : nullptr;
+    float mom = run ? run->momentum : 0.f;
+    k_bn_partial<T, 0><<<grid, 256, 0, c.stream>>>((const T*)z, nullptr, nullptr, nullptr, nullptr, c.partial, rows, C, 0);
+    k_bn_finalize<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, C, rows, mean, 0, rm, mom);
+    k_bn_partial<T, 1><<<grid, 256, 0, c.stream>>>((const T*)z, nullptr, nullptr, mean, nullptr, c.partial, rows, C, 0);
+    k_bn_finalize<<<(C + 63) / 64, 256, 0, c.stream>>>(c.partial, nslab, C, rows, rstd, 1, rv, mom);
+  }
   size_t n = (size_t)rows * C;
   k_bn_apply<T><<<ew_blocks(n), 256, 0, c.stream>>>((const T*)z, g, b, (const T*)res, (T*)y, mean, rstd, n, C, relu);
   return hipGetLastError();
 }
 hipError_t op_batchnorm_fwd(const OpCtx& c, const void* z, const float* g, const float* b, const void* res, void* y,
-                            float* mean, float* rstd, int rows, int C, int relu) {
+                            float* mean, float* rstd, int rows, int C, int relu, const BnRunning* run) {
   ProfScope prof_(c, KC_BATCHNORM);
   if (rows == 0) return hipSuccess;
-  if (bn_fast_ok(c, rows, C, z, y, res, nullptr)) return bn_fwd_fast(c, z, g, b, res, y, mean, rstd, rows, C, relu);
-  return c.dt == BF16 ? bn_fwd_t<bf16_t>(c, z, g, b, res, y, mean, rstd, rows, C, relu)
-                      : bn_fwd_t<float>(c, z, g, b, res, y, mean, rstd, rows, C, relu);
+  if (run && (!run->mean || !run->var)) return hipErrorInvalidValue;
+  if (run && run->use) k_bn_load_running<<<(C + 255) / 256, 256, 0, c.stream>>>(run->mean, run->var, mean, rstd, C);
+  if (bn_fast_ok(c, rows, C, z, y, res, nullptr)) return bn_fwd_fast(c, z, g, b, res, y, mean, rstd, rows, C, relu, run);
+  return c.dt == BF16 ? bn_fwd_t<bf16_t>(c, z, g, b, res, y, mean, rstd, rows, C, relu, run)
+                      : bn_fwd_t<float>(c, z, g, b, res, y, mean, rstd, rows, C, relu, run);
 }
 
 template <typename T>

@@ -194,6 +194,18 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
   c->lowp = dt == BF16 ? pa.take(c->P * 2) : nullptr;
   c->mom = sp.opt.kind >= LP_OPT_SGDM ? (float*)sa.take(c->P * 4) : nullptr;
   c->var = sp.opt.kind == LP_OPT_ADAM ? (float*)sa.take(c->P * 4) : nullptr;
+  // running mean and variance of every batch normalisation (found by its gain tensor "...bn*.g")
+  c->run_off.assign(c->tensors.size(), -1);
+  c->bn_run_elems = 0;
+  for (size_t i = 0; i < c->tensors.size(); ++i) {
+    const std::string& n = c->tensors[i].name;
+    if (n.size() < 2 || n.compare(n.size() - 2, 2, ".g") != 0) continue;
+    size_t dot = n.rfind('.', n.size() - 3);
+    if (n.compare(dot + 1, 2, "bn") != 0) continue;
+    c->run_off[i] = (long)c->bn_run_elems;
+    c->bn_run_elems += 2 * ((c->tensors[i].numel + 63) & ~(size_t)63);
+  }
+  c->bn_run = c->bn_run_elems ? (float*)sa.take(c->bn_run_elems * 4) : nullptr;
   if (sa.used == 0) sa.take(256);
   c->grads = (float*)wa.take(c->P * 4);
 
@@ -435,6 +447,12 @@ extern "C" int lp_init_blocks(const lp_model_spec* spec, const lp_buffers* buffe
   if (c->mom) CKI(op_fill_f32(o, c->mom, c->P, 0.f));
   if (c->var) CKI(op_fill_f32(o, c->var, c->P, 0.f));
   CKI(op_fill_f32(o, c->grads, c->P, 0.f));
+  for (size_t i = 0; i < c->run_off.size(); ++i)
+    if (c->bn_run && c->run_off[i] >= 0) {   // mean 0, variance 1
+      const size_t C = c->tensors[i].numel;
+      CKI(op_fill_f32(o, c->bn_run + c->run_off[i], C, 0.f));
+      CKI(op_fill_f32(o, c->bn_run + c->run_off[i] + C, C, 1.f));
+    }
   for (size_t i = 0; i < c->tensors.size(); ++i) {
     const Tensor& t = c->tensors[i];
     if (t.init == 0) CKI(op_init_normal(o, c->master + t.off, t.numel, t.std, spec->seed, (uint64_t)i));
@@ -623,6 +641,7 @@ static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* los
   int st = check_call(c, x, y, batch, losses);
   if (st != LP_OK) return st;
   int L = c->spec.n_layers, J = c->spec.n_heads;
+  c->bn_mode = train ? (c->bn_momentum > 0.f ? 1 : 0) : (c->bn_eval_running ? 2 : 0);
   if (train && batch > 0 && c->spec.schedule == LP_SCHED_PIPELINED) return run_pipelined(c, x, y, batch, losses);
   for (int li = 1; li <= L; ++li) c->layers[li].in_override = nullptr;
   if (batch == 0) {
@@ -735,6 +754,16 @@ extern "C" int lp_step_graph(lp_ctx* c, int on) {
   return LP_OK;
 }
 
+extern "C" int lp_bn_running(lp_ctx* c, float momentum, int eval_with_running) {
+  if (!c) return LP_EINVAL;
+  if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
+  if (!(momentum >= 0.f && momentum <= 1.f)) return fail(c, LP_EINVAL, "momentum must lie in [0, 1]");
+  if (momentum != c->bn_momentum) drop_graph(c);   // a captured step has the old weight baked into its launches
+  c->bn_momentum = momentum;
+  c->bn_eval_running = eval_with_running != 0;
+  return LP_OK;
+}
+
 extern "C" int lp_local_step(lp_ctx* c, const void* x, const int32_t* y, int batch, float* losses) {
   if (c && c->ok && c->graph_on) return run_graph(c, x, y, batch, losses);
   return run(c, x, y, batch, losses, true);
@@ -772,6 +801,16 @@ static int resolve(lp_ctx* c, const char* name, Resolved* r) {
     r->numel = 1;
     for (int i = 0; i < r->ndim; ++i) r->numel *= (size_t)r->shape[i];
     r->bytes = r->numel * dtype_size(c->dt);
+    return LP_OK;
+  }
+  if (suffix(".running_mean") || suffix(".running_var")) {
+    const bool is_var = suffix(".running_var");
+    std::string gname = n.substr(0, n.rfind('.')) + ".g";
+    auto gi = c->index.find(gname);
+    if (gi == c->index.end() || !c->bn_run || c->run_off[gi->second] < 0) return fail(c, LP_ENOTFOUND, "no tensor " + n);
+    const Tensor& t = c->tensors[gi->second];
+    r->ptr = c->bn_run + c->run_off[gi->second] + (is_var ? t.numel : 0);
+    r->dtype = F32; r->ndim = 1; r->shape[0] = (int64_t)t.numel; r->numel = t.numel; r->bytes = t.numel * 4;
     return LP_OK;
   }
   float* base = c->master;

@@ -300,6 +300,10 @@ def test_step_graph_replay_bit_identical(lpmod, name, ns):
             ev.append(tr.eval(xd, yd).cpu().numpy().copy())
             torch.cuda.synchronize()
         P = tr.get_params()
+        for k in list(P):       # the running statistics of every batch normalisation travel with the replay too
+            if k.endswith(".g") and k.split(".")[-2].startswith("bn"):
+                P[k[:-1] + "running_mean"] = tr.get(k[:-1] + "running_mean")
+                P[k[:-1] + "running_var"] = tr.get(k[:-1] + "running_var")
         assert lpmod.lp_get_step(tr.ctx) == 6
         outs.append((ls, ev, P))
         tr.close()
@@ -310,4 +314,71 @@ def test_step_graph_replay_bit_identical(lpmod, name, ns):
     tr = lpmod.LocalTrainer(LI.make_config("cfg3_small"))
     with pytest.raises(lpmod.LpError):
         tr.step_graph(True)
+    tr.close()
+
+
+def _bn_prefixes(names):
+    return [k[:-1] for k in names if k.endswith(".g") and k.split(".")[-2].startswith("bn")]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("sched", ["sync", "pipelined"])
+def test_bn_running_statistics_and_evaluation(lpmod, dtype, sched):
+    """Running mean / variance of every batch normalisation (stages and appendix-B.3 heads) after three steps
+    with batches of different sizes, and the losses of an evaluation that normalises with them, against the
+    oracle; momentum 0 freezes them; the default evaluation still uses the batch's own statistics."""
+    cfg = dataclasses.replace(LI.make_config("cfg2_small", head="bn_pool_linear_ce"), dtype=dtype)
+    tol = tol_for(cfg)
+    stored = stored_for(cfg)
+    tr = lpmod.LocalTrainer(cfg, n_streams=2, schedule=sched)
+    P0 = generic_params(cfg)
+    tr.set_params(P0)
+    pres = _bn_prefixes(P0)
+    assert pres
+    for pre in pres:        # start: mean 0, variance 1
+        assert not np.any(tr.get(pre + "running_mean"))
+        np.testing.assert_array_equal(tr.get(pre + "running_var"), np.ones_like(P0[pre + "g"]))
+    tr.bn_running(0.3, eval_with_running=True)
+    P = {k: v.astype(np.float64) for k, v in P0.items()}
+    st, pipe = oracle.new_state(cfg, P), oracle.new_pipeline(cfg)
+    run = oracle.BatchNormRunning(0.3)
+    for step, b in enumerate([cfg.batch, cfg.batch - 1, cfg.batch]):
+        x, y = data_for(cfg, step, batch=b)
+        xd, yd = tr.stage(x, y)
+        tr.step(xd, yd)
+        if sched == "sync":
+            _, P, _ = oracle.local_step(cfg, P, st, x, y, stored=stored, bn=run)
+        else:
+            _, P = oracle.pipelined_step(cfg, P, st, pipe, x, y, stored=stored, bn=run)
+        if dtype == "bf16":     # keep the two weight trajectories together: only the statistics are under test
+            tr.set_params({k: v.astype(np.float32) for k, v in P.items()})
+            P = {k: v.astype(np.float32).astype(np.float64) for k, v in P.items()}
+    for pre in pres:
+        if pre not in run.mean:      # a block the pipeline has not reached yet
+            assert not np.any(tr.get(pre + "running_mean")), pre
+            continue
+        assert relerr(tr.get(pre + "running_mean"), run.mean[pre]) <= tol, (pre, "mean")
+        assert relerr(tr.get(pre + "running_var"), run.var[pre]) <= tol, (pre, "var")
+    x, y = data_for(cfg, 7, batch=3)
+    xd, yd = tr.stage(x, y)
+    got = tr.eval(xd, yd).cpu().numpy().copy()
+    ref = oracle.eval_loss(cfg, P, x, y, stored=stored, bn=run)
+    for j in range(len(ref)):
+        assert abs(got[j] - ref[j]) <= tol * abs(ref[j]), (j, got[j], ref[j])
+    # evaluation changed nothing; momentum 0 freezes the statistics; batch-statistics evaluation is still there
+    snap = {pre: (tr.get(pre + "running_mean"), tr.get(pre + "running_var")) for pre in pres}
+    tr.bn_running(0.0, eval_with_running=False)
+    got_batch = tr.eval(xd, yd).cpu().numpy().copy()
+    ref_batch = oracle.eval_loss(cfg, P, x, y, stored=stored)
+    for j in range(len(ref)):
+        assert abs(got_batch[j] - ref_batch[j]) <= tol * abs(ref_batch[j]), (j, got_batch[j], ref_batch[j])
+    assert np.any(got_batch != got)
+    tr.step(xd, yd)
+    for pre in pres:
+        np.testing.assert_array_equal(tr.get(pre + "running_mean"), snap[pre][0])
+        np.testing.assert_array_equal(tr.get(pre + "running_var"), snap[pre][1])
+    with pytest.raises(lpmod.LpError):
+        tr.bn_running(1.5)
+    with pytest.raises(lpmod.LpError):
+        tr.get("L1.ln1.running_mean")
     tr.close()
