@@ -79,16 +79,34 @@ __device__ __forceinline__ void store_tile(const TileRegs& t, bf16_t (*dst)[ALD]
   *reinterpret_cast<bf16x8*>(&dst[r][ch + 8]) = t.v1;
 }
 
+// Work order.  The grid is one-dimensional: block L takes sequence block L / (B*H) (counted from the heavy end)
+// of head-and-batch index L % (B*H).  With causal masking the work of a 128-row block grows with its position
+// (shrinks, for the key blocks of dK/dV), and workgroups go to the eight XCDs round-robin by their linear
+// index and to compute units as slots free up: so the heaviest blocks start first and the light ones fill the
+// gaps, every XCD gets the same mix when B*H is a multiple of 8, and all blocks of one head and batch entry
+// run on one XCD, whose L2 then serves their shared K and V (or Q and dO) tiles.
+struct AttnBlock { int x, h, b; };
+__device__ __forceinline__ AttnBlock attn_block(int H, int BH, int nblk, bool heavy_last) {
+  const int cls = blockIdx.x / BH, bh = blockIdx.x % BH;
+  AttnBlock a;
+  a.x = heavy_last ? nblk - 1 - cls : cls;
+  a.h = bh % H;
+  a.b = bh / H;
+  return a;
+}
+
 // ================================================================================= forward
 __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
-                                                       float* __restrict__ lse, int S, int H, int causal) {
+                                                       float* __restrict__ lse, int S, int H, int BH, int causal) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[64][ALD];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[64][ALD];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, hf = lane >> 5;
-  const int h = blockIdx.y, b = blockIdx.z, d = H * 64;
+  const AttnBlock ab = attn_block(H, BH, (S + 127) / 128, causal != 0);
+  const int bx = ab.x;
+  const int h = ab.h, b = ab.b, d = H * 64;
   const size_t ld = (size_t)3 * d;
   const bf16_t* base = qkv + (size_t)b * S * ld;
-  const int q0 = blockIdx.x * 128 + wave * 32, qi = q0 + n;
+  const int q0 = bx * 128 + wave * 32, qi = q0 + n;
   bf16x8 qf[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk)
@@ -97,7 +115,7 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict_
   f32x16 oacc[2];
   zero16(oacc[0]); zero16(oacc[1]);
   const float c = 0.125f * kLog2e;
-  int q_hi = blockIdx.x * 128 + 127;
+  int q_hi = bx * 128 + 127;
   if (q_hi > S - 1) q_hi = S - 1;
   const int n_tiles = causal ? q_hi / 64 + 1 : (S + 63) / 64;
   TileRegs kr = load_tile(base + d + h * 64, ld, 0, S), vr = load_tile(base + 2 * d + h * 64, ld, 0, S);
@@ -193,17 +211,19 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict_
 }
 
 // ================================================================================= backward: dQ
-__global__ void __launch_bounds__(256) k_attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
+__global__ void __launch_bounds__(256, 2) k_attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
                                                           const float* __restrict__ lse,
                                                           const bf16_t* __restrict__ dout, bf16_t* __restrict__ dqkv,
-                                                          float* __restrict__ delta, int S, int H, int causal) {
+                                                          float* __restrict__ delta, int S, int H, int BH, int causal) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[64][ALD];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[64][ALD];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, hf = lane >> 5;
-  const int h = blockIdx.y, b = blockIdx.z, d = H * 64;
+  const AttnBlock ab = attn_block(H, BH, (S + 127) / 128, causal != 0);
+  const int bx = ab.x;
+  const int h = ab.h, b = ab.b, d = H * 64;
   const size_t ld = (size_t)3 * d;
   const bf16_t* base = qkv + (size_t)b * S * ld;
-  const int q0 = blockIdx.x * 128 + wave * 32, qi = q0 + n;
+  const int q0 = bx * 128 + wave * 32, qi = q0 + n;
   bf16x8 qf[4], dof[4];
   float D = 0.f, lse2 = 0.f;
 #pragma unroll
@@ -228,7 +248,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd_dq_mfma(const bf16_t* __restri
   f32x16 dqa[2];
   zero16(dqa[0]); zero16(dqa[1]);
   const float scale = 0.125f, c = 0.125f * kLog2e;
-  int q_hi = blockIdx.x * 128 + 127;
+  int q_hi = bx * 128 + 127;
   if (q_hi > S - 1) q_hi = S - 1;
   const int n_tiles = causal ? q_hi / 64 + 1 : (S + 63) / 64;
   TileRegs kr = load_tile(base + d + h * 64, ld, 0, S), vr = load_tile(base + 2 * d + h * 64, ld, 0, S);
@@ -304,17 +324,19 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dkv_mfma(const bf16_t* __re
                                                            const float* __restrict__ lse,
                                                            const float* __restrict__ delta,
                                                            const bf16_t* __restrict__ dout,
-                                                           bf16_t* __restrict__ dqkv, int S, int H, int causal) {
+                                                           bf16_t* __restrict__ dqkv, int S, int H, int BH, int causal) {
   __shared__ __attribute__((aligned(16))) bf16_t Qs[64][ALD];
   __shared__ __attribute__((aligned(16))) bf16_t dOs[64][ALD];
   __shared__ __attribute__((aligned(16))) float lse2s[64];
   __shared__ __attribute__((aligned(16))) float deltas[64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, hf = lane >> 5;
-  const int h = blockIdx.y, b = blockIdx.z, d = H * 64;
+  const AttnBlock ab = attn_block(H, BH, (S + 127) / 128, false);
+  const int bx = ab.x;
+  const int h = ab.h, b = ab.b, d = H * 64;
   const size_t ld = (size_t)3 * d;
   const bf16_t* base = qkv + (size_t)b * S * ld;
   const bf16_t* dob = dout + (size_t)b * S * d;
-  const int k0w = blockIdx.x * 128 + wave * 32, kj = k0w + n;
+  const int k0w = bx * 128 + wave * 32, kj = k0w + n;
   bf16x8 kf[4], vf[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
@@ -329,7 +351,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dkv_mfma(const bf16_t* __re
   f32x16 dka[2], dva[2];
   zero16(dka[0]); zero16(dka[1]); zero16(dva[0]); zero16(dva[1]);
   const float scale = 0.125f, c = 0.125f * kLog2e;
-  const int t_begin = causal ? (blockIdx.x * 128) / 64 : 0;
+  const int t_begin = causal ? (bx * 128) / 64 : 0;
   const int t_end = (S + 63) / 64;
   TileRegs qr = load_tile(base + h * 64, ld, t_begin * 64, S), dor = load_tile(dob + h * 64, (size_t)d, t_begin * 64, S);
   for (int it = t_begin; it < t_end; ++it) {
@@ -409,18 +431,18 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dkv_mfma(const bf16_t* __re
 
 hipError_t attn_fwd_mfma(const OpCtx& c, const void* qkv, void* o, float* lse, int B, int S, int H, int causal) {
   if (B * S == 0) return hipSuccess;
-  dim3 grid((S + 127) / 128, H, B);
-  k_attn_fwd_mfma<<<grid, 256, 0, c.stream>>>((const bf16_t*)qkv, (bf16_t*)o, lse, S, H, causal);
+  const int grid = ((S + 127) / 128) * H * B;
+  k_attn_fwd_mfma<<<grid, 256, 0, c.stream>>>((const bf16_t*)qkv, (bf16_t*)o, lse, S, H, H * B, causal);
   return hipGetLastError();
 }
 hipError_t attn_bwd_mfma(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout,
                          void* dqkv, float* delta, int B, int S, int H, int causal) {
   if (B * S == 0) return hipSuccess;
-  dim3 grid((S + 127) / 128, H, B);
+  const int grid = ((S + 127) / 128) * H * B;
   k_attn_bwd_dq_mfma<<<grid, 256, 0, c.stream>>>((const bf16_t*)qkv, (const bf16_t*)o, lse, (const bf16_t*)dout,
-                                                 (bf16_t*)dqkv, delta, S, H, causal);
+                                                 (bf16_t*)dqkv, delta, S, H, H * B, causal);
   k_attn_bwd_dkv_mfma<<<grid, 256, 0, c.stream>>>((const bf16_t*)qkv, lse, delta, (const bf16_t*)dout, (bf16_t*)dqkv,
-                                                  S, H, causal);
+                                                  S, H, H * B, causal);
   return hipGetLastError();
 }
 
