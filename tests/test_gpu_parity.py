@@ -365,6 +365,19 @@ def test_bn_running_statistics_and_evaluation(lpmod, dtype, sched):
     ref = oracle.eval_loss(cfg, P, x, y, stored=stored, bn=run)
     for j in range(len(ref)):
         assert abs(got[j] - ref[j]) <= tol * abs(ref[j]), (j, got[j], ref[j])
+    # statistics written through the named tensors are the ones the next evaluation uses
+    fake = oracle.BatchNormRunning(0.3)
+    rng = np.random.default_rng(5)
+    for pre in pres:
+        C = P0[pre + "g"].shape[0]
+        fake.mean[pre] = rng.normal(0.0, 0.5, C).astype(np.float32).astype(np.float64)
+        fake.var[pre] = rng.uniform(0.5, 2.0, C).astype(np.float32).astype(np.float64)
+        tr.set(pre + "running_mean", fake.mean[pre].astype(np.float32))
+        tr.set(pre + "running_var", fake.var[pre].astype(np.float32))
+    got_fake = tr.eval(xd, yd).cpu().numpy().copy()
+    ref_fake = oracle.eval_loss(cfg, P, x, y, stored=stored, bn=fake)
+    for j in range(len(ref)):
+        assert abs(got_fake[j] - ref_fake[j]) <= tol * abs(ref_fake[j]), (j, got_fake[j], ref_fake[j])
     # evaluation changed nothing; momentum 0 freezes the statistics; batch-statistics evaluation is still there
     snap = {pre: (tr.get(pre + "running_mean"), tr.get(pre + "running_var")) for pre in pres}
     tr.bn_running(0.0, eval_with_running=False)
