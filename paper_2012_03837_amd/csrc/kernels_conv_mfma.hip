@@ -155,6 +155,22 @@ __global__ void k_conv_splitk_reduce(const float* __restrict__ ws, float* __rest
   out[idx] = accumulate ? out[idx] + a : a;
 }
 
+// The same sum for a compute-dtype output: 8 consecutive columns per thread, through the epilogue.
+__global__ void k_conv_splitk_reduce8(const float* __restrict__ ws, Epilogue e, int M, int N, int splits) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int n8 = N >> 3;
+  if (idx >= (size_t)M * n8) return;
+  const int m = (int)(idx / n8), n = (int)(idx % n8) * 8;
+  float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < splits; ++s) {
+    const float* p = ws + ((size_t)s * M + m) * N + n;
+    f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) { v[x] += a[x]; v[4 + x] += b[x]; }
+  }
+  epilogue8(e, m, n, v);
+}
+
 Epilogue plain_epilogue(void* C, int64_t ldc, int c_f32, int accumulate) {
   GemmArgs g; g.C = C; g.ldc = ldc; g.c_f32 = c_f32; g.accumulate = accumulate;
   return make_epilogue(g);
@@ -174,6 +190,28 @@ hipError_t launch(const OpCtx& c, LA A, LB B, const Epilogue& e, int M, int N, i
 
 bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+// Forward and data-gradient products of the late stages have few output tiles and a long reduction (4 x 4
+// images with 512 channels: 128 tiles, K = 4608): a block alone on its CU cannot hide the gather latency, and
+// half the CUs get nothing.  Such products are cut along k into enough pieces for two to three blocks per CU;
+// the fp32 partial sums (M x N per piece) are added in piece order.
+template <class LA, class LB>
+hipError_t launch_cut(const OpCtx& c, LA A, LB B, void* out, int M, int N, int K) {
+  const int tiles = ((M + 127) / 128) * ((N + BN - 1) / BN);
+  int splits = 1;
+  if (c.splitk_ws && tiles < 200 && K >= 1024) {
+    splits = (512 + tiles - 1) / tiles;
+    if (splits > K / 512) splits = K / 512;
+    while (splits > 1 && (size_t)splits * M * N > c.splitk_elems) --splits;
+    if (splits < 1) splits = 1;
+  }
+  const Epilogue e = plain_epilogue(out, N, 0, 0);
+  hipError_t err = launch(c, A, B, e, M, N, K, splits);
+  if (err != hipSuccess || splits == 1) return err;
+  const size_t work = (size_t)M * (N / 8);
+  k_conv_splitk_reduce8<<<(unsigned)((work + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, e, M, N, splits);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 bool conv_mfma_ok(const OpCtx& c, const ConvArgs& a, const void* p0, const void* p1, const void* p2) {
@@ -184,13 +222,13 @@ hipError_t conv_fwd_mfma(const OpCtx& c, const ConvArgs& a, const void* x, const
   const int M = a.N * a.P * a.Q, K = a.R * a.S * a.C;
   ConvFwdA A{(const bf16_t*)x, a, M};
   PlainLoader<true> B{Operand{(const bf16_t*)w, K, a.O}};
-  return launch(c, A, B, plain_epilogue(out, a.O, 0, 0), M, a.O, K, 1);
+  return launch_cut(c, A, B, out, M, a.O, K);
 }
 hipError_t conv_bwd_data_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx) {
   const int M = a.N * a.H * a.W, K = a.R * a.S * a.O;
   ConvBwdA A{(const bf16_t*)dout, a, M};
   ConvFilterT B{(const bf16_t*)w, a};
-  return launch(c, A, B, plain_epilogue(dx, a.C, 0, 0), M, a.C, K, 1);
+  return launch_cut(c, A, B, dx, M, a.C, K);
 }
 hipError_t conv_bwd_weight_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                                 int accumulate) {

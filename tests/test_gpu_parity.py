@@ -395,3 +395,14 @@ def test_bn_running_statistics_and_evaluation(lpmod, dtype, sched):
     with pytest.raises(lpmod.LpError):
         tr.get("L1.ln1.running_mean")
     tr.close()
+
+
+def test_convolutions_cut_along_k_match_oracle(lpmod):
+    """Few output tiles and a long reduction (4 x 4 images, 128 channels, K = 1152): the forward and data-gradient
+    convolutions run cut along k with fp32 partial sums added in a fixed order; same bar as every bf16 step."""
+    cfg = LI.configs.resnet_config("t_cut", channels=(128,), in_hw=4, in_ch=3, n_classes=5, batch=8,
+                                   n_basic_blocks=1, dtype="bf16")
+    tr = lpmod.LocalTrainer(cfg, n_streams=1)
+    x, y = data_for(cfg)
+    compare_step(tr, cfg, generic_params(cfg), x, y, label="cut conv", stored=stored_for(cfg))
+    tr.close()
