@@ -53,15 +53,26 @@ struct ConvPatchByCol {        // (j=(r,s,c), k=m) -> input patch element: same 
   __device__ __forceinline__ float operator()(int j, int m) const { return g(m, j); }
 };
 
-constexpr int PBM = 64, PBN = 64, PBK = 16;
+constexpr int PBM = 64, PBN = 64, PBK = 32;
+
+// Which index of an operand is contiguous in memory: a tile is fetched with that index varying fastest
+// over the threads, so that a wavefront's loads fall into as few cache lines as possible.
+template <typename T>
+__device__ __forceinline__ bool k_is_contiguous(const PlainOperand<T>& o) { return o.kc != 0; }
+template <typename O>
+__device__ __forceinline__ bool k_is_contiguous(const O&) { return true; }
 
 // gridDim.z > 1: split-K.  Block z reduces k in [z*kper, (z+1)*kper) and writes its raw fp32 tile to
 // ws[z][M][N]; k_plain_splitk_reduce then adds the slices in order.
+// The next k-tile is fetched into registers before the current one is multiplied, so the memory latency of a
+// tile (which is what a small product costs: a few blocks, nothing else to switch to) overlaps the FMAs.
 template <typename T, typename OA, typename OB>
 __global__ void __launch_bounds__(256) k_gemm_plain(OA A, OB B, Epilogue e, int M, int N, int K, int kper = 0,
                                                     float* ws = nullptr) {
   __shared__ float As[PBK][PBM + 1];
   __shared__ float Bs[PBK][PBN + 1];
+  constexpr int PER = PBM * PBK / 256;
+  static_assert(PBM == PBN && PBM * PBK % 256 == 0, "tile fetch assumes square tiles and whole passes");
   int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
   int m0 = blockIdx.y * PBM, n0 = blockIdx.x * PBN;
   float acc[4][4] = {};
@@ -70,15 +81,33 @@ __global__ void __launch_bounds__(256) k_gemm_plain(OA A, OB B, Epilogue e, int 
     kbeg = blockIdx.z * kper;
     K = kbeg + kper < K ? kbeg + kper : K;
   }
-  for (int k0 = kbeg; k0 < K; k0 += PBK) {
-    for (int i = threadIdx.x; i < PBM * PBK; i += 256) {
-      int kk = i % PBK, mm = i / PBK;
-      int m = m0 + mm, k = k0 + kk;
-      As[kk][mm] = (m < M && k < K) ? A(m, k) : 0.f;
-      int n = n0 + mm;
-      Bs[kk][mm] = (n < N && k < K) ? B(n, k) : 0.f;
+  const bool a_kfast = k_is_contiguous(A), b_kfast = k_is_contiguous(B);
+  float ra[PER], rb[PER];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int i = threadIdx.x + 256 * j;
+      const int ka = a_kfast ? i % PBK : i / PBM, ma = a_kfast ? i / PBK : i % PBM;
+      const int kb = b_kfast ? i % PBK : i / PBN, nb = b_kfast ? i / PBK : i % PBN;
+      ra[j] = (m0 + ma < M && k0 + ka < K) ? A(m0 + ma, k0 + ka) : 0.f;
+      rb[j] = (n0 + nb < N && k0 + kb < K) ? B(n0 + nb, k0 + kb) : 0.f;
     }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int i = threadIdx.x + 256 * j;
+      const int ka = a_kfast ? i % PBK : i / PBM, ma = a_kfast ? i / PBK : i % PBM;
+      const int kb = b_kfast ? i % PBK : i / PBN, nb = b_kfast ? i / PBK : i % PBN;
+      As[ka][ma] = ra[j];
+      Bs[kb][nb] = rb[j];
+    }
+  };
+  if (kbeg < K) fetch(kbeg);
+  for (int k0 = kbeg; k0 < K; k0 += PBK) {
+    stage();
     __syncthreads();
+    if (k0 + PBK < K) fetch(k0 + PBK);
 #pragma unroll
     for (int kk = 0; kk < PBK; ++kk) {
       float a[4], b[4];
