@@ -205,6 +205,9 @@ def main():
     cfg = LI.make_config(args.config)
     tr = lp.LocalTrainer(cfg, n_streams=args.streams, schedule=args.schedule)
     K, W = args.steps, args.warmup
+    if args.schedule == "pipelined":
+        # steady state only: block j first runs in call j, so the warm-up has to cover the ramp-up of the pipeline
+        W = max(W, len(cfg.heads) + 2)
     n_stage = min(K + W, 8)
     staged = [tr.stage(*LI.make_batch(cfg, i)) for i in range(n_stage)]
     torch.cuda.synchronize()
