@@ -96,4 +96,19 @@ def test_null_context_calls_fail_cleanly():
     assert L.lp_eval_loss(None, None, None, 1, None) == B.LP_EINVAL
     assert L.lp_get_tensor(None, b"L1.w1", None, 0) == B.LP_EINVAL
     assert L.lp_num_params(None) == 0
+    assert L.lp_step_graph(None, 1) == B.LP_EINVAL
+    assert L.lp_bn_running(None, 0.1, 0) == B.LP_EINVAL
     L.lp_destroy(None)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box has one GPU: asking the bench for more ends with a message, before anything touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "--gpus must be 1" in r.stderr
+    assert not r.stdout.strip()
