@@ -125,23 +125,29 @@ def cpu_baseline(cfg, budget_s=30.0):
     x, y = LI.make_batch(cfg, 0)
     kind = cfg.layers[0].kind
     if kind == "decoder":
-        # one block: head 1 with its window, input = the token ids (window starts at layer 0)
-        hi = 1
-        s, e = LI.head_windows(cfg)[0]
-        names = [k for k in P if k.startswith("H1.") or (k[0] == "L" and s < int(k.split(".")[0][1:]) <= e)]
-        st = oracle.new_state(cfg, {k: P[k] for k in names}, np.float32)
-        t0 = time.perf_counter()
-        loss, grads, _ = oracle.block_gradients(cfg, P, hi, x, y, dtype=np.float32)
-        for k in grads:
-            OL.optimizer_update(cfg.opt, P[k], grads[k].astype(np.float32), st, k, 1)
-        dt = time.perf_counter() - t0
-        total_flops = gemm_flops_per_step(cfg) + sum(attention_flops_per_step(cfg))
+        # the first blocks of the step, one after another (a block's input is the stored output of the layer its
+        # window starts after), until about ten seconds of CPU work are spent
         import dataclasses
-        sub = dataclasses.replace(cfg, layers=cfg.layers[:e], heads=cfg.heads[:1])
-        sample_flops = gemm_flops_per_step(sub) + sum(attention_flops_per_step(sub))
+        wins = LI.head_windows(cfg)
+        outs, done, dt, sample_flops = {0: x}, [], 0.0, 0.0
+        for hi, (s, e) in enumerate(wins, start=1):
+            if s not in outs or (done and dt > 10.0):
+                break
+            names = [k for k in P if k.startswith(f"H{hi}.") or (k[0] == "L" and s < int(k.split(".")[0][1:]) <= e)]
+            st = oracle.new_state(cfg, {k: P[k] for k in names}, np.float32)
+            t0 = time.perf_counter()
+            loss, grads, out = oracle.block_gradients(cfg, P, hi, outs[s], y, dtype=np.float32)
+            for k in grads:
+                OL.optimizer_update(cfg.opt, P[k], grads[k].astype(np.float32), st, k, 1)
+            dt += time.perf_counter() - t0
+            outs[e] = out
+            done.append(hi)
+            sub = dataclasses.replace(cfg, layers=cfg.layers[s:e], heads=(dataclasses.replace(cfg.heads[hi - 1], after_layer=e - s, window=e - s),))
+            sample_flops += gemm_flops_per_step(sub) + sum(attention_flops_per_step(sub))
+        total_flops = gemm_flops_per_step(cfg) + sum(attention_flops_per_step(cfg))
         scale = total_flops / sample_flops
         step_s = dt * scale
-        sample = (f"block 1 of {len(cfg.heads)} (layers {s + 1}..{e} + aux head + optimizer), float32, "
+        sample = (f"blocks {done[0]}..{done[-1]} of {len(cfg.heads)} (their layers + aux heads + optimizer), float32, "
                   f"{dt:.1f} s, scaled by the step's FLOP ratio x{scale:.2f}")
     else:
         st = oracle.new_state(cfg, P, np.float32)
