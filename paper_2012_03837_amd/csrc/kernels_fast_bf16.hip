@@ -333,12 +333,14 @@ __global__ void __launch_bounds__(256) k_bn_partial_v(const bf16_t* __restrict__
 }
 // Adds the slab partials in order (64 channels x 16 slab groups per block: group q adds slabs q, q+16, ...
 // with two independent pairs of loads in flight, then the group sums are added in order) and finishes.
-// mode 0: forward statistics (needs the pivots from row 0 of z); mode 1: plain sums into sums[0..C), sums[C..2C).
+// mode 0: forward statistics (needs the pivots from row 0 of z); with aux0 / aux1 the batch mean and unbiased
+// variance are also folded into those running statistics with weight auxf.  mode 1: plain sums into out0, out1;
+// with aux0 / aux1 they are also written (auxf == 0) or added (auxf != 0) there: the shift and gain gradients.
 constexpr int kBnFinishGroups = 16;
 __global__ void __launch_bounds__(64 * kBnFinishGroups)
 k_bn_finish_v(const float* __restrict__ partial, int nslab, int C, int rows, const bf16_t* __restrict__ z,
-              float* __restrict__ out0, float* __restrict__ out1, int mode, float* __restrict__ run_mean = nullptr,
-              float* __restrict__ run_var = nullptr, float momentum = 0.f) {
+              float* __restrict__ out0, float* __restrict__ out1, int mode, float* __restrict__ aux0 = nullptr,
+              float* __restrict__ aux1 = nullptr, float auxf = 0.f) {
   __shared__ float sh[2][kBnFinishGroups][64];
   const int lc = threadIdx.x & 63, q = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + lc;
@@ -365,13 +367,17 @@ k_bn_finish_v(const float* __restrict__ partial, int nslab, int C, int rows, con
     const float mu = (float)z[j] + m1;
     out0[j] = mu;
     out1[j] = rsqrtf(var + kBnEpsV);
-    if (run_mean) {   // running statistics take the unbiased batch variance
+    if (aux0) {   // running statistics take the unbiased batch variance
       const float unb = rows > 1 ? var * ((float)rows / (float)(rows - 1)) : var;
-      run_mean[j] = (1.f - momentum) * run_mean[j] + momentum * mu;
-      run_var[j] = (1.f - momentum) * run_var[j] + momentum * unb;
+      aux0[j] = (1.f - auxf) * aux0[j] + auxf * mu;
+      aux1[j] = (1.f - auxf) * aux1[j] + auxf * unb;
     }
   } else {
     out0[j] = a; out1[j] = b;
+    if (aux0) {
+      aux0[j] = auxf != 0.f ? aux0[j] + a : a;
+      aux1[j] = auxf != 0.f ? aux1[j] + b : b;
+    }
   }
 }
 __global__ void __launch_bounds__(256) k_bn_apply_v(const bf16_t* __restrict__ z, const float* __restrict__ g,
@@ -426,12 +432,6 @@ __global__ void __launch_bounds__(256) k_bn_bwd_apply_v(const bf16_t* __restrict
     if (dres) store8(dres + i * 8, d);
   }
 }
-__global__ void k_accum2(const float* src, float* dst0, float* dst1, int C, int accumulate) {
-  int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= C) return;
-  dst0[j] = accumulate ? dst0[j] + src[j] : src[j];
-  dst1[j] = accumulate ? dst1[j] + src[C + j] : src[C + j];
-}
 
 int bn_slab(int rows, int C) {
   int RL = 256 / (C / 8);
@@ -482,11 +482,11 @@ hipError_t bn_bwd_fast(const OpCtx& c, const void* dy, const void* y, const void
   const size_t shm = (size_t)2 * RL * C * sizeof(float);
   k_bn_partial_v<1><<<nslab, 256, shm, c.stream>>>((const bf16_t*)dy, (const bf16_t*)y, (const bf16_t*)z, mean, rstd,
                                                    c.partial, rows, C, slab, relu);
-  k_bn_finish_v<<<(C + 63) / 64, 64 * kBnFinishGroups, 0, c.stream>>>(c.partial, nslab, C, rows, nullptr, sums, sums + C, 1);
+  k_bn_finish_v<<<(C + 63) / 64, 64 * kBnFinishGroups, 0, c.stream>>>(c.partial, nslab, C, rows, nullptr, sums, sums + C, 1,
+                                                                      db, dg, accumulate ? 1.f : 0.f);
   const size_t nch = (size_t)rows * C / 8;
   k_bn_bwd_apply_v<<<blocks_for(nch), 256, 0, c.stream>>>((const bf16_t*)dy, (const bf16_t*)y, (const bf16_t*)z, mean,
                                                          rstd, g, sums, (bf16_t*)dz, (bf16_t*)dres, nch, C, rows, relu);
-  k_accum2<<<(C + 255) / 256, 256, 0, c.stream>>>(sums, db, dg, C, accumulate);
   return hipGetLastError();
 }
 
