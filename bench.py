@@ -172,8 +172,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg3", help="cfg1..cfg5")
     ap.add_argument("--streams", type=int, default=-1,
-                    help="side streams for the heads' chains (0 = one stream); default: 3, and one per stage (at most 4) "
-                         "for the ResNet configurations, whose four chains are short enough to run side by side")
+                    help="side streams for the heads' chains (0 = one stream); default: 2 for the decoders, 3 for the "
+                         "residual MLP, and one per stage (at most 4) for the ResNet configurations, whose four "
+                         "chains are short enough to run side by side (each the fastest measured)")
     ap.add_argument("--schedule", default="sync", choices=["sync", "pipelined"],
                     help="sync: every block works on the call's minibatch (the headline metric); pipelined: block j "
                          "works on block j-1's output of the previous call (steady state after warm-up)")
@@ -212,7 +213,8 @@ def main():
         return
     cfg = LI.make_config(args.config)
     if args.streams < 0:
-        args.streams = min(4, len(cfg.heads)) if cfg.layers[0].kind == "resnet_stage" else 3
+        kind0 = cfg.layers[0].kind
+        args.streams = min(4, len(cfg.heads)) if kind0 == "resnet_stage" else (2 if kind0 == "decoder" else 3)
     tr = lp.LocalTrainer(cfg, n_streams=args.streams, schedule=args.schedule)
     K, W = args.steps, args.warmup
     if args.schedule == "pipelined":
