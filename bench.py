@@ -213,8 +213,7 @@ def main():
         return
     cfg = LI.make_config(args.config)
     if args.streams < 0:
-        kind0 = cfg.layers[0].kind
-        args.streams = min(4, len(cfg.heads)) if kind0 == "resnet_stage" else (2 if kind0 == "decoder" else 3)
+        args.streams = lp.default_side_streams(cfg)
     tr = lp.LocalTrainer(cfg, n_streams=args.streams, schedule=args.schedule)
     K, W = args.steps, args.warmup
     if args.schedule == "pipelined":

@@ -266,6 +266,16 @@ def lp_destroy(ctx: int) -> None:
     lib().lp_destroy(ctx)
 
 
+def default_side_streams(cfg) -> int:
+    """Side streams for the heads' chains that the benchmark times each workload with (the fastest measured on
+    one MI355X): two for the decoders, three for the residual MLP, one per stage (at most four) for the ResNets,
+    whose chains are short enough to run side by side."""
+    kind0 = cfg.layers[0].kind
+    if kind0 == "resnet_stage":
+        return min(4, len(cfg.heads))
+    return 2 if kind0 == "decoder" else 3
+
+
 class LocalTrainer:
     """Owns the three device buffers (torch tensors) and a context over them."""
 

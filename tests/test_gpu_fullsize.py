@@ -66,7 +66,7 @@ def check_block(lpmod, tr, cfg, hi, x, y, P_before, tol=2e-2):
 def run_transformer(lpmod, name, sample_heads, single_contribution_only=True):
     cfg = LI.make_config(name)
     print(f"[case] {name} full size", flush=True)
-    tr = lpmod.LocalTrainer(cfg, n_streams=3)   # the launch configuration bench.py times
+    tr = lpmod.LocalTrainer(cfg, n_streams=lpmod.default_side_streams(cfg))   # the launch configuration bench.py times
     x, y = data_for(cfg)
     xd, yd = tr.stage(x, y)
     wanted = set()
@@ -94,7 +94,7 @@ def test_cfg4_full_last_block(lpmod):
     head 11's contribution and is covered by the scaled-down overlap tests."""
     cfg = LI.make_config("cfg4")
     print("[case] cfg4 full size", flush=True)
-    tr = lpmod.LocalTrainer(cfg, n_streams=3)   # the launch configuration bench.py times
+    tr = lpmod.LocalTrainer(cfg, n_streams=lpmod.default_side_streams(cfg))   # the launch configuration bench.py times
     x, y = data_for(cfg)
     xd, yd = tr.stage(x, y)
     hi = 12
@@ -135,7 +135,7 @@ def test_cfg2_full_step(lpmod):
     stage is reproduced to well under a percent."""
     cfg = LI.make_config("cfg2")
     print("[case] cfg2 full size", flush=True)
-    tr = lpmod.LocalTrainer(cfg, n_streams=3)   # the launch configuration bench.py times
+    tr = lpmod.LocalTrainer(cfg, n_streams=lpmod.default_side_streams(cfg))   # the launch configuration bench.py times
     P0 = LI.init_params(cfg)
     tr.set_params(P0)
     x, y = data_for(cfg)
