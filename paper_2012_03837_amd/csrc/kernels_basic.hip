@@ -398,15 +398,17 @@ hipError_t op_colsum(const OpCtx& c, const void* dy, int64_t ld, float* out, int
   int nslab = (rows + kColsumRows - 1) / kColsumRows;
   if (nslab < 1) nslab = 1;
   if ((size_t)nslab * n > c.partial_elems) return hipErrorInvalidValue;
+  // one slab of rows and nothing to add to: the slab's sums are the result, no second kernel
+  const bool direct = nslab == 1 && !accumulate;
+  float* part = direct ? out : c.partial;
   if (c.dt == BF16 && n % 8 == 0 && ld % 8 == 0 && ((uintptr_t)dy & 15) == 0) {
-    k_colsum_partial_v<<<dim3((n + 127) / 128, nslab), 256, 0, c.stream>>>((const bf16_t*)dy, ld, c.partial, rows, n);
-    k_reduce_partials<<<(n + 63) / 64, 64 * kReduceGroups, 0, c.stream>>>(c.partial, nslab, n, out, accumulate);
-    return LP_LAUNCH_CHECK();
+    k_colsum_partial_v<<<dim3((n + 127) / 128, nslab), 256, 0, c.stream>>>((const bf16_t*)dy, ld, part, rows, n);
+  } else {
+    dim3 grid((n + 63) / 64, nslab);
+    if (c.dt == BF16) k_colsum_partial<bf16_t><<<grid, 256, 0, c.stream>>>((const bf16_t*)dy, ld, part, rows, n);
+    else k_colsum_partial<float><<<grid, 256, 0, c.stream>>>((const float*)dy, ld, part, rows, n);
   }
-  dim3 grid((n + 63) / 64, nslab);
-  if (c.dt == BF16) k_colsum_partial<bf16_t><<<grid, 256, 0, c.stream>>>((const bf16_t*)dy, ld, c.partial, rows, n);
-  else k_colsum_partial<float><<<grid, 256, 0, c.stream>>>((const float*)dy, ld, c.partial, rows, n);
-  k_reduce_partials<<<(n + 63) / 64, 64 * kReduceGroups, 0, c.stream>>>(c.partial, nslab, n, out, accumulate);
+  if (!direct) k_reduce_partials<<<(n + 63) / 64, 64 * kReduceGroups, 0, c.stream>>>(c.partial, nslab, n, out, accumulate);
   return LP_LAUNCH_CHECK();
 }
 

@@ -66,40 +66,52 @@ __device__ __forceinline__ bool k_is_contiguous(const O&) { return true; }
 // ws[z][M][N]; k_plain_splitk_reduce then adds the slices in order.
 // The next k-tile is fetched into registers before the current one is multiplied, so the memory latency of a
 // tile (which is what a small product costs: a few blocks, nothing else to switch to) overlaps the FMAs.
-template <typename T, typename OA, typename OB>
+// TM rows x 4 columns per thread: block tile 16*TM x 64.  Small products take TM = 2: twice the blocks, and a
+// k-tile's multiply phase (which, with a handful of blocks on the chip, is what the product waits for) is
+// 14 instead of 24 instructions per k.
+template <typename T, typename OA, typename OB, int TM = 4>
 __global__ void __launch_bounds__(256) k_gemm_plain(OA A, OB B, Epilogue e, int M, int N, int K, int kper = 0,
                                                     float* ws = nullptr) {
-  __shared__ float As[PBK][PBM + 1];
+  constexpr int BM_ = 16 * TM;
+  __shared__ float As[PBK][BM_ + 1];
   __shared__ float Bs[PBK][PBN + 1];
-  constexpr int PER = PBM * PBK / 256;
-  static_assert(PBM == PBN && PBM * PBK % 256 == 0, "tile fetch assumes square tiles and whole passes");
+  constexpr int PER_A = BM_ * PBK / 256, PER_B = PBN * PBK / 256;
+  static_assert(BM_ * PBK % 256 == 0 && PBN * PBK % 256 == 0, "tile fetch assumes whole passes");
   int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
-  int m0 = blockIdx.y * PBM, n0 = blockIdx.x * PBN;
-  float acc[4][4] = {};
+  int m0 = blockIdx.y * BM_, n0 = blockIdx.x * PBN;
+  float acc[TM][4] = {};
   int kbeg = 0;
   if (ws) {
     kbeg = blockIdx.z * kper;
     K = kbeg + kper < K ? kbeg + kper : K;
   }
   const bool a_kfast = k_is_contiguous(A), b_kfast = k_is_contiguous(B);
-  float ra[PER], rb[PER];
+  float ra[PER_A], rb[PER_B];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
+    for (int j = 0; j < PER_A; ++j) {
       const int i = threadIdx.x + 256 * j;
-      const int ka = a_kfast ? i % PBK : i / PBM, ma = a_kfast ? i / PBK : i % PBM;
-      const int kb = b_kfast ? i % PBK : i / PBN, nb = b_kfast ? i / PBK : i % PBN;
+      const int ka = a_kfast ? i % PBK : i / BM_, ma = a_kfast ? i / PBK : i % BM_;
       ra[j] = (m0 + ma < M && k0 + ka < K) ? A(m0 + ma, k0 + ka) : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < PER_B; ++j) {
+      const int i = threadIdx.x + 256 * j;
+      const int kb = b_kfast ? i % PBK : i / PBN, nb = b_kfast ? i / PBK : i % PBN;
       rb[j] = (n0 + nb < N && k0 + kb < K) ? B(n0 + nb, k0 + kb) : 0.f;
     }
   };
   auto stage = [&]() {
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
+    for (int j = 0; j < PER_A; ++j) {
       const int i = threadIdx.x + 256 * j;
-      const int ka = a_kfast ? i % PBK : i / PBM, ma = a_kfast ? i / PBK : i % PBM;
-      const int kb = b_kfast ? i % PBK : i / PBN, nb = b_kfast ? i / PBK : i % PBN;
+      const int ka = a_kfast ? i % PBK : i / BM_, ma = a_kfast ? i / PBK : i % BM_;
       As[ka][ma] = ra[j];
+    }
+#pragma unroll
+    for (int j = 0; j < PER_B; ++j) {
+      const int i = threadIdx.x + 256 * j;
+      const int kb = b_kfast ? i % PBK : i / PBN, nb = b_kfast ? i / PBK : i % PBN;
       Bs[kb][nb] = rb[j];
     }
   };
@@ -110,21 +122,23 @@ __global__ void __launch_bounds__(256) k_gemm_plain(OA A, OB B, Epilogue e, int 
     if (k0 + PBK < K) fetch(k0 + PBK);
 #pragma unroll
     for (int kk = 0; kk < PBK; ++kk) {
-      float a[4], b[4];
+      float a[TM], b[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+      for (int i = 0; i < TM; ++i) a[i] = As[kk][ty * TM + i];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 4; ++i) b[i] = Bs[kk][tx * 4 + i];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      int m = m0 + ty * TM + i, n = n0 + tx * 4 + j;
       if (m < M && n < N) {
         if (ws) ws[((size_t)blockIdx.z * M + m) * N + n] = acc[i][j];
         else epilogue_store<T>(e, m, n, acc[i][j]);
@@ -142,8 +156,14 @@ __global__ void k_plain_splitk_reduce(const float* ws, float* out, size_t total,
 template <typename T, typename OA, typename OB>
 static hipError_t launch_plain(hipStream_t s, OA A, OB B, const Epilogue& e, int M, int N, int K) {
   if (M <= 0 || N <= 0) return hipSuccess;
-  dim3 grid((N + PBN - 1) / PBN, (M + PBM - 1) / PBM);
-  k_gemm_plain<T, OA, OB><<<grid, 256, 0, s>>>(A, B, e, M, N, K);
+  const int tn = (N + PBN - 1) / PBN, tm = (M + PBM - 1) / PBM;
+  if (tn * ((M + 31) / 32) < 64 && M > 16) {     // a very small product: 16-row tiles
+    k_gemm_plain<T, OA, OB, 1><<<dim3(tn, (M + 15) / 16), 256, 0, s>>>(A, B, e, M, N, K);
+  } else if (tn * tm < 128 && M > 16) {          // a small product: 32-row tiles
+    k_gemm_plain<T, OA, OB, 2><<<dim3(tn, (M + 31) / 32), 256, 0, s>>>(A, B, e, M, N, K);
+  } else {
+    k_gemm_plain<T, OA, OB, 4><<<dim3(tn, tm), 256, 0, s>>>(A, B, e, M, N, K);
+  }
   return hipGetLastError();
 }
 
@@ -190,7 +210,7 @@ static hipError_t conv_bwd_weight_t(const OpCtx& c, const ConvArgs& a, const voi
   int kper = ((Mrows + splits - 1) / splits + PBK - 1) / PBK * PBK;
   splits = (Mrows + kper - 1) / kper;
   dim3 grid((J + PBN - 1) / PBN, (a.O + PBM - 1) / PBM, splits);
-  k_gemm_plain<T, PlainOperand<T>, ConvPatchByCol<T>><<<grid, 256, 0, c.stream>>>(A, B, plain_out(dw, J, 1, 0), a.O, J,
+  k_gemm_plain<T, PlainOperand<T>, ConvPatchByCol<T>, 4><<<grid, 256, 0, c.stream>>>(A, B, plain_out(dw, J, 1, 0), a.O, J,
                                                                                  Mrows, kper, c.splitk_ws);
   size_t total = (size_t)a.O * J;
   k_plain_splitk_reduce<<<(unsigned)((total + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, dw, total, splits, accumulate);
