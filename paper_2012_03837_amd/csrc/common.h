@@ -155,7 +155,9 @@ hipError_t op_init_normal(const OpCtx& c, float* p, size_t n, float std, uint64_
 
 // conv / batchnorm / pooling
 hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out);
-hipError_t op_conv_bwd_data(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx);
+// dx = data gradient (+ add, an activation-gradient tensor of dx's shape: the other branch of a residual block).
+hipError_t op_conv_bwd_data(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
+                            const void* add = nullptr);
 hipError_t op_conv_bwd_weight(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                               int accumulate);
 // Running statistics of one batch normalisation (the evaluation form of the method appendix B.3 cites).

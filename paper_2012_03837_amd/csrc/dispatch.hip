@@ -9,7 +9,8 @@ hipError_t attn_fwd_plain(const OpCtx& c, const void* qkv, void* o, float* lse, 
 hipError_t attn_bwd_plain(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout,
                           void* dqkv, float* delta, int B, int S, int H, int dh, int causal);
 hipError_t conv_fwd_plain(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out);
-hipError_t conv_bwd_data_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx);
+hipError_t conv_bwd_data_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
+                               const void* add = nullptr);
 hipError_t conv_bwd_weight_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                                  int accumulate);
 
@@ -19,7 +20,8 @@ hipError_t attn_bwd_mfma(const OpCtx& c, const void* qkv, const void* o, const f
 
 bool conv_mfma_ok(const OpCtx& c, const ConvArgs& a, const void* p0, const void* p1, const void* p2);
 hipError_t conv_fwd_mfma(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out);
-hipError_t conv_bwd_data_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx);
+hipError_t conv_bwd_data_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
+                              const void* add);
 hipError_t conv_bwd_weight_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                                 int accumulate);
 static bool plain_conv() {
@@ -50,10 +52,12 @@ hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const v
   if (!plain_conv() && conv_mfma_ok(c, a, x, w, out)) return conv_fwd_mfma(c, a, x, w, out);
   return conv_fwd_plain(c, a, x, w, out);
 }
-hipError_t op_conv_bwd_data(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx) {
+hipError_t op_conv_bwd_data(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
+                            const void* add) {
   ProfScope prof_(c, KC_CONV, 2.0 * a.N * a.P * a.Q * a.O * a.R * a.S * a.C);
-  if (!plain_conv() && conv_mfma_ok(c, a, dout, w, dx)) return conv_bwd_data_mfma(c, a, dout, w, dx);
-  return conv_bwd_data_plain(c, a, dout, w, dx);
+  if (!plain_conv() && conv_mfma_ok(c, a, dout, w, dx) && (!add || ((uintptr_t)add & 15) == 0))
+    return conv_bwd_data_mfma(c, a, dout, w, dx, add);
+  return conv_bwd_data_plain(c, a, dout, w, dx, add);
 }
 hipError_t op_conv_bwd_weight(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                               int accumulate) {

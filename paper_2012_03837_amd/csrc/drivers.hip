@@ -183,14 +183,15 @@ static int unit_forward(lp_ctx* c, ConvUnit& u, const void* x, const void* res) 
                       c->bn_for(u.g, u.a.O)));
   return LP_OK;
 }
-// dy -> (dz in sZ) -> dw, and dx if asked.  dres (if non-null) receives the ReLU-masked dy.
-static int unit_backward(lp_ctx* c, ConvUnit& u, const void* x, const void* dy, void* dres, void* dx, int acc) {
+// dy -> (dz in sZ) -> dw, and dx (+ dx_add, if given) if asked.  dres (if non-null) receives the ReLU-masked dy.
+static int unit_backward(lp_ctx* c, ConvUnit& u, const void* x, const void* dy, void* dres, void* dx, int acc,
+                         const void* dx_add = nullptr) {
   OpCtx o = c->op();
   int rows = u.a.N * u.a.P * u.a.Q;
   DO(op_batchnorm_bwd(o, dy, u.y, u.z, u.mean, u.rstd, c->P32(u.g), c->sZ, dres, c->G32(u.g), c->G32(u.b), rows,
                       u.a.O, u.relu, acc));
   DO(op_conv_bwd_weight(o, u.a, c->sZ, x, c->G32(u.w), acc));
-  if (dx) DO(op_conv_bwd_data(o, u.a, c->sZ, c->W(u.w), dx));
+  if (dx) DO(op_conv_bwd_data(o, u.a, c->sZ, c->W(u.w), dx, dx_add));
   return LP_OK;
 }
 static void set_batch(ConvUnit& u, int batch) { u.a.N = batch; }
@@ -230,15 +231,15 @@ static int res_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx
     bool want_dx = need_dx || !first_op;
     // c2: dz2 -> dw2, dt (into sD1); masked upstream gradient ds -> sR
     if ((st = unit_backward(c, b.c2, b.c1.y, g, c->sR, c->sD1, acc)) != LP_OK) return st;
-    // c1
-    if ((st = unit_backward(c, b.c1, bin, c->sD1, nullptr, want_dx ? c->sD1 : nullptr, acc)) != LP_OK) return st;
-    size_t n_in = (size_t)b.c1.a.N * b.c1.a.H * b.c1.a.W * b.c1.a.C;
+    // c1, and the shortcut's share of the block input's gradient, added in the data-gradient epilogue that
+    // finishes last: the identity shortcut's is the masked upstream gradient itself (sR), a projection's is its
+    // own data gradient, which then takes c1's (sD1) as its addend
     void* dst = (first_op && need_dx) ? dx : c->sG;
     if (b.has_proj) {
-      if ((st = unit_backward(c, b.proj, bin, c->sR, nullptr, want_dx ? c->sD2 : nullptr, acc)) != LP_OK) return st;
-      if (want_dx) DO(op_add(o, c->sD1, c->sD2, dst, n_in));
+      if ((st = unit_backward(c, b.c1, bin, c->sD1, nullptr, want_dx ? c->sD1 : nullptr, acc)) != LP_OK) return st;
+      if ((st = unit_backward(c, b.proj, bin, c->sR, nullptr, want_dx ? dst : nullptr, acc, c->sD1)) != LP_OK) return st;
     } else {
-      if (want_dx) DO(op_add(o, c->sD1, c->sR, dst, n_in));
+      if ((st = unit_backward(c, b.c1, bin, c->sD1, nullptr, want_dx ? dst : nullptr, acc, c->sR)) != LP_OK) return st;
     }
     g = dst;
   }

@@ -195,7 +195,7 @@ bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 // half the CUs get nothing.  Such products are cut along k into enough pieces for two to three blocks per CU;
 // the fp32 partial sums (M x N per piece) are added in piece order.
 template <class LA, class LB>
-hipError_t launch_cut(const OpCtx& c, LA A, LB B, void* out, int M, int N, int K) {
+hipError_t launch_cut(const OpCtx& c, LA A, LB B, void* out, int M, int N, int K, const void* add = nullptr) {
   const int tiles = ((M + 127) / 128) * ((N + BN - 1) / BN);
   int splits = 1;
   if (c.splitk_ws && tiles < 200 && K >= 1024) {
@@ -204,7 +204,8 @@ hipError_t launch_cut(const OpCtx& c, LA A, LB B, void* out, int M, int N, int K
     while (splits > 1 && (size_t)splits * M * N > c.splitk_elems) --splits;
     if (splits < 1) splits = 1;
   }
-  const Epilogue e = plain_epilogue(out, N, 0, 0);
+  Epilogue e = plain_epilogue(out, N, 0, 0);
+  e.res = add; e.ldr = N;      // a tensor of the output's shape added to the result
   hipError_t err = launch(c, A, B, e, M, N, K, splits);
   if (err != hipSuccess || splits == 1) return err;
   const size_t work = (size_t)M * (N / 8);
@@ -224,11 +225,12 @@ hipError_t conv_fwd_mfma(const OpCtx& c, const ConvArgs& a, const void* x, const
   PlainLoader<true> B{Operand{(const bf16_t*)w, K, a.O}};
   return launch_cut(c, A, B, out, M, a.O, K);
 }
-hipError_t conv_bwd_data_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx) {
+hipError_t conv_bwd_data_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
+                              const void* add) {
   const int M = a.N * a.H * a.W, K = a.R * a.S * a.O;
   ConvBwdA A{(const bf16_t*)dout, a, M};
   ConvFilterT B{(const bf16_t*)w, a};
-  return launch_cut(c, A, B, dx, M, a.C, K);
+  return launch_cut(c, A, B, dx, M, a.C, K, add);
 }
 hipError_t conv_bwd_weight_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                                 int accumulate) {

@@ -189,11 +189,14 @@ static hipError_t conv_fwd_t(const OpCtx& c, const ConvArgs& a, const void* x, c
   return launch_plain<T>(c.stream, A, B, plain_out(out, a.O, 0, 0), M, a.O, K);
 }
 template <typename T>
-static hipError_t conv_bwd_data_t(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx) {
+static hipError_t conv_bwd_data_t(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
+                                  const void* add) {
   int M = a.N * a.H * a.W, K = a.R * a.S * a.O;
   ConvOutputGather<T> A{(const T*)dout, a};
   ConvFilterT<T> B{(const T*)w, a};
-  return launch_plain<T>(c.stream, A, B, plain_out(dx, a.C, 0, 0), M, a.C, K);
+  Epilogue e = plain_out(dx, a.C, 0, 0);
+  e.res = add; e.ldr = a.C;
+  return launch_plain<T>(c.stream, A, B, e, M, a.C, K);
 }
 template <typename T>
 static hipError_t conv_bwd_weight_t(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
@@ -220,8 +223,9 @@ static hipError_t conv_bwd_weight_t(const OpCtx& c, const ConvArgs& a, const voi
 hipError_t conv_fwd_plain(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {
   return c.dt == BF16 ? conv_fwd_t<bf16_t>(c, a, x, w, out) : conv_fwd_t<float>(c, a, x, w, out);
 }
-hipError_t conv_bwd_data_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx) {
-  return c.dt == BF16 ? conv_bwd_data_t<bf16_t>(c, a, dout, w, dx) : conv_bwd_data_t<float>(c, a, dout, w, dx);
+hipError_t conv_bwd_data_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
+                               const void* add) {
+  return c.dt == BF16 ? conv_bwd_data_t<bf16_t>(c, a, dout, w, dx, add) : conv_bwd_data_t<float>(c, a, dout, w, dx, add);
 }
 hipError_t conv_bwd_weight_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                                  int accumulate) {

@@ -9,7 +9,8 @@ hipError_t attn_fwd_plain(const OpCtx& c, const void* qkv, void* o, float* lse, 
 hipError_t attn_bwd_plain(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout,
                           void* dqkv, float* delta, int B, int S, int H, int dh, int causal);
 hipError_t conv_fwd_plain(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out);
-hipError_t conv_bwd_data_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx);
+hipError_t conv_bwd_data_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
+                               const void* add = nullptr);
 hipError_t conv_bwd_weight_plain(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                                  int accumulate);
 }
