@@ -145,19 +145,26 @@ __global__ void __launch_bounds__(256) k_gemm_plain(OA A, OB B, Epilogue e, int 
       }
     }
 }
+// Eight running sums (slices s, s+8, ... each) keep eight loads in flight; they are combined in a fixed order.
 __global__ void k_plain_splitk_reduce(const float* ws, float* out, size_t total, int splits, int accumulate) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
-  float a = 0.f;
-  for (int s = 0; s < splits; ++s) a += ws[(size_t)s * total + idx];
-  out[idx] = accumulate ? out[idx] + a : a;
+  float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  int s = 0;
+  for (; s + 8 <= splits; s += 8) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a[u] += ws[(size_t)(s + u) * total + idx];
+  }
+  for (; s < splits; ++s) a[0] += ws[(size_t)s * total + idx];
+  const float t = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+  out[idx] = accumulate ? out[idx] + t : t;
 }
 
 template <typename T, typename OA, typename OB>
 static hipError_t launch_plain(hipStream_t s, OA A, OB B, const Epilogue& e, int M, int N, int K) {
   if (M <= 0 || N <= 0) return hipSuccess;
   const int tn = (N + PBN - 1) / PBN, tm = (M + PBM - 1) / PBM;
-  if (tn * ((M + 31) / 32) < 64 && M > 16) {     // a very small product: 16-row tiles
+  if (tn * ((M + 31) / 32) < 64) {               // a very small product: 16-row tiles
     k_gemm_plain<T, OA, OB, 1><<<dim3(tn, (M + 15) / 16), 256, 0, s>>>(A, B, e, M, N, K);
   } else if (tn * tm < 128 && M > 16) {          // a small product: 32-row tiles
     k_gemm_plain<T, OA, OB, 2><<<dim3(tn, (M + 31) / 32), 256, 0, s>>>(A, B, e, M, N, K);
