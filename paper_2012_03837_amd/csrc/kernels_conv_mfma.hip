@@ -150,9 +150,16 @@ __global__ void k_conv_splitk_reduce(const float* __restrict__ ws, float* __rest
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   size_t total = (size_t)M * N;
   if (idx >= total) return;
-  float a = 0.f;
-  for (int s = 0; s < splits; ++s) a += ws[(size_t)s * total + idx];
-  out[idx] = accumulate ? out[idx] + a : a;
+  // four running sums (pieces s, s+4, ... each) keep four loads in flight; combined in a fixed order
+  float a[4] = {0.f, 0.f, 0.f, 0.f};
+  int s = 0;
+  for (; s + 4 <= splits; s += 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) a[u] += ws[(size_t)(s + u) * total + idx];
+  }
+  for (; s < splits; ++s) a[0] += ws[(size_t)s * total + idx];
+  const float t = (a[0] + a[1]) + (a[2] + a[3]);
+  out[idx] = accumulate ? out[idx] + t : t;
 }
 
 // The same sum for a compute-dtype output: 8 consecutive columns per thread, through the epilogue.
