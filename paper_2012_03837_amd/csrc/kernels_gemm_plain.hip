@@ -188,9 +188,81 @@ static Epilogue plain_out(void* C, int64_t ldc, int c_f32, int accumulate) {
   return make_epilogue(g);
 }
 
+// Forward convolution of an input with very few channels (the 3-channel stem): as a GEMM its reduction is
+// 27 long and the gather's index arithmetic costs more than the multiplications.  Here a thread owns one output
+// pixel and 16 output channels: it walks the filter window once (one bounds test per tap), takes the filter
+// from LDS ([k][O] fp32, so the 16 channels are consecutive) and writes 16 consecutive outputs.  Products are
+// added in the same order (r, s, c ascending) as the GEMM form adds them.
+constexpr int kSmallCMaxK = 64;
+// 16 consecutive outputs as 16-byte stores (the caller guarantees 16-byte alignment)
+__device__ __forceinline__ void store16(float* p, const float (&v)[16]) {
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    f32x4 o = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+    *reinterpret_cast<f32x4*>(p + 4 * g) = o;
+  }
+}
+__device__ __forceinline__ void store16(bf16_t* p, const float (&v)[16]) {
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    bf16x8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (bf16_t)v[8 * g + j];
+    *reinterpret_cast<bf16x8*>(p + 8 * g) = o;
+  }
+}
+template <typename T>
+__global__ void __launch_bounds__(256) k_conv_fwd_smallc(const T* __restrict__ x, const T* __restrict__ w,
+                                                         T* __restrict__ out, ConvArgs a, int M) {
+  extern __shared__ __attribute__((aligned(16))) float wsm[];
+  const int K = a.R * a.S * a.C;
+  for (int i = threadIdx.x; i < K * a.O; i += 256) {
+    const int o = i % a.O, k = i / a.O;
+    wsm[i] = to_f(w[(size_t)o * K + k]);
+  }
+  __syncthreads();
+  const int groups = a.O / 16;
+  const size_t gid = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t m = gid / groups;
+  const int og = (int)(gid % groups);
+  if (m >= (size_t)M) return;
+  const int q = (int)(m % a.Q);
+  const size_t t = m / a.Q;
+  const int p = (int)(t % a.P), n = (int)(t / a.P);
+  float acc[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+  int k = 0;
+  for (int r = 0; r < a.R; ++r)
+    for (int s2 = 0; s2 < a.S; ++s2) {
+      const int h = p * a.stride + r - a.pad, wq = q * a.stride + s2 - a.pad;
+      const bool ok = h >= 0 && h < a.H && wq >= 0 && wq < a.W;
+      const T* xp = x + (((size_t)n * a.H + (ok ? h : 0)) * a.W + (ok ? wq : 0)) * a.C;
+      for (int cc = 0; cc < a.C; ++cc, ++k) {
+        const float xv = ok ? to_f(xp[cc]) : 0.f;
+        const f32x4* wr = reinterpret_cast<const f32x4*>(wsm + (size_t)k * a.O + og * 16);   // 64-byte aligned
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 wv = wr[g];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[4 * g + j] = fmaf(xv, wv[j], acc[4 * g + j]);
+        }
+      }
+    }
+  store16(out + m * a.O + og * 16, acc);
+}
+
 template <typename T>
 static hipError_t conv_fwd_t(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {
   int M = a.N * a.P * a.Q, K = a.R * a.S * a.C;
+  if (a.C <= 4 && a.O % 16 == 0 && K <= kSmallCMaxK && M > 0 && ((uintptr_t)out & 15) == 0) {
+    const size_t threads = (size_t)M * (a.O / 16);
+    const size_t shm = (size_t)K * a.O * sizeof(float);
+    if (shm <= 48 * 1024) {
+      k_conv_fwd_smallc<T><<<(unsigned)((threads + 255) / 256), 256, shm, c.stream>>>((const T*)x, (const T*)w, (T*)out, a, M);
+      return hipGetLastError();
+    }
+  }
   ConvInputPatch<T> A{(const T*)x, a};
   PlainOperand<T> B{(const T*)w, K, 1};
   return launch_plain<T>(c.stream, A, B, plain_out(out, a.O, 0, 0), M, a.O, K);
