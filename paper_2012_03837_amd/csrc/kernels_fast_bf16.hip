@@ -347,6 +347,16 @@ k_bn_finish_v(const float* __restrict__ partial, int nslab, int C, int rows, con
   float a = 0.f, b = 0.f;
   if (j < C) {
     int s = q;
+    for (; s + 3 * kBnFinishGroups < nslab; s += 4 * kBnFinishGroups) {      // eight loads in flight
+      float av[4], bv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        av[u] = partial[(size_t)(s + u * kBnFinishGroups) * C + j];
+        bv[u] = partial[(size_t)(nslab + s + u * kBnFinishGroups) * C + j];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { a += av[u]; b += bv[u]; }
+    }
     for (; s + kBnFinishGroups < nslab; s += 2 * kBnFinishGroups) {
       const float a0 = partial[(size_t)s * C + j], b0 = partial[(size_t)(nslab + s) * C + j];
       const float a1 = partial[(size_t)(s + kBnFinishGroups) * C + j], b1 = partial[(size_t)(nslab + s + kBnFinishGroups) * C + j];
