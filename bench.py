@@ -175,6 +175,10 @@ def main():
                     help="side streams for the heads' chains (0 = one stream); default: 2 for the decoders, 3 for the "
                          "residual MLP, and one per stage (at most 4) for the ResNet configurations, whose four "
                          "chains are short enough to run side by side (each the fastest measured)")
+    ap.add_argument("--overlap-steps", action="store_true",
+                    help="lp_overlap_steps: consecutive steps are not joined into the caller's stream, so the next "
+                         "step's first layers run beside the last blocks of the current one (same results, weaker "
+                         "buffer contract; see include/lp.h)")
     ap.add_argument("--schedule", default="sync", choices=["sync", "pipelined"],
                     help="sync: every block works on the call's minibatch (the headline metric); pipelined: block j "
                          "works on block j-1's output of the previous call (steady state after warm-up)")
@@ -223,6 +227,8 @@ def main():
     staged = [tr.stage(*LI.make_batch(cfg, i)) for i in range(n_stage)]
     torch.cuda.synchronize()
 
+    if args.overlap_steps:
+        tr.overlap_steps(True)
     if args.graph:
         tr.step_graph(True)
         xb, yb = staged[0][0].clone(), staged[0][1].clone()
@@ -305,7 +311,7 @@ def main():
         "config": {"workload": cfg.name, "batch": cfg.batch, "n_layers": cfg.n_layers, "n_heads_aux": len(cfg.heads),
                    "windows": LI.head_windows(cfg)[:3] + (["..."] if len(cfg.heads) > 3 else []),
                    "optimizer": cfg.opt.kind, "combine": cfg.combine, "side_streams": args.streams,
-                   "schedule": args.schedule, "graph": bool(args.graph)},
+                   "schedule": args.schedule, "graph": bool(args.graph), "overlap_steps": bool(args.overlap_steps)},
         "roofline": roofline,
         "phases": phases,
         "final_losses": losses[:4],

@@ -189,6 +189,21 @@ int lp_set_step(lp_ctx* ctx, int t);
  * enabled, and lp_eval_loss, run as usual. */
 int lp_step_graph(lp_ctx* ctx, int on);
 
+/* Overlap of consecutive synchronous steps (section 6: updates are applied asynchronously and the blocks keep
+ * working without a global barrier).  By default a call ends by making the caller's stream wait for every
+ * block's chain, so whatever the caller enqueues next sees the finished step.  With overlap on, lp_local_step
+ * leaves its chains running on the library's side streams and the next lp_local_step starts at once: its forward
+ * pass of a layer waits only for the chains of the heads that read or update that layer, so the first layers of
+ * step t+1 run beside the last blocks of step t.  Each step computes exactly what it computes without overlap
+ * (bit for bit).  The price is a weaker contract: x_dev, y_dev and losses_dev of a call must stay untouched
+ * (and losses_dev unread) until lp_join, or any entry point other than lp_local_step, has been called on the
+ * context and the caller's stream has reached that point.  Needs side streams (n_streams > 0; otherwise it
+ * has no effect); LP_EINVAL with the pipelined schedule or while graph replay is on. */
+int lp_overlap_steps(lp_ctx* ctx, int on);
+/* Makes the caller's stream wait for everything earlier calls left running (stream-ordered, does not block
+ * the host).  A no-op unless steps are overlapped. */
+int lp_join(lp_ctx* ctx);
+
 /* Gradient similarity (section 5, "Gradient Angles"; Fig. 6a): out_dev[l-1] (device, n_layers floats) =
  * cosine of the angle between the gradients that the last lp_local_step of ctx_a and of ctx_b left for
  * layer l's parameters, all of the layer's tensors taken as one vector; 0 where either gradient is zero

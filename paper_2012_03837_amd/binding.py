@@ -103,6 +103,8 @@ def lib() -> C.CDLL:
         L.lp_grad_cosine.argtypes = [vp, vp, vp]
         L.lp_step_graph.argtypes = [vp, C.c_int]
         L.lp_bn_running.argtypes = [vp, C.c_float, C.c_int]
+        L.lp_overlap_steps.argtypes = [vp, C.c_int]
+        L.lp_join.argtypes = [vp]
         L.lp_destroy.argtypes = [vp]
         L.lp_destroy.restype = None
         _lib = L
@@ -232,6 +234,14 @@ def lp_step_graph(ctx: int, on: bool) -> None:
     _check(lib().lp_step_graph(ctx, 1 if on else 0), ctx)
 
 
+def lp_overlap_steps(ctx: int, on: bool) -> None:
+    _check(lib().lp_overlap_steps(ctx, 1 if on else 0), ctx)
+
+
+def lp_join(ctx: int) -> None:
+    _check(lib().lp_join(ctx), ctx)
+
+
 def lp_bn_running(ctx: int, momentum: float = 0.1, eval_with_running: bool = False) -> None:
     _check(lib().lp_bn_running(ctx, float(momentum), 1 if eval_with_running else 0), ctx)
 
@@ -319,6 +329,12 @@ class LocalTrainer:
 
     def step_graph(self, on: bool = True) -> None:
         lp_step_graph(self.ctx, on)
+
+    def overlap_steps(self, on: bool = True) -> None:
+        lp_overlap_steps(self.ctx, on)
+
+    def join(self) -> None:
+        lp_join(self.ctx)
 
     def bn_running(self, momentum: float = 0.1, eval_with_running: bool = False) -> None:
         lp_bn_running(self.ctx, momentum, eval_with_running)

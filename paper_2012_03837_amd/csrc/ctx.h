@@ -144,6 +144,10 @@ struct lp_ctx : lp_scratch {
   size_t label_elems_per_sample = 1;
   hipEvent_t ev_pipe = nullptr;
   void use(int i) { static_cast<lp_scratch&>(*this) = sets[i]; }
+  // steps overlapped across calls: a call does not join its chains into the caller's stream; the next step's
+  // forward pass of a layer waits only for the chains that read or update that layer (join_pending otherwise)
+  int overlap_steps = 0;
+  bool pending_join = false;
   int step_t = 0;
   int last_batch = 0;
   // Replay of a captured synchronous step (lp_step_graph): the graph of the last captured call, the

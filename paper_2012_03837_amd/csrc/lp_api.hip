@@ -560,6 +560,15 @@ extern "C" void lp_destroy(lp_ctx* c) {
 extern "C" const char* lp_last_error(const lp_ctx* c) { return c ? c->err.c_str() : g_init_err.c_str(); }
 
 // ------------------------------------------------------------------------------------- step / eval
+// Makes the caller's stream wait for every chain a previous overlapped step left running.
+static int join_pending(lp_ctx* c) {
+  if (!c->pending_join) return LP_OK;
+  for (auto ev : c->ev_chain)
+    if (ev) CK(hipStreamWaitEvent(c->stream, ev, 0));
+  c->pending_join = false;
+  return LP_OK;
+}
+
 static int check_call(lp_ctx* c, const void* x, const int32_t* y, int batch, float* losses) {
   if (!c) return LP_EINVAL;
   if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
@@ -642,6 +651,10 @@ static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* los
   if (st != LP_OK) return st;
   int L = c->spec.n_layers, J = c->spec.n_heads;
   c->bn_mode = train ? (c->bn_momentum > 0.f ? 1 : 0) : (c->bn_eval_running ? 2 : 0);
+  // with per-op timing on, everything runs on the caller's stream so that each duration is the op's own
+  const bool side = train && c->n_side > 0 && !c->prof.on;
+  const bool overlap = side && c->overlap_steps && batch > 0 && c->spec.schedule != LP_SCHED_PIPELINED;
+  if (!overlap && (st = join_pending(c)) != LP_OK) return st;
   if (train && batch > 0 && c->spec.schedule == LP_SCHED_PIPELINED) return run_pipelined(c, x, y, batch, losses);
   for (int li = 1; li <= L; ++li) c->layers[li].in_override = nullptr;
   if (batch == 0) {
@@ -655,12 +668,17 @@ static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* los
     for (int li = 1; li <= L; ++li) c->layers[li].seen = 0;
   }
   const int32_t* ids = c->spec.vocab > 0 ? (const int32_t*)x : nullptr;
-  // with per-op timing on, everything runs on the caller's stream so that each duration is the op's own
-  const bool side = train && c->n_side > 0 && !c->prof.on;
   int hj = 0, chain = 0;
   c->use(0);
   for (int li = 1; li <= L; ++li) {
     c->use(0);
+    if (c->pending_join) {
+      // the previous step's chains may still run: this layer's forward pass overwrites what the chains of the
+      // heads whose window covers the layer read (saved activations) and update (its weights), and its output
+      // is the saved input of the block that starts after it
+      for (int j = 0; j < J; ++j)
+        if (c->heads[j].s_lo <= li && li <= c->heads[j].e) CK(hipStreamWaitEvent(c->stream, c->ev_chain[j], 0));
+    }
     if ((st = drv_forward(c, li, batch, ids)) != LP_OK) return st;
     if (side && hj < J && c->heads[hj].e == li) CK(hipEventRecord(c->ev_fwd[li], c->stream));
     // every head attached after this layer runs as soon as the activation exists
@@ -695,8 +713,12 @@ static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* los
     }
   }
   c->use(0);
-  if (side)
+  if (overlap) {
+    c->pending_join = true;        // joined by the next call that is not an overlapped step
+  } else if (side) {
     for (int j = 0; j < J; ++j) CK(hipStreamWaitEvent(c->stream, c->ev_chain[j], 0));
+    c->pending_join = false;
+  }
   return LP_OK;
 }
 
@@ -749,9 +771,27 @@ extern "C" int lp_step_graph(lp_ctx* c, int on) {
     return fail(c, LP_EINVAL, "graph replay needs an optimizer without per-step scalars (Adam's bias correction changes every step)");
   if (on && c->spec.schedule == LP_SCHED_PIPELINED)
     return fail(c, LP_EINVAL, "graph replay is for the synchronous schedule");
+  if (on && c->overlap_steps) return fail(c, LP_EINVAL, "overlapped steps are not replayed through a graph");
   if (!on) drop_graph(c);
   c->graph_on = on != 0;
   return LP_OK;
+}
+
+extern "C" int lp_overlap_steps(lp_ctx* c, int on) {
+  if (!c) return LP_EINVAL;
+  if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
+  if (on && c->graph_on) return fail(c, LP_EINVAL, "steps replayed through a graph are not overlapped");
+  if (on && c->spec.schedule == LP_SCHED_PIPELINED) return fail(c, LP_EINVAL, "overlapping steps is for the synchronous schedule");
+  int st = join_pending(c);
+  if (st != LP_OK) return st;
+  c->overlap_steps = on != 0;
+  return LP_OK;
+}
+
+extern "C" int lp_join(lp_ctx* c) {
+  if (!c) return LP_EINVAL;
+  if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
+  return join_pending(c);
 }
 
 extern "C" int lp_bn_running(lp_ctx* c, float momentum, int eval_with_running) {
@@ -846,6 +886,7 @@ extern "C" int lp_get_tensor(lp_ctx* c, const char* name, void* dst, size_t byte
   if (st != LP_OK) return st;
   if (!dst) return fail(c, LP_EINVAL, "dst_host is null");
   if (bytes != r.bytes) return fail(c, LP_ESHAPE, std::string(name) + ": have " + std::to_string(r.bytes) + " bytes, caller gave " + std::to_string(bytes));
+  if ((st = join_pending(c)) != LP_OK) return st;
   CK(hipStreamSynchronize(c->stream));
   if (bytes) CK(hipMemcpy(dst, r.ptr, bytes, hipMemcpyDeviceToHost));
   return LP_OK;
@@ -857,6 +898,7 @@ extern "C" int lp_set_tensor(lp_ctx* c, const char* name, const void* src, size_
   if (st != LP_OK) return st;
   if (!src) return fail(c, LP_EINVAL, "src_host is null");
   if (bytes != r.bytes) return fail(c, LP_ESHAPE, std::string(name) + ": have " + std::to_string(r.bytes) + " bytes, caller gave " + std::to_string(bytes));
+  if ((st = join_pending(c)) != LP_OK) return st;
   CK(hipStreamSynchronize(c->stream));
   if (bytes) CK(hipMemcpy(r.ptr, src, bytes, hipMemcpyHostToDevice));
   if (r.is_param) {
@@ -876,6 +918,10 @@ extern "C" int lp_grad_cosine(lp_ctx* a, lp_ctx* b, float* out_dev) {
   lp_ctx* c = a;     // errors are recorded on ctx_a
   if (!a->ok || !b->ok) return fail(a, LP_ESTATE, "context is not usable");
   if (!out_dev) return fail(a, LP_EINVAL, "out_dev is null");
+  { int sj = join_pending(a); if (sj != LP_OK) return sj; }
+  if (b->pending_join)      // ctx_b's chains run on streams of its own: drain them
+    for (size_t i = 1; i < b->sets.size(); ++i)
+      if (b->sets[i].cur_stream) CK(hipStreamSynchronize(b->sets[i].cur_stream));
   if (a->spec.n_layers != b->spec.n_layers) return fail(a, LP_ESHAPE, "the two contexts have different numbers of layers");
   for (int li = 1; li <= a->spec.n_layers; ++li)
     if (a->layers[li].p_end - a->layers[li].p_begin != b->layers[li].p_end - b->layers[li].p_begin)

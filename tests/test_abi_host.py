@@ -98,6 +98,8 @@ def test_null_context_calls_fail_cleanly():
     assert L.lp_num_params(None) == 0
     assert L.lp_step_graph(None, 1) == B.LP_EINVAL
     assert L.lp_bn_running(None, 0.1, 0) == B.LP_EINVAL
+    assert L.lp_overlap_steps(None, 1) == B.LP_EINVAL
+    assert L.lp_join(None) == B.LP_EINVAL
     L.lp_destroy(None)
 
 

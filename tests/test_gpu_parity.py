@@ -406,3 +406,45 @@ def test_convolutions_cut_along_k_match_oracle(lpmod):
     x, y = data_for(cfg)
     compare_step(tr, cfg, generic_params(cfg), x, y, label="cut conv", stored=stored_for(cfg))
     tr.close()
+
+
+@pytest.mark.parametrize("name,ns", [("cfg1_small", 2), ("cfg2_small", 3), ("cfg3_small", 2), ("cfg4_small", 2),
+                                     ("cfg5_small", 1)])
+def test_overlapped_steps_bit_identical(lpmod, name, ns):
+    """Six steps issued back to back with lp_overlap_steps on (no join in between: every step has its own input,
+    label and loss buffers) leave the same losses, weights and optimizer state, bit for bit, as six ordinary
+    steps; an evaluation issued right behind them sees the finished weights; graph replay refuses to combine."""
+    import torch
+    cfg = LI.make_config(name)
+    n = 6
+    outs = []
+    for overlap in (False, True):
+        tr = lpmod.LocalTrainer(cfg, n_streams=ns)
+        tr.set_params(generic_params(cfg))
+        if overlap:
+            tr.overlap_steps(True)
+        bufs = [tr.stage(*data_for(cfg, i, batch=cfg.batch - (i % 2))) for i in range(n)]
+        loss = [torch.zeros(len(cfg.heads), device=bufs[0][0].device) for _ in range(n)]
+        for i in range(n):
+            xd, yd = bufs[i]
+            lpmod.lp_local_step(tr.ctx, xd.data_ptr(), yd.data_ptr(), xd.shape[0], loss[i].data_ptr())
+        ev = tr.eval(*bufs[0]).cpu().numpy().copy()        # any other entry point joins first
+        torch.cuda.synchronize()
+        P = tr.get_params()
+        for k in list(P):
+            for sfx in (".m", ".v"):
+                try:
+                    P[k + sfx] = tr.get(k + sfx)
+                except lpmod.LpError:
+                    pass
+        outs.append(([l.cpu().numpy().copy() for l in loss], ev, P))
+        if overlap and cfg.opt.kind != "adam":
+            with pytest.raises(lpmod.LpError):
+                tr.step_graph(True)
+        tr.close()
+    for a, b in zip(outs[0][0], outs[1][0]):
+        np.testing.assert_array_equal(a, b)
+    np.testing.assert_array_equal(outs[0][1], outs[1][1])
+    assert outs[0][2].keys() == outs[1][2].keys()
+    for k in outs[0][2]:
+        np.testing.assert_array_equal(outs[0][2][k], outs[1][2][k])
