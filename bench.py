@@ -21,14 +21,25 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3       # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0
 
-# Traffic beyond L2 of the timed kernel class, bytes per launch: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
-# (two separate runs of this file), scaled by the same counters' readings for the plain copy kernel
-# (--copy-calibration).  Counters cannot be read from inside this process, so the figures measured for the
-# committed kernels are recorded here; the summary with the commands is profiles/cfg3_gemm_hbm_traffic_pmc.md.
-MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 4.23e8, "read_bytes_per_step": 60.3e9, "written_bytes_per_step": 15.9e9,
-             "algorithmic_bytes_per_step": 31.1e9},
-}
+
+
+def measured_traffic(cfg_name, kernel):
+    """HBM-side traffic of one kernel instance in this workload, bytes per launch, from the committed rocprofv3
+    counter summary profiles/<cfg>_step_hbm_traffic_pmc.md (FETCH_SIZE and WRITE_SIZE of two separate runs of this
+    file, scaled by the same counters' readings for the plain copy kernel of --copy-calibration).  Counters cannot
+    be read from inside this process; the summary holds one machine-readable line per kernel:
+      traffic: kernel="<name>" fetch_bytes_per_launch=<x> write_bytes_per_launch=<y>
+    Returns (bytes per launch or None, note)."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"{cfg_name}_step_hbm_traffic_pmc.md")
+    if not os.path.exists(path):
+        return None, f"no counter summary for {cfg_name} under profiles/"
+    pat = re.compile(r'traffic: kernel="([^"]+)" fetch_bytes_per_launch=([0-9.eE+-]+) write_bytes_per_launch=([0-9.eE+-]+)')
+    for line in open(path):
+        m = pat.search(line)
+        if m and m.group(1) == kernel:
+            return float(m.group(2)) + float(m.group(3)), f"profiles/{os.path.basename(path)}"
+    return None, f"profiles/{os.path.basename(path)} has no line for {kernel}"
 
 
 def gemm_flops_per_step(cfg):
@@ -170,7 +181,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="cfg3", help="cfg1..cfg5")
+    ap.add_argument("--config", default="cfg5",
+                    help="cfg1..cfg5; the default is the largest single-GPU configuration (24 layers, 6 chunks)")
     ap.add_argument("--streams", type=int, default=-1,
                     help="side streams for the heads' chains (0 = one stream); default: 2 for the decoders, 3 for the "
                          "residual MLP, and one per stage (at most 4) for the ResNet configurations, whose four "
@@ -280,14 +292,33 @@ def main():
         if key in phases:
             p = phases[key]
             peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
-            algo = gf if key == "gemm" else gf
-            ach = algo / (p["ms_per_step"] * 1e-3) / 1e12
-            roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": kernel_names[key],
-                        "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
-                        "traffic": MEASURED_TRAFFIC.get(cfg.name, {}).get("bytes_per_launch"),
-                        "traffic_detail": MEASURED_TRAFFIC.get(cfg.name),
-                        "algorithmic_flops_per_step": algo, "launches_per_step": p["ops_per_step"],
-                        "avg_launch_ms": p["ms_per_step"] / p["ops_per_step"]}
+            ach = gf / (p["ms_per_step"] * 1e-3) / 1e12
+            cls = {"kernels": kernel_names[key], "achieved": ach, "frac": ach / peak, "algorithmic_flops_per_step": gf,
+                   "ops_per_step": p["ops_per_step"], "ms_per_step": p["ms_per_step"]}
+            kern = lp.lp_profile_gemm_kernels(tr.ctx) if key == "gemm" else []
+            if kern:
+                # the single time-dominant kernel instance of this run: algorithmic FLOPs of its launches over the
+                # summed duration of exactly those launches (an event pair around each, on the launch stream)
+                dom = max(kern, key=lambda r: r["ms"])
+                d_ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+                traffic, note = measured_traffic(cfg.name, dom["name"])
+                roofline = {"bound": "mfma", "kernel": dom["name"], "achieved": d_ach, "peak": peak, "unit": "TFLOP/s",
+                            "frac": d_ach / peak, "traffic": traffic, "traffic_source": note,
+                            "launches_per_step": dom["launches"] / K,
+                            "avg_launch_us": dom["ms"] / dom["launches"] * 1e3,
+                            "flops_per_launch": dom["flops"] / dom["launches"],
+                            "share_of_gemm_time": dom["ms"] / sum(r["ms"] for r in kern),
+                            "gemm_class": cls,
+                            "by_kernel": [{"kernel": r["name"], "launches_per_step": r["launches"] / K,
+                                           "avg_launch_us": r["ms"] / r["launches"] * 1e3,
+                                           "tflops": r["flops"] / (r["ms"] * 1e-3) / 1e12}
+                                          for r in sorted(kern, key=lambda r: -r["ms"])]}
+            else:
+                roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": kernel_names[key],
+                            "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                            "traffic_source": "not measured for this workload",
+                            "algorithmic_flops_per_step": gf, "launches_per_step": p["ops_per_step"],
+                            "avg_launch_ms": p["ms_per_step"] / p["ops_per_step"]}
         if "gemm" in phases:
             phases["gemm"]["algorithmic_tflops"] = gf / 1e12
             phases["gemm"]["by_shape"] = [

@@ -111,6 +111,11 @@ typedef struct {
                                into the caller's stream before lp_local_step returns.  Results do not depend
                                on n (every per-parameter accumulation keeps its order).  At most 8.        */
   int schedule;             /* lp_schedule: how lp_local_step feeds the blocks (see there)                 */
+  int debug;                /* != 0: keep, for every convolution + normalisation unit of a ResNet stage, a copy of
+                               the upstream gradient its backward pass was given and of the input gradient it
+                               produced (named tensors "<unit>.dy", "<unit>.dx", see lp_get_tensor), so that a unit
+                               can be checked in isolation; costs two activation-sized buffers per unit and two
+                               copies per unit per step.  0 for training.                                   */
 } lp_model_spec;
 
 typedef struct { size_t param_bytes, state_bytes, work_bytes; } lp_sizes;
@@ -165,7 +170,12 @@ int lp_bn_running(lp_ctx* ctx, float momentum, int eval_with_running);
 /* Named tensors.  Parameters "L3.wqkv", "H2.w" (fp32 master; setting one also refreshes the bf16
  * working copy); their gradients of the last step "L3.wqkv.grad" and optimizer moments ".m", ".v"
  * (fp32); batch-normalisation running statistics "L2.b1.bn1.running_mean", ".running_var" (fp32); layer outputs of the last forward "L3.out" and the embedded input "L0.out" (compute
- * dtype, shaped for the batch of that call).  lp_tensor_info reports shape, lp_dtype and bytes.
+ * dtype, shaped for the batch of that call).  For every convolution + normalisation unit of a ResNet stage,
+ * named like its filter without the ".w" ("L1.stem", "L2.b1.conv1", "L2.b1.conv2", "L2.b1.proj"): the stored
+ * convolution output "<unit>.z" and the unit's output "<unit>.y" of the last forward pass (compute dtype, NHWC)
+ * and, in a context created with spec.debug != 0, the upstream gradient "<unit>.dy" given to the unit's last
+ * backward pass and the input gradient "<unit>.dx" it produced (including the shortcut's share where the
+ * library adds it in the same kernel); LP_ENOTFOUND without the debug flag or when the unit computed none.  lp_tensor_info reports shape, lp_dtype and bytes.
  * get/set copy synchronously between host memory and the device after draining the stream;
  * `bytes` must equal the tensor's size. */
 int lp_tensor_info(lp_ctx* ctx, const char* name, int64_t shape[4], int* ndim, int* dtype, size_t* bytes);
@@ -196,8 +206,9 @@ int lp_step_graph(lp_ctx* ctx, int on);
  * pass of a layer waits only for the chains of the heads that read or update that layer, so the first layers of
  * step t+1 run beside the last blocks of step t.  Each step computes exactly what it computes without overlap
  * (bit for bit).  The price is a weaker contract: x_dev, y_dev and losses_dev of a call must stay untouched
- * (and losses_dev unread) until lp_join, or any entry point other than lp_local_step, has been called on the
- * context and the caller's stream has reached that point.  Needs side streams (n_streams > 0; otherwise it
+ * (and losses_dev unread) until lp_join, or any entry point that takes the context other than lp_local_step,
+ * lp_last_error, lp_num_params, lp_param_name and lp_destroy (which drains the side streams itself), has been
+ * called on the context and the caller's stream has reached that point.  Needs side streams (n_streams > 0; otherwise it
  * has no effect); LP_EINVAL with the pipelined schedule or while graph replay is on. */
 int lp_overlap_steps(lp_ctx* ctx, int on);
 /* Makes the caller's stream wait for everything earlier calls left running (stream-ordered, does not block
@@ -220,13 +231,21 @@ int lp_grad_cosine(lp_ctx* ctx_a, lp_ctx* ctx_b, float* out_dev);
  * pairs.  Enabling resets the totals. */
 typedef enum {
   LP_KC_GEMM = 0, LP_KC_ATTN_FWD, LP_KC_ATTN_BWD, LP_KC_LAYERNORM, LP_KC_SOFTMAX_CE, LP_KC_OPTIMIZER, LP_KC_EMBED,
-  LP_KC_COLSUM, LP_KC_CONV, LP_KC_BATCHNORM, LP_KC_OTHER, LP_KC_COUNT
+  LP_KC_COLSUM, LP_KC_CONV, LP_KC_BATCHNORM, LP_KC_OTHER,
+  LP_KC_GEMM_KERNEL,   /* the main kernel launch of every bf16 GEMM op alone (see lp_profile_gemm_kernels) */
+  LP_KC_COUNT
 } lp_kernel_class;
 int lp_profile_enable(lp_ctx* ctx, int on);
 /* GEMM ops by shape since profiling was enabled, as text into the host buffer `out` of `cap` bytes, one
  * line per shape: "M N K a_kc b_kc c_f32 count total_ms" (operand layouts as in lpk_gemm).  LP_ESHAPE if
  * the buffer is too small. */
 int lp_profile_gemm_shapes(lp_ctx* ctx, char* out, size_t cap);
+/* The main kernel of every bf16 GEMM op since profiling was enabled, grouped by kernel instance, as text into
+ * the host buffer `out`: one line per instance, "name<TAB>launches<TAB>total_ms<TAB>algorithmic_flops", where the
+ * name is the kernel's name as a profiler prints it ("k_gemm_dma<true, true, 4, 2, 4, true>") and the time is
+ * that of the one launch (an event pair around it; the op's partial-sum fix-up kernel, if any, is outside).
+ * LP_ESHAPE if the buffer is too small. */
+int lp_profile_gemm_kernels(lp_ctx* ctx, char* out, size_t cap);
 int lp_profile_read(lp_ctx* ctx, int kernel_class, double* total_ms, long long* launches, double* flops);
 
 /* Text of the last error on this context (or of the last failed init when ctx is NULL); valid

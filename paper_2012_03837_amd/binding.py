@@ -49,7 +49,7 @@ class lp_model_spec(C.Structure):
     _fields_ = [("n_layers", C.c_int), ("layers", C.POINTER(lp_layer_spec)), ("n_heads", C.c_int),
                 ("heads", C.POINTER(lp_head_spec)), ("opt", lp_opt_spec), ("combine", C.c_int), ("dtype", C.c_int),
                 ("max_batch", C.c_int), ("vocab", C.c_int), ("seed", C.c_uint64), ("n_streams", C.c_int),
-                ("schedule", C.c_int)]
+                ("schedule", C.c_int), ("debug", C.c_int)]
 
 
 class lp_sizes(C.Structure):
@@ -98,6 +98,7 @@ def lib() -> C.CDLL:
         L.lp_profile_enable.argtypes = [vp, ip]
         L.lp_profile_read.argtypes = [vp, ip, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]
         L.lp_profile_gemm_shapes.argtypes = [vp, C.c_char_p, sz]
+        L.lp_profile_gemm_kernels.argtypes = [vp, C.c_char_p, sz]
         L.lp_cost_model.argtypes = [C.POINTER(lp_cost_inputs), ip, ip, C.c_double, C.c_double, C.POINTER(lp_cost)]
         L.lp_mlp_flops.argtypes = [ip, ip, ip, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.lp_grad_cosine.argtypes = [vp, vp, vp]
@@ -114,7 +115,7 @@ def lib() -> C.CDLL:
 SCHEDULES = {"sync": 0, "pipelined": 1}
 
 
-def make_spec(cfg, max_batch: int | None = None, n_streams: int = 0, schedule: str = "sync"):
+def make_spec(cfg, max_batch: int | None = None, n_streams: int = 0, schedule: str = "sync", debug: bool = False):
     """lp_model_spec from a plain-data model description (fields as in lp_inputs.ModelCfg).
     Returns (spec, keepalive): the arrays the spec points into must outlive its use."""
     layers = (lp_layer_spec * len(cfg.layers))()
@@ -128,7 +129,7 @@ def make_spec(cfg, max_batch: int | None = None, n_streams: int = 0, schedule: s
     opt = lp_opt_spec(OPT_KINDS[o.kind], o.lr, o.momentum, o.beta1, o.beta2, o.eps, o.weight_decay)
     spec = lp_model_spec(len(cfg.layers), layers, len(cfg.heads), heads, opt, COMBINE[cfg.combine],
                          DTYPES[cfg.dtype], cfg.batch if max_batch is None else max_batch, cfg.vocab, cfg.seed,
-                         n_streams, SCHEDULES[schedule])
+                         n_streams, SCHEDULES[schedule], 1 if debug else 0)
     return spec, (layers, heads)
 
 
@@ -204,7 +205,7 @@ def lp_set_step(ctx: int, t: int) -> None:
 
 
 KERNEL_CLASSES = ("gemm", "attn_fwd", "attn_bwd", "layernorm", "softmax_ce", "optimizer", "embed", "colsum", "conv",
-                  "batchnorm", "other")
+                  "batchnorm", "other", "gemm_kernel")
 
 
 def lp_profile_enable(ctx: int, on: bool) -> None:
@@ -227,6 +228,18 @@ def lp_profile_gemm_shapes(ctx: int):
         M, N, K, a, b, f, n, ms = line.split()
         rows.append({"M": int(M), "N": int(N), "K": int(K), "a_kc": int(a), "b_kc": int(b), "c_f32": int(f),
                      "count": int(n), "ms": float(ms)})
+    return rows
+
+
+def lp_profile_gemm_kernels(ctx: int):
+    """The main kernel of every bf16 GEMM op since profiling was enabled, by kernel instance: dicts with name,
+    launches, ms, flops."""
+    buf = C.create_string_buffer(1 << 16)
+    _check(lib().lp_profile_gemm_kernels(ctx, buf, len(buf)), ctx)
+    rows = []
+    for line in buf.value.decode().splitlines():
+        name, n, ms, fl = line.split("\t")
+        rows.append({"name": name, "launches": int(n), "ms": float(ms), "flops": float(fl)})
     return rows
 
 
@@ -290,14 +303,14 @@ class LocalTrainer:
     """Owns the three device buffers (torch tensors) and a context over them."""
 
     def __init__(self, cfg, device="cuda:0", max_batch: int | None = None, stream=None, n_streams: int = 0,
-                 schedule: str = "sync"):
+                 schedule: str = "sync", debug: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the local-update step runs only on the HIP device")
         self.torch = torch
         self.cfg = cfg
         self.device = torch.device(device)
-        self.spec, self._keep = make_spec(cfg, max_batch, n_streams, schedule)
+        self.spec, self._keep = make_spec(cfg, max_batch, n_streams, schedule, debug)
         sz = lp_query_sizes(self.spec)
         self.sizes = sz
         with torch.cuda.device(self.device):

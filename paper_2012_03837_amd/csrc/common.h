@@ -2,6 +2,7 @@
 // kernel-launch API ("ops") that the layer drivers call.  gfx950 only.
 #pragma once
 #include <map>
+#include <string>
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -73,15 +74,19 @@ struct ConvArgs {
 
 // Optional per-kernel-class timing with HIP events recorded on the launch stream.
 enum KernelClass { KC_GEMM = 0, KC_ATTN_FWD, KC_ATTN_BWD, KC_LAYERNORM, KC_SOFTMAX_CE, KC_OPTIMIZER, KC_EMBED,
-                   KC_COLSUM, KC_CONV, KC_BATCHNORM, KC_OTHER, KC_COUNT };
+                   KC_COLSUM, KC_CONV, KC_BATCHNORM, KC_OTHER, KC_GEMM_KERNEL, KC_COUNT };
 struct Profiler {
   bool on = false;
-  struct Pair { hipEvent_t a, b; int kc; uint64_t tag; };
+  struct Pair { hipEvent_t a, b; int kc; uint64_t tag; const char* kname; double flops; };
   Pair* pairs = nullptr; int cap = 0; int used = 0; int dropped = 0;
   double total_ms[KC_COUNT] = {}; long long launches[KC_COUNT] = {}; double flops[KC_COUNT] = {};
   // GEMM ops by shape: tag = M | N << 20 | K << 40 | a_kc << 60 | b_kc << 61 | c_f32 << 62
   struct ShapeTotal { double ms = 0; long long n = 0; };
   std::map<uint64_t, ShapeTotal> by_shape;
+  // Main GEMM kernels by instance name (class KC_GEMM_KERNEL: a pair brackets that one launch, without the
+  // partial-sum fix-up an op may launch behind it): launches, summed time, algorithmic FLOPs.
+  struct KernelTotal { double ms = 0; long long n = 0; double flops = 0; };
+  std::map<std::string, KernelTotal> by_kernel;
 };
 
 struct OpCtx {
@@ -98,15 +103,17 @@ struct OpCtx {
 // RAII bracket: records an event pair around the launches of one op when profiling is on.
 struct ProfScope {
   Profiler* p; hipStream_t s; int idx = -1;
-  ProfScope(const OpCtx& c, int kc, double flops = 0.0, uint64_t tag = 0) : p(c.prof), s(c.stream) {
+  ProfScope(const OpCtx& c, int kc, double flops = 0.0, uint64_t tag = 0, const char* kname = nullptr)
+      : p(c.prof), s(c.stream) {
     if (!p || !p->on) { p = nullptr; return; }
     p->launches[kc] += 1; p->flops[kc] += flops;
     if (p->used >= p->cap) { p->dropped += 1; p = nullptr; return; }
     idx = p->used++;
-    p->pairs[idx].kc = kc; p->pairs[idx].tag = tag;
+    p->pairs[idx].kc = kc; p->pairs[idx].tag = tag; p->pairs[idx].kname = kname; p->pairs[idx].flops = flops;
     (void)hipEventRecord(p->pairs[idx].a, s);
   }
-  ~ProfScope() { if (p) (void)hipEventRecord(p->pairs[idx].b, s); }
+  void finish() { if (p) { (void)hipEventRecord(p->pairs[idx].b, s); p = nullptr; } }
+  ~ProfScope() { finish(); }
 };
 
 // ---- ops (each enqueues on ctx.stream and returns a hipError_t) -------------------------------

@@ -31,6 +31,10 @@ struct ConvUnit {
   float* mean = nullptr;
   float* rstd = nullptr;
   int relu = 0;
+  // debug contexts only: copies of the upstream gradient of the last backward pass and of the input gradient
+  void* dy_keep = nullptr;
+  void* dx_keep = nullptr;
+  bool dx_valid = false;
 };
 struct BasicBlock { ConvUnit c1, c2, proj; bool has_proj = false; };
 
@@ -99,6 +103,14 @@ struct lp_ctx : lp_scratch {
   std::map<std::string, int> index;
   std::vector<lp::LayerState> layers;   // [0] unused; 1..L
   std::vector<lp::HeadState> heads;     // 0-based
+  struct UnitRef { int li, bi, which; };          // which: 0 stem, 1 conv1, 2 conv2, 3 proj
+  std::map<std::string, UnitRef> units;           // "L2.b1.conv1" -> the unit
+  lp::ConvUnit* unit(const UnitRef& r) {
+    lp::LayerState& S = layers[r.li];
+    if (r.which == 0) return &S.stem;
+    lp::BasicBlock& b = S.blocks[r.bi];
+    return r.which == 1 ? &b.c1 : (r.which == 2 ? &b.c2 : &b.proj);
+  }
   size_t P = 0;                         // flat parameter elements
   int dt = 0;
   hipStream_t stream = nullptr;

@@ -188,10 +188,15 @@ static int unit_backward(lp_ctx* c, ConvUnit& u, const void* x, const void* dy, 
                          const void* dx_add = nullptr) {
   OpCtx o = c->op();
   int rows = u.a.N * u.a.P * u.a.Q;
+  const size_t es = dtype_size(c->dt);
+  if (u.dy_keep) DO(hipMemcpyAsync(u.dy_keep, dy, (size_t)rows * u.a.O * es, hipMemcpyDeviceToDevice, o.stream));
   DO(op_batchnorm_bwd(o, dy, u.y, u.z, u.mean, u.rstd, c->P32(u.g), c->sZ, dres, c->G32(u.g), c->G32(u.b), rows,
                       u.a.O, u.relu, acc));
   DO(op_conv_bwd_weight(o, u.a, c->sZ, x, c->G32(u.w), acc));
   if (dx) DO(op_conv_bwd_data(o, u.a, c->sZ, c->W(u.w), dx, dx_add));
+  u.dx_valid = dx != nullptr;
+  if (dx && u.dx_keep)
+    DO(hipMemcpyAsync(u.dx_keep, dx, (size_t)u.a.N * u.a.H * u.a.W * u.a.C * es, hipMemcpyDeviceToDevice, o.stream));
   return LP_OK;
 }
 static void set_batch(ConvUnit& u, int batch) { u.a.N = batch; }

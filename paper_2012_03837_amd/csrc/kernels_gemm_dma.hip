@@ -26,6 +26,7 @@
 // one stream through the ring of stages, so the loader stays NSTAGE-1 k-tiles ahead across item boundaries
 // and the next item's first k-tiles are in flight while a finished item is written; see the comment in the kernel.
 // Requires K % 32 == 0 (no zero fill on this path).
+#include <stdio.h>
 #include <type_traits>
 #include "common.h"
 #include "gemm_common.h"
@@ -704,8 +705,16 @@ hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool parti
   }
   Operand A{(const bf16_t*)g.A, g.lda, g.M}, B{(const bf16_t*)g.B, g.ldb, g.N};
   Epilogue e = make_epilogue(g);
-  kern<<<dim3(p.G), 128 * WNW, smem, c.stream>>>(A, B, e, g.M, g.N, p, c.splitk_ws);
-  hipError_t err = hipGetLastError();
+  static char kname[64];
+  if (!kname[0])
+    snprintf(kname, sizeof kname, "k_gemm_dma<%s, %s, %d, %d, %d, %s>", A_KC ? "true" : "false", B_KC ? "true" : "false",
+             WNW, TN, NSTAGE, PIPE ? "true" : "false");
+  hipError_t err;
+  {
+    ProfScope one_(c, KC_GEMM_KERNEL, 2.0 * g.M * g.N * g.K, 0, kname);
+    kern<<<dim3(p.G), 128 * WNW, smem, c.stream>>>(A, B, e, g.M, g.N, p, c.splitk_ws);
+    err = hipGetLastError();
+  }
   if (err != hipSuccess || !partials) return err;
   k_sk_fixup<WNW, TN><<<dim3((p.sib ? p.tiles_m * p.tiles_n : p.tail_tiles) * (2 * WNW * 8 * TN / 4)), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, p);
   return hipGetLastError();

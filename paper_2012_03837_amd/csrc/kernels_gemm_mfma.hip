@@ -15,6 +15,8 @@
 // accumulate) reads and writes 16 bytes per lane.
 #include <stdio.h>
 #include <stdlib.h>
+#include <map>
+#include <string>
 #include "common.h"
 #include "gemm_common.h"
 #include "mfma_tile.h"
@@ -161,6 +163,12 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   Operand A{(const bf16_t*)g.A, g.lda, g.M}, B{(const bf16_t*)g.B, g.ldb, g.N};
   const int bm = kRegStaged[best_v].bm, tn = (g.N + BN - 1) / BN, tm = (g.M + bm - 1) / bm;
   dim3 grid(tm * tn * splits);
+  char kname_buf[96];
+  snprintf(kname_buf, sizeof kname_buf, "mfma::k_mfma_tiles<mfma::PlainLoader<%s>, mfma::PlainLoader<%s>, %d>",
+           g.a_kc ? "true" : "false", g.b_kc ? "true" : "false", bm);
+  static std::map<std::string, std::string> names;       // stable storage for the profiler's name pointers
+  const char* kname = names.emplace(kname_buf, kname_buf).first->second.c_str();
+  ProfScope one_(c, KC_GEMM_KERNEL, 2.0 * g.M * g.N * g.K, 0, kname);
 #define LP_GEMM(AK, BK_, BM_)                                                                             \
   k_mfma_tiles<PlainLoader<AK>, PlainLoader<BK_>, BM_><<<grid, 256, 0, c.stream>>>(                       \
       PlainLoader<AK>{A}, PlainLoader<BK_>{B}, e, g.M, g.N, g.K, tm, tn, splits, c.splitk_ws)
@@ -172,6 +180,7 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
 #undef LP_GEMM_BM
 #undef LP_GEMM
   hipError_t err = hipGetLastError();
+  one_.finish();
   if (err != hipSuccess || splits == 1) return err;
   size_t work = (size_t)g.M * (g.N / 8);
   k_splitk_reduce<<<(unsigned)((work + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, splits);

@@ -9,6 +9,7 @@
 using namespace lp;
 
 static thread_local std::string g_init_err;
+static int join_pending(lp_ctx* c);
 
 static int fail(lp_ctx* c, int code, const std::string& msg) {
   if (c) c->err = msg; else g_init_err = msg;
@@ -247,7 +248,7 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
         size_t nin = (size_t)B * u.a.H * u.a.W * u.a.C;
         if (n > max_act) max_act = n;
         if (nin > max_act) max_act = nin;
-        size_t rows = (size_t)B * u.a.P * u.a.Q;
+        if (sp.debug) { u.dy_keep = wa.take(n * es); u.dx_keep = wa.take(nin * es); }
         size_t pr = (size_t)(2 * 1024 + 2) * u.a.O;   // up to 1024 row slabs, two sums each, plus the totals
         if (pr > partial) partial = pr;
       };
@@ -256,6 +257,7 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
       if (S.has_stem) {
         S.stem = make_unit(c, p + "stem.w", p + "stem.bn.", B, hw_in, l.in_ch, l.out_ch, 3, 1, 1, 1);
         alloc_unit(S.stem);
+        c->units[p + "stem"] = {li, 0, 0};
       }
       for (int b = 0; b < l.n_basic_blocks; ++b) {
         std::string q = p + "b" + std::to_string(b + 1) + ".";
@@ -270,6 +272,9 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
         if (bb.has_proj) bb.proj = make_unit(c, q + "proj.w", q + "proj.bn.", B, hin, cin, l.out_ch, 1, stride, 0, 0);
         alloc_unit(bb.c1); alloc_unit(bb.c2);
         if (bb.has_proj) alloc_unit(bb.proj);
+        c->units[q + "conv1"] = {li, b, 1};
+        c->units[q + "conv2"] = {li, b, 2};
+        if (bb.has_proj) c->units[q + "proj"] = {li, b, 3};
         S.blocks.push_back(bb);
       }
       // the stage output is the last block's y; keep `out` as an alias instead of a copy
@@ -478,6 +483,7 @@ static void prof_free(lp_ctx* c) {
 }
 // Folds finished event pairs into the per-class totals.
 static int prof_collect(lp_ctx* c) {
+  { int sj = join_pending(c); if (sj != LP_OK) return sj; }
   if (c->prof.used == 0) return LP_OK;
   CK(hipStreamSynchronize(c->stream));
   for (int i = 0; i < c->prof.used; ++i) {
@@ -485,6 +491,10 @@ static int prof_collect(lp_ctx* c) {
     CK(hipEventElapsedTime(&ms, c->prof.pairs[i].a, c->prof.pairs[i].b));
     c->prof.total_ms[c->prof.pairs[i].kc] += ms;
     if (c->prof.pairs[i].tag) { auto& t = c->prof.by_shape[c->prof.pairs[i].tag]; t.ms += ms; t.n += 1; }
+    if (c->prof.pairs[i].kname) {
+      auto& t = c->prof.by_kernel[c->prof.pairs[i].kname];
+      t.ms += ms; t.n += 1; t.flops += c->prof.pairs[i].flops;
+    }
   }
   c->prof.used = 0;
   return LP_OK;
@@ -493,6 +503,7 @@ static int prof_collect(lp_ctx* c) {
 extern "C" int lp_profile_enable(lp_ctx* c, int on) {
   if (!c) return LP_EINVAL;
   if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
+  { int sj = join_pending(c); if (sj != LP_OK) return sj; }
   if (on && !c->prof.pairs) {
     const int cap = 8192;
     c->prof.pairs = new Profiler::Pair[cap];
@@ -508,6 +519,7 @@ extern "C" int lp_profile_enable(lp_ctx* c, int on) {
     for (int k = 0; k < KC_COUNT; ++k) { c->prof.total_ms[k] = 0; c->prof.launches[k] = 0; c->prof.flops[k] = 0; }
     c->prof.dropped = 0;
     c->prof.by_shape.clear();
+    c->prof.by_kernel.clear();
   }
   c->prof.on = on != 0;
   return LP_OK;
@@ -539,6 +551,22 @@ extern "C" int lp_profile_gemm_shapes(lp_ctx* c, char* out, size_t cap) {
     text += line;
   }
   if (text.size() + 1 > cap) return fail(c, LP_ESHAPE, "buffer too small for the shape table");
+  memcpy(out, text.c_str(), text.size() + 1);
+  return LP_OK;
+}
+
+extern "C" int lp_profile_gemm_kernels(lp_ctx* c, char* out, size_t cap) {
+  if (!c) return LP_EINVAL;
+  if (!out || cap == 0) return fail(c, LP_EINVAL, "out is null or empty");
+  int st = prof_collect(c);
+  if (st != LP_OK) return st;
+  std::string text;
+  for (const auto& kv : c->prof.by_kernel) {
+    char line[96];
+    snprintf(line, sizeof line, "\t%lld\t%.6f\t%.6e\n", kv.second.n, kv.second.ms, kv.second.flops);
+    text += kv.first + line;
+  }
+  if (text.size() + 1 > cap) return fail(c, LP_ESHAPE, "buffer too small for the kernel table");
   memcpy(out, text.c_str(), text.size() + 1);
   return LP_OK;
 }
@@ -772,6 +800,7 @@ extern "C" int lp_step_graph(lp_ctx* c, int on) {
   if (on && c->spec.schedule == LP_SCHED_PIPELINED)
     return fail(c, LP_EINVAL, "graph replay is for the synchronous schedule");
   if (on && c->overlap_steps) return fail(c, LP_EINVAL, "overlapped steps are not replayed through a graph");
+  { int sj = join_pending(c); if (sj != LP_OK) return sj; }
   if (!on) drop_graph(c);
   c->graph_on = on != 0;
   return LP_OK;
@@ -798,6 +827,7 @@ extern "C" int lp_bn_running(lp_ctx* c, float momentum, int eval_with_running) {
   if (!c) return LP_EINVAL;
   if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
   if (!(momentum >= 0.f && momentum <= 1.f)) return fail(c, LP_EINVAL, "momentum must lie in [0, 1]");
+  { int sj = join_pending(c); if (sj != LP_OK) return sj; }
   if (momentum != c->bn_momentum) drop_graph(c);   // a captured step has the old weight baked into its launches
   c->bn_momentum = momentum;
   c->bn_eval_running = eval_with_running != 0;
@@ -819,6 +849,7 @@ static int resolve(lp_ctx* c, const char* name, Resolved* r) {
   if (!c) return LP_EINVAL;
   if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
   if (!name) return fail(c, LP_EINVAL, "name is null");
+  { int sj = join_pending(c); if (sj != LP_OK) return sj; }
   std::string n(name);
   memset(r, 0, sizeof *r);
   auto suffix = [&](const char* s) { size_t k = strlen(s); return n.size() > k && n.compare(n.size() - k, k, s) == 0; };
@@ -842,6 +873,25 @@ static int resolve(lp_ctx* c, const char* name, Resolved* r) {
     for (int i = 0; i < r->ndim; ++i) r->numel *= (size_t)r->shape[i];
     r->bytes = r->numel * dtype_size(c->dt);
     return LP_OK;
+  }
+  if (suffix(".z") || suffix(".y") || suffix(".dy") || suffix(".dx")) {
+    const size_t dot = n.rfind('.');
+    auto ui = c->units.find(n.substr(0, dot));
+    if (ui != c->units.end()) {
+      ConvUnit* u = c->unit(ui->second);
+      const std::string leaf = n.substr(dot + 1);
+      const int B = c->last_batch;
+      const bool in_shaped = leaf == "dx";
+      r->ptr = leaf == "z" ? u->z : leaf == "y" ? u->y : leaf == "dy" ? u->dy_keep : (u->dx_valid ? u->dx_keep : nullptr);
+      if (!r->ptr) return fail(c, LP_ENOTFOUND, "no tensor " + n + " (debug contexts only; .dx only where the unit computed one)");
+      r->ndim = 4; r->shape[0] = B;
+      r->shape[1] = in_shaped ? u->a.H : u->a.P; r->shape[2] = in_shaped ? u->a.W : u->a.Q;
+      r->shape[3] = in_shaped ? u->a.C : u->a.O;
+      r->dtype = c->dt;
+      r->numel = (size_t)B * r->shape[1] * r->shape[2] * r->shape[3];
+      r->bytes = r->numel * dtype_size(c->dt);
+      return LP_OK;
+    }
   }
   if (suffix(".running_mean") || suffix(".running_var")) {
     const bool is_var = suffix(".running_var");
@@ -936,10 +986,15 @@ extern "C" int lp_grad_cosine(lp_ctx* a, lp_ctx* b, float* out_dev) {
   return LP_OK;
 }
 
-extern "C" int lp_get_step(lp_ctx* c) { return c ? c->step_t : -1; }
+extern "C" int lp_get_step(lp_ctx* c) {
+  if (!c) return -1;
+  if (c->ok) (void)join_pending(c);
+  return c->step_t;
+}
 extern "C" int lp_set_step(lp_ctx* c, int t) {
   if (!c) return LP_EINVAL;
   if (t < 0) return fail(c, LP_EINVAL, "step must be >= 0");
+  if (c->ok) { int sj = join_pending(c); if (sj != LP_OK) return sj; }
   c->step_t = t;
   // pipelined schedule: block j has taken part in every call from the j-th on
   for (size_t j = 1; j < c->blk_updates.size(); ++j) c->blk_updates[j] = t - (int)(j - 1) > 0 ? t - (int)(j - 1) : 0;

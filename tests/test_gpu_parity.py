@@ -21,7 +21,8 @@ def lpmod():
     return lp
 
 
-from gpu_util import compare_step, data_for, generic_params, relerr, stored_for, tol_for  # noqa: E402
+from gpu_util import (check_resnet_stage_by_unit, compare_step, data_for, generic_params, relerr, stored_for,  # noqa: E402
+                      tol_for)
 
 
 SMALL = ["cfg1_small", "cfg2_small", "cfg3_small", "cfg4_small", "cfg5_small"]
@@ -195,15 +196,19 @@ def test_gradient_cosines_local_vs_backprop(lpmod, name, dtype, tol):
     tb.close()
 
 
-@pytest.mark.parametrize("name", ["cfg1_small", "cfg3_small", "cfg2_small", "cfg5_small"])
-def test_pipelined_schedule_matches_oracle(lpmod, name):
+@pytest.mark.parametrize("name,dtype", [("cfg1_small", "f32"), ("cfg3_small", "f32"), ("cfg2_small", "f32"),
+                                        ("cfg5_small", "f32"), ("cfg3_small", "bf16"), ("cfg5_small", "bf16")])
+def test_pipelined_schedule_matches_oracle(lpmod, name, dtype):
     """The pipelined schedule (section 6; labels travel with the activations, section 3) over J + 2 calls with a
     different minibatch each: losses (exactly 0 while a block waits for its first input), every block's
     parameters and optimizer moments after the last call, against the oracle's delay line; and the same
-    bits with the blocks spread over side streams."""
-    cfg = dataclasses.replace(LI.make_config(name), dtype="f32")
+    bits with the blocks spread over side streams.  On the bf16 path (decoders: smooth networks, exact
+    oracle) the losses are held to 2e-2 call by call; weights after several Adam steps are compared where the
+    accumulated update is well conditioned (see updated_param_err) and the moments in full."""
+    cfg = dataclasses.replace(LI.make_config(name), dtype=dtype)
     J = len(cfg.heads)
     P0 = generic_params(cfg)
+    ltol, ptol, stol = (1e-4, 2e-4, 4e-4) if dtype == "f32" else (2e-2, 2e-2, 4e-2)
     finals = []
     for ns in (0, 2):
         tr = lpmod.LocalTrainer(cfg, schedule="pipelined", n_streams=ns)
@@ -219,13 +224,13 @@ def test_pipelined_schedule_matches_oracle(lpmod, name):
                 if t < j + 1:
                     assert got[j] == 0.0 and ref[j] == 0.0, (t, j)
                 else:
-                    assert abs(got[j] - ref[j]) <= 1e-4 * abs(ref[j]), (name, t, j, got[j], ref[j])
+                    assert abs(got[j] - ref[j]) <= ltol * abs(ref[j]), (name, t, j, got[j], ref[j])
         got_params = tr.get_params()
         for k in P0:
-            assert relerr(got_params[k], P[k]) <= 2e-4, (name, k, relerr(got_params[k], P[k]))
+            assert relerr(got_params[k], P[k]) <= ptol, (name, k, relerr(got_params[k], P[k]))
             for sname in ("m", "v"):
                 if sname in st:
-                    assert relerr(tr.get(k + "." + sname), st[sname][k]) <= 4e-4, (name, sname, k)
+                    assert relerr(tr.get(k + "." + sname), st[sname][k]) <= stol, (name, sname, k)
         finals.append(got_params)
         tr.close()
     for k in P0:
@@ -448,3 +453,79 @@ def test_overlapped_steps_bit_identical(lpmod, name, ns):
     assert outs[0][2].keys() == outs[1][2].keys()
     for k in outs[0][2]:
         np.testing.assert_array_equal(outs[0][2][k], outs[1][2][k])
+
+
+@pytest.mark.parametrize("joiner", ["bn_running", "get_step", "set_step", "tensor_info", "step_graph_off", "profile_read"])
+def test_every_context_call_joins_overlapped_steps(lpmod, joiner):
+    """With overlapped steps the chains of the last step run on the library's side streams.  Every entry point that
+    takes the context (other than lp_local_step and the three host-only string / count queries) makes the caller's
+    stream wait for them: after such a call, synchronising the caller's stream alone must be enough to read the
+    losses and the updated weights of the last step."""
+    import torch
+    cfg = LI.make_config("cfg2_small")
+    x, y = data_for(cfg)
+    ref = None
+    for overlap in (False, True):
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            tr = lpmod.LocalTrainer(cfg, n_streams=3, stream=s)
+            tr.set_params(generic_params(cfg))
+            xd, yd = tr.stage(x, y)
+            if overlap:
+                tr.overlap_steps(True)
+            for _ in range(3):
+                tr.step(xd, yd)
+            if overlap:
+                if joiner == "bn_running":
+                    tr.bn_running(0.1, False)
+                elif joiner == "get_step":
+                    assert lpmod.lp_get_step(tr.ctx) == 3
+                elif joiner == "set_step":
+                    lpmod.lp_set_step(tr.ctx, 3)
+                elif joiner == "tensor_info":
+                    lpmod.lp_tensor_info(tr.ctx, "L1.out")
+                elif joiner == "step_graph_off":
+                    tr.step_graph(False)
+                else:
+                    lpmod.lp_profile_read(tr.ctx, 0)
+            s.synchronize()                      # the caller's stream only
+            losses = tr.losses.clone()
+            w = tr.params.clone()
+        torch.cuda.synchronize()
+        got = (losses.cpu().numpy().copy(), w.cpu().numpy().copy())
+        tr.close()
+        if ref is None:
+            ref = got
+        else:
+            np.testing.assert_array_equal(ref[0], got[0])
+            np.testing.assert_array_equal(ref[1], got[1])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("nbb", [1, 2])
+def test_resnet_units_against_exact_oracle(lpmod, dtype, nbb):
+    """Every convolution + normalisation unit of a ResNet step against the exact float64 oracle (no storage
+    rounding on the oracle's side), fed the device's own unit input, shortcut input and upstream gradient;
+    the tensors that tie the units together are compared bit for bit (see check_resnet_stage_by_unit)."""
+    cfg = dataclasses.replace(LI.make_config("cfg2_small", n_basic_blocks=nbb), dtype=dtype)
+    print(f"[case] resnet units {dtype} blocks/stage {nbb}", flush=True)
+    tr = lpmod.LocalTrainer(cfg, n_streams=2, debug=True)
+    P0 = generic_params(cfg)
+    tr.set_params(P0)
+    x, y = data_for(cfg)
+    xd, yd = tr.stage(x, y)
+    tr.step(xd, yd)
+    tol = tol_for(cfg)
+    for hi in range(1, len(cfg.heads) + 1):
+        w = check_resnet_stage_by_unit(tr, cfg, hi, P0, x, y, tol, label=f"units/{dtype}")
+        print(f"  stage {hi}: worst rel err {w:.2e}", flush=True)
+    # without the debug flag the gradient copies do not exist
+    tr.close()
+    tr = lpmod.LocalTrainer(cfg)
+    tr.set_params(P0)
+    tr.step(*tr.stage(x, y))
+    assert tr.get("L1.stem.y").shape == (cfg.batch, 12, 12, 8)
+    with pytest.raises(lpmod.LpError) as e:
+        tr.get("L1.stem.dy")
+    assert e.value.status == 8
+    tr.close()

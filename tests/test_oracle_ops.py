@@ -322,3 +322,92 @@ def test_stored_precision_mode_keeps_structure():
     assert set(g0) == set(g1)
     assert np.abs(l0 - l1).max() < 2e-2
     assert np.abs(l0 - l1).max() > 0
+
+
+# ----------------------------------------------------------------------------- storage rounding rule
+# The rule of the oracle's stored="bf16" mode, stated on its own: in a "bf16 compute, fp32 master weights"
+# configuration every tensor that one operation hands to the next through memory is a bf16 tensor: the input,
+# the matrix weights as the passes see them, each convolution output, each normalisation (+ shortcut) (+ ReLU)
+# output, the pooled features and the logits.  What lives inside an operation (sums, batch statistics, the
+# normalised value before it is stored) and every quantity of the backward pass is exact.  A ReLU's derivative
+# is read off the stored output (out > 0), and rounding passes gradients through unchanged.
+# The pin below builds the same network from torch's own convolution / batch-norm / cross-entropy routines with
+# autograd, applies that rule with two tiny autograd functions, and must reproduce the oracle to rounding error;
+# a rounding dropped from, added to or moved inside the oracle changes values by ~2^-9 and fails it.
+class _StoreBf16(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, t):
+        return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+    @staticmethod
+    def backward(ctx, g):
+        return g
+
+
+class _ReluStoreBf16(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, t):
+        out = torch.relu(t).to(torch.float32).to(torch.bfloat16).to(torch.float64)
+        ctx.save_for_backward(out)
+        return out
+
+    @staticmethod
+    def backward(ctx, g):
+        (out,) = ctx.saved_tensors
+        return g * (out > 0).to(g.dtype)
+
+
+@pytest.mark.parametrize("head", ["pool_linear_ce", "bn_pool_linear_ce"])
+def test_stored_precision_rule_vs_torch_straight_through(head):
+    import oracle
+    cfg = LI.configs.resnet_config("t", channels=(4, 6), in_hw=6, in_ch=3, n_classes=3, batch=5,
+                                   n_basic_blocks=2, scheme="greedy", head=head)
+    P = LI.perturb_params(LI.init_params(cfg, seed=2, head_scale=3.0), 4, 0.2)
+    P = {k: v.astype(np.float64) for k, v in P.items()}
+    x, y = LI.make_batch(cfg, 0)
+    x = ops.bf16_round(x.astype(np.float64))
+    losses, grads, _ = oracle.local_gradients(cfg, P, x, y, stored="bf16")
+    exact_losses, exact_grads, _ = oracle.local_gradients(cfg, P, x, y)
+    tP = {k: T(v.transpose(0, 3, 1, 2) if v.ndim == 4 else v, True) for k, v in P.items()}
+    W = {k: (_StoreBf16.apply(v) if v.ndim >= 2 else v) for k, v in tP.items()}      # matrices as the passes see them
+    F = torch.nn.functional
+    st, rl = _StoreBf16.apply, _ReluStoreBf16.apply
+
+    def cb(h, w, bn, stride, pad, relu, res=None):
+        z = st(F.conv2d(h, W[w], stride=stride, padding=pad))
+        v = F.batch_norm(z, None, None, W[bn + "g"], W[bn + "b"], training=True, eps=1e-5)
+        if res is not None:
+            v = v + res
+        return rl(v) if relu else st(v)
+
+    def stage(h, li, stride0):
+        if li == 1:
+            h = cb(h, "L1.stem.w", "L1.stem.bn.", 1, 1, True)
+        for b in (1, 2):
+            q = f"L{li}.b{b}."
+            s_ = stride0 if b == 1 else 1
+            t = cb(h, q + "conv1.w", q + "bn1.", s_, 1, True)
+            sc = cb(h, q + "proj.w", q + "proj.bn.", s_, 0, False) if (q + "proj.w") in W else h
+            h = cb(t, q + "conv2.w", q + "bn2.", 1, 1, True, res=sc)
+        return h
+
+    def head_loss(h, hi):
+        p = f"H{hi}."
+        if head == "bn_pool_linear_ce":
+            h = rl(F.batch_norm(h, None, None, W[p + "bn.g"], W[p + "bn.b"], training=True, eps=1e-5))
+        feat = st(h.mean(dim=(2, 3)))
+        z = st(F.linear(feat, W[p + "w"], W[p + "b"]))
+        return F.cross_entropy(z, torch.tensor(y).long())
+
+    h1 = stage(T(x.transpose(0, 3, 1, 2)), 1, 1)
+    l1 = head_loss(h1, 1)
+    h2 = stage(h1.detach(), 2, 2)           # the block's input is data
+    l2 = head_loss(h2, 2)
+    (l1 + l2).backward()
+    assert abs(l1.item() - losses[0]) < 1e-12 and abs(l2.item() - losses[1]) < 1e-12
+    assert abs(losses[0] - exact_losses[0]) > 1e-7       # the rounding is really there
+    for k in P:
+        tg = tP[k].grad
+        close(grads[k], tg.permute(0, 2, 3, 1) if tg.ndim == 4 else tg, 1e-10)
+    # and the mode stays within the bf16 tolerance of the exact step on this network
+    assert max(abs(losses - exact_losses) / exact_losses) < 2e-2
