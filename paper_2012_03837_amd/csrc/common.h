@@ -118,6 +118,9 @@ struct ProfScope {
 
 // ---- ops (each enqueues on ctx.stream and returns a hipError_t) -------------------------------
 hipError_t op_gemm(const OpCtx& c, const GemmArgs& g);
+// n independent products in one launch where they qualify (bf16, same reduction length and operand layouts,
+// plain fp32 outputs: the weight gradients of one layer), otherwise one after the other.
+hipError_t op_gemm_grouped(const OpCtx& c, const GemmArgs* gs, int n);
 hipError_t op_fill_f32(const OpCtx& c, float* p, size_t n, float v);
 // out[0] = <a, b> / (|a| |b|) over n floats (0 if either norm is 0); uses 3 * 128 floats of c.partial
 hipError_t op_cosine(const OpCtx& c, const float* a, const float* b, size_t n, float* out);

@@ -145,25 +145,28 @@ static int dec_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx
   int S = L.s.seq_len, d = L.s.width, H = L.s.n_heads, F = L.s.hidden, T = batch * S;
   const void* x = layer_input(c, li);
   bool has_emb = (li == 1 && c->spec.vocab > 0);
+  // The four weight gradients read (dY, X) pairs that all stay alive until the end of the layer's backward pass and
+  // nothing in the pass reads them: they are collected and launched together at the end (one grouped launch).
+  GemmArgs wg[4];
   // FFN
   DO(op_colsum(o, dout, d, c->G32(L.t["b2"]), T, d, acc));
-  DO(op_gemm(o, lin_wgrad(c, dout, L.f, T, L.t["w2"], acc)));
+  wg[0] = lin_wgrad(c, dout, L.f, T, L.t["w2"], acc);
   GemmArgs gd = lin_dgrad(c, dout, T, L.t["w2"], c->dF);
   gd.dact = L.s.act == LP_ACT_RELU ? ACT_RELU : ACT_GELU; gd.dact_src = L.fpre; gd.ldd = F;
   DO(op_gemm(o, gd));
   DO(op_colsum(o, c->dF, F, c->G32(L.t["b1"]), T, F, acc));
-  DO(op_gemm(o, lin_wgrad(c, c->dF, L.c, T, L.t["w1"], acc)));
+  wg[1] = lin_wgrad(c, c->dF, L.c, T, L.t["w1"], acc);
   DO(op_gemm(o, lin_dgrad(c, c->dF, T, L.t["w1"], c->dc)));
   // du = dout + LN2-backward(dc)
   DO(op_layernorm_bwd(o, c->dc, L.u, L.mean2, L.rstd2, c->P32(L.t["ln2.g"]), dout, c->du, c->G32(L.t["ln2.g"]),
                       c->G32(L.t["ln2.b"]), T, d, acc));
   // attention block
   DO(op_colsum(o, c->du, d, c->G32(L.t["bo"]), T, d, acc));
-  DO(op_gemm(o, lin_wgrad(c, c->du, L.o, T, L.t["wo"], acc)));
+  wg[2] = lin_wgrad(c, c->du, L.o, T, L.t["wo"], acc);
   DO(op_gemm(o, lin_dgrad(c, c->du, T, L.t["wo"], c->dO)));
   DO(op_attn_bwd(o, L.qkv, L.o, L.lse, c->dO, c->dqkv, c->delta, batch, S, H, d / H, L.s.causal));
   DO(op_colsum(o, c->dqkv, 3 * d, c->G32(L.t["bqkv"]), T, 3 * d, acc));
-  DO(op_gemm(o, lin_wgrad(c, c->dqkv, L.a, T, L.t["wqkv"], acc)));
+  wg[3] = lin_wgrad(c, c->dqkv, L.a, T, L.t["wqkv"], acc);
   DO(op_gemm(o, lin_dgrad(c, c->dqkv, T, L.t["wqkv"], c->da)));
   // dh = du + LN1-backward(da); the input gradient itself is only needed inside a window or for the embedding
   bool want_dx = need_dx || has_emb;
@@ -171,6 +174,7 @@ static int dec_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx
   DO(op_layernorm_bwd(o, c->da, x, L.mean1, L.rstd1, c->P32(L.t["ln1.g"]), c->du, dh, c->G32(L.t["ln1.g"]),
                       c->G32(L.t["ln1.b"]), T, d, acc));
   if (has_emb) DO(op_embed_bwd(o, ids, dh, c->G32(L.t["emb"]), T, c->spec.vocab, d, acc));
+  DO(op_gemm_grouped(o, wg, 4));
   return LP_OK;
 }
 

@@ -81,8 +81,11 @@ __global__ void __launch_bounds__(256) k_ln_fwd_v(const bf16_t* __restrict__ x, 
   if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
 }
 
-constexpr int kRowsPerBlock = 8;
-// Backward; block partials of dg and db go to partial[blk][d] and partial[nblk + blk][d].
+constexpr int kRowsPerBlock = 16;
+// Backward; block partials of dg and db go to partial[blk][d] and partial[nblk + blk][d].  A wave owns four
+// rows of its block's sixteen and keeps the next row's loads (x, dy and the addend, 16 bytes per lane each) in
+// flight while it reduces and writes the current one: with one row at a time the kernel is a chain of memory
+// latencies, not a stream.
 template <int NCH>
 __global__ void __launch_bounds__(256) k_ln_bwd_v(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
                                                   const float* __restrict__ mean, const float* __restrict__ rstd,
@@ -102,27 +105,42 @@ __global__ void __launch_bounds__(256) k_ln_bwd_v(const bf16_t* __restrict__ dy,
   }
   const int row0 = blockIdx.x * kRowsPerBlock;
   const float invd = 1.f / (float)d;
-  for (int r = w; r < kRowsPerBlock; r += 4) {
-    const int row = row0 + r;
+  constexpr int RPW = kRowsPerBlock / 4;
+  bf16x8 xr[2][NCH], dr[2][NCH], ar[2][NCH];
+  float mu[2], rs[2];
+  auto fetch = [&](int slot, int row) {
+    if (row >= rows) return;
+    mu[slot] = mean[row]; rs[slot] = rstd[row];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nch) {
+        xr[slot][i] = *reinterpret_cast<const bf16x8*>(x + (size_t)row * d + 8 * c);
+        dr[slot][i] = *reinterpret_cast<const bf16x8*>(dy + (size_t)row * d + 8 * c);
+        if (add && dx) ar[slot][i] = *reinterpret_cast<const bf16x8*>(add + (size_t)row * d + 8 * c);
+      }
+    }
+  };
+  fetch(0, row0 + w);
+#pragma unroll
+  for (int it = 0; it < RPW; ++it) {
+    const int row = row0 + w + 4 * it, cur = it & 1;
     if (row >= rows) break;
-    const float mu = mean[row], rs = rstd[row];
+    if (it + 1 < RPW) fetch(cur ^ 1, row + 4);
     float xh[NCH][8], dxh[NCH][8];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      int c = lane + 64 * i;
-      if (c < nch) {
-        float xv[8], dv[8];
-        load8(x + (size_t)row * d + 8 * c, xv);
-        load8(dy + (size_t)row * d + 8 * c, dv);
+      if (lane + 64 * i < nch) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          xh[i][e] = (xv[e] - mu) * rs;
-          dxh[i][e] = dv[e] * gg[i][e];
+          const float dv = (float)dr[cur][i][e];
+          xh[i][e] = ((float)xr[cur][i][e] - mu[cur]) * rs[cur];
+          dxh[i][e] = dv * gg[i][e];
           s1 += dxh[i][e];
           s2 += dxh[i][e] * xh[i][e];
-          pg[i][e] += dv[e] * xh[i][e];
-          pb[i][e] += dv[e];
+          pg[i][e] += dv * xh[i][e];
+          pb[i][e] += dv;
         }
       }
     }
@@ -135,12 +153,10 @@ __global__ void __launch_bounds__(256) k_ln_bwd_v(const bf16_t* __restrict__ dy,
         if (c < nch) {
           float o[8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] = (dxh[i][e] - s1 - xh[i][e] * s2) * rs;
+          for (int e = 0; e < 8; ++e) o[e] = (dxh[i][e] - s1 - xh[i][e] * s2) * rs[cur];
           if (add) {
-            float a[8];
-            load8(add + (size_t)row * d + 8 * c, a);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] += a[e];
+            for (int e = 0; e < 8; ++e) o[e] += (float)ar[cur][i][e];
           }
           store8(dx + (size_t)row * d + 8 * c, o);
         }

@@ -194,6 +194,23 @@ struct SkPlan {
   int tiles_m, tiles_n, kt;
   int full, tail_tiles, upb, G;
   int sib;      // 0: ordinary; otherwise tiles_n (panel mode)
+  int ngrp;     // 0: one problem; otherwise the number of problems of a grouped launch (see GroupTable)
+};
+
+// Grouped launch: up to kMaxGroup independent products with the same reduction length, operand layouts and a
+// plain fp32 epilogue (the weight gradients of one layer: dW_i = dY_i^T X_i over the same rows) run as ONE
+// persistent launch.  Their output tiles are numbered one problem after the other (row-major inside a
+// problem, first[i] = number of the i-th problem's first tile), and that one sequence of tiles is spread over
+// the grid exactly like a single problem's: whole tiles first, the last partial wave cut along k.  Each
+// launch by itself has too few tiles for 256 CUs (9 to 36 tiles of 256 x 256 for a width of 768); together
+// they fill the chip with pieces a third to a half as many.
+constexpr int kMaxGroup = 8;
+struct GroupTable {
+  Operand A[kMaxGroup], B[kMaxGroup];
+  void* C[kMaxGroup];
+  int64_t ldc[kMaxGroup];
+  int tiles_n[kMaxGroup];
+  int first[kMaxGroup + 1];
 };
 
 __device__ __forceinline__ void tile_coords(int q, int tiles_m, int tiles_n, int& tm, int& tn) {
@@ -207,6 +224,17 @@ __device__ __forceinline__ void tile_coords(int q, int tiles_m, int tiles_n, int
 __device__ __forceinline__ void plan_tile_coords(const SkPlan& p, int q, int& tm, int& tn) {
   if (p.sib) { tm = q / p.tiles_n; tn = q - tm * p.tiles_n; }
   else tile_coords(q, p.tiles_m, p.tiles_n, tm, tn);
+}
+// Grouped launch: problem of tile q and the tile's coordinates inside it.
+__device__ __forceinline__ int group_tile_coords(const GroupTable& gt, int ngrp, int q, int& tm, int& tn) {
+  int g = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i)
+    if (i < ngrp && q >= gt.first[i]) g = i;
+  const int local = q - gt.first[g];
+  tm = local / gt.tiles_n[g];
+  tn = local - tm * gt.tiles_n[g];
+  return g;
 }
 
 // Epilogue of one wave's 128 x 64 sub-tile: lane (li, hf) holds, for row m = ..+li of m-tile j, the
@@ -347,7 +375,7 @@ __device__ __forceinline__ void interleave_hint_loads() {
 
 template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE, bool PIPE>
 __global__ void __launch_bounds__(128 * WNW, (WNW * TN == 4) ? 2 : (WNW == 4 ? 2 : 1))
-k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) {
+k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws, GroupTable gt) {
   constexpr int BN = 32 * TN * WNW, NWAVES = 2 * WNW;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int AI = (A_BYTES / 1024) / NWAVES, BI = (B_BYTES / 1024) / NWAVES, LPT = AI + BI;
@@ -413,11 +441,17 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
   // Writes one finished item: a whole tile through the fused epilogue, a piece of a cut tile as raw partial sums.
   auto write_item = [&](const f32x16 (&acc)[TN][4], const ItemIter& it) {
     int tm, tn;
-    plan_tile_coords(p, it.q, tm, tn);
-    const int cm = tm * BM + wm, cn = tn * BN + wn;
     if (it.ks == 0 && it.ke == p.kt) {
-      store_subtile<TN>(e, acc, cm, cn, li, hf, M, N,
-                        xpose_shape(WNW, TN, PIPE) ? smem + NSTAGE * STAGE_BYTES + wave * XPOSE_BYTES_PER_WAVE : nullptr);
+      char* xs = xpose_shape(WNW, TN, PIPE) ? smem + NSTAGE * STAGE_BYTES + wave * XPOSE_BYTES_PER_WAVE : nullptr;
+      if (p.ngrp) {
+        const int g = __builtin_amdgcn_readfirstlane(group_tile_coords(gt, p.ngrp, it.q, tm, tn));
+        Epilogue eg = e;
+        eg.C = gt.C[g]; eg.ldc = gt.ldc[g];
+        store_subtile<TN>(eg, acc, tm * BM + wm, tn * BN + wn, li, hf, gt.A[g].rows, gt.B[g].rows, xs);
+        return;
+      }
+      plan_tile_coords(p, it.q, tm, tn);
+      store_subtile<TN>(e, acc, tm * BM + wm, tn * BN + wn, li, hf, M, N, xs);
       return;
     }
     float* sp = ws + (size_t)(2 * v + (it.ks == 0 ? 1 : 0)) * (BM * BN);
@@ -467,9 +501,15 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
       if (l_left > 0) return true;
       if (!advance(L)) return false;
       int tm, tn;
-      plan_tile_coords(p, L.q, tm, tn);
-      pa.init(A, tm * BM, wave, lane, L.ks * BK);
-      pb.init(B, tn * BN, wave, lane, L.ks * BK);
+      if (p.ngrp) {
+        const int g = __builtin_amdgcn_readfirstlane(group_tile_coords(gt, p.ngrp, L.q, tm, tn));
+        pa.init(gt.A[g], tm * BM, wave, lane, L.ks * BK);
+        pb.init(gt.B[g], tn * BN, wave, lane, L.ks * BK);
+      } else {
+        plan_tile_coords(p, L.q, tm, tn);
+        pa.init(A, tm * BM, wave, lane, L.ks * BK);
+        pb.init(B, tn * BN, wave, lane, L.ks * BK);
+      }
       lt = 0; l_left = L.ke - L.ks;
       return true;
     };
@@ -583,10 +623,16 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
     int nt = 0;
     auto start_item = [&]() {          // addresses of the item's operands and the first NSTAGE-1 k-tiles' loads
       int tm, tn;
-      plan_tile_coords(p, I.q, tm, tn);
       nt = I.ke - I.ks;
-      pa.init(A, tm * BM, wave, lane, I.ks * BK);
-      pb.init(B, tn * BN, wave, lane, I.ks * BK);
+      if (p.ngrp) {
+        const int g = __builtin_amdgcn_readfirstlane(group_tile_coords(gt, p.ngrp, I.q, tm, tn));
+        pa.init(gt.A[g], tm * BM, wave, lane, I.ks * BK);
+        pb.init(gt.B[g], tn * BN, wave, lane, I.ks * BK);
+      } else {
+        plan_tile_coords(p, I.q, tm, tn);
+        pa.init(A, tm * BM, wave, lane, I.ks * BK);
+        pb.init(B, tn * BN, wave, lane, I.ks * BK);
+      }
 #pragma unroll
       for (int s = 0; s < NSTAGE - 1; ++s)
         if (s < nt) {
@@ -652,14 +698,20 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws) 
 // One thread per run of 8 columns (the unit of the fused epilogue), with the main kernel's
 // lane-to-element mapping: thread (wave, ij, q, lane) owns acc[i][j][8q .. 8q+7] of that lane.
 template <int WNW, int TN>
-__global__ void __launch_bounds__(256) k_sk_fixup(const float* __restrict__ ws, Epilogue e, int M, int N, SkPlan p) {
+__global__ void __launch_bounds__(256) k_sk_fixup(const float* __restrict__ ws, Epilogue e, int M, int N, SkPlan p,
+                                                  GroupTable gt) {
   constexpr int BN = 32 * TN * WNW, NWAVES = 2 * WNW, UNITS_PER_WAVE = 8 * TN, BLOCKS_PER_TILE = NWAVES * UNITS_PER_WAVE / 4;
   const int tr = blockIdx.x / BLOCKS_PER_TILE;
   const int unit = (blockIdx.x % BLOCKS_PER_TILE) * 4 + (threadIdx.x >> 6);      // (wave, ij, q)
   const int lane = threadIdx.x & 63;
   const int wave = unit / UNITS_PER_WAVE, ij = (unit % UNITS_PER_WAVE) >> 1, q = unit & 1;
   int tm, tn;
-  plan_tile_coords(p, p.sib ? tr : p.full * p.G + tr, tm, tn);
+  if (p.ngrp) {
+    const int g = group_tile_coords(gt, p.ngrp, p.full * p.G + tr, tm, tn);
+    e.C = gt.C[g]; e.ldc = gt.ldc[g]; M = gt.A[g].rows; N = gt.B[g].rows;
+  } else {
+    plan_tile_coords(p, p.sib ? tr : p.full * p.G + tr, tm, tn);
+  }
   const int i = ij >> 2, j = ij & 3, li = lane & 31, hf = lane >> 5;
   const int m = tm * BM + (wave / WNW) * 128 + 32 * j + li;
   const int n = tn * BN + (wave % WNW) * (32 * TN) + 32 * i + 16 * q + 8 * hf;
@@ -693,7 +745,8 @@ int device_cus() {
 }
 
 template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE, bool PIPE>
-hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool partials) {
+hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool partials, const GroupTable* grp = nullptr,
+                  double flops = 0.0) {
   constexpr int BN = 32 * TN * WNW;
   constexpr int smem = NSTAGE * (BM + BN) * BK * 2 + (xpose_shape(WNW, TN, PIPE) ? 2 * WNW * XPOSE_BYTES_PER_WAVE : 0);
   static bool configured = false;
@@ -710,13 +763,15 @@ hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool parti
     snprintf(kname, sizeof kname, "k_gemm_dma<%s, %s, %d, %d, %d, %s>", A_KC ? "true" : "false", B_KC ? "true" : "false",
              WNW, TN, NSTAGE, PIPE ? "true" : "false");
   hipError_t err;
+  static const GroupTable no_group = {};
+  const GroupTable& gt = grp ? *grp : no_group;
   {
-    ProfScope one_(c, KC_GEMM_KERNEL, 2.0 * g.M * g.N * g.K, 0, kname);
-    kern<<<dim3(p.G), 128 * WNW, smem, c.stream>>>(A, B, e, g.M, g.N, p, c.splitk_ws);
+    ProfScope one_(c, KC_GEMM_KERNEL, grp ? flops : 2.0 * g.M * g.N * g.K, 0, kname);
+    kern<<<dim3(p.G), 128 * WNW, smem, c.stream>>>(A, B, e, g.M, g.N, p, c.splitk_ws, gt);
     err = hipGetLastError();
   }
   if (err != hipSuccess || !partials) return err;
-  k_sk_fixup<WNW, TN><<<dim3((p.sib ? p.tiles_m * p.tiles_n : p.tail_tiles) * (2 * WNW * 8 * TN / 4)), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, p);
+  k_sk_fixup<WNW, TN><<<dim3((p.sib ? p.tiles_m * p.tiles_n : p.tail_tiles) * (2 * WNW * 8 * TN / 4)), 256, 0, c.stream>>>(c.splitk_ws, e, g.M, g.N, p, gt);
   return hipGetLastError();
 }
 
@@ -738,6 +793,7 @@ bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int kind, int mode, DmaGem
   p.tiles_n = (g.N + bn - 1) / bn;
   p.kt = g.K / BK;
   p.sib = 0;
+  p.ngrp = 0;
   const long T = (long)p.tiles_m * p.tiles_n;
   const long min_len = 4, max_cut = 16;                 // shortest piece; most pieces per tile
   auto clamp_upb = [&](long upb, bool within_tile) {
@@ -796,7 +852,7 @@ bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int kind, int mode, DmaGem
 hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d) {
   SkPlan p;
   p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.kt = d.kt; p.full = d.full; p.tail_tiles = d.tail_tiles;
-  p.upb = d.upb; p.G = d.G; p.sib = d.sib;
+  p.upb = d.upb; p.G = d.G; p.sib = d.sib; p.ngrp = 0;
   const bool partials = d.partial_bytes > 0;
 #define LP_DMA(AK, BK_)                                                    \
   (d.kind == 1 ? launch<AK, BK_, 4, 2, 4, true>(c, g, p, partials)                \
@@ -807,6 +863,64 @@ hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d) {
   if (!g.a_kc && g.b_kc) return LP_DMA(false, true);
   return LP_DMA(false, false);
 #undef LP_DMA
+}
+
+// Grouped launch of n products (see GroupTable).  Returns hipErrorInvalidValue if the set does not qualify
+// (the caller then launches them one by one): same K (a multiple of 32), same operand layouts, fp32 output,
+// the same accumulate flag and nothing else fused, at most kMaxGroup problems, workspace for the cut tail.
+hipError_t gemm_dma_grouped(const OpCtx& c, const GemmArgs* gs, int n) {
+  if (n < 2 || n > kMaxGroup || c.dt != BF16) return hipErrorInvalidValue;
+  const GemmArgs& g0 = gs[0];
+  GroupTable gt = {};
+  long T = 0;
+  double flops = 0.0;
+  for (int i = 0; i < n; ++i) {
+    const GemmArgs& g = gs[i];
+    if (!gemm_dma_ok(g) || g.K != g0.K || g.a_kc != g0.a_kc || g.b_kc != g0.b_kc || !g.c_f32 ||
+        g.accumulate != g0.accumulate || g.bias || g.pre || g.act != ACT_NONE || g.dact != ACT_NONE || g.res)
+      return hipErrorInvalidValue;
+    if (g.M % 8 || g.N % 8 || g.lda % 8 || g.ldb % 8 || g.ldc % 8 || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15) ||
+        ((uintptr_t)g.C & 15))
+      return hipErrorInvalidValue;
+    gt.A[i] = Operand{(const bf16_t*)g.A, g.lda, g.M};
+    gt.B[i] = Operand{(const bf16_t*)g.B, g.ldb, g.N};
+    gt.C[i] = g.C; gt.ldc[i] = g.ldc;
+    gt.tiles_n[i] = (g.N + 255) / 256;
+    gt.first[i] = (int)T;
+    T += (long)((g.M + BM - 1) / BM) * gt.tiles_n[i];
+    flops += 2.0 * g.M * g.N * g.K;
+  }
+  for (int i = n; i <= kMaxGroup; ++i) gt.first[i] = (int)T;
+  for (int i = n; i < kMaxGroup; ++i) gt.tiles_n[i] = 1;
+  SkPlan p;
+  p.G = device_cus() & ~7;
+  p.tiles_m = (int)T; p.tiles_n = 1;                 // only the product is used outside the tile numbering
+  p.kt = g0.K / BK;
+  p.sib = 0; p.ngrp = n;
+  p.full = (int)(T / p.G);
+  p.tail_tiles = (int)(T - (long)p.full * p.G);
+  p.upb = p.kt;
+  bool partials = false;
+  if (p.tail_tiles > 0) {
+    const long U = (long)p.tail_tiles * p.kt;
+    long upb = (U + p.G - 1) / p.G;
+    if (upb < 4) upb = 4;
+    if (upb * 16 < p.kt) upb = (p.kt + 15) / 16;
+    if (upb > p.kt) upb = p.kt;
+    p.upb = (int)upb;
+    if (p.upb < p.kt) {
+      partials = true;
+      if (!c.splitk_ws || (size_t)2 * p.G * BM * 256 > c.splitk_elems) return hipErrorInvalidValue;
+    }
+  }
+  ProfScope prof_(c, KC_GEMM, flops);
+  GemmArgs g = g0;                                    // epilogue flags (fp32 output, accumulate) are common
+#define LP_DMA_G(AK, BK_) launch<AK, BK_, 4, 2, 4, true>(c, g, p, partials, &gt, flops)
+  if (g.a_kc && g.b_kc) return LP_DMA_G(true, true);
+  if (g.a_kc && !g.b_kc) return LP_DMA_G(true, false);
+  if (!g.a_kc && g.b_kc) return LP_DMA_G(false, true);
+  return LP_DMA_G(false, false);
+#undef LP_DMA_G
 }
 
 }  // namespace lp

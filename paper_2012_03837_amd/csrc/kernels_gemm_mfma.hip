@@ -27,6 +27,7 @@ hipError_t gemm_plain(const OpCtx& c, const GemmArgs& g);
 bool gemm_dma_ok(const GemmArgs& g);
 bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int kind, int mode, DmaGemmPlan* out);
 hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d);
+hipError_t gemm_dma_grouped(const OpCtx& c, const GemmArgs* gs, int n);
 
 namespace {
 
@@ -200,6 +201,28 @@ hipError_t op_gemm(const OpCtx& c, const GemmArgs& g) {
   if (c.gemm_variant >= 2 && !(c.dt == BF16 && fast_ok(g))) return hipErrorInvalidValue;
   if (c.dt == BF16 && !use_plain() && fast_ok(g)) return gemm_mfma(c, g);
   return gemm_plain(c, g);
+}
+
+static bool grouping_off() {     // LP_NO_GROUP=1: every product in a launch of its own (for measurements)
+  static int v = -1;
+  if (v < 0) { const char* s = getenv("LP_NO_GROUP"); v = (s && s[0] == '1') ? 1 : 0; }
+  return v != 0;
+}
+
+hipError_t op_gemm_grouped(const OpCtx& c, const GemmArgs* gs, int n) {
+  if (n >= 2 && c.dt == BF16 && !use_plain() && !grouping_off() && c.gemm_variant == 0 && env_choice() == 0) {
+    bool ok = true;
+    for (int i = 0; i < n; ++i) ok = ok && fast_ok(gs[i]);
+    if (ok) {
+      hipError_t e = gemm_dma_grouped(c, gs, n);
+      if (e != hipErrorInvalidValue) return e;          // launched (or failed for a reason of the device's)
+    }
+  }
+  for (int i = 0; i < n; ++i) {
+    hipError_t e = op_gemm(c, gs[i]);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace lp

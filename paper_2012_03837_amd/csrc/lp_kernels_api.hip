@@ -5,6 +5,7 @@
 namespace lp {
 hipError_t gemm_plain(const OpCtx& c, const GemmArgs& g);
 hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g);
+hipError_t gemm_dma_grouped(const OpCtx& c, const GemmArgs* gs, int n);
 hipError_t attn_fwd_plain(const OpCtx& c, const void* qkv, void* o, float* lse, int B, int S, int H, int dh, int causal);
 hipError_t attn_bwd_plain(const OpCtx& c, const void* qkv, const void* o, const float* lse, const void* dout,
                           void* dqkv, float* delta, int B, int S, int H, int dh, int causal);
@@ -40,6 +41,20 @@ extern "C" int lpk_gemm(int dtype, const void* A, int64_t lda, int a_kc, const v
   if (variant == 1 || dtype != BF16) return (int)gemm_plain(c, g);
   c.gemm_variant = variant;
   return (int)op_gemm(c, g);
+}
+extern "C" int lpk_gemm_grouped(int n, const void* const* A, const int64_t* lda, const void* const* B, const int64_t* ldb,
+                                float* const* C, const int64_t* ldc, const int* M, const int* N, int K, int a_kc,
+                                int b_kc, int accumulate, float* splitk_ws, size_t splitk_ws_elems, void* stream) {
+  if (n < 1 || n > 8 || !A || !lda || !B || !ldb || !C || !ldc || !M || !N) return (int)hipErrorInvalidValue;
+  GemmArgs g[8];
+  for (int i = 0; i < n; ++i) {
+    g[i].A = A[i]; g[i].lda = lda[i]; g[i].a_kc = a_kc; g[i].B = B[i]; g[i].ldb = ldb[i]; g[i].b_kc = b_kc;
+    g[i].C = C[i]; g[i].ldc = ldc[i]; g[i].c_f32 = 1; g[i].M = M[i]; g[i].N = N[i]; g[i].K = K;
+    g[i].accumulate = accumulate;
+  }
+  OpCtx c = mk(BF16, stream);
+  c.splitk_ws = splitk_ws; c.splitk_elems = splitk_ws_elems;
+  return (int)gemm_dma_grouped(c, g, n);
 }
 extern "C" int lpk_attention_fwd(int dtype, const void* qkv, void* o, float* lse, int B, int S, int H, int dh,
                                  int causal, int plain, void* stream) {

@@ -37,6 +37,19 @@ def lpk_gemm(dtype, A, lda, a_kc, B, ldb, b_kc, Cout, ldc, c_f32, M, N, K, bias=
                        _sz(0 if splitk_ws is None else splitk_ws.numel()), _stream()), "lpk_gemm")
 
 
+def lpk_gemm_grouped(As, Bs, Cs, Ms, Ns, K, a_kc, b_kc, accumulate, splitk_ws):
+    """As, Bs, Cs: lists of torch CUDA tensors (bf16 operands as stored, fp32 outputs [M_i, N_i])."""
+    n = len(As)
+    vp = (C.c_void_p * n)
+    i64 = (C.c_int64 * n)
+    ia = (C.c_int * n)
+    _ck(lib().lpk_gemm_grouped(_i(n), vp(*[a.data_ptr() for a in As]), i64(*[a.shape[1] for a in As]),
+                               vp(*[b.data_ptr() for b in Bs]), i64(*[b.shape[1] for b in Bs]),
+                               vp(*[c.data_ptr() for c in Cs]), i64(*[c.shape[1] for c in Cs]), ia(*Ms), ia(*Ns), _i(K),
+                               _i(a_kc), _i(b_kc), _i(accumulate), _p(splitk_ws), _sz(splitk_ws.numel()), _stream()),
+        "lpk_gemm_grouped")
+
+
 def lpk_attention_fwd(dtype, qkv, o, lse, B, S, H, dh, causal=1, plain=0):
     _ck(lib().lpk_attention_fwd(_i(dtype), _p(qkv), _p(o), _p(lse), _i(B), _i(S), _i(H), _i(dh), _i(causal), _i(plain),
                                 _stream()), "lpk_attention_fwd")

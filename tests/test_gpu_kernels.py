@@ -397,3 +397,57 @@ def test_conv_and_batchnorm(K, dtype, N, H, C, O, R, stride, pad):
     assert relerr(host(dz), rdz) <= (6e-3 if dtype else 2e-5)
     assert relerr(host(dres), dy_eff) <= 1e-7
     assert relerr(host(dg), rdg) <= 2e-5 and relerr(host(db), rdb) <= 2e-5
+
+
+# Weight gradients of one layer as one grouped launch: products of different sizes over the same rows.
+GROUPS = [
+    # (K, [(M, N), ...]): a decoder layer's four at width 768 / FFN 3072; ragged sizes; more tiles than blocks
+    (8192, [(768, 3072), (3072, 768), (768, 768), (2304, 768)]),
+    (2048, [(264, 520), (520, 136), (8, 8), (1000, 264), (136, 776)]),
+    (512, [(4096, 4104), (2056, 1032)]),
+]
+
+
+@pytest.mark.parametrize("a_kc,b_kc", [(0, 0), (1, 1), (1, 0)])
+@pytest.mark.parametrize("gi", [0, 1, 2])
+def test_gemm_grouped(K, gi, a_kc, b_kc):
+    """Every product of a grouped launch against the CPU oracle's linear layer in float64, with and without
+    accumulation onto existing outputs; bit-repeatable; and the same bits as each product launched alone where the
+    two cut the reduction identically is not required (different cuts add partial sums in a different order)."""
+    import torch
+    Kd, shapes = GROUPS[gi]
+    rng = np.random.default_rng(17 + gi)
+    ws = zeros(1 << 25)
+    As, Bs, refs = [], [], []
+    for (M, N) in shapes:
+        A = rnd(rng, (M, Kd), 1, 0.5)
+        B = rnd(rng, (N, Kd), 1, 0.5)
+        As.append(dev(A if a_kc else np.ascontiguousarray(A.T), 1))
+        Bs.append(dev(B if b_kc else np.ascontiguousarray(B.T), 1))
+        refs.append(oracle_product(f"grp{gi}", A, B))
+    Ms, Ns = [m for m, _ in shapes], [n for _, n in shapes]
+    outs = [torch.full((m, n), 3.0, device="cuda", dtype=torch.float32) for m, n in shapes]
+    K.lpk_gemm_grouped(As, Bs, outs, Ms, Ns, Kd, a_kc, b_kc, 0, ws)
+    for o, r, sh in zip(outs, refs, shapes):
+        err = float((o.double() - r).norm() / r.norm())
+        assert err <= 2e-6, (sh, err)
+    again = [torch.zeros_like(o) for o in outs]
+    K.lpk_gemm_grouped(As, Bs, again, Ms, Ns, Kd, a_kc, b_kc, 0, ws)
+    for o, a in zip(outs, again):
+        assert torch.equal(o, a)
+    acc = [torch.full((m, n), 0.5, device="cuda", dtype=torch.float32) for m, n in shapes]
+    K.lpk_gemm_grouped(As, Bs, acc, Ms, Ns, Kd, a_kc, b_kc, 1, ws)
+    for o, r, sh in zip(acc, refs, shapes):
+        err = float((o.double() - (r + 0.5)).norm() / r.norm())
+        assert err <= 2e-6, (sh, "accumulate", err)
+
+
+def test_gemm_grouped_rejects_mixed_reductions(K):
+    import torch
+    ws = zeros(1 << 25)
+    a = torch.zeros(64, 64, device="cuda", dtype=torch.bfloat16)
+    o = torch.zeros(64, 64, device="cuda", dtype=torch.float32)
+    with pytest.raises(RuntimeError):
+        K.lpk_gemm_grouped([a], [a], [o], [64], [64], 64, 1, 1, 0, ws)            # a single product is not a group
+    with pytest.raises(RuntimeError):
+        K.lpk_gemm_grouped([a, a], [a, a], [o, o], [64, 64], [64, 64], 40, 1, 1, 0, ws)   # K not a multiple of 32
