@@ -61,6 +61,19 @@ int lpk_layernorm_bwd(int dtype, const void* dy, const void* x, const float* mea
                       const float* g, const void* add, void* dx, float* dg, float* db, int rows, int d,
                       int accumulate, float* scratch_dev, size_t scratch_elems, void* stream);
 
+/* lpk_layernorm_bwd for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * lpk_layernorm_bwd without the scratch pair: the partial sums of dg and db go through an array built into
+ * the library (LPK_STATIC_SCRATCH_FLOATS floats = 8 MiB, held on every GPU the library runs on until the
+ * process ends).  Nothing is allocated or freed.  hipErrorInvalidValue (and a line on stderr) if
+ * ((rows + 7) / 8) * d * 2 exceeds LPK_STATIC_SCRATCH_FLOATS; 8192 rows of width 1024 just fit.  All calls on
+ * one GPU share the array, whatever their stream: calls that overlap in time on one GPU race, so order them on
+ * one stream or with events.  The array keeps the last call's partial sums; a call reads only what it wrote. */
+#define LPK_STATIC_SCRATCH_FLOATS (1u << 21)
+int lpk_layernorm_bwd_static(int dtype, const void* dy, const void* x, const float* mean, const float* rstd,
+                             const float* g, const void* add, void* dx, float* dg, float* db, int rows, int d,
+                             int accumulate, void* stream);
+
 /* Row-wise softmax cross-entropy (the auxiliary objective, section 3): loss_rows[r] = lse(z_r) - z[r,y_r];
  * with write_grad, z is overwritten by (softmax(z_r) - onehot(y_r)) * inv_rows. */
 int lpk_softmax_ce(int dtype, void* z, int64_t ld, const int32_t* y, float* loss_rows, int rows, int n,

@@ -1,4 +1,7 @@
 // Kernel-level C ABI (include/lp_kernels.h): thin wrappers that build an OpCtx and call one op.
+#include <stdio.h>
+#include <mutex>
+
 #include "../../include/lp_kernels.h"
 #include "common.h"
 
@@ -78,6 +81,43 @@ extern "C" int lpk_layernorm_bwd(int dtype, const void* dy, const void* x, const
                                  int accumulate, float* scratch, size_t scratch_elems, void* stream) {
   return (int)op_layernorm_bwd(mk(dtype, stream, scratch, scratch_elems), dy, x, mean, rstd, g, add, dx, dg, db, rows,
                                d, accumulate);
+}
+// Workspace of lpk_layernorm_bwd_static: every GPU the library runs on holds its own copy of this array until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the address the
+// kernels get is looked up once per device, with that device current, and kept in g_static_ptr.
+static __device__ __align__(256) float scratch[LPK_STATIC_SCRATCH_FLOATS];
+static float* g_static_ptr[64];
+static std::mutex g_static_mu;
+
+extern "C" int lpk_layernorm_bwd_static(int dtype, const void* dy, const void* x, const float* mean, const float* rstd,
+                                        const float* g, const void* add, void* dx, float* dg, float* db, int rows,
+                                        int d, int accumulate, void* stream) {
+  if (rows < 0 || d < 1) return (int)hipErrorInvalidValue;
+  // the vectorised bf16 kernel writes one pair of partial rows per 8 input rows (the generic one per 32)
+  const size_t need = (size_t)((rows + 7) / 8) * (size_t)d * 2;
+  if (need > (size_t)LPK_STATIC_SCRATCH_FLOATS) {
+    fprintf(stderr, "lpk_layernorm_bwd_static: rows=%d d=%d needs %zu floats of workspace, the built-in one holds %zu\n",
+            rows, d, need, (size_t)LPK_STATIC_SCRATCH_FLOATS);
+    return (int)hipErrorInvalidValue;
+  }
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
+  float* ws;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return (int)e;
+      g_static_ptr[dev] = (float*)p;
+    }
+    ws = g_static_ptr[dev];
+  }
+  // every partial row that is read is written first by the same call: nothing has to start at zero
+  return (int)op_layernorm_bwd(mk(dtype, stream, ws, (size_t)LPK_STATIC_SCRATCH_FLOATS), dy, x, mean, rstd, g, add, dx,
+                               dg, db, rows, d, accumulate);
 }
 extern "C" int lpk_softmax_ce(int dtype, void* z, int64_t ld, const int32_t* y, float* loss_rows, int rows, int n,
                               int write_grad, float inv_rows, void* stream) {

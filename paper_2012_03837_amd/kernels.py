@@ -65,6 +65,15 @@ def lpk_layernorm_fwd(dtype, x, g, b, y, mean, rstd, rows, d):
         "lpk_layernorm_fwd")
 
 
+def lpk_layernorm_bwd_static(dtype, dy, x, mean, rstd, g, add, dx, dg, db, rows, d, accumulate):
+    rc = lib().lpk_layernorm_bwd_static(_i(dtype), _p(dy), _p(x), _p(mean), _p(rstd), _p(g), _p(add), _p(dx), _p(dg),
+                                        _p(db), _i(rows), _i(d), _i(accumulate), _stream())
+    if rc == 1:
+        raise KernelError(f"lpk_layernorm_bwd_static: rows={rows}, d={d} exceed the built-in workspace "
+                          f"(((rows + 7) // 8) * d * 2 must be <= {1 << 21})")
+    _ck(rc, "lpk_layernorm_bwd_static")
+
+
 def lpk_layernorm_bwd(dtype, dy, x, mean, rstd, g, add, dx, dg, db, rows, d, accumulate, scratch):
     _ck(lib().lpk_layernorm_bwd(_i(dtype), _p(dy), _p(x), _p(mean), _p(rstd), _p(g), _p(add), _p(dx), _p(dg), _p(db),
                                 _i(rows), _i(d), _i(accumulate), _p(scratch), _sz(scratch.numel()), _stream()),
