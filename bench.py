@@ -44,8 +44,9 @@ def measured_traffic(cfg_name, kernel):
 
 def gemm_flops_per_step(cfg):
     """Algorithmic FLOPs of the dense contractions of one step (2*M*N*K each): forward once per
-    layer; per head, its own forward + dgrad + wgrad and dgrad + wgrad of every layer in its window
-    (appendix A.2 accounting: one forward per layer, one backward per (head, layer-in-window))."""
+    layer; per head, its own forward + dgrad + wgrad and the dgrad of every layer in its window; the
+    wgrad of every covered layer once (appendix A.2 counts a whole backward pass per (head, layer);
+    the weight-gradient half of it is shared between the heads that cover a layer)."""
     import lp_inputs as LI
     B = cfg.batch
     kind = cfg.layers[0].kind
@@ -79,10 +80,15 @@ def gemm_flops_per_step(cfg):
         return 2.0 * rows * h.in_dim * h.n_classes
 
     total = sum(layer_fwd(l) for l in cfg.layers)
+    covered = set()
     for h, (s, e) in zip(cfg.heads, LI.head_windows(cfg)):
         total += 3.0 * head_fwd(h)
         for li in range(s + 1, e + 1):
-            total += 2.0 * layer_fwd(cfg.layers[li - 1])
+            total += layer_fwd(cfg.layers[li - 1])          # the input-gradient products, once per (head, layer)
+            covered.add(li)
+    # the weight-gradient products once per covered layer: a layer inside several windows takes ONE parameter pass,
+    # driven by the sum of the heads' gradients at its output (the parameter gradient is linear in it)
+    total += sum(layer_fwd(cfg.layers[li - 1]) for li in covered)
     return total
 
 

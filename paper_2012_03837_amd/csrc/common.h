@@ -137,7 +137,8 @@ hipError_t op_posenc_init(const OpCtx& c, float* pe, int S, int d);
 
 hipError_t op_layernorm_fwd(const OpCtx& c, const void* x, const float* g, const float* b, void* y,
                             float* mean, float* rstd, int rows, int d);
-// dx = (add ? add : 0) + LN-backward(dy); dg/db accumulate if `accumulate`.  dx may be null.
+// dx = (add ? add : 0) + LN-backward(dy); dg/db accumulate if `accumulate`.  dx may be null; dg and db may
+// both be null (input gradient only).
 hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const float* mean, const float* rstd,
                             const float* g, const void* add, void* dx, float* dg, float* db, int rows, int d,
                             int accumulate);

@@ -44,6 +44,10 @@ struct LayerState {
   int coverage = 0;                  // number of heads whose window covers this layer
   int seen = 0;                      // contributions received so far in the current step
   void* out = nullptr;               // layer output (compute dtype)
+  // Layers inside several windows (overlapping schemes): the sum of the heads' gradients with respect to this
+  // layer's output, in the compute dtype.  The layer's parameter gradient is linear in that upstream gradient,
+  // so one pass on the sum replaces one pass per head (null: every head runs its own full backward pass).
+  void* gsum = nullptr;
   const void* in_override = nullptr; // pipelined schedule: this layer reads its input here (a block's first layer)
   size_t out_elems_per_sample = 0;
   // tensor indices (−1 if absent)
@@ -187,7 +191,9 @@ struct lp_ctx : lp_scratch {
 
 namespace lp {
 int drv_forward(lp_ctx* c, int li, int batch, const int32_t* ids_or_null);
-int drv_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int accumulate);
+// params == false: only the gradient with respect to the layer's input (no parameter gradient is touched).
+int drv_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int accumulate,
+                 bool params = true);
 int drv_head(lp_ctx* c, int hi, int batch, const int32_t* y, float* loss_out, bool backward, void* dh);
 size_t layer_out_elems(const lp_layer_spec& s, int batch);
 }

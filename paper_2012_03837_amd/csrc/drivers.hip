@@ -84,30 +84,36 @@ static int mlp_forward(lp_ctx* c, int li, int batch) {
   return LP_OK;
 }
 
-static int mlp_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int acc) {
+static int mlp_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int acc, bool params) {
   LayerState& L = c->layers[li];
   OpCtx o = c->op();
   const void* x = layer_input(c, li);
   bool proj = L.t.count("win") > 0;
   const void* p = proj ? L.mlp_p : x;
   int width = L.s.width, hidden = L.s.hidden;
-  DO(op_colsum(o, dout, width, c->G32(L.t["b2"]), batch, width, acc));
-  DO(op_gemm(o, lin_wgrad(c, dout, L.mlp_r, batch, L.t["w2"], acc)));
+  if (params) {
+    DO(op_colsum(o, dout, width, c->G32(L.t["b2"]), batch, width, acc));
+    DO(op_gemm(o, lin_wgrad(c, dout, L.mlp_r, batch, L.t["w2"], acc)));
+  }
   // da = (dout W2) * relu'(r)
   GemmArgs gd = lin_dgrad(c, dout, batch, L.t["w2"], c->dF);
   gd.dact = ACT_RELU; gd.dact_src = L.mlp_r; gd.ldd = hidden;
   DO(op_gemm(o, gd));
-  DO(op_colsum(o, c->dF, hidden, c->G32(L.t["b1"]), batch, hidden, acc));
-  DO(op_gemm(o, lin_wgrad(c, c->dF, p, batch, L.t["w1"], acc)));
-  if (!proj && !need_dx) return LP_OK;
+  if (params) {
+    DO(op_colsum(o, c->dF, hidden, c->G32(L.t["b1"]), batch, hidden, acc));
+    DO(op_gemm(o, lin_wgrad(c, c->dF, p, batch, L.t["w1"], acc)));
+  }
+  if (!need_dx && !(proj && params)) return LP_OK;
   // dp = da W1 + dout
   void* dp = proj ? c->dc : dx;
   GemmArgs g1 = lin_dgrad(c, c->dF, batch, L.t["w1"], dp);
   g1.res = dout; g1.ldr = width;
   DO(op_gemm(o, g1));
   if (proj) {
-    DO(op_colsum(o, dp, width, c->G32(L.t["bin"]), batch, width, acc));
-    DO(op_gemm(o, lin_wgrad(c, dp, x, batch, L.t["win"], acc)));
+    if (params) {
+      DO(op_colsum(o, dp, width, c->G32(L.t["bin"]), batch, width, acc));
+      DO(op_gemm(o, lin_wgrad(c, dp, x, batch, L.t["win"], acc)));
+    }
     if (need_dx) DO(op_gemm(o, lin_dgrad(c, dp, batch, L.t["win"], dx)));
   }
   return LP_OK;
@@ -139,7 +145,7 @@ static int dec_forward(lp_ctx* c, int li, int batch, const int32_t* ids) {
 }
 
 static int dec_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int acc,
-                        const int32_t* ids) {
+                        const int32_t* ids, bool params) {
   LayerState& L = c->layers[li];
   OpCtx o = c->op();
   int S = L.s.seq_len, d = L.s.width, H = L.s.n_heads, F = L.s.hidden, T = batch * S;
@@ -149,32 +155,33 @@ static int dec_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx
   // nothing in the pass reads them: they are collected and launched together at the end (one grouped launch).
   GemmArgs wg[4];
   // FFN
-  DO(op_colsum(o, dout, d, c->G32(L.t["b2"]), T, d, acc));
+  if (params) DO(op_colsum(o, dout, d, c->G32(L.t["b2"]), T, d, acc));
   wg[0] = lin_wgrad(c, dout, L.f, T, L.t["w2"], acc);
   GemmArgs gd = lin_dgrad(c, dout, T, L.t["w2"], c->dF);
   gd.dact = L.s.act == LP_ACT_RELU ? ACT_RELU : ACT_GELU; gd.dact_src = L.fpre; gd.ldd = F;
   DO(op_gemm(o, gd));
-  DO(op_colsum(o, c->dF, F, c->G32(L.t["b1"]), T, F, acc));
+  if (params) DO(op_colsum(o, c->dF, F, c->G32(L.t["b1"]), T, F, acc));
   wg[1] = lin_wgrad(c, c->dF, L.c, T, L.t["w1"], acc);
   DO(op_gemm(o, lin_dgrad(c, c->dF, T, L.t["w1"], c->dc)));
   // du = dout + LN2-backward(dc)
-  DO(op_layernorm_bwd(o, c->dc, L.u, L.mean2, L.rstd2, c->P32(L.t["ln2.g"]), dout, c->du, c->G32(L.t["ln2.g"]),
-                      c->G32(L.t["ln2.b"]), T, d, acc));
+  DO(op_layernorm_bwd(o, c->dc, L.u, L.mean2, L.rstd2, c->P32(L.t["ln2.g"]), dout, c->du,
+                      params ? c->G32(L.t["ln2.g"]) : nullptr, params ? c->G32(L.t["ln2.b"]) : nullptr, T, d, acc));
   // attention block
-  DO(op_colsum(o, c->du, d, c->G32(L.t["bo"]), T, d, acc));
+  if (params) DO(op_colsum(o, c->du, d, c->G32(L.t["bo"]), T, d, acc));
   wg[2] = lin_wgrad(c, c->du, L.o, T, L.t["wo"], acc);
   DO(op_gemm(o, lin_dgrad(c, c->du, T, L.t["wo"], c->dO)));
   DO(op_attn_bwd(o, L.qkv, L.o, L.lse, c->dO, c->dqkv, c->delta, batch, S, H, d / H, L.s.causal));
-  DO(op_colsum(o, c->dqkv, 3 * d, c->G32(L.t["bqkv"]), T, 3 * d, acc));
+  if (params) DO(op_colsum(o, c->dqkv, 3 * d, c->G32(L.t["bqkv"]), T, 3 * d, acc));
   wg[3] = lin_wgrad(c, c->dqkv, L.a, T, L.t["wqkv"], acc);
   DO(op_gemm(o, lin_dgrad(c, c->dqkv, T, L.t["wqkv"], c->da)));
   // dh = du + LN1-backward(da); the input gradient itself is only needed inside a window or for the embedding
-  bool want_dx = need_dx || has_emb;
+  bool want_dx = need_dx || (has_emb && params);
   void* dh = want_dx ? (has_emb ? c->da : dx) : nullptr;   // LN backward may write over its own dy rows
-  DO(op_layernorm_bwd(o, c->da, x, L.mean1, L.rstd1, c->P32(L.t["ln1.g"]), c->du, dh, c->G32(L.t["ln1.g"]),
-                      c->G32(L.t["ln1.b"]), T, d, acc));
-  if (has_emb) DO(op_embed_bwd(o, ids, dh, c->G32(L.t["emb"]), T, c->spec.vocab, d, acc));
-  DO(op_gemm_grouped(o, wg, 4));
+  if (params || want_dx)
+    DO(op_layernorm_bwd(o, c->da, x, L.mean1, L.rstd1, c->P32(L.t["ln1.g"]), c->du, dh,
+                        params ? c->G32(L.t["ln1.g"]) : nullptr, params ? c->G32(L.t["ln1.b"]) : nullptr, T, d, acc));
+  if (has_emb && params) DO(op_embed_bwd(o, ids, dh, c->G32(L.t["emb"]), T, c->spec.vocab, d, acc));
+  if (params) DO(op_gemm_grouped(o, wg, 4));
   return LP_OK;
 }
 
@@ -268,11 +275,14 @@ int drv_forward(lp_ctx* c, int li, int batch, const int32_t* ids) {
   }
   return LP_EINVAL;
 }
-int drv_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int accumulate) {
+int drv_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int accumulate, bool params) {
   switch (c->layers[li].s.kind) {
-    case LP_LAYER_RESMLP: return mlp_backward(c, li, batch, dout, dx, need_dx, accumulate);
-    case LP_LAYER_DECODER: return dec_backward(c, li, batch, dout, dx, need_dx, accumulate, (const int32_t*)c->x_in);
-    case LP_LAYER_RESNET_STAGE: return res_backward(c, li, batch, dout, dx, need_dx, accumulate);
+    case LP_LAYER_RESMLP: return mlp_backward(c, li, batch, dout, dx, need_dx, accumulate, params);
+    case LP_LAYER_DECODER:
+      return dec_backward(c, li, batch, dout, dx, need_dx, accumulate, (const int32_t*)c->x_in, params);
+    case LP_LAYER_RESNET_STAGE:
+      if (!params) { c->err = "a ResNet stage has no input-gradient-only pass"; return LP_EUNSUPPORTED; }
+      return res_backward(c, li, batch, dout, dx, need_dx, accumulate);
   }
   return LP_EINVAL;
 }

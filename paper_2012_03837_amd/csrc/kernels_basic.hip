@@ -326,7 +326,7 @@ hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const
   if (ln_fast_ok(c, dy, x, add, dx, d)) {
     int nb = 0;
     hipError_t e = ln_bwd_fast(c, dy, x, mean, rstd, g, add, dx, rows, d, &nb);
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || !dg) return e;          // no dg: the caller wants the input gradient only
     k_reduce_partials<<<dim3((d + 63) / 64, 2), 64 * kReduceGroups, 0, c.stream>>>(c.partial, nb, d, dg, accumulate, db);
     return LP_LAUNCH_CHECK();
   }
@@ -340,7 +340,7 @@ hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const
     k_ln_bwd<float><<<nblk, 256, shm, c.stream>>>((const float*)dy, (const float*)x, mean, rstd, g,
                                                   (const float*)add, (float*)dx, c.partial, rows, d);
   hipError_t e = LP_LAUNCH_CHECK();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || !dg) return e;
   k_reduce_partials<<<dim3((d + 63) / 64, 2), 64 * kReduceGroups, 0, c.stream>>>(c.partial, nblk, d, dg, accumulate, db);
   return LP_LAUNCH_CHECK();
 }

@@ -2,6 +2,7 @@
 // (paper section 3) and named-tensor access.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "ctx.h"
@@ -184,6 +185,12 @@ static ConvUnit make_unit(lp_ctx* c, const std::string& wname, const std::string
   return u;
 }
 
+static bool no_linearity() {     // LP_NO_LINEARITY=1: every head runs its own full backward pass (for measurements)
+  static int v = -1;
+  if (v < 0) { const char* s = getenv("LP_NO_LINEARITY"); v = (s && s[0] == '1') ? 1 : 0; }
+  return v != 0;
+}
+
 // Assigns every work / params / state region.  With null bases it only measures.
 static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
   const lp_model_spec& sp = c->spec;
@@ -216,6 +223,9 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
     LayerState& S = c->layers[li];
     const lp_layer_spec& l = S.s;
     if (l.kind != LP_LAYER_RESNET_STAGE) S.out = wa.take(layer_out_elems(l, B) * es);
+    S.gsum = nullptr;
+    if (l.kind != LP_LAYER_RESNET_STAGE && S.coverage > 1 && sp.schedule == LP_SCHED_SYNC && !no_linearity())
+      S.gsum = wa.take(layer_out_elems(l, B) * es);
     if (l.kind == LP_LAYER_RESMLP) {
       S.mlp_p = l.in_dim != l.width ? wa.take((size_t)B * l.width * es) : nullptr;
       S.mlp_r = wa.take((size_t)B * l.hidden * es);
@@ -723,9 +733,24 @@ static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* los
         bool need_dx = lj > Hd.s_lo + 1;          // the window input is data: no gradient leaves the window
         // contributions of several heads to one layer keep their order: wait for the previous one
         if (set && S.seen > 0) CK(hipStreamWaitEvent(c->cur_stream, c->ev_contrib[lj], 0));
-        if ((st = drv_backward(c, lj, batch, dcur, dnext, need_dx, S.seen > 0 ? 1 : 0)) != LP_OK) return st;
-        S.seen += 1;
-        if (set && S.seen < S.coverage) CK(hipEventRecord(c->ev_contrib[lj], c->cur_stream));
+        if (S.gsum) {
+          // A layer inside several windows (appendix A.2 counts a backward pass per head; the parameter gradient is
+          // linear in the gradient arriving at the layer's output, so the passes can share their parameter part):
+          // every head adds its gradient at this layer's output to the layer's sum, in head order, and continues
+          // downwards with an input-gradient-only pass driven by ITS OWN gradient (the sum would carry the other
+          // heads' losses beyond their windows); the last head to arrive runs the one parameter pass on the sum.
+          const size_t n = layer_out_elems(S.s, batch);
+          if (S.seen == 0) CK(hipMemcpyAsync(S.gsum, dcur, n * dtype_size(c->dt), hipMemcpyDeviceToDevice, c->cur_stream));
+          else CK(op_add(c->op(), S.gsum, dcur, S.gsum, n));
+          S.seen += 1;
+          if (set && S.seen < S.coverage) CK(hipEventRecord(c->ev_contrib[lj], c->cur_stream));
+          if (need_dx && (st = drv_backward(c, lj, batch, dcur, dnext, true, 0, false)) != LP_OK) return st;
+          if (S.seen == S.coverage && (st = drv_backward(c, lj, batch, S.gsum, nullptr, false, 0, true)) != LP_OK) return st;
+        } else {
+          if ((st = drv_backward(c, lj, batch, dcur, dnext, need_dx, S.seen > 0 ? 1 : 0)) != LP_OK) return st;
+          S.seen += 1;
+          if (set && S.seen < S.coverage) CK(hipEventRecord(c->ev_contrib[lj], c->cur_stream));
+        }
         void* t = dcur; dcur = dnext; dnext = t;
       }
       if ((st = optimizer_range(c, Hd.p_begin, Hd.p_end, 1.f)) != LP_OK) return st;
