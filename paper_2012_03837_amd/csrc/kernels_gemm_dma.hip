@@ -27,6 +27,7 @@
 // and the next item's first k-tiles are in flight while a finished item is written; see the comment in the kernel.
 // Requires K % 32 == 0 (no zero fill on this path).
 #include <stdio.h>
+#include <stdlib.h>
 #include <type_traits>
 #include "common.h"
 #include "gemm_common.h"
@@ -902,12 +903,29 @@ hipError_t gemm_dma_grouped(const OpCtx& c, const GemmArgs* gs, int n) {
   p.upb = p.kt;
   bool partials = false;
   if (p.tail_tiles > 0) {
+    // Two ways to spread the last partial wave of tiles over the grid.  Balanced: the tail's k-steps in tile-major
+    // order are cut into G equal ranges (every CU busy to the end, but ranges start anywhere inside a tile: blocks
+    // that run side by side sit at different k-steps of different tiles, so no operand panel is shared in L2, and
+    // nearly every block writes partial sums).  Uniform: every tail tile is cut into the same s = floor(G / tiles)
+    // equal pieces (s = 1: whole tiles, no partial sums and no fix-up launch at all); blocks of one tile row or
+    // column then walk the same k-steps together and share their operand panels.  Measured on a layer's four
+    // weight gradients: width 768 (108 tiles: two pieces each, 128 k-steps against 108) 182 -> 172 us alone and the
+    // same step time; width 1024 (192 tiles: whole, 256 k-steps against 192) 279 -> 309 us: the k-step of this
+    // kernel with both operands k-major costs 1.05 .. 1.2 us however the operands are shared, so idle CUs are not
+    // paid back.  The uniform cut is taken when it leaves the longest block at most 1.25 times the balanced work.
     const long U = (long)p.tail_tiles * p.kt;
     long upb = (U + p.G - 1) / p.G;
     if (upb < 4) upb = 4;
     if (upb * 16 < p.kt) upb = (p.kt + 15) / 16;
     if (upb > p.kt) upb = p.kt;
-    p.upb = (int)upb;
+    long s = p.G / p.tail_tiles;
+    if (s < 1) s = 1;
+    while (s > 1 && (p.kt % s != 0 || p.kt / s < 4)) --s;
+    const long upb_uniform = p.kt / s;
+    static int forced = -1;           // LP_GROUP_SPLIT=balanced|uniform forces one (for measurements)
+    if (forced < 0) { const char* e = getenv("LP_GROUP_SPLIT"); forced = !e ? 0 : (e[0] == 'b' ? 1 : (e[0] == 'u' ? 2 : 0)); }
+    const bool uniform = forced == 2 || (forced == 0 && (double)upb_uniform <= 1.25 * (double)upb);
+    p.upb = (int)(uniform ? upb_uniform : upb);
     if (p.upb < p.kt) {
       partials = true;
       if (!c.splitk_ws || (size_t)2 * p.G * BM * 256 > c.splitk_elems) return hipErrorInvalidValue;
