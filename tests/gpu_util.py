@@ -119,7 +119,7 @@ def compare_step(tr, cfg, P0, x, y, n_steps=1, check_state=True, label="", store
                     if sname in st:
                         e = relerr(tr.get(k + "." + sname), st[sname][k])
                         worst["state"] = max(worst["state"], e)
-                        assert e <= 2 * tol, (label, sname, k, e)
+                        assert e <= tol, (label, sname, k, e)
         P = newP
     return worst
 

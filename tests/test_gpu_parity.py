@@ -208,7 +208,8 @@ def test_pipelined_schedule_matches_oracle(lpmod, name, dtype):
     cfg = dataclasses.replace(LI.make_config(name), dtype=dtype)
     J = len(cfg.heads)
     P0 = generic_params(cfg)
-    ltol, ptol, stol = (1e-4, 2e-4, 4e-4) if dtype == "f32" else (2e-2, 2e-2, 4e-2)
+    ltol, ptol, stol = (1e-4, 1e-4, 1e-4) if dtype == "f32" else (2e-2, 2e-2, 2e-2)
+    worst_p = worst_s = 0.0
     finals = []
     for ns in (0, 2):
         tr = lpmod.LocalTrainer(cfg, schedule="pipelined", n_streams=ns)
@@ -227,10 +228,14 @@ def test_pipelined_schedule_matches_oracle(lpmod, name, dtype):
                     assert abs(got[j] - ref[j]) <= ltol * abs(ref[j]), (name, t, j, got[j], ref[j])
         got_params = tr.get_params()
         for k in P0:
+            worst_p = max(worst_p, relerr(got_params[k], P[k]))
             assert relerr(got_params[k], P[k]) <= ptol, (name, k, relerr(got_params[k], P[k]))
             for sname in ("m", "v"):
                 if sname in st:
-                    assert relerr(tr.get(k + "." + sname), st[sname][k]) <= stol, (name, sname, k)
+                    e = relerr(tr.get(k + "." + sname), st[sname][k])
+                    worst_s = max(worst_s, e)
+                    assert e <= stol, (name, sname, k, e)
+        print(f"  pipelined {name}/{dtype} streams {ns}: worst param rel err {worst_p:.2e}, worst moment rel err {worst_s:.2e}", flush=True)
         finals.append(got_params)
         tr.close()
     for k in P0:
@@ -277,7 +282,7 @@ def test_pipelined_schedule_with_changing_batch_sizes(lpmod):
             assert abs(got[j] - ref[j]) <= 1e-4 * max(abs(ref[j]), 1e-30), (t, j, got[j], ref[j])
     got_params = tr.get_params()
     for k in P0:
-        assert relerr(got_params[k], P[k]) <= 2e-4, k
+        assert relerr(got_params[k], P[k]) <= 1e-4, (k, relerr(got_params[k], P[k]))
     tr.close()
 
 
