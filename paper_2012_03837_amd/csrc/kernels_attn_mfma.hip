@@ -141,6 +141,8 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict_
         st[i] = MFMA32(kf, qf[kk], st[i]);
       }
     }
+    // The scale 1/sqrt(64) * log2(e) is positive: the running maximum is taken over the raw scores and scaled once,
+    // and the scaling of every score rides in the fused multiply-add that feeds the exponential.
     float mt = -INFINITY;
     // only tiles that touch the diagonal or the end of the sequence need the mask (wave-uniform test)
     const bool need_mask = k0 + 63 >= S || (causal && k0 + 63 > q0);
@@ -150,7 +152,7 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict_
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           int kj = k0 + 32 * i + 8 * (v / 4) + 4 * hf + (v % 4);
-          float s = st[i][v] * c;
+          float s = st[i][v];
           if (kj >= S || (causal && kj > qi)) s = -INFINITY;
           st[i][v] = s;
           mt = fmaxf(mt, s);
@@ -159,13 +161,9 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict_
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float s = st[i][v] * c;
-          st[i][v] = s;
-          mt = fmaxf(mt, s);
-        }
+        for (int v = 0; v < 16; ++v) mt = fmaxf(mt, st[i][v]);
     }
-    mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+    mt = fmaxf(mt, __shfl_xor(mt, 32, 64)) * c;
     float mn = fmaxf(m, mt);
     float mref = mn == -INFINITY ? 0.f : mn;
     float alpha = exp2f(m - mref);
@@ -174,16 +172,19 @@ __global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict_
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        float p = __builtin_amdgcn_exp2f(st[i][v] - mref);
+        float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[i][v], c, -mref));
         st[i][v] = p;
         rs += p;
       }
     l = l * alpha + rs;
     m = mn;
+    // once the running maxima have settled every lane's alpha is exactly 1: skip the rescale then (wave-uniform)
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
 #pragma unroll
-    for (int dh = 0; dh < 2; ++dh)
+      for (int dh = 0; dh < 2; ++dh)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[dh][v] *= alpha;
+        for (int v = 0; v < 16; ++v) oacc[dh][v] *= alpha;
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -285,7 +286,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dq_mfma(const bf16_t* __res
           int kj = k0 + 32 * i + 8 * (v / 4) + 4 * hf + (v % 4);
           bool masked = kj >= S || qi >= S || (causal && kj > qi);
           float p = __builtin_amdgcn_exp2f(st[i][v] * c - lse2);
-          st[i][v] = masked ? 0.f : p * (dp[i][v] - D) * scale;
+          st[i][v] = masked ? 0.f : p * (dp[i][v] - D);
         }
     } else {
 #pragma unroll
@@ -293,7 +294,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dq_mfma(const bf16_t* __res
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           float p = __builtin_amdgcn_exp2f(st[i][v] * c - lse2);
-          st[i][v] = p * (dp[i][v] - D) * scale;
+          st[i][v] = p * (dp[i][v] - D);        // the factor 1/sqrt(64) of dS is applied once, to the finished dQ
         }
     }
 #pragma unroll
@@ -313,7 +314,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dq_mfma(const bf16_t* __res
       for (int g = 0; g < 4; ++g) {
         bf16x4 w;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) w[j] = (bf16_t)dqa[dh][4 * g + j];
+        for (int j = 0; j < 4; ++j) w[j] = (bf16_t)(dqa[dh][4 * g + j] * scale);
         *reinterpret_cast<bf16x4*>(dqp + 32 * dh + 8 * g + 4 * hf) = w;
       }
   }
@@ -399,7 +400,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dkv_mfma(const bf16_t* __re
             p = masked ? 0.f : p;
           }
           s[v] = p;
-          dp[v] = p * (dp[v] - d4[j]) * scale;
+          dp[v] = p * (dp[v] - d4[j]);          // the factor 1/sqrt(64) of dS is applied once, to the finished dK
         }
       }
 #pragma unroll
@@ -422,7 +423,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dkv_mfma(const bf16_t* __re
       for (int g = 0; g < 4; ++g) {
         bf16x4 wk, wv;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { wk[j] = (bf16_t)dka[dh][4 * g + j]; wv[j] = (bf16_t)dva[dh][4 * g + j]; }
+        for (int j = 0; j < 4; ++j) { wk[j] = (bf16_t)(dka[dh][4 * g + j] * scale); wv[j] = (bf16_t)dva[dh][4 * g + j]; }
         *reinterpret_cast<bf16x4*>(dkp + 32 * dh + 8 * g + 4 * hf) = wk;
         *reinterpret_cast<bf16x4*>(dvp + 32 * dh + 8 * g + 4 * hf) = wv;
       }
