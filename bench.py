@@ -197,7 +197,7 @@ def main():
                     help="lp_overlap_steps: consecutive steps are not joined into the caller's stream, so the next "
                          "step's first layers run beside the last blocks of the current one (same results, weaker "
                          "buffer contract; see include/lp.h)")
-    ap.add_argument("--schedule", default="sync", choices=["sync", "pipelined"],
+    ap.add_argument("--schedule", default="sync", choices=["sync", "pipelined", "pipelined_grouped"],
                     help="sync: every block works on the call's minibatch (the headline metric); pipelined: block j "
                          "works on block j-1's output of the previous call (steady state after warm-up)")
     ap.add_argument("--graph", action="store_true",
@@ -238,7 +238,7 @@ def main():
         args.streams = lp.default_side_streams(cfg)
     tr = lp.LocalTrainer(cfg, n_streams=args.streams, schedule=args.schedule)
     K, W = args.steps, args.warmup
-    if args.schedule == "pipelined":
+    if args.schedule != "sync":
         # steady state only: block j first runs in call j, so the warm-up has to cover the ramp-up of the pipeline
         W = max(W, len(cfg.heads) + 2)
     n_stage = min(K + W, 8)

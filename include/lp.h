@@ -69,8 +69,14 @@ typedef enum { LP_ACT_GELU = 0, LP_ACT_RELU = 1 } lp_act;
 /* LP_SCHED_SYNC: every block works on the call's minibatch (one forward pass with the current weights).
  * LP_SCHED_PIPELINED: the steady-state pipeline of section 6 / section 3: block 1 works on the call's
  * minibatch, block j >= 2 on the activation that block j-1 produced in the previous call, with the labels
- * that travelled with it; blocks are then independent within a call.  Needs windows that tile the layers. */
-typedef enum { LP_SCHED_SYNC = 0, LP_SCHED_PIPELINED = 1 } lp_schedule;
+ * that travelled with it; blocks are then independent within a call.  Needs windows that tile the layers.
+ * LP_SCHED_PIPELINED_GROUPED: the same schedule and the same results up to the order of floating-point sums; the
+ * blocks of a call are walked in lockstep (stage s of every block before stage s + 1 of any) and the GEMMs of one
+ * stage, one per block and of one shape, go out as grouped launches (two teams of blocks on two of the side streams
+ * if there are any).  For decoder layers in blocks of equal depth with vocabulary heads: LP_EUNSUPPORTED otherwise.
+ * Measured on one MI355X it costs the same per call as LP_SCHED_PIPELINED (independent chains over the side
+ * streams): what the grouped products gain, the coarser interleaving of memory-bound and matrix kernels loses. */
+typedef enum { LP_SCHED_SYNC = 0, LP_SCHED_PIPELINED = 1, LP_SCHED_PIPELINED_GROUPED = 2 } lp_schedule;
 
 typedef struct {
   int kind;                 /* lp_layer_kind */

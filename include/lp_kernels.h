@@ -35,17 +35,19 @@ int lpk_gemm(int dtype, const void* A, int64_t lda, int a_kc, const void* B, int
              const void* dact_src, int dact, int64_t ldd, const void* res, int64_t ldr, int accumulate, int variant,
              float* splitk_ws_dev, size_t splitk_ws_elems, void* stream);
 
-/* n (2..8) independent bf16 products C_i[M_i, N_i] (+)= sum_k A_i(m,k) B_i(n,k) with fp32 outputs, one reduction
- * length K (a multiple of 32), one pair of operand layouts and nothing fused, in ONE persistent launch: the
- * weight gradients of the linear maps of one layer (section 3: the backward pass inside a block), each of
- * which alone has too few output tiles for the chip.  The arrays are HOST arrays of n entries holding DEVICE
- * pointers, leading dimensions and sizes (M_i, N_i multiples of 8).  The tiles of all products form one
- * sequence that is spread over the grid like a single product's; its last partial wave is cut along k through
- * splitk_ws_dev (at least 2^25 floats).  hipErrorInvalidValue, with nothing launched, if the set does not
- * qualify. */
+/* n (2..16) independent bf16 products C_i[M_i, N_i] (+)= epilogue(sum_k A_i(m,k) B_i(n,k)) with one reduction length K
+ * (a multiple of 32) and one pair of operand layouts, in ONE persistent launch: the weight gradients of the linear
+ * maps of one layer, or the same-shaped products of independent blocks (section 3: blocks are trained in
+ * parallel; section 6), each of which alone has too few output tiles for the chip.  Every array is a HOST array of
+ * n entries holding DEVICE pointers, leading dimensions and sizes (M_i, N_i multiples of 8).  Outputs are fp32
+ * (c_f32) or bf16; per problem an optional bias (fp32 [N_i]) and an optional residual (bf16 [M_i, N_i], leading
+ * dimension ldc_i), `bias` and `res` may be NULL; act as in lpk_gemm, common to all.  The tiles of all products form
+ * one sequence that is spread over the grid like a single product's; its last partial wave is cut along k through
+ * splitk_ws_dev (at least 2^25 floats).  hipErrorInvalidValue, with nothing launched, if the set does not qualify. */
 int lpk_gemm_grouped(int n, const void* const* A, const int64_t* lda, const void* const* B, const int64_t* ldb,
-                     float* const* C, const int64_t* ldc, const int* M, const int* N, int K, int a_kc, int b_kc,
-                     int accumulate, float* splitk_ws_dev, size_t splitk_ws_elems, void* stream);
+                     void* const* C, const int64_t* ldc, int c_f32, const int* M, const int* N, int K, int a_kc,
+                     int b_kc, const float* const* bias, int act, const void* const* res, int accumulate,
+                     float* splitk_ws_dev, size_t splitk_ws_elems, void* stream);
 
 /* Causal (or full) multi-head attention of a decoder layer (appendix B.2).  qkv [B*S, 3*H*dh]
  * (q | k | v), o [B*S, H*dh], lse [B,H,S] = log-sum-exp of the scaled scores, delta [B,H,S] scratch. */

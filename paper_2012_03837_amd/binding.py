@@ -112,7 +112,7 @@ def lib() -> C.CDLL:
     return _lib
 
 
-SCHEDULES = {"sync": 0, "pipelined": 1}
+SCHEDULES = {"sync": 0, "pipelined": 1, "pipelined_grouped": 2}
 
 
 def make_spec(cfg, max_batch: int | None = None, n_streams: int = 0, schedule: str = "sync", debug: bool = False):

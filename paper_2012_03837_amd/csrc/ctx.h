@@ -57,6 +57,7 @@ struct LayerState {
   // decoder
   void *a = nullptr, *qkv = nullptr, *o = nullptr, *u = nullptr, *c = nullptr, *fpre = nullptr, *f = nullptr;
   float *mean1 = nullptr, *rstd1 = nullptr, *mean2 = nullptr, *rstd2 = nullptr, *lse = nullptr;
+  lp::GemmArgs wg[4];                  // decoder: the weight-gradient products of the backward pass in flight
   // resnet stage
   bool has_stem = false;
   ConvUnit stem;
@@ -159,6 +160,7 @@ struct lp_ctx : lp_scratch {
   std::vector<int> in_batch, ran_batch, blk_updates;
   size_t label_elems_per_sample = 1;
   hipEvent_t ev_pipe = nullptr;
+  bool lockstep = false;                 // pipelined blocks are walked stage by stage (grouped GEMMs across blocks)
   void use(int i) { static_cast<lp_scratch&>(*this) = sets[i]; }
   // steps overlapped across calls: a call does not join its chains into the caller's stream; the next step's
   // forward pass of a layer waits only for the chains that read or update that layer (join_pending otherwise)
@@ -190,6 +192,14 @@ struct lp_ctx : lp_scratch {
 };
 
 namespace lp {
+// The GEMMs a driver stage hands back for the caller to launch (see drivers.hip).
+struct StageGemms { GemmArgs g[4]; int n = 0; };
+constexpr int kDecFwdStages = 4, kDecBwdStages = 5, kVocabHeadStages = 4;
+int dec_forward_stage(lp_ctx* c, int li, int batch, const int32_t* ids, int stage, StageGemms* out);
+int dec_backward_stage(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int acc,
+                       const int32_t* ids, bool params, int stage, StageGemms* out);
+int vocab_head_stage(lp_ctx* c, int hi, int batch, const int32_t* y, float* loss_out, bool backward, void* dh,
+                     int stage, StageGemms* out);
 int drv_forward(lp_ctx* c, int li, int batch, const int32_t* ids_or_null);
 // params == false: only the gradient with respect to the layer's input (no parameter gradient is touched).
 int drv_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int accumulate,

@@ -120,68 +120,104 @@ static int mlp_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx
 }
 
 // ===================================================================================== decoder layer
-static int dec_forward(lp_ctx* c, int li, int batch, const int32_t* ids) {
+// The forward and backward passes of a decoder layer are written as STAGES: a stage runs the ops that precede a set
+// of mutually independent GEMMs and hands those GEMMs back instead of launching them.  One layer at a time, the
+// caller launches them at once (dec_forward / dec_backward below); the pipelined schedule walks the same stage of
+// all its blocks before it launches, so the same-shaped products of independent blocks share one grouped launch.
+int dec_forward_stage(lp_ctx* c, int li, int batch, const int32_t* ids, int stage, StageGemms* out) {
   LayerState& L = c->layers[li];
   OpCtx o = c->op();
   int S = L.s.seq_len, d = L.s.width, H = L.s.n_heads, T = batch * S;
-  if (li == 1 && c->spec.vocab > 0)
-    DO(op_embed_fwd(o, ids, c->P32(L.t["emb"]), c->pe, c->h0, T, S, d, c->spec.vocab));
-  const void* x = layer_input(c, li);
-  DO(op_layernorm_fwd(o, x, c->P32(L.t["ln1.g"]), c->P32(L.t["ln1.b"]), L.a, L.mean1, L.rstd1, T, d));
-  DO(op_gemm(o, lin_fwd(c, L.a, T, L.t["wqkv"], L.t["bqkv"], L.qkv)));
-  DO(op_attn_fwd(o, L.qkv, L.o, L.lse, batch, S, H, d / H, L.s.causal));
-  GemmArgs go = lin_fwd(c, L.o, T, L.t["wo"], L.t["bo"], L.u);
-  go.res = x; go.ldr = d;
-  DO(op_gemm(o, go));
-  DO(op_layernorm_fwd(o, L.u, c->P32(L.t["ln2.g"]), c->P32(L.t["ln2.b"]), L.c, L.mean2, L.rstd2, T, d));
-  GemmArgs g1 = lin_fwd(c, L.c, T, L.t["w1"], L.t["b1"], L.f);
-  g1.act = L.s.act == LP_ACT_RELU ? ACT_RELU : ACT_GELU;
-  g1.pre = L.fpre;
-  DO(op_gemm(o, g1));
-  GemmArgs g2 = lin_fwd(c, L.f, T, L.t["w2"], L.t["b2"], L.out);
-  g2.res = L.u; g2.ldr = d;
-  DO(op_gemm(o, g2));
+  out->n = 0;
+  if (stage == 0) {
+    if (li == 1 && c->spec.vocab > 0 && !L.in_override)
+      DO(op_embed_fwd(o, ids, c->P32(L.t["emb"]), c->pe, c->h0, T, S, d, c->spec.vocab));
+    const void* x = layer_input(c, li);
+    DO(op_layernorm_fwd(o, x, c->P32(L.t["ln1.g"]), c->P32(L.t["ln1.b"]), L.a, L.mean1, L.rstd1, T, d));
+    out->g[out->n++] = lin_fwd(c, L.a, T, L.t["wqkv"], L.t["bqkv"], L.qkv);
+  } else if (stage == 1) {
+    DO(op_attn_fwd(o, L.qkv, L.o, L.lse, batch, S, H, d / H, L.s.causal));
+    GemmArgs go = lin_fwd(c, L.o, T, L.t["wo"], L.t["bo"], L.u);
+    go.res = layer_input(c, li); go.ldr = d;
+    out->g[out->n++] = go;
+  } else if (stage == 2) {
+    DO(op_layernorm_fwd(o, L.u, c->P32(L.t["ln2.g"]), c->P32(L.t["ln2.b"]), L.c, L.mean2, L.rstd2, T, d));
+    GemmArgs g1 = lin_fwd(c, L.c, T, L.t["w1"], L.t["b1"], L.f);
+    g1.act = L.s.act == LP_ACT_RELU ? ACT_RELU : ACT_GELU;
+    g1.pre = L.fpre;
+    out->g[out->n++] = g1;
+  } else {
+    GemmArgs g2 = lin_fwd(c, L.f, T, L.t["w2"], L.t["b2"], L.out);
+    g2.res = L.u; g2.ldr = d;
+    out->g[out->n++] = g2;
+  }
+  return LP_OK;
+}
+
+static int dec_forward(lp_ctx* c, int li, int batch, const int32_t* ids) {
+  StageGemms sg;
+  for (int stage = 0; stage < kDecFwdStages; ++stage) {
+    int st = dec_forward_stage(c, li, batch, ids, stage, &sg);
+    if (st != LP_OK) return st;
+    DO(op_gemm_grouped(c->op(), sg.g, sg.n));
+  }
+  return LP_OK;
+}
+
+// The four weight gradients read (dY, X) pairs that all stay alive until the end of the layer's backward pass and
+// nothing in the pass reads them: they are collected in L.wg and handed back together by the last stage (one
+// grouped launch).
+int dec_backward_stage(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int acc,
+                       const int32_t* ids, bool params, int stage, StageGemms* out) {
+  LayerState& L = c->layers[li];
+  OpCtx o = c->op();
+  int S = L.s.seq_len, d = L.s.width, H = L.s.n_heads, F = L.s.hidden, T = batch * S;
+  bool has_emb = (li == 1 && c->spec.vocab > 0 && !L.in_override);
+  out->n = 0;
+  if (stage == 0) {            // FFN, second map
+    if (params) DO(op_colsum(o, dout, d, c->G32(L.t["b2"]), T, d, acc));
+    L.wg[0] = lin_wgrad(c, dout, L.f, T, L.t["w2"], acc);
+    GemmArgs gd = lin_dgrad(c, dout, T, L.t["w2"], c->dF);
+    gd.dact = L.s.act == LP_ACT_RELU ? ACT_RELU : ACT_GELU; gd.dact_src = L.fpre; gd.ldd = F;
+    out->g[out->n++] = gd;
+  } else if (stage == 1) {     // FFN, first map
+    if (params) DO(op_colsum(o, c->dF, F, c->G32(L.t["b1"]), T, F, acc));
+    L.wg[1] = lin_wgrad(c, c->dF, L.c, T, L.t["w1"], acc);
+    out->g[out->n++] = lin_dgrad(c, c->dF, T, L.t["w1"], c->dc);
+  } else if (stage == 2) {     // du = dout + LN2-backward(dc); attention output projection
+    DO(op_layernorm_bwd(o, c->dc, L.u, L.mean2, L.rstd2, c->P32(L.t["ln2.g"]), dout, c->du,
+                        params ? c->G32(L.t["ln2.g"]) : nullptr, params ? c->G32(L.t["ln2.b"]) : nullptr, T, d, acc));
+    if (params) DO(op_colsum(o, c->du, d, c->G32(L.t["bo"]), T, d, acc));
+    L.wg[2] = lin_wgrad(c, c->du, L.o, T, L.t["wo"], acc);
+    out->g[out->n++] = lin_dgrad(c, c->du, T, L.t["wo"], c->dO);
+  } else if (stage == 3) {     // attention, q/k/v projection
+    DO(op_attn_bwd(o, L.qkv, L.o, L.lse, c->dO, c->dqkv, c->delta, batch, S, H, d / H, L.s.causal));
+    if (params) DO(op_colsum(o, c->dqkv, 3 * d, c->G32(L.t["bqkv"]), T, 3 * d, acc));
+    L.wg[3] = lin_wgrad(c, c->dqkv, L.a, T, L.t["wqkv"], acc);
+    out->g[out->n++] = lin_dgrad(c, c->dqkv, T, L.t["wqkv"], c->da);
+  } else {
+    // dh = du + LN1-backward(da); the input gradient itself is only needed inside a window or for the embedding
+    const void* x = layer_input(c, li);
+    bool want_dx = need_dx || (has_emb && params);
+    void* dh = want_dx ? (has_emb ? c->da : dx) : nullptr;   // LN backward may write over its own dy rows
+    if (params || want_dx)
+      DO(op_layernorm_bwd(o, c->da, x, L.mean1, L.rstd1, c->P32(L.t["ln1.g"]), c->du, dh,
+                          params ? c->G32(L.t["ln1.g"]) : nullptr, params ? c->G32(L.t["ln1.b"]) : nullptr, T, d, acc));
+    if (has_emb && params) DO(op_embed_bwd(o, ids, dh, c->G32(L.t["emb"]), T, c->spec.vocab, d, acc));
+    if (params)
+      for (int i = 0; i < 4; ++i) out->g[out->n++] = L.wg[i];
+  }
   return LP_OK;
 }
 
 static int dec_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool need_dx, int acc,
                         const int32_t* ids, bool params) {
-  LayerState& L = c->layers[li];
-  OpCtx o = c->op();
-  int S = L.s.seq_len, d = L.s.width, H = L.s.n_heads, F = L.s.hidden, T = batch * S;
-  const void* x = layer_input(c, li);
-  bool has_emb = (li == 1 && c->spec.vocab > 0);
-  // The four weight gradients read (dY, X) pairs that all stay alive until the end of the layer's backward pass and
-  // nothing in the pass reads them: they are collected and launched together at the end (one grouped launch).
-  GemmArgs wg[4];
-  // FFN
-  if (params) DO(op_colsum(o, dout, d, c->G32(L.t["b2"]), T, d, acc));
-  wg[0] = lin_wgrad(c, dout, L.f, T, L.t["w2"], acc);
-  GemmArgs gd = lin_dgrad(c, dout, T, L.t["w2"], c->dF);
-  gd.dact = L.s.act == LP_ACT_RELU ? ACT_RELU : ACT_GELU; gd.dact_src = L.fpre; gd.ldd = F;
-  DO(op_gemm(o, gd));
-  if (params) DO(op_colsum(o, c->dF, F, c->G32(L.t["b1"]), T, F, acc));
-  wg[1] = lin_wgrad(c, c->dF, L.c, T, L.t["w1"], acc);
-  DO(op_gemm(o, lin_dgrad(c, c->dF, T, L.t["w1"], c->dc)));
-  // du = dout + LN2-backward(dc)
-  DO(op_layernorm_bwd(o, c->dc, L.u, L.mean2, L.rstd2, c->P32(L.t["ln2.g"]), dout, c->du,
-                      params ? c->G32(L.t["ln2.g"]) : nullptr, params ? c->G32(L.t["ln2.b"]) : nullptr, T, d, acc));
-  // attention block
-  if (params) DO(op_colsum(o, c->du, d, c->G32(L.t["bo"]), T, d, acc));
-  wg[2] = lin_wgrad(c, c->du, L.o, T, L.t["wo"], acc);
-  DO(op_gemm(o, lin_dgrad(c, c->du, T, L.t["wo"], c->dO)));
-  DO(op_attn_bwd(o, L.qkv, L.o, L.lse, c->dO, c->dqkv, c->delta, batch, S, H, d / H, L.s.causal));
-  if (params) DO(op_colsum(o, c->dqkv, 3 * d, c->G32(L.t["bqkv"]), T, 3 * d, acc));
-  wg[3] = lin_wgrad(c, c->dqkv, L.a, T, L.t["wqkv"], acc);
-  DO(op_gemm(o, lin_dgrad(c, c->dqkv, T, L.t["wqkv"], c->da)));
-  // dh = du + LN1-backward(da); the input gradient itself is only needed inside a window or for the embedding
-  bool want_dx = need_dx || (has_emb && params);
-  void* dh = want_dx ? (has_emb ? c->da : dx) : nullptr;   // LN backward may write over its own dy rows
-  if (params || want_dx)
-    DO(op_layernorm_bwd(o, c->da, x, L.mean1, L.rstd1, c->P32(L.t["ln1.g"]), c->du, dh,
-                        params ? c->G32(L.t["ln1.g"]) : nullptr, params ? c->G32(L.t["ln1.b"]) : nullptr, T, d, acc));
-  if (has_emb && params) DO(op_embed_bwd(o, ids, dh, c->G32(L.t["emb"]), T, c->spec.vocab, d, acc));
-  if (params) DO(op_gemm_grouped(o, wg, 4));
+  StageGemms sg;
+  for (int stage = 0; stage < kDecBwdStages; ++stage) {
+    int st = dec_backward_stage(c, li, batch, dout, dx, need_dx, acc, ids, params, stage, &sg);
+    if (st != LP_OK) return st;
+    DO(op_gemm_grouped(c->op(), sg.g, sg.n));
+  }
   return LP_OK;
 }
 
@@ -288,12 +324,47 @@ int drv_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx, bool 
 }
 
 // ===================================================================================== heads
+// The vocabulary head (LayerNorm, projection, cross-entropy) in stages, like the decoder layer: stage 0 ends in the
+// logits product, stage 1 (loss, dZ) in the head's weight gradient, stage 2 in its input gradient, stage 3 is the
+// LayerNorm backward.  Without `backward` only stages 0 and 1 do anything, and stage 1 hands back no product.
+int vocab_head_stage(lp_ctx* c, int hi, int batch, const int32_t* y, float* loss_out, bool backward, void* dh,
+                     int stage, StageGemms* out) {
+  HeadState& Hd = c->heads[hi];
+  LayerState& L = c->layers[Hd.e];
+  OpCtx o = c->op();
+  const int rows = batch * L.s.seq_len, in_dim = Hd.s.in_dim, ncls = Hd.s.n_classes;
+  out->n = 0;
+  if (stage == 0) {
+    DO(op_layernorm_fwd(o, L.out, c->P32(Hd.t["ln.g"]), c->P32(Hd.t["ln.b"]), c->feat, c->hmean, c->hrstd, rows, in_dim));
+    out->g[out->n++] = lin_fwd(c, c->feat, rows, Hd.t["w"], -1, c->logits);
+  } else if (stage == 1) {
+    DO(op_softmax_ce(o, c->logits, ncls, y, c->loss_rows, rows, ncls, backward ? 1 : 0, 1.0f / (float)rows));
+    DO(op_mean(o, c->loss_rows, rows, loss_out));
+    if (backward) out->g[out->n++] = lin_wgrad(c, c->logits, c->feat, rows, Hd.t["w"], 0);    // logits now hold dZ
+  } else if (stage == 2) {
+    if (backward) out->g[out->n++] = lin_dgrad(c, c->logits, rows, Hd.t["w"], c->dfeat);
+  } else if (backward) {
+    DO(op_layernorm_bwd(o, c->dfeat, L.out, c->hmean, c->hrstd, c->P32(Hd.t["ln.g"]), nullptr, dh,
+                        c->G32(Hd.t["ln.g"]), c->G32(Hd.t["ln.b"]), rows, in_dim, 0));
+  }
+  return LP_OK;
+}
+
 // Loss of head hi on the output of layer e; if `backward`, also the head's parameter gradients and
 // d loss / d h_e into dh.
 int drv_head(lp_ctx* c, int hi, int batch, const int32_t* y, float* loss_out, bool backward, void* dh) {
   HeadState& Hd = c->heads[hi];
   LayerState& L = c->layers[Hd.e];
   OpCtx o = c->op();
+  if (Hd.s.kind == LP_HEAD_LN_LINEAR_CE && !Hd.t.count("b")) {
+    StageGemms sg;
+    for (int stage = 0; stage < kVocabHeadStages; ++stage) {
+      int st = vocab_head_stage(c, hi, batch, y, loss_out, backward, dh, stage, &sg);
+      if (st != LP_OK) return st;
+      DO(op_gemm_grouped(c->op(), sg.g, sg.n));
+    }
+    return LP_OK;
+  }
   const void* h = L.out;
   int rows, in_dim = Hd.s.in_dim, ncls = Hd.s.n_classes;
   const void* feat = h;

@@ -205,11 +205,10 @@ struct SkPlan {
 // the grid exactly like a single problem's: whole tiles first, the last partial wave cut along k.  Each
 // launch by itself has too few tiles for 256 CUs (9 to 36 tiles of 256 x 256 for a width of 768); together
 // they fill the chip with pieces a third to a half as many.
-constexpr int kMaxGroup = 8;
+constexpr int kMaxGroup = 16;
 struct GroupTable {
   Operand A[kMaxGroup], B[kMaxGroup];
-  void* C[kMaxGroup];
-  int64_t ldc[kMaxGroup];
+  Epilogue e[kMaxGroup];          // every problem has its own fused epilogue and output
   int tiles_n[kMaxGroup];
   int first[kMaxGroup + 1];
 };
@@ -446,9 +445,7 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws, 
       char* xs = xpose_shape(WNW, TN, PIPE) ? smem + NSTAGE * STAGE_BYTES + wave * XPOSE_BYTES_PER_WAVE : nullptr;
       if (p.ngrp) {
         const int g = __builtin_amdgcn_readfirstlane(group_tile_coords(gt, p.ngrp, it.q, tm, tn));
-        Epilogue eg = e;
-        eg.C = gt.C[g]; eg.ldc = gt.ldc[g];
-        store_subtile<TN>(eg, acc, tm * BM + wm, tn * BN + wn, li, hf, gt.A[g].rows, gt.B[g].rows, xs);
+        store_subtile<TN>(gt.e[g], acc, tm * BM + wm, tn * BN + wn, li, hf, gt.A[g].rows, gt.B[g].rows, xs);
         return;
       }
       plan_tile_coords(p, it.q, tm, tn);
@@ -709,7 +706,7 @@ __global__ void __launch_bounds__(256) k_sk_fixup(const float* __restrict__ ws, 
   int tm, tn;
   if (p.ngrp) {
     const int g = group_tile_coords(gt, p.ngrp, p.full * p.G + tr, tm, tn);
-    e.C = gt.C[g]; e.ldc = gt.ldc[g]; M = gt.A[g].rows; N = gt.B[g].rows;
+    e = gt.e[g]; M = gt.A[g].rows; N = gt.B[g].rows;
   } else {
     plan_tile_coords(p, p.sib ? tr : p.full * p.G + tr, tm, tn);
   }
@@ -866,26 +863,27 @@ hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d) {
 #undef LP_DMA
 }
 
-// Grouped launch of n products (see GroupTable).  Returns hipErrorInvalidValue if the set does not qualify
-// (the caller then launches them one by one): same K (a multiple of 32), same operand layouts, fp32 output,
-// the same accumulate flag and nothing else fused, at most kMaxGroup problems, workspace for the cut tail.
+// Grouped launch of n products (see GroupTable).  Returns hipErrorInvalidValue, with nothing launched, if the set
+// does not qualify (the caller then launches them one by one): bf16 operands, the same K (a multiple of 32) and the
+// same operand layouts for all, every pointer and leading dimension fit for 16-byte accesses, at most kMaxGroup
+// problems, workspace for the cut tail.  Epilogues and output types may differ from problem to problem.
 hipError_t gemm_dma_grouped(const OpCtx& c, const GemmArgs* gs, int n) {
   if (n < 2 || n > kMaxGroup || c.dt != BF16) return hipErrorInvalidValue;
   const GemmArgs& g0 = gs[0];
   GroupTable gt = {};
   long T = 0;
   double flops = 0.0;
+  auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
   for (int i = 0; i < n; ++i) {
     const GemmArgs& g = gs[i];
-    if (!gemm_dma_ok(g) || g.K != g0.K || g.a_kc != g0.a_kc || g.b_kc != g0.b_kc || !g.c_f32 ||
-        g.accumulate != g0.accumulate || g.bias || g.pre || g.act != ACT_NONE || g.dact != ACT_NONE || g.res)
-      return hipErrorInvalidValue;
-    if (g.M % 8 || g.N % 8 || g.lda % 8 || g.ldb % 8 || g.ldc % 8 || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15) ||
-        ((uintptr_t)g.C & 15))
+    if (!gemm_dma_ok(g) || g.K != g0.K || g.a_kc != g0.a_kc || g.b_kc != g0.b_kc) return hipErrorInvalidValue;
+    if (g.M % 8 || g.N % 8 || g.lda % 8 || g.ldb % 8 || g.ldc % 8 || !al16(g.A) || !al16(g.B) || !al16(g.C) ||
+        (g.bias && !al16(g.bias)) || (g.pre && !al16(g.pre)) || (g.dact_src && (!al16(g.dact_src) || g.ldd % 8)) ||
+        (g.res && (!al16(g.res) || g.ldr % 8)))
       return hipErrorInvalidValue;
     gt.A[i] = Operand{(const bf16_t*)g.A, g.lda, g.M};
     gt.B[i] = Operand{(const bf16_t*)g.B, g.ldb, g.N};
-    gt.C[i] = g.C; gt.ldc[i] = g.ldc;
+    gt.e[i] = make_epilogue(g);
     gt.tiles_n[i] = (g.N + 255) / 256;
     gt.first[i] = (int)T;
     T += (long)((g.M + BM - 1) / BM) * gt.tiles_n[i];

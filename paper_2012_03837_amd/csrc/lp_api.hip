@@ -80,8 +80,20 @@ static int validate(const lp_model_spec* sp, std::string& err) {
     if (kind0 == LP_LAYER_DECODER && h.n_classes != sp->vocab) { err = std::string(where) + "n_classes != vocab"; return LP_ESHAPE; }
     if (kind0 == LP_LAYER_DECODER && h.bias) { err = std::string(where) + "vocabulary heads have no bias"; return LP_EUNSUPPORTED; }
   }
-  if (sp->schedule != LP_SCHED_SYNC && sp->schedule != LP_SCHED_PIPELINED) { err = "bad schedule"; return LP_EINVAL; }
-  if (sp->schedule == LP_SCHED_PIPELINED) {     // blocks must tile the layers: window j starts where window j-1 ends
+  if (sp->schedule < LP_SCHED_SYNC || sp->schedule > LP_SCHED_PIPELINED_GROUPED) { err = "bad schedule"; return LP_EINVAL; }
+  if (sp->schedule == LP_SCHED_PIPELINED_GROUPED) {
+    const lp_head_spec& h0 = sp->heads[0];
+    const int nl0 = (h0.window < h0.after_layer ? h0.window : h0.after_layer);
+    for (int j = 0; j < sp->n_heads; ++j) {
+      const lp_head_spec& h = sp->heads[j];
+      const int w = h.window < h.after_layer ? h.window : h.after_layer;
+      if (kind0 != LP_LAYER_DECODER || w != nl0 || h.kind != LP_HEAD_LN_LINEAR_CE || h.bias) {
+        err = "the grouped pipelined schedule needs decoder blocks of equal depth with vocabulary heads";
+        return LP_EUNSUPPORTED;
+      }
+    }
+  }
+  if (sp->schedule != LP_SCHED_SYNC) {          // blocks must tile the layers: window j starts where window j-1 ends
     int end = 0;
     for (int j = 0; j < sp->n_heads; ++j) {
       const lp_head_spec& h = sp->heads[j];
@@ -314,7 +326,7 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
         const Tensor& w = c->tensors[Hd.t["w"]];
         if (w.shape[0] % 8 == 0 && w.shape[1] % 8 == 0) c->wt[Hd.t["w"]] = wa.take(w.numel * 2);
       }
-  if (sp.schedule == LP_SCHED_PIPELINED) {
+  if (sp.schedule != LP_SCHED_SYNC) {
     const int J = sp.n_heads;
     c->label_elems_per_sample = kind0 == LP_LAYER_DECODER ? (size_t)sp.layers[0].seq_len : 1;
     c->stash_act.assign(J + 1, nullptr);
@@ -325,9 +337,14 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
     }
     c->in_batch.assign(J + 1, 0); c->ran_batch.assign(J + 1, 0); c->blk_updates.assign(J + 1, 0);
   }
+  // Grouped pipelined schedule: the blocks are walked in lockstep, stage by stage, so that their same-shaped GEMMs
+  // share grouped launches; every block then needs a scratch set of its own.
+  c->lockstep = sp.schedule == LP_SCHED_PIPELINED_GROUPED;
   // one scratch set for the caller's stream and one per side stream
   c->n_side = sp.n_streams;
-  c->sets.assign(1 + c->n_side, lp_scratch());
+  int nsets = 1 + c->n_side;
+  if (c->lockstep && nsets < sp.n_heads) nsets = sp.n_heads;
+  c->sets.assign(nsets, lp_scratch());
   for (auto& S : c->sets) {
     S.partial_elems = partial;
     S.partial = (float*)wa.take(partial * 4);
@@ -626,6 +643,103 @@ static int optimizer_range(lp_ctx* c, size_t b, size_t e, float grad_scale, int 
   return c->lowp ? refresh_wt(c, b, e - b) : LP_OK;      // behind the update, on the same stream
 }
 
+// Launches the products collected from one stage of several blocks, at most 16 to a grouped launch.
+static int launch_collected(lp_ctx* c, std::vector<GemmArgs>& v) {
+  for (size_t i = 0; i < v.size(); i += 16) {
+    const int n = (int)(v.size() - i < 16 ? v.size() - i : 16);
+    CK(op_gemm_grouped(c->op(), v.data() + i, n));
+  }
+  v.clear();
+  return LP_OK;
+}
+
+// The blocks of a pipelined call in lockstep (decoder blocks of equal depth): within a call the blocks are
+// independent (section 6), so stage s of every block of a team runs before stage s + 1 of any, and the GEMMs that
+// a stage hands back, one per block and of one shape, go out as one grouped launch.  With side streams the active
+// blocks form two teams on two streams: while one team's memory-bound kernels (normalisation, cross-entropy,
+// attention, column sums) run, the other team's grouped GEMM has the matrix cores.  Block j works in scratch
+// set j - 1.
+static int run_lockstep(lp_ctx* c, const int32_t* ids, float* losses) {
+  const int J = c->spec.n_heads, nl = c->heads[0].e - c->heads[0].s_lo;
+  std::vector<int> act;
+  for (int j = 1; j <= J; ++j) {
+    c->ran_batch[j] = c->in_batch[j];
+    if (c->in_batch[j] > 0) act.push_back(j);
+  }
+  // the teams (and with them the composition of every grouped launch, i.e. the order of every sum) do not depend
+  // on the number of streams: results are bit-identical with and without side streams
+  const int n_teams = act.size() >= 2 ? 2 : 1;
+  const bool two_streams = n_teams == 2 && c->n_side >= 2 && !c->prof.on;
+  std::vector<int> team[2];
+  for (size_t i = 0; i < act.size(); ++i) team[n_teams == 2 ? (int)(i & 1) : 0].push_back(act[i]);
+  hipStream_t tstream[2] = {c->stream, c->stream};
+  if (two_streams) {
+    CK(hipEventRecord(c->ev_pipe, c->stream));
+    for (int k = 0; k < 2; ++k) {
+      tstream[k] = c->sets[1 + k].cur_stream;
+      CK(hipStreamWaitEvent(tstream[k], c->ev_pipe, 0));
+    }
+  }
+  int cur_team = 0;
+  auto use_block = [&](int j) { c->use(j - 1); c->cur_stream = tstream[cur_team]; };
+  std::vector<GemmArgs> coll;
+  StageGemms sg;
+  int st;
+  for (int j : act)
+    if (j >= 2) c->layers[c->heads[j - 1].s_lo + 1].in_override = c->stash_act[j];
+  for (int off = 0; off < nl; ++off)
+    for (int stage = 0; stage < kDecFwdStages; ++stage)
+      for (cur_team = 0; cur_team < n_teams; ++cur_team) {
+        for (int j : team[cur_team]) {
+          use_block(j);
+          if ((st = dec_forward_stage(c, c->heads[j - 1].s_lo + 1 + off, c->in_batch[j], ids, stage, &sg)) != LP_OK) return st;
+          coll.insert(coll.end(), sg.g, sg.g + sg.n);
+        }
+        if ((st = launch_collected(c, coll)) != LP_OK) return st;
+      }
+  for (int stage = 0; stage < kVocabHeadStages; ++stage)
+    for (cur_team = 0; cur_team < n_teams; ++cur_team) {
+      for (int j : team[cur_team]) {
+        use_block(j);
+        if ((st = vocab_head_stage(c, j - 1, c->in_batch[j], c->ybuf[j], losses + (j - 1), true, c->dA, stage, &sg)) != LP_OK) return st;
+        coll.insert(coll.end(), sg.g, sg.g + sg.n);
+      }
+      if ((st = launch_collected(c, coll)) != LP_OK) return st;
+    }
+  for (int off = nl - 1; off >= 0; --off) {
+    const bool flip = ((nl - 1 - off) & 1) != 0;       // the blocks' gradient buffers alternate layer by layer
+    for (int stage = 0; stage < kDecBwdStages; ++stage)
+      for (cur_team = 0; cur_team < n_teams; ++cur_team) {
+        for (int j : team[cur_team]) {
+          use_block(j);
+          const void* dcur = flip ? c->dB : c->dA;
+          void* dnext = flip ? c->dA : c->dB;
+          if ((st = dec_backward_stage(c, c->heads[j - 1].s_lo + 1 + off, c->in_batch[j], dcur, dnext, off > 0, 0, ids, true,
+                                       stage, &sg)) != LP_OK) return st;
+          coll.insert(coll.end(), sg.g, sg.g + sg.n);
+        }
+        if ((st = launch_collected(c, coll)) != LP_OK) return st;
+      }
+    for (int j : act) c->layers[c->heads[j - 1].s_lo + 1 + off].seen = 1;
+  }
+  for (cur_team = 0; cur_team < n_teams; ++cur_team) {
+    for (int j : team[cur_team]) {
+      use_block(j);
+      HeadState& Hd = c->heads[j - 1];
+      const int t_blk = ++c->blk_updates[j];          // the block's own number of updates
+      if ((st = optimizer_range(c, Hd.p_begin, Hd.p_end, 1.f, t_blk)) != LP_OK) return st;
+      for (int lj = Hd.e; lj > Hd.s_lo; --lj)
+        if ((st = optimizer_range(c, c->layers[lj].p_begin, c->layers[lj].p_end, 1.f, t_blk)) != LP_OK) return st;
+    }
+    if (two_streams) {
+      CK(hipEventRecord(c->ev_chain[cur_team], tstream[cur_team]));
+      CK(hipStreamWaitEvent(c->stream, c->ev_chain[cur_team], 0));
+    }
+  }
+  c->use(0);
+  return LP_OK;
+}
+
 // One call of the pipelined schedule: first the hand-over on the caller's stream (every block's output of
 // the previous call and the labels that go with it move one block forward; the call's labels are kept for
 // the following calls), then every block that has an input runs as an independent chain.
@@ -647,10 +761,11 @@ static int run_pipelined(lp_ctx* c, const void* x, const int32_t* y, int batch, 
   }
   c->in_batch[1] = batch;
   CK(hipMemcpyAsync(c->ybuf[1], y, (size_t)batch * ly, hipMemcpyDeviceToDevice, c->stream));
-  const bool side = c->n_side > 0 && !c->prof.on;
-  if (side) CK(hipEventRecord(c->ev_pipe, c->stream));
   const int32_t* ids = c->spec.vocab > 0 ? (const int32_t*)x : nullptr;
   for (int li = 1; li <= c->spec.n_layers; ++li) { c->layers[li].seen = 0; c->layers[li].in_override = nullptr; }
+  if (c->lockstep) return run_lockstep(c, ids, losses);
+  const bool side = c->n_side > 0 && !c->prof.on;
+  if (side) CK(hipEventRecord(c->ev_pipe, c->stream));
   int chain = 0, st;
   for (int j = 1; j <= J; ++j) {
     const int nb = c->in_batch[j];
@@ -691,9 +806,9 @@ static int run(lp_ctx* c, const void* x, const int32_t* y, int batch, float* los
   c->bn_mode = train ? (c->bn_momentum > 0.f ? 1 : 0) : (c->bn_eval_running ? 2 : 0);
   // with per-op timing on, everything runs on the caller's stream so that each duration is the op's own
   const bool side = train && c->n_side > 0 && !c->prof.on;
-  const bool overlap = side && c->overlap_steps && batch > 0 && c->spec.schedule != LP_SCHED_PIPELINED;
+  const bool overlap = side && c->overlap_steps && batch > 0 && c->spec.schedule == LP_SCHED_SYNC;
   if (!overlap && (st = join_pending(c)) != LP_OK) return st;
-  if (train && batch > 0 && c->spec.schedule == LP_SCHED_PIPELINED) return run_pipelined(c, x, y, batch, losses);
+  if (train && batch > 0 && c->spec.schedule != LP_SCHED_SYNC) return run_pipelined(c, x, y, batch, losses);
   for (int li = 1; li <= L; ++li) c->layers[li].in_override = nullptr;
   if (batch == 0) {
     CK(op_fill_f32(c->op(), losses, (size_t)J, 0.f));
@@ -822,7 +937,7 @@ extern "C" int lp_step_graph(lp_ctx* c, int on) {
   if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
   if (on && c->spec.opt.kind == LP_OPT_ADAM)
     return fail(c, LP_EINVAL, "graph replay needs an optimizer without per-step scalars (Adam's bias correction changes every step)");
-  if (on && c->spec.schedule == LP_SCHED_PIPELINED)
+  if (on && c->spec.schedule != LP_SCHED_SYNC)
     return fail(c, LP_EINVAL, "graph replay is for the synchronous schedule");
   if (on && c->overlap_steps) return fail(c, LP_EINVAL, "overlapped steps are not replayed through a graph");
   { int sj = join_pending(c); if (sj != LP_OK) return sj; }
@@ -835,7 +950,7 @@ extern "C" int lp_overlap_steps(lp_ctx* c, int on) {
   if (!c) return LP_EINVAL;
   if (!c->ok) return fail(c, LP_ESTATE, "context is not usable");
   if (on && c->graph_on) return fail(c, LP_EINVAL, "steps replayed through a graph are not overlapped");
-  if (on && c->spec.schedule == LP_SCHED_PIPELINED) return fail(c, LP_EINVAL, "overlapping steps is for the synchronous schedule");
+  if (on && c->spec.schedule != LP_SCHED_SYNC) return fail(c, LP_EINVAL, "overlapping steps is for the synchronous schedule");
   int st = join_pending(c);
   if (st != LP_OK) return st;
   c->overlap_steps = on != 0;

@@ -46,13 +46,16 @@ extern "C" int lpk_gemm(int dtype, const void* A, int64_t lda, int a_kc, const v
   return (int)op_gemm(c, g);
 }
 extern "C" int lpk_gemm_grouped(int n, const void* const* A, const int64_t* lda, const void* const* B, const int64_t* ldb,
-                                float* const* C, const int64_t* ldc, const int* M, const int* N, int K, int a_kc,
-                                int b_kc, int accumulate, float* splitk_ws, size_t splitk_ws_elems, void* stream) {
-  if (n < 1 || n > 8 || !A || !lda || !B || !ldb || !C || !ldc || !M || !N) return (int)hipErrorInvalidValue;
-  GemmArgs g[8];
+                                void* const* C, const int64_t* ldc, int c_f32, const int* M, const int* N, int K, int a_kc,
+                                int b_kc, const float* const* bias, int act, const void* const* res, int accumulate,
+                                float* splitk_ws, size_t splitk_ws_elems, void* stream) {
+  if (n < 1 || n > 16 || !A || !lda || !B || !ldb || !C || !ldc || !M || !N) return (int)hipErrorInvalidValue;
+  GemmArgs g[16];
   for (int i = 0; i < n; ++i) {
     g[i].A = A[i]; g[i].lda = lda[i]; g[i].a_kc = a_kc; g[i].B = B[i]; g[i].ldb = ldb[i]; g[i].b_kc = b_kc;
-    g[i].C = C[i]; g[i].ldc = ldc[i]; g[i].c_f32 = 1; g[i].M = M[i]; g[i].N = N[i]; g[i].K = K;
+    g[i].C = C[i]; g[i].ldc = ldc[i]; g[i].c_f32 = c_f32; g[i].M = M[i]; g[i].N = N[i]; g[i].K = K;
+    g[i].bias = bias ? bias[i] : nullptr; g[i].act = act;
+    g[i].res = res ? res[i] : nullptr; g[i].ldr = ldc[i];
     g[i].accumulate = accumulate;
   }
   OpCtx c = mk(BF16, stream);

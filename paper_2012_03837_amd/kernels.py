@@ -37,16 +37,22 @@ def lpk_gemm(dtype, A, lda, a_kc, B, ldb, b_kc, Cout, ldc, c_f32, M, N, K, bias=
                        _sz(0 if splitk_ws is None else splitk_ws.numel()), _stream()), "lpk_gemm")
 
 
-def lpk_gemm_grouped(As, Bs, Cs, Ms, Ns, K, a_kc, b_kc, accumulate, splitk_ws):
-    """As, Bs, Cs: lists of torch CUDA tensors (bf16 operands as stored, fp32 outputs [M_i, N_i])."""
+def lpk_gemm_grouped(As, Bs, Cs, Ms, Ns, K, a_kc, b_kc, accumulate, splitk_ws, biases=None, act=0, ress=None):
+    """As, Bs, Cs: lists of torch CUDA tensors (bf16 operands as stored; outputs [M_i, N_i], all fp32 or all bf16);
+    biases / ress: optional lists of fp32 [N_i] / bf16 [M_i, N_i] tensors."""
+    import torch
     n = len(As)
     vp = (C.c_void_p * n)
     i64 = (C.c_int64 * n)
     ia = (C.c_int * n)
+    c_f32 = 1 if Cs[0].dtype == torch.float32 else 0
+    bias = vp(*[b.data_ptr() for b in biases]) if biases is not None else None
+    res = vp(*[r.data_ptr() for r in ress]) if ress is not None else None
     _ck(lib().lpk_gemm_grouped(_i(n), vp(*[a.data_ptr() for a in As]), i64(*[a.shape[1] for a in As]),
                                vp(*[b.data_ptr() for b in Bs]), i64(*[b.shape[1] for b in Bs]),
-                               vp(*[c.data_ptr() for c in Cs]), i64(*[c.shape[1] for c in Cs]), ia(*Ms), ia(*Ns), _i(K),
-                               _i(a_kc), _i(b_kc), _i(accumulate), _p(splitk_ws), _sz(splitk_ws.numel()), _stream()),
+                               vp(*[c.data_ptr() for c in Cs]), i64(*[c.shape[1] for c in Cs]), _i(c_f32), ia(*Ms), ia(*Ns),
+                               _i(K), _i(a_kc), _i(b_kc), bias, _i(act), res, _i(accumulate), _p(splitk_ws),
+                               _sz(splitk_ws.numel()), _stream()),
         "lpk_gemm_grouped")
 
 

@@ -189,3 +189,52 @@ def test_cfg2_full_step(lpmod):
         worst = max(worst, w)
     print("  worst rel err", worst, flush=True)
     tr.close()
+
+
+def test_cfg3_full_pipelined_grouped_blocks(lpmod):
+    """The pipelined schedule at full size, where the blocks of a call are walked in lockstep and their same-shaped
+    products share grouped launches.  Block 4 runs for the first time in call 4, with its initial weights, on the
+    activation block 3 produced in call 3 and the labels of minibatch 1, beside blocks 1..3 (already updated, on
+    younger minibatches): the oracle, fed that activation as data, must reproduce block 4's loss, gradients,
+    updated weights and Adam moments; the same for block 1 on the call's own minibatch."""
+    cfg = LI.make_config("cfg3")
+    print("[case] cfg3 full size, pipelined", flush=True)
+    tr = lpmod.LocalTrainer(cfg, schedule="pipelined_grouped", n_streams=lpmod.default_side_streams(cfg))
+    names4 = block_names(cfg, 4)[2]
+    P4 = {k: tr.get(k) for k in names4}
+    batches = [data_for(cfg, t) for t in range(4)]
+    for t in range(3):
+        got = tr.step(*tr.stage(*batches[t])).cpu().numpy().copy()
+        assert np.all(got[t + 1:] == 0.0) and np.all(got[:t + 1] > 0.0), got
+    h3 = tr.get("L3.out").astype(np.float64)            # what block 4 reads in the next call
+    names1 = block_names(cfg, 1)[2]
+    P1 = {k: tr.get(k) for k in names1}                 # block 1 after three updates
+    m1 = {k: tr.get(k + ".m").astype(np.float64) for k in names1}
+    v1 = {k: tr.get(k + ".v").astype(np.float64) for k in names1}
+    got = tr.step(*tr.stage(*batches[3])).cpu().numpy().copy()
+    # block 4: first update, labels of minibatch 1
+    y1 = batches[0][1]
+    ref_loss, grads, _ = oracle.block_gradients(cfg, P4, 4, h3, y1)
+    assert abs(got[3] - ref_loss) <= 2e-2 * abs(ref_loss), (got[3], ref_loss)
+    st = oracle.new_state(cfg, P4)
+    worst = 0.0
+    for k in names4:
+        err = relerr(tr.get(k + ".grad"), grads[k])
+        worst = max(worst, err)
+        assert err <= 2e-2, (k, err)
+        newp = OL.optimizer_update(cfg.opt, P4[k].astype(np.float64), grads[k], st, k, 1)
+        assert updated_param_err(tr.get(k), newp, grads[k], cfg.opt.kind) <= 2e-2, k
+        assert relerr(tr.get(k + ".m"), st["m"][k]) <= 2e-2 and relerr(tr.get(k + ".v"), st["v"][k]) <= 2e-2, k
+    # block 1: fourth update, on the call's own minibatch
+    x4, y4 = batches[3]
+    ref_loss, grads, _ = oracle.block_gradients(cfg, P1, 1, x4, y4)
+    assert abs(got[0] - ref_loss) <= 2e-2 * abs(ref_loss), (got[0], ref_loss)
+    st = {"t": 3, "m": m1, "v": v1}
+    for k in names1:
+        err = relerr(tr.get(k + ".grad"), grads[k])
+        worst = max(worst, err)
+        assert err <= 2e-2, (k, err)
+        OL.optimizer_update(cfg.opt, P1[k].astype(np.float64), grads[k], st, k, 4)
+        assert relerr(tr.get(k + ".m"), st["m"][k]) <= 2e-2 and relerr(tr.get(k + ".v"), st["v"][k]) <= 2e-2, k
+    print(f"  pipelined call 4, blocks 4 and 1: worst grad rel err {worst:.4f}", flush=True)
+    tr.close()

@@ -442,6 +442,26 @@ def test_gemm_grouped(K, gi, a_kc, b_kc):
         assert err <= 2e-6, (sh, "accumulate", err)
 
 
+def test_gemm_grouped_with_epilogues(K):
+    """Twelve same-shaped forward products of independent blocks in one launch (the pipelined schedule's layer
+    GEMMs): bf16 outputs through each problem's own fused epilogue (bias, ReLU, residual), ragged row counts."""
+    import torch
+    rng = np.random.default_rng(23)
+    ws = zeros(1 << 25)
+    Kd, N = 256, 520
+    Ms = [1304, 1304, 776, 8, 1304, 2056, 1304, 1304, 600, 1304, 1304, 1304]
+    W = [rnd(rng, (N, Kd), 1, 0.5) for _ in Ms]
+    X = [rnd(rng, (m, Kd), 1, 0.5) for m in Ms]
+    bias = [rng.standard_normal(N).astype(np.float32) for _ in Ms]
+    res = [rnd(rng, (m, N), 1) for m in Ms]
+    outs = [torch.zeros(m, N, device="cuda", dtype=torch.bfloat16) for m in Ms]
+    K.lpk_gemm_grouped([dev(x, 1) for x in X], [dev(w, 1) for w in W], outs, Ms, [N] * len(Ms), Kd, 1, 1, 0, ws,
+                       biases=[dev(b, 0) for b in bias], act=1, ress=[dev(r, 1) for r in res])
+    for i, m in enumerate(Ms):
+        ref = np.maximum(ops.linear_fwd(X[i].astype(np.float64), W[i].astype(np.float64), bias[i].astype(np.float64)), 0.0) + res[i]
+        assert relerr(host(outs[i]), ref) <= 4e-3, (i, m)
+
+
 def test_gemm_grouped_rejects_mixed_reductions(K):
     import torch
     ws = zeros(1 << 25)

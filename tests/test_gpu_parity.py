@@ -196,9 +196,13 @@ def test_gradient_cosines_local_vs_backprop(lpmod, name, dtype, tol):
     tb.close()
 
 
-@pytest.mark.parametrize("name,dtype", [("cfg1_small", "f32"), ("cfg3_small", "f32"), ("cfg2_small", "f32"),
-                                        ("cfg5_small", "f32"), ("cfg3_small", "bf16"), ("cfg5_small", "bf16")])
-def test_pipelined_schedule_matches_oracle(lpmod, name, dtype):
+@pytest.mark.parametrize("name,dtype,sched", [("cfg1_small", "f32", "pipelined"), ("cfg3_small", "f32", "pipelined"),
+                                              ("cfg2_small", "f32", "pipelined"), ("cfg5_small", "f32", "pipelined"),
+                                              ("cfg3_small", "bf16", "pipelined"), ("cfg5_small", "bf16", "pipelined"),
+                                              ("cfg3_small", "f32", "pipelined_grouped"),
+                                              ("cfg3_small", "bf16", "pipelined_grouped"),
+                                              ("cfg5_small", "bf16", "pipelined_grouped")])
+def test_pipelined_schedule_matches_oracle(lpmod, name, dtype, sched):
     """The pipelined schedule (section 6; labels travel with the activations, section 3) over J + 2 calls with a
     different minibatch each: losses (exactly 0 while a block waits for its first input), every block's
     parameters and optimizer moments after the last call, against the oracle's delay line; and the same
@@ -212,7 +216,7 @@ def test_pipelined_schedule_matches_oracle(lpmod, name, dtype):
     worst_p = worst_s = 0.0
     finals = []
     for ns in (0, 2):
-        tr = lpmod.LocalTrainer(cfg, schedule="pipelined", n_streams=ns)
+        tr = lpmod.LocalTrainer(cfg, schedule=sched, n_streams=ns)
         tr.set_params(P0)
         P = {k: v.astype(np.float64) for k, v in P0.items()}
         st, pipe = oracle.new_state(cfg, P), oracle.new_pipeline(cfg)
@@ -246,6 +250,9 @@ def test_pipelined_schedule_needs_tiling_windows(lpmod):
     cfg = dataclasses.replace(LI.make_config("cfg4_small"), dtype="f32")      # overlapping windows
     with pytest.raises(lpmod.LpError):
         lpmod.LocalTrainer(cfg, schedule="pipelined")
+    with pytest.raises(lpmod.LpError) as e:                                    # the grouped form is for decoder blocks
+        lpmod.LocalTrainer(LI.make_config("cfg2_small"), schedule="pipelined_grouped")
+    assert e.value.status == 7
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -259,12 +266,13 @@ def test_paper_form_resnet_head(lpmod, dtype):
     tr.close()
 
 
-def test_pipelined_schedule_with_changing_batch_sizes(lpmod):
+@pytest.mark.parametrize("sched", ["pipelined", "pipelined_grouped"])
+def test_pipelined_schedule_with_changing_batch_sizes(lpmod, sched):
     """Minibatches of different sizes travel down the pipeline with their own labels; a call with batch 0
     does not advance it."""
     cfg = dataclasses.replace(LI.make_config("cfg3_small"), dtype="f32")
     J = len(cfg.heads)
-    tr = lpmod.LocalTrainer(cfg, schedule="pipelined", n_streams=2)
+    tr = lpmod.LocalTrainer(cfg, schedule=sched, n_streams=2)
     P0 = generic_params(cfg)
     tr.set_params(P0)
     P = {k: v.astype(np.float64) for k, v in P0.items()}
