@@ -301,7 +301,9 @@ def main():
             ach = gf / (p["ms_per_step"] * 1e-3) / 1e12
             cls = {"kernels": kernel_names[key], "achieved": ach, "frac": ach / peak, "algorithmic_flops_per_step": gf,
                    "ops_per_step": p["ops_per_step"], "ms_per_step": p["ms_per_step"]}
-            kern = lp.lp_profile_gemm_kernels(tr.ctx) if key == "gemm" else []
+            kern = lp.lp_profile_gemm_kernels(tr.ctx)
+            if key == "conv":
+                kern = [r for r in kern if "Conv" in r["name"]]
             if kern:
                 # the single time-dominant kernel instance of this run: algorithmic FLOPs of its launches over the
                 # summed duration of exactly those launches (an event pair around each, on the launch stream)
@@ -314,7 +316,7 @@ def main():
                             "avg_launch_us": dom["ms"] / dom["launches"] * 1e3,
                             "flops_per_launch": dom["flops"] / dom["launches"],
                             "share_of_gemm_time": dom["ms"] / sum(r["ms"] for r in kern),
-                            "gemm_class": cls,
+                            ("gemm_class" if key == "gemm" else "conv_class"): cls,
                             "by_kernel": [{"kernel": r["name"], "launches_per_step": r["launches"] / K,
                                            "avg_launch_us": r["ms"] / r["launches"] * 1e3,
                                            "tflops": r["flops"] / (r["ms"] * 1e-3) / 1e12}

@@ -246,7 +246,7 @@ int lp_profile_enable(lp_ctx* ctx, int on);
  * line per shape: "M N K a_kc b_kc c_f32 count total_ms" (operand layouts as in lpk_gemm).  LP_ESHAPE if
  * the buffer is too small. */
 int lp_profile_gemm_shapes(lp_ctx* ctx, char* out, size_t cap);
-/* The main kernel of every bf16 GEMM op since profiling was enabled, grouped by kernel instance, as text into
+/* The main kernel of every bf16 GEMM op (and of every convolution run as implicit GEMM) since profiling was enabled, grouped by kernel instance, as text into
  * the host buffer `out`: one line per instance, "name<TAB>launches<TAB>total_ms<TAB>algorithmic_flops", where the
  * name is the kernel's name as a profiler prints it ("k_gemm_dma<true, true, 4, 2, 4, true>") and the time is
  * that of the one launch (an event pair around it; the op's partial-sum fix-up kernel, if any, is outside).

@@ -6,6 +6,7 @@
 //   dgrad   : dx[(n,h,w), c]   = sum_{(r,s,o)} dout[n, (h+pad-r)/st, (w+pad-s)/st, o] * w[o, r, s, c]
 //   wgrad   : dw[o, (r,s,c)]   = sum_{(n,p,q)} dout[(n,p,q), o] * x[n, p*st+r-pad, q*st+s-pad, c]   (fp32, split-K)
 // Needs C % 8 == 0 and O % 8 == 0; the 3-channel stem convolution stays on the plain kernel.
+#include <stdio.h>
 #include "common.h"
 #include "gemm_common.h"
 #include "mfma_tile.h"
@@ -183,13 +184,18 @@ Epilogue plain_epilogue(void* C, int64_t ldc, int c_f32, int accumulate) {
   return make_epilogue(g);
 }
 
+// `loaders` names the two loader types as a profiler prints them: the launch is timed under the kernel's name.
 template <class LA, class LB>
-hipError_t launch(const OpCtx& c, LA A, LB B, const Epilogue& e, int M, int N, int K, int splits) {
+hipError_t launch(const OpCtx& c, LA A, LB B, const Epilogue& e, int M, int N, int K, int splits, const char* loaders) {
   const int tn = (N + BN - 1) / BN;
   const bool big = ((M + 255) / 256) * tn * splits >= 400;
   const int bm = big ? 256 : 128;
   const int tm = (M + bm - 1) / bm;
   dim3 grid(tm * tn * splits);
+  static char names[2][96];
+  char* kname = names[big ? 1 : 0];
+  if (!kname[0]) snprintf(kname, sizeof names[0], "mfma::k_mfma_tiles<%s, %d>", loaders, bm);
+  ProfScope one_(c, KC_GEMM_KERNEL, 2.0 * M * N * K, 0, kname);
   if (big) k_mfma_tiles<LA, LB, 256><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
   else k_mfma_tiles<LA, LB, 128><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
   return hipGetLastError();
@@ -202,7 +208,8 @@ bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 // half the CUs get nothing.  Such products are cut along k into enough pieces for two to three blocks per CU;
 // the fp32 partial sums (M x N per piece) are added in piece order.
 template <class LA, class LB>
-hipError_t launch_cut(const OpCtx& c, LA A, LB B, void* out, int M, int N, int K, const void* add = nullptr) {
+hipError_t launch_cut(const OpCtx& c, LA A, LB B, void* out, int M, int N, int K, const char* loaders,
+                      const void* add = nullptr) {
   const int tiles = ((M + 127) / 128) * ((N + BN - 1) / BN);
   int splits = 1;
   if (c.splitk_ws && tiles < 200 && K >= 1024) {
@@ -213,7 +220,7 @@ hipError_t launch_cut(const OpCtx& c, LA A, LB B, void* out, int M, int N, int K
   }
   Epilogue e = plain_epilogue(out, N, 0, 0);
   e.res = add; e.ldr = N;      // a tensor of the output's shape added to the result
-  hipError_t err = launch(c, A, B, e, M, N, K, splits);
+  hipError_t err = launch(c, A, B, e, M, N, K, splits, loaders);
   if (err != hipSuccess || splits == 1) return err;
   const size_t work = (size_t)M * (N / 8);
   k_conv_splitk_reduce8<<<(unsigned)((work + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, e, M, N, splits);
@@ -230,14 +237,14 @@ hipError_t conv_fwd_mfma(const OpCtx& c, const ConvArgs& a, const void* x, const
   const int M = a.N * a.P * a.Q, K = a.R * a.S * a.C;
   ConvFwdA A{(const bf16_t*)x, a, M};
   PlainLoader<true> B{Operand{(const bf16_t*)w, K, a.O}};
-  return launch_cut(c, A, B, out, M, a.O, K);
+  return launch_cut(c, A, B, out, M, a.O, K, "ConvFwdA, mfma::PlainLoader<true>");
 }
 hipError_t conv_bwd_data_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
                               const void* add) {
   const int M = a.N * a.H * a.W, K = a.R * a.S * a.O;
   ConvBwdA A{(const bf16_t*)dout, a, M};
   ConvFilterT B{(const bf16_t*)w, a};
-  return launch_cut(c, A, B, dx, M, a.C, K, add);
+  return launch_cut(c, A, B, dx, M, a.C, K, "ConvBwdA, ConvFilterT", add);
 }
 hipError_t conv_bwd_weight_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                                 int accumulate) {
@@ -253,7 +260,8 @@ hipError_t conv_bwd_weight_mfma(const OpCtx& c, const ConvArgs& a, const void* d
     while (splits > 1 && (size_t)splits * a.O * J > c.splitk_elems) --splits;
     if (splits < 1) splits = 1;
   }
-  hipError_t e = launch(c, A, B, plain_epilogue(dw, J, 1, accumulate), a.O, J, Mrows, splits);
+  hipError_t e = launch(c, A, B, plain_epilogue(dw, J, 1, accumulate), a.O, J, Mrows, splits,
+                        "mfma::PlainLoader<false>, ConvPatchT");
   if (e != hipSuccess || splits == 1) return e;
   size_t total = (size_t)a.O * J;
   k_conv_splitk_reduce<<<(unsigned)((total + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, dw, a.O, J, splits, accumulate);
