@@ -120,7 +120,7 @@ __device__ __forceinline__ void epilogue8(const Epilogue& e, int m, int n, float
 
 // Per-lane global pointers of the direct-to-LDS loads of one operand: NI loads per thread per k-tile.
 // ROWS = tile rows of this operand.  The pointers are for k-tile 0; a k-tile step adds `kstep` elements.
-template <bool KC, int ROWS, int NI>
+template <bool KC, int ROWS, int NI, int KT = 32>
 struct DmaPlan {
   const bf16_t* g[NI];
   int lds_off[NI];      // byte offset of the wave's 1 KB destination inside the operand's stage region
@@ -130,7 +130,15 @@ struct DmaPlan {
     for (int i = 0; i < NI; ++i) {
       int q = wave * NI + i;              // which 1 KB of the tile
       lds_off[i] = q * 1024;
-      if (KC) {
+      if (KC && KT == 64) {
+        // 64-deep k-tiles: a tile row is one whole 128-byte line; an instruction covers 8 rows, lane l carries
+        // 16-byte chunk c of row l / 8 into slot c ^ ((row >> 1) & 7)
+        int row = q * 8 + (lane >> 3), slot = lane & 7;
+        int c = slot ^ ((row >> 1) & 7);
+        int rg = r0 + row;
+        rg = rg < o.rows ? rg : o.rows - 1;
+        g[i] = o.p + (size_t)rg * o.ld + kbase + 8 * c;
+      } else if (KC) {
         int row = q * 16 + (lane >> 2), slot = lane & 3;
         int c = slot ^ ((row >> 2) & 3);
         int rg = r0 + row;
@@ -146,7 +154,7 @@ struct DmaPlan {
         g[i] = o.p + (size_t)(kbase + k) * o.ld + rg;
       }
     }
-    kstep = KC ? (int64_t)BK : (int64_t)BK * o.ld;
+    kstep = KC ? (int64_t)KT : (int64_t)KT * o.ld;
   }
   __device__ __forceinline__ void issue(char* stage_base, int tile) const {
 #pragma unroll
@@ -160,6 +168,10 @@ struct DmaPlan {
 // fragment reads
 __device__ __forceinline__ bf16x8 frag_kc(const char* sm, int row, int chunk) {
   return *reinterpret_cast<const bf16x8*>(sm + row * 64 + 16 * (chunk ^ ((row >> 2) & 3)));
+}
+// 64-deep kc tile: 128-byte rows, chunk c (0..7) of row r in slot c ^ ((r >> 1) & 7)
+__device__ __forceinline__ bf16x8 frag_kc64(const char* sm, int row, int chunk) {
+  return *reinterpret_cast<const bf16x8*>(sm + row * 128 + 16 * (chunk ^ ((row >> 1) & 7)));
 }
 template <int ROWS>
 __device__ __forceinline__ bf16x8 frag_t(const char* sm, int rowbase, int k) {
@@ -373,11 +385,11 @@ __device__ __forceinline__ void interleave_hint_loads() {
   }
 }
 
-template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE, bool PIPE>
+template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE, bool PIPE, int KT = 32>
 __global__ void __launch_bounds__(128 * WNW, (WNW * TN == 4) ? 2 : (WNW == 4 ? 2 : 1))
 k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws, GroupTable gt) {
   constexpr int BN = 32 * TN * WNW, NWAVES = 2 * WNW;
-  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+  constexpr int A_BYTES = BM * KT * 2, B_BYTES = BN * KT * 2, STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int AI = (A_BYTES / 1024) / NWAVES, BI = (B_BYTES / 1024) / NWAVES, LPT = AI + BI;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int lane = threadIdx.x & 63;
@@ -435,8 +447,8 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws, 
     return false;
   };
 
-  DmaPlan<A_KC, BM, AI> pa;
-  DmaPlan<B_KC, BN, BI> pb;
+  DmaPlan<A_KC, BM, AI, KT> pa;
+  DmaPlan<B_KC, BN, BI, KT> pb;
 
   // Writes one finished item: a whole tile through the fused epilogue, a piece of a cut tile as raw partial sums.
   auto write_item = [&](const f32x16 (&acc)[TN][4], const ItemIter& it) {
@@ -464,7 +476,105 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws, 
         }
   };
 
-  if constexpr (PIPE) {
+  if constexpr (KT == 64) {
+    // 64-deep k-tiles (both operands k-contiguous, 8 waves): a tile row is a whole 128-byte line, so a direct-to-LDS
+    // instruction asks for 8 whole lines instead of 16 half lines, and there is one barrier per 64 of k.  Two
+    // stages of 64 KB: the loads of k-tile t + 2 are issued, into the stage k-tile t has just been read from, in
+    // the last of t's four 16-deep substeps (behind the barrier that also says k-tile t + 1 has landed), so they
+    // have a whole k-tile of MFMA time to land.  As in the 32-deep loop the k-tiles of all of a block's items form
+    // one stream through the two stages.
+    static_assert(A_KC && B_KC && NSTAGE == 2, "the 64-deep loop takes k-contiguous operands and two stages");
+    auto read = [&](const char* as, const char* bs, int kk, bf16x8* fn, bf16x8* fm) {
+#pragma unroll
+      for (int i = 0; i < TN; ++i) fn[i] = frag_kc64(bs, wn + 32 * i + n_row, 2 * kk + hf);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) fm[j] = frag_kc64(as, wm + 32 * j + li, 2 * kk + hf);
+    };
+    constexpr int NDS = 4 + TN;
+    ItemIter L = first_item(), C = L;
+    int lt = 0, l_left = 0, lstage = 0, cstage = 0, inflight = 0;
+    auto loader_ready = [&]() -> bool {
+      if (l_left > 0) return true;
+      if (!advance(L)) return false;
+      int tm, tn;
+      if (p.ngrp) {
+        const int g = __builtin_amdgcn_readfirstlane(group_tile_coords(gt, p.ngrp, L.q, tm, tn));
+        pa.init(gt.A[g], tm * BM, wave, lane, L.ks * KT);
+        pb.init(gt.B[g], tn * BN, wave, lane, L.ks * KT);
+      } else {
+        plan_tile_coords(p, L.q, tm, tn);
+        pa.init(A, tm * BM, wave, lane, L.ks * KT);
+        pb.init(B, tn * BN, wave, lane, L.ks * KT);
+      }
+      lt = 0; l_left = L.ke - L.ks;
+      return true;
+    };
+    auto issue_tile = [&]() {
+      char* dst = smem + lstage * STAGE_BYTES;
+      pa.issue(dst, lt);
+      pb.issue(dst + A_BYTES, lt);
+      ++lt; --l_left; ++inflight;
+      lstage ^= 1;
+    };
+#pragma unroll 1
+    for (int s = 0; s < 2; ++s)
+      if (loader_ready()) issue_tile();
+    if (!advance(C)) return;
+    bf16x8 fn0[TN], fm0[4], fn1[TN], fm1[4];
+    if (inflight >= 2) wait_loads_and_barrier<LPT>(); else wait_loads_and_barrier<0>();
+    --inflight;
+    read(smem, smem + A_BYTES, 0, fn0, fm0);
+    for (;;) {
+      f32x16 acc[TN][4];
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) acc[i][j][x] = 0.f;
+      auto mma = [&](const bf16x8* fn, const bf16x8* fm) {
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
+      };
+      const int nt = C.ke - C.ks;
+      for (int t = 0; t < nt; ++t) {
+        const char* as = smem + cstage * STAGE_BYTES;
+        const char* bs = as + A_BYTES;
+        read(as, bs, 1, fn1, fm1);
+        mma(fn0, fm0);
+        interleave_hint<4 * TN, NDS, 0>();
+        __builtin_amdgcn_sched_barrier(0);
+        read(as, bs, 2, fn0, fm0);
+        mma(fn1, fm1);
+        interleave_hint<4 * TN, NDS, 0>();
+        __builtin_amdgcn_sched_barrier(0);
+        read(as, bs, 3, fn1, fm1);
+        mma(fn0, fm0);
+        interleave_hint<4 * TN, NDS, 0>();
+        __builtin_amdgcn_sched_barrier(0);
+        // last substep: behind the barrier every wave has read all of this stage and the next k-tile has landed
+        const bool more = inflight > 0;
+        const bool last = t + 1 == nt;
+        if (more) {
+          wait_loads_and_barrier<0>();
+          --inflight;
+          cstage ^= 1;
+          if (!last) read(smem + cstage * STAGE_BYTES, smem + cstage * STAGE_BYTES + A_BYTES, 0, fn0, fm0);
+          if (loader_ready()) issue_tile();
+        }
+        mma(fn1, fm1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      const ItemIter done = C;
+      const bool have = advance(C);
+      write_item(acc, done);
+      if (!have) break;
+      read(smem + cstage * STAGE_BYTES, smem + cstage * STAGE_BYTES + A_BYTES, 0, fn0, fm0);
+    }
+  } else if constexpr (PIPE) {
     // The block's k-tiles, item after item, are one stream through the ring of LDS stages: the loader runs
     // NSTAGE-1 k-tiles ahead of the MFMAs *across item boundaries*, so the first k-tiles of the next item are
     // already in flight while the current item finishes and is written.
@@ -501,12 +611,12 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws, 
       int tm, tn;
       if (p.ngrp) {
         const int g = __builtin_amdgcn_readfirstlane(group_tile_coords(gt, p.ngrp, L.q, tm, tn));
-        pa.init(gt.A[g], tm * BM, wave, lane, L.ks * BK);
-        pb.init(gt.B[g], tn * BN, wave, lane, L.ks * BK);
+        pa.init(gt.A[g], tm * BM, wave, lane, L.ks * KT);
+        pb.init(gt.B[g], tn * BN, wave, lane, L.ks * KT);
       } else {
         plan_tile_coords(p, L.q, tm, tn);
-        pa.init(A, tm * BM, wave, lane, L.ks * BK);
-        pb.init(B, tn * BN, wave, lane, L.ks * BK);
+        pa.init(A, tm * BM, wave, lane, L.ks * KT);
+        pb.init(B, tn * BN, wave, lane, L.ks * KT);
       }
       lt = 0; l_left = L.ke - L.ks;
       return true;
@@ -624,12 +734,12 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws, 
       nt = I.ke - I.ks;
       if (p.ngrp) {
         const int g = __builtin_amdgcn_readfirstlane(group_tile_coords(gt, p.ngrp, I.q, tm, tn));
-        pa.init(gt.A[g], tm * BM, wave, lane, I.ks * BK);
-        pb.init(gt.B[g], tn * BN, wave, lane, I.ks * BK);
+        pa.init(gt.A[g], tm * BM, wave, lane, I.ks * KT);
+        pb.init(gt.B[g], tn * BN, wave, lane, I.ks * KT);
       } else {
         plan_tile_coords(p, I.q, tm, tn);
-        pa.init(A, tm * BM, wave, lane, I.ks * BK);
-        pb.init(B, tn * BN, wave, lane, I.ks * BK);
+        pa.init(A, tm * BM, wave, lane, I.ks * KT);
+        pb.init(B, tn * BN, wave, lane, I.ks * KT);
       }
 #pragma unroll
       for (int s = 0; s < NSTAGE - 1; ++s)
@@ -742,13 +852,13 @@ int device_cus() {
   return n;
 }
 
-template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE, bool PIPE>
+template <bool A_KC, bool B_KC, int WNW, int TN, int NSTAGE, bool PIPE, int KT = 32>
 hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool partials, const GroupTable* grp = nullptr,
                   double flops = 0.0) {
   constexpr int BN = 32 * TN * WNW;
-  constexpr int smem = NSTAGE * (BM + BN) * BK * 2 + (xpose_shape(WNW, TN, PIPE) ? 2 * WNW * XPOSE_BYTES_PER_WAVE : 0);
+  constexpr int smem = NSTAGE * (BM + BN) * KT * 2 + (xpose_shape(WNW, TN, PIPE) ? 2 * WNW * XPOSE_BYTES_PER_WAVE : 0);
   static bool configured = false;
-  auto kern = k_gemm_dma<A_KC, B_KC, WNW, TN, NSTAGE, PIPE>;
+  auto kern = k_gemm_dma<A_KC, B_KC, WNW, TN, NSTAGE, PIPE, KT>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
@@ -758,8 +868,8 @@ hipError_t launch(const OpCtx& c, const GemmArgs& g, const SkPlan& p, bool parti
   Epilogue e = make_epilogue(g);
   static char kname[64];
   if (!kname[0])
-    snprintf(kname, sizeof kname, "k_gemm_dma<%s, %s, %d, %d, %d, %s>", A_KC ? "true" : "false", B_KC ? "true" : "false",
-             WNW, TN, NSTAGE, PIPE ? "true" : "false");
+    snprintf(kname, sizeof kname, KT == 32 ? "k_gemm_dma<%s, %s, %d, %d, %d, %s>" : "k_gemm_dma<%s, %s, %d, %d, %d, %s, 64>",
+             A_KC ? "true" : "false", B_KC ? "true" : "false", WNW, TN, NSTAGE, PIPE ? "true" : "false");
   hipError_t err;
   static const GroupTable no_group = {};
   const GroupTable& gt = grp ? *grp : no_group;
@@ -784,16 +894,19 @@ bool gemm_dma_ok(const GemmArgs& g) { return g.K % 32 == 0 && g.K >= 32 && g.M >
 // mode 0: every tile whole, one per block per wave; 1: the last, partial wave of tiles cut along k;
 // 2: panel mode (see SkPlan).  Modes 1 and 2 need workspace.  Returns false if the mode does not apply.
 bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int kind, int mode, DmaGemmPlan* out) {
+  // kind 3: 256 x 256 with 8 waves and 64-deep k-tiles (k-contiguous operands, K a multiple of 64)
+  if (kind == 3 && !(g.a_kc && g.b_kc && g.K % 64 == 0)) return false;
+  const int bk = kind == 3 ? 64 : BK;
   const int bn = kind == 0 ? 128 : 256, per_cu = kind == 0 ? 2 : 1;
   SkPlan p;
   p.G = (device_cus() * per_cu) & ~7;
   p.tiles_m = (g.M + BM - 1) / BM;
   p.tiles_n = (g.N + bn - 1) / bn;
-  p.kt = g.K / BK;
+  p.kt = g.K / bk;
   p.sib = 0;
   p.ngrp = 0;
   const long T = (long)p.tiles_m * p.tiles_n;
-  const long min_len = 4, max_cut = 16;                 // shortest piece; most pieces per tile
+  const long min_len = kind == 3 ? 2 : 4, max_cut = 16;                 // shortest piece; most pieces per tile
   auto clamp_upb = [&](long upb, bool within_tile) {
     if (upb < min_len) upb = min_len;
     if (upb * max_cut < p.kt) upb = (p.kt + max_cut - 1) / max_cut;
@@ -852,6 +965,7 @@ hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d) {
   p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.kt = d.kt; p.full = d.full; p.tail_tiles = d.tail_tiles;
   p.upb = d.upb; p.G = d.G; p.sib = d.sib; p.ngrp = 0;
   const bool partials = d.partial_bytes > 0;
+  if (d.kind == 3) return launch<true, true, 4, 2, 2, true, 64>(c, g, p, partials);
 #define LP_DMA(AK, BK_)                                                    \
   (d.kind == 1 ? launch<AK, BK_, 4, 2, 4, true>(c, g, p, partials)                \
    : d.kind == 2 ? launch<AK, BK_, 2, 4, 5, true>(c, g, p, partials)              \
