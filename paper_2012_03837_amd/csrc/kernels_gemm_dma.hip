@@ -483,14 +483,18 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws, 
     // the last of t's four 16-deep substeps (behind the barrier that also says k-tile t + 1 has landed), so they
     // have a whole k-tile of MFMA time to land.  As in the 32-deep loop the k-tiles of all of a block's items form
     // one stream through the two stages.
-    static_assert(A_KC && B_KC && NSTAGE == 2, "the 64-deep loop takes k-contiguous operands and two stages");
+    static_assert(NSTAGE == 2, "the 64-deep loop has two stages");
     auto read = [&](const char* as, const char* bs, int kk, bf16x8* fn, bf16x8* fm) {
 #pragma unroll
-      for (int i = 0; i < TN; ++i) fn[i] = frag_kc64(bs, wn + 32 * i + n_row, 2 * kk + hf);
+      for (int i = 0; i < TN; ++i)
+        fn[i] = B_KC ? frag_kc64(bs, wn + 32 * i + n_row, 2 * kk + hf)
+                     : frag_t<BN>(bs, wn + 32 * i + n_rowbase_t, 16 * kk + 8 * hf + kq);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) fm[j] = frag_kc64(as, wm + 32 * j + li, 2 * kk + hf);
+      for (int j = 0; j < 4; ++j)
+        fm[j] = A_KC ? frag_kc64(as, wm + 32 * j + li, 2 * kk + hf)
+                     : frag_t<BM>(as, wm + 32 * j + m_rowbase_t, 16 * kk + 8 * hf + kq);
     };
-    constexpr int NDS = 4 + TN;
+    constexpr int NDS = (A_KC ? 4 : 8) + (B_KC ? TN : 2 * TN);
     ItemIter L = first_item(), C = L;
     int lt = 0, l_left = 0, lstage = 0, cstage = 0, inflight = 0;
     auto loader_ready = [&]() -> bool {
@@ -539,13 +543,23 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws, 
           for (int j = 0; j < 4; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[i], fm[j], acc[i][j], 0, 0, 0);
       };
-      const int nt = C.ke - C.ks;
-      for (int t = 0; t < nt; ++t) {
+      // One 64-deep k-tile.  STEADY (1: first of a run, 2: later ones): the loader is two k-tiles ahead inside this
+      // item, so everything is unconditional: the A half of k-tile t + 2 goes out in t's last substep (behind the
+      // barrier), its B half in the first substep of t + 1, so that a wave's eight loads do not reach the memory
+      // pipeline in one burst.  Otherwise (0) the whole k-tile goes out in the last substep, if there is one.
+      auto step = [&](auto steady, bool last) {
+        constexpr int ST = decltype(steady)::value;
         const char* as = smem + cstage * STAGE_BYTES;
         const char* bs = as + A_BYTES;
         read(as, bs, 1, fn1, fm1);
-        mma(fn0, fm0);
-        interleave_hint<4 * TN, NDS, 0>();
+        if (ST == 2) {
+          pb.issue(smem + (lstage ^ 1) * STAGE_BYTES + A_BYTES, lt - 1);
+          mma(fn0, fm0);
+          interleave_hint_loads<4 * TN, NDS, BI>();
+        } else {
+          mma(fn0, fm0);
+          interleave_hint<4 * TN, NDS, 0>();
+        }
         __builtin_amdgcn_sched_barrier(0);
         read(as, bs, 2, fn0, fm0);
         mma(fn1, fm1);
@@ -556,18 +570,41 @@ k_gemm_dma(Operand A, Operand B, Epilogue e, int M, int N, SkPlan p, float* ws, 
         interleave_hint<4 * TN, NDS, 0>();
         __builtin_amdgcn_sched_barrier(0);
         // last substep: behind the barrier every wave has read all of this stage and the next k-tile has landed
-        const bool more = inflight > 0;
-        const bool last = t + 1 == nt;
-        if (more) {
+        if (ST != 0) {
           wait_loads_and_barrier<0>();
-          --inflight;
           cstage ^= 1;
-          if (!last) read(smem + cstage * STAGE_BYTES, smem + cstage * STAGE_BYTES + A_BYTES, 0, fn0, fm0);
-          if (loader_ready()) issue_tile();
+          read(smem + cstage * STAGE_BYTES, smem + cstage * STAGE_BYTES + A_BYTES, 0, fn0, fm0);
+          pa.issue(smem + lstage * STAGE_BYTES, lt);
+          ++lt; --l_left;
+          lstage ^= 1;
+          mma(fn1, fm1);
+          interleave_hint_loads<4 * TN, NDS, AI>();
+        } else {
+          const bool more = inflight > 0;
+          bool load = false;
+          if (more) load = loader_ready();
+          __builtin_amdgcn_sched_barrier(0);
+          if (more) {
+            wait_loads_and_barrier<0>();
+            --inflight;
+            cstage ^= 1;
+            if (load) issue_tile();
+            if (!last) read(smem + cstage * STAGE_BYTES, smem + cstage * STAGE_BYTES + A_BYTES, 0, fn0, fm0);
+          }
+          mma(fn1, fm1);
+          interleave_hint<4 * TN, NDS, 0>();
         }
-        mma(fn1, fm1);
         __builtin_amdgcn_sched_barrier(0);
+      };
+      const int nt = C.ke - C.ks;
+      int t = 0;
+      typedef std::integral_constant<int, 0> General;
+      if (nt >= 3) {           // k-tiles 0 .. nt - 3 have their k-tile t + 2 inside this item
+        step(std::integral_constant<int, 1>{}, false);
+        for (t = 1; t + 3 <= nt; ++t) step(std::integral_constant<int, 2>{}, false);
+        pb.issue(smem + (lstage ^ 1) * STAGE_BYTES + A_BYTES, lt - 1);
       }
+      for (; t < nt; ++t) step(General{}, t + 1 == nt);
       const ItemIter done = C;
       const bool have = advance(C);
       write_item(acc, done);
@@ -894,8 +931,8 @@ bool gemm_dma_ok(const GemmArgs& g) { return g.K % 32 == 0 && g.K >= 32 && g.M >
 // mode 0: every tile whole, one per block per wave; 1: the last, partial wave of tiles cut along k;
 // 2: panel mode (see SkPlan).  Modes 1 and 2 need workspace.  Returns false if the mode does not apply.
 bool gemm_dma_plan(const OpCtx& c, const GemmArgs& g, int kind, int mode, DmaGemmPlan* out) {
-  // kind 3: 256 x 256 with 8 waves and 64-deep k-tiles (k-contiguous operands, K a multiple of 64)
-  if (kind == 3 && !(g.a_kc && g.b_kc && g.K % 64 == 0)) return false;
+  // kind 3: 256 x 256 with 8 waves and 64-deep k-tiles (K a multiple of 64)
+  if (kind == 3 && g.K % 64 != 0) return false;
   const int bk = kind == 3 ? 64 : BK;
   const int bn = kind == 0 ? 128 : 256, per_cu = kind == 0 ? 2 : 1;
   SkPlan p;
@@ -965,9 +1002,9 @@ hipError_t gemm_dma(const OpCtx& c, const GemmArgs& g, const DmaGemmPlan& d) {
   p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.kt = d.kt; p.full = d.full; p.tail_tiles = d.tail_tiles;
   p.upb = d.upb; p.G = d.G; p.sib = d.sib; p.ngrp = 0;
   const bool partials = d.partial_bytes > 0;
-  if (d.kind == 3) return launch<true, true, 4, 2, 2, true, 64>(c, g, p, partials);
 #define LP_DMA(AK, BK_)                                                    \
-  (d.kind == 1 ? launch<AK, BK_, 4, 2, 4, true>(c, g, p, partials)                \
+  (d.kind == 3 ? launch<AK, BK_, 4, 2, 2, true, 64>(c, g, p, partials)            \
+   : d.kind == 1 ? launch<AK, BK_, 4, 2, 4, true>(c, g, p, partials)              \
    : d.kind == 2 ? launch<AK, BK_, 2, 4, 5, true>(c, g, p, partials)              \
                  : launch<AK, BK_, 2, 2, 3, false>(c, g, p, partials))
   if (g.a_kc && g.b_kc) return LP_DMA(true, true);
@@ -1008,7 +1045,12 @@ hipError_t gemm_dma_grouped(const OpCtx& c, const GemmArgs* gs, int n) {
   SkPlan p;
   p.G = device_cus() & ~7;
   p.tiles_m = (int)T; p.tiles_n = 1;                 // only the product is used outside the tile numbering
-  p.kt = g0.K / BK;
+  static int deep_ok = -1;           // LP_GROUP_K64=0 keeps the 32-deep k-tiles (for measurements)
+  if (deep_ok < 0) { const char* e = getenv("LP_GROUP_K64"); deep_ok = (e && e[0] == '0') ? 0 : 1; }
+  const bool deep = deep_ok && g0.K % 64 == 0 && g0.K >= 128;
+  const int bk = deep ? 64 : BK;
+  const long min_len = deep ? 2 : 4;
+  p.kt = g0.K / bk;
   p.sib = 0; p.ngrp = n;
   p.full = (int)(T / p.G);
   p.tail_tiles = (int)(T - (long)p.full * p.G);
@@ -1027,12 +1069,12 @@ hipError_t gemm_dma_grouped(const OpCtx& c, const GemmArgs* gs, int n) {
     // paid back.  The uniform cut is taken when it leaves the longest block at most 1.25 times the balanced work.
     const long U = (long)p.tail_tiles * p.kt;
     long upb = (U + p.G - 1) / p.G;
-    if (upb < 4) upb = 4;
+    if (upb < min_len) upb = min_len;
     if (upb * 16 < p.kt) upb = (p.kt + 15) / 16;
     if (upb > p.kt) upb = p.kt;
     long s = p.G / p.tail_tiles;
     if (s < 1) s = 1;
-    while (s > 1 && (p.kt % s != 0 || p.kt / s < 4)) --s;
+    while (s > 1 && (p.kt % s != 0 || p.kt / s < min_len)) --s;
     const long upb_uniform = p.kt / s;
     static int forced = -1;           // LP_GROUP_SPLIT=balanced|uniform forces one (for measurements)
     if (forced < 0) { const char* e = getenv("LP_GROUP_SPLIT"); forced = !e ? 0 : (e[0] == 'b' ? 1 : (e[0] == 'u' ? 2 : 0)); }
@@ -1045,7 +1087,8 @@ hipError_t gemm_dma_grouped(const OpCtx& c, const GemmArgs* gs, int n) {
   }
   ProfScope prof_(c, KC_GEMM, flops);
   GemmArgs g = g0;                                    // epilogue flags (fp32 output, accumulate) are common
-#define LP_DMA_G(AK, BK_) launch<AK, BK_, 4, 2, 4, true>(c, g, p, partials, &gt, flops)
+#define LP_DMA_G(AK, BK_) \
+  (deep ? launch<AK, BK_, 4, 2, 2, true, 64>(c, g, p, partials, &gt, flops) : launch<AK, BK_, 4, 2, 4, true>(c, g, p, partials, &gt, flops))
   if (g.a_kc && g.b_kc) return LP_DMA_G(true, true);
   if (g.a_kc && !g.b_kc) return LP_DMA_G(true, false);
   if (!g.a_kc && g.b_kc) return LP_DMA_G(false, true);

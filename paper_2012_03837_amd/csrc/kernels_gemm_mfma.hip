@@ -103,6 +103,12 @@ static bool trace_on() {     // LP_GEMM_TRACE=1 prints the chosen kernel and pla
 static const double kDmaStep[4] = {2796.0, 2300.0, 2300.0, 4200.0};      // 256 x 128 (two per CU), 256 x 256; 64-deep
 static const double kDmaFixed[4] = {7000.0, 9000.0, 9000.0, 9000.0};
 
+static bool deep_auto() {     // LP_GEMM_K64=0 keeps the 64-deep k-tiles out of the automatic choice (for measurements)
+  static int v = -1;
+  if (v < 0) { const char* s = getenv("LP_GEMM_K64"); v = (s && s[0] == '0') ? 0 : 1; }
+  return v != 0;
+}
+
 hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   const int choice = c.gemm_variant ? c.gemm_variant : env_choice();
@@ -111,7 +117,7 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   DmaGemmPlan best_dma;
   bool use_dma = false;
   int force_kind = -1, force_cut = -1;
-  if (choice == 20 || choice == 21) { force_kind = 3; force_cut = choice - 20; }     // 64-deep k-tiles, tail whole / cut
+  if (choice >= 20 && choice <= 22) { force_kind = 3; force_cut = choice - 20; }     // 64-deep k-tiles: tail whole / cut / panel mode
   else if (choice >= 13) force_kind = (choice - 13) / 2;
   else if (choice >= 9) { force_kind = choice - 9; force_cut = 2; }
   else if (choice >= 3) { force_kind = (choice - 3) / 2; force_cut = (choice - 3) % 2; }
@@ -121,7 +127,7 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   const bool short_and_few = g.K <= 1024 && (long)((g.M + 255) / 256) * ((g.N + 255) / 256) <= 512;
   if (gemm_dma_ok(g) && choice != 2 && !(choice == 0 && short_and_few)) {
     for (int kind = 0; kind < 4; ++kind) {
-      if (force_kind >= 0 ? kind != force_kind : kind >= 2) continue;   // the 4-wave and the 64-deep shapes only when asked for
+      if (force_kind >= 0 ? kind != force_kind : (kind == 2 || (kind == 3 && !deep_auto()))) continue;   // the 4-wave shape only when asked for
       for (int cut = 0; cut < 3; ++cut) {                 // tail whole / cut along k / panel mode
         if (force_cut >= 0 && cut != force_cut) continue;
         DmaGemmPlan d;

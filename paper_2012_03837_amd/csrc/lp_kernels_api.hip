@@ -34,7 +34,7 @@ extern "C" int lpk_gemm(int dtype, const void* A, int64_t lda, int a_kc, const v
                         int64_t ldc, int c_f32, int M, int N, int K, const float* bias, int act, void* pre,
                         const void* dact_src, int dact, int64_t ldd, const void* res, int64_t ldr, int accumulate,
                         int variant, float* splitk_ws, size_t splitk_ws_elems, void* stream) {
-  if (variant < 0 || (variant > 11 && variant != 20 && variant != 21)) return (int)hipErrorInvalidValue;
+  if (variant < 0 || (variant > 11 && (variant < 20 || variant > 22))) return (int)hipErrorInvalidValue;
   GemmArgs g;
   g.A = A; g.lda = lda; g.a_kc = a_kc; g.B = B; g.ldb = ldb; g.b_kc = b_kc; g.C = C; g.ldc = ldc; g.c_f32 = c_f32;
   g.M = M; g.N = N; g.K = K; g.bias = bias; g.act = act; g.pre = pre; g.dact_src = dact_src; g.dact = dact; g.ldd = ldd;

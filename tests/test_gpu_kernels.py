@@ -405,11 +405,12 @@ GROUPS = [
     (8192, [(768, 3072), (3072, 768), (768, 768), (2304, 768)]),
     (2048, [(264, 520), (520, 136), (8, 8), (1000, 264), (136, 776)]),
     (512, [(4096, 4104), (2056, 1032)]),
+    (1056, [(520, 264), (264, 776), (2056, 520)]),       # K not a multiple of 64: the 32-deep k-tiles
 ]
 
 
 @pytest.mark.parametrize("a_kc,b_kc", [(0, 0), (1, 1), (1, 0)])
-@pytest.mark.parametrize("gi", [0, 1, 2])
+@pytest.mark.parametrize("gi", [0, 1, 2, 3])
 def test_gemm_grouped(K, gi, a_kc, b_kc):
     """Every product of a grouped launch against the CPU oracle's linear layer in float64, with and without
     accumulation onto existing outputs; bit-repeatable; and the same bits as each product launched alone where the
@@ -473,32 +474,35 @@ def test_gemm_grouped_rejects_mixed_reductions(K):
         K.lpk_gemm_grouped([a, a], [a, a], [o, o], [64, 64], [64, 64], 40, 1, 1, 0, ws)   # K not a multiple of 32
 
 
-@pytest.mark.parametrize("variant", [20, 21])
-def test_gemm_persistent_64_deep_k_tiles(K, variant):
-    """The direct-to-LDS kernel with 64-deep k-tiles (k-contiguous operands, K a multiple of 64), tail whole / cut
-    along k: against the CPU oracle's linear layer, with a fused epilogue, and bit-repeatable."""
+@pytest.mark.parametrize("variant", [20, 21, 22])
+@pytest.mark.parametrize("a_kc,b_kc", [(1, 1), (1, 0), (0, 0), (0, 1)])
+def test_gemm_persistent_64_deep_k_tiles(K, variant, a_kc, b_kc):
+    """The direct-to-LDS kernel with 64-deep k-tiles (K a multiple of 64), tail whole / cut along k / panel mode:
+    against the CPU oracle's linear layer, with a fused epilogue, and bit-repeatable."""
     import torch
-    rng = np.random.default_rng(11)
+    rng = np.random.default_rng(11 if variant != 22 else 13)
     ws = zeros(1 << 25)
-    for (M, N, Kd) in DMA_SHAPES:
+    for (M, N, Kd) in (DMA_SHAPES if variant != 22 else PANEL_SHAPES):
         A = rnd(rng, (M, Kd), 1, 0.5)
         B = rnd(rng, (N, Kd), 1, 0.5)
         if Kd % 64:
             continue
-        dA, dB = dev(A, 1), dev(B, 1)
-        ref = oracle_product("dma", A, B)
+        Am = A if a_kc else np.ascontiguousarray(A.T)
+        Bm = B if b_kc else np.ascontiguousarray(B.T)
+        dA, dB = dev(Am, 1), dev(Bm, 1)
+        ref = oracle_product("dma" if variant != 22 else "panel", A, B)
         out = torch.full((M, N), 7.0, device="cuda", dtype=torch.float32)
-        K.lpk_gemm(1, dA, Kd, 1, dB, Kd, 1, out, N, 1, M, N, Kd, variant=variant, splitk_ws=ws)
+        K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out, N, 1, M, N, Kd, variant=variant, splitk_ws=ws)
         err = float((out.double() - ref).norm() / ref.norm())
         assert err <= 2e-6, (M, N, Kd, variant, err)
         bias = rng.standard_normal(N).astype(np.float32)
         res = rnd(rng, (M, N), 1)
         outb = torch.zeros(M, N, device="cuda", dtype=torch.bfloat16)
-        K.lpk_gemm(1, dA, Kd, 1, dB, Kd, 1, outb, N, 0, M, N, Kd, bias=dev(bias, 0), res=dev(res, 1), ldr=N, variant=variant,
-                   splitk_ws=ws)
+        K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, outb, N, 0, M, N, Kd, bias=dev(bias, 0), res=dev(res, 1),
+                   ldr=N, variant=variant, splitk_ws=ws)
         refb = ref + torch.from_numpy(bias).cuda().double() + torch.from_numpy(res).cuda().double()
         errb = float((outb.double() - refb).norm() / refb.norm())
         assert errb <= 4e-3, (M, N, Kd, variant, errb)
         out2 = torch.zeros_like(out)
-        K.lpk_gemm(1, dA, Kd, 1, dB, Kd, 1, out2, N, 1, M, N, Kd, variant=variant, splitk_ws=ws)
+        K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out2, N, 1, M, N, Kd, variant=variant, splitk_ws=ws)
         assert torch.equal(out, out2)
