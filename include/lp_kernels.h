@@ -26,7 +26,8 @@ extern "C" {
  * of tiles computed whole / cut along k, 5 / 6 the same with 256 x 256 tiles and 8 wavefronts, 7 / 8 with
  * 256 x 256 tiles and 4 wavefronts; 9 / 10 / 11 those three tile shapes in panel mode (outputs 2..8 tiles
  * wide: the tile columns of one tile row walk the same cut of the reduction together, so that the other
- * operand is fetched once per row); an error if the shape does not qualify (K % 32 != 0, no workspace for
+ * operand is fetched once per row); 20 / 21 / 22 the 8-wavefront 256 x 256 shape with 64-deep k-tiles (K a
+ * multiple of 64), tail whole / cut along k / panel mode; an error if the shape does not qualify (K % 32 != 0, no workspace for
  * a cut, an output too narrow or too wide or a reduction too short for panel mode).  splitk_ws_dev (may be NULL) is fp32 workspace of
  * splitk_ws_elems floats: with it, reductions over few output tiles are split along k and the partial sums
  * added in a fixed order (at most max(8 * M * N, 2^25) floats are used). */

@@ -506,3 +506,42 @@ def test_gemm_persistent_64_deep_k_tiles(K, variant, a_kc, b_kc):
         out2 = torch.zeros_like(out)
         K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out2, N, 1, M, N, Kd, variant=variant, splitk_ws=ws)
         assert torch.equal(out, out2)
+
+
+@pytest.mark.parametrize("variant", [5, 6, 20, 21])
+@pytest.mark.parametrize("a_kc,b_kc", [(1, 1), (1, 0)])
+def test_gemm_persistent_fused_epilogues(K, variant, a_kc, b_kc):
+    """Every fused epilogue of the direct-to-LDS kernel (whole sub-tiles through the row-layout path, ragged edges
+    through the element path): bias + GELU / ReLU with the stored pre-activation and a residual, and the backward
+    forms (activation derivative from a stored source, residual added), against float64 from the CPU oracle's ops."""
+    import torch
+    rng = np.random.default_rng(17)
+    ws = zeros(1 << 25)
+    for (M, N, Kd) in [(520, 264, 256), (2056, 776, 128), (4096, 1024, 64)]:
+        A = rnd(rng, (M, Kd), 1, 0.5)
+        B = rnd(rng, (N, Kd), 1, 0.5)
+        bias = rng.standard_normal(N).astype(np.float32)
+        ldr, ldd = N + 8, N + 16                                   # strided residual and derivative source
+        res = rnd(rng, (M, ldr), 1)
+        dsrc = rnd(rng, (M, ldd), 1)
+        Am = A if a_kc else np.ascontiguousarray(A.T)
+        Bm = B if b_kc else np.ascontiguousarray(B.T)
+        dA, dB, dres, dds, dbias = dev(Am, 1), dev(Bm, 1), dev(res, 1), dev(dsrc, 1), dev(bias, 0)
+        ref0 = A.astype(np.float64) @ B.astype(np.float64).T
+        v = ref0 + bias
+        for act, fwd in ((2, ops.gelu_fwd), (1, lambda z: np.maximum(z, 0.0))):
+            out = torch.full((M, N), 3.0, device="cuda", dtype=torch.bfloat16)
+            pre = torch.full((M, N), 3.0, device="cuda", dtype=torch.bfloat16)
+            K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out, N, 0, M, N, Kd, bias=dbias, act=act, pre=pre,
+                       res=dres, ldr=ldr, variant=variant, splitk_ws=ws)
+            want = fwd(v) + res[:, :N]
+            assert relerr(host(pre), v) <= 4e-3, (M, N, Kd, variant, "pre")
+            assert relerr(host(out), want) <= 4e-3, (M, N, Kd, variant, "act", act)
+            assert np.max(np.abs(host(out).astype(np.float64) - want)) <= 0.02 * max(1.0, np.max(np.abs(want)))
+        for dact, fn in ((1, lambda s, g: g * (s > 0)), (2, ops.gelu_bwd)):
+            out = torch.full((M, N), 3.0, device="cuda", dtype=torch.bfloat16)
+            K.lpk_gemm(1, dA, Am.shape[1], a_kc, dB, Bm.shape[1], b_kc, out, N, 0, M, N, Kd, dact_src=dds, dact=dact, ldd=ldd,
+                       res=dres, ldr=ldr, variant=variant, splitk_ws=ws)
+            want = fn(dsrc[:, :N].astype(np.float64), ref0) + res[:, :N]
+            assert relerr(host(out), want) <= 4e-3, (M, N, Kd, variant, "dact", dact)
+            assert np.max(np.abs(host(out).astype(np.float64) - want)) <= 0.02 * max(1.0, np.max(np.abs(want)))
