@@ -96,11 +96,11 @@ __device__ __forceinline__ AttnBlock attn_block(int H, int BH, int nblk, bool he
 }
 
 // ================================================================================= forward
-__global__ void __launch_bounds__(256) k_attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
+__global__ void __launch_bounds__(256, 3) k_attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
                                                        float* __restrict__ lse, int S, int H, int BH, int causal) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[64][ALD];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[64][ALD];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, hf = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), n = lane & 31, hf = lane >> 5;
   const AttnBlock ab = attn_block(H, BH, (S + 127) / 128, causal != 0);
   const int bx = ab.x;
   const int h = ab.h, b = ab.b, d = H * 64;
@@ -218,7 +218,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dq_mfma(const bf16_t* __res
                                                           float* __restrict__ delta, int S, int H, int BH, int causal) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[64][ALD];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[64][ALD];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, hf = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), n = lane & 31, hf = lane >> 5;
   const AttnBlock ab = attn_block(H, BH, (S + 127) / 128, causal != 0);
   const int bx = ab.x;
   const int h = ab.h, b = ab.b, d = H * 64;
@@ -330,7 +330,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dkv_mfma(const bf16_t* __re
   __shared__ __attribute__((aligned(16))) bf16_t dOs[64][ALD];
   __shared__ __attribute__((aligned(16))) float lse2s[64];
   __shared__ __attribute__((aligned(16))) float deltas[64];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, hf = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), n = lane & 31, hf = lane >> 5;
   const AttnBlock ab = attn_block(H, BH, (S + 127) / 128, false);
   const int bx = ab.x;
   const int h = ab.h, b = ab.b, d = H * 64;
@@ -386,21 +386,35 @@ __global__ void __launch_bounds__(256, 2) k_attn_bwd_dkv_mfma(const bf16_t* __re
         s = MFMA32(qa, kf[kk], s);
         dp = MFMA32(da, vf[kk], dp);
       }
+      // wave-uniform: the masked form only on tiles that touch the diagonal or the end of the sequence
+      if (need_mask) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f32x4 l4 = *reinterpret_cast<const f32x4*>(&lse2s[32 * i + 8 * g + 4 * hf]);
-        f32x4 d4 = *reinterpret_cast<const f32x4*>(&deltas[32 * i + 8 * g + 4 * hf]);
+        for (int g = 0; g < 4; ++g) {
+          f32x4 l4 = *reinterpret_cast<const f32x4*>(&lse2s[32 * i + 8 * g + 4 * hf]);
+          f32x4 d4 = *reinterpret_cast<const f32x4*>(&deltas[32 * i + 8 * g + 4 * hf]);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          int v = 4 * g + j;
-          float p = __builtin_amdgcn_exp2f(s[v] * c - l4[j]);
-          if (need_mask) {
+          for (int j = 0; j < 4; ++j) {
+            int v = 4 * g + j;
+            float p = __builtin_amdgcn_exp2f(s[v] * c - l4[j]);
             int qrow = q0 + 32 * i + 8 * g + 4 * hf + j;
             bool masked = qrow >= S || kj >= S || (causal && kj > qrow);
             p = masked ? 0.f : p;
+            s[v] = p;
+            dp[v] = p * (dp[v] - d4[j]);
           }
-          s[v] = p;
-          dp[v] = p * (dp[v] - d4[j]);          // the factor 1/sqrt(64) of dS is applied once, to the finished dK
+        }
+      } else {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4 l4 = *reinterpret_cast<const f32x4*>(&lse2s[32 * i + 8 * g + 4 * hf]);
+          f32x4 d4 = *reinterpret_cast<const f32x4*>(&deltas[32 * i + 8 * g + 4 * hf]);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            int v = 4 * g + j;
+            float p = __builtin_amdgcn_exp2f(s[v] * c - l4[j]);
+            s[v] = p;
+            dp[v] = p * (dp[v] - d4[j]);          // the factor 1/sqrt(64) of dS is applied once, to the finished dK
+          }
         }
       }
 #pragma unroll
