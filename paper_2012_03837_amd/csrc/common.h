@@ -143,6 +143,9 @@ hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const
                             const float* g, const void* add, void* dx, float* dg, float* db, int rows, int d,
                             int accumulate);
 hipError_t op_colsum(const OpCtx& c, const void* dy, int64_t ld, float* out, int rows, int n, int accumulate);
+// count (<= 4 for the single pair of launches) column sums over the same rows; the same bits as op_colsum one by one
+hipError_t op_colsum_batched(const OpCtx& c, int count, const void* const* dy, const int64_t* ld, float* const* out,
+                             int rows, const int* n, int accumulate);
 
 hipError_t op_attn_fwd(const OpCtx& c, const void* qkv, void* o, float* lse, int B, int S, int H, int dh,
                        int causal);

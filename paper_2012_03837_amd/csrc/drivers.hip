@@ -175,24 +175,20 @@ int dec_backward_stage(lp_ctx* c, int li, int batch, const void* dout, void* dx,
   bool has_emb = (li == 1 && c->spec.vocab > 0 && !L.in_override);
   out->n = 0;
   if (stage == 0) {            // FFN, second map
-    if (params) DO(op_colsum(o, dout, d, c->G32(L.t["b2"]), T, d, acc));
     L.wg[0] = lin_wgrad(c, dout, L.f, T, L.t["w2"], acc);
     GemmArgs gd = lin_dgrad(c, dout, T, L.t["w2"], c->dF);
     gd.dact = L.s.act == LP_ACT_RELU ? ACT_RELU : ACT_GELU; gd.dact_src = L.fpre; gd.ldd = F;
     out->g[out->n++] = gd;
   } else if (stage == 1) {     // FFN, first map
-    if (params) DO(op_colsum(o, c->dF, F, c->G32(L.t["b1"]), T, F, acc));
     L.wg[1] = lin_wgrad(c, c->dF, L.c, T, L.t["w1"], acc);
     out->g[out->n++] = lin_dgrad(c, c->dF, T, L.t["w1"], c->dc);
   } else if (stage == 2) {     // du = dout + LN2-backward(dc); attention output projection
     DO(op_layernorm_bwd(o, c->dc, L.u, L.mean2, L.rstd2, c->P32(L.t["ln2.g"]), dout, c->du,
                         params ? c->G32(L.t["ln2.g"]) : nullptr, params ? c->G32(L.t["ln2.b"]) : nullptr, T, d, acc));
-    if (params) DO(op_colsum(o, c->du, d, c->G32(L.t["bo"]), T, d, acc));
     L.wg[2] = lin_wgrad(c, c->du, L.o, T, L.t["wo"], acc);
     out->g[out->n++] = lin_dgrad(c, c->du, T, L.t["wo"], c->dO);
   } else if (stage == 3) {     // attention, q/k/v projection
     DO(op_attn_bwd(o, L.qkv, L.o, L.lse, c->dO, c->dqkv, c->delta, batch, S, H, d / H, L.s.causal));
-    if (params) DO(op_colsum(o, c->dqkv, 3 * d, c->G32(L.t["bqkv"]), T, 3 * d, acc));
     L.wg[3] = lin_wgrad(c, c->dqkv, L.a, T, L.t["wqkv"], acc);
     out->g[out->n++] = lin_dgrad(c, c->dqkv, T, L.t["wqkv"], c->da);
   } else {
@@ -204,8 +200,15 @@ int dec_backward_stage(lp_ctx* c, int li, int batch, const void* dout, void* dx,
       DO(op_layernorm_bwd(o, c->da, x, L.mean1, L.rstd1, c->P32(L.t["ln1.g"]), c->du, dh,
                           params ? c->G32(L.t["ln1.g"]) : nullptr, params ? c->G32(L.t["ln1.b"]) : nullptr, T, d, acc));
     if (has_emb && params) DO(op_embed_bwd(o, ids, dh, c->G32(L.t["emb"]), T, c->spec.vocab, d, acc));
-    if (params)
+    if (params) {
+      // the four bias gradients: column sums of the same dY matrices the weight gradients read, in one pair of launches
+      const void* dys[4] = {dout, c->dF, c->du, c->dqkv};
+      const int64_t lds[4] = {d, F, d, 3 * d};
+      float* outs[4] = {c->G32(L.t["b2"]), c->G32(L.t["b1"]), c->G32(L.t["bo"]), c->G32(L.t["bqkv"])};
+      const int ns[4] = {d, F, d, 3 * d};
+      DO(op_colsum_batched(o, 4, dys, lds, outs, T, ns, acc));
       for (int i = 0; i < 4; ++i) out->g[out->n++] = L.wg[i];
+    }
   }
   return LP_OK;
 }

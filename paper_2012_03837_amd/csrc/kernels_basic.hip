@@ -348,6 +348,7 @@ hipError_t op_layernorm_bwd(const OpCtx& c, const void* dy, const void* x, const
 // ------------------------------------------------------------------------------------ column sums
 // out[j] (+)= sum_r dy[r, j]  (bias gradients).  Block = 64 columns x 4 row-lanes over a slab of rows.
 constexpr int kColsumRows = 128;
+constexpr int kMaxColsumBatch = 4;
 template <typename T>
 __global__ void k_colsum_partial(const T* dy, int64_t ld, float* partial, int rows, int n) {
   __shared__ float sh[4][64];
@@ -409,6 +410,120 @@ hipError_t op_colsum(const OpCtx& c, const void* dy, int64_t ld, float* out, int
     else k_colsum_partial<float><<<grid, 256, 0, c.stream>>>((const float*)dy, ld, part, rows, n);
   }
   if (!direct) k_reduce_partials<<<(n + 63) / 64, 64 * kReduceGroups, 0, c.stream>>>(c.partial, nslab, n, out, accumulate);
+  return LP_LAUNCH_CHECK();
+}
+
+// Several column sums over the same rows in one pair of launches (the four bias gradients of a decoder layer, whose
+// dY matrices all stay alive until the end of the layer's backward pass): the column blocks of all problems form one
+// grid, each problem keeps a partial table of its own behind the previous one's, and the sums are taken in exactly the
+// order of the single-problem kernels above, so the results are the same bits.
+struct ColsumBatch {
+  const bf16_t* dy[kMaxColsumBatch];
+  int64_t ld[kMaxColsumBatch];
+  float* out[kMaxColsumBatch];
+  int n[kMaxColsumBatch];
+  int first128[kMaxColsumBatch + 1];      // first 128-column block of problem p in the partial kernel's grid
+  int first64[kMaxColsumBatch + 1];       // first 64-column block in the reduce kernel's grid
+  size_t part_off[kMaxColsumBatch];       // start of problem p's [nslab][n] partial table
+  int count;
+};
+__global__ void __launch_bounds__(256)
+k_colsum_partial_batched(ColsumBatch b, float* __restrict__ partial, int rows) {
+  __shared__ float sh[16][128];
+  int p = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxColsumBatch; ++i)
+    if (i < b.count && (int)blockIdx.x >= b.first128[i]) p = i;
+  const bf16_t* dy = b.dy[p];
+  const int64_t ld = b.ld[p];
+  const int n = b.n[p];
+  float* part = partial + b.part_off[p];
+  const int ch = threadIdx.x & 15, w = threadIdx.x >> 4;
+  const int cb = blockIdx.x - b.first128[p];
+  const int col = cb * 128 + ch * 8;
+  const int r0 = blockIdx.y * kColsumRows;
+  const int r1 = r0 + kColsumRows < rows ? r0 + kColsumRows : rows;
+  float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (col < n)
+    for (int r = r0 + w; r < r1; r += 16) {
+      bf16x8 v = *reinterpret_cast<const bf16x8*>(dy + (size_t)r * ld + col);
+#pragma unroll
+      for (int x = 0; x < 8; ++x) a[x] += (float)v[x];
+    }
+#pragma unroll
+  for (int x = 0; x < 8; ++x) sh[w][ch * 8 + x] = a[x];
+  __syncthreads();
+  if (threadIdx.x < 128) {
+    const int cc = cb * 128 + threadIdx.x;
+    if (cc < n) {
+      float t = 0.f;
+#pragma unroll
+      for (int g = 0; g < 16; ++g) t += sh[g][threadIdx.x];
+      part[(size_t)blockIdx.y * n + cc] = t;
+    }
+  }
+}
+__global__ void __launch_bounds__(64 * kReduceGroups)
+k_reduce_partials_batched(ColsumBatch b, const float* __restrict__ partial, int nblk, int accumulate) {
+  __shared__ float sh[kReduceGroups][64];
+  int p = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxColsumBatch; ++i)
+    if (i < b.count && (int)blockIdx.x >= b.first64[i]) p = i;
+  const float* part = partial + b.part_off[p];
+  const int n = b.n[p];
+  float* out = b.out[p];
+  int lc = threadIdx.x & 63, q = threadIdx.x >> 6;
+  int j = (blockIdx.x - b.first64[p]) * 64 + lc;
+  float a = 0.f;
+  if (j < n) {
+    int r = q;
+    for (; r + 3 * kReduceGroups < nblk; r += 4 * kReduceGroups) {
+      float v0 = part[(size_t)r * n + j], v1 = part[(size_t)(r + kReduceGroups) * n + j];
+      float v2 = part[(size_t)(r + 2 * kReduceGroups) * n + j], v3 = part[(size_t)(r + 3 * kReduceGroups) * n + j];
+      a += v0; a += v1; a += v2; a += v3;
+    }
+    for (; r < nblk; r += kReduceGroups) a += part[(size_t)r * n + j];
+  }
+  sh[q][lc] = a;
+  __syncthreads();
+  if (q == 0 && j < n) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < kReduceGroups; ++g) t += sh[g][lc];
+    out[j] = accumulate ? out[j] + t : t;
+  }
+}
+hipError_t op_colsum_batched(const OpCtx& c, int count, const void* const* dy, const int64_t* ld, float* const* out,
+                             int rows, const int* n, int accumulate) {
+  if (count <= 0) return hipSuccess;
+  const int nslab = (rows + kColsumRows - 1) / kColsumRows;
+  bool fast = c.dt == BF16 && count <= kMaxColsumBatch && nslab > 1;
+  size_t total = 0;
+  for (int p = 0; p < count; ++p) {
+    fast = fast && n[p] > 0 && n[p] % 8 == 0 && ld[p] % 8 == 0 && ((uintptr_t)dy[p] & 15) == 0;
+    total += (size_t)nslab * n[p];
+  }
+  if (!fast || total > c.partial_elems) {         // one by one: any type, any alignment
+    for (int p = 0; p < count; ++p) {
+      hipError_t e = op_colsum(c, dy[p], ld[p], out[p], rows, n[p], accumulate);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
+  ProfScope prof_(c, KC_COLSUM);
+  ColsumBatch b = {};
+  b.count = count;
+  size_t off = 0;
+  int f128 = 0, f64 = 0;
+  for (int p = 0; p < count; ++p) {
+    b.dy[p] = (const bf16_t*)dy[p]; b.ld[p] = ld[p]; b.out[p] = out[p]; b.n[p] = n[p];
+    b.first128[p] = f128; b.first64[p] = f64; b.part_off[p] = off;
+    f128 += (n[p] + 127) / 128; f64 += (n[p] + 63) / 64; off += (size_t)nslab * n[p];
+  }
+  for (int p = count; p <= kMaxColsumBatch; ++p) { b.first128[p] = f128; b.first64[p] = f64; }
+  k_colsum_partial_batched<<<dim3(f128, nslab), 256, 0, c.stream>>>(b, c.partial, rows);
+  k_reduce_partials_batched<<<f64, 64 * kReduceGroups, 0, c.stream>>>(b, c.partial, nslab, accumulate);
   return LP_LAUNCH_CHECK();
 }
 

@@ -258,8 +258,10 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
       size_t widest = F > 3 * d ? F : 3 * d;
       size_t pr = ((T + 7) / 8) * d * 2;      // LayerNorm backward: dg and db partials of every 8-row block
       size_t pc = ((T + 127) / 128) * (widest > (size_t)sp.vocab ? widest : (size_t)sp.vocab);
+      size_t pb = ((T + 127) / 128) * (F + 5 * d);   // the four bias gradients' partial tables side by side
       if (pr > partial) partial = pr;
       if (pc > partial) partial = pc;
+      if (pb > partial) partial = pb;
     } else {
       int hw_in = l.in_hw, hw_out = l.in_hw / l.stride;
       std::string p = "L" + std::to_string(li) + ".";
