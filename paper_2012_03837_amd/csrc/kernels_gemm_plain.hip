@@ -174,9 +174,82 @@ static hipError_t launch_plain(hipStream_t s, OA A, OB B, const Epilogue& e, int
   return hipGetLastError();
 }
 
+// A product with a handful of rows or columns (a classifier head over 10 classes: its forward map and its weight
+// gradient): as tiles it is one to eight blocks that walk K in 32-deep steps, each step a memory latency, 35 us
+// for 10 x 512 x 256.  Here a block owns 64 output elements (neighbouring threads own neighbouring columns, so an
+// operand that is contiguous in n is read in whole lines and the other one is broadcast) and its four waves each
+// take a quarter of K, 32 k at a time with every load of the step in flight at once (16-byte loads where k is the
+// contiguous index); a thread adds its products in k order and the four quarters are added in order through LDS.
+template <typename T>
+__device__ __forceinline__ void skinny_load8(const PlainOperand<T>& o, int i, int k, int K, bool vec, float (&v)[8]) {
+  if (o.kc && vec) {          // k .. k + 7 inside K, 16-byte aligned
+    const T* p = o.p + (size_t)i * o.ld + k;
+    if constexpr (sizeof(T) == 2) {
+      bf16x8 r = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = (float)r[u];
+    } else {
+      f32x4 r0 = *reinterpret_cast<const f32x4*>(p), r1 = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { v[u] = r0[u]; v[4 + u] = r1[u]; }
+    }
+  } else {
+    // unconditional loads from a clamped index, then a select: a load under a branch of its own would be waited
+    // for before the next one is issued
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int kk = k + u < K ? k + u : K - 1;
+      const float x = o(i, kk);
+      v[u] = k + u < K ? x : 0.f;
+    }
+  }
+}
+template <typename T>
+__global__ void __launch_bounds__(256) k_gemm_skinny(PlainOperand<T> A, PlainOperand<T> B, Epilogue e, int M, int N, int K,
+                                                     int a_vec, int b_vec) {
+  __shared__ float part[4][64];
+  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const size_t idx = (size_t)blockIdx.x * 64 + lane;
+  const bool live = idx < (size_t)M * N;
+  const int m = live ? (int)(idx / N) : 0, n = live ? (int)(idx % N) : 0;
+  const int kq = ((K + 3) / 4 + 7) & ~7;            // a wave's share of K, a multiple of 8
+  const int k_lo = w * kq, k_hi = k_lo + kq < K ? k_lo + kq : K;
+  float acc = 0.f;
+  for (int k0 = k_lo; k0 < k_hi; k0 += 32) {
+    float a[4][8], b[4][8];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int k = k0 + 8 * c;
+      const bool whole = k + 8 <= k_hi;
+      if (k < k_hi) {
+        skinny_load8(A, m, k, k_hi, a_vec && whole, a[c]);
+        skinny_load8(B, n, k, k_hi, b_vec && whole, b[c]);
+      } else {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { a[c][u] = 0.f; b[c][u] = 0.f; }
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc = fmaf(a[c][u], b[c][u], acc);
+  }
+  part[w][lane] = acc;
+  __syncthreads();
+  if (w == 0 && live) epilogue_store<T>(e, m, n, ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]);
+}
+
 template <typename T>
 static hipError_t gemm_plain_t(const OpCtx& c, const GemmArgs& g) {
   PlainOperand<T> A{(const T*)g.A, g.lda, g.a_kc}, B{(const T*)g.B, g.ldb, g.b_kc};
+  if (g.M > 0 && g.N > 0 && (g.M <= 16 || g.N <= 16) && g.K <= 4096 && (size_t)g.M * g.N <= (size_t)1 << 16) {
+    const size_t total = (size_t)g.M * g.N;
+    const int per16 = 16 / (int)sizeof(T);          // elements per 16 bytes: vector loads need rows that start on them
+    const int a_vec = g.a_kc && g.lda % per16 == 0 && ((uintptr_t)g.A & 15) == 0;
+    const int b_vec = g.b_kc && g.ldb % per16 == 0 && ((uintptr_t)g.B & 15) == 0;
+    k_gemm_skinny<T><<<(unsigned)((total + 63) / 64), 256, 0, c.stream>>>(A, B, make_epilogue(g), g.M, g.N, g.K, a_vec, b_vec);
+    return hipGetLastError();
+  }
   return launch_plain<T>(c.stream, A, B, make_epilogue(g), g.M, g.N, g.K);
 }
 hipError_t gemm_plain(const OpCtx& c, const GemmArgs& g) {
