@@ -187,17 +187,27 @@ Epilogue plain_epilogue(void* C, int64_t ldc, int c_f32, int accumulate) {
 // `loaders` names the two loader types as a profiler prints them: the launch is timed under the kernel's name.
 template <class LA, class LB>
 hipError_t launch(const OpCtx& c, LA A, LB B, const Epilogue& e, int M, int N, int K, int splits, const char* loaders) {
-  const int tn = (N + BN - 1) / BN;
+  const bool narrow = N <= 64;                 // 64-column tiles: no padded half (the 64-channel convolutions)
+  const int bn = narrow ? 64 : BN;
+  const int tn = (N + bn - 1) / bn;
   const bool big = ((M + 255) / 256) * tn * splits >= 400;
-  const int bm = big ? 256 : 128;
+  const bool low = M <= 64 && !narrow;         // 64-row tiles (the filter gradient of a 64-channel convolution)
+  const int bm = low ? 64 : (big ? 256 : 128);
   const int tm = (M + bm - 1) / bm;
   dim3 grid(tm * tn * splits);
-  static char names[2][96];
-  char* kname = names[big ? 1 : 0];
-  if (!kname[0]) snprintf(kname, sizeof names[0], "mfma::k_mfma_tiles<%s, %d>", loaders, bm);
+  static char names[5][96];
+  char* kname = names[low ? 4 : (big ? 1 : 0) + (narrow ? 2 : 0)];
+  if (!kname[0]) snprintf(kname, sizeof names[0], "mfma::k_mfma_tiles<%s, %d, %d>", loaders, bm, bn);
   ProfScope one_(c, KC_GEMM_KERNEL, 2.0 * M * N * K, 0, kname);
-  if (big) k_mfma_tiles<LA, LB, 256><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
-  else k_mfma_tiles<LA, LB, 128><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
+  if (low) {
+    k_mfma_tiles<LA, LB, 64><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
+  } else if (narrow) {
+    if (big) k_mfma_tiles<LA, LB, 256, 64><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
+    else k_mfma_tiles<LA, LB, 128, 64><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
+  } else {
+    if (big) k_mfma_tiles<LA, LB, 256><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
+    else k_mfma_tiles<LA, LB, 128><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
+  }
   return hipGetLastError();
 }
 
@@ -210,7 +220,7 @@ bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 template <class LA, class LB>
 hipError_t launch_cut(const OpCtx& c, LA A, LB B, void* out, int M, int N, int K, const char* loaders,
                       const void* add = nullptr) {
-  const int tiles = ((M + 127) / 128) * ((N + BN - 1) / BN);
+  const int tiles = ((M + 127) / 128) * (N <= 64 ? 1 : (N + BN - 1) / BN);
   int splits = 1;
   if (c.splitk_ws && tiles < 200 && K >= 1024) {
     splits = (512 + tiles - 1) / tiles;

@@ -172,7 +172,7 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   const int bm = kRegStaged[best_v].bm, tn = (g.N + BN - 1) / BN, tm = (g.M + bm - 1) / bm;
   dim3 grid(tm * tn * splits);
   char kname_buf[96];
-  snprintf(kname_buf, sizeof kname_buf, "mfma::k_mfma_tiles<mfma::PlainLoader<%s>, mfma::PlainLoader<%s>, %d>",
+  snprintf(kname_buf, sizeof kname_buf, "mfma::k_mfma_tiles<mfma::PlainLoader<%s>, mfma::PlainLoader<%s>, %d, 128>",
            g.a_kc ? "true" : "false", g.b_kc ? "true" : "false", bm);
   static std::map<std::string, std::string> names;       // stable storage for the profiler's name pointers
   const char* kname = names.emplace(kname_buf, kname_buf).first->second.c_str();

@@ -173,18 +173,24 @@ struct PlainLoader {
   }
 };
 
-template <class LA, class LB, int BM>
-__global__ void __launch_bounds__(256, BM == 128 ? 3 : 2) k_mfma_tiles(LA A, LB B, Epilogue e, int M, int N, int K, int tiles_m,
+// BN_ = 128: the four waves form a 2 x 2 grid, each BM/2 rows x 64 columns.  BN_ = 64 (outputs at most 64 columns
+// wide: the 64-channel convolutions, whose tiles would otherwise be half padding): the waves are stacked, each BM/4
+// rows x 64 columns.
+template <class LA, class LB, int BM, int BN_ = 128>
+__global__ void __launch_bounds__(256, BM == 64 ? 4 : (BM == 128 ? 3 : 2)) k_mfma_tiles(LA A, LB B, Epilogue e, int M, int N, int K, int tiles_m,
                                                        int tiles_n, int splits, float* ws) {
   constexpr bool A_KC = LA::KC, B_KC = LB::KC;
-  constexpr int TM = BM / 64;          // 32-row MFMA tiles per wave along m
+  constexpr int WROWS = BN_ == 128 ? BM / 2 : BM / 4;     // rows of a wave's sub-tile
+  constexpr int TM = WROWS / 32;        // 32-row MFMA tiles per wave along m
   constexpr int TA_LD = BM + 16;
+  constexpr int TBL = BN_ + 16;         // [k][row] tile of the n-side operand: padded rows
   constexpr int A_ELEMS = BM * KC_LD > BK * TA_LD ? BM * KC_LD : BK * TA_LD;
+  constexpr int BE = BN_ * KC_LD > BK * TBL ? BN_ * KC_LD : BK * TBL;
   // one block of LDS: operand buffers A0 A1 B0 B1; the epilogue reuses it (>= 32 KB) as its patches
-  __shared__ __attribute__((aligned(16))) bf16_t Sm[2 * A_ELEMS + 2 * B_ELEMS];
-  static_assert((2 * A_ELEMS + 2 * B_ELEMS) * 2 >= 4 * 8192, "epilogue patches do not fit");
+  constexpr int SM_ELEMS = 2 * A_ELEMS + 2 * BE > 4 * 4096 ? 2 * A_ELEMS + 2 * BE : 4 * 4096;
+  __shared__ __attribute__((aligned(16))) bf16_t Sm[SM_ELEMS];
   bf16_t* const As[2] = {Sm, Sm + A_ELEMS};
-  bf16_t* const Bs[2] = {Sm + 2 * A_ELEMS, Sm + 2 * A_ELEMS + B_ELEMS};
+  bf16_t* const Bs[2] = {Sm + 2 * A_ELEMS, Sm + 2 * A_ELEMS + BE};
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // XCD-aware renumbering, then column-major groups of 8 tile rows
   const int split = blockIdx.x % splits;
@@ -198,8 +204,8 @@ __global__ void __launch_bounds__(256, BM == 128 ? 3 : 2) k_mfma_tiles(LA A, LB 
     int tm = first + (pid % width) % gs, tn = (pid % width) / gs;
     pid = tm * tiles_n + tn;
   }
-  const int m0 = (pid / tiles_n) * BM, n0 = (pid % tiles_n) * BN;
-  const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * 64;
+  const int m0 = (pid / tiles_n) * BM, n0 = (pid % tiles_n) * BN_;
+  const int wm = (BN_ == 128 ? (wave >> 1) : wave) * WROWS, wn = BN_ == 128 ? (wave & 1) * 64 : 0;
 
   f32x16 acc[2][TM];
 #pragma unroll
@@ -214,18 +220,18 @@ __global__ void __launch_bounds__(256, BM == 128 ? 3 : 2) k_mfma_tiles(LA A, LB 
   // other block on the CU).  The barrier waits for LDS traffic only: a __syncthreads would also wait for
   // every outstanding global load and put that latency back on the critical path of each k-tile.
   constexpr int NSET = 2;
-  bf16x8 ra[NSET][BM / 64], rb[NSET][BN / 64];
+  bf16x8 ra[NSET][BM / 64], rb[NSET][BN_ / 64];
   unsigned inva[NSET], invb[NSET];       // chunks the loader declared invalid (implicit zero padding)
   A.template init<BM>(m0);
-  B.template init<BN>(n0);
+  B.template init<BN_>(n0);
   auto fetch = [&](int s, int k0) {
     inva[s] = A.template fetch<BM>(m0, k0, K, ra[s]);
-    invb[s] = B.template fetch<BN>(n0, k0, K, rb[s]);
+    invb[s] = B.template fetch<BN_>(n0, k0, K, rb[s]);
   };
   auto stage = [&](int buf, int s, int k0) {
     if (k0 + BK <= K) k0 = -BK;      // no chunk of this tile can reach K: the masks fold away
     if (A_KC) stage_kc<BM>(As[buf], ra[s], k0, K, inva[s]); else stage_t<BM, TA_LD>(As[buf], ra[s], k0, K, inva[s]);
-    if (B_KC) stage_kc<BN>(Bs[buf], rb[s], k0, K, invb[s]); else stage_t<BN, TB_LD>(Bs[buf], rb[s], k0, K, invb[s]);
+    if (B_KC) stage_kc<BN_>(Bs[buf], rb[s], k0, K, invb[s]); else stage_t<BN_, TBL>(Bs[buf], rb[s], k0, K, invb[s]);
   };
   auto lds_barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
   // fragment addressing that does not depend on k
@@ -261,7 +267,7 @@ __global__ void __launch_bounds__(256, BM == 128 ? 3 : 2) k_mfma_tiles(LA A, LB 
       bf16x8 fn[2], fm[TM];
 #pragma unroll
       for (int i = 0; i < 2; ++i)
-        fn[i] = B_KC ? frag_kc(bs, wn + 32 * i + n_row, ks, lane) : frag_t<TB_LD>(bs, wn + 32 * i + n_rowbase_t, ks, lane);
+        fn[i] = B_KC ? frag_kc(bs, wn + 32 * i + n_row, ks, lane) : frag_t<TBL>(bs, wn + 32 * i + n_rowbase_t, ks, lane);
 #pragma unroll
       for (int j = 0; j < TM; ++j)
         fm[j] = A_KC ? frag_kc(as, wm + 32 * j + li, ks, lane) : frag_t<TA_LD>(as, wm + 32 * j + m_rowbase_t, ks, lane);
@@ -294,7 +300,7 @@ __global__ void __launch_bounds__(256, BM == 128 ? 3 : 2) k_mfma_tiles(LA A, LB 
   // chunk c of row r in slot c ^ ((r >> 1) & 7): conflict-free both ways); lane L then holds chunk L % 8 of
   // row L / 8 (+ 8 per instruction) and an instruction stores 8 whole lines.  The pre-activation, if asked
   // for, goes the same way through a second patch.
-  if (splits == 1 && !e.c_f32 && m0 + wm + BM / 2 <= M && n0 + wn + 64 <= N) {
+  if (splits == 1 && !e.c_f32 && m0 + wm + WROWS <= M && n0 + wn + 64 <= N) {
     char* xs = reinterpret_cast<char*>(Sm) + wave * 8192;
     const int rr = lane >> 3, rc = lane & 7;
     bf16_t* cbase = reinterpret_cast<bf16_t*>(e.C) + (size_t)(m0 + wm + rr) * e.ldc + n0 + wn + 8 * rc;
