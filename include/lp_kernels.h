@@ -113,6 +113,13 @@ int lpk_conv_bwd_data(int dtype, const void* dout, const void* w, void* dx, int 
                       int stride, int pad, void* stream);
 int lpk_conv_bwd_weight(int dtype, const void* dout, const void* x, float* dw, int N, int H, int W, int C, int O,
                         int R, int stride, int pad, int accumulate, void* stream);
+/* The same filter gradient with fp32 workspace (device memory, splitk_ws_elems floats, contents undefined on
+ * return): with it the reduction over the N*P*Q output pixels is cut into pieces whose partial sums are added in a
+ * fixed order, which is how the step computes it; a 3-channel stem with 64 output channels then takes one image per
+ * block (needs N*O*R*R*C floats).  Without enough workspace the call computes the gradient uncut. */
+int lpk_conv_bwd_weight_ws(int dtype, const void* dout, const void* x, float* dw, int N, int H, int W, int C, int O,
+                           int R, int stride, int pad, int accumulate, float* splitk_ws_dev, size_t splitk_ws_elems,
+                           void* stream);
 
 /* BatchNorm with batch statistics over rows = N*H*W, fused residual add and ReLU. */
 int lpk_batchnorm_fwd(int dtype, const void* z, const float* g, const float* b, const void* res, void* y,

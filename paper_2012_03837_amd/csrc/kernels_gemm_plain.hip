@@ -350,12 +350,76 @@ static hipError_t conv_bwd_data_t(const OpCtx& c, const ConvArgs& a, const void*
   e.res = add; e.ldr = a.C;
   return launch_plain<T>(c.stream, A, B, e, M, a.C, K);
 }
+// Filter gradient of a convolution with very few input channels and 64 output channels (the 3-channel stem:
+// 64 x 27 sums over 262144 pixels).  As a split-K GEMM it is 512 blocks of one 64 x 64 tile, 27 of whose columns are
+// real, each k-step a gather with its index arithmetic: 123 us + 26 us for the reduction.  Here a block takes one image:
+// the image sits in LDS as fp32 with its zero border, a thread owns one output channel o and a quarter of the
+// (r, s, c) taps, walks the image's pixels in order, reads dy[pixel, o] (a wave reads 64 consecutive channels) and
+// its taps from LDS (one address per wave: a broadcast), and leaves its sums in the image's slice of the workspace;
+// the slices are added in order by the split-K reduction.
+constexpr int kStemMaxTaps = 32;
+template <typename T>
+__global__ void __launch_bounds__(256) k_conv_wgrad_smallc(const T* __restrict__ dout, const T* __restrict__ x,
+                                                           float* __restrict__ ws, ConvArgs a) {
+  extern __shared__ __attribute__((aligned(16))) float xs[];
+  const int Hp = a.H + 2 * a.pad, Wp = a.W + 2 * a.pad, J = a.R * a.S * a.C;
+  const int n = blockIdx.x;
+  for (int i = threadIdx.x; i < Hp * Wp * a.C; i += 256) {
+    const int c = i % a.C, t = i / a.C, w = t % Wp - a.pad, h = t / Wp - a.pad;
+    const bool ok = h >= 0 && h < a.H && w >= 0 && w < a.W;
+    xs[i] = ok ? to_f(x[(((size_t)n * a.H + h) * a.W + w) * a.C + c]) : 0.f;
+  }
+  __syncthreads();
+  const int o = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const int per = (J + 3) / 4, j0 = g * per;
+  int off[kStemMaxTaps / 4];
+  float acc[kStemMaxTaps / 4];
+#pragma unroll
+  for (int t = 0; t < kStemMaxTaps / 4; ++t) {
+    const int j = j0 + t < J ? j0 + t : J - 1;
+    const int c = j % a.C, rs = j / a.C, s2 = rs % a.S, r = rs / a.S;
+    off[t] = (r * Wp + s2) * a.C + c;
+    acc[t] = 0.f;
+  }
+  const T* dy = dout + (size_t)n * a.P * a.Q * a.O + o;
+  for (int p = 0; p < a.P; ++p)
+    for (int q = 0; q < a.Q; q += 4) {
+      float d[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int qq = q + u < a.Q ? q + u : a.Q - 1;
+        const float v = to_f(dy[(size_t)(p * a.Q + qq) * a.O]);
+        d[u] = q + u < a.Q ? v : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int qq = q + u < a.Q ? q + u : a.Q - 1;
+        const float* base = xs + ((p * a.stride) * Wp + qq * a.stride) * a.C;
+#pragma unroll
+        for (int t = 0; t < kStemMaxTaps / 4; ++t) acc[t] = fmaf(d[u], base[off[t]], acc[t]);
+      }
+    }
+#pragma unroll
+  for (int t = 0; t < kStemMaxTaps / 4; ++t)
+    if (t < per && j0 + t < J) ws[((size_t)n * a.O + o) * J + j0 + t] = acc[t];
+}
+
 template <typename T>
 static hipError_t conv_bwd_weight_t(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
                                     int accumulate) {
   int Mrows = a.N * a.P * a.Q, J = a.R * a.S * a.C;
   PlainOperand<T> A{(const T*)dout, a.O, 0};            // (o, m) -> dout[m*O + o]
   ConvPatchByCol<T> B{ConvInputPatch<T>{(const T*)x, a}};
+  {
+    const size_t shm = (size_t)(a.H + 2 * a.pad) * (a.W + 2 * a.pad) * a.C * sizeof(float);
+    if (a.C <= 4 && a.O == 64 && J <= kStemMaxTaps && a.N >= 2 && shm <= 48 * 1024 && c.splitk_ws &&
+        (size_t)a.N * a.O * J <= c.splitk_elems) {
+      k_conv_wgrad_smallc<T><<<a.N, 256, shm, c.stream>>>((const T*)dout, (const T*)x, c.splitk_ws, a);
+      size_t total = (size_t)a.O * J;
+      k_plain_splitk_reduce<<<(unsigned)((total + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, dw, total, a.N, accumulate);
+      return hipGetLastError();
+    }
+  }
   // few output tiles and a very long reduction (the stem: 64 x 27 outputs over 262144 pixels): split-K
   int tiles = ((J + PBN - 1) / PBN) * ((a.O + PBM - 1) / PBM);
   int splits = tiles >= 256 ? 1 : 512 / tiles;

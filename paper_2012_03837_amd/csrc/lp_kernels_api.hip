@@ -157,6 +157,13 @@ extern "C" int lpk_conv_bwd_weight(int dtype, const void* dout, const void* x, f
                                    int O, int R, int stride, int pad, int accumulate, void* stream) {
   return (int)op_conv_bwd_weight(mk(dtype, stream), mkconv(N, H, W, C, O, R, stride, pad), dout, x, dw, accumulate);
 }
+extern "C" int lpk_conv_bwd_weight_ws(int dtype, const void* dout, const void* x, float* dw, int N, int H, int W, int C,
+                                      int O, int R, int stride, int pad, int accumulate, float* splitk_ws,
+                                      size_t splitk_ws_elems, void* stream) {
+  OpCtx c = mk(dtype, stream);
+  c.splitk_ws = splitk_ws; c.splitk_elems = splitk_ws ? splitk_ws_elems : 0;
+  return (int)op_conv_bwd_weight(c, mkconv(N, H, W, C, O, R, stride, pad), dout, x, dw, accumulate);
+}
 extern "C" int lpk_batchnorm_fwd(int dtype, const void* z, const float* g, const float* b, const void* res, void* y,
                                  float* mean, float* rstd, int rows, int C, int relu, float* scratch,
                                  size_t scratch_elems, void* stream) {

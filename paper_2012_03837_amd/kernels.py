@@ -125,6 +125,12 @@ def lpk_conv_bwd_weight(dtype, dout, x, dw, N, H, W, Cin, O, R, stride, pad, acc
                                   _i(stride), _i(pad), _i(accumulate), _stream()), "lpk_conv_bwd_weight")
 
 
+def lpk_conv_bwd_weight_ws(dtype, dout, x, dw, N, H, W, Cin, O, R, stride, pad, splitk_ws, accumulate=0):
+    _ck(lib().lpk_conv_bwd_weight_ws(_i(dtype), _p(dout), _p(x), _p(dw), _i(N), _i(H), _i(W), _i(Cin), _i(O), _i(R),
+                                     _i(stride), _i(pad), _i(accumulate), _p(splitk_ws), _sz(splitk_ws.numel()),
+                                     _stream()), "lpk_conv_bwd_weight_ws")
+
+
 def lpk_batchnorm_fwd(dtype, z, g, b, res, y, mean, rstd, rows, Cc, relu, scratch):
     _ck(lib().lpk_batchnorm_fwd(_i(dtype), _p(z), _p(g), _p(b), _p(res), _p(y), _p(mean), _p(rstd), _i(rows), _i(Cc),
                                 _i(relu), _p(scratch), _sz(scratch.numel()), _stream()), "lpk_batchnorm_fwd")

@@ -356,7 +356,7 @@ def test_transpose_bf16_bit_exact(K, R, C):
 
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("N,H,C,O,R,stride,pad", [(3, 9, 5, 7, 3, 1, 1), (2, 8, 16, 24, 3, 2, 1), (2, 8, 16, 8, 1, 2, 0),
-                                                  (4, 12, 3, 64, 3, 1, 1), (5, 14, 64, 136, 3, 1, 1),
+                                                  (4, 12, 3, 64, 3, 1, 1), (3, 10, 3, 64, 3, 2, 1), (5, 14, 64, 136, 3, 1, 1),
                                                   (3, 16, 72, 128, 3, 2, 1), (6, 10, 128, 64, 1, 2, 0)])
 def test_conv_and_batchnorm(K, dtype, N, H, C, O, R, stride, pad):
     import torch
@@ -378,6 +378,14 @@ def test_conv_and_batchnorm(K, dtype, N, H, C, O, R, stride, pad):
     rdx, rdw = ops.conv2d_bwd(x.astype(np.float64), w.astype(np.float64), stride, pad, dout.astype(np.float64))
     assert relerr(host(dx), rdx) <= tol
     assert relerr(host(dw), rdw) <= 2e-6
+    # the same filter gradient cut along the pixels with workspace (the form a step uses), twice: bit-repeatable
+    ws = zeros(max(64 * O * R * R * C, N * O * R * R * C))
+    dw2 = torch.full((O, R, R, C), 5.0, device="cuda", dtype=torch.float32)
+    dw3 = torch.zeros(O, R, R, C, device="cuda", dtype=torch.float32)
+    K.lpk_conv_bwd_weight_ws(dtype, dev(dout, dtype), dev(x, dtype), dw2, N, H, H, C, O, R, stride, pad, ws)
+    K.lpk_conv_bwd_weight_ws(dtype, dev(dout, dtype), dev(x, dtype), dw3, N, H, H, C, O, R, stride, pad, ws)
+    assert relerr(host(dw2), rdw) <= 2e-6
+    assert torch.equal(dw2, dw3)
     # batchnorm + residual + relu on the conv output
     rows = N * P * P
     z = host(out).astype(np.float32)
