@@ -51,7 +51,8 @@ def relerr(a, ref):
 
 GEMM_SHAPES = [(200, 136, 72), (128, 128, 32), (1, 8, 8), (333, 257, 40), (64, 1000, 128), (600, 128, 600),
                (264, 136, 4104), (520, 264, 2048), (304, 520, 96), (1000, 264, 320), (8, 8, 32),
-               (10, 136, 264), (264, 10, 520)]        # a 10-class head's weight gradient and forward map (skinny products)
+               (10, 136, 264), (264, 10, 520),        # a 10-class head's weight gradient and forward map (skinny products)
+               (5, 24, 77), (24, 3, 100)]             # skinny, reduction not a multiple of 8 or of the waves' shares
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
