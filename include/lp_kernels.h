@@ -121,6 +121,15 @@ int lpk_conv_bwd_weight_ws(int dtype, const void* dout, const void* x, float* dw
                            int R, int stride, int pad, int accumulate, float* splitk_ws_dev, size_t splitk_ws_elems,
                            void* stream);
 
+/* One convolution + normalisation unit of a ResNet stage, forward (appendix B.3): z = conv(x, w) as lpk_conv_fwd,
+ * then y = [relu](bn(z) (+ res)) as lpk_batchnorm_fwd, with z, y, mean, rstd all written.  Where the convolution's
+ * output is whole tiles of the matrix-core kernel, the convolution itself leaves the per-channel sums of its rounded
+ * outputs in scratch_dev and the normalisation does not read z for its statistics; otherwise the two run as the
+ * separate calls would.  scratch_dev: at least max(3 * (N*P*Q/32 + O), (2*1024 + 2) * O) floats. */
+int lpk_conv_bn_fwd(int dtype, const void* x, const void* w, void* z, const float* g, const float* b, const void* res,
+                    void* y, float* mean, float* rstd, int N, int H, int W, int C, int O, int R, int stride, int pad,
+                    int relu, float* scratch_dev, size_t scratch_elems, void* stream);
+
 /* BatchNorm with batch statistics over rows = N*H*W, fused residual add and ReLU. */
 int lpk_batchnorm_fwd(int dtype, const void* z, const float* g, const float* b, const void* res, void* y,
                       float* mean, float* rstd, int rows, int C, int relu, float* scratch_dev, size_t scratch_elems,

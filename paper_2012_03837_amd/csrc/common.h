@@ -168,7 +168,17 @@ hipError_t op_optimizer(const OpCtx& c, const OptArgs& o, float* p, const float*
 hipError_t op_init_normal(const OpCtx& c, float* p, size_t n, float std, uint64_t seed, uint64_t stream_id);
 
 // conv / batchnorm / pooling
-hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out);
+// Column statistics of a convolution's output, left by the convolution kernel itself for the batch normalisation
+// behind it: for slab t of slab_rows consecutive rows and column j, p = the slab's first row, s0 = sum (z - p),
+// s1 = sum (z - p)^2 over the rounded outputs, stored as buf[(0 * nslab + t) * C + j], [(1 * nslab + t) ...] and
+// [(2 * nslab + t) ...].  The caller sets buf / cap (floats); nslab stays 0 if the launch did not produce them.
+struct ConvStats {
+  float* buf = nullptr;
+  size_t cap = 0;
+  int nslab = 0, slab_rows = 0;
+};
+hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out,
+                       ConvStats* stats = nullptr);
 // dx = data gradient (+ add, an activation-gradient tensor of dx's shape: the other branch of a residual block).
 hipError_t op_conv_bwd_data(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
                             const void* add = nullptr);
@@ -188,7 +198,7 @@ struct BnRunning {
 // saves the mean and reciprocal standard deviation it normalised with.
 hipError_t op_batchnorm_fwd(const OpCtx& c, const void* z, const float* g, const float* b, const void* res,
                             void* y, float* mean, float* rstd, int rows, int C, int relu,
-                            const BnRunning* run = nullptr);
+                            const BnRunning* run = nullptr, const ConvStats* pre = nullptr);
 // dy_eff = relu ? dy * (y > 0) : dy;  dz = bn-backward(dy_eff); dg, db; if dres: dres = dy_eff.
 hipError_t op_batchnorm_bwd(const OpCtx& c, const void* dy, const void* y, const void* z, const float* mean,
                             const float* rstd, const float* g, void* dz, void* dres, float* dg, float* db,

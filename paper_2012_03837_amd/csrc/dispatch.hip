@@ -19,7 +19,7 @@ hipError_t attn_bwd_mfma(const OpCtx& c, const void* qkv, const void* o, const f
                          void* dqkv, float* delta, int B, int S, int H, int causal);
 
 bool conv_mfma_ok(const OpCtx& c, const ConvArgs& a, const void* p0, const void* p1, const void* p2);
-hipError_t conv_fwd_mfma(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out);
+hipError_t conv_fwd_mfma(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out, ConvStats* st);
 hipError_t conv_bwd_data_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
                               const void* add);
 hipError_t conv_bwd_weight_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* x, float* dw,
@@ -47,9 +47,10 @@ hipError_t op_attn_bwd(const OpCtx& c, const void* qkv, const void* o, const flo
   if (use_mfma_attn(c, dh)) return attn_bwd_mfma(c, qkv, o, lse, dout, dqkv, delta, B, S, H, causal);
   return attn_bwd_plain(c, qkv, o, lse, dout, dqkv, delta, B, S, H, dh, causal);
 }
-hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {
+hipError_t op_conv_fwd(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out, ConvStats* stats) {
   ProfScope prof_(c, KC_CONV, 2.0 * a.N * a.P * a.Q * a.O * a.R * a.S * a.C);
-  if (!plain_conv() && conv_mfma_ok(c, a, x, w, out)) return conv_fwd_mfma(c, a, x, w, out);
+  if (stats) { stats->nslab = 0; stats->slab_rows = 0; }
+  if (!plain_conv() && conv_mfma_ok(c, a, x, w, out)) return conv_fwd_mfma(c, a, x, w, out, stats);
   return conv_fwd_plain(c, a, x, w, out);
 }
 hipError_t op_conv_bwd_data(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,

@@ -227,10 +227,14 @@ static int dec_backward(lp_ctx* c, int li, int batch, const void* dout, void* dx
 // ===================================================================================== ResNet stage
 static int unit_forward(lp_ctx* c, ConvUnit& u, const void* x, const void* res) {
   OpCtx o = c->op();
-  DO(op_conv_fwd(o, u.a, x, c->W(u.w), u.z));
+  // the convolution leaves the normalisation's column statistics in the stream's partial buffer where it can
+  // (whole tiles, batch statistics wanted); the normalisation then skips its own pass over z
+  const BnRunning* run = c->bn_for(u.g, u.a.O);
+  ConvStats st;
+  if (!(run && run->use)) { st.buf = o.partial; st.cap = o.partial_elems; }
+  DO(op_conv_fwd(o, u.a, x, c->W(u.w), u.z, &st));
   int rows = u.a.N * u.a.P * u.a.Q;
-  DO(op_batchnorm_fwd(o, u.z, c->P32(u.g), c->P32(u.b), res, u.y, u.mean, u.rstd, rows, u.a.O, u.relu,
-                      c->bn_for(u.g, u.a.O)));
+  DO(op_batchnorm_fwd(o, u.z, c->P32(u.g), c->P32(u.b), res, u.y, u.mean, u.rstd, rows, u.a.O, u.relu, run, &st));
   return LP_OK;
 }
 // dy -> (dz in sZ) -> dw, and dx (+ dx_add, if given) if asked.  dres (if non-null) receives the ReLU-masked dy.

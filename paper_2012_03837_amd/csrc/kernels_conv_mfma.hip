@@ -7,6 +7,7 @@
 //   wgrad   : dw[o, (r,s,c)]   = sum_{(n,p,q)} dout[(n,p,q), o] * x[n, p*st+r-pad, q*st+s-pad, c]   (fp32, split-K)
 // Needs C % 8 == 0 and O % 8 == 0; the 3-channel stem convolution stays on the plain kernel.
 #include <stdio.h>
+#include <type_traits>
 #include "common.h"
 #include "gemm_common.h"
 #include "mfma_tile.h"
@@ -185,8 +186,11 @@ Epilogue plain_epilogue(void* C, int64_t ldc, int c_f32, int accumulate) {
 }
 
 // `loaders` names the two loader types as a profiler prints them: the launch is timed under the kernel's name.
+// st (forward convolutions only): if the launch qualifies (whole tiles, one piece, room in st->buf) the kernel also
+// leaves the normalisation's per-sub-tile column statistics there and st->nslab / st->slab_rows say how many.
 template <class LA, class LB>
-hipError_t launch(const OpCtx& c, LA A, LB B, const Epilogue& e, int M, int N, int K, int splits, const char* loaders) {
+hipError_t launch(const OpCtx& c, LA A, LB B, const Epilogue& e, int M, int N, int K, int splits, const char* loaders,
+                  ConvStats* st = nullptr) {
   const bool narrow = N <= 64;                 // 64-column tiles: no padded half (the 64-channel convolutions)
   const int bn = narrow ? 64 : BN;
   const int tn = (N + bn - 1) / bn;
@@ -195,10 +199,28 @@ hipError_t launch(const OpCtx& c, LA A, LB B, const Epilogue& e, int M, int N, i
   const int bm = low ? 64 : (big ? 256 : 128);
   const int tm = (M + bm - 1) / bm;
   dim3 grid(tm * tn * splits);
+  bool stats = false;
+  if constexpr (std::is_same<LA, ConvFwdA>::value) {
+    if (st && st->buf && !low && splits == 1 && !e.c_f32 && M % bm == 0 && N % bn == 0) {
+      if ((size_t)3 * (M / bm) * N <= st->cap) { stats = true; st->nslab = M / bm; st->slab_rows = bm; }
+    }
+  }
   static char names[5][96];
   char* kname = names[low ? 4 : (big ? 1 : 0) + (narrow ? 2 : 0)];
   if (!kname[0]) snprintf(kname, sizeof names[0], "mfma::k_mfma_tiles<%s, %d, %d>", loaders, bm, bn);
   ProfScope one_(c, KC_GEMM_KERNEL, 2.0 * M * N * K, 0, kname);
+  if constexpr (std::is_same<LA, ConvFwdA>::value) {
+    if (stats) {
+      if (narrow) {
+        if (big) k_mfma_tiles<LA, LB, 256, 64, true><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, 1, st->buf);
+        else k_mfma_tiles<LA, LB, 128, 64, true><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, 1, st->buf);
+      } else {
+        if (big) k_mfma_tiles<LA, LB, 256, 128, true><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, 1, st->buf);
+        else k_mfma_tiles<LA, LB, 128, 128, true><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, 1, st->buf);
+      }
+      return hipGetLastError();
+    }
+  }
   if (low) {
     k_mfma_tiles<LA, LB, 64><<<grid, 256, 0, c.stream>>>(A, B, e, M, N, K, tm, tn, splits, c.splitk_ws);
   } else if (narrow) {
@@ -219,7 +241,7 @@ bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 // the fp32 partial sums (M x N per piece) are added in piece order.
 template <class LA, class LB>
 hipError_t launch_cut(const OpCtx& c, LA A, LB B, void* out, int M, int N, int K, const char* loaders,
-                      const void* add = nullptr) {
+                      const void* add = nullptr, ConvStats* st = nullptr) {
   const int tiles = ((M + 127) / 128) * (N <= 64 ? 1 : (N + BN - 1) / BN);
   int splits = 1;
   if (c.splitk_ws && tiles < 200 && K >= 1024) {
@@ -230,7 +252,7 @@ hipError_t launch_cut(const OpCtx& c, LA A, LB B, void* out, int M, int N, int K
   }
   Epilogue e = plain_epilogue(out, N, 0, 0);
   e.res = add; e.ldr = N;      // a tensor of the output's shape added to the result
-  hipError_t err = launch(c, A, B, e, M, N, K, splits, loaders);
+  hipError_t err = launch(c, A, B, e, M, N, K, splits, loaders, st);
   if (err != hipSuccess || splits == 1) return err;
   const size_t work = (size_t)M * (N / 8);
   k_conv_splitk_reduce8<<<(unsigned)((work + 255) / 256), 256, 0, c.stream>>>(c.splitk_ws, e, M, N, splits);
@@ -243,11 +265,11 @@ bool conv_mfma_ok(const OpCtx& c, const ConvArgs& a, const void* p0, const void*
   return c.dt == BF16 && a.C % 8 == 0 && a.O % 8 == 0 && a.C >= 8 && a.O >= 8 && al16(p0) && al16(p1) && al16(p2);
 }
 
-hipError_t conv_fwd_mfma(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out) {
+hipError_t conv_fwd_mfma(const OpCtx& c, const ConvArgs& a, const void* x, const void* w, void* out, ConvStats* st) {
   const int M = a.N * a.P * a.Q, K = a.R * a.S * a.C;
   ConvFwdA A{(const bf16_t*)x, a, M};
   PlainLoader<true> B{Operand{(const bf16_t*)w, K, a.O}};
-  return launch_cut(c, A, B, out, M, a.O, K, "ConvFwdA, mfma::PlainLoader<true>");
+  return launch_cut(c, A, B, out, M, a.O, K, "ConvFwdA, mfma::PlainLoader<true>", nullptr, st);
 }
 hipError_t conv_bwd_data_mfma(const OpCtx& c, const ConvArgs& a, const void* dout, const void* w, void* dx,
                               const void* add) {

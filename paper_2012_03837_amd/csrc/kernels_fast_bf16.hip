@@ -406,6 +406,64 @@ k_bn_finish_v(const float* __restrict__ partial, int nslab, int C, int rows, con
     }
   }
 }
+// Forward statistics from the per-slab sums the convolution kernel left (ConvStats: slab t has its own pivot p_t, the
+// first of its slab_rows rows): every slab is shifted to slab 0's pivot P, with d = p_t - P
+//   sum (z - P) = s0_t + n d,   sum (z - P)^2 = s1_t + 2 d s0_t + n d^2,
+// the slabs are added in the order of k_bn_finish_v (16 groups of every 16th slab, then the groups in order), and the
+// batch mean, 1 / sqrt(var + eps) and the running pair follow as there.
+__global__ void __launch_bounds__(64 * kBnFinishGroups)
+k_bn_finish_slabs(const float* __restrict__ st, int nslab, int slab_rows, int C, int rows, float* __restrict__ mean,
+                  float* __restrict__ rstd, float* __restrict__ run_mean, float* __restrict__ run_var, float mom) {
+  __shared__ float sh[2][kBnFinishGroups][64];
+  const int lc = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lc;
+  float a = 0.f, b = 0.f, P = 0.f;
+  if (j < C) {
+    const float* s0p = st + j;
+    const float* s1p = st + (size_t)nslab * C + j;
+    const float* pp = st + (size_t)2 * nslab * C + j;
+    P = pp[0];
+    const float n = (float)slab_rows;
+    int s = q;
+    for (; s + 3 * kBnFinishGroups < nslab; s += 4 * kBnFinishGroups) {      // twelve loads in flight
+      float s0[4], s1[4], p[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const size_t o = (size_t)(s + u * kBnFinishGroups) * C;
+        s0[u] = s0p[o]; s1[u] = s1p[o]; p[u] = pp[o];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float d = p[u] - P;
+        a += s0[u] + n * d;
+        b += s1[u] + 2.f * d * s0[u] + n * d * d;
+      }
+    }
+    for (; s < nslab; s += kBnFinishGroups) {
+      const size_t o = (size_t)s * C;
+      const float s0 = s0p[o], s1 = s1p[o], d = pp[o] - P;
+      a += s0 + n * d;
+      b += s1 + 2.f * d * s0 + n * d * d;
+    }
+  }
+  sh[0][q][lc] = a; sh[1][q][lc] = b;
+  __syncthreads();
+  if (q != 0 || j >= C) return;
+  a = 0.f; b = 0.f;
+#pragma unroll
+  for (int g = 0; g < kBnFinishGroups; ++g) { a += sh[0][g][lc]; b += sh[1][g][lc]; }
+  const float inv = 1.f / (float)rows, m1 = a * inv;
+  float var = b * inv - m1 * m1;
+  var = var > 0.f ? var : 0.f;
+  const float mu = P + m1;
+  mean[j] = mu;
+  rstd[j] = rsqrtf(var + kBnEpsV);
+  if (run_mean) {   // running statistics take the unbiased batch variance
+    const float unb = rows > 1 ? var * ((float)rows / (float)(rows - 1)) : var;
+    run_mean[j] = (1.f - mom) * run_mean[j] + mom * mu;
+    run_var[j] = (1.f - mom) * run_var[j] + mom * unb;
+  }
+}
 __global__ void __launch_bounds__(256) k_bn_apply_v(const bf16_t* __restrict__ z, const float* __restrict__ g,
                                                     const float* __restrict__ b, const bf16_t* __restrict__ res,
                                                     bf16_t* __restrict__ y, const float* __restrict__ mean,
@@ -480,9 +538,14 @@ size_t bn_fast_scratch(int rows, int C) {
   return (2 * nslab + 2) * (size_t)C;
 }
 hipError_t bn_fwd_fast(const OpCtx& c, const void* z, const float* g, const float* b, const void* res, void* y,
-                       float* mean, float* rstd, int rows, int C, int relu, const BnRunning* run) {
+                       float* mean, float* rstd, int rows, int C, int relu, const BnRunning* run, const ConvStats* pre) {
   const bool given = run && run->use;   // mean / rstd already hold the statistics to normalise with
-  if (!given) {
+  if (!given && pre && pre->nslab > 0 && (size_t)pre->nslab * pre->slab_rows == (size_t)rows) {
+    // the convolution in front left the per-slab sums: no pass over z for the statistics
+    k_bn_finish_slabs<<<(C + 63) / 64, 64 * kBnFinishGroups, 0, c.stream>>>(
+        pre->buf, pre->nslab, pre->slab_rows, C, rows, mean, rstd, run ? run->mean : nullptr, run ? run->var : nullptr,
+        run ? run->momentum : 0.f);
+  } else if (!given) {
     const int slab = bn_slab(rows, C), nslab = (rows + slab - 1) / slab;
     if ((size_t)2 * nslab * C > c.partial_elems) return hipErrorInvalidValue;
     const int RL = 256 / (C / 8);

@@ -7,7 +7,7 @@ namespace lp {
 
 bool bn_fast_ok(const OpCtx& c, int rows, int C, const void* a, const void* b, const void* cc, const void* d);
 hipError_t bn_fwd_fast(const OpCtx& c, const void* z, const float* g, const float* b, const void* res, void* y,
-                       float* mean, float* rstd, int rows, int C, int relu, const BnRunning* run);
+                       float* mean, float* rstd, int rows, int C, int relu, const BnRunning* run, const ConvStats* pre);
 hipError_t bn_bwd_fast(const OpCtx& c, const void* dy, const void* y, const void* z, const float* mean,
                        const float* rstd, const float* g, void* dz, void* dres, float* dg, float* db, int rows, int C,
                        int relu, int accumulate);
@@ -139,12 +139,13 @@ static hipError_t bn_fwd_t(const OpCtx& c, const void* z, const float* g, const 
   return hipGetLastError();
 }
 hipError_t op_batchnorm_fwd(const OpCtx& c, const void* z, const float* g, const float* b, const void* res, void* y,
-                            float* mean, float* rstd, int rows, int C, int relu, const BnRunning* run) {
+                            float* mean, float* rstd, int rows, int C, int relu, const BnRunning* run,
+                            const ConvStats* pre) {
   ProfScope prof_(c, KC_BATCHNORM);
   if (rows == 0) return hipSuccess;
   if (run && (!run->mean || !run->var)) return hipErrorInvalidValue;
   if (run && run->use) k_bn_load_running<<<(C + 255) / 256, 256, 0, c.stream>>>(run->mean, run->var, mean, rstd, C);
-  if (bn_fast_ok(c, rows, C, z, y, res, nullptr)) return bn_fwd_fast(c, z, g, b, res, y, mean, rstd, rows, C, relu, run);
+  if (bn_fast_ok(c, rows, C, z, y, res, nullptr)) return bn_fwd_fast(c, z, g, b, res, y, mean, rstd, rows, C, relu, run, pre);
   return c.dt == BF16 ? bn_fwd_t<bf16_t>(c, z, g, b, res, y, mean, rstd, rows, C, relu, run)
                       : bn_fwd_t<float>(c, z, g, b, res, y, mean, rstd, rows, C, relu, run);
 }

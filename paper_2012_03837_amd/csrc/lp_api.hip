@@ -275,6 +275,8 @@ static void plan(lp_ctx* c, const lp_buffers* buf, lp_sizes* sizes) {
         if (sp.debug) { u.dy_keep = wa.take(n * es); u.dx_keep = wa.take(nin * es); }
         size_t pr = (size_t)(2 * 1024 + 2) * u.a.O;   // up to 1024 row slabs, two sums each, plus the totals
         if (pr > partial) partial = pr;
+        size_t ps = 3 * (n / 32 + u.a.O);              // statistics left by the convolution: three per 32-row sub-tile and column
+        if (ps > partial) partial = ps;
       };
       S.has_stem = l.has_stem != 0;
       S.blocks.clear();

@@ -164,6 +164,17 @@ extern "C" int lpk_conv_bwd_weight_ws(int dtype, const void* dout, const void* x
   c.splitk_ws = splitk_ws; c.splitk_elems = splitk_ws ? splitk_ws_elems : 0;
   return (int)op_conv_bwd_weight(c, mkconv(N, H, W, C, O, R, stride, pad), dout, x, dw, accumulate);
 }
+extern "C" int lpk_conv_bn_fwd(int dtype, const void* x, const void* w, void* z, const float* g, const float* b,
+                               const void* res, void* y, float* mean, float* rstd, int N, int H, int W, int C, int O,
+                               int R, int stride, int pad, int relu, float* scratch, size_t scratch_elems, void* stream) {
+  OpCtx c = mk(dtype, stream, scratch, scratch_elems);
+  ConvArgs a = mkconv(N, H, W, C, O, R, stride, pad);
+  ConvStats st;
+  st.buf = scratch; st.cap = scratch ? scratch_elems : 0;
+  hipError_t e = op_conv_fwd(c, a, x, w, z, &st);
+  if (e != hipSuccess) return (int)e;
+  return (int)op_batchnorm_fwd(c, z, g, b, res, y, mean, rstd, a.N * a.P * a.Q, O, relu, nullptr, &st);
+}
 extern "C" int lpk_batchnorm_fwd(int dtype, const void* z, const float* g, const float* b, const void* res, void* y,
                                  float* mean, float* rstd, int rows, int C, int relu, float* scratch,
                                  size_t scratch_elems, void* stream) {

@@ -176,7 +176,12 @@ struct PlainLoader {
 // BN_ = 128: the four waves form a 2 x 2 grid, each BM/2 rows x 64 columns.  BN_ = 64 (outputs at most 64 columns
 // wide: the 64-channel convolutions, whose tiles would otherwise be half padding): the waves are stacked, each BM/4
 // rows x 64 columns.
-template <class LA, class LB, int BM, int BN_ = 128>
+//
+// STATS (the convolution in front of a batch normalisation; splits == 1, M a multiple of BM and N of BN_, so every
+// sub-tile takes the whole-line path): each block also leaves, per output column, the sums the normalisation needs over
+// the rows of the tile, taken from the rounded values it stores: p = the tile's first row, s0 = sum (z - p),
+// s1 = sum (z - p)^2, in ws as [3][M / BM][N] (s0, s1, p).  The statistics pass over z is then not needed.
+template <class LA, class LB, int BM, int BN_ = 128, bool STATS = false>
 __global__ void __launch_bounds__(256, BM == 64 ? 4 : (BM == 128 ? 3 : 2)) k_mfma_tiles(LA A, LB B, Epilogue e, int M, int N, int K, int tiles_m,
                                                        int tiles_n, int splits, float* ws) {
   constexpr bool A_KC = LA::KC, B_KC = LB::KC;
@@ -303,6 +308,7 @@ __global__ void __launch_bounds__(256, BM == 64 ? 4 : (BM == 128 ? 3 : 2)) k_mfm
   if (splits == 1 && !e.c_f32 && m0 + wm + WROWS <= M && n0 + wn + 64 <= N) {
     char* xs = reinterpret_cast<char*>(Sm) + wave * 8192;
     const int rr = lane >> 3, rc = lane & 7;
+    float st_s0 = 0.f, st_s1 = 0.f, st_p = 0.f;
     bf16_t* cbase = reinterpret_cast<bf16_t*>(e.C) + (size_t)(m0 + wm + rr) * e.ldc + n0 + wn + 8 * rc;
     bf16_t* pbase = reinterpret_cast<bf16_t*>(e.pre) + (size_t)(m0 + wm + rr) * e.ldc + n0 + wn + 8 * rc;
 #pragma unroll
@@ -331,6 +337,41 @@ __global__ void __launch_bounds__(256, BM == 64 ? 4 : (BM == 128 ? 3 : 2)) k_mfm
         const size_t off = (size_t)(32 * j + 8 * I) * e.ldc;
         *reinterpret_cast<bf16x8*>(cbase + off) = *reinterpret_cast<const bf16x8*>(xs + r * 128 + slot);
         if (e.pre) *reinterpret_cast<bf16x8*>(pbase + off) = *reinterpret_cast<const bf16x8*>(xs + 4096 + r * 128 + slot);
+      }
+      if constexpr (STATS) {       // lane = column: element lane % 8 of chunk lane / 8 of every row of the patch
+        const int sc = lane >> 3, se = (lane & 7) * 2;
+#pragma unroll
+        for (int r = 0; r < 32; ++r) {
+          const float v = (float)*reinterpret_cast<const bf16_t*>(xs + r * 128 + ((sc ^ ((r >> 1) & 7)) << 4) + se);
+          if (j == 0 && r == 0) st_p = v;
+          const float t = v - st_p;
+          st_s0 += t;
+          st_s1 += t * t;
+        }
+      }
+    }
+    if constexpr (STATS) {
+      // one set of sums per tile: the waves that share columns (all four, or waves w and w + 2) leave theirs in their
+      // own patch, and the first of them shifts the others to its pivot (d = p_w - p: s0 += s0_w + n d,
+      // s1 += s1_w + 2 d s0_w + n d^2) in wave order.  Every wave of the block is here (whole tiles only).
+      float* mine = reinterpret_cast<float*>(xs);
+      mine[lane] = st_s0; mine[64 + lane] = st_s1; mine[128 + lane] = st_p;
+      __syncthreads();
+      constexpr int SHARE = BN_ == 128 ? 2 : 4, STEP = BN_ == 128 ? 2 : 1;
+      if (wave < STEP) {
+        const float n = (float)WROWS;
+#pragma unroll
+        for (int u = 1; u < SHARE; ++u) {
+          const float* o = reinterpret_cast<const float*>(reinterpret_cast<const char*>(Sm) + (wave + u * STEP) * 8192);
+          const float o0 = o[lane], o1 = o[64 + lane], d = o[128 + lane] - st_p;
+          st_s0 += o0 + n * d;
+          st_s1 += o1 + 2.f * d * o0 + n * d * d;
+        }
+        const size_t nslab = (size_t)M / BM, slab = (size_t)m0 / BM;
+        float* sp = ws + slab * N + n0 + wn + lane;
+        sp[0] = st_s0;
+        sp[nslab * N] = st_s1;
+        sp[2 * nslab * N] = st_p;
       }
     }
     return;

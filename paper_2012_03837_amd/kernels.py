@@ -131,6 +131,12 @@ def lpk_conv_bwd_weight_ws(dtype, dout, x, dw, N, H, W, Cin, O, R, stride, pad, 
                                      _stream()), "lpk_conv_bwd_weight_ws")
 
 
+def lpk_conv_bn_fwd(dtype, x, w, z, g, b, res, y, mean, rstd, N, H, W, Cin, O, R, stride, pad, relu, scratch):
+    _ck(lib().lpk_conv_bn_fwd(_i(dtype), _p(x), _p(w), _p(z), _p(g), _p(b), _p(res), _p(y), _p(mean), _p(rstd), _i(N),
+                              _i(H), _i(W), _i(Cin), _i(O), _i(R), _i(stride), _i(pad), _i(relu), _p(scratch),
+                              _sz(scratch.numel()), _stream()), "lpk_conv_bn_fwd")
+
+
 def lpk_batchnorm_fwd(dtype, z, g, b, res, y, mean, rstd, rows, Cc, relu, scratch):
     _ck(lib().lpk_batchnorm_fwd(_i(dtype), _p(z), _p(g), _p(b), _p(res), _p(y), _p(mean), _p(rstd), _i(rows), _i(Cc),
                                 _i(relu), _p(scratch), _sz(scratch.numel()), _stream()), "lpk_batchnorm_fwd")

@@ -555,3 +555,45 @@ def test_gemm_persistent_fused_epilogues(K, variant, a_kc, b_kc):
             want = fn(dsrc[:, :N].astype(np.float64), ref0) + res[:, :N]
             assert relerr(host(out), want) <= 4e-3, (M, N, Kd, variant, "dact", dact)
             assert np.max(np.abs(host(out).astype(np.float64) - want)) <= 0.02 * max(1.0, np.max(np.abs(want)))
+
+
+@pytest.mark.parametrize("N,H,C,O,R,stride,pad", [(4, 16, 16, 64, 3, 1, 1), (8, 16, 32, 128, 3, 1, 1), (16, 16, 64, 256, 3, 2, 1),
+                                                  (64, 8, 16, 64, 1, 2, 0), (100, 32, 8, 64, 3, 1, 1), (2, 32, 8, 192, 3, 1, 1),
+                                                  (3, 10, 16, 64, 3, 1, 1), (5, 12, 24, 72, 3, 1, 1)])
+def test_conv_bn_unit_forward(K, N, H, C, O, R, stride, pad):
+    """A convolution + normalisation unit in one call (the convolution leaves the normalisation's column sums where its
+    output is whole tiles, 128- and 256-row tiles, 64 and 128 columns wide: the first five shapes; the others fall back
+    to the separate statistics pass): z, the batch
+    mean and 1 / sqrt(var + eps), and y against the CPU oracle's convolution and batch normalisation, and the same
+    bits as the two separate calls for z; twice: bit-repeatable."""
+    import torch
+    rng = np.random.default_rng(N * 100 + H)
+    x = rnd(rng, (N, H, H, C), 1)
+    w = rnd(rng, (O, R, R, C), 1, 0.3)
+    P = (H + 2 * pad - R) // stride + 1
+    g = rng.standard_normal(O).astype(np.float32); b = rng.standard_normal(O).astype(np.float32)
+    res = rnd(rng, (N, P, P, O), 1)
+    scratch = zeros(max(3 * (N * P * P // 32 + O), (2 * 1024 + 2) * O) + 64)
+    outs = []
+    for rep in range(2):
+        z = torch.zeros(N, P, P, O, device="cuda", dtype=torch.bfloat16)
+        y = torch.zeros_like(z); mean = zeros(O); rstd = zeros(O)
+        K.lpk_conv_bn_fwd(1, dev(x, 1), dev(w, 1), z, dev(g, 0), dev(b, 0), dev(res, 1), y, mean, rstd, N, H, H, C, O, R,
+                          stride, pad, 1, scratch)
+        outs.append((z, y, mean, rstd))
+    z, y, mean, rstd = outs[0]
+    for a_, b_ in zip(outs[0], outs[1]):
+        assert torch.equal(a_, b_)
+    z2 = torch.zeros_like(z)
+    K.lpk_conv_fwd(1, dev(x, 1), dev(w, 1), z2, N, H, H, C, O, R, stride, pad)
+    assert torch.equal(z, z2)
+    ref = ops.conv2d_fwd(x.astype(np.float64), w.astype(np.float64), stride, pad)
+    assert relerr(host(z), ref) <= 4e-3
+    # statistics of the stored (rounded) convolution output, exactly
+    zs = host(z).astype(np.float64).reshape(-1, O)
+    mu = zs.mean(0); var = zs.var(0)
+    assert np.max(np.abs(host(mean) - mu)) <= 1e-5 * max(1.0, np.max(np.abs(mu)))
+    assert relerr(host(rstd), 1.0 / np.sqrt(var + 1e-5)) <= 1e-5
+    ry, _ = ops.batchnorm_fwd(zs.reshape(N, P, P, O), g.astype(np.float64), b.astype(np.float64))
+    ry = np.maximum(ry + res, 0)
+    assert relerr(host(y), ry) <= 4e-3
