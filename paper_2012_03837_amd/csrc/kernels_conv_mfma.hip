@@ -205,9 +205,9 @@ hipError_t launch(const OpCtx& c, LA A, LB B, const Epilogue& e, int M, int N, i
       if ((size_t)3 * (M / bm) * N <= st->cap) { stats = true; st->nslab = M / bm; st->slab_rows = bm; }
     }
   }
-  static char names[5][96];
-  char* kname = names[low ? 4 : (big ? 1 : 0) + (narrow ? 2 : 0)];
-  if (!kname[0]) snprintf(kname, sizeof names[0], "mfma::k_mfma_tiles<%s, %d, %d>", loaders, bm, bn);
+  static char names[10][104];
+  char* kname = names[(low ? 4 : (big ? 1 : 0) + (narrow ? 2 : 0)) + (stats ? 5 : 0)];
+  if (!kname[0]) snprintf(kname, sizeof names[0], "mfma::k_mfma_tiles<%s, %d, %d, %s>", loaders, bm, bn, stats ? "true" : "false");
   ProfScope one_(c, KC_GEMM_KERNEL, 2.0 * M * N * K, 0, kname);
   if constexpr (std::is_same<LA, ConvFwdA>::value) {
     if (stats) {

@@ -171,8 +171,8 @@ hipError_t gemm_mfma(const OpCtx& c, const GemmArgs& g) {
   Operand A{(const bf16_t*)g.A, g.lda, g.M}, B{(const bf16_t*)g.B, g.ldb, g.N};
   const int bm = kRegStaged[best_v].bm, tn = (g.N + BN - 1) / BN, tm = (g.M + bm - 1) / bm;
   dim3 grid(tm * tn * splits);
-  char kname_buf[96];
-  snprintf(kname_buf, sizeof kname_buf, "mfma::k_mfma_tiles<mfma::PlainLoader<%s>, mfma::PlainLoader<%s>, %d, 128>",
+  char kname_buf[112];
+  snprintf(kname_buf, sizeof kname_buf, "mfma::k_mfma_tiles<mfma::PlainLoader<%s>, mfma::PlainLoader<%s>, %d, 128, false>",
            g.a_kc ? "true" : "false", g.b_kc ? "true" : "false", bm);
   static std::map<std::string, std::string> names;       // stable storage for the profiler's name pointers
   const char* kname = names.emplace(kname_buf, kname_buf).first->second.c_str();
